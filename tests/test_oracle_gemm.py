@@ -1,0 +1,294 @@
+"""Pins of the oracle's tile GEMM (paper Section 4, Algorithm 1) against things that do
+not come from the oracle: exact rational fused multiply-adds, exact integer products,
+the standard error bound, numpy's matmul, and invariance under the visit order.
+"""
+import itertools
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import gemm_mp_oracle as orc
+from tests.exact import fma32, fma64
+
+FP64, FP32, FP16, FP8 = 0, 1, 2, 3
+U = {FP64: 2.0 ** -53, FP32: 2.0 ** -24, FP16: 2.0 ** -11, FP8: 2.0 ** -4}
+
+
+def _store(X, nb, pmap):
+    return orc.store_tiles(np.ascontiguousarray(X), nb, pmap)
+
+
+def _run(nb, A, mA, B, mB, C0, mC, alpha, beta, policy=orc.POLICY_OPERAND, jobs=None):
+    Ay, eA = _store(A, nb, mA)
+    By, eB = _store(B, nb, mB)
+    Cy = None if C0 is None else _store(C0, nb, mC)[0]
+    MT, NT = mC.shape
+    if jobs is None:
+        jobs = orc.whole_tile_jobs(nb, [(i, j) for i in range(MT) for j in range(NT)])
+    return orc.gemm_jobs(nb, Ay, mA, eA, By, mB, eB, Cy, mC, alpha, beta, jobs, policy=policy)
+
+
+def _maps(shape, value):
+    return np.full(shape, value, dtype=np.uint16)
+
+
+@pytest.mark.parametrize("nb", [2, 4, 8])
+def test_all_fp64_map_equals_exact_fma_triple_loop_bit_for_bit(nb):
+    rng = np.random.default_rng(10 + nb)
+    M, N, K = 8, 8, 16
+    A, B, C0 = rng.standard_normal((M, K)), rng.standard_normal((K, N)), rng.standard_normal((M, N))
+    alpha, beta = 1.5, -0.25
+    got = _run(nb, A, _maps((M // nb, K // nb), FP64), B, _maps((K // nb, N // nb), FP64),
+               C0, _maps((M // nb, N // nb), FP64), alpha, beta)
+    for i in range(M):
+        for j in range(N):
+            s = 0.0
+            for k in range(K):
+                s = fma64(A[i, k], B[k, j], s)
+            assert got[i, j] == alpha * s + beta * C0[i, j]
+
+
+@pytest.mark.parametrize("nb", [2, 4])
+def test_all_fp32_map_equals_exact_fmaf_triple_loop_bit_for_bit(nb):
+    rng = np.random.default_rng(20 + nb)
+    M, N, K = 4, 8, 8
+    A, B, C0 = rng.standard_normal((M, K)), rng.standard_normal((K, N)), rng.standard_normal((M, N))
+    alpha, beta = 0.75, 2.0
+    got = _run(nb, A, _maps((M // nb, K // nb), FP32), B, _maps((K // nb, N // nb), FP32),
+               C0, _maps((M // nb, N // nb), FP32), alpha, beta)
+    A32, B32, C32 = A.astype(np.float32), B.astype(np.float32), C0.astype(np.float32)
+    a32, b32 = np.float32(alpha), np.float32(beta)
+    for i in range(M):
+        for j in range(N):
+            s = np.float32(0)
+            for k in range(K):
+                s = fma32(A32[i, k], B32[k, j], s)
+            want = np.float32(np.float32(a32 * s) + np.float32(b32 * C32[i, j]))
+            assert got[i, j] == float(want)
+
+
+@pytest.mark.parametrize("policy", [orc.POLICY_OPERAND, orc.POLICY_C_TILE])
+def test_small_integer_inputs_give_the_exact_integer_product_for_every_map(policy):
+    """Entries in {-3..3}: every storage format holds them exactly (with its tile scale) and
+    all partial sums are small integers, so any index, transpose or scale mistake shows."""
+    rng = np.random.default_rng(30)
+    nb, MT, NT, KT = 8, 3, 4, 4
+    M, N, K = MT * nb, NT * nb, KT * nb
+    for trial in range(6):
+        A = rng.integers(-3, 4, (M, K)).astype(np.float64)
+        B = rng.integers(-3, 4, (K, N)).astype(np.float64)
+        C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
+        A[0:nb, 0:nb] = 0.0                                    # an all-zero tile (scale exponent 0)
+        mA = rng.integers(0, 4, (MT, KT)).astype(np.uint16)
+        mB = rng.integers(0, 4, (KT, NT)).astype(np.uint16)
+        mC = rng.integers(0, 2, (MT, NT)).astype(np.uint16)
+        got = _run(nb, A, mA, B, mB, C0, mC, 2.0, -3.0, policy=policy)
+        want = 2 * (A.astype(np.int64) @ B.astype(np.int64)) - 3 * C0.astype(np.int64)
+        assert np.array_equal(got, want.astype(np.float64))
+
+
+def test_product_precision_table():
+    """q = pC under the paper-literal reading; under the default reading the better-stored
+    operand's precision, capped by what C keeps (FP64 C: no cap; FP32 C: FP32)."""
+    rank = {FP64: 3, FP32: 2, FP16: 1, FP8: 0}
+    by_rank = {v: k for k, v in rank.items()}
+    for pA, pB, pC in itertools.product(range(4), range(4), range(2)):
+        assert orc.product_precision(pA, pB, pC, orc.POLICY_C_TILE) == pC
+        want = by_rank[min(rank[pC], max(rank[pA], rank[pB]))]
+        assert orc.product_precision(pA, pB, pC, orc.POLICY_OPERAND) == want
+    # the only FP64/FP32 case where the two readings differ
+    assert orc.product_precision(FP32, FP32, FP64, orc.POLICY_OPERAND) == FP32
+    assert orc.product_precision(FP32, FP32, FP64, orc.POLICY_C_TILE) == FP64
+
+
+def test_product_counts_of_the_banded_tiny_map_and_of_iid_maps():
+    import workloads as W
+    w = W.tiny()
+    counts = [0, 0, 0, 0]
+    for I, J, L in itertools.product(range(4), range(4), range(4)):
+        counts[orc.product_precision(w.mapA[I, L], w.mapB[L, J], w.mapC[I, J])] += 1
+    assert counts == [28, 26, 10, 0]              # closed form for |I-L|, |L-J| bands, FP64 C
+    w = W.random_maps()
+    c = np.zeros(4)
+    for I, J, L in itertools.product(range(w.MT), range(w.NT), range(w.KT)):
+        c[orc.product_precision(w.mapA[I, L], w.mapB[L, J], w.mapC[I, J])] += 1
+    frac = c / c.sum()
+    # expectation: FP64 (7/16)/2, FP32 (7/16)/2 + 5/16, FP16 1/4
+    assert abs(frac[0] - 0.21875) < 0.04 and abs(frac[1] - 0.53125) < 0.04 and abs(frac[2] - 0.25) < 0.04
+    assert frac[3] == 0
+
+
+def _mixed_problem(seed, nb=16, MT=3, NT=3, KT=4, with_fp8=True, pc_codes=(FP64, FP32)):
+    rng = np.random.default_rng(seed)
+    M, N, K = MT * nb, NT * nb, KT * nb
+    A, B, C0 = rng.standard_normal((M, K)), rng.standard_normal((K, N)), rng.standard_normal((M, N))
+    hi = 4 if with_fp8 else 3
+    mA = rng.integers(0, hi, (MT, KT)).astype(np.uint16)
+    mB = rng.integers(0, hi, (KT, NT)).astype(np.uint16)
+    mC = rng.choice(pc_codes, (MT, NT)).astype(np.uint16)
+    return nb, A, mA, B, mB, C0, mC
+
+
+@pytest.mark.parametrize("policy", [orc.POLICY_OPERAND, orc.POLICY_C_TILE])
+def test_error_stays_within_the_standard_bound_and_is_not_suspiciously_small(policy):
+    """|C - exact(alpha*Ahat*Bhat + beta*Chat)| <= sum_L nb*u_q*|a||b| + (K+3)*u_T*(|a||b| + |c|)
+    elementwise; and where a product ran below FP64 the error is not at FP64 level either."""
+    nb, A, mA, B, mB, C0, mC = _mixed_problem(40)
+    alpha, beta = 1.25, 0.5
+    Ay, eA = _store(A, nb, mA)
+    By, eB = _store(B, nb, mB)
+    Cy, _ = _store(C0, nb, mC)
+    Ah = Ay * np.kron(2.0 ** eA, np.ones((nb, nb)))
+    Bh = By * np.kron(2.0 ** eB, np.ones((nb, nb)))
+    MT, NT = mC.shape
+    KT = mA.shape[1]
+    jobs = orc.whole_tile_jobs(nb, [(i, j) for i in range(MT) for j in range(NT)])
+    got = orc.gemm_jobs(nb, Ay, mA, eA, By, mB, eB, Cy, mC, alpha, beta, jobs, policy=policy)
+    exact = alpha * (Ah.astype(np.longdouble) @ Bh.astype(np.longdouble)) + beta * Cy
+    err = np.abs(got - exact).astype(np.float64)
+    absprod = np.zeros_like(got)
+    bound = np.zeros_like(got)
+    lowq = np.zeros(mC.shape, dtype=bool)
+    for I in range(MT):
+        for J in range(NT):
+            T = mC[I, J]
+            blk = (slice(I * nb, (I + 1) * nb), slice(J * nb, (J + 1) * nb))
+            for L in range(KT):
+                q = orc.product_precision(mA[I, L], mB[L, J], mC[I, J], policy)
+                lowq[I, J] |= q != FP64
+                p = np.abs(Ah[I * nb:(I + 1) * nb, L * nb:(L + 1) * nb]) @ np.abs(Bh[L * nb:(L + 1) * nb, J * nb:(J + 1) * nb])
+                # storage-to-q down-cast (FP64 -> FP32) adds 2u per product term
+                bound[blk] += abs(alpha) * (nb + 2) * max(U[q], U[FP32] if q != FP64 else 0) * p
+                absprod[blk] += p
+            bound[blk] += (KT * nb + 3) * U[T] * (abs(alpha) * absprod[blk] + abs(beta) * np.abs(Cy[blk]))
+    assert np.all(err <= bound)
+    for I in range(MT):
+        for J in range(NT):
+            blk = (slice(I * nb, (I + 1) * nb), slice(J * nb, (J + 1) * nb))
+            if lowq[I, J]:
+                assert np.linalg.norm(err[blk]) > 2.0 ** -30 * np.linalg.norm(absprod[blk])
+
+
+@pytest.mark.parametrize("p,dtype,tol", [(FP64, np.float64, 1e-14), (FP32, np.float32, 1e-5), (FP16, np.float16, 2e-3)])
+def test_uniform_map_single_reduction_tile_matches_numpy_matmul_in_that_dtype(p, dtype, tol):
+    rng = np.random.default_rng(50 + p)
+    nb = 32
+    A, B = rng.uniform(-1, 1, (nb, nb)), rng.uniform(-1, 1, (nb, nb))
+    mC = _maps((1, 1), FP64 if p == FP64 else FP32)
+    got = _run(nb, A, _maps((1, 1), p), B, _maps((1, 1), p), None, mC, 1.0, 0.0)
+    with np.errstate(over="ignore"):
+        want = (A.astype(dtype).astype(np.float32 if p == FP16 else dtype) @
+                B.astype(dtype).astype(np.float32 if p == FP16 else dtype)).astype(np.float64)
+    # FP16 tiles carry a power-of-two scale, so their stored values are at least as accurate
+    # as an unscaled half cast; compare at the level of the half unit roundoff.
+    assert np.linalg.norm(got - want) <= tol * np.linalg.norm(np.abs(A) @ np.abs(B))
+
+
+def test_visit_order_listing_loop_nest_equals_tile_owner_loop_nest_bit_for_bit():
+    """Algorithm 1 prints the reduction tile index outermost; the oracle's default walks one C
+    tile at a time.  With the per-tile reduction order kept ascending both give the same bits,
+    for every map, as does any permutation or splitting of the jobs."""
+    for seed in (60, 61):
+        nb, A, mA, B, mB, C0, mC = _mixed_problem(seed)
+        alpha, beta = -0.5, 1.5
+        Ay, eA = _store(A, nb, mA)
+        By, eB = _store(B, nb, mB)
+        Cy, _ = _store(C0, nb, mC)
+        MT, NT = mC.shape
+        KT = mA.shape[1]
+        tiles = [(i, j) for i in range(MT) for j in range(NT)]
+        jobs = orc.whole_tile_jobs(nb, tiles)
+        ref = orc.gemm_jobs(nb, Ay, mA, eA, By, mB, eB, Cy, mC, alpha, beta, jobs)
+        # (a) listing order: for l, for i, for j, each task one call that carries the running sums
+        state = {t: np.zeros(nb * nb) for t in tiles}
+        out = np.full_like(ref, np.nan)
+        for L in range(KT):
+            for (i, j) in tiles:
+                orc.gemm_jobs(nb, Ay, mA, eA, By, mB, eB, Cy, mC, alpha, beta,
+                              orc.whole_tile_jobs(nb, [(i, j)]), out=out, L_range=(L, L + 1),
+                              state=state[(i, j)], resume=L > 0, finish=L == KT - 1)
+        assert np.array_equal(out, ref)
+        # (b) permuted jobs, and tiles cut into ragged sub-rectangles
+        rng = np.random.default_rng(seed)
+        perm = rng.permutation(len(tiles))
+        out = orc.gemm_jobs(nb, Ay, mA, eA, By, mB, eB, Cy, mC, alpha, beta, jobs[perm])
+        assert np.array_equal(out, ref)
+        pieces = []
+        for (i, j) in tiles:
+            r, c = int(rng.integers(1, nb)), int(rng.integers(1, nb))
+            pieces += [[i, j, 0, r, 0, c], [i, j, r, nb, 0, c], [i, j, 0, r, c, nb], [i, j, r, nb, c, nb]]
+        out = orc.gemm_jobs(nb, Ay, mA, eA, By, mB, eB, Cy, mC, alpha, beta, np.array(pieces, dtype=np.int32))
+        assert np.array_equal(out, ref)
+
+
+def test_beta_zero_never_reads_c_and_alpha_zero_skips_products():
+    nb, A, mA, B, mB, C0, mC = _mixed_problem(70)
+    poisoned = np.full_like(C0, np.nan)
+    Ay, eA = _store(A, nb, mA)
+    By, eB = _store(B, nb, mB)
+    MT, NT = mC.shape
+    jobs = orc.whole_tile_jobs(nb, [(i, j) for i in range(MT) for j in range(NT)])
+    got = orc.gemm_jobs(nb, Ay, mA, eA, By, mB, eB, poisoned, mC, 1.0, 0.0, jobs)
+    assert np.all(np.isfinite(got))
+    Cy, _ = _store(C0, nb, mC)
+    Ay[0, 0] = np.inf                       # would poison every product of row 0 if it were formed
+    got = orc.gemm_jobs(nb, Ay, mA, eA, By, mB, eB, Cy, mC, 0.0, 0.5, jobs)
+    want = np.empty_like(Cy)
+    for I in range(MT):
+        for J in range(NT):
+            blk = (slice(I * nb, (I + 1) * nb), slice(J * nb, (J + 1) * nb))
+            if mC[I, J] == FP64:
+                want[blk] = 0.5 * Cy[blk]
+            else:
+                want[blk] = (np.float32(0.5) * Cy[blk].astype(np.float32)).astype(np.float64)
+    assert np.array_equal(got, want)
+
+
+def test_low_precision_products_are_scaled_back_by_the_tile_exponents():
+    """FP16 x FP16 product of tiles holding tiny and huge numbers: without the per-tile
+    exponents the stored tiles would flush to zero / overflow."""
+    rng = np.random.default_rng(80)
+    nb = 16
+    A = rng.standard_normal((nb, nb)) * 1e-9
+    B = rng.standard_normal((nb, nb)) * 1e7
+    m16 = _maps((1, 1), FP16)
+    for pC in (FP64, FP32):
+        got = _run(nb, A, m16, B, m16, None, _maps((1, 1), pC), 1.0, 0.0)
+        ref = A @ B
+        assert np.linalg.norm(got - ref) <= 4 * 2.0 ** -11 * np.linalg.norm(np.abs(A) @ np.abs(B))
+        assert np.linalg.norm(got) > 0.5 * np.linalg.norm(ref)
+
+
+def test_stored_tiles_match_library_casts_and_scale_window():
+    rng = np.random.default_rng(90)
+    nb = 8
+    X = rng.standard_normal((2 * nb, 4 * nb)) * np.kron(10.0 ** rng.integers(-12, 6, (2, 4)), np.ones((nb, nb)))
+    X[0:nb, 0:nb] = 0.0
+    pmap = np.array([[FP16, FP64, FP32, FP16], [FP8, FP16, FP8, FP32]], dtype=np.uint16)
+    pmap[0, 0] = FP16
+    Y, e = orc.store_tiles(X, nb, pmap)
+    for I in range(2):
+        for J in range(4):
+            blk = (slice(I * nb, (I + 1) * nb), slice(J * nb, (J + 1) * nb))
+            p = pmap[I, J]
+            if p == FP64:
+                assert e[I, J] == 0 and np.array_equal(Y[blk], X[blk])
+            elif p == FP32:
+                assert e[I, J] == 0 and np.array_equal(Y[blk], X[blk].astype(np.float32).astype(np.float64))
+            else:
+                m = np.abs(X[blk]).max()
+                if m == 0:
+                    assert e[I, J] == 0 and not Y[blk].any()
+                    continue
+                top = 15 if p == FP16 else 8
+                assert 2.0 ** (top - 1) <= m * 2.0 ** -float(e[I, J]) < 2.0 ** top
+                scaled = X[blk] * 2.0 ** -float(e[I, J])
+                if p == FP16:
+                    assert np.array_equal(Y[blk], scaled.astype(np.float16).astype(np.float64))
+                else:
+                    torch = pytest.importorskip("torch")
+                    # scaled magnitudes stay below 256, far from e4m3's saturation; torch may go
+                    # through FP32, which for these seeded values lands on no e4m3 midpoint
+                    t = torch.from_numpy(scaled).to(torch.float8_e4m3fn).to(torch.float64).numpy()
+                    assert np.array_equal(Y[blk], t)

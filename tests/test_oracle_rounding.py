@@ -1,0 +1,116 @@
+"""Pins of the oracle's software rounding (storage rounding of FP16 / FP8 tiles).
+
+FP16 is pinned to numpy's binary16 conversion (an independent library routine that
+rounds once from FP64); FP8 e4m3fn to a brute-force nearest-value search over the
+table of all codes written from the format's definition, and to torch's e4m3fn cast.
+"""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import gemm_mp_oracle as orc
+from tests.exact import e4m3_table
+
+
+def _all_half():
+    codes = np.arange(65536, dtype=np.uint16)
+    return codes, codes.view(np.float16).astype(np.float64)
+
+
+def test_fp16_every_value_is_a_fixed_point_and_codes_round_trip():
+    codes, vals = _all_half()
+    finite = np.isfinite(vals)
+    y, bits = orc.round_fp16(vals[finite])
+    assert np.array_equal(y, vals[finite])
+    assert np.array_equal(bits, codes[finite])
+    for c in (0x0001, 0x03FF, 0x0400, 0x3C00, 0x7BFF, 0x8001, 0xFBFF, 0x7C00, 0xFC00):
+        assert orc.fp16_value(c) == float(np.array(c, dtype=np.uint16).view(np.float16))
+
+
+def test_fp16_midpoints_and_their_neighbours_match_numpy():
+    codes = np.arange(0x0000, 0x7C00, dtype=np.uint16)          # positive finite, ascending
+    v = codes.view(np.float16).astype(np.float64)
+    mid = 0.5 * (v[:-1] + v[1:])                                 # exact in FP64
+    probes = np.concatenate([mid, np.nextafter(mid, np.inf), np.nextafter(mid, -np.inf),
+                             [65504.0 + 16.0, np.nextafter(65520.0, 0), np.nextafter(65520.0, np.inf), 1e300, 5e-324]])
+    probes = np.concatenate([probes, -probes])
+    with np.errstate(over="ignore"):
+        want = probes.astype(np.float16)
+    y, bits = orc.round_fp16(probes)
+    assert np.array_equal(bits, want.view(np.uint16))
+    assert np.array_equal(y, want.astype(np.float64))
+
+
+def test_fp16_random_doubles_match_numpy_and_avoid_double_rounding():
+    rng = np.random.default_rng(1)
+    x = np.exp(rng.uniform(np.log(1e-9), np.log(1e5), 200000)) * rng.choice([-1.0, 1.0], 200000)
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16)
+    y, bits = orc.round_fp16(x)
+    assert np.array_equal(bits, want.view(np.uint16))
+    # a value just above an FP16 midpoint that FP32 would first pull onto the midpoint
+    trap = 1.0 + 2.0 ** -11 + 2.0 ** -40
+    assert orc.round_fp16([trap])[0][0] == 1.0 + 2.0 ** -10
+    assert float(np.float16(np.float32(trap))) == 1.0          # what double rounding would give
+
+
+def test_fp16_specials():
+    y, bits = orc.round_fp16(np.array([np.inf, -np.inf, 0.0, -0.0]))
+    assert list(bits) == [0x7C00, 0xFC00, 0x0000, 0x8000]
+    y, bits = orc.round_fp16(np.array([np.nan]))
+    assert np.isnan(y[0]) and (bits[0] & 0x7C00) == 0x7C00 and (bits[0] & 0x3FF) != 0
+
+
+def _brute_force_e4m3(x, table):
+    """Nearest finite e4m3 value (ties to the even code); beyond the largest -> +-448."""
+    fx = Fraction(x)
+    sign = 1 if np.signbit(x) else 0
+    best = None
+    for code, v in table:
+        if (code >> 7) != sign:
+            continue
+        d = abs(v - fx)
+        if best is None or d < best[0] or (d == best[0] and code % 2 == 0):
+            best = (d, code, v)
+    return best[1], best[2]
+
+
+def test_fp8_matches_brute_force_search_over_all_codes():
+    table = e4m3_table()
+    pos = sorted(v for c, v in table if c < 0x80)
+    probes = []
+    for a, b in zip(pos[:-1], pos[1:]):
+        m = float((a + b) / 2)
+        probes += [float(a), m, np.nextafter(m, np.inf), np.nextafter(m, -np.inf)]
+    probes += [448.0, 449.0, 463.9, 464.0, 465.0, 480.0, 1e6, 1e300, 2.0 ** -10, 2.0 ** -10 * 1.001, 2.0 ** -11, 1e-300]
+    rng = np.random.default_rng(2)
+    probes += list(np.exp(rng.uniform(np.log(1e-4), np.log(600.0), 3000)))
+    probes = np.array(probes + [-p for p in probes] + [0.0, -0.0])
+    y, bits = orc.round_fp8(probes)
+    for x, yy, bb in zip(probes, y, bits):
+        code, val = _brute_force_e4m3(float(x), table)
+        assert bb == code, (x, hex(bb), hex(code))
+        assert Fraction(float(yy)) == val
+
+
+def test_fp8_specials_saturate_and_nan():
+    y, bits = orc.round_fp8(np.array([np.inf, -np.inf, np.nan, 1e10, -1e10]))
+    assert list(bits[:2]) == [0x7E, 0xFE] and list(bits[3:]) == [0x7E, 0xFE]
+    assert np.isnan(y[2]) and (bits[2] & 0x7F) == 0x7F
+    assert y[0] == 448.0 and y[1] == -448.0
+
+
+def test_fp8_decode_and_round_agree_with_torch_e4m3fn():
+    torch = pytest.importorskip("torch")
+    codes = torch.arange(256, dtype=torch.uint8)
+    want = codes.view(torch.float8_e4m3fn).to(torch.float32).numpy().astype(np.float64)
+    got = np.array([orc.fp8_value(c) for c in range(256)])
+    assert np.array_equal(np.isnan(want), np.isnan(got))
+    ok = ~np.isnan(want)
+    assert np.array_equal(want[ok], got[ok])
+    rng = np.random.default_rng(3)
+    x32 = (np.exp(rng.uniform(np.log(1e-4), np.log(440.0), 100000)) * rng.choice([-1, 1], 100000)).astype(np.float32)
+    tb = torch.from_numpy(x32).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    _, bits = orc.round_fp8(x32.astype(np.float64))
+    assert np.array_equal(bits, tb)
