@@ -1,0 +1,173 @@
+/*
+ * gemm_mp.h - C ABI of the tile-centric mixed-precision GEMM for one MI355X (gfx950).
+ *
+ *     C <- alpha * A * B + beta * C          (paper Section 4, Algorithm 1)
+ *
+ * A (M x K), B (K x N) and C (M x N) are cut into square tiles of one size
+ * tile_nb.  Every tile is stored in its own precision, given per matrix by a
+ * precision map (one unsigned 16-bit code per tile, row-major over tiles;
+ * paper Section 5.2).  A tile product A(I,L)*B(L,J) is computed on the matrix
+ * cores at the precision the policy assigns to it, operands being converted
+ * from their stored precision on the fly by the consumer ("receiver-side
+ * conversion", Section 4), and is accumulated into C(I,J) in that tile's
+ * precision.  Each C tile region is owned by exactly one workgroup: there are
+ * no atomics on C and results are reproducible run to run.
+ *
+ * Conventions
+ *   - Dense matrices handed to / returned by the library are row-major FP64 in
+ *     DEVICE memory, leading dimension `ld` in elements.
+ *   - Precision maps and everything returned through pointers marked "host"
+ *     live in HOST memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls marked [async] only enqueue work on it; calls marked [sync] wait
+ *     for it before they return.
+ *   - The library never allocates or frees operand memory.  The caller asks
+ *     gemm_mp_storage_bytes() and binds a device buffer of at least that size
+ *     per matrix; the buffer must stay valid until the context is destroyed or
+ *     rebound.  The library owns only small per-tile tables.
+ *   - Every entry point returns a status code (0 = success).  Nothing throws or
+ *     aborts.  Output arguments are written only on success.
+ *   - A context must not be used from two threads at once.
+ *
+ * Packed layout of a matrix (what the bound buffer holds): tile (I,J) starts at
+ * a 256-byte aligned offset, tiles in row-major order; inside a tile of A or C
+ * element (r,c) sits at index r*tile_nb + c; inside a tile of B at index
+ * c*tile_nb + r (so the reduction index is contiguous for both operands).
+ * Element types: FP64 / FP32 IEEE; FP16 IEEE binary16; FP8 OCP e4m3 ("fn": no
+ * infinities, max finite 448).  FP16 / FP8 tiles hold x * 2^-e with one
+ * power-of-two exponent e per tile chosen so that the largest magnitude falls
+ * in [2^14,2^15) resp. [2^7,2^8); e = 0 for an all-zero tile.
+ */
+#ifndef GEMM_MP_H
+#define GEMM_MP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gemm_mp_ctx gemm_mp_ctx; /* opaque; created and destroyed by the library */
+typedef void *gemm_mp_stream;           /* a hipStream_t */
+
+/* Precision codes of a map entry: 0 and 1 as in the paper (Section 5.2); 2, 3 extend them. */
+enum { GEMM_MP_FP64 = 0, GEMM_MP_FP32 = 1, GEMM_MP_FP16 = 2, GEMM_MP_FP8_E4M3 = 3 };
+
+enum {
+    GEMM_MP_OK = 0,
+    GEMM_MP_EINVAL = -1,       /* bad argument: null pointer, size, letter, map code, alignment */
+    GEMM_MP_ESTATE = -2,       /* call order: a map, a buffer or packed data is missing */
+    GEMM_MP_ENOMEM = -3,       /* a table could not be allocated */
+    GEMM_MP_EUNSUPPORTED = -4, /* valid request this build does not implement */
+    GEMM_MP_EHIP = -5          /* the HIP runtime reported an error */
+};
+
+/* How the precision q of the product A(I,L)*B(L,J) that updates C(I,J) is chosen.
+ *   OPERAND (default): the better of the two operands' stored precisions, but never above
+ *       what the C tile keeps: q = min(cap(pC), max(pA,pB)), cap(FP64)=FP64, else FP32.
+ *   C_TILE: the paper's literal statement (Section 5.2: the result precision follows the C
+ *       tile and operands are converted when their maps differ): q = pC.
+ * The two agree on FP64/FP32 maps except for (pA,pB,pC) = (FP32,FP32,FP64). */
+enum { GEMM_MP_POLICY_OPERAND = 0, GEMM_MP_POLICY_C_TILE = 1 };
+
+typedef struct gemm_mp_stats {
+    int64_t products[4];     /* tile products per product precision (index = precision code) */
+    double flops[4];         /* 2*nb^3 * products[q] */
+    int64_t tiles[3][4];     /* stored tiles per matrix (0=A,1=B,2=C) and precision */
+    uint64_t packed_bytes[3];/* size of the packed buffer per matrix */
+    int64_t work_items;      /* owner workgroups launched by gemm_mp_run */
+} gemm_mp_stats;
+
+/* Create a context for C(MxN) = A(MxK) * B(KxN) with square tiles of tile_nb (Section 4:
+ * tiles of one fixed size).  EINVAL unless all sizes are positive, M, N, K are multiples of
+ * tile_nb, and tile_nb is a multiple of 128 (the owner workgroup's footprint).  Host only. */
+int gemm_mp_create(gemm_mp_ctx **out, int64_t M, int64_t N, int64_t K, int32_t tile_nb);
+
+/* Release the context and its tables (not the bound buffers). */
+int gemm_mp_destroy(gemm_mp_ctx *ctx);
+
+/* Choose the product-precision policy (see above).  Host only. */
+int gemm_mp_set_policy(gemm_mp_ctx *ctx, int policy);
+
+/* Give the precision map of matrix `which` ('A', 'B' or 'C'): rows x cols codes, row-major,
+ * host memory, copied (Section 5.2).  rows/cols must equal the matrix's tile counts (EINVAL),
+ * codes must be 0..3 (EINVAL); C tiles may only be FP64 or FP32 (EUNSUPPORTED).  Any earlier
+ * binding and packed data of that matrix are forgotten.  Host only. */
+int gemm_mp_set_precision_map(gemm_mp_ctx *ctx, char which, const uint16_t *map_host,
+                              int32_t rows, int32_t cols);
+
+/* Tile scan [sync]: per tile of the dense device matrix, the sum of squares and the largest
+ * magnitude, written to host arrays of rows x cols doubles (either may be NULL).  The sum of
+ * squares of a tile is defined in one order: per tile column a running fused multiply-add
+ * down the rows, then the column sums added pairwise, neighbours first, level by level.
+ * (The paper draws its maps at random, Section 5.2; this scan feeds the norm rule below.) */
+int gemm_mp_tile_scan(gemm_mp_ctx *ctx, char which, const double *dense_dev, int64_t ld,
+                      gemm_mp_stream stream, double *sumsq_host, double *maxabs_host);
+
+/* Norm-based precision map [sync]: scan the dense device matrix and store tile T at the lowest
+ * precision p allowed by `allowed_mask` (bit p = code p) that satisfies
+ *     |T|_F * sqrt(#tiles) / |X|_F <= threshold / u_p        (u = 2^-53, 2^-24, 2^-11, 2^-4),
+ * else at the highest allowed one; evaluated on squares in FP64 as
+ *     (S_T * #tiles) * (u_p*u_p) <= (threshold*threshold) * S,  S = sum of S_T in tile order.
+ * This is the Frobenius-norm tile criterion of the tile-adaptive work the paper builds on
+ * (cited in its Sections 1-2); the paper itself leaves selection strategies to future work
+ * (Section 6).  The map becomes the matrix's map as by gemm_mp_set_precision_map and is also
+ * copied to map_out_host if that is not NULL.  The scale exponents of FP16/FP8 tiles are taken
+ * from this scan, so gemm_mp_pack_tiles must then be given the same matrix values. */
+int gemm_mp_compute_precision_map(gemm_mp_ctx *ctx, char which, const double *dense_dev,
+                                  int64_t ld, double threshold, uint32_t allowed_mask,
+                                  gemm_mp_stream stream, uint16_t *map_out_host);
+
+/* Bytes the packed form of matrix `which` needs; ESTATE before its map is set.  Host only. */
+int gemm_mp_storage_bytes(gemm_mp_ctx *ctx, char which, size_t *bytes);
+
+/* Bind the caller's device buffer (256-byte aligned, at least storage_bytes) that holds, or
+ * will hold, the packed tiles of `which`.  The caller keeps ownership.  Host only. */
+int gemm_mp_bind_storage(gemm_mp_ctx *ctx, char which, void *dev_ptr, size_t bytes);
+
+/* Pack [async]: round every element of the dense device matrix once, to nearest even, into
+ * its tile's precision (FP16/FP8 after the tile's power-of-two scaling; FP8 saturates) and
+ * write it in the packed layout (Section 5.2: values are initialised in the precision their
+ * map gives).  ESTATE unless map and buffer are set.  For 'C' this defines the C that beta
+ * multiplies; with beta == 0 packing C may be skipped. */
+int gemm_mp_pack_tiles(gemm_mp_ctx *ctx, char which, const double *dense_dev, int64_t ld,
+                       gemm_mp_stream stream);
+
+/* Run [async]: C <- alpha*A*B + beta*C on the packed tiles (Algorithm 1; beta is applied once
+ * per C tile, as in the definition in Section 4).  For each C tile the reduction tiles L are
+ * taken in ascending order; a product whose precision equals the C tile's accumulate type
+ * (FP64 for FP64 tiles, FP32 otherwise) continues the running sum inside the matrix
+ * instruction, any other product is formed in an FP32 accumulator and added once.  FP16/FP8
+ * products use FP32-accumulating matrix instructions on the scaled operands; 2^(eA+eB) is
+ * applied to the finished tile product.  alpha, beta are rounded to the accumulate type.
+ * beta == 0: C is not read.  alpha == 0: no product is formed.
+ * ESTATE unless A and B are packed, C's map and buffer are set, and (beta != 0) C is packed. */
+int gemm_mp_run(gemm_mp_ctx *ctx, double alpha, double beta, gemm_mp_stream stream);
+
+/* Unpack [async]: the numbers the packed tiles stand for (stored value times 2^e), exactly,
+ * as a dense FP64 device matrix.  For verification; not part of the timed path. */
+int gemm_mp_unpack_tiles(gemm_mp_ctx *ctx, char which, double *dense_dev, int64_t ld,
+                         gemm_mp_stream stream);
+
+/* Descriptor of tile (I,J) of `which`: byte offset in the packed buffer, precision code and
+ * scale exponent (each pointer may be NULL).  The exponent is known once the matrix has been
+ * packed (or its map computed by the norm rule); asking for it earlier is ESTATE.  [sync on
+ * the stream last used for that matrix when the exponent is requested] */
+int gemm_mp_tile_info(gemm_mp_ctx *ctx, char which, int32_t I, int32_t J, size_t *offset,
+                      int *prec, int *scale_exp);
+
+/* Product and storage statistics of the current maps and policy; ESTATE until all three maps
+ * are set.  Host only. */
+int gemm_mp_get_stats(gemm_mp_ctx *ctx, gemm_mp_stats *out);
+
+/* Product precision the given policy assigns (pure function; -1 on a bad code). */
+int gemm_mp_product_precision(int pA, int pB, int pC, int policy);
+
+/* Static, human-readable text for a status code. */
+const char *gemm_mp_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GEMM_MP_H */

@@ -1,0 +1,533 @@
+// Host side of libgemm_mp: context, precision maps, packed layout, the precision-bucketed
+// owner-workgroup schedule, and the C ABI declared in include/gemm_mp.h.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <vector>
+
+#include "gemm_mp_internal.h"
+
+using namespace gmp;
+
+namespace {
+
+struct Matrix {
+    int rows_t = 0, cols_t = 0;
+    bool has_map = false;
+    std::vector<uint16_t> map;
+    std::vector<uint64_t> offset;
+    uint64_t bytes = 0;
+    void *storage = nullptr;
+    size_t storage_bytes = 0;
+    bool packed = false;
+    bool exps_valid = false;       // device exponents describe the packed (or to-be-packed) data
+    bool exps_from_rule = false;   // ... and were taken from the scan of the norm rule
+    bool tables_current = false;   // device copies of prec / offset match the host map
+    uint8_t *d_prec = nullptr;
+    uint64_t *d_offset = nullptr;
+    int32_t *d_exp = nullptr;
+    double *d_sumsq = nullptr, *d_maxabs = nullptr, *d_part_sum = nullptr, *d_part_max = nullptr;
+    hipStream_t last_stream = nullptr;
+    int ntiles() const { return rows_t * cols_t; }
+};
+
+}  // namespace
+
+struct gemm_mp_ctx {
+    int64_t M, N, K;
+    int nb, MT, NT, KT;
+    int policy = GEMM_MP_POLICY_OPERAND;
+    Matrix mat[3];
+    bool sched_current = false;
+    std::vector<uint8_t> q;
+    std::vector<WorkItem> items[2];   // [0]: regions of FP64 C tiles, [1]: of FP32 C tiles
+    uint8_t *d_q = nullptr;
+    WorkItem *d_items = nullptr;      // both lists, [0] first
+    gemm_mp_stats stats;
+    bool kernel_ready = false;
+};
+
+namespace {
+
+int which_index(char w)
+{
+    switch (w) {
+    case 'A': case 'a': return 0;
+    case 'B': case 'b': return 1;
+    case 'C': case 'c': return 2;
+    default: return -1;
+    }
+}
+
+#define HIP_TRY(expr) do { if ((expr) != hipSuccess) { (void)hipGetLastError(); return GEMM_MP_EHIP; } } while (0)
+
+template <typename T>
+int dev_alloc(T **p, size_t n)
+{
+    if (*p) return GEMM_MP_OK;
+    if (hipMalloc((void **)p, n * sizeof(T) + 16) != hipSuccess) { (void)hipGetLastError(); *p = nullptr; return GEMM_MP_ENOMEM; }
+    return GEMM_MP_OK;
+}
+
+void free_matrix_tables(Matrix &m)
+{
+    (void)hipFree(m.d_prec); (void)hipFree(m.d_offset); (void)hipFree(m.d_exp);
+    (void)hipFree(m.d_sumsq); (void)hipFree(m.d_maxabs); (void)hipFree(m.d_part_sum); (void)hipFree(m.d_part_max);
+    m.d_prec = nullptr; m.d_offset = nullptr; m.d_exp = nullptr;
+    m.d_sumsq = m.d_maxabs = m.d_part_sum = m.d_part_max = nullptr;
+}
+
+// Packed layout: tiles in row-major order, each at a 256-byte aligned offset.
+void layout(gemm_mp_ctx *c, Matrix &m)
+{
+    const uint64_t elems = (uint64_t)c->nb * (uint64_t)c->nb;
+    m.offset.resize(m.ntiles());
+    uint64_t off = 0;
+    for (int t = 0; t < m.ntiles(); ++t) {
+        m.offset[t] = off;
+        off += (elems * (uint64_t)elem_bytes(m.map[t]) + 255u) & ~(uint64_t)255u;
+    }
+    m.bytes = off;
+}
+
+int install_map(gemm_mp_ctx *c, int w, const uint16_t *map)
+{
+    Matrix &m = c->mat[w];
+    if (m.last_stream || m.d_prec) (void)hipStreamSynchronize(m.last_stream);   // tables may be in use
+    m.map.assign(map, map + m.ntiles());
+    m.has_map = true;
+    layout(c, m);
+    m.storage = nullptr;
+    m.storage_bytes = 0;
+    m.packed = false;
+    m.exps_valid = false;
+    m.exps_from_rule = false;
+    m.tables_current = false;
+    c->sched_current = false;
+    return GEMM_MP_OK;
+}
+
+// Device copies of the per-tile tables (small; owned by the library).
+int ensure_tables(Matrix &m)
+{
+    const size_t n = (size_t)m.ntiles();
+    int rc;
+    if ((rc = dev_alloc(&m.d_prec, n))) return rc;
+    if ((rc = dev_alloc(&m.d_offset, n))) return rc;
+    if (!m.d_exp) {
+        if ((rc = dev_alloc(&m.d_exp, n))) return rc;
+        HIP_TRY(hipMemset(m.d_exp, 0, n * sizeof(int32_t)));
+    }
+    if (!m.tables_current) {
+        std::vector<uint8_t> p8(n);
+        for (size_t t = 0; t < n; ++t) p8[t] = (uint8_t)m.map[t];
+        HIP_TRY(hipMemcpy(m.d_prec, p8.data(), n, hipMemcpyHostToDevice));
+        HIP_TRY(hipMemcpy(m.d_offset, m.offset.data(), n * sizeof(uint64_t), hipMemcpyHostToDevice));
+        m.tables_current = true;
+    }
+    return GEMM_MP_OK;
+}
+
+int ensure_scan_buffers(gemm_mp_ctx *c, Matrix &m)
+{
+    const size_t n = (size_t)m.ntiles(), parts = (size_t)(c->nb / kScanCols);
+    int rc;
+    if ((rc = dev_alloc(&m.d_sumsq, n))) return rc;
+    if ((rc = dev_alloc(&m.d_maxabs, n))) return rc;
+    if ((rc = dev_alloc(&m.d_part_sum, n * parts))) return rc;
+    if ((rc = dev_alloc(&m.d_part_max, n * parts))) return rc;
+    return GEMM_MP_OK;
+}
+
+PackedView view_of(const Matrix &m)
+{
+    PackedView v;
+    v.prec = m.d_prec;
+    v.offset = m.d_offset;
+    v.exp = m.d_exp;
+    v.storage = (char *)m.storage;
+    return v;
+}
+
+int check_dense(const void *p, int64_t ld, int64_t cols)
+{
+    if (!p || ld < cols || (ld & 1) || ((uintptr_t)p & 15u)) return GEMM_MP_EINVAL;
+    return GEMM_MP_OK;
+}
+
+double unit_roundoff(int p)
+{
+    static const double u[4] = {0x1p-53, 0x1p-24, 0x1p-11, 0x1p-4};
+    return u[p];
+}
+
+// Relative cost of one tile product by precision: inverse matrix-core peak (FP64 : FP32 :
+// FP16 : FP8 = 1/78.6 : 1/157.3 : 1/2516.6 : 1/5033.2 TFLOP/s) plus a floor for the operand
+// traffic that the low precisions cannot hide.
+const double kCost[4] = {64.0, 32.0, 3.0, 2.0};
+
+// The schedule.  Every C tile is cut into (nb/128)^2 owner regions; a region's cost is the
+// sum over its reduction tiles of the cost of that product's precision.  C tiles are sorted by
+// cost, dealt to eight bins (one per XCD: workgroup p is dispatched to XCD p mod 8) so that the
+// bins' total costs are balanced, heaviest first; the launch order interleaves the bins, so
+// each XCD works through its own C tiles, keeping their A row panels and B column panels in
+// its L2, and the cheap regions fill the tail.
+void build_schedule(gemm_mp_ctx *c)
+{
+    const int MT = c->MT, NT = c->NT, KT = c->KT;
+    const Matrix &A = c->mat[0], &B = c->mat[1], &C = c->mat[2];
+    c->q.resize((size_t)MT * NT * KT);
+    std::memset(&c->stats, 0, sizeof(c->stats));
+    std::vector<double> cost((size_t)MT * NT, 0.0);
+    for (int I = 0; I < MT; ++I)
+        for (int J = 0; J < NT; ++J) {
+            const int pC = C.map[I * NT + J];
+            for (int L = 0; L < KT; ++L) {
+                const int q = product_precision(A.map[I * KT + L], B.map[L * NT + J], pC, c->policy);
+                c->q[((size_t)I * NT + J) * KT + L] = (uint8_t)q;
+                c->stats.products[q] += 1;
+                cost[(size_t)I * NT + J] += kCost[q];
+            }
+        }
+    const double f = 2.0 * (double)c->nb * (double)c->nb * (double)c->nb;
+    for (int q = 0; q < 4; ++q) c->stats.flops[q] = f * (double)c->stats.products[q];
+    for (int w = 0; w < 3; ++w) {
+        for (int t = 0; t < c->mat[w].ntiles(); ++t) c->stats.tiles[w][c->mat[w].map[t]] += 1;
+        c->stats.packed_bytes[w] = c->mat[w].bytes;
+    }
+
+    const int mr = c->nb / kMacro;
+    const size_t per_tile = (size_t)mr * mr;
+    constexpr int kBins = 8;
+    for (int list = 0; list < 2; ++list) {
+        std::vector<int> order;
+        for (int t = 0; t < MT * NT; ++t)
+            if ((C.map[t] == GEMM_MP_FP64) == (list == 0)) order.push_back(t);
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cost[a] > cost[b]; });
+        std::vector<int> bins[kBins];
+        double load[kBins] = {0};
+        for (int t : order) {
+            int best = 0;
+            for (int b = 1; b < kBins; ++b)
+                if (load[b] < load[best]) best = b;
+            bins[best].push_back(t);
+            load[best] += cost[t];
+        }
+        std::vector<WorkItem> &items = c->items[list];
+        items.clear();
+        items.reserve(order.size() * per_tile);
+        size_t pos[kBins] = {0};
+        bool any = true;
+        while (any) {
+            any = false;
+            for (int b = 0; b < kBins; ++b) {
+                if (pos[b] >= bins[b].size() * per_tile) continue;
+                any = true;
+                const size_t k = pos[b]++;
+                WorkItem it;
+                it.tile = (uint32_t)bins[b][k / per_tile];
+                const size_t r = k % per_tile;
+                it.mi = (uint16_t)(r / mr);
+                it.mj = (uint16_t)(r % mr);
+                items.push_back(it);
+            }
+        }
+    }
+    c->stats.work_items = (int64_t)(c->items[0].size() + c->items[1].size());
+    c->sched_current = true;
+}
+
+int upload_schedule(gemm_mp_ctx *c)
+{
+    (void)hipFree(c->d_q); (void)hipFree(c->d_items);
+    c->d_q = nullptr; c->d_items = nullptr;
+    int rc;
+    if ((rc = dev_alloc(&c->d_q, c->q.size()))) return rc;
+    const size_t n0 = c->items[0].size(), n1 = c->items[1].size();
+    if ((rc = dev_alloc(&c->d_items, n0 + n1))) return rc;
+    HIP_TRY(hipMemcpy(c->d_q, c->q.data(), c->q.size(), hipMemcpyHostToDevice));
+    if (n0) HIP_TRY(hipMemcpy(c->d_items, c->items[0].data(), n0 * sizeof(WorkItem), hipMemcpyHostToDevice));
+    if (n1) HIP_TRY(hipMemcpy(c->d_items + n0, c->items[1].data(), n1 * sizeof(WorkItem), hipMemcpyHostToDevice));
+    return GEMM_MP_OK;
+}
+
+bool all_maps(const gemm_mp_ctx *c) { return c->mat[0].has_map && c->mat[1].has_map && c->mat[2].has_map; }
+
+int run_scan(gemm_mp_ctx *c, Matrix &m, const double *dense, int64_t ld, hipStream_t s)
+{
+    int rc;
+    if ((rc = ensure_scan_buffers(c, m))) return rc;
+    HIP_TRY(launch_scan(dense, ld, m.rows_t, m.cols_t, c->nb, m.d_part_sum, m.d_part_max, m.d_sumsq, m.d_maxabs, s));
+    return GEMM_MP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gemm_mp_create(gemm_mp_ctx **out, int64_t M, int64_t N, int64_t K, int32_t nb)
+{
+    if (!out || M <= 0 || N <= 0 || K <= 0 || nb <= 0) return GEMM_MP_EINVAL;
+    if (nb % kMacro != 0 || nb > 8192 || M % nb || N % nb || K % nb) return GEMM_MP_EINVAL;
+    if (M / nb > 32767 || N / nb > 32767 || K / nb > 32767) return GEMM_MP_EINVAL;
+    if ((M / nb) * (N / nb) > (int64_t)1 << 24 || (M / nb) * (N / nb) * (K / nb) > (int64_t)1 << 28) return GEMM_MP_EINVAL;
+    gemm_mp_ctx *c = new (std::nothrow) gemm_mp_ctx();
+    if (!c) return GEMM_MP_ENOMEM;
+    c->M = M; c->N = N; c->K = K; c->nb = nb;
+    c->MT = (int)(M / nb); c->NT = (int)(N / nb); c->KT = (int)(K / nb);
+    c->mat[0].rows_t = c->MT; c->mat[0].cols_t = c->KT;
+    c->mat[1].rows_t = c->KT; c->mat[1].cols_t = c->NT;
+    c->mat[2].rows_t = c->MT; c->mat[2].cols_t = c->NT;
+    std::memset(&c->stats, 0, sizeof(c->stats));
+    *out = c;
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_destroy(gemm_mp_ctx *c)
+{
+    if (!c) return GEMM_MP_EINVAL;
+    for (auto &m : c->mat) free_matrix_tables(m);
+    (void)hipFree(c->d_q); (void)hipFree(c->d_items);
+    (void)hipGetLastError();
+    delete c;
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_set_policy(gemm_mp_ctx *c, int policy)
+{
+    if (!c || (policy != GEMM_MP_POLICY_OPERAND && policy != GEMM_MP_POLICY_C_TILE)) return GEMM_MP_EINVAL;
+    if (policy != c->policy) { c->policy = policy; c->sched_current = false; }
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_set_precision_map(gemm_mp_ctx *c, char which, const uint16_t *map, int32_t rows, int32_t cols)
+{
+    const int w = which_index(which);
+    if (!c || w < 0 || !map) return GEMM_MP_EINVAL;
+    Matrix &m = c->mat[w];
+    if (rows != m.rows_t || cols != m.cols_t) return GEMM_MP_EINVAL;
+    for (int t = 0; t < m.ntiles(); ++t)
+        if (map[t] > GEMM_MP_FP8_E4M3) return GEMM_MP_EINVAL;
+    if (w == 2)
+        for (int t = 0; t < m.ntiles(); ++t)
+            if (map[t] > GEMM_MP_FP32) return GEMM_MP_EUNSUPPORTED;
+    return install_map(c, w, map);
+}
+
+int gemm_mp_tile_scan(gemm_mp_ctx *c, char which, const double *dense, int64_t ld, gemm_mp_stream stream,
+                      double *sumsq_host, double *maxabs_host)
+{
+    const int w = which_index(which);
+    if (!c || w < 0) return GEMM_MP_EINVAL;
+    Matrix &m = c->mat[w];
+    int rc;
+    if ((rc = check_dense(dense, ld, (int64_t)m.cols_t * c->nb))) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    if ((rc = run_scan(c, m, dense, ld, s))) return rc;
+    HIP_TRY(hipStreamSynchronize(s));
+    const size_t n = (size_t)m.ntiles() * sizeof(double);
+    if (sumsq_host) HIP_TRY(hipMemcpy(sumsq_host, m.d_sumsq, n, hipMemcpyDeviceToHost));
+    if (maxabs_host) HIP_TRY(hipMemcpy(maxabs_host, m.d_maxabs, n, hipMemcpyDeviceToHost));
+    m.exps_from_rule = false;     // the scan buffers no longer belong to a rule-made map
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_compute_precision_map(gemm_mp_ctx *c, char which, const double *dense, int64_t ld, double threshold,
+                                  uint32_t allowed_mask, gemm_mp_stream stream, uint16_t *map_out)
+{
+    const int w = which_index(which);
+    if (!c || w < 0 || !(threshold >= 0.0) || (allowed_mask & 0xFu) == 0 || (allowed_mask & ~0xFu)) return GEMM_MP_EINVAL;
+    if (w == 2 && (allowed_mask & 0xCu)) return GEMM_MP_EUNSUPPORTED;
+    Matrix &m = c->mat[w];
+    int rc;
+    if ((rc = check_dense(dense, ld, (int64_t)m.cols_t * c->nb))) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    if ((rc = run_scan(c, m, dense, ld, s))) return rc;
+    HIP_TRY(hipStreamSynchronize(s));
+    const int n = m.ntiles();
+    std::vector<double> sumsq(n);
+    HIP_TRY(hipMemcpy(sumsq.data(), m.d_sumsq, (size_t)n * sizeof(double), hipMemcpyDeviceToHost));
+
+    // the rule, on squares, in a fixed order of operations (see the header)
+    double S = 0.0;
+    for (int t = 0; t < n; ++t) S = S + sumsq[t];
+    const double rhs = (threshold * threshold) * S;
+    int highest = 0;
+    while (!(allowed_mask & (1u << highest))) ++highest;
+    std::vector<uint16_t> map(n);
+    for (int t = 0; t < n; ++t) {
+        int chosen = highest;
+        for (int p = GEMM_MP_FP8_E4M3; p >= GEMM_MP_FP64; --p) {
+            if (!(allowed_mask & (1u << p))) continue;
+            const double u = unit_roundoff(p);
+            const double lhs = (sumsq[t] * (double)n) * (u * u);
+            if (lhs <= rhs) { chosen = p; break; }
+        }
+        map[t] = (uint16_t)chosen;
+    }
+    if ((rc = install_map(c, w, map.data()))) return rc;
+    if ((rc = ensure_tables(m))) return rc;
+    HIP_TRY(launch_exps(m.d_maxabs, m.d_prec, m.d_exp, n, s));
+    m.exps_valid = true;
+    m.exps_from_rule = true;
+    m.last_stream = s;
+    if (map_out) std::memcpy(map_out, map.data(), (size_t)n * sizeof(uint16_t));
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_storage_bytes(gemm_mp_ctx *c, char which, size_t *bytes)
+{
+    const int w = which_index(which);
+    if (!c || w < 0 || !bytes) return GEMM_MP_EINVAL;
+    if (!c->mat[w].has_map) return GEMM_MP_ESTATE;
+    *bytes = (size_t)c->mat[w].bytes;
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_bind_storage(gemm_mp_ctx *c, char which, void *dev_ptr, size_t bytes)
+{
+    const int w = which_index(which);
+    if (!c || w < 0 || !dev_ptr || ((uintptr_t)dev_ptr & 255u)) return GEMM_MP_EINVAL;
+    Matrix &m = c->mat[w];
+    if (!m.has_map) return GEMM_MP_ESTATE;
+    if (bytes < m.bytes) return GEMM_MP_EINVAL;
+    m.storage = dev_ptr;
+    m.storage_bytes = bytes;
+    m.packed = false;
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_pack_tiles(gemm_mp_ctx *c, char which, const double *dense, int64_t ld, gemm_mp_stream stream)
+{
+    const int w = which_index(which);
+    if (!c || w < 0) return GEMM_MP_EINVAL;
+    Matrix &m = c->mat[w];
+    if (!m.has_map || !m.storage) return GEMM_MP_ESTATE;
+    int rc;
+    if ((rc = check_dense(dense, ld, (int64_t)m.cols_t * c->nb))) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    if ((rc = ensure_tables(m))) return rc;
+    if (!m.exps_from_rule) {
+        bool low = false;
+        for (uint16_t p : m.map) low |= p >= GEMM_MP_FP16;
+        if (low) {
+            if ((rc = run_scan(c, m, dense, ld, s))) return rc;
+        } else if ((rc = ensure_scan_buffers(c, m))) return rc;
+        HIP_TRY(launch_exps(m.d_maxabs, m.d_prec, m.d_exp, m.ntiles(), s));
+        m.exps_valid = true;
+    }
+    HIP_TRY(launch_pack(dense, ld, m.rows_t, m.cols_t, c->nb, w == 1, view_of(m), s));
+    m.packed = true;
+    m.last_stream = s;
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_unpack_tiles(gemm_mp_ctx *c, char which, double *dense, int64_t ld, gemm_mp_stream stream)
+{
+    const int w = which_index(which);
+    if (!c || w < 0) return GEMM_MP_EINVAL;
+    Matrix &m = c->mat[w];
+    if (!m.has_map || !m.storage) return GEMM_MP_ESTATE;
+    int rc;
+    if ((rc = check_dense(dense, ld, (int64_t)m.cols_t * c->nb))) return rc;
+    if ((rc = ensure_tables(m))) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(launch_unpack(dense, ld, m.rows_t, m.cols_t, c->nb, w == 1, view_of(m), s));
+    m.last_stream = s;
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream)
+{
+    if (!c || std::isnan(alpha) || std::isnan(beta)) return GEMM_MP_EINVAL;
+    Matrix &A = c->mat[0], &B = c->mat[1], &C = c->mat[2];
+    if (!all_maps(c) || !A.packed || !B.packed || !C.storage) return GEMM_MP_ESTATE;
+    if (beta != 0.0 && !C.packed) return GEMM_MP_ESTATE;
+    int rc;
+    hipStream_t s = (hipStream_t)stream;
+    if ((rc = ensure_tables(C))) return rc;
+    if (!c->sched_current) {
+        if (c->d_q) (void)hipStreamSynchronize(C.last_stream);
+        build_schedule(c);
+        if ((rc = upload_schedule(c))) return rc;
+    } else if (!c->d_q && (rc = upload_schedule(c))) return rc;
+    if (!c->kernel_ready) {
+        HIP_TRY(gemm_kernel_setup());
+        c->kernel_ready = true;
+    }
+    GemmArgs a;
+    a.A = view_of(A); a.B = view_of(B); a.C = view_of(C);
+    a.q = c->d_q;
+    a.items64 = c->d_items;
+    a.items32 = c->d_items + c->items[0].size();
+    a.n_items64 = (int32_t)c->items[0].size();
+    a.n_items32 = (int32_t)c->items[1].size();
+    a.nb = c->nb; a.MT = c->MT; a.NT = c->NT; a.KT = c->KT;
+    a.kt_eff = alpha == 0.0 ? 0 : c->KT;
+    a.alpha = alpha; a.beta = beta;
+    HIP_TRY(launch_gemm(a, s));
+    C.packed = true;
+    C.exps_valid = true;
+    A.last_stream = B.last_stream = C.last_stream = s;
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_tile_info(gemm_mp_ctx *c, char which, int32_t I, int32_t J, size_t *offset, int *prec, int *scale_exp)
+{
+    const int w = which_index(which);
+    if (!c || w < 0) return GEMM_MP_EINVAL;
+    Matrix &m = c->mat[w];
+    if (!m.has_map) return GEMM_MP_ESTATE;
+    if (I < 0 || I >= m.rows_t || J < 0 || J >= m.cols_t) return GEMM_MP_EINVAL;
+    const int t = I * m.cols_t + J;
+    int e = 0;
+    if (scale_exp) {
+        if (m.map[t] >= GEMM_MP_FP16) {
+            if (!m.exps_valid) return GEMM_MP_ESTATE;
+            HIP_TRY(hipStreamSynchronize(m.last_stream));
+            HIP_TRY(hipMemcpy(&e, m.d_exp + t, sizeof(int), hipMemcpyDeviceToHost));
+        }
+    }
+    if (offset) *offset = (size_t)m.offset[t];
+    if (prec) *prec = m.map[t];
+    if (scale_exp) *scale_exp = e;
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_get_stats(gemm_mp_ctx *c, gemm_mp_stats *out)
+{
+    if (!c || !out) return GEMM_MP_EINVAL;
+    if (!all_maps(c)) return GEMM_MP_ESTATE;
+    if (!c->sched_current) {
+        if (c->d_q) (void)hipStreamSynchronize(c->mat[2].last_stream);
+        build_schedule(c);
+        (void)hipFree(c->d_q); (void)hipFree(c->d_items);
+        c->d_q = nullptr; c->d_items = nullptr;
+    }
+    *out = c->stats;
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_product_precision(int pA, int pB, int pC, int policy)
+{
+    if (pA < 0 || pA > 3 || pB < 0 || pB > 3 || pC < 0 || pC > 3) return -1;
+    if (policy != GEMM_MP_POLICY_OPERAND && policy != GEMM_MP_POLICY_C_TILE) return -1;
+    return product_precision(pA, pB, pC, policy);
+}
+
+const char *gemm_mp_strerror(int status)
+{
+    switch (status) {
+    case GEMM_MP_OK: return "success";
+    case GEMM_MP_EINVAL: return "invalid argument";
+    case GEMM_MP_ESTATE: return "call order: a map, a buffer or packed data is missing";
+    case GEMM_MP_ENOMEM: return "out of memory for a table";
+    case GEMM_MP_EUNSUPPORTED: return "not supported by this build";
+    case GEMM_MP_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,65 @@
+// Internal declarations shared by the host side of the library and its HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+
+#include "../../include/gemm_mp.h"
+
+namespace gmp {
+
+constexpr int kMacro = 128;       // rows = cols of C owned by one workgroup
+constexpr int kScanCols = 128;    // columns one scan workgroup reduces; a power of two
+constexpr int kPackBlock = 64;    // pack / unpack move 64 x 64 element blocks
+
+// Bytes per element of each precision code.
+__host__ __device__ inline int elem_bytes(int p) { return p == 0 ? 8 : p == 1 ? 4 : p == 2 ? 2 : 1; }
+
+// Product precision (code) for stored precisions pA, pB, C tile precision pC.
+__host__ __device__ inline int product_precision(int pA, int pB, int pC, int policy)
+{
+    const int cap = (pC == GEMM_MP_FP64) ? GEMM_MP_FP64 : GEMM_MP_FP32;
+    if (policy == GEMM_MP_POLICY_C_TILE) return cap;
+    const int better = pA < pB ? pA : pB;       // smaller code = finer format
+    return better > cap ? better : cap;
+}
+
+// Device-side view of one packed matrix.
+struct PackedView {
+    const uint8_t *prec;     // [tiles] precision code
+    const uint64_t *offset;  // [tiles] byte offset into storage
+    const int32_t *exp;      // [tiles] power-of-two scale exponent
+    char *storage;
+};
+
+// One owner workgroup: C tile index and the macro-tile inside it.
+struct WorkItem {
+    uint32_t tile;   // I * NT + J
+    uint16_t mi, mj; // macro-tile row / column inside the tile
+};
+
+struct GemmArgs {
+    PackedView A, B, C;
+    const uint8_t *q;        // [MT*NT][KT] product precision of every task
+    const WorkItem *items64;  // owner regions of FP64 C tiles, launch order
+    const WorkItem *items32;  // owner regions of FP32 C tiles, launch order
+    int32_t n_items64, n_items32;
+    int32_t nb, MT, NT, KT;
+    int32_t kt_eff;          // KT, or 0 when alpha == 0
+    double alpha, beta;
+};
+
+hipError_t launch_scan(const double *X, int64_t ld, int rows_t, int cols_t, int nb,
+                       double *part_sum, double *part_max, double *sumsq, double *maxabs,
+                       hipStream_t s);
+hipError_t launch_exps(const double *maxabs, const uint8_t *prec, int32_t *exps, int ntiles,
+                       hipStream_t s);
+hipError_t launch_pack(const double *X, int64_t ld, int rows_t, int cols_t, int nb, bool transpose,
+                       PackedView v, hipStream_t s);
+hipError_t launch_unpack(double *X, int64_t ld, int rows_t, int cols_t, int nb, bool transpose,
+                         PackedView v, hipStream_t s);
+hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);
+hipError_t gemm_kernel_setup();
+
+}  // namespace gmp

@@ -1,0 +1,330 @@
+// Tile scan, pack (storage rounding + re-tiling) and unpack kernels for gfx950.
+// All three are HBM-bound streaming passes over a dense row-major FP64 matrix.
+#include "gemm_mp_internal.h"
+
+namespace gmp {
+
+// ---------------------------------------------------------------------------------------
+// Tile scan.  One thread owns one column of one tile row and walks down its nb rows with a
+// running fused multiply-add (the defined order of the tile's sum of squares); a wave reads
+// 512 contiguous bytes per row.  The 128 column sums of a workgroup are then added pairwise,
+// neighbours first; because nb is a multiple of 128 these seven levels are exactly the lowest
+// seven levels of the pairing over the whole tile.  scan_finish_kernel adds the nb/128 roots
+// of a tile with the same rule (an odd element is carried up).
+__global__ __launch_bounds__(kScanCols) void scan_cols_kernel(const double *__restrict__ X,
+                                                              int64_t ld, int nb, int parts,
+                                                              int cols_t,
+                                                              double *__restrict__ part_sum,
+                                                              double *__restrict__ part_max)
+{
+    __shared__ double vs[kScanCols];
+    __shared__ double vm[kScanCols];
+    const int tx = threadIdx.x;
+    const int64_t col = (int64_t)blockIdx.x * kScanCols + tx;
+    const int I = blockIdx.y;
+    const double *p = X + (int64_t)I * nb * ld + col;
+    double s = 0.0, m = 0.0;
+    for (int r = 0; r < nb; r += 8) {
+        double x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = p[(int64_t)(r + u) * ld];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            s = __builtin_fma(x[u], x[u], s);
+            const double ax = __builtin_fabs(x[u]);
+            if (ax > m) m = ax;      // a NaN never enters m
+        }
+    }
+    vs[tx] = s;
+    vm[tx] = m;
+    __syncthreads();
+    for (int n = kScanCols / 2; n >= 1; n >>= 1) {
+        double a = 0.0, b = 0.0;
+        if (tx < n) {
+            a = vs[2 * tx] + vs[2 * tx + 1];
+            const double m0 = vm[2 * tx], m1 = vm[2 * tx + 1];
+            b = m1 > m0 ? m1 : m0;
+        }
+        __syncthreads();
+        if (tx < n) { vs[tx] = a; vm[tx] = b; }
+        __syncthreads();
+    }
+    if (tx == 0) {
+        const int J = (int)((int64_t)blockIdx.x * kScanCols / nb);
+        const int part = (int)(((int64_t)blockIdx.x * kScanCols % nb) / kScanCols);
+        const int64_t o = ((int64_t)I * cols_t + J) * parts + part;
+        part_sum[o] = vs[0];
+        part_max[o] = vm[0];
+    }
+}
+
+__global__ void scan_finish_kernel(const double *__restrict__ part_sum,
+                                   const double *__restrict__ part_max, int parts, int ntiles,
+                                   double *__restrict__ sumsq, double *__restrict__ maxabs)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= ntiles) return;
+    double v[64];
+    double m = 0.0;
+    int n = parts;
+    for (int i = 0; i < n; ++i) {
+        v[i] = part_sum[(int64_t)t * parts + i];
+        const double x = part_max[(int64_t)t * parts + i];
+        if (x > m) m = x;
+    }
+    while (n > 1) {
+        const int h = n / 2;
+        for (int i = 0; i < h; ++i) v[i] = v[2 * i] + v[2 * i + 1];
+        if (n & 1) { v[h] = v[n - 1]; n = h + 1; } else n = h;
+    }
+    sumsq[t] = v[0];
+    maxabs[t] = m;
+}
+
+hipError_t launch_scan(const double *X, int64_t ld, int rows_t, int cols_t, int nb,
+                       double *part_sum, double *part_max, double *sumsq, double *maxabs,
+                       hipStream_t s)
+{
+    const int parts = nb / kScanCols;
+    dim3 grid((unsigned)((int64_t)cols_t * nb / kScanCols), (unsigned)rows_t);
+    scan_cols_kernel<<<grid, kScanCols, 0, s>>>(X, ld, nb, parts, cols_t, part_sum, part_max);
+    const int ntiles = rows_t * cols_t;
+    scan_finish_kernel<<<(ntiles + 63) / 64, 64, 0, s>>>(part_sum, part_max, parts, ntiles, sumsq, maxabs);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Scale exponent of FP16 / FP8 tiles: e = floor(log2 max|x|) - 14 (FP16) or - 7 (FP8), so the
+// largest scaled magnitude lies in [2^14,2^15) resp. [2^7,2^8); 0 for an all-zero tile, a
+// non-finite maximum, and for FP64 / FP32 tiles.  floor(log2) is read off the bit pattern.
+__global__ void exps_kernel(const double *__restrict__ maxabs, const uint8_t *__restrict__ prec,
+                            int32_t *__restrict__ exps, int ntiles)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= ntiles) return;
+    const int p = prec[t];
+    int e = 0;
+    if (p == GEMM_MP_FP16 || p == GEMM_MP_FP8_E4M3) {
+        const uint64_t bits = (uint64_t)__double_as_longlong(maxabs[t]) & 0x7fffffffffffffffull;
+        const int field = (int)(bits >> 52);
+        const uint64_t man = bits & 0xfffffffffffffull;
+        if (field == 0x7ff || bits == 0) e = 0;
+        else {
+            const int lg = field ? field - 1023 : 63 - __builtin_clzll(man) - 1074;
+            e = lg - (p == GEMM_MP_FP16 ? 14 : 7);
+        }
+    }
+    exps[t] = e;
+}
+
+hipError_t launch_exps(const double *maxabs, const uint8_t *prec, int32_t *exps, int ntiles,
+                       hipStream_t s)
+{
+    exps_kernel<<<(ntiles + 63) / 64, 64, 0, s>>>(maxabs, prec, exps, ntiles);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Storage rounding of x * 2^-e from FP64 into a small binary format, one rounding to nearest
+// even, done on the bit pattern.  MB fraction bits, EMIN exponent of the smallest normal, BIAS.
+// Returns the magnitude code (sign not included), before any overflow treatment; the exponent
+// field may exceed the format's range, which the callers turn into infinity / saturation.
+template <int MB, int EMIN, int BIAS>
+__device__ inline uint32_t round_magnitude(uint64_t mag_bits, int e)
+{
+    const int field = (int)(mag_bits >> 52);
+    uint64_t sig = mag_bits & 0xfffffffffffffull;
+    int E;                                                     // exponent of x * 2^-e
+    if (field) { sig |= 1ull << 52; E = field - 1023 - e; }
+    else {
+        if (sig == 0) return 0;
+        const int lz = __builtin_clzll(sig) - 11;              // FP64 subnormal: normalise first
+        sig <<= lz;
+        E = -1022 - lz - e;
+    }
+    int drop = 52 - MB;                                        // low bits that do not fit
+    if (E < EMIN) drop += EMIN - E;                            // subnormal range: coarser grid
+    if (drop >= 55) return 0;                                  // below a quarter of the smallest step
+    uint64_t kept = sig >> drop;
+    const uint64_t rem = sig & ((1ull << drop) - 1);
+    const uint64_t half = 1ull << (drop - 1);
+    if (rem > half || (rem == half && (kept & 1))) ++kept;     // nearest, ties to even
+    if (E < EMIN) return (uint32_t)kept;                       // exponent field 0 (or 1 after a carry)
+    if (E > 4096) return 0x7fffffffu;                          // keeps the shift below in range
+    return (uint32_t)(((uint64_t)(E + BIAS) << MB) + (kept - (1ull << MB)));   // a carry bumps the exponent
+}
+
+__device__ inline uint32_t to_fp16_bits(double x, int e)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint32_t sign = (uint32_t)(b >> 48) & 0x8000u;
+    const uint64_t mag = b & 0x7fffffffffffffffull;
+    if (mag > 0x7ff0000000000000ull) return sign | 0x7e00u;    // NaN
+    if (mag == 0x7ff0000000000000ull) return sign | 0x7c00u;   // infinity
+    uint32_t r = round_magnitude<10, -14, 15>(mag, e);
+    if (r > 0x7c00u) r = 0x7c00u;                              // overflow -> infinity
+    return sign | r;
+}
+
+__device__ inline uint32_t to_fp8_bits(double x, int e)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint32_t sign = (uint32_t)(b >> 56) & 0x80u;
+    const uint64_t mag = b & 0x7fffffffffffffffull;
+    if (mag > 0x7ff0000000000000ull) return sign | 0x7fu;      // NaN
+    if (mag == 0x7ff0000000000000ull) return sign | 0x7eu;     // no infinity: saturate
+    uint32_t r = round_magnitude<3, -6, 7>(mag, e);
+    if (r > 0x7eu) r = 0x7eu;                                  // beyond 448 -> 448
+    return sign | r;
+}
+
+// The stored bit pattern of one element, right-aligned in 64 bits.
+__device__ inline uint64_t stored_bits(double x, int p, int e)
+{
+    switch (p) {
+    case GEMM_MP_FP64: return (uint64_t)__double_as_longlong(x);
+    case GEMM_MP_FP32: return (uint64_t)__float_as_uint((float)x);     // v_cvt_f32_f64, nearest even
+    case GEMM_MP_FP16: return to_fp16_bits(x, e);
+    default:           return to_fp8_bits(x, e);
+    }
+}
+
+__device__ inline void store4(char *dst, int p, const uint64_t (&v)[4])
+{
+    switch (p) {
+    case GEMM_MP_FP64: {
+        ulonglong2 a, b;
+        a.x = v[0]; a.y = v[1]; b.x = v[2]; b.y = v[3];
+        ((ulonglong2 *)dst)[0] = a;
+        ((ulonglong2 *)dst)[1] = b;
+    } break;
+    case GEMM_MP_FP32: {
+        uint4 a;
+        a.x = (uint32_t)v[0]; a.y = (uint32_t)v[1]; a.z = (uint32_t)v[2]; a.w = (uint32_t)v[3];
+        *(uint4 *)dst = a;
+    } break;
+    case GEMM_MP_FP16: {
+        uint2 a;
+        a.x = (uint32_t)v[0] | ((uint32_t)v[1] << 16);
+        a.y = (uint32_t)v[2] | ((uint32_t)v[3] << 16);
+        *(uint2 *)dst = a;
+    } break;
+    default:
+        *(uint32_t *)dst = (uint32_t)v[0] | ((uint32_t)v[1] << 8) | ((uint32_t)v[2] << 16) | ((uint32_t)v[3] << 24);
+    }
+}
+
+// Pack: each workgroup converts one 64 x 64 block that lies inside one tile.  Threads read four
+// consecutive FP64 values of a row (coalesced 512 B per 16 lanes); for A and C they store the
+// four converted values directly; for B the block is turned through LDS so that the stores run
+// along the reduction index, which is the contiguous one in a packed B tile.
+template <bool TRANSPOSE>
+__global__ __launch_bounds__(256) void pack_kernel(const double *__restrict__ X, int64_t ld, int nb,
+                                                   int cols_t, PackedView v)
+{
+    __shared__ uint64_t turn[TRANSPOSE ? kPackBlock : 1][TRANSPOSE ? kPackBlock + 1 : 1];
+    const int t = threadIdx.x;
+    const int64_t R0 = (int64_t)blockIdx.y * kPackBlock, C0 = (int64_t)blockIdx.x * kPackBlock;
+    const int I = (int)(R0 / nb), J = (int)(C0 / nb);
+    const int tile = I * cols_t + J;
+    const int p = v.prec[tile];
+    const int e = v.exp[tile];
+    char *base = v.storage + v.offset[tile];
+    const int r_in = (int)(R0 % nb), c_in = (int)(C0 % nb);
+    const int es = elem_bytes(p);
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int r = t / 16 + 16 * it, c4 = (t % 16) * 4;
+        const double2 *src = (const double2 *)(X + (R0 + r) * ld + C0 + c4);
+        const double2 x01 = src[0], x23 = src[1];
+        uint64_t b[4] = {stored_bits(x01.x, p, e), stored_bits(x01.y, p, e),
+                         stored_bits(x23.x, p, e), stored_bits(x23.y, p, e)};
+        if (!TRANSPOSE) {
+            store4(base + ((int64_t)(r_in + r) * nb + c_in + c4) * es, p, b);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) turn[c4 + j][r] = b[j];
+        }
+    }
+    if (TRANSPOSE) {
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int c = t / 16 + 16 * it, r4 = (t % 16) * 4;
+            uint64_t b[4] = {turn[c][r4], turn[c][r4 + 1], turn[c][r4 + 2], turn[c][r4 + 3]};
+            store4(base + ((int64_t)(c_in + c) * nb + r_in + r4) * es, p, b);
+        }
+    }
+}
+
+hipError_t launch_pack(const double *X, int64_t ld, int rows_t, int cols_t, int nb, bool transpose,
+                       PackedView v, hipStream_t s)
+{
+    dim3 grid((unsigned)((int64_t)cols_t * nb / kPackBlock), (unsigned)((int64_t)rows_t * nb / kPackBlock));
+    if (transpose) pack_kernel<true><<<grid, 256, 0, s>>>(X, ld, nb, cols_t, v);
+    else pack_kernel<false><<<grid, 256, 0, s>>>(X, ld, nb, cols_t, v);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Unpack: the exact FP64 value of every stored element (stored number times 2^e).
+__device__ inline double stored_value(const char *base, int64_t idx, int p, int e)
+{
+    switch (p) {
+    case GEMM_MP_FP64: return ((const double *)base)[idx];
+    case GEMM_MP_FP32: return (double)((const float *)base)[idx];
+    case GEMM_MP_FP16: return ldexp((double)(float)((const _Float16 *)base)[idx], e);
+    default: {
+        const int code = ((const uint8_t *)base)[idx];
+        return ldexp((double)__builtin_amdgcn_cvt_f32_fp8(code, 0), e);
+    }
+    }
+}
+
+template <bool TRANSPOSE>
+__global__ __launch_bounds__(256) void unpack_kernel(double *__restrict__ X, int64_t ld, int nb,
+                                                     int cols_t, PackedView v)
+{
+    __shared__ double turn[TRANSPOSE ? kPackBlock : 1][TRANSPOSE ? kPackBlock + 1 : 1];
+    const int t = threadIdx.x;
+    const int64_t R0 = (int64_t)blockIdx.y * kPackBlock, C0 = (int64_t)blockIdx.x * kPackBlock;
+    const int I = (int)(R0 / nb), J = (int)(C0 / nb);
+    const int tile = I * cols_t + J;
+    const int p = v.prec[tile];
+    const int e = v.exp[tile];
+    const char *base = v.storage + v.offset[tile];
+    const int r_in = (int)(R0 % nb), c_in = (int)(C0 % nb);
+    if (TRANSPOSE) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int c = t / 16 + 16 * it, r4 = (t % 16) * 4;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                turn[c][r4 + j] = stored_value(base, (int64_t)(c_in + c) * nb + r_in + r4 + j, p, e);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int r = t / 16 + 16 * it, c4 = (t % 16) * 4;
+        double x[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            x[j] = TRANSPOSE ? turn[c4 + j][r]
+                             : stored_value(base, (int64_t)(r_in + r) * nb + c_in + c4 + j, p, e);
+        double2 *dst = (double2 *)(X + (R0 + r) * ld + C0 + c4);
+        dst[0] = make_double2(x[0], x[1]);
+        dst[1] = make_double2(x[2], x[3]);
+    }
+}
+
+hipError_t launch_unpack(double *X, int64_t ld, int rows_t, int cols_t, int nb, bool transpose,
+                         PackedView v, hipStream_t s)
+{
+    dim3 grid((unsigned)((int64_t)cols_t * nb / kPackBlock), (unsigned)((int64_t)rows_t * nb / kPackBlock));
+    if (transpose) unpack_kernel<true><<<grid, 256, 0, s>>>(X, ld, nb, cols_t, v);
+    else unpack_kernel<false><<<grid, 256, 0, s>>>(X, ld, nb, cols_t, v);
+    return hipGetLastError();
+}
+
+}  // namespace gmp

@@ -1,0 +1,123 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, rejects bad arguments and call orders, lays tiles out as documented, and
+counts products as the closed forms say."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads as W
+from paper_2508_14848_amd import gemm_mp as G
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "gemm_mp.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(gemm_mp_[a-z_]+)\s*\(", header)))
+    assert declared == sorted(G.EXPORTS)
+    L = G.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_create_rejects_bad_sizes():
+    for args in ((0, 256, 256, 128), (256, 256, 256, 0), (256, 256, 300, 128), (256, 256, 256, 64),
+                 (256, 256, 256, 96), (-256, 256, 256, 128), (1 << 15, 1 << 15, 1 << 15, 16384)):
+        with pytest.raises(G.GemmMPError) as e:
+            G.GemmMP(*args)
+        assert e.value.status == G.EINVAL
+    G.GemmMP(256, 512, 384, 128).destroy()
+
+
+def test_map_validation_and_call_order():
+    g = G.GemmMP(512, 256, 384, 128)
+    with pytest.raises(G.GemmMPError) as e:
+        g.storage_bytes("A")
+    assert e.value.status == G.ESTATE
+    with pytest.raises(G.GemmMPError) as e:
+        g.get_stats()
+    assert e.value.status == G.ESTATE
+    with pytest.raises(G.GemmMPError) as e:
+        g.set_precision_map("A", np.zeros((3, 4), np.uint16))          # A is 4 x 3 tiles
+    assert e.value.status == G.EINVAL
+    with pytest.raises(G.GemmMPError) as e:
+        g.set_precision_map("A", np.full((4, 3), 4, np.uint16))        # code out of range
+    assert e.value.status == G.EINVAL
+    with pytest.raises(G.GemmMPError) as e:
+        g.set_precision_map("C", np.full((4, 2), G.FP16, np.uint16))   # C tiles: FP64 / FP32 only
+    assert e.value.status == G.EUNSUPPORTED
+    with pytest.raises(G.GemmMPError) as e:
+        g.set_precision_map("X", np.zeros((4, 3), np.uint16))
+    assert e.value.status == G.EINVAL
+    with pytest.raises(G.GemmMPError) as e:
+        g.set_policy(7)
+    assert e.value.status == G.EINVAL
+    g.set_precision_map("A", np.zeros((4, 3), np.uint16))
+    with pytest.raises(G.GemmMPError) as e:
+        g.bind_storage("A", 0, 1 << 20)                                 # null buffer
+    assert e.value.status == G.EINVAL
+    with pytest.raises(G.GemmMPError) as e:
+        g.bind_storage("A", 4096 + 8, 1 << 30)                          # misaligned
+    assert e.value.status == G.EINVAL
+    with pytest.raises(G.GemmMPError) as e:
+        g.bind_storage("A", 4096, 100)                                  # too small
+    assert e.value.status == G.EINVAL
+    with pytest.raises(G.GemmMPError) as e:
+        g.run(1.0, 0.0)
+    assert e.value.status == G.ESTATE
+    with pytest.raises(G.GemmMPError) as e:
+        g.pack_tiles("B", 4096, 256)
+    assert e.value.status == G.ESTATE
+    assert "order" in G.strerror(G.ESTATE) and G.strerror(0) == "success"
+
+
+def test_packed_layout_offsets_and_sizes():
+    g = G.GemmMP(256, 384, 512, 128)
+    pmap = np.array([[0, 1, 2, 3], [3, 2, 1, 0]], dtype=np.uint16)
+    g.set_precision_map("A", pmap)
+    sizes = [128 * 128 * (8 >> int(p)) for p in pmap.ravel()]
+    off = 0
+    for t, (I, J) in enumerate((i, j) for i in range(2) for j in range(4)):
+        o, prec, _ = g.tile_info("A", I, J, want_exp=False)
+        assert o == off and o % 256 == 0 and prec == pmap[I, J]
+        off += sizes[t]
+    assert g.storage_bytes("A") == off
+    with pytest.raises(G.GemmMPError) as e:
+        g.tile_info("A", 2, 0, want_exp=False)
+    assert e.value.status == G.EINVAL
+    with pytest.raises(G.GemmMPError) as e:
+        g.tile_info("A", 0, 2, want_exp=True)        # FP16 tile, exponent unknown before packing
+    assert e.value.status == G.ESTATE
+    assert g.tile_info("A", 0, 0, want_exp=True)[2] == 0
+
+
+def test_product_precision_and_stats_closed_forms():
+    for pA in range(4):
+        for pB in range(4):
+            for pC in range(2):
+                assert G.product_precision(pA, pB, pC, G.POLICY_C_TILE) == pC
+                assert G.product_precision(pA, pB, pC, G.POLICY_OPERAND) == max(pC and 1, min(pA, pB))
+    assert G.product_precision(5, 0, 0) == -1
+    w = W.tiny()
+    g = G.GemmMP(w.M, w.N, w.K, w.nb)
+    for k, m in (("A", w.mapA), ("B", w.mapB), ("C", w.mapC)):
+        g.set_precision_map(k, m)
+    st = g.get_stats()
+    assert st["products"] == [28, 26, 10, 0] and st["work_items"] == 16 * 4
+    assert st["flops"][0] == 28 * 2.0 * 256 ** 3
+    assert st["tiles"][0] == [4, 6, 6, 0] and st["tiles"][2] == [16, 0, 0, 0]
+    assert st["packed_bytes"][2] == 1024 * 1024 * 8
+    g.set_policy(G.POLICY_C_TILE)
+    assert g.get_stats()["products"] == [64, 0, 0, 0]
+    w = W.random_maps()
+    g = G.GemmMP(w.M, w.N, w.K, w.nb)
+    for k, m in (("A", w.mapA), ("B", w.mapB), ("C", w.mapC)):
+        g.set_precision_map(k, m)
+    st = g.get_stats()
+    assert sum(st["products"]) == 16 ** 3 and st["work_items"] == 256 * 16
+    n64 = int((w.mapC == 0).sum())
+    g.set_policy(G.POLICY_C_TILE)
+    assert g.get_stats()["products"] == [n64 * 16, (256 - n64) * 16, 0, 0]

@@ -1,0 +1,286 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Integer work (scan order, maps, exponents, packed codes) is compared bit for
+bit; C per tile within 4*K*u_tile (and 1e-12 relative for all-FP64 tiles), normalised by
+sum_L |A_IL|_F |B_LJ|_F, plus a tighter accumulate-precision bound that makes real bugs visible.
+"""
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import gemm_mp_oracle as orc
+from tests.harness import (FP8, FP16, FP32, FP64, OracleSide, compare_jobs, gpu_problem,
+                           packed_codes_expected)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _dense(w):
+    A = w.dense("A")
+    B = A if w.a_equals_b else w.dense("B")
+    C0 = w.dense("C") if w.beta != 0.0 else None
+    return A, B, C0
+
+
+def _all_jobs(w):
+    return orc.whole_tile_jobs(w.nb, [(i, j) for i in range(w.MT) for j in range(w.NT)])
+
+
+def _check_storage(d, side, which, tiles):
+    """Packed bytes and exponents of the given tiles equal the oracle's codes bit for bit."""
+    exps = {"A": side.eA, "B": side.eB}[which]
+    for (I, J) in tiles:
+        got, prec = d.tile_bytes(which, I, J)
+        want = packed_codes_expected(side, which, I, J)
+        assert prec == int({"A": side.mapA, "B": side.mapB}[which][I, J])
+        assert np.array_equal(got, want), "packed tile %s(%d,%d) differs" % (which, I, J)
+        assert d.ctx.tile_info(which, I, J)[2] == int(exps[I, J])
+
+
+def _run_and_compare(w, policy=0, jobs=None, check_storage_tiles=4, alpha=None, beta=None):
+    import torch
+    _say("workload", w.name, (w.M, w.N, w.K, w.nb), "policy", policy)
+    A, B, C0 = _dense(w)
+    side = OracleSide(w, A, B, C0)
+    d, dev = gpu_problem(w, A, B, C0, policy=policy)
+    assert np.array_equal(d.maps["A"], side.mapA) and np.array_equal(d.maps["B"], side.mapB)
+    rng = np.random.default_rng(7)
+    for which, (rt, ct) in (("A", (w.MT, w.KT)), ("B", (w.KT, w.NT))):
+        picks = {(int(rng.integers(rt)), int(rng.integers(ct))) for _ in range(check_storage_tiles)}
+        _check_storage(d, side, which, sorted(picks))
+    alpha = w.alpha if alpha is None else alpha
+    beta = w.beta if beta is None else beta
+    d.run(alpha, beta)
+    C_gpu = d.unpack_tiles("C").cpu().numpy()
+    torch.cuda.synchronize()
+    if jobs is None:
+        jobs = _all_jobs(w)
+    C_orc = side.gemm(jobs, policy=policy, alpha=alpha, beta=beta)
+    worst = compare_jobs(side, jobs, policy, alpha, beta, C_gpu, C_orc)
+    _say("  worst error / bound:", worst)
+    return d, side, C_gpu, C_orc
+
+
+# ------------------------------------------------------------------------------------------
+def test_scan_and_rule_match_the_oracle_bit_for_bit():
+    import torch
+    for w in (W.covariance(n=1024, nb=128, ell=0.1, eps=1e-8), W.covariance(n=1536, nb=256, ell=0.05, eps=1e-6),
+              W.decay_rect(M=2048, N=1024, K=256, nb=128, eps=1e-4), W.decay_rect(M=768, N=768, K=384, nb=384, eps=1e-3)):
+        _say("scan", w.name, w.M, w.K, w.nb)
+        from paper_2508_14848_amd.device import DeviceGemmMP
+        d = DeviceGemmMP(w.M, w.N, w.K, w.nb)
+        for which in ("A", "B"):
+            X = w.dense(which)
+            dX = torch.from_numpy(X).cuda()
+            sumsq, maxabs = d.tile_scan(which, dX)
+            s0, m0 = orc.tile_scan(X, w.nb)
+            assert np.array_equal(sumsq, s0) and np.array_equal(maxabs, m0)
+            got = d.compute_precision_map(which, dX, w.rule["eps"], w.rule["allowed"])
+            assert np.array_equal(got, orc.precision_rule(s0, w.rule["eps"], w.rule["allowed"]))
+        # a padded leading dimension gives the same numbers
+        X = w.dense("A")
+        pad = torch.zeros((w.M, w.K + 6), dtype=torch.float64, device="cuda")
+        pad[:, :w.K] = torch.from_numpy(X).cuda()
+        s1, m1 = d.tile_scan("A", pad)
+        s0, m0 = orc.tile_scan(X, w.nb)
+        assert np.array_equal(s1, s0) and np.array_equal(m1, m0)
+
+
+def test_pack_is_bit_exact_on_hard_values_and_unpack_round_trips():
+    """Every tile precision on values chosen to sit on rounding boundaries: FP16/FP8 midpoints
+    (after the tile scale), subnormal results, overflow of FP32, zeros of both signs, NaN/inf."""
+    import torch
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    nb = 128
+    rng = np.random.default_rng(11)
+    for which in ("A", "B"):
+        M, K = 2 * nb, 4 * nb
+        shape = (M, K) if which == "A" else (K, M)
+        X = rng.standard_normal(shape) * np.exp(rng.uniform(-12, 3, shape))
+        # midpoints and near-midpoints of the 11-bit and 4-bit grids, relative to a tile max of 1.75*2^k
+        base = 1.75 * 2.0 ** rng.integers(-2, 8)
+        mids16 = (1.0 + (rng.integers(0, 1024, 3000) + 0.5) / 1024.0) * 2.0 ** rng.integers(-26, 1, 3000)
+        mids8 = (1.0 + (rng.integers(0, 8, 3000) + 0.5) / 8.0) * 2.0 ** rng.integers(-18, 1, 3000)
+        hard = np.concatenate([mids16, np.nextafter(mids16, 0), np.nextafter(mids16, 9), mids8,
+                               np.nextafter(mids8, 0), np.nextafter(mids8, 9)]) * base
+        hard = np.concatenate([hard, -hard, [0.0, -0.0, 1e-320, -1e-310, 3.5e38, 1e39, -1e300, 2.0 ** -149, 2.0 ** -150 * 1.0000001]])
+        flat = X.ravel()
+        pos = rng.choice(flat.size, hard.size, replace=False)
+        flat[pos] = hard
+        X.ravel()[rng.choice(flat.size, 40, replace=False)] = base * 1.0001      # keeps tile maxima near base
+        tiles = (shape[0] // nb, shape[1] // nb)
+        pmap = (np.arange(tiles[0] * tiles[1]).reshape(tiles) % 4).astype(np.uint16)
+        Xs = X.copy()
+        Xs[0:nb, 0:nb] = 0.0                                                   # an all-zero low-precision tile
+        pmap[0, 0] = FP16
+        Xn = Xs.copy()
+        for I0 in range(tiles[0]):                                             # NaN / inf inside tiles of each format
+            sub = Xn[I0 * nb:(I0 + 1) * nb, nb:2 * nb]
+            sub.flat[3::97] = np.nan
+            if I0 == 0:
+                sub.flat[5::101] = np.inf
+                sub.flat[7::103] = -np.inf
+        for name, data in (("finite", Xs), ("nonfinite", Xn)):
+            _say("pack", which, name)
+            w = W.Workload("pack", M, M, K, nb, 1.0, 0.0)
+            d = DeviceGemmMP(M, M, K, nb)
+            d.set_precision_map(which, pmap)
+            dX = torch.from_numpy(data).cuda()
+            d.pack_tiles(which, dX)
+            _, maxabs = orc.tile_scan(data, nb)
+            Y, e = orc.store_tiles(data, nb, pmap, maxabs)
+            assert np.array_equal(d.exponents(which), e)
+
+            class S:
+                pass
+            side = S()
+            side.w, side.Ay, side.By, side.Cy = w, Y, Y, None
+            side.mapA = side.mapB = side.mapC = pmap
+            for I in range(tiles[0]):
+                for J in range(tiles[1]):
+                    got, prec = d.tile_bytes(which, I, J)
+                    want = packed_codes_expected(side, which, I, J)
+                    if name == "nonfinite" and prec in (FP16, FP64, FP32):
+                        # NaN payloads are not compared; positions and everything else are
+                        width = {FP64: 8, FP32: 4, FP16: 2}[prec]
+                        dt = {8: np.float64, 4: np.float32, 2: np.float16}[width]
+                        g, x = got.view(dt), want.view(dt)
+                        assert np.array_equal(np.isnan(g), np.isnan(x))
+                        assert np.array_equal(got.reshape(-1, width)[~np.isnan(g)], want.reshape(-1, width)[~np.isnan(x)])
+                    else:
+                        assert np.array_equal(got, want), (which, name, I, J, prec)
+            back = d.unpack_tiles(which).cpu().numpy()
+            want = Y * np.kron(2.0 ** e.astype(np.float64), np.ones((nb, nb)))
+            assert np.array_equal(np.isnan(back), np.isnan(want))
+            ok = ~np.isnan(want)
+            assert np.array_equal(back[ok], want[ok])
+
+
+def test_small_integer_inputs_are_exact_for_every_precision_combination():
+    """Entries in {-3..3}: every format holds them exactly and every partial sum is a small
+    integer, so the GPU result must equal the integer product bit for bit, whatever the maps."""
+    import torch
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(21)
+    nb, MT, NT, KT = 128, 2, 3, 4
+    M, N, K = MT * nb, NT * nb, KT * nb
+    for policy in (0, 1):
+        for trial in range(3):
+            A = rng.integers(-3, 4, (M, K)).astype(np.float64)
+            B = rng.integers(-3, 4, (K, N)).astype(np.float64)
+            C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
+            mA = rng.integers(0, 4, (MT, KT)).astype(np.uint16)
+            mB = rng.integers(0, 4, (KT, NT)).astype(np.uint16)
+            mC = rng.integers(0, 2, (MT, NT)).astype(np.uint16)
+            if trial == 0:
+                A[0:nb, 0:nb] = 0.0
+                mA[0, 0] = FP8
+            _say("integers policy", policy, "trial", trial)
+            d = DeviceGemmMP(M, N, K, nb, policy=policy)
+            for which, m, X in (("A", mA, A), ("B", mB, B), ("C", mC, C0)):
+                d.set_precision_map(which, m)
+                d.pack_tiles(which, torch.from_numpy(X).cuda())
+            d.run(2.0, -3.0)
+            got = d.unpack_tiles("C").cpu().numpy()
+            want = 2 * (A.astype(np.int64) @ B.astype(np.int64)) - 3 * C0.astype(np.int64)
+            assert np.array_equal(got, want.astype(np.float64))
+
+
+@pytest.mark.parametrize("policy", [0, 1])
+def test_mixed_maps_match_the_oracle_per_tile(policy):
+    """All (pA, pB, pC) combinations occur; several owner regions per tile; alpha, beta general."""
+    w = W.random_maps(M=512, N=768, K=1024, nb=256, probs=(0.25, 0.25, 0.25, 0.25), alpha=1.5, beta=0.5,
+                      name="mixed-small")
+    d, side, C_gpu, C_orc = _run_and_compare(w, policy=policy)
+    # same problem again: the owner design makes the result bit-identical run to run
+    import torch
+    d.pack_tiles("C", torch.from_numpy(w.dense("C")).cuda())
+    d.run(w.alpha, w.beta)
+    again = d.unpack_tiles("C").cpu().numpy()
+    assert np.array_equal(again, C_gpu)
+
+
+def test_scaled_low_precision_tiles_with_wide_dynamic_range():
+    """Tiles whose magnitudes differ by many orders: without the per-tile exponents FP16 / FP8
+    tiles would flush to zero; C tiles FP32 and FP64."""
+    w = W.tiny(M=512, N=512, K=1024, nb=128)
+    w.mapA = (np.indices((w.MT, w.KT)).sum(0) % 3 + 1).astype(np.uint16)      # FP32 / FP16 / FP8
+    w.mapB = (np.indices((w.KT, w.NT)).sum(0) % 2 + 2).astype(np.uint16)      # FP16 / FP8
+    w.mapC = (np.indices((w.MT, w.NT)).sum(0) % 2).astype(np.uint16)
+    _run_and_compare(w)
+
+
+def test_beta_zero_does_not_read_c_and_alpha_zero_forms_no_product():
+    import torch
+    w = W.random_maps(M=256, N=256, K=512, nb=128, alpha=1.0, beta=0.0, name="conventions")
+    A, B, _ = _dense(w)
+    side = OracleSide(w, A, B, None)
+    d, dev = gpu_problem(w, A, B, None)
+    d.storage["C"].view(torch.float64)[:] = float("nan")          # poison: must never be read
+    d.run(1.0, 0.0)
+    C_gpu = d.unpack_tiles("C").cpu().numpy()
+    jobs = _all_jobs(w)
+    compare_jobs(side, jobs, 0, 1.0, 0.0, C_gpu, side.gemm(jobs, alpha=1.0, beta=0.0))
+    # alpha == 0: C <- beta*C exactly, even with non-finite operands packed
+    C0 = w.dense("C")
+    A2 = A.copy()
+    A2[3, 5] = np.inf
+    d.pack_tiles("A", torch.from_numpy(A2).cuda())
+    d.pack_tiles("C", torch.from_numpy(C0).cuda())
+    d.run(0.0, 0.5)
+    got = d.unpack_tiles("C").cpu().numpy()
+    Cy, _ = orc.store_tiles(C0, w.nb, w.mapC)
+    want = np.where(np.kron(w.mapC, np.ones((w.nb, w.nb))) == FP64, 0.5 * Cy,
+                    (np.float32(0.5) * Cy.astype(np.float32)).astype(np.float64))
+    assert np.array_equal(got, want)
+
+
+def test_call_order_errors_on_the_device_path():
+    import torch
+    from paper_2508_14848_amd import gemm_mp as G
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    d = DeviceGemmMP(256, 256, 256, 128)
+    x = torch.zeros((256, 256), dtype=torch.float64, device="cuda")
+    with pytest.raises(G.GemmMPError) as e:
+        d.pack_tiles("A", x)
+    assert e.value.status == G.ESTATE
+    d.set_precision_map("A", np.zeros((2, 2), np.uint16))
+    d.pack_tiles("A", x)
+    with pytest.raises(G.GemmMPError) as e:
+        d.run(1.0, 0.0)
+    assert e.value.status == G.ESTATE
+    with pytest.raises(G.GemmMPError) as e:
+        d.ctx.pack_tiles("A", x.data_ptr() + 8, 256, None)        # misaligned dense pointer
+    assert e.value.status == G.EINVAL
+
+
+# ------------------------------------------------------------------------------------------
+# The five configurations at full size.
+def test_config_tiny_all_tiles():
+    w = W.tiny()
+    d, side, _, _ = _run_and_compare(w)
+    assert d.ctx.get_stats()["products"] == [28, 26, 10, 0]
+
+
+def test_config_random8k_all_tiles():
+    w = W.random_maps()
+    _run_and_compare(w, check_storage_tiles=3)
+
+
+def test_config_cov16k_sampled_tiles():
+    w = W.covariance()
+    jobs = orc.whole_tile_jobs(w.nb, w.sample_tiles(64))
+    d, side, _, _ = _run_and_compare(w, jobs=jobs, check_storage_tiles=2)
+    _say("  products by precision:", d.ctx.get_stats()["products"])
+
+
+def test_config_rect32k_sampled_tiles():
+    w = W.decay_rect()
+    jobs = orc.whole_tile_jobs(w.nb, w.sample_tiles(64))
+    d, side, _, _ = _run_and_compare(w, jobs=jobs, check_storage_tiles=2)
+    st = d.ctx.get_stats()
+    _say("  products by precision:", st["products"])
+    assert st["products"][0] == 0 and st["products"][3] > 0
