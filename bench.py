@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the tile-centric mixed-precision GEMM hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic problem whose dense FP64 inputs are
+already resident in HBM: tile scan + norm rule (where the workload's maps come from the rule),
+pack of A and B (and of C when beta != 0), schedule, and gemm_mp_run.  Unpacking is
+verification only and is not timed.
+
+Prints ONE JSON line.  `value` is the effective rate 2*M*N*K / t_step in TFLOP/s; `roofline`
+prices the dominant kernel (the owner-workgroup GEMM kernel) against the precision-weighted
+MFMA peak of this workload's product mix; `cpu_baseline` is the CPU oracle timed on a bounded
+sample of the same workload on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X published dense peaks, TFLOP/s, by product precision code (FP64, FP32, FP16, FP8).
+PEAK_TFLOPS = [78.6, 157.3, 2516.6, 5033.2]
+DTYPE_NAMES = ["f64", "f32", "f16", "f8e4m3"]
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cov16k",
+                    choices=["tiny", "random8k", "cov16k", "rect32k", "cov64k"])
+    ap.add_argument("--policy", type=int, default=0, choices=[0, 1])
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, A, B, C0, seconds):
+    """Time the oracle, as it stands, on a bounded sample of this workload's C tiles."""
+    import numpy as np
+    from oracle import gemm_mp_oracle as orc
+    from tests.harness import OracleSide
+
+    side = OracleSide(w, A, B, C0)
+    tiles = w.sample_tiles(64)
+    nb = w.nb
+    rows = min(nb, 64)
+    flops_per_row = 2.0 * nb * w.K
+
+    def run(jobs):
+        t0 = time.perf_counter()
+        side.gemm(np.array(jobs, dtype=np.int32))
+        return time.perf_counter() - t0
+
+    (I, J) = tiles[0]
+    t_probe = run([[I, J, 0, rows, 0, nb]])
+    rate = rows * flops_per_row / t_probe
+    want_rows = int(max(rows, min(len(tiles) * nb, seconds * rate / flops_per_row)))
+    jobs, left = [], want_rows
+    for (I, J) in tiles:
+        if left <= 0:
+            break
+        r = min(nb, left)
+        jobs.append([I, J, 0, r, 0, nb])
+        left -= r
+    t = run(jobs)
+    done_rows = sum(j[3] for j in jobs)
+    return {"value": done_rows * flops_per_row / t / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(),
+            "kind": "oracle", "seconds": round(t, 2),
+            "sample": "%d rows x %d cols of %d seeded C tiles of %s (all reduction tiles), %.3g flop"
+                      % (done_rows, nb, len(jobs), w.name, done_rows * flops_per_row)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build is a one-GPU path (no sharding, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import workloads as W
+    from paper_2508_14848_amd import gemm_mp as G
+    from paper_2508_14848_amd.device import DeviceGemmMP
+
+    G.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    w = W.CONFIGS[args.workload]()
+    t0 = time.perf_counter()
+    A = w.dense("A")
+    B = A if w.a_equals_b else w.dense("B")
+    C0 = w.dense("C") if w.beta != 0.0 else None
+    t_gen = time.perf_counter() - t0
+    dA = torch.from_numpy(A).to(dev)
+    dB = dA if w.a_equals_b else torch.from_numpy(B).to(dev)
+    dC = torch.from_numpy(C0).to(dev) if C0 is not None else None
+    torch.cuda.synchronize()
+
+    d = DeviceGemmMP(w.M, w.N, w.K, w.nb, device=dev, policy=args.policy)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    stage_ms = {"scan_rule": [], "pack": [], "run": []}
+
+    def step(record):
+        e = [ev() for _ in range(4)]
+        e[0].record()
+        if w.rule is not None:
+            d.compute_precision_map("A", dA, w.rule["eps"], w.rule["allowed"])
+            d.compute_precision_map("B", dB, w.rule["eps"], w.rule["allowed"])
+        else:
+            d.set_precision_map("A", w.mapA)
+            d.set_precision_map("B", w.mapB)
+        d.set_precision_map("C", w.mapC)
+        e[1].record()
+        d.pack_tiles("A", dA)
+        d.pack_tiles("B", dB)
+        if dC is not None:
+            d.pack_tiles("C", dC)
+        e[2].record()
+        d.run(w.alpha, w.beta)
+        e[3].record()
+        if record:
+            torch.cuda.synchronize()
+            for k, (a, b) in zip(("scan_rule", "pack", "run"), ((0, 1), (1, 2), (2, 3))):
+                stage_ms[k].append(e[a].elapsed_time(e[b]))
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+
+    st = d.ctx.get_stats()
+    flops_total = 2.0 * w.M * w.N * w.K
+    assert abs(sum(st["flops"]) - flops_total) < 1e-6 * flops_total
+    t_roof = sum(f / (p * 1e12) for f, p in zip(st["flops"], PEAK_TFLOPS))          # seconds
+    run_ms = float(np.mean(stage_ms["run"]))
+    achieved = flops_total / (run_ms * 1e-3) / 1e12
+    peak_mix = flops_total / t_roof / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(w.name + ("" if args.policy == 0 else "-ctile"), {}).get("bytes_per_launch")
+    used = [DTYPE_NAMES[q] for q in range(4) if st["products"][q]]
+    out = {
+        "metric": "effective TFLOP/s (2MNK/t) and % of precision-weighted MFMA peak, 1 GPU",
+        "value": flops_total / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "+".join(used), "data": "synthetic",
+        "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "tile_nb": w.nb,
+                   "alpha": w.alpha, "beta": w.beta, "policy": ["operand", "c_tile"][args.policy],
+                   "products_by_precision": dict(zip(DTYPE_NAMES, st["products"])),
+                   "work_items": st["work_items"], "host_generation_s": round(t_gen, 1)},
+        "stages_ms": {k: float(np.mean(v)) for k, v in stage_ms.items()},
+        "run_only": {"ms": run_ms, "min_ms": float(np.min(stage_ms["run"])), "effective_tflops": achieved,
+                     "roofline_ms": t_roof * 1e3, "frac_of_precision_weighted_peak": t_roof * 1e3 / run_ms},
+        "roofline": {"bound": "mfma", "kernel": "gemm_mp_owner_kernel", "achieved": achieved, "peak": peak_mix,
+                     "unit": "TFLOP/s", "frac": achieved / peak_mix, "traffic": traffic,
+                     "note": "peak = 2MNK / sum_q(F_q/P_q), P = 78.6/157.3/2516.6/5033.2 TFLOP/s for f64/f32/f16/f8; "
+                             "achieved = 2MNK / mean event time of gemm_mp_run on its stream"},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, A, B, C0, args.cpu_seconds)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

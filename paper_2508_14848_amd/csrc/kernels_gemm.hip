@@ -31,6 +31,8 @@ typedef double d4 __attribute__((ext_vector_type(4)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef int i8v __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vectors: these stay in registers
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kRowBytes = 128;                       // converted bytes per row and chunk
 constexpr int kRowStride = 144;                      // + 16 B pad against LDS bank conflicts
@@ -41,79 +43,98 @@ constexpr int kThreads = 256;
 
 enum { Q64 = GEMM_MP_FP64, Q32 = GEMM_MP_FP32, Q16 = GEMM_MP_FP16, Q8 = GEMM_MP_FP8_E4M3 };
 
-// Raw (still in stored precision) data of one 16-byte converted segment: at most 32 bytes.
-struct Raw { uint4 lo, hi; };
+// Raw (still in stored precision) data of one 16-byte converted segment.  Every segment is
+// fetched with the same instruction whatever the stored precision: the aligned 16 bytes that
+// contain its source (plus the next 16 for the one down-cast, FP64 -> FP32, whose source is
+// 32 bytes).  Loads therefore need no control flow and are all issued back to back; when the
+// source is narrower than 16 bytes, neighbouring lanes fetch the same 16 bytes and each picks
+// its part at conversion time (`sub` = byte offset of the source inside the 16 bytes).
+struct Raw { u32x4 lo, hi; };
 
-// Load the source of the segment that starts at element index `eidx` of the tile.
-// Q: product precision (fixes how many elements a 16-byte segment holds); p: stored precision.
-template <int Q>
-__device__ inline void load_raw(Raw &r, const char *tile, int p, int64_t eidx)
+typedef const __attribute__((address_space(1))) u32x4 *GlobalVec;
+
+// 16-byte load through the global (not the flat) address space.
+__device__ __forceinline__ u32x4 load16(const char *p)
 {
-    if (Q == Q64) {            // 2 elements
-        if (p == Q64) r.lo = *(const uint4 *)(tile + eidx * 8);
-        else if (p == Q32) { const uint2 v = *(const uint2 *)(tile + eidx * 4); r.lo.x = v.x; r.lo.y = v.y; }
-        else if (p == Q16) r.lo.x = *(const uint32_t *)(tile + eidx * 2);
-        else r.lo.x = *(const uint16_t *)(tile + eidx);
-    } else if (Q == Q32) {     // 4 elements
-        if (p == Q64) { r.lo = *(const uint4 *)(tile + eidx * 8); r.hi = *(const uint4 *)(tile + eidx * 8 + 16); }
-        else if (p == Q32) r.lo = *(const uint4 *)(tile + eidx * 4);
-        else if (p == Q16) { const uint2 v = *(const uint2 *)(tile + eidx * 2); r.lo.x = v.x; r.lo.y = v.y; }
-        else r.lo.x = *(const uint32_t *)(tile + eidx);
-    } else if (Q == Q16) {     // 8 elements
-        if (p == Q16) r.lo = *(const uint4 *)(tile + eidx * 2);
-        else { const uint2 v = *(const uint2 *)(tile + eidx); r.lo.x = v.x; r.lo.y = v.y; }
-    } else {                   // 16 elements, FP8 only
-        r.lo = *(const uint4 *)(tile + eidx);
-    }
+    return *(GlobalVec)(uintptr_t)p;
 }
 
-__device__ inline float half_lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w & 0xffffu)); }
-__device__ inline float half_hi(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w >> 16)); }
-__device__ inline uint32_t pack_half2(float a, float b)
+// Q: product precision (fixes how many elements a 16-byte converted segment holds);
+// p: stored precision; eidx: element index of the segment's first element in the tile.
+template <int Q>
+__device__ __forceinline__ void load_raw(Raw &r, const char *tile, int p, int64_t eidx)
+{
+    const int64_t off = eidx << (3 - p);
+    r.lo = load16(tile + (off & ~(int64_t)15));
+    if (Q == Q32 && p == Q64) r.hi = load16(tile + off + 16);
+}
+
+__device__ __forceinline__ float half_lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w & 0xffffu)); }
+__device__ __forceinline__ float half_hi(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w >> 16)); }
+__device__ __forceinline__ uint32_t pack_half2(float a, float b)
 {
     return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)a) |
            ((uint32_t)__builtin_bit_cast(unsigned short, (_Float16)b) << 16);
 }
-__device__ inline uint2 dbits(double d) { return __builtin_bit_cast(uint2, d); }
-
-// Receiver-side conversion of one segment to precision Q.  e: the tile's scale exponent.
-template <int Q>
-__device__ inline uint4 convert(const Raw &r, int p, int e)
+__device__ __forceinline__ u32x2 dbits(double d) { return __builtin_bit_cast(u32x2, d); }
+__device__ __forceinline__ double as_double(uint32_t lo, uint32_t hi) { return __builtin_bit_cast(double, u32x2{lo, hi}); }
+__device__ __forceinline__ uint32_t pick_word(const u32x4 v, int w)      // w = 0..3, per lane
 {
-    uint4 o = r.lo;
+    const uint32_t a = (w & 1) ? v.y : v.x, b = (w & 1) ? v.w : v.z;
+    return (w & 2) ? b : a;
+}
+__device__ __forceinline__ u32x2 pick_pair(const u32x4 v, int hi)         // low or high 8 bytes
+{
+    return u32x2{hi ? v.z : v.x, hi ? v.w : v.y};
+}
+
+// Receiver-side conversion of one segment to precision Q.  e: the tile's scale exponent;
+// sub: byte offset of the segment's source inside the 16 bytes that were loaded.
+template <int Q>
+__device__ __forceinline__ u32x4 convert(const Raw &r, int p, int e, int sub)
+{
+    u32x4 o = r.lo;
     if (Q == Q64) {
         if (p == Q64) return o;
         double a, b;
-        if (p == Q32) { a = (double)__uint_as_float(r.lo.x); b = (double)__uint_as_float(r.lo.y); }
-        else if (p == Q16) { a = ldexp((double)half_lo(r.lo.x), e); b = ldexp((double)half_hi(r.lo.x), e); }
-        else {
-            a = ldexp((double)__builtin_amdgcn_cvt_f32_fp8((int)r.lo.x, 0), e);
-            b = ldexp((double)__builtin_amdgcn_cvt_f32_fp8((int)r.lo.x, 1), e);
+        if (p == Q32) {
+            const u32x2 w = pick_pair(r.lo, sub >> 3);
+            a = (double)__uint_as_float(w.x); b = (double)__uint_as_float(w.y);
+        } else if (p == Q16) {
+            const uint32_t w = pick_word(r.lo, sub >> 2);
+            a = ldexp((double)half_lo(w), e); b = ldexp((double)half_hi(w), e);
+        } else {
+            const uint32_t w = pick_word(r.lo, sub >> 2) >> ((sub & 2) * 8);
+            a = ldexp((double)__builtin_amdgcn_cvt_f32_fp8((int)w, 0), e);
+            b = ldexp((double)__builtin_amdgcn_cvt_f32_fp8((int)w, 1), e);
         }
-        const uint2 ab = dbits(a), bb = dbits(b);
+        const u32x2 ab = dbits(a), bb = dbits(b);
         o.x = ab.x; o.y = ab.y; o.z = bb.x; o.w = bb.y;
     } else if (Q == Q32) {
         if (p == Q32) return o;
         float f0, f1, f2, f3;
         if (p == Q64) {        // the only down-cast: round to nearest even
-            f0 = (float)__builtin_bit_cast(double, make_uint2(r.lo.x, r.lo.y));
-            f1 = (float)__builtin_bit_cast(double, make_uint2(r.lo.z, r.lo.w));
-            f2 = (float)__builtin_bit_cast(double, make_uint2(r.hi.x, r.hi.y));
-            f3 = (float)__builtin_bit_cast(double, make_uint2(r.hi.z, r.hi.w));
+            f0 = (float)as_double(r.lo.x, r.lo.y);
+            f1 = (float)as_double(r.lo.z, r.lo.w);
+            f2 = (float)as_double(r.hi.x, r.hi.y);
+            f3 = (float)as_double(r.hi.z, r.hi.w);
         } else if (p == Q16) {
-            f0 = ldexpf(half_lo(r.lo.x), e); f1 = ldexpf(half_hi(r.lo.x), e);
-            f2 = ldexpf(half_lo(r.lo.y), e); f3 = ldexpf(half_hi(r.lo.y), e);
+            const u32x2 w = pick_pair(r.lo, sub >> 3);
+            f0 = ldexpf(half_lo(w.x), e); f1 = ldexpf(half_hi(w.x), e);
+            f2 = ldexpf(half_lo(w.y), e); f3 = ldexpf(half_hi(w.y), e);
         } else {
-            f0 = ldexpf(__builtin_amdgcn_cvt_f32_fp8((int)r.lo.x, 0), e);
-            f1 = ldexpf(__builtin_amdgcn_cvt_f32_fp8((int)r.lo.x, 1), e);
-            f2 = ldexpf(__builtin_amdgcn_cvt_f32_fp8((int)r.lo.x, 2), e);
-            f3 = ldexpf(__builtin_amdgcn_cvt_f32_fp8((int)r.lo.x, 3), e);
+            const int w = (int)pick_word(r.lo, sub >> 2);
+            f0 = ldexpf(__builtin_amdgcn_cvt_f32_fp8(w, 0), e);
+            f1 = ldexpf(__builtin_amdgcn_cvt_f32_fp8(w, 1), e);
+            f2 = ldexpf(__builtin_amdgcn_cvt_f32_fp8(w, 2), e);
+            f3 = ldexpf(__builtin_amdgcn_cvt_f32_fp8(w, 3), e);
         }
         o.x = __float_as_uint(f0); o.y = __float_as_uint(f1); o.z = __float_as_uint(f2); o.w = __float_as_uint(f3);
     } else if (Q == Q16) {
         if (p == Q16) return o;
         // FP8 -> FP16 is exact (every e4m3 number is a binary16 number); operands stay scaled
-        const int w0 = (int)r.lo.x, w1 = (int)r.lo.y;
+        const u32x2 w = pick_pair(r.lo, sub >> 3);
+        const int w0 = (int)w.x, w1 = (int)w.y;
         o.x = pack_half2(__builtin_amdgcn_cvt_f32_fp8(w0, 0), __builtin_amdgcn_cvt_f32_fp8(w0, 1));
         o.y = pack_half2(__builtin_amdgcn_cvt_f32_fp8(w0, 2), __builtin_amdgcn_cvt_f32_fp8(w0, 3));
         o.z = pack_half2(__builtin_amdgcn_cvt_f32_fp8(w1, 0), __builtin_amdgcn_cvt_f32_fp8(w1, 1));
@@ -136,10 +157,10 @@ struct Geometry {
     int seg_row, seg_part;          // staging: this thread's first row and its 16-byte part
 };
 
-__device__ inline int chunk_elems(int q) { return kRowBytes >> (3 - q); }   // 16, 32, 64, 128
+__device__ __forceinline__ int chunk_elems(int q) { return kRowBytes >> (3 - q); }   // 16, 32, 64, 128
 
 template <int Q>
-__device__ inline void issue_loads(Raw (&ra)[4], Raw (&rb)[4], const Chunk &c, const Geometry &G,
+__device__ __forceinline__ void issue_loads(Raw (&ra)[4], Raw (&rb)[4], const Chunk &c, const Geometry &G,
                                    int nb, int arow0, int brow0)
 {
     constexpr int n_q = 16 / (8 >> Q);   // elements per 16-byte converted segment
@@ -157,36 +178,40 @@ __device__ inline void issue_loads(Raw (&ra)[4], Raw (&rb)[4], const Chunk &c, c
 }
 
 template <int Q>
-__device__ inline void convert_store(const Raw (&ra)[4], const Raw (&rb)[4], const Chunk &c,
+__device__ __forceinline__ void convert_store(const Raw (&ra)[4], const Raw (&rb)[4], const Chunk &c,
                                      const Geometry &G, char *stage)
 {
+    constexpr int n_q = 16 / (8 >> Q);
     int seg_row = G.seg_row, seg_part = G.seg_part;
     asm volatile("" : "+v"(seg_row), "+v"(seg_part));
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int row = seg_row + 32 * j;
-        *(uint4 *)(stage + row * kRowStride + seg_part * 16) = convert<Q>(ra[j], c.pA, c.eA);
-        *(uint4 *)(stage + kOperandStage + row * kRowStride + seg_part * 16) = convert<Q>(rb[j], c.pB, c.eB);
+        // source offset inside the loaded 16 bytes: (seg_part * n_q elements * size_p) mod 16;
+        // rows and chunk starts are multiples of 16 bytes in every precision
+        const int subA = ((seg_part * n_q) << (3 - c.pA)) & 15, subB = ((seg_part * n_q) << (3 - c.pB)) & 15;
+        *(u32x4 *)(stage + row * kRowStride + seg_part * 16) = convert<Q>(ra[j], c.pA, c.eA, subA);
+        *(u32x4 *)(stage + kOperandStage + row * kRowStride + seg_part * 16) = convert<Q>(rb[j], c.pB, c.eB, subB);
     }
 }
 
 // 32 bytes of one fragment row.
-struct Frag { uint4 lo, hi; };
-__device__ inline Frag read_frag(const char *operand, int row, int g)
+struct Frag { u32x4 lo, hi; };
+__device__ __forceinline__ Frag read_frag(const char *operand, int row, int g)
 {
     const char *p = operand + row * kRowStride + g * 32;
     Frag f;
-    f.lo = *(const uint4 *)p;
-    f.hi = *(const uint4 *)(p + 16);
+    f.lo = *(const u32x4 *)p;
+    f.hi = *(const u32x4 *)(p + 16);
     return f;
 }
-__device__ inline uint32_t frag_word(const Frag &f, int w)
+__device__ __forceinline__ uint32_t frag_word(const Frag &f, int w)
 {
-    const uint4 &v = w < 4 ? f.lo : f.hi;
-    switch (w & 3) { case 0: return v.x; case 1: return v.y; case 2: return v.z; default: return v.w; }
+    const u32x4 v = w < 4 ? f.lo : f.hi;
+    return v[w & 3];
 }
 
-__device__ inline void mma_fp64(d4 (&acc)[4][4], const char *stage, const Geometry &G)
+__device__ __forceinline__ void mma_fp64(d4 (&acc)[4][4], const char *stage, const Geometry &G)
 {
     Frag a[4], b[4];
     const int arow = 4 * (G.li & 3) + (G.li >> 2);      // see the fragment convention above
@@ -200,8 +225,8 @@ __device__ inline void mma_fp64(d4 (&acc)[4][4], const char *stage, const Geomet
         double av[4], bv[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            av[t] = __builtin_bit_cast(double, make_uint2(frag_word(a[t], 2 * kk), frag_word(a[t], 2 * kk + 1)));
-            bv[t] = __builtin_bit_cast(double, make_uint2(frag_word(b[t], 2 * kk), frag_word(b[t], 2 * kk + 1)));
+            av[t] = as_double(frag_word(a[t], 2 * kk), frag_word(a[t], 2 * kk + 1));
+            bv[t] = as_double(frag_word(b[t], 2 * kk), frag_word(b[t], 2 * kk + 1));
         }
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt)
@@ -211,7 +236,7 @@ __device__ inline void mma_fp64(d4 (&acc)[4][4], const char *stage, const Geomet
     }
 }
 
-__device__ inline void mma_fp32(f4 (&acc)[4][4], const char *stage, const Geometry &G)
+__device__ __forceinline__ void mma_fp32(f4 (&acc)[4][4], const char *stage, const Geometry &G)
 {
     Frag a[4], b[4];
 #pragma unroll
@@ -231,7 +256,7 @@ __device__ inline void mma_fp32(f4 (&acc)[4][4], const char *stage, const Geomet
     }
 }
 
-__device__ inline void mma_fp16(f4 (&acc)[4][4], const char *stage, const Geometry &G)
+__device__ __forceinline__ void mma_fp16(f4 (&acc)[4][4], const char *stage, const Geometry &G)
 {
     Frag a[4], b[4];
 #pragma unroll
@@ -252,7 +277,7 @@ __device__ inline void mma_fp16(f4 (&acc)[4][4], const char *stage, const Geomet
     }
 }
 
-__device__ inline void mma_fp8(f4 (&acc)[4][4], const char *stage, const Geometry &G)
+__device__ __forceinline__ void mma_fp8(f4 (&acc)[4][4], const char *stage, const Geometry &G)
 {
     Frag a[4], b[4];
 #pragma unroll
@@ -275,8 +300,8 @@ __device__ inline void mma_fp8(f4 (&acc)[4][4], const char *stage, const Geometr
 
 // Everything that describes a chunk is the same for all lanes of the workgroup; passing it
 // through readfirstlane keeps it in scalar registers and makes every branch on it a scalar one.
-__device__ inline int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
-__device__ inline const char *uni(const char *p)
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ const char *uni(const char *p)
 {
     const uint64_t v = (uint64_t)p;
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
@@ -285,7 +310,7 @@ __device__ inline const char *uni(const char *p)
 }
 
 // Load the descriptors of tile product L of this C tile (q = -1 past the end).
-__device__ inline Chunk open_product(const GemmArgs &P, int I, int J, int tileC, int L)
+__device__ __forceinline__ Chunk open_product(const GemmArgs &P, int I, int J, int tileC, int L)
 {
     Chunk c;
     c.koff = 0;
@@ -310,7 +335,7 @@ struct Region {
 
 // Loads / conversion of a chunk whose precision is only known at run time (the first chunk of
 // the next tile product).
-__device__ inline void issue_loads_any(Raw (&ra)[4], Raw (&rb)[4], const Chunk &c, const Geometry &G, const Region &R)
+__device__ __forceinline__ void issue_loads_any(Raw (&ra)[4], Raw (&rb)[4], const Chunk &c, const Geometry &G, const Region &R)
 {
     switch (c.q) {
     case Q64: issue_loads<Q64>(ra, rb, c, G, R.nb, R.arow0, R.brow0); break;
@@ -320,7 +345,7 @@ __device__ inline void issue_loads_any(Raw (&ra)[4], Raw (&rb)[4], const Chunk &
     default: break;
     }
 }
-__device__ inline void convert_store_any(const Raw (&ra)[4], const Raw (&rb)[4], const Chunk &c, const Geometry &G, char *stage)
+__device__ __forceinline__ void convert_store_any(const Raw (&ra)[4], const Raw (&rb)[4], const Chunk &c, const Geometry &G, char *stage)
 {
     switch (c.q) {
     case Q64: convert_store<Q64>(ra, rb, c, G, stage); break;
@@ -332,7 +357,7 @@ __device__ inline void convert_store_any(const Raw (&ra)[4], const Raw (&rb)[4],
 }
 
 template <int Q, typename Acc>
-__device__ inline void mma(Acc (&acc)[4][4], const char *stage, const Geometry &G)
+__device__ __forceinline__ void mma(Acc (&acc)[4][4], const char *stage, const Geometry &G)
 {
     if constexpr (Q == Q64) mma_fp64(acc, stage, G);
     else if constexpr (Q == Q32) mma_fp32(acc, stage, G);
@@ -344,7 +369,7 @@ __device__ inline void mma(Acc (&acc)[4][4], const char *stage, const Geometry &
 // product's first chunk; on exit it holds the first chunk of the next product (if any).
 // While the MFMAs of a chunk run, the loads of the following chunk are in flight.
 template <int Q, typename Acc>
-__device__ inline void product_loop(Acc (&acc)[4][4], Chunk cur, const Chunk &next, char *lds, int &stage,
+__device__ __forceinline__ void product_loop(Acc (&acc)[4][4], Chunk cur, const Chunk &next, char *lds, int &stage,
                                     const Geometry &G, const Region &R)
 {
     Raw ra[4], rb[4];
@@ -366,7 +391,7 @@ __device__ inline void product_loop(Acc (&acc)[4][4], Chunk cur, const Chunk &ne
 
 // The finished tile product joins the running sum once: s += 2^esum * t, then t = 0.
 template <typename AccS>
-__device__ inline void fold(AccS (&s)[4][4], f4 (&t)[4][4], int esum)
+__device__ __forceinline__ void fold(AccS (&s)[4][4], f4 (&t)[4][4], int esum)
 {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
