@@ -35,10 +35,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vectors:
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kRowBytes = 128;                       // converted bytes per row and chunk
-constexpr int kRowStride = 144;                      // + 16 B pad against LDS bank conflicts
-constexpr int kOperandStage = kMacro * kRowStride;   // 18432 B
+constexpr int kRowStride = 136;                      // + 8 B pad: 17 eight-byte words per row, so the
+                                                     // 16 rows x 4 k-groups of a fragment read and the
+                                                     // 8 rows x 8 parts of a staging write each spread
+                                                     // evenly over the LDS banks
+constexpr int kOperandStage = kMacro * kRowStride;   // 17408 B
 constexpr int kStage = 2 * kOperandStage;            // A then B
-constexpr int kLdsBytes = 2 * kStage;                // two stages: 73728 B
+constexpr int kLdsBytes = 2 * kStage;                // two stages: 69632 B
 constexpr int kThreads = 256;
 
 enum { Q64 = GEMM_MP_FP64, Q32 = GEMM_MP_FP32, Q16 = GEMM_MP_FP16, Q8 = GEMM_MP_FP8_E4M3 };
@@ -46,27 +49,41 @@ enum { Q64 = GEMM_MP_FP64, Q32 = GEMM_MP_FP32, Q16 = GEMM_MP_FP16, Q8 = GEMM_MP_
 // Raw (still in stored precision) data of one 16-byte converted segment.  Every segment is
 // fetched with the same instruction whatever the stored precision: the aligned 16 bytes that
 // contain its source (plus the next 16 for the one down-cast, FP64 -> FP32, whose source is
-// 32 bytes).  Loads therefore need no control flow and are all issued back to back; when the
-// source is narrower than 16 bytes, neighbouring lanes fetch the same 16 bytes and each picks
-// its part at conversion time (`sub` = byte offset of the source inside the 16 bytes).
+// 32 bytes).  Loads therefore need no control flow and no per-chunk address arithmetic in the
+// vector ALU: they are buffer loads whose descriptor is the packed tile, whose vector offset
+// is a per-thread constant of the tile product, and whose scalar offset carries the chunk and
+// the row block.  When the source is narrower than 16 bytes, neighbouring lanes fetch the same
+// 16 bytes and each picks its part at conversion time (`sub` = byte offset of its source
+// inside them).  This matters on gfx950: FP64 and FP32 MFMAs do not overlap with other vector
+// ALU instructions, so every one of those in the inner loop costs matrix throughput.
 struct Raw { u32x4 lo, hi; };
 
-typedef const __attribute__((address_space(1))) u32x4 *GlobalVec;
+// One operand tile of a tile product.  Everything is wave-uniform except voff and sub.
+struct Operand {
+    const char *base;              // the packed tile and its size: the buffer descriptor is
+    int bytes;                     // formed from them at each load (scalar moves only)
+    int p, e;                      // stored precision, scale exponent
+    int voff;                      // this thread's first segment in chunk 0, aligned down to 16 B
+    int sub;                       // offset of that segment's source inside the 16 loaded bytes
+};
 
-// 16-byte load through the global (not the flat) address space.
-__device__ __forceinline__ u32x4 load16(const char *p)
-{
-    return *(GlobalVec)(uintptr_t)p;
-}
+// One tile product A(I,L)*B(L,J): q is its precision (-1: there is none).
+struct Product {
+    Operand a, b;
+    int q;
+};
 
-// Q: product precision (fixes how many elements a 16-byte converted segment holds);
-// p: stored precision; eidx: element index of the segment's first element in the tile.
-template <int Q>
-__device__ __forceinline__ void load_raw(Raw &r, const char *tile, int p, int64_t eidx)
+// soff: byte offset of (chunk, row block) in the tile; down: FP64 tile feeding an FP32 product.
+__device__ __forceinline__ void load_seg(Raw &r, const Operand &o, int soff, bool down)
 {
-    const int64_t off = eidx << (3 - p);
-    r.lo = load16(tile + (off & ~(int64_t)15));
-    if (Q == Q32 && p == Q64) r.hi = load16(tile + off + 16);
+#ifdef GMP_EXP_NOLOAD   /* timing experiment only: no global traffic, operands are garbage */
+    r.lo = u32x4{(uint32_t)(o.voff + soff), 1u, 2u, 3u};
+    r.hi = r.lo;
+#else
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)o.base, 0, o.bytes, 0x00020000);
+    r.lo = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o.voff, soff, 0);
+    if (down) r.hi = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o.voff + 16, soff, 0);
+#endif
 }
 
 __device__ __forceinline__ float half_lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w & 0xffffu)); }
@@ -143,163 +160,63 @@ __device__ __forceinline__ u32x4 convert(const Raw &r, int p, int e, int sub)
     return o;
 }
 
-// One tile product A(I,L)*B(L,J) as the loader and the MFMA loop see it; koff is the first
-// reduction index (in elements) of the chunk being loaded.
-struct Chunk {
-    const char *a, *b;     // tile bases
-    int64_t koff;
-    int pA, pB, q;
-    int eA, eB;
-};
-
 struct Geometry {
     int tid, lane, li, g, wm, wn;
     int seg_row, seg_part;          // staging: this thread's first row and its 16-byte part
+    int wbase;                      // byte offset of that segment in an LDS operand stage
+};
+
+struct Region {
+    int nb, arow0, brow0;
 };
 
 __device__ __forceinline__ int chunk_elems(int q) { return kRowBytes >> (3 - q); }   // 16, 32, 64, 128
 
-template <int Q>
-__device__ __forceinline__ void issue_loads(Raw (&ra)[4], Raw (&rb)[4], const Chunk &c, const Geometry &G,
-                                   int nb, int arow0, int brow0)
+// Nothing may be moved across this point by the instruction scheduler.
+#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// Staging of one chunk: each thread owns four 16-byte converted segments per operand
+// (rows seg_row + 32 j, bytes [16 part, 16 part + 16) of the row).  c: chunk index in the product.
+__device__ __forceinline__ void load_pair(Raw &ra, Raw &rb, const Product &pr, int nb, int c, int j)
 {
-    constexpr int n_q = 16 / (8 >> Q);   // elements per 16-byte converted segment
-    // The offsets below are cheap to form and would otherwise be hoisted, for every precision
-    // pair, out of the whole reduction loop and kept in registers; the empty asm pins their
-    // computation here.
-    int seg_row = G.seg_row, seg_part = G.seg_part;
-    asm volatile("" : "+v"(seg_row), "+v"(seg_part));
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int row = seg_row + 32 * j;
-        load_raw<Q>(ra[j], c.a, c.pA, (int64_t)(arow0 + row) * nb + c.koff + seg_part * n_q);
-        load_raw<Q>(rb[j], c.b, c.pB, (int64_t)(brow0 + row) * nb + c.koff + seg_part * n_q);
-    }
+    // element offset of (chunk c, row block j) in a tile, then bytes in each operand's precision
+    const int eoff = c * chunk_elems(pr.q) + j * 32 * nb;
+    load_seg(ra, pr.a, eoff << (3 - pr.a.p), pr.q == Q32 && pr.a.p == Q64);
+    load_seg(rb, pr.b, eoff << (3 - pr.b.p), pr.q == Q32 && pr.b.p == Q64);
+}
+
+__device__ __forceinline__ void lds_store16(char *p, u32x4 v)     // rows are only 8-byte aligned
+{
+#ifdef GMP_EXP_NOLDSWRITE   /* timing experiment only */
+    if (v.x == 0x12345u) *(u32x2 *)p = u32x2{v.x, v.y};
+    return;
+#endif
+    *(u32x2 *)p = u32x2{v.x, v.y};
+    *(u32x2 *)(p + 8) = u32x2{v.z, v.w};
 }
 
 template <int Q>
-__device__ __forceinline__ void convert_store(const Raw (&ra)[4], const Raw (&rb)[4], const Chunk &c,
-                                     const Geometry &G, char *stage)
+__device__ __forceinline__ void store_pair(const Raw &ra, const Raw &rb, const Product &pr, const Geometry &G, char *stage, int j)
 {
-    constexpr int n_q = 16 / (8 >> Q);
-    int seg_row = G.seg_row, seg_part = G.seg_part;
-    asm volatile("" : "+v"(seg_row), "+v"(seg_part));
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int row = seg_row + 32 * j;
-        // source offset inside the loaded 16 bytes: (seg_part * n_q elements * size_p) mod 16;
-        // rows and chunk starts are multiples of 16 bytes in every precision
-        const int subA = ((seg_part * n_q) << (3 - c.pA)) & 15, subB = ((seg_part * n_q) << (3 - c.pB)) & 15;
-        *(u32x4 *)(stage + row * kRowStride + seg_part * 16) = convert<Q>(ra[j], c.pA, c.eA, subA);
-        *(u32x4 *)(stage + kOperandStage + row * kRowStride + seg_part * 16) = convert<Q>(rb[j], c.pB, c.eB, subB);
+    char *dst = stage + G.wbase + j * (32 * kRowStride);
+    lds_store16(dst, convert<Q>(ra, pr.a.p, pr.a.e, pr.a.sub));
+    lds_store16(dst + kOperandStage, convert<Q>(rb, pr.b.p, pr.b.e, pr.b.sub));
+}
+
+// The same for a product whose precision is only known at run time (the next tile product).
+__device__ __forceinline__ void store_pair_any(const Raw &ra, const Raw &rb, const Product &pr, const Geometry &G, char *stage, int j)
+{
+    switch (pr.q) {
+    case Q64: store_pair<Q64>(ra, rb, pr, G, stage, j); break;
+    case Q32: store_pair<Q32>(ra, rb, pr, G, stage, j); break;
+    case Q16: store_pair<Q16>(ra, rb, pr, G, stage, j); break;
+    case Q8:  store_pair<Q8>(ra, rb, pr, G, stage, j);  break;
+    default: break;
     }
 }
 
-// 32 bytes of one fragment row.
-struct Frag { u32x4 lo, hi; };
-__device__ __forceinline__ Frag read_frag(const char *operand, int row, int g)
-{
-    const char *p = operand + row * kRowStride + g * 32;
-    Frag f;
-    f.lo = *(const u32x4 *)p;
-    f.hi = *(const u32x4 *)(p + 16);
-    return f;
-}
-__device__ __forceinline__ uint32_t frag_word(const Frag &f, int w)
-{
-    const u32x4 v = w < 4 ? f.lo : f.hi;
-    return v[w & 3];
-}
-
-__device__ __forceinline__ void mma_fp64(d4 (&acc)[4][4], const char *stage, const Geometry &G)
-{
-    Frag a[4], b[4];
-    const int arow = 4 * (G.li & 3) + (G.li >> 2);      // see the fragment convention above
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        a[t] = read_frag(stage, G.wm * 64 + t * 16 + arow, G.g);
-        b[t] = read_frag(stage + kOperandStage, G.wn * 64 + t * 16 + G.li, G.g);
-    }
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        double av[4], bv[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            av[t] = as_double(frag_word(a[t], 2 * kk), frag_word(a[t], 2 * kk + 1));
-            bv[t] = as_double(frag_word(b[t], 2 * kk), frag_word(b[t], 2 * kk + 1));
-        }
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[mt], bv[nt], acc[mt][nt], 0, 0, 0);
-    }
-}
-
-__device__ __forceinline__ void mma_fp32(f4 (&acc)[4][4], const char *stage, const Geometry &G)
-{
-    Frag a[4], b[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        a[t] = read_frag(stage, G.wm * 64 + t * 16 + G.li, G.g);
-        b[t] = read_frag(stage + kOperandStage, G.wn * 64 + t * 16 + G.li, G.g);
-    }
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(frag_word(a[mt], kk)),
-                                                                   __uint_as_float(frag_word(b[nt], kk)),
-                                                                   acc[mt][nt], 0, 0, 0);
-    }
-}
-
-__device__ __forceinline__ void mma_fp16(f4 (&acc)[4][4], const char *stage, const Geometry &G)
-{
-    Frag a[4], b[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        a[t] = read_frag(stage, G.wm * 64 + t * 16 + G.li, G.g);
-        b[t] = read_frag(stage + kOperandStage, G.wn * 64 + t * 16 + G.li, G.g);
-    }
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
-                const h8 x = __builtin_bit_cast(h8, kk ? a[mt].hi : a[mt].lo);
-                const h8 y = __builtin_bit_cast(h8, kk ? b[nt].hi : b[nt].lo);
-                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x, y, acc[mt][nt], 0, 0, 0);
-            }
-    }
-}
-
-__device__ __forceinline__ void mma_fp8(f4 (&acc)[4][4], const char *stage, const Geometry &G)
-{
-    Frag a[4], b[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        a[t] = read_frag(stage, G.wm * 64 + t * 16 + G.li, G.g);
-        b[t] = read_frag(stage + kOperandStage, G.wn * 64 + t * 16 + G.li, G.g);
-    }
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-            const i8v x = {(int)a[mt].lo.x, (int)a[mt].lo.y, (int)a[mt].lo.z, (int)a[mt].lo.w,
-                           (int)a[mt].hi.x, (int)a[mt].hi.y, (int)a[mt].hi.z, (int)a[mt].hi.w};
-            const i8v y = {(int)b[nt].lo.x, (int)b[nt].lo.y, (int)b[nt].lo.z, (int)b[nt].lo.w,
-                           (int)b[nt].hi.x, (int)b[nt].hi.y, (int)b[nt].hi.z, (int)b[nt].hi.w};
-            // 16x16x128, both operands e4m3, block scales 2^0 (E8M0 code 127)
-            acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(x, y, acc[mt][nt], 0, 0, 0, 127, 0, 127);
-        }
-}
-
-// Everything that describes a chunk is the same for all lanes of the workgroup; passing it
-// through readfirstlane keeps it in scalar registers and makes every branch on it a scalar one.
+// Everything that describes a tile product is the same for all lanes of the workgroup; passing
+// it through readfirstlane keeps it in scalar registers and makes every branch on it scalar.
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ const char *uni(const char *p)
 {
@@ -309,84 +226,255 @@ __device__ __forceinline__ const char *uni(const char *p)
     return (const char *)(((uint64_t)hi << 32) | lo);
 }
 
-// Load the descriptors of tile product L of this C tile (q = -1 past the end).
-__device__ __forceinline__ Chunk open_product(const GemmArgs &P, int I, int J, int tileC, int L)
+// Descriptor of one operand tile: `row0` is the first tile row this workgroup reads.
+__device__ __forceinline__ Operand open_operand(const PackedView &V, int tile, int q, int row0, const Geometry &G, int nb)
 {
-    Chunk c;
-    c.koff = 0;
-    c.a = c.b = nullptr;
-    c.pA = c.pB = c.eA = c.eB = 0;
-    c.q = -1;
-    if (L >= P.kt_eff) return c;
-    const int ta = I * P.KT + L, tb = L * P.NT + J;
-    c.a = uni(P.A.storage + P.A.offset[ta]);
-    c.b = uni(P.B.storage + P.B.offset[tb]);
-    c.pA = uni(P.A.prec[ta]);
-    c.pB = uni(P.B.prec[tb]);
-    c.eA = uni(P.A.exp[ta]);
-    c.eB = uni(P.B.exp[tb]);
-    c.q = uni(P.q[(int64_t)tileC * P.KT + L]);
-    return c;
+    Operand o;
+    o.base = uni(V.storage + V.offset[tile]);
+    o.p = uni(V.prec[tile]);
+    o.e = uni(V.exp[tile]);
+    const int shift = 3 - o.p;                                   // log2 of the element size
+    o.bytes = (nb * nb) << shift;
+    const int n_q = 2 << q;                                      // elements per 16-byte converted segment
+    const int boff = ((row0 + G.seg_row) * nb + G.seg_part * n_q) << shift;
+    o.voff = boff & ~15;
+    o.sub = boff & 15;
+    return o;
 }
 
-struct Region {
-    int nb, arow0, brow0;
+// Load the descriptors of tile product L of this C tile (q = -1 past the end).
+__device__ __forceinline__ Product open_product(const GemmArgs &P, int I, int J, int tileC, int L, const Geometry &G, const Region &R)
+{
+    Product pr;
+    pr.q = -1;
+    if (L >= P.kt_eff) {
+        pr.a = Operand{};
+        pr.b = Operand{};
+        return pr;
+    }
+    pr.q = uni(P.q[(int64_t)tileC * P.KT + L]);
+    pr.a = open_operand(P.A, I * P.KT + L, pr.q, R.arow0, G, R.nb);
+    pr.b = open_operand(P.B, L * P.NT + J, pr.q, R.brow0, G, R.nb);
+    return pr;
+}
+
+// What a product loop needs in order to open the following tile product itself; it does so only
+// when it reaches its last chunk, which keeps the scalar registers of one product, not two,
+// live through the chunk loop.
+struct Walk {
+    const GemmArgs *P;
+    int I, J, tileC;
 };
 
-// Loads / conversion of a chunk whose precision is only known at run time (the first chunk of
-// the next tile product).
-__device__ __forceinline__ void issue_loads_any(Raw (&ra)[4], Raw (&rb)[4], const Chunk &c, const Geometry &G, const Region &R)
+// Per-lane LDS offsets of the fragment rows (stage 0): A rows of this wave's 64 x 64 part and B
+// rows; row block t adds t * 16 * kRowStride, macro-step m adds 8 m (or 16 m / 32 m).
+struct FragBase {
+    const char *a, *b;
+};
+template <int Q>
+__device__ __forceinline__ FragBase frag_base(const char *lds, const Geometry &G)
 {
-    switch (c.q) {
-    case Q64: issue_loads<Q64>(ra, rb, c, G, R.nb, R.arow0, R.brow0); break;
-    case Q32: issue_loads<Q32>(ra, rb, c, G, R.nb, R.arow0, R.brow0); break;
-    case Q16: issue_loads<Q16>(ra, rb, c, G, R.nb, R.arow0, R.brow0); break;
-    case Q8:  issue_loads<Q8>(ra, rb, c, G, R.nb, R.arow0, R.brow0);  break;
-    default: break;
-    }
+    // FP64 accumulators hold C[4v+g][i] where the FP32-result ones hold C[4g+v][i]; reading A row
+    // 4*(i%4) + i/4 in lane i on the FP64 path makes both address the same C element.
+    const int arow = (Q == Q64) ? 4 * (G.li & 3) + (G.li >> 2) : G.li;
+    FragBase f;
+    f.a = lds + (G.wm * 64 + arow) * kRowStride + G.g * 32;
+    f.b = lds + kOperandStage + (G.wn * 64 + G.li) * kRowStride + G.g * 32;
+    return f;
 }
-__device__ __forceinline__ void convert_store_any(const Raw (&ra)[4], const Raw (&rb)[4], const Chunk &c, const Geometry &G, char *stage)
+#ifdef GMP_EXP_NOLDSREAD   /* timing experiment only */
+__device__ __forceinline__ u32x2 lds_load8(const char *p) { return u32x2{(uint32_t)(uintptr_t)p, 7u}; }
+#else
+__device__ __forceinline__ u32x2 lds_load8(const char *p) { return *(const u32x2 *)p; }
+#endif
+
+// ---- FP64 / FP32 products: software-pipelined chunk loop -----------------------------------
+// A chunk is consumed in four macro-steps of 8 bytes of reduction index per lane: one FP64
+// k-step (16 MFMAs of 64 cycles) or two FP32 k-steps (32 MFMAs of 32 cycles), i.e. about 1024
+// matrix-core cycles each.  A macro-step is issued as four groups (one per 16-row block of A);
+// after each group comes a slot of other work, so that everything else hides under the MFMAs:
+//   macro-step 0      : global loads of the next chunk, 2 per slot
+//   macro-steps 0..2  : LDS reads of the next macro-step's fragments, 2 per slot
+//   macro-step 2      : conversion + LDS writes of the next chunk into the other stage
+//   macro-step 3      : barrier in slot 0, then LDS reads of the next chunk's first fragments
+// fr[buf][0..3] = A fragments of row blocks 0..3, fr[buf][4..7] = B fragments.
+template <int Q, typename Acc>
+__device__ __forceinline__ void mfma_group(Acc (&acc)[4][4], const u32x2 (&fr)[8], int mt)
 {
-    switch (c.q) {
-    case Q64: convert_store<Q64>(ra, rb, c, G, stage); break;
-    case Q32: convert_store<Q32>(ra, rb, c, G, stage); break;
-    case Q16: convert_store<Q16>(ra, rb, c, G, stage); break;
-    case Q8:  convert_store<Q8>(ra, rb, c, G, stage);  break;
-    default: break;
+    if constexpr (Q == Q64) {
+        const double a = as_double(fr[mt].x, fr[mt].y);
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+            acc[mt][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, as_double(fr[4 + nt].x, fr[4 + nt].y), acc[mt][nt], 0, 0, 0);
+    } else {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(fr[mt][sub]), __uint_as_float(fr[4 + nt][sub]),
+                                                                   acc[mt][nt], 0, 0, 0);
     }
 }
 
-template <int Q, typename Acc>
-__device__ __forceinline__ void mma(Acc (&acc)[4][4], const char *stage, const Geometry &G)
+// Order in which the eight fragments of a macro-step are fetched, two per slot: the B fragments
+// first, so that A block 0 (needed first) is never the last to arrive.
+__device__ __forceinline__ void read_frag_slot(u32x2 (&fr)[8], const char *fa, const char *fb, int m, int slot)
 {
-    if constexpr (Q == Q64) mma_fp64(acc, stage, G);
-    else if constexpr (Q == Q32) mma_fp32(acc, stage, G);
-    else if constexpr (Q == Q16) mma_fp16(acc, stage, G);
-    else mma_fp8(acc, stage, G);
+    constexpr int kBlock = 16 * kRowStride;
+    if (slot < 2) {
+        fr[4 + 2 * slot] = lds_load8(fb + (2 * slot) * kBlock + 8 * m);
+        fr[5 + 2 * slot] = lds_load8(fb + (2 * slot + 1) * kBlock + 8 * m);
+    } else {
+        fr[2 * slot - 4] = lds_load8(fa + (2 * slot - 4) * kBlock + 8 * m);
+        fr[2 * slot - 3] = lds_load8(fa + (2 * slot - 3) * kBlock + 8 * m);
+    }
 }
 
-// All chunks of one tile product at precision Q.  On entry LDS stage `stage` holds the
-// product's first chunk; on exit it holds the first chunk of the next product (if any).
-// While the MFMAs of a chunk run, the loads of the following chunk are in flight.
+// pr / c: product and chunk index of the chunk to stage (the next chunk of this product, or
+// chunk 0 of the next product when LAST).
+template <int Q, bool LAST, typename Acc>
+__device__ __forceinline__ void pipelined_chunk(Acc (&acc)[4][4], u32x2 (&fr)[2][8], const Product &pr, int c, char *lds, int stage,
+                                                const FragBase &F, const Geometry &G, int nb)
+{
+    Raw ra[4], rb[4];
+    const char *fa = F.a + stage * kStage, *fb = F.b + stage * kStage;
+    const char *na = F.a + (stage ^ 1) * kStage, *nbp = F.b + (stage ^ 1) * kStage;
+    char *wst = lds + (stage ^ 1) * kStage;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+#pragma unroll
+        for (int grp = 0; grp < 4; ++grp) {
+            mfma_group<Q>(acc, fr[m & 1], grp);
+            SCHED_FENCE();
+            if (m == 0) {
+                if (!LAST || pr.q >= 0) load_pair(ra[grp], rb[grp], pr, nb, c, grp);
+            }
+            if (m < 3) read_frag_slot(fr[(m + 1) & 1], fa, fb, m + 1, grp);
+            if (m == 2) {
+                if constexpr (LAST) store_pair_any(ra[grp], rb[grp], pr, G, wst, grp);
+                else store_pair<Q>(ra[grp], rb[grp], pr, G, wst, grp);
+            }
+            if (m == 3) {
+#ifndef GMP_EXP_NOBARRIER
+                if (grp == 0) __syncthreads();
+#endif
+                if constexpr (!LAST) {
+                    // first fragments of the next chunk: B0 B1 B2 | B3 A0 A1 | A2 A3
+                    constexpr int kBlock = 16 * kRowStride;
+                    if (grp == 1) {
+                        fr[0][4] = lds_load8(nbp); fr[0][5] = lds_load8(nbp + kBlock); fr[0][6] = lds_load8(nbp + 2 * kBlock);
+                    } else if (grp == 2) {
+                        fr[0][7] = lds_load8(nbp + 3 * kBlock); fr[0][0] = lds_load8(na); fr[0][1] = lds_load8(na + kBlock);
+                    } else if (grp == 3) {
+                        fr[0][2] = lds_load8(na + 2 * kBlock); fr[0][3] = lds_load8(na + 3 * kBlock);
+                    }
+                }
+            }
+            SCHED_FENCE();
+        }
+    }
+}
+
+// All chunks of one FP64 / FP32 tile product.  On entry LDS stage `stage` holds the product's
+// first chunk; on exit it holds the first chunk of the next product (if any).
 template <int Q, typename Acc>
-__device__ __forceinline__ void product_loop(Acc (&acc)[4][4], Chunk cur, const Chunk &next, char *lds, int &stage,
-                                    const Geometry &G, const Region &R)
+__device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
+                                                          const Geometry &G, const Region &R)
+{
+    const FragBase F = frag_base<Q>(lds, G);
+    u32x2 fr[2][8];
+#pragma unroll
+    for (int slot = 0; slot < 4; ++slot) read_frag_slot(fr[0], F.a + stage * kStage, F.b + stage * kStage, 0, slot);
+    const int n = R.nb / (kRowBytes >> (3 - Q));
+    for (int c = 1; c < n; ++c) {
+        pipelined_chunk<Q, false>(acc, fr, cur, c, lds, stage, F, G, R.nb);
+        stage ^= 1;
+    }
+    const Product next = open_product(*W.P, W.I, W.J, W.tileC, Lnext, G, R);
+    pipelined_chunk<Q, true>(acc, fr, next, 0, lds, stage, F, G, R.nb);
+    stage ^= 1;
+    return next;
+}
+
+// ---- FP16 / FP8 products: one chunk = 2 k-steps of 16x16x32 FP16, or one 16x16x128 FP8 step ----
+__device__ __forceinline__ void mma_fp16(f4 (&acc)[4][4], const char *lds, int stage, const Geometry &G)
+{
+    const FragBase F = frag_base<Q16>(lds + stage * kStage, G);
+    constexpr int kBlock = 16 * kRowStride;
+    u32x2 a[4][4], b[4][4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            a[t][w] = lds_load8(F.a + t * kBlock + 8 * w);
+            b[t][w] = lds_load8(F.b + t * kBlock + 8 * w);
+        }
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+                const h8 x = __builtin_bit_cast(h8, u32x4{a[mt][2 * kk].x, a[mt][2 * kk].y, a[mt][2 * kk + 1].x, a[mt][2 * kk + 1].y});
+                const h8 y = __builtin_bit_cast(h8, u32x4{b[nt][2 * kk].x, b[nt][2 * kk].y, b[nt][2 * kk + 1].x, b[nt][2 * kk + 1].y});
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x, y, acc[mt][nt], 0, 0, 0);
+            }
+}
+
+__device__ __forceinline__ void mma_fp8(f4 (&acc)[4][4], const char *lds, int stage, const Geometry &G)
+{
+    const FragBase F = frag_base<Q8>(lds + stage * kStage, G);
+    constexpr int kBlock = 16 * kRowStride;
+    u32x2 a[4][4], b[4][4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            a[t][w] = lds_load8(F.a + t * kBlock + 8 * w);
+            b[t][w] = lds_load8(F.b + t * kBlock + 8 * w);
+        }
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            const i8v x = {(int)a[mt][0].x, (int)a[mt][0].y, (int)a[mt][1].x, (int)a[mt][1].y,
+                           (int)a[mt][2].x, (int)a[mt][2].y, (int)a[mt][3].x, (int)a[mt][3].y};
+            const i8v y = {(int)b[nt][0].x, (int)b[nt][0].y, (int)b[nt][1].x, (int)b[nt][1].y,
+                           (int)b[nt][2].x, (int)b[nt][2].y, (int)b[nt][3].x, (int)b[nt][3].y};
+            // 16x16x128, both operands e4m3, block scales 2^0 (E8M0 code 127)
+            acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(x, y, acc[mt][nt], 0, 0, 0, 127, 0, 127);
+        }
+}
+
+// Loads of the following chunk are in flight while the MFMAs of a chunk run.
+template <int Q>
+__device__ __forceinline__ Product product_loop_simple(f4 (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
+                                                       const Geometry &G, const Region &R)
 {
     Raw ra[4], rb[4];
     const int n = R.nb / (kRowBytes >> (3 - Q));
-    for (int c = 0; c < n - 1; ++c) {
-        cur.koff += kRowBytes >> (3 - Q);
-        issue_loads<Q>(ra, rb, cur, G, R.nb, R.arow0, R.brow0);
-        mma<Q>(acc, lds + stage * kStage, G);
-        convert_store<Q>(ra, rb, cur, G, lds + (stage ^ 1) * kStage);
+    for (int c = 1; c < n; ++c) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) load_pair(ra[j], rb[j], cur, R.nb, c, j);
+        if constexpr (Q == Q16) mma_fp16(acc, lds, stage, G);
+        else mma_fp8(acc, lds, stage, G);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) store_pair<Q>(ra[j], rb[j], cur, G, lds + (stage ^ 1) * kStage, j);
         __syncthreads();
         stage ^= 1;
     }
-    issue_loads_any(ra, rb, next, G, R);
-    mma<Q>(acc, lds + stage * kStage, G);
-    convert_store_any(ra, rb, next, G, lds + (stage ^ 1) * kStage);
+    const Product next = open_product(*W.P, W.I, W.J, W.tileC, Lnext, G, R);
+    if (next.q >= 0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) load_pair(ra[j], rb[j], next, R.nb, 0, j);
+    }
+    if constexpr (Q == Q16) mma_fp16(acc, lds, stage, G);
+    else mma_fp8(acc, lds, stage, G);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) store_pair_any(ra[j], rb[j], next, G, lds + (stage ^ 1) * kStage, j);
     __syncthreads();
     stage ^= 1;
+    return next;
 }
 
 // The finished tile product joins the running sum once: s += 2^esum * t, then t = 0.
@@ -427,6 +515,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     G.wn = wave & 1;
     G.seg_row = G.tid >> 3;
     G.seg_part = G.tid & 7;
+    G.wbase = G.seg_row * kRowStride + G.seg_part * 16;
 
     const WorkItem it = items[blockIdx.x];
     const int tileC = uni((int)it.tile);
@@ -447,30 +536,39 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
         }
 
     int stage = 0;
-    Chunk cur = open_product(P, I, J, tileC, 0);
-    {
+    Product cur = open_product(P, I, J, tileC, 0, G, R);
+    if (cur.q >= 0) {
         Raw ra[4], rb[4];
-        issue_loads_any(ra, rb, cur, G, R);
-        convert_store_any(ra, rb, cur, G, lds);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) load_pair(ra[j], rb[j], cur, R.nb, 0, j);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) store_pair_any(ra[j], rb[j], cur, G, lds, j);
     }
     __syncthreads();
 
+    Walk W;
+    W.P = &P;
+    W.I = I;
+    W.J = J;
+    W.tileC = tileC;
     for (int L = 0; L < P.kt_eff; ++L) {
-        const Chunk next = open_product(P, I, J, tileC, L + 1);
         const int q = cur.q;
+        Product next;
         if (q == QT) {
-            product_loop<QT>(s, cur, next, lds, stage, G, R);
+            next = product_loop_pipelined<QT>(s, cur, W, L + 1, lds, stage, G, R);
         } else {
-            if (q == Q32) product_loop<Q32>(t, cur, next, lds, stage, G, R);
-            else if (q == Q16) product_loop<Q16>(t, cur, next, lds, stage, G, R);
-            else product_loop<Q8>(t, cur, next, lds, stage, G, R);
-            fold(s, t, q == Q32 ? 0 : cur.eA + cur.eB);
+            const int esum = q == Q32 ? 0 : cur.a.e + cur.b.e;
+            if (q == Q32) next = product_loop_pipelined<Q32>(t, cur, W, L + 1, lds, stage, G, R);
+            else if (q == Q16) next = product_loop_simple<Q16>(t, cur, W, L + 1, lds, stage, G, R);
+            else next = product_loop_simple<Q8>(t, cur, W, L + 1, lds, stage, G, R);
+            fold(s, t, esum);
         }
         cur = next;
     }
 
     // Epilogue: v = alpha*s (+ beta*c0): two rounded products and one rounded sum in T.
-    T *ctile = (T *)(P.C.storage + P.C.offset[tileC]);
+    typedef __attribute__((address_space(1))) T *GlobalT;
+    GlobalT ctile = (GlobalT)(uintptr_t)(P.C.storage + P.C.offset[tileC]);
     const T alpha = (T)P.alpha, beta = (T)P.beta;
     const bool use_c = P.beta != 0.0;
 #pragma unroll
@@ -481,7 +579,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
             for (int v = 0; v < 4; ++v) {
                 const int row = R.arow0 + G.wm * 64 + mt * 16 + 4 * G.g + v;
                 const int col = R.brow0 + G.wn * 64 + nt * 16 + G.li;
-                T *p = ctile + (int64_t)row * P.nb + col;
+                GlobalT p = ctile + (int64_t)row * P.nb + col;
                 T val = alpha * (T)s[mt][nt][v];
                 if (use_c) { const T bc = beta * *p; val = val + bc; }
                 *p = val;
