@@ -55,18 +55,27 @@ def cpu_baseline(w, A, B, C0, seconds):
         side.gemm(np.array(jobs, dtype=np.int32))
         return time.perf_counter() - t0
 
-    (I, J) = tiles[0]
-    t_probe = run([[I, J, 0, rows, 0, nb]])
-    rate = rows * flops_per_row / t_probe
-    want_rows = int(max(rows, min(len(tiles) * nb, seconds * rate / flops_per_row)))
-    jobs, left = [], want_rows
-    for (I, J) in tiles:
-        if left <= 0:
-            break
-        r = min(nb, left)
-        jobs.append([I, J, 0, r, 0, nb])
-        left -= r
+    def sample(want_rows):
+        jobs, left = [], want_rows
+        for (I, J) in tiles:
+            if left <= 0:
+                break
+            r = min(nb, left)
+            jobs.append([I, J, 0, r, 0, nb])
+            left -= r
+        return jobs
+
+    # the first call pays thread start-up and page faults: probe twice, then size the sample
+    run(sample(rows))
+    jobs = sample(4 * rows)
     t = run(jobs)
+    for _ in range(3):
+        done = sum(j[3] for j in jobs)
+        if t >= seconds / 3 or done >= len(tiles) * nb:
+            break
+        want = int(min(len(tiles) * nb, max(2 * done, done * seconds / max(t, 1e-3))))
+        jobs = sample(want)
+        t = run(jobs)
     done_rows = sum(j[3] for j in jobs)
     return {"value": done_rows * flops_per_row / t / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(),
             "kind": "oracle", "seconds": round(t, 2),

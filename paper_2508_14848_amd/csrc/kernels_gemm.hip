@@ -377,6 +377,23 @@ __device__ __forceinline__ void pipelined_chunk(Acc (&acc)[4][4], u32x2 (&fr)[2]
 
 // All chunks of one FP64 / FP32 tile product.  On entry LDS stage `stage` holds the product's
 // first chunk; on exit it holds the first chunk of the next product (if any).
+// Chunks 1..n-1 of a product whose operands are stored at precisions PA, PB: with both known
+// at compile time the staging code is straight-line (no conversion at all when PA = PB = Q).
+template <int Q, int PA, int PB, typename Acc>
+__device__ __forceinline__ void steady_chunks(Acc (&acc)[4][4], u32x2 (&fr)[2][8], const Product &cur, int n, char *lds, int &stage,
+                                              const FragBase &F, const Geometry &G, int nb)
+{
+    Product cp = cur;
+    cp.a.p = PA;
+    cp.b.p = PB;
+    for (int c = 1; c < n; ++c) {
+        pipelined_chunk<Q, false>(acc, fr, cp, c, lds, stage, F, G, nb);
+        stage ^= 1;
+    }
+}
+
+// All chunks of one FP64 / FP32 tile product.  On entry LDS stage `stage` holds the product's
+// first chunk; on exit it holds the first chunk of the next product (if any), which is returned.
 template <int Q, typename Acc>
 __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
                                                           const Geometry &G, const Region &R)
@@ -386,10 +403,15 @@ __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], cons
 #pragma unroll
     for (int slot = 0; slot < 4; ++slot) read_frag_slot(fr[0], F.a + stage * kStage, F.b + stage * kStage, 0, slot);
     const int n = R.nb / (kRowBytes >> (3 - Q));
-    for (int c = 1; c < n; ++c) {
-        pipelined_chunk<Q, false>(acc, fr, cur, c, lds, stage, F, G, R.nb);
-        stage ^= 1;
+#define GMP_STEADY(PA, PB) case (PA) * 4 + (PB): steady_chunks<Q, PA, PB>(acc, fr, cur, n, lds, stage, F, G, R.nb); break;
+    switch (cur.a.p * 4 + cur.b.p) {
+        GMP_STEADY(0, 0) GMP_STEADY(0, 1) GMP_STEADY(0, 2) GMP_STEADY(0, 3)
+        GMP_STEADY(1, 0) GMP_STEADY(1, 1) GMP_STEADY(1, 2) GMP_STEADY(1, 3)
+        GMP_STEADY(2, 0) GMP_STEADY(2, 1) GMP_STEADY(2, 2) GMP_STEADY(2, 3)
+        GMP_STEADY(3, 0) GMP_STEADY(3, 1) GMP_STEADY(3, 2) GMP_STEADY(3, 3)
+    default: break;
     }
+#undef GMP_STEADY
     const Product next = open_product(*W.P, W.I, W.J, W.tileC, Lnext, G, R);
     pipelined_chunk<Q, true>(acc, fr, next, 0, lds, stage, F, G, R.nb);
     stage ^= 1;
@@ -447,22 +469,39 @@ __device__ __forceinline__ void mma_fp8(f4 (&acc)[4][4], const char *lds, int st
 }
 
 // Loads of the following chunk are in flight while the MFMAs of a chunk run.
+template <int Q, int PA, int PB>
+__device__ __forceinline__ void simple_chunks(f4 (&acc)[4][4], const Product &cur, int n, char *lds, int &stage, const Geometry &G, int nb)
+{
+    Raw ra[4], rb[4];
+    Product cp = cur;
+    cp.a.p = PA;
+    cp.b.p = PB;
+    for (int c = 1; c < n; ++c) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) load_pair(ra[j], rb[j], cp, nb, c, j);
+        if constexpr (Q == Q16) mma_fp16(acc, lds, stage, G);
+        else mma_fp8(acc, lds, stage, G);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) store_pair<Q>(ra[j], rb[j], cp, G, lds + (stage ^ 1) * kStage, j);
+        __syncthreads();
+        stage ^= 1;
+    }
+}
+
 template <int Q>
 __device__ __forceinline__ Product product_loop_simple(f4 (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
                                                        const Geometry &G, const Region &R)
 {
-    Raw ra[4], rb[4];
     const int n = R.nb / (kRowBytes >> (3 - Q));
-    for (int c = 1; c < n; ++c) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) load_pair(ra[j], rb[j], cur, R.nb, c, j);
-        if constexpr (Q == Q16) mma_fp16(acc, lds, stage, G);
-        else mma_fp8(acc, lds, stage, G);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) store_pair<Q>(ra[j], rb[j], cur, G, lds + (stage ^ 1) * kStage, j);
-        __syncthreads();
-        stage ^= 1;
+    if constexpr (Q == Q8) {
+        simple_chunks<Q8, Q8, Q8>(acc, cur, n, lds, stage, G, R.nb);
+    } else {
+        if (cur.a.p == Q16 && cur.b.p == Q16) simple_chunks<Q16, Q16, Q16>(acc, cur, n, lds, stage, G, R.nb);
+        else if (cur.a.p == Q16) simple_chunks<Q16, Q16, Q8>(acc, cur, n, lds, stage, G, R.nb);
+        else if (cur.b.p == Q16) simple_chunks<Q16, Q8, Q16>(acc, cur, n, lds, stage, G, R.nb);
+        else simple_chunks<Q16, Q8, Q8>(acc, cur, n, lds, stage, G, R.nb);
     }
+    Raw ra[4], rb[4];
     const Product next = open_product(*W.P, W.I, W.J, W.tileC, Lnext, G, R);
     if (next.q >= 0) {
 #pragma unroll
