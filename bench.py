@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--policy", type=int, default=0, choices=[0, 1])
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain 1 GiB device copy, three times (reference for the HBM byte counters)")
     return ap.parse_args()
 
 
@@ -99,6 +101,14 @@ def main():
     G.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
+    if args.calibrate_copy:
+        src = torch.ones(1 << 27, dtype=torch.float64, device=dev)          # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "plain copy", "bytes_read": src.numel() * 8, "bytes_written": src.numel() * 8}))
+        return
     w = W.CONFIGS[args.workload]()
     t0 = time.perf_counter()
     A = w.dense("A")
