@@ -175,6 +175,17 @@ __device__ __forceinline__ int chunk_elems(int q) { return kRowBytes >> (3 - q);
 // Nothing may be moved across this point by the instruction scheduler.
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// A copy of the lane geometry whose values the optimiser must treat as new.  Every product
+// loop starts from one: otherwise the per-lane addresses of all the specialised loops are
+// hoisted to the top of the kernel and held in registers for its whole life, which pushes the
+// staging data of the inner loops out of the vector registers.
+__device__ __forceinline__ Geometry fresh(const Geometry &G)
+{
+    Geometry g = G;
+    asm volatile("" : "+v"(g.li), "+v"(g.g), "+v"(g.wm), "+v"(g.wn), "+v"(g.wbase), "+v"(g.seg_row), "+v"(g.seg_part));
+    return g;
+}
+
 // Staging of one chunk: each thread owns four 16-byte converted segments per operand
 // (rows seg_row + 32 j, bytes [16 part, 16 part + 16) of the row).  c: chunk index in the product.
 __device__ __forceinline__ void load_pair(Raw &ra, Raw &rb, const Product &pr, int nb, int c, int j)
@@ -311,8 +322,29 @@ __device__ __forceinline__ void mfma_group(Acc (&acc)[4][4], const u32x2 (&fr)[8
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(fr[mt][sub]), __uint_as_float(fr[4 + nt][sub]),
-                                                                   acc[mt][nt], 0, 0, 0);
+                // written as asm so that the accumulator is read and written in place in an
+                // accumulation register: left to itself the register allocator rotates the FP32
+                // side accumulators through other registers with a copy per loop iteration, and
+                // those copies are vector-ALU instructions the FP32 MFMAs cannot hide
+                asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0"
+                             : "+a"(acc[mt][nt])
+                             : "v"(fr[mt][sub]), "v"(fr[4 + nt][sub]));
+    }
+}
+
+// The asm MFMAs are invisible to the compiler's hazard handling.  Around every run of them a
+// fence takes all sixteen accumulators as in/out accumulation registers and waits 32 cycles:
+// whatever register copies the compiler needs are placed outside the fenced region, after the
+// last MFMA has retired and long enough before the first one issues.
+template <typename Acc>
+__device__ __forceinline__ void acc_fence(Acc (&acc)[4][4])
+{
+    if constexpr (std::is_same<Acc, f4>::value) {
+        asm volatile("s_nop 15\n\ts_nop 15"
+                     : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]),
+                       "+a"(acc[1][0]), "+a"(acc[1][1]), "+a"(acc[1][2]), "+a"(acc[1][3]),
+                       "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),
+                       "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3]));
     }
 }
 
@@ -396,13 +428,15 @@ __device__ __forceinline__ void steady_chunks(Acc (&acc)[4][4], u32x2 (&fr)[2][8
 // first chunk; on exit it holds the first chunk of the next product (if any), which is returned.
 template <int Q, typename Acc>
 __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
-                                                          const Geometry &G, const Region &R)
+                                                          const Geometry &G0, const Region &R)
 {
+    const Geometry G = fresh(G0);
     const FragBase F = frag_base<Q>(lds, G);
     u32x2 fr[2][8];
 #pragma unroll
     for (int slot = 0; slot < 4; ++slot) read_frag_slot(fr[0], F.a + stage * kStage, F.b + stage * kStage, 0, slot);
     const int n = R.nb / (kRowBytes >> (3 - Q));
+    acc_fence(acc);
 #define GMP_STEADY(PA, PB) case (PA) * 4 + (PB): steady_chunks<Q, PA, PB>(acc, fr, cur, n, lds, stage, F, G, R.nb); break;
     switch (cur.a.p * 4 + cur.b.p) {
         GMP_STEADY(0, 0) GMP_STEADY(0, 1) GMP_STEADY(0, 2) GMP_STEADY(0, 3)
@@ -412,8 +446,11 @@ __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], cons
     default: break;
     }
 #undef GMP_STEADY
+    acc_fence(acc);
     const Product next = open_product(*W.P, W.I, W.J, W.tileC, Lnext, G, R);
+    acc_fence(acc);
     pipelined_chunk<Q, true>(acc, fr, next, 0, lds, stage, F, G, R.nb);
+    acc_fence(acc);
     stage ^= 1;
     return next;
 }
@@ -490,8 +527,9 @@ __device__ __forceinline__ void simple_chunks(f4 (&acc)[4][4], const Product &cu
 
 template <int Q>
 __device__ __forceinline__ Product product_loop_simple(f4 (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
-                                                       const Geometry &G, const Region &R)
+                                                       const Geometry &G0, const Region &R)
 {
+    const Geometry G = fresh(G0);
     const int n = R.nb / (kRowBytes >> (3 - Q));
     if constexpr (Q == Q8) {
         simple_chunks<Q8, Q8, Q8>(acc, cur, n, lds, stage, G, R.nb);
@@ -516,9 +554,9 @@ __device__ __forceinline__ Product product_loop_simple(f4 (&acc)[4][4], const Pr
     return next;
 }
 
-// The finished tile product joins the running sum once: s += 2^esum * t, then t = 0.
+// The finished tile product joins the running sum once: s += 2^esum * t.
 template <typename AccS>
-__device__ __forceinline__ void fold(AccS (&s)[4][4], f4 (&t)[4][4], int esum)
+__device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int esum)
 {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -529,7 +567,6 @@ __device__ __forceinline__ void fold(AccS (&s)[4][4], f4 (&t)[4][4], int esum)
                 if constexpr (std::is_same<AccS, d4>::value) s[i][j][v] = s[i][j][v] + ldexp((double)t[i][j][v], esum);
                 else s[i][j][v] = s[i][j][v] + ldexpf(t[i][j][v], esum);
             }
-            t[i][j] = f4{0, 0, 0, 0};
         }
 }
 
@@ -565,14 +602,10 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     R.brow0 = uni((int)it.mj) * kMacro;
 
     AccS s[4][4];
-    f4 t[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            s[i][j] = AccS{0, 0, 0, 0};
-            t[i][j] = f4{0, 0, 0, 0};
-        }
+        for (int j = 0; j < 4; ++j) s[i][j] = AccS{0, 0, 0, 0};
 
     int stage = 0;
     Product cur = open_product(P, I, J, tileC, 0, G, R);
@@ -596,6 +629,12 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
         if (q == QT) {
             next = product_loop_pipelined<QT>(s, cur, W, L + 1, lds, stage, G, R);
         } else {
+            // the FP32 accumulator of a product below T lives only for that product
+            f4 t[4][4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
             const int esum = q == Q32 ? 0 : cur.a.e + cur.b.e;
             if (q == Q32) next = product_loop_pipelined<Q32>(t, cur, W, L + 1, lds, stage, G, R);
             else if (q == Q16) next = product_loop_simple<Q16>(t, cur, W, L + 1, lds, stage, G, R);

@@ -161,32 +161,34 @@ def test_pack_is_bit_exact_on_hard_values_and_unpack_round_trips():
 
 def test_small_integer_inputs_are_exact_for_every_precision_combination():
     """Entries in {-3..3}: every format holds them exactly and every partial sum is a small
-    integer, so the GPU result must equal the integer product bit for bit, whatever the maps."""
+    integer, so the GPU result must equal the integer product bit for bit, whatever the maps.
+    Several tile sizes and reduction lengths, so that every kind of product-to-product
+    transition inside an owner workgroup occurs many times."""
     import torch
     from paper_2508_14848_amd.device import DeviceGemmMP
     rng = np.random.default_rng(21)
-    nb, MT, NT, KT = 128, 2, 3, 4
-    M, N, K = MT * nb, NT * nb, KT * nb
-    for policy in (0, 1):
-        for trial in range(3):
-            A = rng.integers(-3, 4, (M, K)).astype(np.float64)
-            B = rng.integers(-3, 4, (K, N)).astype(np.float64)
-            C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
-            mA = rng.integers(0, 4, (MT, KT)).astype(np.uint16)
-            mB = rng.integers(0, 4, (KT, NT)).astype(np.uint16)
-            mC = rng.integers(0, 2, (MT, NT)).astype(np.uint16)
-            if trial == 0:
-                A[0:nb, 0:nb] = 0.0
-                mA[0, 0] = FP8
-            _say("integers policy", policy, "trial", trial)
-            d = DeviceGemmMP(M, N, K, nb, policy=policy)
-            for which, m, X in (("A", mA, A), ("B", mB, B), ("C", mC, C0)):
-                d.set_precision_map(which, m)
-                d.pack_tiles(which, torch.from_numpy(X).cuda())
-            d.run(2.0, -3.0)
-            got = d.unpack_tiles("C").cpu().numpy()
-            want = 2 * (A.astype(np.int64) @ B.astype(np.int64)) - 3 * C0.astype(np.int64)
-            assert np.array_equal(got, want.astype(np.float64))
+    for (nb, MT, NT, KT) in ((128, 2, 3, 4), (256, 2, 2, 9), (384, 1, 2, 5)):
+        M, N, K = MT * nb, NT * nb, KT * nb
+        for policy in (0, 1):
+            for trial in range(3):
+                A = rng.integers(-3, 4, (M, K)).astype(np.float64)
+                B = rng.integers(-3, 4, (K, N)).astype(np.float64)
+                C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
+                mA = rng.integers(0, 4, (MT, KT)).astype(np.uint16)
+                mB = rng.integers(0, 4, (KT, NT)).astype(np.uint16)
+                mC = rng.integers(0, 2, (MT, NT)).astype(np.uint16)
+                if trial == 0:
+                    A[0:nb, 0:nb] = 0.0
+                    mA[0, 0] = FP8
+                _say("integers", (nb, MT, NT, KT), "policy", policy, "trial", trial)
+                d = DeviceGemmMP(M, N, K, nb, policy=policy)
+                for which, m, X in (("A", mA, A), ("B", mB, B), ("C", mC, C0)):
+                    d.set_precision_map(which, m)
+                    d.pack_tiles(which, torch.from_numpy(X).cuda())
+                d.run(2.0, -3.0)
+                got = d.unpack_tiles("C").cpu().numpy()
+                want = 2 * (A.astype(np.int64) @ B.astype(np.int64)) - 3 * C0.astype(np.int64)
+                assert np.array_equal(got, want.astype(np.float64))
 
 
 @pytest.mark.parametrize("policy", [0, 1])
