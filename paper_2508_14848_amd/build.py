@@ -9,7 +9,7 @@ SOURCES = ["gemm_mp_host.hip", "kernels_scan_pack.hip", "kernels_gemm.hip"]
 # -ffp-contract=off: the only fused multiply-adds are the ones the code asks for.
 # packed-fp32 instructions are switched off for this target.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-ffp-contract=off",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function", "-Wno-inline-asm"]
 
 
 def build_library(verbose=False, extra_flags=()):

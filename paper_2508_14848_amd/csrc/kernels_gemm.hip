@@ -41,7 +41,15 @@ constexpr int kRowStride = 136;                      // + 8 B pad: 17 eight-byte
                                                      // evenly over the LDS banks
 constexpr int kOperandStage = kMacro * kRowStride;   // 17408 B
 constexpr int kStage = 2 * kOperandStage;            // A then B
-constexpr int kLdsBytes = 2 * kStage;                // two stages: 69632 B
+constexpr int kHiLdsBytes = 2 * kStage;              // FP64 / FP32 products: two stages, 69632 B
+
+// FP16 / FP8 products use a ring of five stages of unpadded 128-byte rows whose 16-byte slots
+// are XOR-swizzled with (row & 7): slot = segment ^ (row & 7).
+constexpr int kLoOperand = kMacro * kRowBytes;       // 16384 B
+constexpr int kLoStage = 2 * kLoOperand;             // A then B: 32768 B
+constexpr int kLoStages = 5;                         // chunk i lives in stage i % 5, requested 4 chunks ahead
+constexpr int kLoLdsBytes = kLoStages * kLoStage;    // 163840 B: all of the LDS of a CU
+constexpr int kLdsBytes = kLoLdsBytes > kHiLdsBytes ? kLoLdsBytes : kHiLdsBytes;
 constexpr int kThreads = 256;
 
 enum { Q64 = GEMM_MP_FP64, Q32 = GEMM_MP_FP32, Q16 = GEMM_MP_FP16, Q8 = GEMM_MP_FP8_E4M3 };
@@ -74,6 +82,14 @@ struct Product {
 };
 
 // soff: byte offset of (chunk, row block) in the tile; down: FP64 tile feeding an FP32 product.
+// FP16 / FP8 products whose operands are both stored in the product's precision run through the
+// DMA ring (lo_run); every other product expects its first chunk staged by its predecessor.
+__device__ __forceinline__ bool is_ring(const Product &pr)
+{
+    return (pr.q == Q16 || pr.q == Q8) && pr.a.p == pr.q && pr.b.p == pr.q;
+}
+__device__ __forceinline__ bool wants_first_chunk(const Product &pr) { return pr.q >= 0 && !is_ring(pr); }
+
 __device__ __forceinline__ void load_seg(Raw &r, const Operand &o, int soff, bool down)
 {
 #ifdef GMP_EXP_NOLOAD   /* timing experiment only: no global traffic, operands are garbage */
@@ -228,6 +244,20 @@ __device__ __forceinline__ void store_pair_any(const Raw &ra, const Raw &rb, con
 
 // Everything that describes a tile product is the same for all lanes of the workgroup; passing
 // it through readfirstlane keeps it in scalar registers and makes every branch on it scalar.
+// Wave-uniform reads of the small descriptor tables (read-only for the whole kernel) through
+// the constant address space, so that they are scalar loads: no vector registers, no vector
+// ALU, and no interference with the counter of outstanding vector-memory operations.  Byte
+// tables are read as the aligned 32-bit word around the byte (the tables are allocated with
+// padding).
+typedef const __attribute__((address_space(4))) uint32_t *ConstWord;
+typedef const __attribute__((address_space(4))) uint64_t *ConstDword;
+__device__ __forceinline__ int table_i32(const int32_t *t, int64_t i) { return (int)*(ConstWord)(uintptr_t)(t + i); }
+__device__ __forceinline__ uint64_t table_u64(const uint64_t *t, int64_t i) { return *(ConstDword)(uintptr_t)(t + i); }
+__device__ __forceinline__ int table_u8(const uint8_t *t, int64_t i)
+{
+    const uintptr_t a = (uintptr_t)(t + i);
+    return (int)((*(ConstWord)(a & ~(uintptr_t)3) >> ((a & 3) * 8)) & 0xffu);
+}
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ const char *uni(const char *p)
 {
@@ -241,9 +271,9 @@ __device__ __forceinline__ const char *uni(const char *p)
 __device__ __forceinline__ Operand open_operand(const PackedView &V, int tile, int q, int row0, const Geometry &G, int nb)
 {
     Operand o;
-    o.base = uni(V.storage + V.offset[tile]);
-    o.p = uni(V.prec[tile]);
-    o.e = uni(V.exp[tile]);
+    o.base = V.storage + table_u64(V.offset, tile);
+    o.p = table_u8(V.prec, tile);
+    o.e = table_i32(V.exp, tile);
     const int shift = 3 - o.p;                                   // log2 of the element size
     o.bytes = (nb * nb) << shift;
     const int n_q = 2 << q;                                      // elements per 16-byte converted segment
@@ -263,7 +293,7 @@ __device__ __forceinline__ Product open_product(const GemmArgs &P, int I, int J,
         pr.b = Operand{};
         return pr;
     }
-    pr.q = uni(P.q[(int64_t)tileC * P.KT + L]);
+    pr.q = table_u8(P.q, (int64_t)tileC * P.KT + L);
     pr.a = open_operand(P.A, I * P.KT + L, pr.q, R.arow0, G, R.nb);
     pr.b = open_operand(P.B, L * P.NT + J, pr.q, R.brow0, G, R.nb);
     return pr;
@@ -309,8 +339,16 @@ __device__ __forceinline__ u32x2 lds_load8(const char *p) { return *(const u32x2
 //   macro-step 2      : conversion + LDS writes of the next chunk into the other stage
 //   macro-step 3      : barrier in slot 0, then LDS reads of the next chunk's first fragments
 // fr[buf][0..3] = A fragments of row blocks 0..3, fr[buf][4..7] = B fragments.
+// POS: 1 = first group of a chunk, 2 = last group of a chunk, 0 = neither.
+// The FP32 MFMAs are written as asm so that the accumulator is read and written in place in an
+// accumulation register: left to itself the register allocator rotates the FP32 side
+// accumulators through other registers with a copy per loop iteration, and those copies are
+// vector-ALU instructions the FP32 MFMAs cannot hide.  Asm MFMAs are invisible to the compiler's
+// hazard handling, so the first one of a chunk carries wait states in front (a register copy
+// or zeroing may sit right before it) and the last one carries the wait states an 8-pass MFMA
+// needs before an ordinary instruction may touch its result.
 template <int Q, typename Acc>
-__device__ __forceinline__ void mfma_group(Acc (&acc)[4][4], const u32x2 (&fr)[8], int mt)
+__device__ __forceinline__ void mfma_group(Acc (&acc)[4][4], const u32x2 (&fr)[8], int mt, int POS)
 {
     if constexpr (Q == Q64) {
         const double a = as_double(fr[mt].x, fr[mt].y);
@@ -321,14 +359,17 @@ __device__ __forceinline__ void mfma_group(Acc (&acc)[4][4], const u32x2 (&fr)[8
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt)
-                // written as asm so that the accumulator is read and written in place in an
-                // accumulation register: left to itself the register allocator rotates the FP32
-                // side accumulators through other registers with a copy per loop iteration, and
-                // those copies are vector-ALU instructions the FP32 MFMAs cannot hide
-                asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0"
-                             : "+a"(acc[mt][nt])
-                             : "v"(fr[mt][sub]), "v"(fr[4 + nt][sub]));
+            for (int nt = 0; nt < 4; ++nt) {
+                if (POS == 1 && sub == 0 && nt == 0)
+                    asm volatile("s_nop 3\n\tv_mfma_f32_16x16x4_f32 %0, %1, %2, %0"
+                                 : "+a"(acc[mt][nt]) : "v"(fr[mt][sub]), "v"(fr[4 + nt][sub]));
+                else if (POS == 2 && sub == 1 && nt == 3)
+                    asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0\n\ts_nop 11"
+                                 : "+a"(acc[mt][nt]) : "v"(fr[mt][sub]), "v"(fr[4 + nt][sub]));
+                else
+                    asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0"
+                                 : "+a"(acc[mt][nt]) : "v"(fr[mt][sub]), "v"(fr[4 + nt][sub]));
+            }
     }
 }
 
@@ -346,6 +387,17 @@ __device__ __forceinline__ void acc_fence(Acc (&acc)[4][4])
                        "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),
                        "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3]));
     }
+}
+
+// Lighter form before a run of asm MFMAs: any register copy or zeroing the compiler still owes
+// the accumulators is forced in front of it, and eight cycles pass before the first MFMA reads.
+__device__ __forceinline__ void acc_settle(f4 (&acc)[4][4])
+{
+    asm volatile("s_nop 7"
+                 : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]),
+                   "+a"(acc[1][0]), "+a"(acc[1][1]), "+a"(acc[1][2]), "+a"(acc[1][3]),
+                   "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),
+                   "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3]));
 }
 
 // Order in which the eight fragments of a macro-step are fetched, two per slot: the B fragments
@@ -376,14 +428,16 @@ __device__ __forceinline__ void pipelined_chunk(Acc (&acc)[4][4], u32x2 (&fr)[2]
     for (int m = 0; m < 4; ++m) {
 #pragma unroll
         for (int grp = 0; grp < 4; ++grp) {
-            mfma_group<Q>(acc, fr[m & 1], grp);
+            mfma_group<Q>(acc, fr[m & 1], grp, (m == 0 && grp == 0) ? 1 : (m == 3 && grp == 3) ? 2 : 0);
             SCHED_FENCE();
             if (m == 0) {
-                if (!LAST || pr.q >= 0) load_pair(ra[grp], rb[grp], pr, nb, c, grp);
+                if (!LAST || wants_first_chunk(pr)) load_pair(ra[grp], rb[grp], pr, nb, c, grp);
             }
             if (m < 3) read_frag_slot(fr[(m + 1) & 1], fa, fb, m + 1, grp);
             if (m == 2) {
-                if constexpr (LAST) store_pair_any(ra[grp], rb[grp], pr, G, wst, grp);
+                if constexpr (LAST) {
+                    if (wants_first_chunk(pr)) store_pair_any(ra[grp], rb[grp], pr, G, wst, grp);
+                }
                 else store_pair<Q>(ra[grp], rb[grp], pr, G, wst, grp);
             }
             if (m == 3) {
@@ -455,8 +509,325 @@ __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], cons
     return next;
 }
 
-// ---- FP16 / FP8 products: one chunk = 2 k-steps of 16x16x32 FP16, or one 16x16x128 FP8 step ----
-__device__ __forceinline__ void mma_fp16(f4 (&acc)[4][4], const char *lds, int stage, const Geometry &G)
+// ---- FP16 / FP8 products --------------------------------------------------------------------
+// These MFMAs are fast (a chunk is ~530 matrix-core cycles per wave) and, unlike the FP64/FP32
+// ones, overlap with vector-ALU work; what limits them is the latency of global memory and the
+// LDS.  Consecutive FP16/FP8 products of a C region are therefore run as one stream of chunks
+// through a ring of four LDS stages, each chunk requested three chunks ahead.  An operand
+// stored in the product's own precision goes from global memory straight into LDS with the
+// buffer-load-to-LDS instruction (no registers, no vector ALU); an FP8 tile feeding an FP16
+// product goes through registers (exact FP8 -> FP16 conversion) one chunk later.
+struct LoGeom {
+    int dma_row;      // tile row this lane fetches in DMA instruction j = 0 of its wave (+ 8 j)
+    int dma_seg;      // byte offset of its 16-byte segment in the 128-byte chunk row
+    int wbase;        // register path: swizzled LDS offset of (seg_row, seg_part); + 4096 j
+    int fa0, fa1;     // fragment reads, A rows of this wave, row block 0: the lane's two 16-byte halves
+    int fb0, fb1;     // same for B (includes the operand offset)
+};
+
+__device__ __forceinline__ LoGeom lo_geometry(const Geometry &G)
+{
+    LoGeom g;
+    const int wave = G.tid >> 6;
+    g.dma_row = wave * 32 + (G.lane >> 3);
+    g.dma_seg = ((G.lane & 7) ^ ((G.lane >> 3) & 7)) * 16;
+    g.wbase = G.seg_row * kRowBytes + ((G.seg_part ^ (G.seg_row & 7)) * 16);
+    const int x = G.li & 7;
+    g.fa0 = (G.wm * 64 + G.li) * kRowBytes + (((2 * G.g) ^ x) * 16);
+    g.fa1 = (G.wm * 64 + G.li) * kRowBytes + (((2 * G.g + 1) ^ x) * 16);
+    g.fb0 = kLoOperand + (G.wn * 64 + G.li) * kRowBytes + (((2 * G.g) ^ x) * 16);
+    g.fb1 = kLoOperand + (G.wn * 64 + G.li) * kRowBytes + (((2 * G.g + 1) ^ x) * 16);
+    return g;
+}
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// Four buffer-load-to-LDS instructions: 32 rows x 128 bytes of one operand chunk per wave.
+// Lane l of instruction j writes LDS bytes [dst + 1024 j + 16 l, +16), i.e. row 8 j + l/8,
+// slot l%8, and fetches the segment that belongs there.  The loads are asm because the
+// compiler, not knowing which stage a later LDS read touches, would wait for all of them
+// before every read; completion is awaited explicitly (lo_wait_dma) before the barrier that
+// publishes the stage.  They write no register, so nothing the compiler allocates depends on
+// their completion.
+__device__ __forceinline__ void lo_dma(const Operand &o, int soff, int rows8_bytes, unsigned dst)
+{
+    const uint64_t b = (uint64_t)o.base;
+    const i32x4 rsrc = {(int)(uint32_t)b, (int)((uint32_t)(b >> 32) & 0xffffu), o.bytes, 0x00020000};
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(GMP_EXP_NODMA)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :
+                     : "s"(dst + 1024u * j), "v"(o.voff), "s"(rsrc), "s"(__builtin_amdgcn_readfirstlane(soff + j * rows8_bytes))
+                     : "memory", "m0");
+#else
+    (void)rsrc; (void)soff; (void)rows8_bytes; (void)dst;
+#endif
+}
+
+// Wait until at most `newer` vector-memory operations are outstanding.  Loads complete in
+// order, so this guarantees the ones issued before the newest `newer` have landed; operations
+// the compiler issued on its own in between only make the wait stricter.
+__device__ __forceinline__ void lo_wait_dma(int newer)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    if (newer >= 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+    else if (newer >= 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else if (newer >= 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    else if (newer >= 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else if (newer >= 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#else
+    (void)newer;
+#endif
+}
+
+// Where the chunk stream of a run of FP16/FP8 products stands.
+struct LoCursor {
+    Product pr;     // product being staged
+    int L, c, n;    // its reduction tile, the next chunk to stage, chunks per product
+};
+
+// Prepare an operand for this path: an operand in the product's precision is fetched by DMA.
+__device__ __forceinline__ void lo_operand(Operand &o, int q, int row0, int nb, const LoGeom &LG)
+{
+    if (o.p == q) {
+        o.voff = (((row0 + LG.dma_row) * nb) << (3 - q)) + LG.dma_seg;
+        o.sub = 0;
+    }
+}
+
+// One buffer-load-to-LDS instruction of a chunk request (see lo_dma): k = 0..3 are the four
+// row blocks of the A chunk, k = 4..7 those of the B chunk.
+__device__ __forceinline__ void lo_dma_one(const Product &pr, int soff0, int rows8_bytes, unsigned dst, int k)
+{
+    const Operand &o = k < 4 ? pr.a : pr.b;
+    const int j = k & 3;
+    const uint64_t b = (uint64_t)o.base;
+    const i32x4 rsrc = {(int)(uint32_t)b, (int)((uint32_t)(b >> 32) & 0xffffu), o.bytes, 0x00020000};
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(GMP_EXP_NODMA)
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(dst + (k < 4 ? 0u : (unsigned)kLoOperand) + 1024u * j), "v"(o.voff), "s"(rsrc),
+                   "s"(__builtin_amdgcn_readfirstlane(soff0 + j * rows8_bytes))
+                 : "memory", "m0");
+#else
+    (void)rsrc; (void)soff0; (void)rows8_bytes; (void)dst;
+#endif
+}
+
+// Fragment registers of one chunk: index (operand * 4 + row block) * 2 + half; operand 0 = A.
+// Two sets: while the MFMAs of a chunk run from one, the fragments of the next chunk (already
+// published in its ring stage) are read into the other.  Read r = 0..15 of a chunk: B first.
+__device__ __forceinline__ void lo_read_one(u32x4 (&f)[16], const char *stage, const LoGeom &LG, int r)
+{
+    constexpr int kBlock = 16 * kRowBytes;
+    const int op = r < 8 ? 1 : 0, t = (r & 7) >> 1, half = r & 1;
+    const int o = op ? (half ? LG.fb1 : LG.fb0) : (half ? LG.fa1 : LG.fa0);
+    f[(op * 4 + t) * 2 + half] = *(const u32x4 *)(stage + o + t * kBlock);
+}
+__device__ __forceinline__ void lo_read_slot(u32x4 (&f)[16], const char *stage, const LoGeom &LG, int slot)
+{
+#pragma unroll
+    for (int r = 4 * slot; r < 4 * slot + 4; ++r) lo_read_one(f, stage, LG, r);
+}
+
+// One step of the chunk stream: the MFMAs of a chunk from fragment set PAR.  These MFMAs leave
+// issue slots free while they execute (16 or 32 cycles each), and everything else the step has
+// to do is placed into those slots, one or two instructions behind each MFMA: first the reads
+// of the next chunk's fragments from the ring stage `next` into the other set, then the eight
+// DMA instructions that request a later chunk of product `pr` into the stage at `dst`.
+// The MFMAs are asm in place, see mfma_group.
+template <int Q, int PAR>
+__device__ __forceinline__ void lo_chunk(f4 (&acc)[4][4], u32x4 (&fr)[2][16], const char *next, const LoGeom &LG,
+                                         const Product &pr, int soff0, int rows8_bytes, unsigned dst)
+{
+    constexpr int kMfmas = Q == Q16 ? 32 : 16;
+#pragma unroll
+    for (int m = 0; m < kMfmas; ++m) {
+        const int g = m >> 2, nt = m & 3, mt = g & 3, kk = g >> 2;
+        const bool first = m == 0, last = m == kMfmas - 1;
+        if constexpr (Q == Q16) {
+            const u32x4 x = fr[PAR][mt * 2 + kk], y = fr[PAR][(4 + nt) * 2 + kk];
+            if (first) asm volatile("s_nop 3\n\tv_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+            else if (last) asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0\n\ts_nop 11" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+            else asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+        } else {
+            const u32x4 a0 = fr[PAR][mt * 2], a1 = fr[PAR][mt * 2 + 1], b0 = fr[PAR][(4 + nt) * 2], b1 = fr[PAR][(4 + nt) * 2 + 1];
+            const i8v x = {(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, (int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w};
+            const i8v y = {(int)b0.x, (int)b0.y, (int)b0.z, (int)b0.w, (int)b1.x, (int)b1.y, (int)b1.z, (int)b1.w};
+            // 16x16x128, both operands e4m3 (format selectors 0), no block scaling
+            if (first) asm volatile("s_nop 3\n\tv_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+            else if (last) asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0\n\ts_nop 11" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+            else asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+        }
+        SCHED_FENCE();
+        if constexpr (Q == Q16) {
+            if (m < 16) lo_read_one(fr[PAR ^ 1], next, LG, m);
+            else if (m < 24) lo_dma_one(pr, soff0, rows8_bytes, dst, m - 16);
+        } else {
+            if (m < 8) {
+                lo_read_one(fr[PAR ^ 1], next, LG, 2 * m);
+                lo_read_one(fr[PAR ^ 1], next, LG, 2 * m + 1);
+            } else {
+                lo_dma_one(pr, soff0, rows8_bytes, dst, m - 8);
+            }
+        }
+        SCHED_FENCE();
+    }
+}
+
+template <typename AccS>
+__device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int esum);
+
+// A run of consecutive ring products starting at product `cur` (reduction tile L).  On return
+// `cur` is the first product after the run (q = -1: none) and L its index; if that product wants
+// its first chunk staged, it is in stage 0 of the two-stage layout.
+template <typename AccS>
+__device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, const Walk &W, char *lds, const Geometry &G0,
+                                       const Region &R)
+{
+    const Geometry G = fresh(G0);
+    const LoGeom LG = lo_geometry(G);
+    const GemmArgs &P = *W.P;
+    const int wave = G.tid >> 6;
+    f4 t[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
+
+    // staging cursor
+    LoCursor pf;
+    pf.pr = cur;
+    pf.L = L;
+    pf.c = 0;
+    pf.n = R.nb / chunk_elems(cur.q);
+    lo_operand(pf.pr.a, pf.pr.q, R.arow0, R.nb, LG);
+    lo_operand(pf.pr.b, pf.pr.q, R.brow0, R.nb, LG);
+    bool pf_valid = true;
+    Product after;            // first product that does not belong to the run
+    after.q = -1;
+    after.a = Operand{};
+    after.b = Operand{};
+    int staged = 0;           // chunks requested so far
+    int st_req = 0;           // ring stage (byte offset) of the next request
+    const int wave_off = uni(wave * 4096);
+
+    // A request = eight DMA instructions per wave (chunk pf.c of product pf.pr into the stage at
+    // st_req), then req_done moves the cursor on.  Every step of the stream issues one, so that
+    // the number of outstanding instructions is the same at every step; past the end of the
+    // stream the requests are empty: the operands' descriptors get length zero, which turns
+    // every lane's load into an out-of-range one that touches no global memory (it zero-fills
+    // its 16 bytes of a stage nobody reads any more).
+    auto req_done = [&]() __attribute__((always_inline)) {
+        st_req = st_req + kLoStage == kLoLdsBytes ? 0 : st_req + kLoStage;
+        if (!pf_valid) return;
+        ++staged;
+        if (++pf.c == pf.n) {                       // next product: does it continue the run?
+            ++pf.L;
+            Product nx = open_product(P, W.I, W.J, W.tileC, pf.L, G, R);
+            if (is_ring(nx)) {
+                lo_operand(nx.a, nx.q, R.arow0, R.nb, LG);
+                lo_operand(nx.b, nx.q, R.brow0, R.nb, LG);
+                pf.pr = nx;
+                pf.n = R.nb / chunk_elems(nx.q);
+            } else {
+                after = nx;
+                pf_valid = false;
+                pf.pr.a.bytes = 0;
+                pf.pr.b.bytes = 0;
+            }
+            pf.c = 0;
+        }
+    };
+#define GMP_LO_REQ_ARGS pf.pr, (pf.c * chunk_elems(pf.pr.q)) << (3 - pf.pr.q), (8 * R.nb) << (3 - pf.pr.q), (unsigned)(st_req + wave_off)
+
+    // prologue: chunks 0..4 requested; chunks 0 and 1 complete and published; fragments of chunk 0 read
+#pragma unroll 1
+    for (int i = 0; i < kLoStages; ++i) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) lo_dma_one(GMP_LO_REQ_ARGS, k);
+        req_done();
+    }
+    lo_wait_dma(8 * (kLoStages - 2));
+    __syncthreads();
+    u32x4 fr[2][16];
+#pragma unroll
+    for (int slot = 0; slot < 4; ++slot) lo_read_slot(fr[0], lds, LG, slot);
+
+    // compute: product by product; inside a product the accumulators are touched by MFMAs only
+    int cL = L;
+    int cq = cur.q;
+    int cesum = cur.a.e + cur.b.e;
+    int done = 0;                                  // chunks computed
+    int st_next = kLoStage;                        // ring stage of chunk done + 1
+    // One step: the MFMAs of chunk `done` from fragment set PAR; in their shadow the fragments of
+    // chunk done + 1 are read from the ring stage after it (past the end of the stream that read
+    // is harmless and unused) and chunk done + 5 is requested into the stage that chunk `done`
+    // occupied (every wave finished reading it before the barrier that ended the previous step).
+    // Then wait until chunk done + 2 is complete in LDS for every wave: everything but the three
+    // requests after it.
+#define GMP_LO_STEP(QQ, PAR)                                                         \
+    do {                                                                             \
+        lo_chunk<QQ, PAR>(t, fr, lds + st_next, LG, GMP_LO_REQ_ARGS);                \
+        req_done();                                                                  \
+        ++done;                                                                      \
+        st_next = st_next + kLoStage == kLoLdsBytes ? 0 : st_next + kLoStage;        \
+        lo_wait_dma(8 * (kLoStages - 2));                                            \
+        __syncthreads();                                                             \
+    } while (0)
+    while (done < staged) {
+        const int cn = R.nb / chunk_elems(cq);
+        // precision and exponent sum of the product after this one, fetched early
+        const bool more = cL + 1 < P.kt_eff;
+        const int nq = more ? table_u8(P.q, (int64_t)W.tileC * P.KT + cL + 1) : -1;
+        const int nesum = more ? table_i32(P.A.exp, W.I * P.KT + cL + 1) + table_i32(P.B.exp, (cL + 1) * P.NT + W.J) : 0;
+        if (cq == Q16) {                           // 64 elements per chunk: always an even count
+            for (int cc = 0; cc < cn; cc += 2) {
+                GMP_LO_STEP(Q16, 0);
+                GMP_LO_STEP(Q16, 1);
+            }
+        } else {
+            for (int cc = 0; cc + 2 <= cn; cc += 2) {
+                GMP_LO_STEP(Q8, 0);
+                GMP_LO_STEP(Q8, 1);
+            }
+            if (cn & 1) {                          // odd count: bring the fragments back to set 0
+                GMP_LO_STEP(Q8, 0);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) fr[0][i] = fr[1][i];
+            }
+        }
+        // the product is complete: it joins the running sum
+        fold(s, t, cesum);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
+        ++cL;
+        cq = nq;
+        cesum = nesum;
+    }
+#undef GMP_LO_STEP
+#undef GMP_LO_REQ_ARGS
+    lo_wait_dma(0);                                // the empty requests still write (zeros) into the ring
+    __syncthreads();
+
+    L = cL;
+    cur = after;
+    if (wants_first_chunk(after)) {                // hand over to the two-stage layout
+        Raw xa[4], xb[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) load_pair(xa[j], xb[j], after, R.nb, 0, j);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) store_pair_any(xa[j], xb[j], after, G, lds, j);
+        __syncthreads();
+    }
+}
+
+// ---- FP16 products with one FP8 operand: two-stage loop with the conversion in registers ----
+__device__ __forceinline__ void mma_fp16_padded(f4 (&acc)[4][4], const char *lds, int stage, const Geometry &G)
 {
     const FragBase F = frag_base<Q16>(lds + stage * kStage, G);
     constexpr int kBlock = 16 * kRowStride;
@@ -476,38 +847,17 @@ __device__ __forceinline__ void mma_fp16(f4 (&acc)[4][4], const char *lds, int s
             for (int nt = 0; nt < 4; ++nt) {
                 const h8 x = __builtin_bit_cast(h8, u32x4{a[mt][2 * kk].x, a[mt][2 * kk].y, a[mt][2 * kk + 1].x, a[mt][2 * kk + 1].y});
                 const h8 y = __builtin_bit_cast(h8, u32x4{b[nt][2 * kk].x, b[nt][2 * kk].y, b[nt][2 * kk + 1].x, b[nt][2 * kk + 1].y});
-                acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(x, y, acc[mt][nt], 0, 0, 0);
+                if (kk == 0 && mt == 0 && nt == 0)
+                    asm volatile("s_nop 3\n\tv_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+                else if (kk == 1 && mt == 3 && nt == 3)
+                    asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0\n\ts_nop 11" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+                else
+                    asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
             }
 }
 
-__device__ __forceinline__ void mma_fp8(f4 (&acc)[4][4], const char *lds, int stage, const Geometry &G)
-{
-    const FragBase F = frag_base<Q8>(lds + stage * kStage, G);
-    constexpr int kBlock = 16 * kRowStride;
-    u32x2 a[4][4], b[4][4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            a[t][w] = lds_load8(F.a + t * kBlock + 8 * w);
-            b[t][w] = lds_load8(F.b + t * kBlock + 8 * w);
-        }
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-            const i8v x = {(int)a[mt][0].x, (int)a[mt][0].y, (int)a[mt][1].x, (int)a[mt][1].y,
-                           (int)a[mt][2].x, (int)a[mt][2].y, (int)a[mt][3].x, (int)a[mt][3].y};
-            const i8v y = {(int)b[nt][0].x, (int)b[nt][0].y, (int)b[nt][1].x, (int)b[nt][1].y,
-                           (int)b[nt][2].x, (int)b[nt][2].y, (int)b[nt][3].x, (int)b[nt][3].y};
-            // 16x16x128, both operands e4m3, block scales 2^0 (E8M0 code 127)
-            acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(x, y, acc[mt][nt], 0, 0, 0, 127, 0, 127);
-        }
-}
-
-// Loads of the following chunk are in flight while the MFMAs of a chunk run.
-template <int Q, int PA, int PB>
-__device__ __forceinline__ void simple_chunks(f4 (&acc)[4][4], const Product &cur, int n, char *lds, int &stage, const Geometry &G, int nb)
+template <int PA, int PB>
+__device__ __forceinline__ void mixed16_chunks(f4 (&acc)[4][4], const Product &cur, int n, char *lds, int &stage, const Geometry &G, int nb)
 {
     Raw ra[4], rb[4];
     Product cp = cur;
@@ -516,39 +866,36 @@ __device__ __forceinline__ void simple_chunks(f4 (&acc)[4][4], const Product &cu
     for (int c = 1; c < n; ++c) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) load_pair(ra[j], rb[j], cp, nb, c, j);
-        if constexpr (Q == Q16) mma_fp16(acc, lds, stage, G);
-        else mma_fp8(acc, lds, stage, G);
+        mma_fp16_padded(acc, lds, stage, G);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) store_pair<Q>(ra[j], rb[j], cp, G, lds + (stage ^ 1) * kStage, j);
+        for (int j = 0; j < 4; ++j) store_pair<Q16>(ra[j], rb[j], cp, G, lds + (stage ^ 1) * kStage, j);
         __syncthreads();
         stage ^= 1;
     }
 }
 
-template <int Q>
-__device__ __forceinline__ Product product_loop_simple(f4 (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
-                                                       const Geometry &G0, const Region &R)
+// On entry LDS stage `stage` holds the product's first chunk; on exit it holds the first chunk
+// of the next product if that one wants it.
+__device__ __forceinline__ Product product_loop_mixed16(f4 (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
+                                                        const Geometry &G0, const Region &R)
 {
     const Geometry G = fresh(G0);
-    const int n = R.nb / (kRowBytes >> (3 - Q));
-    if constexpr (Q == Q8) {
-        simple_chunks<Q8, Q8, Q8>(acc, cur, n, lds, stage, G, R.nb);
-    } else {
-        if (cur.a.p == Q16 && cur.b.p == Q16) simple_chunks<Q16, Q16, Q16>(acc, cur, n, lds, stage, G, R.nb);
-        else if (cur.a.p == Q16) simple_chunks<Q16, Q16, Q8>(acc, cur, n, lds, stage, G, R.nb);
-        else if (cur.b.p == Q16) simple_chunks<Q16, Q8, Q16>(acc, cur, n, lds, stage, G, R.nb);
-        else simple_chunks<Q16, Q8, Q8>(acc, cur, n, lds, stage, G, R.nb);
-    }
+    const int n = R.nb / chunk_elems(Q16);
+    if (cur.a.p == Q16) mixed16_chunks<Q16, Q8>(acc, cur, n, lds, stage, G, R.nb);
+    else mixed16_chunks<Q8, Q16>(acc, cur, n, lds, stage, G, R.nb);
     Raw ra[4], rb[4];
     const Product next = open_product(*W.P, W.I, W.J, W.tileC, Lnext, G, R);
-    if (next.q >= 0) {
+    const bool give = wants_first_chunk(next);
+    if (give) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) load_pair(ra[j], rb[j], next, R.nb, 0, j);
     }
-    if constexpr (Q == Q16) mma_fp16(acc, lds, stage, G);
-    else mma_fp8(acc, lds, stage, G);
+    mma_fp16_padded(acc, lds, stage, G);
+    acc_fence(acc);
+    if (give) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) store_pair_any(ra[j], rb[j], next, G, lds + (stage ^ 1) * kStage, j);
+        for (int j = 0; j < 4; ++j) store_pair_any(ra[j], rb[j], next, G, lds + (stage ^ 1) * kStage, j);
+    }
     __syncthreads();
     stage ^= 1;
     return next;
@@ -609,7 +956,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 
     int stage = 0;
     Product cur = open_product(P, I, J, tileC, 0, G, R);
-    if (cur.q >= 0) {
+    if (wants_first_chunk(cur)) {
         Raw ra[4], rb[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) load_pair(ra[j], rb[j], cur, R.nb, 0, j);
@@ -623,25 +970,47 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     W.I = I;
     W.J = J;
     W.tileC = tileC;
-    for (int L = 0; L < P.kt_eff; ++L) {
+    int L = 0;
+    while (L < P.kt_eff) {
         const int q = cur.q;
+        if (is_ring(cur)) {
+            lo_run(s, cur, L, W, lds, G, R);       // all consecutive products of that kind
+            stage = 0;
+            continue;
+        }
         Product next;
-        if (q == QT) {
-            next = product_loop_pipelined<QT>(s, cur, W, L + 1, lds, stage, G, R);
-        } else {
-            // the FP32 accumulator of a product below T lives only for that product
+        if (q == Q16) {                            // FP16 product with one FP8 operand
             f4 t[4][4];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
-            const int esum = q == Q32 ? 0 : cur.a.e + cur.b.e;
-            if (q == Q32) next = product_loop_pipelined<Q32>(t, cur, W, L + 1, lds, stage, G, R);
-            else if (q == Q16) next = product_loop_simple<Q16>(t, cur, W, L + 1, lds, stage, G, R);
-            else next = product_loop_simple<Q8>(t, cur, W, L + 1, lds, stage, G, R);
+            const int esum = cur.a.e + cur.b.e;
+            next = product_loop_mixed16(t, cur, W, L + 1, lds, stage, G, R);
             fold(s, t, esum);
+            cur = next;
+            ++L;
+            continue;
+        }
+        if (q == QT) {
+            next = product_loop_pipelined<QT>(s, cur, W, L + 1, lds, stage, G, R);
+        } else {
+            if constexpr (QT == Q64) {
+                // an FP32 product of an FP64 C tile: its FP32 accumulator lives only for that product
+                f4 t[4][4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
+                next = product_loop_pipelined<Q32>(t, cur, W, L + 1, lds, stage, G, R);
+                fold(s, t, 0);
+            } else {
+                next = cur;                        // not reachable: the host never schedules FP64 products on FP32 tiles
+                next.q = -1;
+            }
         }
         cur = next;
+        ++L;
     }
 
     // Epilogue: v = alpha*s (+ beta*c0): two rounded products and one rounded sum in T.
