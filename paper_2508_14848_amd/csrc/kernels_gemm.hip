@@ -49,7 +49,13 @@ constexpr int kLoOperand = kMacro * kRowBytes;       // 16384 B
 constexpr int kLoStage = 2 * kLoOperand;             // A then B: 32768 B
 constexpr int kLoStages = 5;                         // chunk i lives in stage i % 5, requested 4 chunks ahead
 constexpr int kLoLdsBytes = kLoStages * kLoStage;    // 163840 B: all of the LDS of a CU
+#ifdef GMP_EXP_OCC2
+constexpr int kLdsBytes = kHiLdsBytes;
+#define GMP_WAVES_PER_EU 2
+#else
 constexpr int kLdsBytes = kLoLdsBytes > kHiLdsBytes ? kLoLdsBytes : kHiLdsBytes;
+#define GMP_WAVES_PER_EU 1
+#endif
 constexpr int kThreads = 256;
 
 enum { Q64 = GEMM_MP_FP64, Q32 = GEMM_MP_FP32, Q16 = GEMM_MP_FP16, Q8 = GEMM_MP_FP8_E4M3 };
@@ -82,14 +88,6 @@ struct Product {
 };
 
 // soff: byte offset of (chunk, row block) in the tile; down: FP64 tile feeding an FP32 product.
-// FP16 / FP8 products whose operands are both stored in the product's precision run through the
-// DMA ring (lo_run); every other product expects its first chunk staged by its predecessor.
-__device__ __forceinline__ bool is_ring(const Product &pr)
-{
-    return (pr.q == Q16 || pr.q == Q8) && pr.a.p == pr.q && pr.b.p == pr.q;
-}
-__device__ __forceinline__ bool wants_first_chunk(const Product &pr) { return pr.q >= 0 && !is_ring(pr); }
-
 __device__ __forceinline__ void load_seg(Raw &r, const Operand &o, int soff, bool down)
 {
 #ifdef GMP_EXP_NOLOAD   /* timing experiment only: no global traffic, operands are garbage */
@@ -177,6 +175,7 @@ __device__ __forceinline__ u32x4 convert(const Raw &r, int p, int e, int sub)
 }
 
 struct Geometry {
+    bool ring;                      // FP32 C tiles only: pure FP16 / FP8 products go through the DMA ring
     int tid, lane, li, g, wm, wn;
     int seg_row, seg_part;          // staging: this thread's first row and its 16-byte part
     int wbase;                      // byte offset of that segment in an LDS operand stage
@@ -185,6 +184,20 @@ struct Geometry {
 struct Region {
     int nb, arow0, brow0;
 };
+
+// On FP32 C tiles, FP16 / FP8 products whose operands are both stored in the product's precision
+// run through the DMA ring (lo_run); every other product expects its first chunk staged by its
+// predecessor.
+__device__ __forceinline__ bool is_ring(const Product &pr, const Geometry &G)
+{
+#ifdef GMP_EXP_OCC2   /* timing experiment only: no ring; such products are not computed */
+    return false;
+#else
+    return G.ring && (pr.q == Q16 || pr.q == Q8) && pr.a.p == pr.q && pr.b.p == pr.q;
+#endif
+}
+__device__ __forceinline__ bool wants_first_chunk(const Product &pr, const Geometry &G) { return pr.q >= 0 && !is_ring(pr, G); }
+
 
 __device__ __forceinline__ int chunk_elems(int q) { return kRowBytes >> (3 - q); }   // 16, 32, 64, 128
 
@@ -258,6 +271,22 @@ __device__ __forceinline__ int table_u8(const uint8_t *t, int64_t i)
     const uintptr_t a = (uintptr_t)(t + i);
     return (int)((*(ConstWord)(a & ~(uintptr_t)3) >> ((a & 3) * 8)) & 0xffu);
 }
+// The kernel's arguments, read where they are needed from the kernel-argument segment (constant
+// memory, scalar loads) instead of being held in scalar registers for the kernel's lifetime:
+// there are some forty of them and the chunk loops need the registers.  The pointer is made
+// opaque each time so that the reads are issued at the point of use.
+typedef const __attribute__((address_space(4))) GemmArgs *ArgsPtr;
+__device__ __forceinline__ ArgsPtr args()
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    uint64_t p = (uint64_t)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(p));
+    return (ArgsPtr)p;
+#else
+    return (ArgsPtr)0;
+#endif
+}
+
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ const char *uni(const char *p)
 {
@@ -267,13 +296,14 @@ __device__ __forceinline__ const char *uni(const char *p)
     return (const char *)(((uint64_t)hi << 32) | lo);
 }
 
-// Descriptor of one operand tile: `row0` is the first tile row this workgroup reads.
-__device__ __forceinline__ Operand open_operand(const PackedView &V, int tile, int q, int row0, const Geometry &G, int nb)
+// Descriptor of one operand tile from its table entries; `row0` is the first tile row this
+// workgroup reads.
+__device__ __forceinline__ Operand make_operand(const char *base, int p, int e, int q, int row0, const Geometry &G, int nb)
 {
     Operand o;
-    o.base = V.storage + table_u64(V.offset, tile);
-    o.p = table_u8(V.prec, tile);
-    o.e = table_i32(V.exp, tile);
+    o.base = base;
+    o.p = p;
+    o.e = e;
     const int shift = 3 - o.p;                                   // log2 of the element size
     o.bytes = (nb * nb) << shift;
     const int n_q = 2 << q;                                      // elements per 16-byte converted segment
@@ -283,19 +313,27 @@ __device__ __forceinline__ Operand open_operand(const PackedView &V, int tile, i
     return o;
 }
 
-// Load the descriptors of tile product L of this C tile (q = -1 past the end).
-__device__ __forceinline__ Product open_product(const GemmArgs &P, int I, int J, int tileC, int L, const Geometry &G, const Region &R)
+// Load the descriptors of tile product L of this C tile (q = -1 past the end).  The seven table
+// reads are independent and are all issued before the first of them is awaited.
+__device__ __forceinline__ Product open_product(int I, int J, int tileC, int L, const Geometry &G, const Region &R)
 {
+    const ArgsPtr K = args();
     Product pr;
     pr.q = -1;
-    if (L >= P.kt_eff) {
+    if (L >= K->kt_eff) {
         pr.a = Operand{};
         pr.b = Operand{};
         return pr;
     }
-    pr.q = table_u8(P.q, (int64_t)tileC * P.KT + L);
-    pr.a = open_operand(P.A, I * P.KT + L, pr.q, R.arow0, G, R.nb);
-    pr.b = open_operand(P.B, L * P.NT + J, pr.q, R.brow0, G, R.nb);
+    const int64_t ta = (int64_t)I * K->KT + L, tb = (int64_t)L * K->NT + J;
+    const int q = table_u8(K->q, (int64_t)tileC * K->KT + L);
+    const uint64_t offa = table_u64(K->A.offset, ta), offb = table_u64(K->B.offset, tb);
+    const int pa = table_u8(K->A.prec, ta), pb = table_u8(K->B.prec, tb);
+    const int ea = table_i32(K->A.exp, ta), eb = table_i32(K->B.exp, tb);
+    SCHED_FENCE();
+    pr.q = q;
+    pr.a = make_operand(K->A.storage + offa, pa, ea, q, R.arow0, G, R.nb);
+    pr.b = make_operand(K->B.storage + offb, pb, eb, q, R.brow0, G, R.nb);
     return pr;
 }
 
@@ -303,7 +341,6 @@ __device__ __forceinline__ Product open_product(const GemmArgs &P, int I, int J,
 // when it reaches its last chunk, which keeps the scalar registers of one product, not two,
 // live through the chunk loop.
 struct Walk {
-    const GemmArgs *P;
     int I, J, tileC;
 };
 
@@ -431,12 +468,12 @@ __device__ __forceinline__ void pipelined_chunk(Acc (&acc)[4][4], u32x2 (&fr)[2]
             mfma_group<Q>(acc, fr[m & 1], grp, (m == 0 && grp == 0) ? 1 : (m == 3 && grp == 3) ? 2 : 0);
             SCHED_FENCE();
             if (m == 0) {
-                if (!LAST || wants_first_chunk(pr)) load_pair(ra[grp], rb[grp], pr, nb, c, grp);
+                if (!LAST || wants_first_chunk(pr, G)) load_pair(ra[grp], rb[grp], pr, nb, c, grp);
             }
             if (m < 3) read_frag_slot(fr[(m + 1) & 1], fa, fb, m + 1, grp);
             if (m == 2) {
                 if constexpr (LAST) {
-                    if (wants_first_chunk(pr)) store_pair_any(ra[grp], rb[grp], pr, G, wst, grp);
+                    if (wants_first_chunk(pr, G)) store_pair_any(ra[grp], rb[grp], pr, G, wst, grp);
                 }
                 else store_pair<Q>(ra[grp], rb[grp], pr, G, wst, grp);
             }
@@ -501,7 +538,7 @@ __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], cons
     }
 #undef GMP_STEADY
     acc_fence(acc);
-    const Product next = open_product(*W.P, W.I, W.J, W.tileC, Lnext, G, R);
+    const Product next = open_product(W.I, W.J, W.tileC, Lnext, G, R);
     acc_fence(acc);
     pipelined_chunk<Q, true>(acc, fr, next, 0, lds, stage, F, G, R.nb);
     acc_fence(acc);
@@ -624,7 +661,11 @@ __device__ __forceinline__ void lo_read_one(u32x4 (&f)[16], const char *stage, c
     constexpr int kBlock = 16 * kRowBytes;
     const int op = r < 8 ? 1 : 0, t = (r & 7) >> 1, half = r & 1;
     const int o = op ? (half ? LG.fb1 : LG.fb0) : (half ? LG.fa1 : LG.fa0);
+#ifdef GMP_EXP_NOLOREAD   /* timing experiment only */
+    f[(op * 4 + t) * 2 + half] = u32x4{(uint32_t)o, 1u, 2u, (uint32_t)(uintptr_t)stage};
+#else
     f[(op * 4 + t) * 2 + half] = *(const u32x4 *)(stage + o + t * kBlock);
+#endif
 }
 __device__ __forceinline__ void lo_read_slot(u32x4 (&f)[16], const char *stage, const LoGeom &LG, int slot)
 {
@@ -638,7 +679,7 @@ __device__ __forceinline__ void lo_read_slot(u32x4 (&f)[16], const char *stage, 
 // of the next chunk's fragments from the ring stage `next` into the other set, then the eight
 // DMA instructions that request a later chunk of product `pr` into the stage at `dst`.
 // The MFMAs are asm in place, see mfma_group.
-template <int Q, int PAR>
+template <int Q, int PAR, bool FIRST>
 __device__ __forceinline__ void lo_chunk(f4 (&acc)[4][4], u32x4 (&fr)[2][16], const char *next, const LoGeom &LG,
                                          const Product &pr, int soff0, int rows8_bytes, unsigned dst)
 {
@@ -647,19 +688,32 @@ __device__ __forceinline__ void lo_chunk(f4 (&acc)[4][4], u32x4 (&fr)[2][16], co
     for (int m = 0; m < kMfmas; ++m) {
         const int g = m >> 2, nt = m & 3, mt = g & 3, kk = g >> 2;
         const bool first = m == 0, last = m == kMfmas - 1;
+        // FIRST: the product's first chunk starts its accumulators from zero (C operand 0)
+        const bool zero = FIRST && (Q == Q8 || m < 16);
         if constexpr (Q == Q16) {
             const u32x4 x = fr[PAR][mt * 2 + kk], y = fr[PAR][(4 + nt) * 2 + kk];
-            if (first) asm volatile("s_nop 3\n\tv_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
-            else if (last) asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0\n\ts_nop 11" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
-            else asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+            if (zero) {
+                if (first) asm volatile("s_nop 3\n\tv_mfma_f32_16x16x32_f16 %0, %1, %2, 0" : "=a"(acc[mt][nt]) : "v"(x), "v"(y));
+                else asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, 0" : "=a"(acc[mt][nt]) : "v"(x), "v"(y));
+            } else {
+                if (first) asm volatile("s_nop 3\n\tv_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+                else if (last) asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0\n\ts_nop 11" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+                else asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+            }
         } else {
             const u32x4 a0 = fr[PAR][mt * 2], a1 = fr[PAR][mt * 2 + 1], b0 = fr[PAR][(4 + nt) * 2], b1 = fr[PAR][(4 + nt) * 2 + 1];
             const i8v x = {(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, (int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w};
             const i8v y = {(int)b0.x, (int)b0.y, (int)b0.z, (int)b0.w, (int)b1.x, (int)b1.y, (int)b1.z, (int)b1.w};
             // 16x16x128, both operands e4m3 (format selectors 0), no block scaling
-            if (first) asm volatile("s_nop 3\n\tv_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
-            else if (last) asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0\n\ts_nop 11" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
-            else asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+            if (zero) {
+                if (first) asm volatile("s_nop 3\n\tv_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, 0" : "=a"(acc[mt][nt]) : "v"(x), "v"(y));
+                else if (last) asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, 0\n\ts_nop 11" : "=a"(acc[mt][nt]) : "v"(x), "v"(y));
+                else asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, 0" : "=a"(acc[mt][nt]) : "v"(x), "v"(y));
+            } else {
+                if (first) asm volatile("s_nop 3\n\tv_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+                else if (last) asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0\n\ts_nop 11" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+                else asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+            }
         }
         SCHED_FENCE();
         if constexpr (Q == Q16) {
@@ -689,13 +743,8 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
 {
     const Geometry G = fresh(G0);
     const LoGeom LG = lo_geometry(G);
-    const GemmArgs &P = *W.P;
     const int wave = G.tid >> 6;
-    f4 t[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
+    f4 t[4][4];               // set by the first chunk of every product
 
     // staging cursor
     LoCursor pf;
@@ -706,10 +755,11 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
     lo_operand(pf.pr.a, pf.pr.q, R.arow0, R.nb, LG);
     lo_operand(pf.pr.b, pf.pr.q, R.brow0, R.nb, LG);
     bool pf_valid = true;
-    Product after;            // first product that does not belong to the run
-    after.q = -1;
-    after.a = Operand{};
-    after.b = Operand{};
+    // Descriptors of the product after the one being staged: opened one product ahead so that the
+    // latency of the table reads is not paid when the cursor moves on.  When the run ends this is
+    // the first product that does not belong to it.
+    Product nx = open_product(W.I, W.J, W.tileC, L + 1, G, R);
+    bool need_open = false;
     int staged = 0;           // chunks requested so far
     int st_req = 0;           // ring stage (byte offset) of the next request
     const int wave_off = uni(wave * 4096);
@@ -722,18 +772,21 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
     // its 16 bytes of a stage nobody reads any more).
     auto req_done = [&]() __attribute__((always_inline)) {
         st_req = st_req + kLoStage == kLoLdsBytes ? 0 : st_req + kLoStage;
+        if (need_open) {                            // second step of a product: look one product ahead
+            nx = open_product(W.I, W.J, W.tileC, pf.L + 1, G, R);
+            need_open = false;
+        }
         if (!pf_valid) return;
         ++staged;
         if (++pf.c == pf.n) {                       // next product: does it continue the run?
             ++pf.L;
-            Product nx = open_product(P, W.I, W.J, W.tileC, pf.L, G, R);
-            if (is_ring(nx)) {
-                lo_operand(nx.a, nx.q, R.arow0, R.nb, LG);
-                lo_operand(nx.b, nx.q, R.brow0, R.nb, LG);
+            if (is_ring(nx, G)) {
                 pf.pr = nx;
+                lo_operand(pf.pr.a, nx.q, R.arow0, R.nb, LG);
+                lo_operand(pf.pr.b, nx.q, R.brow0, R.nb, LG);
                 pf.n = R.nb / chunk_elems(nx.q);
+                need_open = true;
             } else {
-                after = nx;
                 pf_valid = false;
                 pf.pr.a.bytes = 0;
                 pf.pr.b.bytes = 0;
@@ -768,43 +821,51 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
     // occupied (every wave finished reading it before the barrier that ended the previous step).
     // Then wait until chunk done + 2 is complete in LDS for every wave: everything but the three
     // requests after it.
-#define GMP_LO_STEP(QQ, PAR)                                                         \
+#ifdef GMP_EXP_NOLOBAR   /* timing experiment only */
+#define GMP_LO_BARRIER() do {} while (0)
+#else
+#define GMP_LO_BARRIER() __syncthreads()
+#endif
+#define GMP_LO_STEP(QQ, PAR, FIRST)                                                         \
     do {                                                                             \
-        lo_chunk<QQ, PAR>(t, fr, lds + st_next, LG, GMP_LO_REQ_ARGS);                \
+        lo_chunk<QQ, PAR, FIRST>(t, fr, lds + st_next, LG, GMP_LO_REQ_ARGS);                \
         req_done();                                                                  \
         ++done;                                                                      \
         st_next = st_next + kLoStage == kLoLdsBytes ? 0 : st_next + kLoStage;        \
         lo_wait_dma(8 * (kLoStages - 2));                                            \
-        __syncthreads();                                                             \
+        GMP_LO_BARRIER();                                                            \
     } while (0)
     while (done < staged) {
         const int cn = R.nb / chunk_elems(cq);
         // precision and exponent sum of the product after this one, fetched early
-        const bool more = cL + 1 < P.kt_eff;
-        const int nq = more ? table_u8(P.q, (int64_t)W.tileC * P.KT + cL + 1) : -1;
-        const int nesum = more ? table_i32(P.A.exp, W.I * P.KT + cL + 1) + table_i32(P.B.exp, (cL + 1) * P.NT + W.J) : 0;
+        const ArgsPtr K = args();
+        const bool more = cL + 1 < K->kt_eff;
+        const int nq = more ? table_u8(K->q, (int64_t)W.tileC * K->KT + cL + 1) : -1;
+        const int nesum = more ? table_i32(K->A.exp, W.I * K->KT + cL + 1) + table_i32(K->B.exp, (cL + 1) * K->NT + W.J) : 0;
         if (cq == Q16) {                           // 64 elements per chunk: always an even count
-            for (int cc = 0; cc < cn; cc += 2) {
-                GMP_LO_STEP(Q16, 0);
-                GMP_LO_STEP(Q16, 1);
+            GMP_LO_STEP(Q16, 0, true);
+            GMP_LO_STEP(Q16, 1, false);
+            for (int cc = 2; cc < cn; cc += 2) {
+                GMP_LO_STEP(Q16, 0, false);
+                GMP_LO_STEP(Q16, 1, false);
             }
         } else {
-            for (int cc = 0; cc + 2 <= cn; cc += 2) {
-                GMP_LO_STEP(Q8, 0);
-                GMP_LO_STEP(Q8, 1);
+            GMP_LO_STEP(Q8, 0, true);
+            if (cn > 1) {
+                GMP_LO_STEP(Q8, 1, false);
+                for (int cc = 2; cc + 2 <= cn; cc += 2) {
+                    GMP_LO_STEP(Q8, 0, false);
+                    GMP_LO_STEP(Q8, 1, false);
+                }
+                if (cn & 1) GMP_LO_STEP(Q8, 0, false);
             }
             if (cn & 1) {                          // odd count: bring the fragments back to set 0
-                GMP_LO_STEP(Q8, 0);
 #pragma unroll
                 for (int i = 0; i < 16; ++i) fr[0][i] = fr[1][i];
             }
         }
         // the product is complete: it joins the running sum
         fold(s, t, cesum);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
         ++cL;
         cq = nq;
         cesum = nesum;
@@ -815,21 +876,26 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
     __syncthreads();
 
     L = cL;
-    cur = after;
-    if (wants_first_chunk(after)) {                // hand over to the two-stage layout
+    cur = nx;
+    if (wants_first_chunk(nx, G)) {                // hand over to the two-stage layout
         Raw xa[4], xb[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) load_pair(xa[j], xb[j], after, R.nb, 0, j);
+        for (int j = 0; j < 4; ++j) load_pair(xa[j], xb[j], nx, R.nb, 0, j);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) store_pair_any(xa[j], xb[j], after, G, lds, j);
+        for (int j = 0; j < 4; ++j) store_pair_any(xa[j], xb[j], nx, G, lds, j);
         __syncthreads();
     }
 }
 
-// ---- FP16 products with one FP8 operand: two-stage loop with the conversion in registers ----
-__device__ __forceinline__ void mma_fp16_padded(f4 (&acc)[4][4], const char *lds, int stage, const Geometry &G)
+// ---- FP16 / FP8 products outside the ring: two-stage loop, conversion in registers ----------
+// Used for FP16 products with an FP8 operand and for every FP16 / FP8 product of an FP64 C tile
+// (whose kernel has no registers to spare for the ring's fragment sets).  One chunk = 2 k-steps
+// of 16x16x32 FP16, or one 16x16x128 FP8 step; the loads of the following chunk are in flight
+// while the MFMAs of a chunk run.
+template <int Q>
+__device__ __forceinline__ void mma_padded(f4 (&acc)[4][4], const char *lds, int stage, const Geometry &G)
 {
-    const FragBase F = frag_base<Q16>(lds + stage * kStage, G);
+    const FragBase F = frag_base<Q>(lds + stage * kStage, G);
     constexpr int kBlock = 16 * kRowStride;
     u32x2 a[4][4], b[4][4];
 #pragma unroll
@@ -839,25 +905,44 @@ __device__ __forceinline__ void mma_fp16_padded(f4 (&acc)[4][4], const char *lds
             a[t][w] = lds_load8(F.a + t * kBlock + 8 * w);
             b[t][w] = lds_load8(F.b + t * kBlock + 8 * w);
         }
+    if constexpr (Q == Q16) {
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk)
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) {
+                    const h8 x = __builtin_bit_cast(h8, u32x4{a[mt][2 * kk].x, a[mt][2 * kk].y, a[mt][2 * kk + 1].x, a[mt][2 * kk + 1].y});
+                    const h8 y = __builtin_bit_cast(h8, u32x4{b[nt][2 * kk].x, b[nt][2 * kk].y, b[nt][2 * kk + 1].x, b[nt][2 * kk + 1].y});
+                    if (kk == 0 && mt == 0 && nt == 0)
+                        asm volatile("s_nop 3\n\tv_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+                    else if (kk == 1 && mt == 3 && nt == 3)
+                        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0\n\ts_nop 11" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+                    else
+                        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+                }
+    } else {
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt) {
-                const h8 x = __builtin_bit_cast(h8, u32x4{a[mt][2 * kk].x, a[mt][2 * kk].y, a[mt][2 * kk + 1].x, a[mt][2 * kk + 1].y});
-                const h8 y = __builtin_bit_cast(h8, u32x4{b[nt][2 * kk].x, b[nt][2 * kk].y, b[nt][2 * kk + 1].x, b[nt][2 * kk + 1].y});
-                if (kk == 0 && mt == 0 && nt == 0)
-                    asm volatile("s_nop 3\n\tv_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
-                else if (kk == 1 && mt == 3 && nt == 3)
-                    asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0\n\ts_nop 11" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+                const i8v x = {(int)a[mt][0].x, (int)a[mt][0].y, (int)a[mt][1].x, (int)a[mt][1].y,
+                               (int)a[mt][2].x, (int)a[mt][2].y, (int)a[mt][3].x, (int)a[mt][3].y};
+                const i8v y = {(int)b[nt][0].x, (int)b[nt][0].y, (int)b[nt][1].x, (int)b[nt][1].y,
+                               (int)b[nt][2].x, (int)b[nt][2].y, (int)b[nt][3].x, (int)b[nt][3].y};
+                // 16x16x128, both operands e4m3 (format selectors 0), no block scaling
+                if (mt == 0 && nt == 0)
+                    asm volatile("s_nop 3\n\tv_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+                else if (mt == 3 && nt == 3)
+                    asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0\n\ts_nop 11" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
                 else
-                    asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+                    asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
             }
+    }
 }
 
-template <int PA, int PB>
-__device__ __forceinline__ void mixed16_chunks(f4 (&acc)[4][4], const Product &cur, int n, char *lds, int &stage, const Geometry &G, int nb)
+template <int Q, int PA, int PB>
+__device__ __forceinline__ void simple_chunks(f4 (&acc)[4][4], const Product &cur, int n, char *lds, int &stage, const Geometry &G, int nb)
 {
     Raw ra[4], rb[4];
     Product cp = cur;
@@ -866,9 +951,9 @@ __device__ __forceinline__ void mixed16_chunks(f4 (&acc)[4][4], const Product &c
     for (int c = 1; c < n; ++c) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) load_pair(ra[j], rb[j], cp, nb, c, j);
-        mma_fp16_padded(acc, lds, stage, G);
+        mma_padded<Q>(acc, lds, stage, G);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) store_pair<Q16>(ra[j], rb[j], cp, G, lds + (stage ^ 1) * kStage, j);
+        for (int j = 0; j < 4; ++j) store_pair<Q>(ra[j], rb[j], cp, G, lds + (stage ^ 1) * kStage, j);
         __syncthreads();
         stage ^= 1;
     }
@@ -876,21 +961,28 @@ __device__ __forceinline__ void mixed16_chunks(f4 (&acc)[4][4], const Product &c
 
 // On entry LDS stage `stage` holds the product's first chunk; on exit it holds the first chunk
 // of the next product if that one wants it.
-__device__ __forceinline__ Product product_loop_mixed16(f4 (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
-                                                        const Geometry &G0, const Region &R)
+template <int Q>
+__device__ __forceinline__ Product product_loop_simple(f4 (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
+                                                       const Geometry &G0, const Region &R)
 {
     const Geometry G = fresh(G0);
-    const int n = R.nb / chunk_elems(Q16);
-    if (cur.a.p == Q16) mixed16_chunks<Q16, Q8>(acc, cur, n, lds, stage, G, R.nb);
-    else mixed16_chunks<Q8, Q16>(acc, cur, n, lds, stage, G, R.nb);
+    const int n = R.nb / chunk_elems(Q);
+    if constexpr (Q == Q8) {
+        simple_chunks<Q8, Q8, Q8>(acc, cur, n, lds, stage, G, R.nb);
+    } else {
+        if (cur.a.p == Q16 && cur.b.p == Q16) simple_chunks<Q16, Q16, Q16>(acc, cur, n, lds, stage, G, R.nb);
+        else if (cur.a.p == Q16) simple_chunks<Q16, Q16, Q8>(acc, cur, n, lds, stage, G, R.nb);
+        else if (cur.b.p == Q16) simple_chunks<Q16, Q8, Q16>(acc, cur, n, lds, stage, G, R.nb);
+        else simple_chunks<Q16, Q8, Q8>(acc, cur, n, lds, stage, G, R.nb);
+    }
     Raw ra[4], rb[4];
-    const Product next = open_product(*W.P, W.I, W.J, W.tileC, Lnext, G, R);
-    const bool give = wants_first_chunk(next);
+    const Product next = open_product(W.I, W.J, W.tileC, Lnext, G, R);
+    const bool give = wants_first_chunk(next, G);
     if (give) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) load_pair(ra[j], rb[j], next, R.nb, 0, j);
     }
-    mma_fp16_padded(acc, lds, stage, G);
+    mma_padded<Q>(acc, lds, stage, G);
     acc_fence(acc);
     if (give) {
 #pragma unroll
@@ -905,13 +997,14 @@ __device__ __forceinline__ Product product_loop_mixed16(f4 (&acc)[4][4], const P
 template <typename AccS>
 __device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int esum)
 {
+    constexpr bool kDouble = std::is_same<AccS, d4>::value;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                if constexpr (std::is_same<AccS, d4>::value) s[i][j][v] = s[i][j][v] + ldexp((double)t[i][j][v], esum);
+                if constexpr (kDouble) s[i][j][v] = s[i][j][v] + ldexp((double)t[i][j][v], esum);
                 else s[i][j][v] = s[i][j][v] + ldexpf(t[i][j][v], esum);
             }
         }
@@ -921,7 +1014,7 @@ __device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int e
 //             in the FP32 accumulator t first.
 // T = float : FP32 C tiles; FP32 products continue s, FP16 / FP8 products go through t.
 template <typename T>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(GMP_WAVES_PER_EU, GMP_WAVES_PER_EU)))
 void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 {
     using AccS = typename std::conditional<std::is_same<T, double>::value, d4, f4>::type;
@@ -929,6 +1022,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     Geometry G;
+    G.ring = QT == Q32;
     G.tid = threadIdx.x;
     G.lane = G.tid & 63;
     G.li = G.lane & 15;
@@ -942,9 +1036,10 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 
     const WorkItem it = items[blockIdx.x];
     const int tileC = uni((int)it.tile);
-    const int I = tileC / P.NT, J = tileC % P.NT;
+    const int NT = args()->NT;
+    const int I = tileC / NT, J = tileC % NT;
     Region R;
-    R.nb = P.nb;
+    R.nb = args()->nb;
     R.arow0 = uni((int)it.mi) * kMacro;
     R.brow0 = uni((int)it.mj) * kMacro;
 
@@ -955,8 +1050,8 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
         for (int j = 0; j < 4; ++j) s[i][j] = AccS{0, 0, 0, 0};
 
     int stage = 0;
-    Product cur = open_product(P, I, J, tileC, 0, G, R);
-    if (wants_first_chunk(cur)) {
+    Product cur = open_product(I, J, tileC, 0, G, R);
+    if (wants_first_chunk(cur, G)) {
         Raw ra[4], rb[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) load_pair(ra[j], rb[j], cur, R.nb, 0, j);
@@ -966,27 +1061,28 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     __syncthreads();
 
     Walk W;
-    W.P = &P;
     W.I = I;
     W.J = J;
     W.tileC = tileC;
     int L = 0;
-    while (L < P.kt_eff) {
+    const int kt_eff = args()->kt_eff;
+    while (L < kt_eff) {
         const int q = cur.q;
-        if (is_ring(cur)) {
+        if (is_ring(cur, G)) {
             lo_run(s, cur, L, W, lds, G, R);       // all consecutive products of that kind
             stage = 0;
             continue;
         }
         Product next;
-        if (q == Q16) {                            // FP16 product with one FP8 operand
+        if (q == Q16 || q == Q8) {                 // FP16 / FP8 product outside the ring
             f4 t[4][4];
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
             const int esum = cur.a.e + cur.b.e;
-            next = product_loop_mixed16(t, cur, W, L + 1, lds, stage, G, R);
+            if (q == Q16) next = product_loop_simple<Q16>(t, cur, W, L + 1, lds, stage, G, R);
+            else next = product_loop_simple<Q8>(t, cur, W, L + 1, lds, stage, G, R);
             fold(s, t, esum);
             cur = next;
             ++L;
@@ -1015,9 +1111,10 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 
     // Epilogue: v = alpha*s (+ beta*c0): two rounded products and one rounded sum in T.
     typedef __attribute__((address_space(1))) T *GlobalT;
-    GlobalT ctile = (GlobalT)(uintptr_t)(P.C.storage + P.C.offset[tileC]);
-    const T alpha = (T)P.alpha, beta = (T)P.beta;
-    const bool use_c = P.beta != 0.0;
+    const ArgsPtr K = args();
+    GlobalT ctile = (GlobalT)(uintptr_t)(K->C.storage + table_u64(K->C.offset, tileC));
+    const T alpha = (T)K->alpha, beta = (T)K->beta;
+    const bool use_c = K->beta != 0.0;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
@@ -1026,7 +1123,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
             for (int v = 0; v < 4; ++v) {
                 const int row = R.arow0 + G.wm * 64 + mt * 16 + 4 * G.g + v;
                 const int col = R.brow0 + G.wn * 64 + nt * 16 + G.li;
-                GlobalT p = ctile + (int64_t)row * P.nb + col;
+                GlobalT p = ctile + (int64_t)row * R.nb + col;
                 T val = alpha * (T)s[mt][nt][v];
                 if (use_c) { const T bc = beta * *p; val = val + bc; }
                 *p = val;
