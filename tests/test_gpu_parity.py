@@ -286,3 +286,19 @@ def test_config_rect32k_sampled_tiles():
     st = d.ctx.get_stats()
     _say("  products by precision:", st["products"])
     assert st["products"][0] == 0 and st["products"][3] > 0
+
+
+def test_config_cov64k_sampled_blocks():
+    """The largest configuration (65536^3, 2048-wide tiles): 16 rows of each of 66 C tiles."""
+    w = W.CONFIGS["cov64k"]()
+    tiles = sorted(set(w.sample_tiles(64)) | {(0, 0), (w.MT // 2, w.NT // 2 + 1)})
+    rng = np.random.default_rng(11)
+    jobs = []
+    for (I, J) in tiles:
+        r0 = int(rng.integers(0, w.nb - 16))
+        jobs.append([I, J, r0, r0 + 16, 0, w.nb])
+    jobs = np.array(jobs, dtype=np.int32)
+    d, side, _, _ = _run_and_compare(w, jobs=jobs, check_storage_tiles=2)
+    st = d.ctx.get_stats()
+    _say("  products by precision:", st["products"])
+    assert st["work_items"] == (w.M // 128) * (w.N // 128)
