@@ -337,9 +337,7 @@ __device__ __forceinline__ Product open_product(int I, int J, int tileC, int L, 
     return pr;
 }
 
-// What a product loop needs in order to open the following tile product itself; it does so only
-// when it reaches its last chunk, which keeps the scalar registers of one product, not two,
-// live through the chunk loop.
+// What a product loop needs in order to open the following tile product itself.
 struct Walk {
     int I, J, tileC;
 };
@@ -527,6 +525,8 @@ __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], cons
 #pragma unroll
     for (int slot = 0; slot < 4; ++slot) read_frag_slot(fr[0], F.a + stage * kStage, F.b + stage * kStage, 0, slot);
     const int n = R.nb / (kRowBytes >> (3 - Q));
+    // the following product's descriptors: read now, needed only at this product's last chunk
+    const Product next = open_product(W.I, W.J, W.tileC, Lnext, G, R);
     acc_fence(acc);
 #define GMP_STEADY(PA, PB) case (PA) * 4 + (PB): steady_chunks<Q, PA, PB>(acc, fr, cur, n, lds, stage, F, G, R.nb); break;
     switch (cur.a.p * 4 + cur.b.p) {
@@ -537,8 +537,6 @@ __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], cons
     default: break;
     }
 #undef GMP_STEADY
-    acc_fence(acc);
-    const Product next = open_product(W.I, W.J, W.tileC, Lnext, G, R);
     acc_fence(acc);
     pipelined_chunk<Q, true>(acc, fr, next, 0, lds, stage, F, G, R.nb);
     acc_fence(acc);
