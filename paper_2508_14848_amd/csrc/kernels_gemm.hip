@@ -10,9 +10,11 @@
 // 16 FP64 / 32 FP32 / 64 FP16 / 128 FP8 values):
 //   global (stored precision) -> registers -> convert to q ("receiver-side conversion": exact
 //   up-casts with the tile's 2^e applied, or the one down-cast FP64 -> FP32) -> LDS (rows of
-//   128 B + 16 B pad) -> 16x16 MFMA fragments.  The loads of the next chunk are issued before
+//   128 B + 8 B pad) -> 16x16 MFMA fragments.  The loads of the next chunk are issued before
 //   the MFMAs of the current one and land in the other LDS stage afterwards; the chunk stream
 //   runs across tile-product boundaries so the pipeline never drains inside a C region.
+// FP16 / FP8 products of FP32 C tiles whose operands need no conversion skip the registers:
+//   global -> LDS by buffer-load-to-LDS into a ring of five unpadded, swizzled stages.
 //
 // Fragment convention.  Packed A tiles are row-major and packed B tiles are stored transposed,
 // so both operands have the reduction index contiguous.  Lane (i = lane%16, g = lane/16) reads
@@ -49,13 +51,7 @@ constexpr int kLoOperand = kMacro * kRowBytes;       // 16384 B
 constexpr int kLoStage = 2 * kLoOperand;             // A then B: 32768 B
 constexpr int kLoStages = 5;                         // chunk i lives in stage i % 5, requested 4 chunks ahead
 constexpr int kLoLdsBytes = kLoStages * kLoStage;    // 163840 B: all of the LDS of a CU
-#ifdef GMP_EXP_OCC2
-constexpr int kLdsBytes = kHiLdsBytes;
-#define GMP_WAVES_PER_EU 2
-#else
 constexpr int kLdsBytes = kLoLdsBytes > kHiLdsBytes ? kLoLdsBytes : kHiLdsBytes;
-#define GMP_WAVES_PER_EU 1
-#endif
 constexpr int kThreads = 256;
 
 enum { Q64 = GEMM_MP_FP64, Q32 = GEMM_MP_FP32, Q16 = GEMM_MP_FP16, Q8 = GEMM_MP_FP8_E4M3 };
@@ -90,14 +86,9 @@ struct Product {
 // soff: byte offset of (chunk, row block) in the tile; down: FP64 tile feeding an FP32 product.
 __device__ __forceinline__ void load_seg(Raw &r, const Operand &o, int soff, bool down)
 {
-#ifdef GMP_EXP_NOLOAD   /* timing experiment only: no global traffic, operands are garbage */
-    r.lo = u32x4{(uint32_t)(o.voff + soff), 1u, 2u, 3u};
-    r.hi = r.lo;
-#else
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)o.base, 0, o.bytes, 0x00020000);
     r.lo = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o.voff, soff, 0);
     if (down) r.hi = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o.voff + 16, soff, 0);
-#endif
 }
 
 __device__ __forceinline__ float half_lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (unsigned short)(w & 0xffffu)); }
@@ -183,6 +174,7 @@ struct Geometry {
 
 struct Region {
     int nb, arow0, brow0;
+    int kt_eff;                     // number of reduction tiles to process (0 when alpha == 0)
 };
 
 // On FP32 C tiles, FP16 / FP8 products whose operands are both stored in the product's precision
@@ -190,11 +182,7 @@ struct Region {
 // predecessor.
 __device__ __forceinline__ bool is_ring(const Product &pr, const Geometry &G)
 {
-#ifdef GMP_EXP_OCC2   /* timing experiment only: no ring; such products are not computed */
-    return false;
-#else
     return G.ring && (pr.q == Q16 || pr.q == Q8) && pr.a.p == pr.q && pr.b.p == pr.q;
-#endif
 }
 __device__ __forceinline__ bool wants_first_chunk(const Product &pr, const Geometry &G) { return pr.q >= 0 && !is_ring(pr, G); }
 
@@ -227,10 +215,6 @@ __device__ __forceinline__ void load_pair(Raw &ra, Raw &rb, const Product &pr, i
 
 __device__ __forceinline__ void lds_store16(char *p, u32x4 v)     // rows are only 8-byte aligned
 {
-#ifdef GMP_EXP_NOLDSWRITE   /* timing experiment only */
-    if (v.x == 0x12345u) *(u32x2 *)p = u32x2{v.x, v.y};
-    return;
-#endif
     *(u32x2 *)p = u32x2{v.x, v.y};
     *(u32x2 *)(p + 8) = u32x2{v.z, v.w};
 }
@@ -313,27 +297,32 @@ __device__ __forceinline__ Operand make_operand(const char *base, int p, int e, 
     return o;
 }
 
-// Load the descriptors of tile product L of this C tile (q = -1 past the end).  The seven table
-// reads are independent and are all issued before the first of them is awaited.
+// Load the descriptors of tile product L of this C tile (q = -1 past the end).  Two rounds of
+// scalar loads, each issued as one batch: the table pointers and tile counts from the kernel
+// arguments, then the seven table entries.
 __device__ __forceinline__ Product open_product(int I, int J, int tileC, int L, const Geometry &G, const Region &R)
 {
-    const ArgsPtr K = args();
     Product pr;
     pr.q = -1;
-    if (L >= K->kt_eff) {
-        pr.a = Operand{};
-        pr.b = Operand{};
-        return pr;
-    }
-    const int64_t ta = (int64_t)I * K->KT + L, tb = (int64_t)L * K->NT + J;
-    const int q = table_u8(K->q, (int64_t)tileC * K->KT + L);
-    const uint64_t offa = table_u64(K->A.offset, ta), offb = table_u64(K->B.offset, tb);
-    const int pa = table_u8(K->A.prec, ta), pb = table_u8(K->B.prec, tb);
-    const int ea = table_i32(K->A.exp, ta), eb = table_i32(K->B.exp, tb);
+    pr.a = Operand{};
+    pr.b = Operand{};
+    if (L >= R.kt_eff) return pr;
+    const ArgsPtr K = args();
+    const uint8_t *tq = K->q, *tpa = K->A.prec, *tpb = K->B.prec;
+    const uint64_t *toa = K->A.offset, *tob = K->B.offset;
+    const int32_t *tea = K->A.exp, *teb = K->B.exp;
+    const char *sa = K->A.storage, *sb = K->B.storage;
+    const int KT = K->KT, NT = K->NT;
+    SCHED_FENCE();
+    const int64_t ta = (int64_t)I * KT + L, tb = (int64_t)L * NT + J;
+    const int q = table_u8(tq, (int64_t)tileC * KT + L);
+    const uint64_t offa = table_u64(toa, ta), offb = table_u64(tob, tb);
+    const int pa = table_u8(tpa, ta), pb = table_u8(tpb, tb);
+    const int ea = table_i32(tea, ta), eb = table_i32(teb, tb);
     SCHED_FENCE();
     pr.q = q;
-    pr.a = make_operand(K->A.storage + offa, pa, ea, q, R.arow0, G, R.nb);
-    pr.b = make_operand(K->B.storage + offb, pb, eb, q, R.brow0, G, R.nb);
+    pr.a = make_operand(sa + offa, pa, ea, q, R.arow0, G, R.nb);
+    pr.b = make_operand(sb + offb, pb, eb, q, R.brow0, G, R.nb);
     return pr;
 }
 
@@ -358,11 +347,7 @@ __device__ __forceinline__ FragBase frag_base(const char *lds, const Geometry &G
     f.b = lds + kOperandStage + (G.wn * 64 + G.li) * kRowStride + G.g * 32;
     return f;
 }
-#ifdef GMP_EXP_NOLDSREAD   /* timing experiment only */
-__device__ __forceinline__ u32x2 lds_load8(const char *p) { return u32x2{(uint32_t)(uintptr_t)p, 7u}; }
-#else
 __device__ __forceinline__ u32x2 lds_load8(const char *p) { return *(const u32x2 *)p; }
-#endif
 
 // ---- FP64 / FP32 products: software-pipelined chunk loop -----------------------------------
 // A chunk is consumed in four macro-steps of 8 bytes of reduction index per lane: one FP64
@@ -424,17 +409,6 @@ __device__ __forceinline__ void acc_fence(Acc (&acc)[4][4])
     }
 }
 
-// Lighter form before a run of asm MFMAs: any register copy or zeroing the compiler still owes
-// the accumulators is forced in front of it, and eight cycles pass before the first MFMA reads.
-__device__ __forceinline__ void acc_settle(f4 (&acc)[4][4])
-{
-    asm volatile("s_nop 7"
-                 : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]),
-                   "+a"(acc[1][0]), "+a"(acc[1][1]), "+a"(acc[1][2]), "+a"(acc[1][3]),
-                   "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),
-                   "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3]));
-}
-
 // Order in which the eight fragments of a macro-step are fetched, two per slot: the B fragments
 // first, so that A block 0 (needed first) is never the last to arrive.
 __device__ __forceinline__ void read_frag_slot(u32x2 (&fr)[8], const char *fa, const char *fb, int m, int slot)
@@ -476,9 +450,7 @@ __device__ __forceinline__ void pipelined_chunk(Acc (&acc)[4][4], u32x2 (&fr)[2]
                 else store_pair<Q>(ra[grp], rb[grp], pr, G, wst, grp);
             }
             if (m == 3) {
-#ifndef GMP_EXP_NOBARRIER
                 if (grp == 0) __syncthreads();
-#endif
                 if constexpr (!LAST) {
                     // first fragments of the next chunk: B0 B1 B2 | B3 A0 A1 | A2 A3
                     constexpr int kBlock = 16 * kRowStride;
@@ -577,29 +549,6 @@ __device__ __forceinline__ LoGeom lo_geometry(const Geometry &G)
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-// Four buffer-load-to-LDS instructions: 32 rows x 128 bytes of one operand chunk per wave.
-// Lane l of instruction j writes LDS bytes [dst + 1024 j + 16 l, +16), i.e. row 8 j + l/8,
-// slot l%8, and fetches the segment that belongs there.  The loads are asm because the
-// compiler, not knowing which stage a later LDS read touches, would wait for all of them
-// before every read; completion is awaited explicitly (lo_wait_dma) before the barrier that
-// publishes the stage.  They write no register, so nothing the compiler allocates depends on
-// their completion.
-__device__ __forceinline__ void lo_dma(const Operand &o, int soff, int rows8_bytes, unsigned dst)
-{
-    const uint64_t b = (uint64_t)o.base;
-    const i32x4 rsrc = {(int)(uint32_t)b, (int)((uint32_t)(b >> 32) & 0xffffu), o.bytes, 0x00020000};
-#if defined(__HIP_DEVICE_COMPILE__) && !defined(GMP_EXP_NODMA)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                     :
-                     : "s"(dst + 1024u * j), "v"(o.voff), "s"(rsrc), "s"(__builtin_amdgcn_readfirstlane(soff + j * rows8_bytes))
-                     : "memory", "m0");
-#else
-    (void)rsrc; (void)soff; (void)rows8_bytes; (void)dst;
-#endif
-}
-
 // Wait until at most `newer` vector-memory operations are outstanding.  Loads complete in
 // order, so this guarantees the ones issued before the newest `newer` have landed; operations
 // the compiler issued on its own in between only make the wait stricter.
@@ -632,22 +581,27 @@ __device__ __forceinline__ void lo_operand(Operand &o, int q, int row0, int nb, 
     }
 }
 
-// One buffer-load-to-LDS instruction of a chunk request (see lo_dma): k = 0..3 are the four
-// row blocks of the A chunk, k = 4..7 those of the B chunk.
+// One buffer-load-to-LDS instruction of a chunk request: k = 0..3 are the four 8-row blocks of
+// this wave's 32 rows of the A chunk, k = 4..7 those of the B chunk.  Lane l of instruction j
+// writes LDS bytes [dst + 1024 j + 16 l, +16), i.e. row 8 j + l/8, slot l%8, and fetches the
+// segment that belongs there.  The loads are asm because the compiler, not knowing which stage
+// a later LDS read touches, would wait for all of them before every read; completion is awaited
+// explicitly (lo_wait_dma) before the barrier that publishes the stage.  They write no
+// register, so nothing the compiler allocates depends on their completion.
 __device__ __forceinline__ void lo_dma_one(const Product &pr, int soff0, int rows8_bytes, unsigned dst, int k)
 {
     const Operand &o = k < 4 ? pr.a : pr.b;
     const int j = k & 3;
     const uint64_t b = (uint64_t)o.base;
     const i32x4 rsrc = {(int)(uint32_t)b, (int)((uint32_t)(b >> 32) & 0xffffu), o.bytes, 0x00020000};
-#if defined(__HIP_DEVICE_COMPILE__) && !defined(GMP_EXP_NODMA)
+#if defined(__HIP_DEVICE_COMPILE__)
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(dst + (k < 4 ? 0u : (unsigned)kLoOperand) + 1024u * j), "v"(o.voff), "s"(rsrc),
                    "s"(__builtin_amdgcn_readfirstlane(soff0 + j * rows8_bytes))
                  : "memory", "m0");
 #else
-    (void)rsrc; (void)soff0; (void)rows8_bytes; (void)dst;
+    (void)rsrc; (void)soff0; (void)rows8_bytes; (void)dst; (void)j;
 #endif
 }
 
@@ -659,11 +613,7 @@ __device__ __forceinline__ void lo_read_one(u32x4 (&f)[16], const char *stage, c
     constexpr int kBlock = 16 * kRowBytes;
     const int op = r < 8 ? 1 : 0, t = (r & 7) >> 1, half = r & 1;
     const int o = op ? (half ? LG.fb1 : LG.fb0) : (half ? LG.fa1 : LG.fa0);
-#ifdef GMP_EXP_NOLOREAD   /* timing experiment only */
-    f[(op * 4 + t) * 2 + half] = u32x4{(uint32_t)o, 1u, 2u, (uint32_t)(uintptr_t)stage};
-#else
     f[(op * 4 + t) * 2 + half] = *(const u32x4 *)(stage + o + t * kBlock);
-#endif
 }
 __device__ __forceinline__ void lo_read_slot(u32x4 (&f)[16], const char *stage, const LoGeom &LG, int slot)
 {
@@ -819,11 +769,6 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
     // occupied (every wave finished reading it before the barrier that ended the previous step).
     // Then wait until chunk done + 2 is complete in LDS for every wave: everything but the three
     // requests after it.
-#ifdef GMP_EXP_NOLOBAR   /* timing experiment only */
-#define GMP_LO_BARRIER() do {} while (0)
-#else
-#define GMP_LO_BARRIER() __syncthreads()
-#endif
 #define GMP_LO_STEP(QQ, PAR, FIRST)                                                         \
     do {                                                                             \
         lo_chunk<QQ, PAR, FIRST>(t, fr, lds + st_next, LG, GMP_LO_REQ_ARGS);                \
@@ -831,13 +776,13 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
         ++done;                                                                      \
         st_next = st_next + kLoStage == kLoLdsBytes ? 0 : st_next + kLoStage;        \
         lo_wait_dma(8 * (kLoStages - 2));                                            \
-        GMP_LO_BARRIER();                                                            \
+        __syncthreads();                                                             \
     } while (0)
     while (done < staged) {
         const int cn = R.nb / chunk_elems(cq);
         // precision and exponent sum of the product after this one, fetched early
         const ArgsPtr K = args();
-        const bool more = cL + 1 < K->kt_eff;
+        const bool more = cL + 1 < R.kt_eff;
         const int nq = more ? table_u8(K->q, (int64_t)W.tileC * K->KT + cL + 1) : -1;
         const int nesum = more ? table_i32(K->A.exp, W.I * K->KT + cL + 1) + table_i32(K->B.exp, (cL + 1) * K->NT + W.J) : 0;
         if (cq == Q16) {                           // 64 elements per chunk: always an even count
@@ -1012,7 +957,7 @@ __device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int e
 //             in the FP32 accumulator t first.
 // T = float : FP32 C tiles; FP32 products continue s, FP16 / FP8 products go through t.
 template <typename T>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(GMP_WAVES_PER_EU, GMP_WAVES_PER_EU)))
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 {
     using AccS = typename std::conditional<std::is_same<T, double>::value, d4, f4>::type;
@@ -1038,6 +983,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     const int I = tileC / NT, J = tileC % NT;
     Region R;
     R.nb = args()->nb;
+    R.kt_eff = args()->kt_eff;
     R.arow0 = uni((int)it.mi) * kMacro;
     R.brow0 = uni((int)it.mj) * kMacro;
 
@@ -1063,8 +1009,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     W.J = J;
     W.tileC = tileC;
     int L = 0;
-    const int kt_eff = args()->kt_eff;
-    while (L < kt_eff) {
+    while (L < R.kt_eff) {
         const int q = cur.q;
         if (is_ring(cur, G)) {
             lo_run(s, cur, L, W, lds, G, R);       // all consecutive products of that kind
