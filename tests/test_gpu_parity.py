@@ -191,6 +191,36 @@ def test_small_integer_inputs_are_exact_for_every_precision_combination():
                 assert np.array_equal(got, want.astype(np.float64))
 
 
+def test_runs_of_unconverted_low_precision_products_are_exact():
+    """Long and short runs of FP8 / FP16 products whose operands need no conversion (the path
+    that streams operands straight into LDS), entered from and left to every other kind of
+    product, at one, two, three and four chunks per product; small integers, so exact."""
+    import torch
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(5)
+    pattern = np.array([3, 3, 3, 2, 2, 1, 3, 3, 0, 2, 3, 2, 2, 2], dtype=np.uint16)
+    for nb in (128, 256, 384, 512):
+        MT, NT, KT = 2, 2, len(pattern)
+        M, N, K = MT * nb, NT * nb, KT * nb
+        A = rng.integers(-3, 4, (M, K)).astype(np.float64)
+        B = rng.integers(-3, 4, (K, N)).astype(np.float64)
+        mA = np.tile(pattern, (MT, 1))
+        mB = np.tile(pattern[:, None], (1, NT))
+        mA[1] = np.roll(pattern, 3)                 # second tile row: runs broken by mixed products
+        mC = np.array([[FP32, FP64], [FP32, FP32]], dtype=np.uint16)
+        _say("runs", nb)
+        d = DeviceGemmMP(M, N, K, nb)
+        for which, m, X in (("A", mA, A), ("B", mB, B)):
+            d.set_precision_map(which, m)
+            d.pack_tiles(which, torch.from_numpy(X).cuda())
+        d.set_precision_map("C", mC)
+        d.run(1.0, 0.0)
+        got = d.unpack_tiles("C").cpu().numpy()
+        want = (A.astype(np.int64) @ B.astype(np.int64)).astype(np.float64)
+        assert np.array_equal(got, want)
+        assert d.ctx.get_stats()["products"][FP8] >= 10
+
+
 @pytest.mark.parametrize("policy", [0, 1])
 def test_mixed_maps_match_the_oracle_per_tile(policy):
     """All (pA, pB, pC) combinations occur; several owner regions per tile; alpha, beta general."""
