@@ -31,8 +31,11 @@ def parse():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cov16k",
-                    choices=["tiny", "random8k", "cov16k", "rect32k", "cov64k"])
-    ap.add_argument("--policy", type=int, default=0, choices=[0, 1])
+                    choices=["tiny", "random8k", "cov16k", "rect32k", "cov64k",
+                             "paper100", "paper80", "paper50", "paper20", "paper0"],
+                    help="paperNN: the paper's own runs, NN %% of the tiles FP64 and the rest FP32 (Section 5.2)")
+    ap.add_argument("--policy", type=int, default=None, choices=[0, 1],
+                    help="0 = operand policy, 1 = C-tile policy (default: the workload's own)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -110,6 +113,8 @@ def main():
         print(json.dumps({"calibration": "plain copy", "bytes_read": src.numel() * 8, "bytes_written": src.numel() * 8}))
         return
     w = W.CONFIGS[args.workload]()
+    if args.policy is None:
+        args.policy = w.policy
     t0 = time.perf_counter()
     A = w.dense("A")
     B = A if w.a_equals_b else w.dense("B")
@@ -167,7 +172,7 @@ def main():
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(w.name + ("" if args.policy == 0 else "-ctile"), {}).get("bytes_per_launch")
+        traffic = json.load(open(tpath)).get(w.name + ("" if args.policy == w.policy else "-policy%d" % args.policy), {}).get("bytes_per_launch")
     used = [DTYPE_NAMES[q] for q in range(4) if st["products"][q]]
     out = {
         "metric": "effective TFLOP/s (2MNK/t) and % of precision-weighted MFMA peak, 1 GPU",

@@ -318,6 +318,16 @@ def test_config_rect32k_sampled_tiles():
     assert st["products"][0] == 0 and st["products"][3] > 0
 
 
+@pytest.mark.parametrize("pct", [100, 80, 50, 20, 0])
+def test_paper_ratio_runs_match_the_oracle(pct):
+    """The paper's own experiment at a small size: aD:bS maps on A, B and C, every task at its C
+    tile's precision (Section 5.2); all C tiles compared."""
+    w = W.paper_ratio(pct, n=1024, nb=256)
+    d, side, _, _ = _run_and_compare(w, policy=w.policy, check_storage_tiles=2)
+    n64 = int((w.mapC == FP64).sum())
+    assert d.ctx.get_stats()["products"] == [n64 * w.KT, (w.MT * w.NT - n64) * w.KT, 0, 0]
+
+
 def test_config_cov64k_sampled_blocks():
     """The largest configuration (65536^3, 2048-wide tiles): 16 rows of each of 66 C tiles."""
     w = W.CONFIGS["cov64k"]()

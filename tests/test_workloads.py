@@ -55,3 +55,20 @@ def test_morton_points_are_sorted_and_cluster_neighbours():
     norms = np.array([[np.linalg.norm(A[i * 128:(i + 1) * 128, j * 128:(j + 1) * 128]) for j in range(8)]
                       for i in range(8)])
     assert np.all(np.diag(norms) > 5 * norms[0, 7])       # off-diagonal tiles decay
+
+
+def test_paper_ratio_maps_have_the_exact_ratio_and_a_random_pattern():
+    """The paper's aD:bS runs: a % of the tiles of A, B and C FP64, the rest FP32 (Section 5.1)."""
+    for pct in (100, 80, 50, 20, 0):
+        w = W.paper_ratio(pct, n=4096, nb=256)
+        for m in (w.mapA, w.mapB, w.mapC):
+            assert m.shape == (16, 16) and m.dtype == np.uint16
+            assert set(np.unique(m)) <= {W.FP64, W.FP32}
+            assert int((m == W.FP64).sum()) == round(pct / 100 * 256)
+        assert w.policy == 1 and w.alpha == 1.0 and w.beta == 1.0
+    w = W.paper_ratio(50, n=4096, nb=256)
+    assert not np.array_equal(w.mapA, w.mapB) and not np.array_equal(w.mapA, w.mapC)
+    # not a structured pattern: every tile row and column holds both precisions
+    assert all(0 < int((w.mapA[i] == W.FP64).sum()) < 16 for i in range(16))
+    x = w.panel("A", 0, 8)
+    assert x.shape == (8, 4096) and np.all(np.abs(x) <= 1.0)

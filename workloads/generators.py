@@ -18,6 +18,10 @@ in its introduction; no public dataset is involved):
   cov16k      16384^3, tile 1024, A = B = exp(-dist/0.1), Morton-ordered points, rule 1e-8
   rect32k     32768 x 32768 x 4096, tile 1024, N(0,1) with tile (I,J) scaled 2^(-4|I-J|), rule 1e-4 incl. FP8
   cov64k      65536^3, tile 2048, A = B = exp(-dist/0.05), rule 1e-6
+  paperNN     the paper's own experiment (Section 5.2, Figure 3 maps, Figure 4 runs): 32768^3,
+              tile 2048, U[-1,1], NN % of the tiles of A, B and C in FP64 and the rest in FP32,
+              chosen at random; product precision = the C tile's (policy C_TILE); NN = 100, 80,
+              50, 20, 0
 """
 import numpy as np
 
@@ -88,6 +92,7 @@ class Workload:
         self.rule = None          # dict(eps=..., allowed=bitmask) -> maps of A, B from the norm rule
         self.mapA = self.mapB = self.mapC = None
         self.a_equals_b = False
+        self.policy = 0           # product-precision policy the workload is meant to run under
 
     @property
     def MT(self):
@@ -201,6 +206,28 @@ def random_maps(M=8192, N=8192, K=8192, nb=512, probs=(0.25, 0.25, 0.5), c_probs
     return w
 
 
+def _exact_ratio_map(seed, which, rows, cols, pct_double):
+    """round(pct/100 * tiles) tiles FP64, the rest FP32; which ones is decided by ranking a hash
+    of the tile index, so the ratio is exact and the pattern random."""
+    total = rows * cols
+    keys = _hash(seed, _MATRIX_ID[which], 1, np.arange(total), 0)
+    n64 = int(round(pct_double / 100.0 * total))
+    m = np.full(total, FP32, dtype=np.uint16)
+    m[np.argsort(keys, kind="stable")[:n64]] = FP64
+    return m.reshape(rows, cols)
+
+
+def paper_ratio(pct_double, n=32768, nb=2048, seed=MASTER_SEED, name=None):
+    """The paper's 'aD:bS' runs (Section 5.1 notation): a % of the tiles of each of A, B and C are
+    FP64 and b % FP32, placed at random; every task runs at its C tile's precision."""
+    w = _TileScaled(name or "paper%d" % pct_double, n, n, n, nb, 1.0, 1.0, seed=seed, dist="uniform")
+    w.mapA = _exact_ratio_map(seed, "mapA", w.MT, w.KT, pct_double)
+    w.mapB = _exact_ratio_map(seed, "mapB", w.KT, w.NT, pct_double)
+    w.mapC = _exact_ratio_map(seed, "mapC", w.MT, w.NT, pct_double)
+    w.policy = 1
+    return w
+
+
 def covariance(n=16384, nb=1024, ell=0.1, eps=1e-8, allowed=0b0111, seed=MASTER_SEED, name="cov16k"):
     return _Covariance(name, n, nb, ell, eps, allowed, seed=seed)
 
@@ -219,4 +246,9 @@ CONFIGS = {
     "cov16k": covariance,
     "rect32k": decay_rect,
     "cov64k": lambda: covariance(n=65536, nb=2048, ell=0.05, eps=1e-6, name="cov64k"),
+    "paper100": lambda: paper_ratio(100),
+    "paper80": lambda: paper_ratio(80),
+    "paper50": lambda: paper_ratio(50),
+    "paper20": lambda: paper_ratio(20),
+    "paper0": lambda: paper_ratio(0),
 }
