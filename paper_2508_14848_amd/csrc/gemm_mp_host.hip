@@ -44,6 +44,7 @@ struct gemm_mp_ctx {
     std::vector<uint8_t> q;
     std::vector<WorkItem> items[2];   // [0]: regions of FP64 C tiles, [1]: of FP32 C tiles
     uint8_t *d_q = nullptr;
+    ProductDesc *d_prod = nullptr;    // one record per task (+ 2 padding records), filled on the device
     WorkItem *d_items = nullptr;      // both lists, [0] first
     gemm_mp_stats stats;
     bool kernel_ready = false;
@@ -241,10 +242,12 @@ void build_schedule(gemm_mp_ctx *c)
 
 int upload_schedule(gemm_mp_ctx *c)
 {
-    (void)hipFree(c->d_q); (void)hipFree(c->d_items);
-    c->d_q = nullptr; c->d_items = nullptr;
+    (void)hipFree(c->d_q); (void)hipFree(c->d_items); (void)hipFree(c->d_prod);
+    c->d_q = nullptr; c->d_items = nullptr; c->d_prod = nullptr;
     int rc;
     if ((rc = dev_alloc(&c->d_q, c->q.size()))) return rc;
+    if ((rc = dev_alloc(&c->d_prod, c->q.size() + 2))) return rc;
+    HIP_TRY(hipMemset(c->d_prod, 0, (c->q.size() + 2) * sizeof(ProductDesc)));
     const size_t n0 = c->items[0].size(), n1 = c->items[1].size();
     if ((rc = dev_alloc(&c->d_items, n0 + n1))) return rc;
     HIP_TRY(hipMemcpy(c->d_q, c->q.data(), c->q.size(), hipMemcpyHostToDevice));
@@ -289,7 +292,7 @@ int gemm_mp_destroy(gemm_mp_ctx *c)
 {
     if (!c) return GEMM_MP_EINVAL;
     for (auto &m : c->mat) free_matrix_tables(m);
-    (void)hipFree(c->d_q); (void)hipFree(c->d_items);
+    (void)hipFree(c->d_q); (void)hipFree(c->d_items); (void)hipFree(c->d_prod);
     (void)hipGetLastError();
     delete c;
     return GEMM_MP_OK;
@@ -460,6 +463,7 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
     GemmArgs a;
     a.A = view_of(A); a.B = view_of(B); a.C = view_of(C);
     a.q = c->d_q;
+    a.prod = c->d_prod;
     a.items64 = c->d_items;
     a.items32 = c->d_items + c->items[0].size();
     a.n_items64 = (int32_t)c->items[0].size();
@@ -503,8 +507,8 @@ int gemm_mp_get_stats(gemm_mp_ctx *c, gemm_mp_stats *out)
     if (!c->sched_current) {
         if (c->d_q) (void)hipStreamSynchronize(c->mat[2].last_stream);
         build_schedule(c);
-        (void)hipFree(c->d_q); (void)hipFree(c->d_items);
-        c->d_q = nullptr; c->d_items = nullptr;
+        (void)hipFree(c->d_q); (void)hipFree(c->d_items); (void)hipFree(c->d_prod);
+        c->d_q = nullptr; c->d_items = nullptr; c->d_prod = nullptr;
     }
     *out = c->stats;
     return GEMM_MP_OK;

@@ -39,9 +39,24 @@ struct WorkItem {
     uint16_t mi, mj; // macro-tile row / column inside the tile
 };
 
+// Everything the GEMM kernel needs to know about one tile product A(I,L)*B(L,J), gathered into
+// one 32-byte record so that a workgroup opens a product with a single scalar load.  The table
+// is [MT*NT][KT] (C tile major) and is rebuilt on the device before every run from the maps,
+// offsets and exponents current at that time.
+struct ProductDesc {
+    uint64_t a_off, b_off;   // byte offsets of the two operand tiles in the packed A / B storage
+    int32_t ea, eb;          // their scale exponents
+    uint32_t codes;          // pA | pB << 8 | q << 16
+    uint32_t pad;
+};
+
+static_assert(sizeof(ProductDesc) == 32, "the kernel reads a record as two 16-byte scalar loads");
+static_assert(sizeof(WorkItem) == 8, "the kernel reads an item as one 8-byte scalar load");
+
 struct GemmArgs {
     PackedView A, B, C;
     const uint8_t *q;        // [MT*NT][KT] product precision of every task
+    ProductDesc *prod;       // [MT*NT][KT] (+ padding records), written by launch_gemm
     const WorkItem *items64;  // owner regions of FP64 C tiles, launch order
     const WorkItem *items32;  // owner regions of FP32 C tiles, launch order
     int32_t n_items64, n_items32;

@@ -29,6 +29,7 @@
 
 namespace gmp {
 
+
 typedef double d4 __attribute__((ext_vector_type(4)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
@@ -175,6 +176,8 @@ struct Geometry {
 struct Region {
     int nb, arow0, brow0;
     int kt_eff;                     // number of reduction tiles to process (0 when alpha == 0)
+    const ProductDesc *prod;        // this C tile's row of the product table: entry L
+    const char *sa, *sb;            // packed A and B storage
 };
 
 // On FP32 C tiles, FP16 / FP8 products whose operands are both stored in the product's precision
@@ -297,33 +300,31 @@ __device__ __forceinline__ Operand make_operand(const char *base, int p, int e, 
     return o;
 }
 
-// Load the descriptors of tile product L of this C tile (q = -1 past the end).  Two rounds of
-// scalar loads, each issued as one batch: the table pointers and tile counts from the kernel
-// arguments, then the seven table entries.
+// Load the descriptors of tile product L of this C tile (q = -1 past the end): one 32-byte
+// scalar load from the product table.
+typedef const __attribute__((address_space(4))) u32x4 *ConstQuad;
+__device__ __forceinline__ Product make_product(const u32x4 lo, const u32x4 hi, const Geometry &G, const Region &R)
+{
+    Product pr;
+    const uint64_t offa = (uint64_t)lo.x | ((uint64_t)lo.y << 32), offb = (uint64_t)lo.z | ((uint64_t)lo.w << 32);
+    const int ea = (int)hi.x, eb = (int)hi.y;
+    const int pa = (int)(hi.z & 0xffu), pb = (int)((hi.z >> 8) & 0xffu), q = (int)((hi.z >> 16) & 0xffu);
+    pr.q = q;
+    pr.a = make_operand(R.sa + offa, pa, ea, q, R.arow0, G, R.nb);
+    pr.b = make_operand(R.sb + offb, pb, eb, q, R.brow0, G, R.nb);
+    return pr;
+}
 __device__ __forceinline__ Product open_product(int I, int J, int tileC, int L, const Geometry &G, const Region &R)
 {
+    (void)I; (void)J; (void)tileC;
     Product pr;
     pr.q = -1;
     pr.a = Operand{};
     pr.b = Operand{};
     if (L >= R.kt_eff) return pr;
-    const ArgsPtr K = args();
-    const uint8_t *tq = K->q, *tpa = K->A.prec, *tpb = K->B.prec;
-    const uint64_t *toa = K->A.offset, *tob = K->B.offset;
-    const int32_t *tea = K->A.exp, *teb = K->B.exp;
-    const char *sa = K->A.storage, *sb = K->B.storage;
-    const int KT = K->KT, NT = K->NT;
-    SCHED_FENCE();
-    const int64_t ta = (int64_t)I * KT + L, tb = (int64_t)L * NT + J;
-    const int q = table_u8(tq, (int64_t)tileC * KT + L);
-    const uint64_t offa = table_u64(toa, ta), offb = table_u64(tob, tb);
-    const int pa = table_u8(tpa, ta), pb = table_u8(tpb, tb);
-    const int ea = table_i32(tea, ta), eb = table_i32(teb, tb);
-    SCHED_FENCE();
-    pr.q = q;
-    pr.a = make_operand(sa + offa, pa, ea, q, R.arow0, G, R.nb);
-    pr.b = make_operand(sb + offb, pb, eb, q, R.brow0, G, R.nb);
-    return pr;
+    const ConstQuad rec = (ConstQuad)(uintptr_t)(R.prod + L);
+    const u32x4 lo = rec[0], hi = rec[1];
+    return make_product(lo, hi, G, R);
 }
 
 // What a product loop needs in order to open the following tile product itself.
@@ -625,13 +626,15 @@ __device__ __forceinline__ void lo_read_slot(u32x4 (&f)[16], const char *stage, 
 // issue slots free while they execute (16 or 32 cycles each), and everything else the step has
 // to do is placed into those slots, one or two instructions behind each MFMA: first the reads
 // of the next chunk's fragments from the ring stage `next` into the other set, then the eight
-// DMA instructions that request a later chunk of product `pr` into the stage at `dst`.
+// DMA instructions that request a later chunk of product `pr` into the stage at `dst`, and the
+// scalar bookkeeping of the step (`book`, straight-line code).
 // The MFMAs are asm in place, see mfma_group.
-template <int Q, int PAR, bool FIRST>
+template <int Q, int PAR, bool FIRST, typename Book>
 __device__ __forceinline__ void lo_chunk(f4 (&acc)[4][4], u32x4 (&fr)[2][16], const char *next, const LoGeom &LG,
-                                         const Product &pr, int soff0, int rows8_bytes, unsigned dst)
+                                         const Product &pr, int soff0, int rows8_bytes, unsigned dst, Book book)
 {
     constexpr int kMfmas = Q == Q16 ? 32 : 16;
+    constexpr int kBookSlot = Q == Q16 ? 26 : 13;    // a slot with little else in it
 #pragma unroll
     for (int m = 0; m < kMfmas; ++m) {
         const int g = m >> 2, nt = m & 3, mt = g & 3, kk = g >> 2;
@@ -664,6 +667,7 @@ __device__ __forceinline__ void lo_chunk(f4 (&acc)[4][4], u32x4 (&fr)[2][16], co
             }
         }
         SCHED_FENCE();
+        if (m == kBookSlot) book();                  // the step's scalar bookkeeping (branch-free)
         if constexpr (Q == Q16) {
             if (m < 16) lo_read_one(fr[PAR ^ 1], next, LG, m);
             else if (m < 24) lo_dma_one(pr, soff0, rows8_bytes, dst, m - 16);
@@ -713,20 +717,30 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
     const int wave_off = uni(wave * 4096);
 
     // A request = eight DMA instructions per wave (chunk pf.c of product pf.pr into the stage at
-    // st_req), then req_done moves the cursor on.  Every step of the stream issues one, so that
-    // the number of outstanding instructions is the same at every step; past the end of the
-    // stream the requests are empty: the operands' descriptors get length zero, which turns
-    // every lane's load into an out-of-range one that touches no global memory (it zero-fills
-    // its 16 bytes of a stage nobody reads any more).
-    auto req_done = [&]() __attribute__((always_inline)) {
+    // st_req).  Every step of the stream issues one, so that the number of outstanding
+    // instructions is the same at every step; past the end of the stream the requests are
+    // empty: the operands' descriptors get length zero, which turns every lane's load into an
+    // out-of-range one that touches no global memory (it zero-fills its 16 bytes of a stage
+    // nobody reads any more).
+    // The bookkeeping after a request is split in two: `advance` is straight-line scalar code
+    // (it runs in the shadow of the step's MFMAs) and only decides whether `turn` is needed,
+    // the rare part with loads and branches that opens the product after next or moves the
+    // cursor to the next product.
+    int done = 0;                                  // chunks computed
+    int st_next = kLoStage;                        // ring stage of chunk done + 1
+    bool slow = false;
+    auto advance = [&]() __attribute__((always_inline)) {
         st_req = st_req + kLoStage == kLoLdsBytes ? 0 : st_req + kLoStage;
+        staged += pf_valid ? 1 : 0;
+        pf.c += 1;
+        slow = need_open || (pf_valid && pf.c == pf.n);
+    };
+    auto turn = [&]() __attribute__((always_inline)) {
         if (need_open) {                            // second step of a product: look one product ahead
             nx = open_product(W.I, W.J, W.tileC, pf.L + 1, G, R);
             need_open = false;
         }
-        if (!pf_valid) return;
-        ++staged;
-        if (++pf.c == pf.n) {                       // next product: does it continue the run?
+        if (pf_valid && pf.c == pf.n) {             // next product: does it continue the run?
             ++pf.L;
             if (is_ring(nx, G)) {
                 pf.pr = nx;
@@ -742,14 +756,15 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
             pf.c = 0;
         }
     };
-#define GMP_LO_REQ_ARGS pf.pr, (pf.c * chunk_elems(pf.pr.q)) << (3 - pf.pr.q), (8 * R.nb) << (3 - pf.pr.q), (unsigned)(st_req + wave_off)
+#define GMP_LO_REQ_ARGS pf.pr, pf.c * kRowBytes, (8 * R.nb) << (3 - pf.pr.q), (unsigned)(st_req + wave_off)
 
     // prologue: chunks 0..4 requested; chunks 0 and 1 complete and published; fragments of chunk 0 read
 #pragma unroll 1
     for (int i = 0; i < kLoStages; ++i) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) lo_dma_one(GMP_LO_REQ_ARGS, k);
-        req_done();
+        advance();
+        if (slow) turn();
     }
     lo_wait_dma(8 * (kLoStages - 2));
     __syncthreads();
@@ -761,30 +776,31 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
     int cL = L;
     int cq = cur.q;
     int cesum = cur.a.e + cur.b.e;
-    int done = 0;                                  // chunks computed
-    int st_next = kLoStage;                        // ring stage of chunk done + 1
     // One step: the MFMAs of chunk `done` from fragment set PAR; in their shadow the fragments of
     // chunk done + 1 are read from the ring stage after it (past the end of the stream that read
     // is harmless and unused) and chunk done + 5 is requested into the stage that chunk `done`
     // occupied (every wave finished reading it before the barrier that ended the previous step).
     // Then wait until chunk done + 2 is complete in LDS for every wave: everything but the three
     // requests after it.
-#define GMP_LO_STEP(QQ, PAR, FIRST)                                                         \
+    auto step_book = [&]() __attribute__((always_inline)) {
+        advance();
+        ++done;
+        st_next = st_next + kLoStage == kLoLdsBytes ? 0 : st_next + kLoStage;
+    };
+#define GMP_LO_STEP(QQ, PAR, FIRST)                                                  \
     do {                                                                             \
-        lo_chunk<QQ, PAR, FIRST>(t, fr, lds + st_next, LG, GMP_LO_REQ_ARGS);                \
-        req_done();                                                                  \
-        ++done;                                                                      \
-        st_next = st_next + kLoStage == kLoLdsBytes ? 0 : st_next + kLoStage;        \
+        lo_chunk<QQ, PAR, FIRST>(t, fr, lds + st_next, LG, GMP_LO_REQ_ARGS, step_book); \
+        if (slow) turn();                                                            \
         lo_wait_dma(8 * (kLoStages - 2));                                            \
         __syncthreads();                                                             \
     } while (0)
     while (done < staged) {
         const int cn = R.nb / chunk_elems(cq);
         // precision and exponent sum of the product after this one, fetched early
-        const ArgsPtr K = args();
         const bool more = cL + 1 < R.kt_eff;
-        const int nq = more ? table_u8(K->q, (int64_t)W.tileC * K->KT + cL + 1) : -1;
-        const int nesum = more ? table_i32(K->A.exp, W.I * K->KT + cL + 1) + table_i32(K->B.exp, (cL + 1) * K->NT + W.J) : 0;
+        const u32x4 nrec = more ? ((ConstQuad)(uintptr_t)(R.prod + cL + 1))[1] : u32x4{0, 0, 0xff0000u, 0};
+        const int nq = more ? (int)((nrec.z >> 16) & 0xffu) : -1;
+        const int nesum = (int)nrec.x + (int)nrec.y;
         if (cq == Q16) {                           // 64 elements per chunk: always an even count
             GMP_LO_STEP(Q16, 0, true);
             GMP_LO_STEP(Q16, 1, false);
@@ -977,15 +993,20 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     G.seg_part = G.tid & 7;
     G.wbase = G.seg_row * kRowStride + G.seg_part * 16;
 
-    const WorkItem it = items[blockIdx.x];
-    const int tileC = uni((int)it.tile);
-    const int NT = args()->NT;
+    // this workgroup's item and the kernel arguments it needs throughout: scalar loads
+    const uint64_t itw = table_u64((const uint64_t *)items, blockIdx.x);
+    const int tileC = (int)(uint32_t)itw;
+    const ArgsPtr K0 = args();
+    const int NT = K0->NT;
     const int I = tileC / NT, J = tileC % NT;
     Region R;
-    R.nb = args()->nb;
-    R.kt_eff = args()->kt_eff;
-    R.arow0 = uni((int)it.mi) * kMacro;
-    R.brow0 = uni((int)it.mj) * kMacro;
+    R.nb = K0->nb;
+    R.kt_eff = K0->kt_eff;
+    R.arow0 = (int)((itw >> 32) & 0xffffu) * kMacro;
+    R.brow0 = (int)((itw >> 48) & 0xffffu) * kMacro;
+    R.prod = K0->prod + (int64_t)tileC * K0->KT;
+    R.sa = K0->A.storage;
+    R.sb = K0->B.storage;
 
     AccS s[4][4];
 #pragma unroll
@@ -1053,25 +1074,48 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     }
 
     // Epilogue: v = alpha*s (+ beta*c0): two rounded products and one rounded sum in T.
-    typedef __attribute__((address_space(1))) T *GlobalT;
+    // The accumulator layout (a lane holds a 4-row column piece of each 16x16 block) would make
+    // 4- or 8-byte stores scattered over four rows; each wave therefore turns its 64 x 64 block
+    // through a private, padded piece of LDS (the operand stages are dead by now) and moves
+    // 16 bytes per lane along the rows: whole 256- or 512-byte row segments per instruction, for
+    // the C tile read by beta as well.
+    constexpr int kVec = 16 / (int)sizeof(T);                    // elements per lane and pass: 4 or 2
+    constexpr int kLanesPerRow = 64 / kVec;                      // 16 or 32
+    constexpr int kRowsPerPass = 64 / kLanesPerRow;              // 4 or 2
+    constexpr int kEpiStride = 64 + kVec;                        // row pitch in elements: 272 or 528 bytes
+    typedef T VecT __attribute__((ext_vector_type(kVec)));
+    typedef __attribute__((address_space(1))) VecT *GlobalVec;
     const ArgsPtr K = args();
-    GlobalT ctile = (GlobalT)(uintptr_t)(K->C.storage + table_u64(K->C.offset, tileC));
     const T alpha = (T)K->alpha, beta = (T)K->beta;
     const bool use_c = K->beta != 0.0;
+    __syncthreads();                                             // every wave is done with the stages
+    T *stg = (T *)lds + (G.tid >> 6) * (64 * kEpiStride);
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int row = R.arow0 + G.wm * 64 + mt * 16 + 4 * G.g + v;
-                const int col = R.brow0 + G.wn * 64 + nt * 16 + G.li;
-                GlobalT p = ctile + (int64_t)row * R.nb + col;
-                T val = alpha * (T)s[mt][nt][v];
-                if (use_c) { const T bc = beta * *p; val = val + bc; }
-                *p = val;
-            }
+            for (int v = 0; v < 4; ++v) stg[(mt * 16 + 4 * G.g + v) * kEpiStride + nt * 16 + G.li] = (T)s[mt][nt][v];
+    const int er = G.lane / kLanesPerRow, ec = (G.lane % kLanesPerRow) * kVec;
+    const char *cbase = K->C.storage + table_u64(K->C.offset, tileC)
+                        + ((int64_t)(R.arow0 + G.wm * 64 + er) * R.nb + R.brow0 + G.wn * 64 + ec) * (int64_t)sizeof(T);
+    const int64_t pass_bytes = (int64_t)kRowsPerPass * R.nb * (int64_t)sizeof(T);
+#pragma unroll 4
+    for (int pass = 0; pass < 64 / kRowsPerPass; ++pass) {
+        const VecT sv = *(const VecT *)&stg[(pass * kRowsPerPass + er) * kEpiStride + ec];
+        GlobalVec gp = (GlobalVec)(uintptr_t)(cbase + pass * pass_bytes);
+        VecT val;
+#pragma unroll
+        for (int i = 0; i < kVec; ++i) val[i] = alpha * sv[i];
+        if (use_c) {
+            const VecT c0 = *gp;
+#pragma unroll
+            for (int i = 0; i < kVec; ++i) { const T bc = beta * c0[i]; val[i] = val[i] + bc; }
+        }
+        *gp = val;
+    }
 }
+
 
 hipError_t gemm_kernel_setup()
 {
@@ -1082,9 +1126,32 @@ hipError_t gemm_kernel_setup()
                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
 }
 
-// Two launches at most: the owner regions of FP64 C tiles, then those of FP32 C tiles.
+// One thread per task (C tile, L): gather what the owner workgroups need into one record.
+__global__ void product_table_kernel(PackedView A, PackedView B, const uint8_t *__restrict__ q, int MT, int NT, int KT,
+                                     ProductDesc *__restrict__ out)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (int64_t)MT * NT * KT) return;
+    const int L = (int)(idx % KT);
+    const int tileC = (int)(idx / KT);
+    const int I = tileC / NT, J = tileC % NT;
+    const int64_t ta = (int64_t)I * KT + L, tb = (int64_t)L * NT + J;
+    ProductDesc d;
+    d.a_off = A.offset[ta];
+    d.b_off = B.offset[tb];
+    d.ea = A.exp[ta];
+    d.eb = B.exp[tb];
+    d.codes = (uint32_t)A.prec[ta] | ((uint32_t)B.prec[tb] << 8) | ((uint32_t)q[idx] << 16);
+    d.pad = 0;
+    out[idx] = d;
+}
+
+// The product table, then two launches at most: the owner regions of FP64 C tiles, then those
+// of FP32 C tiles.
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
+    const int64_t tasks = (int64_t)a.MT * a.NT * a.KT;
+    product_table_kernel<<<dim3((unsigned)((tasks + 255) / 256)), dim3(256), 0, s>>>(a.A, a.B, a.q, a.MT, a.NT, a.KT, a.prod);
     if (a.n_items64 > 0)
         gemm_mp_owner_kernel<double><<<dim3((unsigned)a.n_items64), dim3(kThreads), kLdsBytes, s>>>(a, a.items64);
     if (a.n_items32 > 0)
