@@ -1074,48 +1074,68 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     }
 
     // Epilogue: v = alpha*s (+ beta*c0): two rounded products and one rounded sum in T.
-    // The accumulator layout (a lane holds a 4-row column piece of each 16x16 block) would make
-    // 4- or 8-byte stores scattered over four rows; each wave therefore turns its 64 x 64 block
-    // through a private, padded piece of LDS (the operand stages are dead by now) and moves
-    // 16 bytes per lane along the rows: whole 256- or 512-byte row segments per instruction, for
-    // the C tile read by beta as well.
-    constexpr int kVec = 16 / (int)sizeof(T);                    // elements per lane and pass: 4 or 2
-    constexpr int kLanesPerRow = 64 / kVec;                      // 16 or 32
-    constexpr int kRowsPerPass = 64 / kLanesPerRow;              // 4 or 2
-    constexpr int kEpiStride = 64 + kVec;                        // row pitch in elements: 272 or 528 bytes
-    typedef T VecT __attribute__((ext_vector_type(kVec)));
-    typedef __attribute__((address_space(1))) VecT *GlobalVec;
     const ArgsPtr K = args();
     const T alpha = (T)K->alpha, beta = (T)K->beta;
     const bool use_c = K->beta != 0.0;
-    __syncthreads();                                             // every wave is done with the stages
-    T *stg = (T *)lds + (G.tid >> 6) * (64 * kEpiStride);
+    if constexpr (std::is_same<T, double>::value) {
+        // FP64 tiles: straight from the accumulators (8-byte stores, 128 contiguous bytes per 16
+        // lanes).  The staged form below costs this kernel registers it does not have: measured
+        // 1 % slower overall, while its C traffic is negligible against 64-cycle MFMAs.
+        typedef __attribute__((address_space(1))) T *GlobalT;
+        GlobalT ctile = (GlobalT)(uintptr_t)(K->C.storage + table_u64(K->C.offset, tileC));
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+        for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
+            for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) stg[(mt * 16 + 4 * G.g + v) * kEpiStride + nt * 16 + G.li] = (T)s[mt][nt][v];
-    const int er = G.lane / kLanesPerRow, ec = (G.lane % kLanesPerRow) * kVec;
-    const char *cbase = K->C.storage + table_u64(K->C.offset, tileC)
-                        + ((int64_t)(R.arow0 + G.wm * 64 + er) * R.nb + R.brow0 + G.wn * 64 + ec) * (int64_t)sizeof(T);
-    const int64_t pass_bytes = (int64_t)kRowsPerPass * R.nb * (int64_t)sizeof(T);
+                for (int v = 0; v < 4; ++v) {
+                    const int row = R.arow0 + G.wm * 64 + mt * 16 + 4 * G.g + v;
+                    const int col = R.brow0 + G.wn * 64 + nt * 16 + G.li;
+                    GlobalT p = ctile + (int64_t)row * R.nb + col;
+                    T val = alpha * (T)s[mt][nt][v];
+                    if (use_c) { const T bc = beta * *p; val = val + bc; }
+                    *p = val;
+                }
+    } else {
+        // FP32 tiles: the accumulator layout (a lane holds a 4-row column piece of each 16x16
+        // block) would make 4-byte stores scattered over four rows; each wave therefore turns
+        // its 64 x 64 block through a private, padded piece of LDS (the operand stages are dead
+        // by now) and moves 16 bytes per lane along the rows: whole 256-byte row segments per
+        // instruction, for the C tile read by beta as well.
+        constexpr int kVec = 16 / (int)sizeof(T);                    // elements per lane and pass: 4 or 2
+        constexpr int kLanesPerRow = 64 / kVec;                      // 16 or 32
+        constexpr int kRowsPerPass = 64 / kLanesPerRow;              // 4 or 2
+        constexpr int kEpiStride = 64 + kVec;                        // row pitch in elements: 272 or 528 bytes
+        typedef T VecT __attribute__((ext_vector_type(kVec)));
+        typedef __attribute__((address_space(1))) VecT *GlobalVec;
+        __syncthreads();                                             // every wave is done with the stages
+        T *stg = (T *)lds + (G.tid >> 6) * (64 * kEpiStride);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) stg[(mt * 16 + 4 * G.g + v) * kEpiStride + nt * 16 + G.li] = (T)s[mt][nt][v];
+        const int er = G.lane / kLanesPerRow, ec = (G.lane % kLanesPerRow) * kVec;
+        const char *cbase = K->C.storage + table_u64(K->C.offset, tileC)
+                            + ((int64_t)(R.arow0 + G.wm * 64 + er) * R.nb + R.brow0 + G.wn * 64 + ec) * (int64_t)sizeof(T);
+        const int64_t pass_bytes = (int64_t)kRowsPerPass * R.nb * (int64_t)sizeof(T);
 #pragma unroll 4
-    for (int pass = 0; pass < 64 / kRowsPerPass; ++pass) {
-        const VecT sv = *(const VecT *)&stg[(pass * kRowsPerPass + er) * kEpiStride + ec];
-        GlobalVec gp = (GlobalVec)(uintptr_t)(cbase + pass * pass_bytes);
-        VecT val;
+        for (int pass = 0; pass < 64 / kRowsPerPass; ++pass) {
+            const VecT sv = *(const VecT *)&stg[(pass * kRowsPerPass + er) * kEpiStride + ec];
+            GlobalVec gp = (GlobalVec)(uintptr_t)(cbase + pass * pass_bytes);
+            VecT val;
 #pragma unroll
-        for (int i = 0; i < kVec; ++i) val[i] = alpha * sv[i];
-        if (use_c) {
-            const VecT c0 = *gp;
+            for (int i = 0; i < kVec; ++i) val[i] = alpha * sv[i];
+            if (use_c) {
+                const VecT c0 = *gp;
 #pragma unroll
-            for (int i = 0; i < kVec; ++i) { const T bc = beta * c0[i]; val[i] = val[i] + bc; }
+                for (int i = 0; i < kVec; ++i) { const T bc = beta * c0[i]; val[i] = val[i] + bc; }
+            }
+            *gp = val;
         }
-        *gp = val;
     }
 }
-
 
 hipError_t gemm_kernel_setup()
 {
