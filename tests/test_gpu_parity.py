@@ -270,6 +270,34 @@ def test_beta_zero_does_not_read_c_and_alpha_zero_forms_no_product():
     assert np.array_equal(got, want)
 
 
+def test_a_context_follows_new_maps_new_data_and_a_new_policy_between_runs():
+    """The per-product table is rebuilt for every run: after the maps, the packed data (hence the
+    scale exponents) or the policy change, the next run must match the oracle for the new state."""
+    import torch
+    w = W.random_maps(M=512, N=512, K=768, nb=128, probs=(0.25, 0.25, 0.25, 0.25), alpha=1.0, beta=0.0,
+                      name="reuse")
+    A, B, _ = _dense(w)
+    d, _ = gpu_problem(w, A, B, None)
+    jobs = _all_jobs(w)
+
+    def check(policy):
+        side = OracleSide(w, A, B, None)
+        d.run(w.alpha, w.beta)
+        C_gpu = d.unpack_tiles("C").cpu().numpy()
+        C_orc = side.gemm(jobs, policy=policy)
+        compare_jobs(side, jobs, policy, w.alpha, w.beta, C_gpu, C_orc)
+
+    check(0)
+    # new maps for A (transposed pattern) and data scaled by 2^-9 (all FP16/FP8 exponents move)
+    w.mapA = np.ascontiguousarray(w.mapB.T[:w.MT, :w.KT]) if w.mapB.T.shape == w.mapA.shape else (3 - w.mapA)
+    A = A * 2.0 ** -9
+    d.set_precision_map("A", w.mapA)
+    d.pack_tiles("A", torch.from_numpy(A).cuda())
+    check(0)
+    d.ctx.set_policy(1)
+    check(1)
+
+
 def test_call_order_errors_on_the_device_path():
     import torch
     from paper_2508_14848_amd import gemm_mp as G
