@@ -36,6 +36,9 @@ def parse():
                     help="paperNN: the paper's own runs, NN %% of the tiles FP64 and the rest FP32 (Section 5.2)")
     ap.add_argument("--policy", type=int, default=None, choices=[0, 1],
                     help="0 = operand policy, 1 = C-tile policy (default: the workload's own)")
+    ap.add_argument("--conversion", default="receiver", choices=["receiver", "sender"],
+                    help="receiver: every task converts its operands on the fly (the paper's strategy); sender: tiles are "
+                         "converted once per needed precision into a workspace before the run (timed as its own stage)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -127,10 +130,10 @@ def main():
 
     d = DeviceGemmMP(w.M, w.N, w.K, w.nb, device=dev, policy=args.policy)
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    stage_ms = {"scan_rule": [], "pack": [], "run": []}
+    stage_ms = {"scan_rule": [], "pack": [], "convert": [], "run": []}
 
     def step(record):
-        e = [ev() for _ in range(4)]
+        e = [ev() for _ in range(5)]
         e[0].record()
         if w.rule is not None:
             d.compute_precision_map("A", dA, w.rule["eps"], w.rule["allowed"])
@@ -145,11 +148,14 @@ def main():
         if dC is not None:
             d.pack_tiles("C", dC)
         e[2].record()
-        d.run(w.alpha, w.beta)
+        if args.conversion == "sender":
+            d.convert_tiles()
         e[3].record()
+        d.run(w.alpha, w.beta)
+        e[4].record()
         if record:
             torch.cuda.synchronize()
-            for k, (a, b) in zip(("scan_rule", "pack", "run"), ((0, 1), (1, 2), (2, 3))):
+            for k, (a, b) in zip(("scan_rule", "pack", "convert", "run"), ((0, 1), (1, 2), (2, 3), (3, 4))):
                 stage_ms[k].append(e[a].elapsed_time(e[b]))
 
     for _ in range(args.warmup):
@@ -172,7 +178,8 @@ def main():
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(w.name + ("" if args.policy == w.policy else "-policy%d" % args.policy), {}).get("bytes_per_launch")
+        key = w.name + ("" if args.policy == w.policy else "-policy%d" % args.policy) + ("" if args.conversion == "receiver" else "-sender")
+        traffic = json.load(open(tpath)).get(key, {}).get("bytes_per_launch")
     used = [DTYPE_NAMES[q] for q in range(4) if st["products"][q]]
     out = {
         "metric": "effective TFLOP/s (2MNK/t) and % of precision-weighted MFMA peak, 1 GPU",
@@ -184,6 +191,8 @@ def main():
         "dtype": "+".join(used), "data": "synthetic",
         "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "tile_nb": w.nb,
                    "alpha": w.alpha, "beta": w.beta, "policy": ["operand", "c_tile"][args.policy],
+                   "conversion": args.conversion, "converted_tiles": st["converted_tiles"],
+                   "converted_bytes": st["converted_bytes"],
                    "products_by_precision": dict(zip(DTYPE_NAMES, st["products"])),
                    "work_items": st["work_items"], "host_generation_s": round(t_gen, 1)},
         "stages_ms": {k: float(np.mean(v)) for k, v in stage_ms.items()},

@@ -77,6 +77,8 @@ typedef struct gemm_mp_stats {
     int64_t tiles[3][4];     /* stored tiles per matrix (0=A,1=B,2=C) and precision */
     uint64_t packed_bytes[3];/* size of the packed buffer per matrix */
     int64_t work_items;      /* owner workgroups launched by gemm_mp_run */
+    int64_t converted_tiles; /* tile copies the sender-side workspace holds (0: receiver-side) */
+    uint64_t converted_bytes;/* their total size */
 } gemm_mp_stats;
 
 /* Create a context for C(MxN) = A(MxK) * B(KxN) with square tiles of tile_nb (Section 4:
@@ -144,6 +146,28 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *ctx, char which, const double *dense_dev, in
  * beta == 0: C is not read.  alpha == 0: no product is formed.
  * ESTATE unless A and B are packed, C's map and buffer are set, and (beta != 0) C is packed. */
 int gemm_mp_run(gemm_mp_ctx *ctx, double alpha, double beta, gemm_mp_stream stream);
+
+/* Sender-side conversion (optional).  The paper converts at the receiver: a tile travels in its
+ * stored precision and every task that needs another precision converts it again (Section 4,
+ * which leaves other conversion strategies to future work, as does Section 6).  These calls
+ * add the opposite strategy on one GPU: every A or B tile is converted once per distinct
+ * product precision that differs from its stored one, into a caller-owned workspace, and
+ * gemm_mp_run then reads the converted copies, so no task converts anything.  The converted
+ * values are exactly the ones the receiver-side path produces (exact up-casts with the tile's
+ * 2^e applied for FP64/FP32 targets, FP8 -> FP16 keeping the tile's exponent, and the one
+ * rounding FP64 -> FP32), so C is the same; what changes is memory (the workspace), one
+ * HBM-bound conversion pass, and which chunk loops the products run through.
+ *
+ * conversion_bytes: size of that workspace for the current maps and policy (0 if no task needs
+ * a conversion).  ESTATE until all three maps are set.  Host only.
+ * convert_tiles [async]: fill the workspace (256-byte aligned device memory of at least
+ * conversion_bytes, owned by the caller, who keeps it alive while it is in use) from the packed
+ * A and B.  ESTATE unless A and B are packed.  Afterwards gemm_mp_run uses the copies until a
+ * map, the policy or the packed A or B changes, or clear_conversion is called; then it is
+ * back to receiver-side conversion without further notice. */
+int gemm_mp_conversion_bytes(gemm_mp_ctx *ctx, size_t *bytes);
+int gemm_mp_convert_tiles(gemm_mp_ctx *ctx, void *workspace_dev, size_t bytes, gemm_mp_stream stream);
+int gemm_mp_clear_conversion(gemm_mp_ctx *ctx);
 
 /* Unpack [async]: the numbers the packed tiles stand for (stored value times 2^e), exactly,
  * as a dense FP64 device matrix.  For verification; not part of the timed path. */

@@ -48,7 +48,17 @@ struct gemm_mp_ctx {
     WorkItem *d_items = nullptr;      // both lists, [0] first
     gemm_mp_stats stats;
     bool kernel_ready = false;
+    // sender-side conversion: per tile of A / B and product precision q, the offset of the copy
+    // in precision q inside the workspace (kNoCopy: no task needs one)
+    std::vector<uint64_t> conv_off[2];
+    uint64_t conv_bytes = 0;
+    int64_t conv_tiles = 0;
+    bool conv_active = false;         // the workspace holds copies that match maps, policy and packed data
+    uint64_t *d_conv[2] = {nullptr, nullptr};   // [tiles][4] device addresses of the copies, 0 = none
+    ConvertJob *d_jobs = nullptr;
 };
+
+constexpr uint64_t kNoCopy = ~(uint64_t)0;
 
 namespace {
 
@@ -194,6 +204,29 @@ void build_schedule(gemm_mp_ctx *c)
         }
     const double f = 2.0 * (double)c->nb * (double)c->nb * (double)c->nb;
     for (int q = 0; q < 4; ++q) c->stats.flops[q] = f * (double)c->stats.products[q];
+
+    // Sender-side conversion plan: which (tile, q) copies the tasks would need, and where each
+    // would live in the workspace (256-byte aligned, A's copies first).
+    c->conv_off[0].assign((size_t)MT * KT * 4, kNoCopy);
+    c->conv_off[1].assign((size_t)KT * NT * 4, kNoCopy);
+    for (int I = 0; I < MT; ++I)
+        for (int J = 0; J < NT; ++J)
+            for (int L = 0; L < KT; ++L) {
+                const int q = c->q[((size_t)I * NT + J) * KT + L];
+                if (A.map[I * KT + L] != q) c->conv_off[0][((size_t)I * KT + L) * 4 + q] = 0;
+                if (B.map[L * NT + J] != q) c->conv_off[1][((size_t)L * NT + J) * 4 + q] = 0;
+            }
+    c->conv_bytes = 0;
+    c->conv_tiles = 0;
+    for (int w = 0; w < 2; ++w)
+        for (size_t k = 0; k < c->conv_off[w].size(); ++k)
+            if (c->conv_off[w][k] != kNoCopy) {
+                const int q = (int)(k & 3);
+                c->conv_off[w][k] = c->conv_bytes;
+                c->conv_bytes += (((uint64_t)c->nb * c->nb * elem_bytes(q)) + 255) & ~(uint64_t)255;
+                c->conv_tiles += 1;
+            }
+    c->conv_active = false;
     for (int w = 0; w < 3; ++w) {
         for (int t = 0; t < c->mat[w].ntiles(); ++t) c->stats.tiles[w][c->mat[w].map[t]] += 1;
         c->stats.packed_bytes[w] = c->mat[w].bytes;
@@ -293,6 +326,7 @@ int gemm_mp_destroy(gemm_mp_ctx *c)
     if (!c) return GEMM_MP_EINVAL;
     for (auto &m : c->mat) free_matrix_tables(m);
     (void)hipFree(c->d_q); (void)hipFree(c->d_items); (void)hipFree(c->d_prod);
+    (void)hipFree(c->d_conv[0]); (void)hipFree(c->d_conv[1]); (void)hipFree(c->d_jobs);
     (void)hipGetLastError();
     delete c;
     return GEMM_MP_OK;
@@ -424,6 +458,7 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *c, char which, const double *dense, int64_t 
     HIP_TRY(launch_pack(dense, ld, m.rows_t, m.cols_t, c->nb, w == 1, view_of(m), s));
     m.packed = true;
     m.last_stream = s;
+    if (w < 2) c->conv_active = false;            // converted copies of the old data are stale
     return GEMM_MP_OK;
 }
 
@@ -464,6 +499,8 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
     a.A = view_of(A); a.B = view_of(B); a.C = view_of(C);
     a.q = c->d_q;
     a.prod = c->d_prod;
+    a.convA = c->conv_active ? c->d_conv[0] : nullptr;
+    a.convB = c->conv_active ? c->d_conv[1] : nullptr;
     a.items64 = c->d_items;
     a.items32 = c->d_items + c->items[0].size();
     a.n_items64 = (int32_t)c->items[0].size();
@@ -475,6 +512,82 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
     C.packed = true;
     C.exps_valid = true;
     A.last_stream = B.last_stream = C.last_stream = s;
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_conversion_bytes(gemm_mp_ctx *c, size_t *bytes)
+{
+    if (!c || !bytes) return GEMM_MP_EINVAL;
+    if (!all_maps(c)) return GEMM_MP_ESTATE;
+    if (!c->sched_current) {
+        if (c->d_q) (void)hipStreamSynchronize(c->mat[2].last_stream);
+        build_schedule(c);
+        (void)hipFree(c->d_q); (void)hipFree(c->d_items); (void)hipFree(c->d_prod);
+        c->d_q = nullptr; c->d_items = nullptr; c->d_prod = nullptr;
+    }
+    *bytes = (size_t)c->conv_bytes;
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_convert_tiles(gemm_mp_ctx *c, void *workspace, size_t bytes, gemm_mp_stream stream)
+{
+    if (!c) return GEMM_MP_EINVAL;
+    Matrix &A = c->mat[0], &B = c->mat[1];
+    if (!all_maps(c) || !A.packed || !B.packed) return GEMM_MP_ESTATE;
+    size_t need = 0;
+    int rc;
+    if ((rc = gemm_mp_conversion_bytes(c, &need))) return rc;
+    if (need > 0 && (!workspace || ((uintptr_t)workspace & 255) || bytes < need)) return GEMM_MP_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    if ((rc = ensure_tables(A)) || (rc = ensure_tables(B))) return rc;
+    // jobs and address tables
+    std::vector<ConvertJob> jobs;
+    std::vector<uint64_t> addr[2];
+    uint32_t max_n16 = 0;
+    for (int w = 0; w < 2; ++w) {
+        const Matrix &m = c->mat[w];
+        addr[w].assign(c->conv_off[w].size(), 0);
+        for (size_t k = 0; k < c->conv_off[w].size(); ++k) {
+            if (c->conv_off[w][k] == kNoCopy) continue;
+            const size_t tile = k >> 2;
+            const int q = (int)(k & 3);
+            ConvertJob j;
+            j.src = (uint64_t)(uintptr_t)((char *)m.storage + m.offset[tile]);
+            j.dst = (uint64_t)(uintptr_t)((char *)workspace + c->conv_off[w][k]);
+            j.tile = (uint32_t)tile;
+            j.p = (uint8_t)m.map[tile];
+            j.q = (uint8_t)q;
+            j.which = (uint8_t)w;
+            j.pad = 0;
+            j.n16 = (uint32_t)(((uint64_t)c->nb * c->nb * elem_bytes(q)) / 16);
+            j.pad2 = 0;
+            max_n16 = std::max(max_n16, j.n16);
+            addr[w][k] = j.dst;
+            jobs.push_back(j);
+        }
+    }
+    // the tables may be in use by an earlier run on another stream
+    if (c->d_conv[0]) (void)hipStreamSynchronize(c->mat[2].last_stream);
+    (void)hipFree(c->d_conv[0]); (void)hipFree(c->d_conv[1]); (void)hipFree(c->d_jobs);
+    c->d_conv[0] = c->d_conv[1] = nullptr; c->d_jobs = nullptr;
+    for (int w = 0; w < 2; ++w) {
+        if ((rc = dev_alloc(&c->d_conv[w], addr[w].size()))) return rc;
+        HIP_TRY(hipMemcpy(c->d_conv[w], addr[w].data(), addr[w].size() * sizeof(uint64_t), hipMemcpyHostToDevice));
+    }
+    if (!jobs.empty()) {
+        if ((rc = dev_alloc(&c->d_jobs, jobs.size()))) return rc;
+        HIP_TRY(hipMemcpy(c->d_jobs, jobs.data(), jobs.size() * sizeof(ConvertJob), hipMemcpyHostToDevice));
+        HIP_TRY(launch_convert(c->d_jobs, (int)jobs.size(), max_n16, A.d_exp, B.d_exp, s));
+    }
+    A.last_stream = B.last_stream = s;
+    c->conv_active = true;
+    return GEMM_MP_OK;
+}
+
+int gemm_mp_clear_conversion(gemm_mp_ctx *c)
+{
+    if (!c) return GEMM_MP_EINVAL;
+    c->conv_active = false;
     return GEMM_MP_OK;
 }
 
@@ -511,6 +624,8 @@ int gemm_mp_get_stats(gemm_mp_ctx *c, gemm_mp_stats *out)
         c->d_q = nullptr; c->d_items = nullptr; c->d_prod = nullptr;
     }
     *out = c->stats;
+    out->converted_tiles = c->conv_active ? c->conv_tiles : 0;
+    out->converted_bytes = c->conv_active ? c->conv_bytes : 0;
     return GEMM_MP_OK;
 }
 

@@ -44,10 +44,21 @@ struct WorkItem {
 // is [MT*NT][KT] (C tile major) and is rebuilt on the device before every run from the maps,
 // offsets and exponents current at that time.
 struct ProductDesc {
-    uint64_t a_off, b_off;   // byte offsets of the two operand tiles in the packed A / B storage
+    uint64_t a_ptr, b_ptr;   // device addresses of the two operand tiles (packed storage, or the
+                             // sender-side workspace when a converted copy exists)
     int32_t ea, eb;          // their scale exponents
-    uint32_t codes;          // pA | pB << 8 | q << 16
+    uint32_t codes;          // pA | pB << 8 | q << 16, pA / pB as the kernel finds them there
     uint32_t pad;
+};
+
+// One sender-side conversion: tile `tile` of a packed matrix (precision p at src) to precision
+// q at dst; n16 = number of 16-byte segments of the result.
+struct ConvertJob {
+    uint64_t src, dst;
+    uint32_t tile;           // index into the matrix's exponent table
+    uint8_t p, q, which, pad;
+    uint32_t n16;
+    uint32_t pad2;
 };
 
 static_assert(sizeof(ProductDesc) == 32, "the kernel reads a record as two 16-byte scalar loads");
@@ -57,6 +68,8 @@ struct GemmArgs {
     PackedView A, B, C;
     const uint8_t *q;        // [MT*NT][KT] product precision of every task
     ProductDesc *prod;       // [MT*NT][KT] (+ padding records), written by launch_gemm
+    const uint64_t *convA;   // [tiles of A][4] address of the copy converted to q, 0 = none; or null
+    const uint64_t *convB;   // same for B
     const WorkItem *items64;  // owner regions of FP64 C tiles, launch order
     const WorkItem *items32;  // owner regions of FP32 C tiles, launch order
     int32_t n_items64, n_items32;
@@ -75,6 +88,8 @@ hipError_t launch_pack(const double *X, int64_t ld, int rows_t, int cols_t, int 
 hipError_t launch_unpack(double *X, int64_t ld, int rows_t, int cols_t, int nb, bool transpose,
                          PackedView v, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);
+hipError_t launch_convert(const ConvertJob *jobs_dev, int njobs, uint32_t max_n16, const int32_t *expA, const int32_t *expB,
+                          hipStream_t s);
 hipError_t gemm_kernel_setup();
 
 }  // namespace gmp

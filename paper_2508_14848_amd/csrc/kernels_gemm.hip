@@ -177,7 +177,6 @@ struct Region {
     int nb, arow0, brow0;
     int kt_eff;                     // number of reduction tiles to process (0 when alpha == 0)
     const ProductDesc *prod;        // this C tile's row of the product table: entry L
-    const char *sa, *sb;            // packed A and B storage
 };
 
 // On FP32 C tiles, FP16 / FP8 products whose operands are both stored in the product's precision
@@ -306,12 +305,12 @@ typedef const __attribute__((address_space(4))) u32x4 *ConstQuad;
 __device__ __forceinline__ Product make_product(const u32x4 lo, const u32x4 hi, const Geometry &G, const Region &R)
 {
     Product pr;
-    const uint64_t offa = (uint64_t)lo.x | ((uint64_t)lo.y << 32), offb = (uint64_t)lo.z | ((uint64_t)lo.w << 32);
+    const uint64_t pta = (uint64_t)lo.x | ((uint64_t)lo.y << 32), ptb = (uint64_t)lo.z | ((uint64_t)lo.w << 32);
     const int ea = (int)hi.x, eb = (int)hi.y;
     const int pa = (int)(hi.z & 0xffu), pb = (int)((hi.z >> 8) & 0xffu), q = (int)((hi.z >> 16) & 0xffu);
     pr.q = q;
-    pr.a = make_operand(R.sa + offa, pa, ea, q, R.arow0, G, R.nb);
-    pr.b = make_operand(R.sb + offb, pb, eb, q, R.brow0, G, R.nb);
+    pr.a = make_operand((const char *)(uintptr_t)pta, pa, ea, q, R.arow0, G, R.nb);
+    pr.b = make_operand((const char *)(uintptr_t)ptb, pb, eb, q, R.brow0, G, R.nb);
     return pr;
 }
 __device__ __forceinline__ Product open_product(int I, int J, int tileC, int L, const Geometry &G, const Region &R)
@@ -1005,8 +1004,6 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     R.arow0 = (int)((itw >> 32) & 0xffffu) * kMacro;
     R.brow0 = (int)((itw >> 48) & 0xffffu) * kMacro;
     R.prod = K0->prod + (int64_t)tileC * K0->KT;
-    R.sa = K0->A.storage;
-    R.sb = K0->B.storage;
 
     AccS s[4][4];
 #pragma unroll
@@ -1146,8 +1143,12 @@ hipError_t gemm_kernel_setup()
                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
 }
 
-// One thread per task (C tile, L): gather what the owner workgroups need into one record.
+// One thread per task (C tile, L): gather what the owner workgroups need into one record.  With
+// sender-side conversion a tile whose stored precision differs from the task's has a copy in
+// that precision: the record then points there and carries the copy's precision (and, for
+// FP64 / FP32 copies, exponent 0: the scale is already applied).
 __global__ void product_table_kernel(PackedView A, PackedView B, const uint8_t *__restrict__ q, int MT, int NT, int KT,
+                                     const uint64_t *__restrict__ convA, const uint64_t *__restrict__ convB,
                                      ProductDesc *__restrict__ out)
 {
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1156,14 +1157,60 @@ __global__ void product_table_kernel(PackedView A, PackedView B, const uint8_t *
     const int tileC = (int)(idx / KT);
     const int I = tileC / NT, J = tileC % NT;
     const int64_t ta = (int64_t)I * KT + L, tb = (int64_t)L * NT + J;
+    const uint32_t qq = q[idx];
     ProductDesc d;
-    d.a_off = A.offset[ta];
-    d.b_off = B.offset[tb];
+    uint32_t pa = A.prec[ta], pb = B.prec[tb];
+    d.a_ptr = (uint64_t)(uintptr_t)(A.storage + A.offset[ta]);
+    d.b_ptr = (uint64_t)(uintptr_t)(B.storage + B.offset[tb]);
     d.ea = A.exp[ta];
     d.eb = B.exp[tb];
-    d.codes = (uint32_t)A.prec[ta] | ((uint32_t)B.prec[tb] << 8) | ((uint32_t)q[idx] << 16);
+    if (convA && pa != qq && convA[ta * 4 + qq]) {
+        d.a_ptr = convA[ta * 4 + qq];
+        pa = qq;
+        if (qq <= (uint32_t)Q32) d.ea = 0;
+    }
+    if (convB && pb != qq && convB[tb * 4 + qq]) {
+        d.b_ptr = convB[tb * 4 + qq];
+        pb = qq;
+        if (qq <= (uint32_t)Q32) d.eb = 0;
+    }
+    d.codes = pa | (pb << 8) | (qq << 16);
     d.pad = 0;
     out[idx] = d;
+}
+
+// Sender-side conversion of whole tiles: one thread per 16-byte segment of the result, using
+// the very conversion the owner workgroups apply on the fly (convert<Q>), so a converted copy
+// holds bit for bit what the receiver-side path would have put into LDS.
+__global__ __launch_bounds__(256) void convert_tiles_kernel(const ConvertJob *__restrict__ jobs, const int32_t *__restrict__ expA,
+                                                            const int32_t *__restrict__ expB)
+{
+    const ConvertJob job = jobs[blockIdx.y];
+    const uint32_t seg = blockIdx.x * 256u + threadIdx.x;
+    if (seg >= job.n16) return;
+    const int p = job.p, q = job.q;
+    const int e = (job.which == 0 ? expA : expB)[job.tile];
+    const uint64_t src_byte = ((uint64_t)seg * (uint64_t)(2u << q)) << (3 - p);   // first source byte of this segment
+    const char *src = (const char *)(uintptr_t)job.src + (src_byte & ~(uint64_t)15);
+    Raw r;
+    r.lo = *(const u32x4 *)src;
+    r.hi = (q == Q32 && p == Q64) ? *(const u32x4 *)(src + 16) : r.lo;
+    const int sub = (int)(src_byte & 15);
+    u32x4 out;
+    switch (q) {
+    case Q64: out = convert<Q64>(r, p, e, sub); break;
+    case Q32: out = convert<Q32>(r, p, e, sub); break;
+    default:  out = convert<Q16>(r, p, e, sub); break;
+    }
+    *(u32x4 *)((char *)(uintptr_t)job.dst + (uint64_t)seg * 16) = out;
+}
+
+hipError_t launch_convert(const ConvertJob *jobs_dev, int njobs, uint32_t max_n16, const int32_t *expA, const int32_t *expB,
+                          hipStream_t s)
+{
+    if (njobs <= 0) return hipSuccess;
+    convert_tiles_kernel<<<dim3((max_n16 + 255u) / 256u, (unsigned)njobs), dim3(256), 0, s>>>(jobs_dev, expA, expB);
+    return hipGetLastError();
 }
 
 // The product table, then two launches at most: the owner regions of FP64 C tiles, then those
@@ -1171,7 +1218,7 @@ __global__ void product_table_kernel(PackedView A, PackedView B, const uint8_t *
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
     const int64_t tasks = (int64_t)a.MT * a.NT * a.KT;
-    product_table_kernel<<<dim3((unsigned)((tasks + 255) / 256)), dim3(256), 0, s>>>(a.A, a.B, a.q, a.MT, a.NT, a.KT, a.prod);
+    product_table_kernel<<<dim3((unsigned)((tasks + 255) / 256)), dim3(256), 0, s>>>(a.A, a.B, a.q, a.MT, a.NT, a.KT, a.convA, a.convB, a.prod);
     if (a.n_items64 > 0)
         gemm_mp_owner_kernel<double><<<dim3((unsigned)a.n_items64), dim3(kThreads), kLdsBytes, s>>>(a, a.items64);
     if (a.n_items32 > 0)

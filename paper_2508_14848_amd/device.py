@@ -56,6 +56,17 @@ class DeviceGemmMP:
     def run(self, alpha, beta):
         self.ctx.run(float(alpha), float(beta), _stream())
 
+    def convert_tiles(self):
+        """Sender-side conversion: allocate the workspace and fill it; returns its size in bytes."""
+        n = self.ctx.conversion_bytes()
+        self.workspace = torch.empty(max(n, 256), dtype=torch.uint8, device=self.device)
+        assert self.workspace.data_ptr() % 256 == 0
+        self.ctx.convert_tiles(self.workspace.data_ptr(), self.workspace.numel(), _stream())
+        return n
+
+    def clear_conversion(self):
+        self.ctx.clear_conversion()
+
     def unpack_tiles(self, which, out=None):
         rows, cols = self.ctx.tiles(which)
         nb = self.ctx.nb

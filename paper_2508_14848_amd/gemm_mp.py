@@ -23,13 +23,15 @@ EXPORTS = [
     "gemm_mp_tile_scan", "gemm_mp_compute_precision_map", "gemm_mp_storage_bytes",
     "gemm_mp_bind_storage", "gemm_mp_pack_tiles", "gemm_mp_run", "gemm_mp_unpack_tiles",
     "gemm_mp_tile_info", "gemm_mp_get_stats", "gemm_mp_product_precision", "gemm_mp_strerror",
+    "gemm_mp_conversion_bytes", "gemm_mp_convert_tiles", "gemm_mp_clear_conversion",
 ]
 
 
 class Stats(ctypes.Structure):
     _fields_ = [("products", ctypes.c_int64 * 4), ("flops", ctypes.c_double * 4),
                 ("tiles", (ctypes.c_int64 * 4) * 3), ("packed_bytes", ctypes.c_uint64 * 3),
-                ("work_items", ctypes.c_int64)]
+                ("work_items", ctypes.c_int64), ("converted_tiles", ctypes.c_int64),
+                ("converted_bytes", ctypes.c_uint64)]
 
 
 class GemmMPError(RuntimeError):
@@ -61,6 +63,9 @@ def lib():
         L.gemm_mp_pack_tiles.argtypes = [P, c, P, i64, P]
         L.gemm_mp_run.argtypes = [P, dbl, dbl, P]
         L.gemm_mp_unpack_tiles.argtypes = [P, c, P, i64, P]
+        L.gemm_mp_conversion_bytes.argtypes = [P, ctypes.POINTER(ctypes.c_size_t)]
+        L.gemm_mp_convert_tiles.argtypes = [P, P, ctypes.c_size_t, P]
+        L.gemm_mp_clear_conversion.argtypes = [P]
         L.gemm_mp_tile_info.argtypes = [P, c, i32, i32, ctypes.POINTER(ctypes.c_size_t),
                                         ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
         L.gemm_mp_get_stats.argtypes = [P, ctypes.POINTER(Stats)]
@@ -156,6 +161,17 @@ class GemmMP:
     def run(self, alpha, beta, stream=None):
         _check(lib().gemm_mp_run(self._h, alpha, beta, stream), "gemm_mp_run")
 
+    def conversion_bytes(self):
+        n = ctypes.c_size_t()
+        _check(lib().gemm_mp_conversion_bytes(self._h, ctypes.byref(n)), "gemm_mp_conversion_bytes")
+        return n.value
+
+    def convert_tiles(self, workspace_ptr, nbytes, stream=None):
+        _check(lib().gemm_mp_convert_tiles(self._h, workspace_ptr, nbytes, stream), "gemm_mp_convert_tiles")
+
+    def clear_conversion(self):
+        _check(lib().gemm_mp_clear_conversion(self._h), "gemm_mp_clear_conversion")
+
     def unpack_tiles(self, which, dense_ptr, ld, stream=None):
         _check(lib().gemm_mp_unpack_tiles(self._h, _w(which), dense_ptr, ld, stream), "gemm_mp_unpack_tiles")
 
@@ -170,4 +186,5 @@ class GemmMP:
         _check(lib().gemm_mp_get_stats(self._h, ctypes.byref(s)), "gemm_mp_get_stats")
         return {"products": list(s.products), "flops": list(s.flops),
                 "tiles": [list(s.tiles[w]) for w in range(3)], "packed_bytes": list(s.packed_bytes),
-                "work_items": s.work_items}
+                "work_items": s.work_items, "converted_tiles": s.converted_tiles,
+                "converted_bytes": s.converted_bytes}

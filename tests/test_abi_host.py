@@ -121,3 +121,38 @@ def test_product_precision_and_stats_closed_forms():
     n64 = int((w.mapC == 0).sum())
     g.set_policy(G.POLICY_C_TILE)
     assert g.get_stats()["products"] == [n64 * 16, (256 - n64) * 16, 0, 0]
+
+
+def test_sender_side_conversion_plan_closed_forms():
+    """Workspace size = one copy per (tile, product precision != stored precision) that some task
+    needs; host logic only."""
+    nb = 128
+    g = G.GemmMP(2 * nb, 2 * nb, 2 * nb, nb)
+    with pytest.raises(G.GemmMPError) as e:
+        g.conversion_bytes()
+    assert e.value.status == G.ESTATE
+    full = lambda p: np.full((2, 2), p, dtype=np.uint16)
+    g.set_precision_map("A", full(G.FP64))
+    g.set_precision_map("B", full(G.FP32))
+    g.set_precision_map("C", full(G.FP64))
+    # every product is FP64: the four FP32 tiles of B need an FP64 copy, A needs nothing
+    assert g.conversion_bytes() == 4 * nb * nb * 8
+    g.set_precision_map("C", full(G.FP32))
+    # now every product is FP32: the four FP64 tiles of A need an FP32 copy
+    assert g.conversion_bytes() == 4 * nb * nb * 4
+    mC = np.array([[G.FP64, G.FP32], [G.FP32, G.FP32]], dtype=np.uint16)
+    g.set_precision_map("C", mC)
+    # C(0,0) runs FP64 products: B(0,0), B(1,0) up; all other C tiles run FP32: A(0,:) and A(1,:) down
+    assert g.conversion_bytes() == 2 * nb * nb * 8 + 4 * nb * nb * 4
+    g.set_precision_map("A", full(G.FP8_E4M3))
+    g.set_precision_map("B", full(G.FP16))
+    g.set_precision_map("C", full(G.FP32))
+    # FP16 products: the FP8 tiles of A get FP16 copies
+    assert g.conversion_bytes() == 4 * nb * nb * 2
+    g.set_precision_map("B", full(G.FP8_E4M3))
+    assert g.conversion_bytes() == 0
+    assert g.get_stats()["converted_tiles"] == 0
+    with pytest.raises(G.GemmMPError) as e:
+        g.convert_tiles(0, 0, None)               # nothing is packed yet
+    assert e.value.status == G.ESTATE
+    g.clear_conversion()

@@ -298,6 +298,40 @@ def test_a_context_follows_new_maps_new_data_and_a_new_policy_between_runs():
     check(1)
 
 
+@pytest.mark.parametrize("policy", [0, 1])
+def test_sender_side_conversion_gives_the_same_c_bit_for_bit(policy):
+    """Converted copies hold exactly what the receiver-side path converts on the fly, so running
+    from them must not change a single bit of C; they must also be dropped when A is repacked."""
+    import torch
+    w = W.random_maps(M=512, N=768, K=1024, nb=256, probs=(0.25, 0.25, 0.25, 0.25), alpha=1.5, beta=0.5,
+                      name="sender-small")
+    A, B, C0 = _dense(w)
+    d, dev = gpu_problem(w, A, B, C0, policy=policy)
+    d.run(w.alpha, w.beta)
+    recv = d.unpack_tiles("C").cpu().numpy()
+    d.pack_tiles("C", dev["C"])
+    nbytes = d.convert_tiles()
+    st = d.ctx.get_stats()
+    assert st["converted_bytes"] == nbytes and (st["converted_tiles"] > 0) == (nbytes > 0)
+    if policy == 0:
+        assert nbytes > 0
+    d.run(w.alpha, w.beta)
+    send = d.unpack_tiles("C").cpu().numpy()
+    assert np.array_equal(send, recv)
+    side = OracleSide(w, A, B, C0)
+    jobs = _all_jobs(w)
+    compare_jobs(side, jobs, policy, w.alpha, w.beta, send, side.gemm(jobs, policy=policy))
+    # new data for A: the copies are stale and must not be used
+    A2 = A * 3.0
+    d.pack_tiles("A", torch.from_numpy(A2).cuda())
+    assert d.ctx.get_stats()["converted_tiles"] == 0
+    d.pack_tiles("C", dev["C"])
+    d.run(w.alpha, w.beta)
+    got = d.unpack_tiles("C").cpu().numpy()
+    side2 = OracleSide(w, A2, B, C0)
+    compare_jobs(side2, jobs, policy, w.alpha, w.beta, got, side2.gemm(jobs, policy=policy))
+
+
 def test_call_order_errors_on_the_device_path():
     import torch
     from paper_2508_14848_amd import gemm_mp as G
