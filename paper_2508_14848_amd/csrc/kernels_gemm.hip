@@ -425,11 +425,15 @@ __device__ __forceinline__ void read_frag_slot(u32x2 (&fr)[8], const char *fa, c
 
 // pr / c: product and chunk index of the chunk to stage (the next chunk of this product, or
 // chunk 0 of the next product when LAST).
-template <int Q, bool LAST, typename Acc>
+// STAGE: the LDS stage the chunk computes from when it is known at compile time (0 / 1; the
+// stage offsets then fold into the instructions' immediate offsets instead of costing vector
+// adds every chunk), -1: taken from `stage`.
+template <int Q, bool LAST, int STAGE = -1, typename Acc>
 __device__ __forceinline__ void pipelined_chunk(Acc (&acc)[4][4], u32x2 (&fr)[2][8], const Product &pr, int c, char *lds, int stage,
                                                 const FragBase &F, const Geometry &G, int nb)
 {
     Raw ra[4], rb[4];
+    if (STAGE >= 0) stage = STAGE;
     const char *fa = F.a + stage * kStage, *fb = F.b + stage * kStage;
     const char *na = F.a + (stage ^ 1) * kStage, *nbp = F.b + (stage ^ 1) * kStage;
     char *wst = lds + (stage ^ 1) * kStage;
@@ -479,9 +483,29 @@ __device__ __forceinline__ void steady_chunks(Acc (&acc)[4][4], u32x2 (&fr)[2][8
     Product cp = cur;
     cp.a.p = PA;
     cp.b.p = PB;
-    for (int c = 1; c < n; ++c) {
-        pipelined_chunk<Q, false>(acc, fr, cp, c, lds, stage, F, G, nb);
-        stage ^= 1;
+    int c = 1;
+    // Pure FP64 products (the slowest MFMAs, nothing to convert) run their chunks in pairs with
+    // the LDS stage a compile-time constant; measured +5 % on them.  The same unrolling slowed
+    // every other operand mix by 1-3 %, so those keep the one-chunk loop.
+    if constexpr (Q == Q64 && PA == Q64 && PB == Q64) {
+        if (stage == 1 && c < n) {                     // bring the loop to stage 0
+            pipelined_chunk<Q, false, 1>(acc, fr, cp, c, lds, 1, F, G, nb);
+            stage = 0;
+            ++c;
+        }
+        for (; c + 1 < n; c += 2) {                    // pairs of chunks with the stages known
+            pipelined_chunk<Q, false, 0>(acc, fr, cp, c, lds, 0, F, G, nb);
+            pipelined_chunk<Q, false, 1>(acc, fr, cp, c + 1, lds, 1, F, G, nb);
+        }
+        if (c < n) {
+            pipelined_chunk<Q, false, 0>(acc, fr, cp, c, lds, 0, F, G, nb);
+            stage = 1;
+        }
+    } else {
+        for (; c < n; ++c) {
+            pipelined_chunk<Q, false>(acc, fr, cp, c, lds, stage, F, G, nb);
+            stage ^= 1;
+        }
     }
 }
 
