@@ -24,6 +24,7 @@
 // so on the FP64 path lane i reads A row 4*(i%4) + i/4 instead of row i, which makes both
 // accumulator kinds address the same C element in the same lane and register.
 #include <type_traits>
+#include <utility>
 
 #include "gemm_mp_internal.h"
 
@@ -170,7 +171,8 @@ struct Geometry {
     bool ring;                      // FP32 C tiles only: pure FP16 / FP8 products go through the DMA ring
     int tid, lane, li, g, wm, wn;
     int seg_row, seg_part;          // staging: this thread's first row and its 16-byte part
-    int wbase;                      // byte offset of that segment in an LDS operand stage
+    int wbase;                      // byte offset of that segment in a padded LDS operand stage
+    int wsw;                        // the same in a swizzled stage (FP64 / FP32 products)
 };
 
 struct Region {
@@ -201,7 +203,7 @@ __device__ __forceinline__ int chunk_elems(int q) { return kRowBytes >> (3 - q);
 __device__ __forceinline__ Geometry fresh(const Geometry &G)
 {
     Geometry g = G;
-    asm volatile("" : "+v"(g.li), "+v"(g.g), "+v"(g.wm), "+v"(g.wn), "+v"(g.wbase), "+v"(g.seg_row), "+v"(g.seg_part));
+    asm volatile("" : "+v"(g.li), "+v"(g.g), "+v"(g.wm), "+v"(g.wn), "+v"(g.wbase), "+v"(g.wsw), "+v"(g.seg_row), "+v"(g.seg_part));
     return g;
 }
 
@@ -221,12 +223,26 @@ __device__ __forceinline__ void lds_store16(char *p, u32x4 v)     // rows are on
     *(u32x2 *)(p + 8) = u32x2{v.z, v.w};
 }
 
+// Two LDS layouts of an operand stage (128 rows of 128 converted bytes):
+//  - FP16 / FP8 products outside the ring: rows padded to 136 bytes;
+//  - FP64 / FP32 products: rows unpadded, the 16-byte segment s of row r stored in slot
+//    s ^ ((r >> 1) & 7).  Stores and fragment reads are then whole aligned 16-byte accesses
+//    (half as many instructions as with 8-byte ones, and every offset fits the instructions'
+//    immediate field: FP64 / FP32 MFMAs do not overlap with the vector ALU, so each address
+//    add saved is matrix time won), and both are free of bank conflicts: the sixteen lanes
+//    served together read sixteen consecutive rows, whose slots are distinct modulo 256 bytes.
 template <int Q>
 __device__ __forceinline__ void store_pair(const Raw &ra, const Raw &rb, const Product &pr, const Geometry &G, char *stage, int j)
 {
-    char *dst = stage + G.wbase + j * (32 * kRowStride);
-    lds_store16(dst, convert<Q>(ra, pr.a.p, pr.a.e, pr.a.sub));
-    lds_store16(dst + kOperandStage, convert<Q>(rb, pr.b.p, pr.b.e, pr.b.sub));
+    if constexpr (Q == Q64 || Q == Q32) {
+        char *dst = stage + G.wsw + j * (32 * kRowBytes);
+        *(u32x4 *)dst = convert<Q>(ra, pr.a.p, pr.a.e, pr.a.sub);
+        *(u32x4 *)(dst + kOperandStage) = convert<Q>(rb, pr.b.p, pr.b.e, pr.b.sub);
+    } else {
+        char *dst = stage + G.wbase + j * (32 * kRowStride);
+        lds_store16(dst, convert<Q>(ra, pr.a.p, pr.a.e, pr.a.sub));
+        lds_store16(dst + kOperandStage, convert<Q>(rb, pr.b.p, pr.b.e, pr.b.sub));
+    }
 }
 
 // The same for a product whose precision is only known at run time (the next tile product).
@@ -237,6 +253,47 @@ __device__ __forceinline__ void store_pair_any(const Raw &ra, const Raw &rb, con
     case Q32: store_pair<Q32>(ra, rb, pr, G, stage, j); break;
     case Q16: store_pair<Q16>(ra, rb, pr, G, stage, j); break;
     case Q8:  store_pair<Q8>(ra, rb, pr, G, stage, j);  break;
+    default: break;
+    }
+}
+
+// One operand of the same: piece i = 2 * (row block) + (0: A, 1: B).
+__device__ __forceinline__ void load_piece(Raw &r, const Product &pr, int nb, int c, int i)
+{
+    const int eoff = c * chunk_elems(pr.q) + (i >> 1) * 32 * nb;
+    const Operand &o = (i & 1) ? pr.b : pr.a;
+    load_seg(r, o, eoff << (3 - o.p), pr.q == Q32 && o.p == Q64);
+}
+// The same without control flow, for a product known only at run time: the second half is
+// always requested, through a descriptor of length zero (such a load touches no memory and
+// returns zeros) unless the piece is the one down-cast.
+__device__ __forceinline__ void load_piece_any(Raw &r, const Product &pr, int nb, int c, int i)
+{
+    const int eoff = c * chunk_elems(pr.q) + (i >> 1) * 32 * nb;
+    const Operand &o = (i & 1) ? pr.b : pr.a;
+    const bool down = pr.q == Q32 && o.p == Q64;
+    const int soff = eoff << (3 - o.p);
+    const __amdgpu_buffer_rsrc_t lo = __builtin_amdgcn_make_buffer_rsrc((void *)o.base, 0, o.bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t hi = __builtin_amdgcn_make_buffer_rsrc((void *)o.base, 0, down ? o.bytes : 0, 0x00020000);
+    r.lo = __builtin_amdgcn_raw_buffer_load_b128(lo, o.voff, soff, 0);
+    r.hi = __builtin_amdgcn_raw_buffer_load_b128(hi, o.voff + 16, soff, 0);
+}
+template <int Q>
+__device__ __forceinline__ void store_piece(const Raw &r, const Product &pr, const Geometry &G, char *stage, int i)
+{
+    static_assert(Q == Q64 || Q == Q32, "swizzled stages only");
+    const Operand &o = (i & 1) ? pr.b : pr.a;
+    char *dst = stage + G.wsw + (i >> 1) * (32 * kRowBytes) + (i & 1) * kOperandStage;
+    *(u32x4 *)dst = convert<Q>(r, o.p, o.e, o.sub);
+}
+__device__ __forceinline__ void store_piece_any(const Raw &r, const Product &pr, const Geometry &G, char *stage, int i)
+{
+    const Operand &o = (i & 1) ? pr.b : pr.a;
+    switch (pr.q) {
+    case Q64: store_piece<Q64>(r, pr, G, stage, i); break;
+    case Q32: store_piece<Q32>(r, pr, G, stage, i); break;
+    case Q16: lds_store16(stage + G.wbase + (i >> 1) * (32 * kRowStride) + (i & 1) * kOperandStage, convert<Q16>(r, o.p, o.e, o.sub)); break;
+    case Q8:  lds_store16(stage + G.wbase + (i >> 1) * (32 * kRowStride) + (i & 1) * kOperandStage, convert<Q8>(r, o.p, o.e, o.sub)); break;
     default: break;
     }
 }
@@ -331,65 +388,100 @@ struct Walk {
     int I, J, tileC;
 };
 
-// Per-lane LDS offsets of the fragment rows (stage 0): A rows of this wave's 64 x 64 part and B
-// rows; row block t adds t * 16 * kRowStride, macro-step m adds 8 m (or 16 m / 32 m).
+// Per-lane LDS offsets of the fragment rows in a padded stage (stage 0): A rows of this wave's
+// 64 x 64 part and B rows; row block t adds t * 16 * kRowStride, 8 w bytes select the word.
 struct FragBase {
     const char *a, *b;
 };
 template <int Q>
 __device__ __forceinline__ FragBase frag_base(const char *lds, const Geometry &G)
 {
-    // FP64 accumulators hold C[4v+g][i] where the FP32-result ones hold C[4g+v][i]; reading A row
-    // 4*(i%4) + i/4 in lane i on the FP64 path makes both address the same C element.
-    const int arow = (Q == Q64) ? 4 * (G.li & 3) + (G.li >> 2) : G.li;
     FragBase f;
-    f.a = lds + (G.wm * 64 + arow) * kRowStride + G.g * 32;
+    f.a = lds + (G.wm * 64 + G.li) * kRowStride + G.g * 32;
     f.b = lds + kOperandStage + (G.wn * 64 + G.li) * kRowStride + G.g * 32;
     return f;
 }
+// The same for a swizzled stage.  Lane (li, g) reads the two 16-byte segments 2g and 2g + 1 of
+// its row (macro-steps 0 and 1 of a chunk): element h of segment 2g + j is reduction index
+// (2g + j) * n + h of the chunk (n = 2 FP64 or 4 FP32 elements per segment) in A and B alike,
+// so each k-step's MFMA pairs equal indices; the order in which a chunk's indices are summed
+// is a permutation of the storage order.  Row block t adds t * 16 * kRowBytes.
+struct HiFrag {
+    const char *a[2], *b[2];
+};
+template <int Q>
+__device__ __forceinline__ HiFrag hi_frag(const char *lds, const Geometry &G)
+{
+    // FP64 accumulators hold C[4v+g][i] where the FP32-result ones hold C[4g+v][i]; reading A row
+    // 4*(i%4) + i/4 in lane i on the FP64 path makes both address the same C element.
+    const int arow = (Q == Q64) ? 4 * (G.li & 3) + (G.li >> 2) : G.li;
+    const int sa = (2 * G.g) ^ ((arow >> 1) & 7), sb = (2 * G.g) ^ ((G.li >> 1) & 7);
+    HiFrag f;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        f.a[j] = lds + (G.wm * 64 + arow) * kRowBytes + ((sa ^ j) * 16);
+        f.b[j] = lds + kOperandStage + (G.wn * 64 + G.li) * kRowBytes + ((sb ^ j) * 16);
+    }
+    return f;
+}
+__device__ __forceinline__ u32x4 lds_load16(const char *p) { return *(const u32x4 *)p; }
 __device__ __forceinline__ u32x2 lds_load8(const char *p) { return *(const u32x2 *)p; }
 
+// The FP32 accumulators of the FP64 / FP32 product loops live in fixed registers: accumulator
+// (mt, nt) of the pinned set is v[192 + 4 (4 mt + nt) : + 3].  Left to the register allocator,
+// every specialised loop gets its own assignment, with register-to-register copies on the way
+// in and out of each tile product's loop (pinning measured 0.5-1.5 % on FP32 tiles).  They are
+// vector registers, not accumulation registers (an MFMA takes either): the folds and the
+// epilogue, which are vector-ALU code, then work on them in place.
+// BASE: 192 = the pinned set (the running sum of an FP32 C tile), -1 = wherever the allocator
+// puts them (accumulation registers: the per-product accumulator of an FP64 C tile, whose
+// kernel has no vector registers to spare).
+#define GMP_VQUADS(X) X(192, 192, 195) X(196, 196, 199) X(200, 200, 203) X(204, 204, 207) X(208, 208, 211) X(212, 212, 215) X(216, 216, 219) X(220, 220, 223) X(224, 224, 227) X(228, 228, 231) X(232, 232, 235) X(236, 236, 239) X(240, 240, 243) X(244, 244, 247) X(248, 248, 251) X(252, 252, 255)
+template <int R>
+__device__ __forceinline__ void mfma_f32_at(f4 &acc, uint32_t a, uint32_t b)
+{
+#define X(R0, LO, HI) if constexpr (R == R0) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+{v[" #LO ":" #HI "]}"(acc) : "v"(a), "v"(b));
+    GMP_VQUADS(X)
+#undef X
+    if constexpr (R < 0) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
 // ---- FP64 / FP32 products: software-pipelined chunk loop -----------------------------------
-// A chunk is consumed in four macro-steps of 8 bytes of reduction index per lane: one FP64
-// k-step (16 MFMAs of 64 cycles) or two FP32 k-steps (32 MFMAs of 32 cycles), i.e. about 1024
-// matrix-core cycles each.  A macro-step is issued as four groups (one per 16-row block of A);
-// after each group comes a slot of other work, so that everything else hides under the MFMAs:
-//   macro-step 0      : global loads of the next chunk, 2 per slot
-//   macro-steps 0..2  : LDS reads of the next macro-step's fragments, 2 per slot
-//   macro-step 2      : conversion + LDS writes of the next chunk into the other stage
-//   macro-step 3      : barrier in slot 0, then LDS reads of the next chunk's first fragments
+// A chunk is two macro-steps of 16 bytes of reduction index per lane: two FP64 k-steps (32 MFMAs
+// of 64 cycles) or four FP32 k-steps (64 MFMAs of 32 cycles) each.  FP64 / FP32 MFMAs do not
+// overlap with vector-ALU instructions, and memory instructions issued in a burst stall the
+// MFMA stream far longer than the same instructions issued one at a time (measured: four LDS
+// writes back to back cost 140 cycles, one between MFMAs about 4).  The chunk is therefore a
+// sequence of 64 positions, one after every FP64 MFMA or every second FP32 MFMA, and each
+// position holds at most one other instruction:
+//   positions  0..15 : global loads of the next chunk (even) and LDS reads of macro-step 1's
+//                      fragments (odd)
+//   positions 34..48 : conversion + LDS write of the next chunk into the other stage (even)
+//   position  52     : barrier
+//   positions 53..60 : LDS reads of the next chunk's first fragments
 // fr[buf][0..3] = A fragments of row blocks 0..3, fr[buf][4..7] = B fragments.
-// POS: 1 = first group of a chunk, 2 = last group of a chunk, 0 = neither.
 // The FP32 MFMAs are written as asm so that the accumulator is read and written in place in an
 // accumulation register: left to itself the register allocator rotates the FP32 side
-// accumulators through other registers with a copy per loop iteration, and those copies are
-// vector-ALU instructions the FP32 MFMAs cannot hide.  Asm MFMAs are invisible to the compiler's
-// hazard handling, so the first one of a chunk carries wait states in front (a register copy
-// or zeroing may sit right before it) and the last one carries the wait states an 8-pass MFMA
-// needs before an ordinary instruction may touch its result.
-template <int Q, typename Acc>
-__device__ __forceinline__ void mfma_group(Acc (&acc)[4][4], const u32x2 (&fr)[8], int mt, int POS)
+// accumulators through other registers with a copy per loop iteration.  Asm MFMAs are invisible
+// to the compiler's hazard handling, so the first one of a chunk carries wait states in front (a
+// register copy or zeroing may sit right before it) and the last one carries the wait states an
+// 8-pass MFMA needs before an ordinary instruction may touch its result.
+// Half-quad u = 0..63 of a chunk: FP32: (macro-step j, row block mt, element h, columns nt0,
+// nt0 + 1); FP64: one MFMA.
+template <int Q, int BASE, int u, typename Acc>
+__device__ __forceinline__ void mfma_half(Acc (&acc)[4][4], const u32x4 (&fr)[2][8])
 {
+    constexpr int j = u >> 5, mt = (u >> 3) & 3;
     if constexpr (Q == Q64) {
-        const double a = as_double(fr[mt].x, fr[mt].y);
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
-            acc[mt][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, as_double(fr[4 + nt].x, fr[4 + nt].y), acc[mt][nt], 0, 0, 0);
+        constexpr int h = (u >> 2) & 1, nt = u & 3;
+        acc[mt][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(as_double(fr[j][mt][2 * h], fr[j][mt][2 * h + 1]),
+                                                           as_double(fr[j][4 + nt][2 * h], fr[j][4 + nt][2 * h + 1]), acc[mt][nt], 0, 0, 0);
     } else {
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
-                if (POS == 1 && sub == 0 && nt == 0)
-                    asm volatile("s_nop 3\n\tv_mfma_f32_16x16x4_f32 %0, %1, %2, %0"
-                                 : "+a"(acc[mt][nt]) : "v"(fr[mt][sub]), "v"(fr[4 + nt][sub]));
-                else if (POS == 2 && sub == 1 && nt == 3)
-                    asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0\n\ts_nop 11"
-                                 : "+a"(acc[mt][nt]) : "v"(fr[mt][sub]), "v"(fr[4 + nt][sub]));
-                else
-                    asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0"
-                                 : "+a"(acc[mt][nt]) : "v"(fr[mt][sub]), "v"(fr[4 + nt][sub]));
-            }
+        constexpr int h = (u >> 1) & 3, nt0 = (u & 1) * 2;
+        if constexpr (u == 0) asm volatile("s_nop 3");
+        mfma_f32_at<(BASE < 0 ? -1 : BASE + 4 * (4 * mt + nt0))>(acc[mt][nt0], fr[j][mt][h], fr[j][4 + nt0][h]);
+        mfma_f32_at<(BASE < 0 ? -1 : BASE + 4 * (4 * mt + nt0 + 1))>(acc[mt][nt0 + 1], fr[j][mt][h], fr[j][4 + nt0 + 1][h]);
+        if constexpr (u == 63) asm volatile("s_nop 11");
     }
 }
 
@@ -397,134 +489,145 @@ __device__ __forceinline__ void mfma_group(Acc (&acc)[4][4], const u32x2 (&fr)[8
 // fence takes all sixteen accumulators as in/out accumulation registers and waits 32 cycles:
 // whatever register copies the compiler needs are placed outside the fenced region, after the
 // last MFMA has retired and long enough before the first one issues.
-template <typename Acc>
+template <int BASE, typename Acc>
 __device__ __forceinline__ void acc_fence(Acc (&acc)[4][4])
 {
     if constexpr (std::is_same<Acc, f4>::value) {
-        asm volatile("s_nop 15\n\ts_nop 15"
-                     : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]),
-                       "+a"(acc[1][0]), "+a"(acc[1][1]), "+a"(acc[1][2]), "+a"(acc[1][3]),
-                       "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),
-                       "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3]));
+        if constexpr (BASE < 0)
+            asm volatile("s_nop 15\n\ts_nop 15"
+                         : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]),
+                           "+a"(acc[1][0]), "+a"(acc[1][1]), "+a"(acc[1][2]), "+a"(acc[1][3]),
+                           "+a"(acc[2][0]), "+a"(acc[2][1]), "+a"(acc[2][2]), "+a"(acc[2][3]),
+                           "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]), "+a"(acc[3][3]));
+        if constexpr (BASE == 192) asm volatile("s_nop 15\n\ts_nop 15" : "+{v[192:195]}"(acc[0][0]), "+{v[196:199]}"(acc[0][1]), "+{v[200:203]}"(acc[0][2]), "+{v[204:207]}"(acc[0][3]), "+{v[208:211]}"(acc[1][0]), "+{v[212:215]}"(acc[1][1]), "+{v[216:219]}"(acc[1][2]), "+{v[220:223]}"(acc[1][3]), "+{v[224:227]}"(acc[2][0]), "+{v[228:231]}"(acc[2][1]), "+{v[232:235]}"(acc[2][2]), "+{v[236:239]}"(acc[2][3]), "+{v[240:243]}"(acc[3][0]), "+{v[244:247]}"(acc[3][1]), "+{v[248:251]}"(acc[3][2]), "+{v[252:255]}"(acc[3][3]));
     }
 }
 
-// Order in which the eight fragments of a macro-step are fetched, two per slot: the B fragments
-// first, so that A block 0 (needed first) is never the last to arrive.
-__device__ __forceinline__ void read_frag_slot(u32x2 (&fr)[8], const char *fa, const char *fb, int m, int slot)
+// Fragment t (0..3: A row blocks, 4..7: B row blocks) of macro-step j from the stage at byte
+// offset `so`.
+__device__ __forceinline__ u32x4 read_frag(const HiFrag &F, int so, int j, int t)
 {
-    constexpr int kBlock = 16 * kRowStride;
-    if (slot < 2) {
-        fr[4 + 2 * slot] = lds_load8(fb + (2 * slot) * kBlock + 8 * m);
-        fr[5 + 2 * slot] = lds_load8(fb + (2 * slot + 1) * kBlock + 8 * m);
-    } else {
-        fr[2 * slot - 4] = lds_load8(fa + (2 * slot - 4) * kBlock + 8 * m);
-        fr[2 * slot - 3] = lds_load8(fa + (2 * slot - 3) * kBlock + 8 * m);
-    }
+    constexpr int kBlock = 16 * kRowBytes;
+    return t < 4 ? lds_load16(F.a[j] + so + t * kBlock) : lds_load16(F.b[j] + so + (t - 4) * kBlock);
 }
 
-// pr / c: product and chunk index of the chunk to stage (the next chunk of this product, or
-// chunk 0 of the next product when LAST).
+// One position of a chunk: MFMAs, then at most one other instruction.
+// pr / c: product and chunk index of the chunk to fetch: the next chunk of this product, or,
+// when LAST, chunk 0 of the next product, which is only loaded into `r`: its conversion is
+// specialised on that product's stored precisions and therefore left to that product's loop.
+struct ChunkCtx {
+    int so, no;        // byte offsets of the stage computed from and of the one being filled
+    char *wst;         // the latter's address
+};
+// MODE: 0 = a chunk followed by another of the same product; 1 = the last chunk, which also
+// stages chunk 0 of the next product (conversion chosen at run time); 2 = the last chunk, which
+// only loads it into `r` (the next product's own loop converts and stores it).
+template <int Q, int BASE, int MODE, int u, typename Acc>
+__device__ __forceinline__ void chunk_position(Acc (&acc)[4][4], u32x4 (&fr)[2][8], Raw (&r)[8], const Product &pr, int c, const ChunkCtx &X,
+                                               const HiFrag &F, const Geometry &G, int nb)
+{
+    mfma_half<Q, BASE, u>(acc, fr);
+    SCHED_FENCE();
+    if constexpr (u < 16 && (u & 1) == 0) {
+        if constexpr (MODE != 0) load_piece_any(r[u >> 1], pr, nb, c, u >> 1);
+        else load_piece(r[u >> 1], pr, nb, c, u >> 1);
+    } else if constexpr (u < 16) {
+        constexpr int t = ((u >> 1) + 4) & 7;                // B0..B3, A0..A3
+        fr[1][t] = read_frag(F, X.so, 1, t);
+    } else if constexpr (MODE != 2 && u >= 34 && u <= 48 && (u & 1) == 0) {
+        constexpr int i = (u - 34) >> 1;
+        if constexpr (MODE == 0) store_piece<Q>(r[i], pr, G, X.wst, i);
+        else store_piece_any(r[i], pr, G, X.wst, i);   // q < 0 (nothing follows): stores nothing
+    } else if constexpr (MODE != 2 && u == 52) {
+        __syncthreads();
+    } else if constexpr (MODE == 0 && u >= 53 && u <= 60) {
+        constexpr int t = (u - 53 + 4) & 7;                  // B0..B3, A0..A3
+        fr[0][t] = read_frag(F, X.no, 0, t);
+    }
+    SCHED_FENCE();
+}
+template <int Q, int BASE, int MODE, typename Acc, int... U>
+__device__ __forceinline__ void chunk_positions(Acc (&acc)[4][4], u32x4 (&fr)[2][8], Raw (&r)[8], const Product &pr, int c, const ChunkCtx &X,
+                                                const HiFrag &F, const Geometry &G, int nb, std::integer_sequence<int, U...>)
+{
+    (chunk_position<Q, BASE, MODE, U>(acc, fr, r, pr, c, X, F, G, nb), ...);
+}
 // STAGE: the LDS stage the chunk computes from when it is known at compile time (0 / 1; the
 // stage offsets then fold into the instructions' immediate offsets instead of costing vector
 // adds every chunk), -1: taken from `stage`.
-template <int Q, bool LAST, int STAGE = -1, typename Acc>
-__device__ __forceinline__ void pipelined_chunk(Acc (&acc)[4][4], u32x2 (&fr)[2][8], const Product &pr, int c, char *lds, int stage,
-                                                const FragBase &F, const Geometry &G, int nb)
+template <int Q, int BASE, int MODE, int STAGE = -1, typename Acc>
+__device__ __forceinline__ void pipelined_chunk(Acc (&acc)[4][4], u32x4 (&fr)[2][8], Raw (&r)[8], const Product &pr, int c, char *lds, int stage,
+                                                const HiFrag &F, const Geometry &G, int nb)
 {
-    Raw ra[4], rb[4];
     if (STAGE >= 0) stage = STAGE;
-    const char *fa = F.a + stage * kStage, *fb = F.b + stage * kStage;
-    const char *na = F.a + (stage ^ 1) * kStage, *nbp = F.b + (stage ^ 1) * kStage;
-    char *wst = lds + (stage ^ 1) * kStage;
-#pragma unroll
-    for (int m = 0; m < 4; ++m) {
-#pragma unroll
-        for (int grp = 0; grp < 4; ++grp) {
-            mfma_group<Q>(acc, fr[m & 1], grp, (m == 0 && grp == 0) ? 1 : (m == 3 && grp == 3) ? 2 : 0);
-            SCHED_FENCE();
-            if (m == 0) {
-                if (!LAST || wants_first_chunk(pr, G)) load_pair(ra[grp], rb[grp], pr, nb, c, grp);
-            }
-            if (m < 3) read_frag_slot(fr[(m + 1) & 1], fa, fb, m + 1, grp);
-            if (m == 2) {
-                if constexpr (LAST) {
-                    if (wants_first_chunk(pr, G)) store_pair_any(ra[grp], rb[grp], pr, G, wst, grp);
-                }
-                else store_pair<Q>(ra[grp], rb[grp], pr, G, wst, grp);
-            }
-            if (m == 3) {
-                if (grp == 0) __syncthreads();
-                if constexpr (!LAST) {
-                    // first fragments of the next chunk: B0 B1 B2 | B3 A0 A1 | A2 A3
-                    constexpr int kBlock = 16 * kRowStride;
-                    if (grp == 1) {
-                        fr[0][4] = lds_load8(nbp); fr[0][5] = lds_load8(nbp + kBlock); fr[0][6] = lds_load8(nbp + 2 * kBlock);
-                    } else if (grp == 2) {
-                        fr[0][7] = lds_load8(nbp + 3 * kBlock); fr[0][0] = lds_load8(na); fr[0][1] = lds_load8(na + kBlock);
-                    } else if (grp == 3) {
-                        fr[0][2] = lds_load8(na + 2 * kBlock); fr[0][3] = lds_load8(na + 3 * kBlock);
-                    }
-                }
-            }
-            SCHED_FENCE();
-        }
-    }
+    ChunkCtx X;
+    X.so = stage * kStage;
+    X.no = (stage ^ 1) * kStage;
+    X.wst = lds + X.no;
+    chunk_positions<Q, BASE, MODE>(acc, fr, r, pr, c, X, F, G, nb, std::make_integer_sequence<int, 64>{});
 }
 
-// All chunks of one FP64 / FP32 tile product.  On entry LDS stage `stage` holds the product's
-// first chunk; on exit it holds the first chunk of the next product (if any).
-// Chunks 1..n-1 of a product whose operands are stored at precisions PA, PB: with both known
-// at compile time the staging code is straight-line (no conversion at all when PA = PB = Q).
-template <int Q, int PA, int PB, typename Acc>
-__device__ __forceinline__ void steady_chunks(Acc (&acc)[4][4], u32x2 (&fr)[2][8], const Product &cur, int n, char *lds, int &stage,
-                                              const FragBase &F, const Geometry &G, int nb)
+// All but the last chunk of a product whose operands are stored at precisions PA, PB: with
+// both known at compile time the staging code is straight-line (no conversion at all when
+// PA = PB = Q).  On entry the product's chunk 0 is either staged in LDS stage `stage` or, when
+// `raw`, still in `hand` as loaded by the preceding product's last chunk.
+template <int Q, int BASE, int PA, int PB, typename Acc>
+__device__ __forceinline__ void steady_chunks(Acc (&acc)[4][4], u32x4 (&fr)[2][8], const Product &cur, int n, char *lds, int &stage,
+                                              const HiFrag &F, const Geometry &G, int nb, Raw (&hand)[8], bool raw)
 {
     Product cp = cur;
+    cp.q = Q;
     cp.a.p = PA;
     cp.b.p = PB;
+    if (raw) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) store_piece<Q>(hand[i], cp, G, lds + stage * kStage, i);
+        __syncthreads();
+    }
+#pragma unroll
+    for (int t = 4; t < 12; ++t) fr[0][t & 7] = read_frag(F, stage * kStage, 0, t & 7);
+    acc_fence<BASE>(acc);
+    Raw r[8];
     int c = 1;
     // Pure FP64 products (the slowest MFMAs, nothing to convert) run their chunks in pairs with
     // the LDS stage a compile-time constant; measured +5 % on them.  The same unrolling slowed
     // every other operand mix by 1-3 %, so those keep the one-chunk loop.
     if constexpr (Q == Q64 && PA == Q64 && PB == Q64) {
         if (stage == 1 && c < n) {                     // bring the loop to stage 0
-            pipelined_chunk<Q, false, 1>(acc, fr, cp, c, lds, 1, F, G, nb);
+            pipelined_chunk<Q, BASE, 0, 1>(acc, fr, r, cp, c, lds, 1, F, G, nb);
             stage = 0;
             ++c;
         }
         for (; c + 1 < n; c += 2) {                    // pairs of chunks with the stages known
-            pipelined_chunk<Q, false, 0>(acc, fr, cp, c, lds, 0, F, G, nb);
-            pipelined_chunk<Q, false, 1>(acc, fr, cp, c + 1, lds, 1, F, G, nb);
+            pipelined_chunk<Q, BASE, 0, 0>(acc, fr, r, cp, c, lds, 0, F, G, nb);
+            pipelined_chunk<Q, BASE, 0, 1>(acc, fr, r, cp, c + 1, lds, 1, F, G, nb);
         }
         if (c < n) {
-            pipelined_chunk<Q, false, 0>(acc, fr, cp, c, lds, 0, F, G, nb);
+            pipelined_chunk<Q, BASE, 0, 0>(acc, fr, r, cp, c, lds, 0, F, G, nb);
             stage = 1;
         }
     } else {
         for (; c < n; ++c) {
-            pipelined_chunk<Q, false>(acc, fr, cp, c, lds, stage, F, G, nb);
+            pipelined_chunk<Q, BASE, 0>(acc, fr, r, cp, c, lds, stage, F, G, nb);
             stage ^= 1;
         }
     }
 }
 
-// All chunks of one FP64 / FP32 tile product.  On entry LDS stage `stage` holds the product's
-// first chunk; on exit it holds the first chunk of the next product (if any), which is returned.
-template <int Q, typename Acc>
+// All chunks of one FP64 / FP32 tile product; returns the next product.  On exit that one's
+// chunk 0 is in `hand` (raw = true: it is an FP64 / FP32 product too), or staged in LDS stage
+// `stage` (any other product that wants it).
+template <int Q, int BASE, bool LATE, typename Acc>
 __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
-                                                          const Geometry &G0, const Region &R)
+                                                          const Geometry &G0, const Region &R, Raw (&hand)[8], bool &raw)
 {
     const Geometry G = fresh(G0);
-    const FragBase F = frag_base<Q>(lds, G);
-    u32x2 fr[2][8];
-#pragma unroll
-    for (int slot = 0; slot < 4; ++slot) read_frag_slot(fr[0], F.a + stage * kStage, F.b + stage * kStage, 0, slot);
+    const HiFrag F = hi_frag<Q>(lds, G);
+    u32x4 fr[2][8];
     const int n = R.nb / (kRowBytes >> (3 - Q));
     // the following product's descriptors: read now, needed only at this product's last chunk
     const Product next = open_product(W.I, W.J, W.tileC, Lnext, G, R);
-    acc_fence(acc);
-#define GMP_STEADY(PA, PB) case (PA) * 4 + (PB): steady_chunks<Q, PA, PB>(acc, fr, cur, n, lds, stage, F, G, R.nb); break;
+#define GMP_STEADY(PA, PB) case (PA) * 4 + (PB): steady_chunks<Q, BASE, PA, PB>(acc, fr, cur, n, lds, stage, F, G, R.nb, hand, raw); break;
     switch (cur.a.p * 4 + cur.b.p) {
         GMP_STEADY(0, 0) GMP_STEADY(0, 1) GMP_STEADY(0, 2) GMP_STEADY(0, 3)
         GMP_STEADY(1, 0) GMP_STEADY(1, 1) GMP_STEADY(1, 2) GMP_STEADY(1, 3)
@@ -533,10 +636,28 @@ __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], cons
     default: break;
     }
 #undef GMP_STEADY
-    acc_fence(acc);
-    pipelined_chunk<Q, true>(acc, fr, next, 0, lds, stage, F, G, R.nb);
-    acc_fence(acc);
-    stage ^= 1;
+    acc_fence<BASE>(acc);
+    const bool want = wants_first_chunk(next, G);
+    Product ld = next;                                 // nothing to fetch: descriptors of length zero
+    ld.a.bytes = want ? next.a.bytes : 0;
+    ld.b.bytes = want ? next.b.bytes : 0;
+    if constexpr (LATE) {
+        pipelined_chunk<Q, BASE, 2>(acc, fr, hand, ld, 0, lds, stage, F, G, R.nb);
+        acc_fence<BASE>(acc);
+        stage ^= 1;
+        raw = want && next.q <= Q32;
+        if (want && !raw) {                            // a product of the padded two-stage loop: staged here
+#pragma unroll
+            for (int i = 0; i < 8; ++i) store_piece_any(hand[i], next, G, lds + stage * kStage, i);
+            __syncthreads();
+        }
+    } else {
+        if (!want) ld.q = -1;
+        pipelined_chunk<Q, BASE, 1>(acc, fr, hand, ld, 0, lds, stage, F, G, R.nb);
+        acc_fence<BASE>(acc);
+        stage ^= 1;
+        raw = false;
+    }
     return next;
 }
 
@@ -965,7 +1086,7 @@ __device__ __forceinline__ Product product_loop_simple(f4 (&acc)[4][4], const Pr
         for (int j = 0; j < 4; ++j) load_pair(ra[j], rb[j], next, R.nb, 0, j);
     }
     mma_padded<Q>(acc, lds, stage, G);
-    acc_fence(acc);
+    acc_fence<-1>(acc);
     if (give) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) store_pair_any(ra[j], rb[j], next, G, lds + (stage ^ 1) * kStage, j);
@@ -1015,6 +1136,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     G.seg_row = G.tid >> 3;
     G.seg_part = G.tid & 7;
     G.wbase = G.seg_row * kRowStride + G.seg_part * 16;
+    G.wsw = G.seg_row * kRowBytes + ((G.seg_part ^ ((G.seg_row >> 1) & 7)) * 16);
 
     // this workgroup's item and the kernel arguments it needs throughout: scalar loads
     const uint64_t itw = table_u64((const uint64_t *)items, blockIdx.x);
@@ -1046,6 +1168,8 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     }
     __syncthreads();
 
+    Raw hand[8];                                   // chunk 0 of an FP64 / FP32 product on its way from
+    bool raw = false;                              // its predecessor's last chunk to its own loop
     Walk W;
     W.I = I;
     W.J = J;
@@ -1074,7 +1198,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
             continue;
         }
         if (q == QT) {
-            next = product_loop_pipelined<QT>(s, cur, W, L + 1, lds, stage, G, R);
+            next = product_loop_pipelined<QT, (QT == Q32 ? 192 : -1), QT == Q32>(s, cur, W, L + 1, lds, stage, G, R, hand, raw);
         } else {
             if constexpr (QT == Q64) {
                 // an FP32 product of an FP64 C tile: its FP32 accumulator lives only for that product
@@ -1083,7 +1207,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
-                next = product_loop_pipelined<Q32>(t, cur, W, L + 1, lds, stage, G, R);
+                next = product_loop_pipelined<Q32, -1, false>(t, cur, W, L + 1, lds, stage, G, R, hand, raw);
                 fold(s, t, 0);
             } else {
                 next = cur;                        // not reachable: the host never schedules FP64 products on FP32 tiles
