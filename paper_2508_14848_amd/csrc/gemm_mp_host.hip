@@ -42,10 +42,11 @@ struct gemm_mp_ctx {
     Matrix mat[3];
     bool sched_current = false;
     std::vector<uint8_t> q;
-    std::vector<WorkItem> items[2];   // [0]: regions of FP64 C tiles, [1]: of FP32 C tiles
+    std::vector<WorkItem> items[3];   // regions of [0] FP64 C tiles, [1] FP32 C tiles, [2] FP32 C tiles
+                                      // whose products are all FP8 x FP8 (256 x 256 regions)
     uint8_t *d_q = nullptr;
     ProductDesc *d_prod = nullptr;    // one record per task (+ 2 padding records), filled on the device
-    WorkItem *d_items = nullptr;      // both lists, [0] first
+    WorkItem *d_items = nullptr;      // the three lists, [0] first
     gemm_mp_stats stats;
     bool kernel_ready = false;
     // sender-side conversion: per tile of A / B and product precision q, the offset of the copy
@@ -232,13 +233,27 @@ void build_schedule(gemm_mp_ctx *c)
         c->stats.packed_bytes[w] = c->mat[w].bytes;
     }
 
-    const int mr = c->nb / kMacro;
-    const size_t per_tile = (size_t)mr * mr;
+    // An FP32 C tile whose every product multiplies two tiles stored in FP8 at FP8 goes to the
+    // kernel with 256 x 256 regions (the tile size permitting).
+    std::vector<uint8_t> all_fp8((size_t)MT * NT, 0);
+    if (c->nb % kMacroFp8 == 0)
+        for (int I = 0; I < MT; ++I)
+            for (int J = 0; J < NT; ++J) {
+                bool ok = C.map[I * NT + J] == GEMM_MP_FP32 && KT > 0;
+                for (int L = 0; ok && L < KT; ++L)
+                    ok = c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_FP8_E4M3 && A.map[I * KT + L] == GEMM_MP_FP8_E4M3 &&
+                         B.map[L * NT + J] == GEMM_MP_FP8_E4M3;
+                all_fp8[(size_t)I * NT + J] = ok;
+            }
     constexpr int kBins = 8;
-    for (int list = 0; list < 2; ++list) {
+    for (int list = 0; list < 3; ++list) {
+        const int mr = c->nb / (list == 2 ? kMacroFp8 : kMacro);
+        const size_t per_tile = (size_t)mr * mr;
         std::vector<int> order;
-        for (int t = 0; t < MT * NT; ++t)
-            if ((C.map[t] == GEMM_MP_FP64) == (list == 0)) order.push_back(t);
+        for (int t = 0; t < MT * NT; ++t) {
+            const int which = C.map[t] == GEMM_MP_FP64 ? 0 : all_fp8[t] ? 2 : 1;
+            if (which == list) order.push_back(t);
+        }
         std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cost[a] > cost[b]; });
         std::vector<int> bins[kBins];
         double load[kBins] = {0};
@@ -269,7 +284,7 @@ void build_schedule(gemm_mp_ctx *c)
             }
         }
     }
-    c->stats.work_items = (int64_t)(c->items[0].size() + c->items[1].size());
+    c->stats.work_items = (int64_t)(c->items[0].size() + c->items[1].size() + c->items[2].size());
     c->sched_current = true;
 }
 
@@ -281,11 +296,12 @@ int upload_schedule(gemm_mp_ctx *c)
     if ((rc = dev_alloc(&c->d_q, c->q.size()))) return rc;
     if ((rc = dev_alloc(&c->d_prod, c->q.size() + 2))) return rc;
     HIP_TRY(hipMemset(c->d_prod, 0, (c->q.size() + 2) * sizeof(ProductDesc)));
-    const size_t n0 = c->items[0].size(), n1 = c->items[1].size();
-    if ((rc = dev_alloc(&c->d_items, n0 + n1))) return rc;
+    const size_t n0 = c->items[0].size(), n1 = c->items[1].size(), n2 = c->items[2].size();
+    if ((rc = dev_alloc(&c->d_items, n0 + n1 + n2))) return rc;
     HIP_TRY(hipMemcpy(c->d_q, c->q.data(), c->q.size(), hipMemcpyHostToDevice));
     if (n0) HIP_TRY(hipMemcpy(c->d_items, c->items[0].data(), n0 * sizeof(WorkItem), hipMemcpyHostToDevice));
     if (n1) HIP_TRY(hipMemcpy(c->d_items + n0, c->items[1].data(), n1 * sizeof(WorkItem), hipMemcpyHostToDevice));
+    if (n2) HIP_TRY(hipMemcpy(c->d_items + n0 + n1, c->items[2].data(), n2 * sizeof(WorkItem), hipMemcpyHostToDevice));
     return GEMM_MP_OK;
 }
 
@@ -503,8 +519,11 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
     a.convB = c->conv_active ? c->d_conv[1] : nullptr;
     a.items64 = c->d_items;
     a.items32 = c->d_items + c->items[0].size();
+    a.items8 = a.items32 + c->items[1].size();
     a.n_items64 = (int32_t)c->items[0].size();
     a.n_items32 = (int32_t)c->items[1].size();
+    a.n_items8 = (int32_t)c->items[2].size();
+    a.pad_items = 0;
     a.nb = c->nb; a.MT = c->MT; a.NT = c->NT; a.KT = c->KT;
     a.kt_eff = alpha == 0.0 ? 0 : c->KT;
     a.alpha = alpha; a.beta = beta;

@@ -10,6 +10,7 @@
 namespace gmp {
 
 constexpr int kMacro = 128;       // rows = cols of C owned by one workgroup
+constexpr int kMacroFp8 = 256;    // the same for C tiles whose products are all FP8 x FP8
 constexpr int kScanCols = 128;    // columns one scan workgroup reduces; a power of two
 constexpr int kPackBlock = 64;    // pack / unpack move 64 x 64 element blocks
 
@@ -72,7 +73,8 @@ struct GemmArgs {
     const uint64_t *convB;   // same for B
     const WorkItem *items64;  // owner regions of FP64 C tiles, launch order
     const WorkItem *items32;  // owner regions of FP32 C tiles, launch order
-    int32_t n_items64, n_items32;
+    const WorkItem *items8;   // 256 x 256 regions of FP32 C tiles made of FP8 x FP8 products only
+    int32_t n_items64, n_items32, n_items8, pad_items;
     int32_t nb, MT, NT, KT;
     int32_t kt_eff;          // KT, or 0 when alpha == 0
     double alpha, beta;

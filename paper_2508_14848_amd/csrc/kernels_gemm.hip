@@ -1282,13 +1282,258 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     }
 }
 
+// ---- FP32 C tiles whose tile products are all FP8 x FP8: 256 x 256 regions -------------------
+// At FP8 rates a 128 x 128 region asks the L2 for 64 bytes and the LDS for 128 bytes per cycle
+// and CU: both paths' full width.  A C tile whose every product takes two FP8 tiles as stored
+// (no conversion) is therefore cut into 256 x 256 regions: 4 waves of 128 x 128, i.e. 4 x 4
+// blocks of the 32x32x64 FP8 MFMA per wave, which halves both the bytes fetched from L2 and the
+// bytes read from LDS per flop, and quarters the number of workgroups and their fixed costs.
+// The 256 accumulator registers of a wave leave no room for a per-product accumulator beside
+// the running sum, so the tile scales are applied inside the matrix core instead: the MFMA's
+// block-scale operands (an E8M0 exponent per operand) carry 2^eA and 2^eB, every product term
+// enters the one FP32 accumulator at its true magnitude, and there is no fold.  (The order of
+// the FP32 additions differs from the smaller regions': one chain over the whole reduction.)
+// Chunks of 128 bytes per row stream through two 64 KB LDS stages by global -> LDS DMA with
+// the same swizzle as the FP64 / FP32 stages; a chunk is two halves of 16 MFMAs; while a half
+// runs, the fragments of the next half are read, and in the second half the requests for the
+// chunk after the next go out into the stage just vacated.  One barrier per chunk, in the
+// middle: it publishes the next chunk (requested a whole chunk earlier) and frees this one's.
+constexpr int kBigMacro = 256;
+constexpr int kBigOperand = kBigMacro * kRowBytes;     // 32 KB
+constexpr int kBigStage = 2 * kBigOperand;             // A then B
+constexpr int kBigLdsBytes = 2 * kBigStage;            // 128 KB
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+struct BigGeom {
+    int voff[2][2];      // [operand][instruction parity]: this lane's byte offset in a tile for DMA instruction 0 / 1
+    int ra[2][2][2];     // [stage][half][which 16 bytes]: LDS address of this lane's fragment bytes, A block 0
+    int rb[2][2][2];     // same for B (includes the operand offset)
+    unsigned dst;        // LDS address of this wave's first DMA row of operand A, stage 0
+    int rows8;           // byte distance of 8 tile rows
+};
+
+// Scale exponents of a product as the two E8M0 operands of the MFMA (bias 127, range +-127;
+// what one operand cannot hold moves to the other; beyond both the FP32 result is 0 or inf
+// in any case), replicated into all four bytes.
+__device__ __forceinline__ void big_scales(int ea, int eb, int &sa, int &sb)
+{
+    int xa = ea < -127 ? -127 : ea > 127 ? 127 : ea;
+    int rest = eb + (ea - xa);
+    int xb = rest < -127 ? -127 : rest > 127 ? 127 : rest;
+    rest = xa + (rest - xb);
+    xa = rest < -127 ? -127 : rest > 127 ? 127 : rest;
+    sa = (xa + 127) * 0x01010101;
+    sb = (xb + 127) * 0x01010101;
+}
+
+// DMA instruction j = 0..15 of a wave for one chunk: j < 8 moves rows 8 j .. 8 j + 7 of the
+// wave's 64 rows of A, j >= 8 the same of B, 16 bytes per lane, into the stage at `dst`.
+// base / bytes: the operand tile (bytes = 0: nothing is fetched, zeros are written).
+__device__ __forceinline__ void big_dma_one(uint64_t base, int bytes, int voff, int soff, unsigned dst)
+{
+    const i32x4 rsrc = {(int)(uint32_t)base, (int)((uint32_t)(base >> 32) & 0xffffu), bytes, 0x00020000};
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(dst), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory", "m0");
+#else
+    (void)rsrc; (void)voff; (void)soff; (void)dst;
+#endif
+}
+struct BigSource {
+    uint64_t a, b;       // operand tiles of the product the chunk belongs to
+    int bytes;           // nb * nb, or 0 past the end of the reduction
+    int c;               // chunk index in that product
+};
+__device__ __forceinline__ void big_request(const BigSource &S, const BigGeom &BG, int stage, int j)
+{
+    const int op = j >> 3, jj = j & 7;
+    big_dma_one(op ? S.b : S.a, S.bytes, BG.voff[op][jj & 1], uni(S.c * kRowBytes + jj * BG.rows8),
+                BG.dst + (unsigned)(stage * kBigStage + op * kBigOperand + jj * 1024));
+}
+// Fragment t (0..3: A blocks of 32 rows, 4..7: B blocks) of half `hc` of the chunk in `stage`.
+__device__ __forceinline__ i8v big_read(const BigGeom &BG, const char *lds, int stage, int hc, int t)
+{
+    const char *p0 = lds + (t < 4 ? BG.ra[stage][hc][0] : BG.rb[stage][hc][0]) + (t & 3) * (32 * kRowBytes);
+    const char *p1 = lds + (t < 4 ? BG.ra[stage][hc][1] : BG.rb[stage][hc][1]) + (t & 3) * (32 * kRowBytes);
+    const u32x4 lo = *(const u32x4 *)p0, hi = *(const u32x4 *)p1;
+    return i8v{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+}
+
+// One chunk held in `STAGE`.  On entry f[0] holds the fragments of its first half; on exit
+// those of the next chunk's first half.  S2: the chunk two ahead, requested into STAGE.
+template <int STAGE>
+__device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], const BigGeom &BG, const char *lds, const BigSource &S2,
+                                          int sa, int sb)
+{
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
+            SCHED_FENCE();
+            const int k = mt * 4 + nt;                       // second half's fragments: B first
+            if (k < 8) f[1][(k + 4) & 7] = big_read(BG, lds, STAGE, 1, (k + 4) & 7);
+            SCHED_FENCE();
+        }
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // the next chunk, requested a chunk ago, has landed
+#endif
+    __syncthreads();                                         // ... in every wave; and all are done reading this stage
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
+            SCHED_FENCE();
+            const int k = mt * 4 + nt;
+            if (k < 8) f[0][(k + 4) & 7] = big_read(BG, lds, STAGE ^ 1, 0, (k + 4) & 7);
+            big_request(S2, BG, STAGE, k);
+            SCHED_FENCE();
+        }
+}
+
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    const uint64_t itw = table_u64((const uint64_t *)items, blockIdx.x);
+    const int tileC = (int)(uint32_t)itw;
+    const ArgsPtr K0 = args();
+    const int nb = K0->nb, kt = K0->kt_eff;
+    const int arow0 = (int)((itw >> 32) & 0xffffu) * kBigMacro, brow0 = (int)((itw >> 48) & 0xffffu) * kBigMacro;
+    const ProductDesc *prod = K0->prod + (int64_t)tileC * K0->KT;
+
+    BigGeom BG;
+    {
+        const int r = lane >> 3, slot = lane & 7;
+        const int seg = slot ^ (r >> 1);                     // instruction 0; odd instructions: ^ 4
+        BG.voff[0][0] = (arow0 + wave * 64 + r) * nb + seg * 16;
+        BG.voff[1][0] = (brow0 + wave * 64 + r) * nb + seg * 16;
+        BG.voff[0][1] = BG.voff[0][0] ^ 64;
+        BG.voff[1][1] = BG.voff[1][0] ^ 64;
+        BG.dst = (unsigned)uni(wave * (64 * kRowBytes));
+        BG.rows8 = 8 * nb;
+        const int i = lane & 31, g = lane >> 5, x = (i >> 1) & 7;
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+            for (int hc = 0; hc < 2; ++hc)
+#pragma unroll
+                for (int w = 0; w < 2; ++w) {
+                    const int slot_r = (4 * hc + 2 * g + w) ^ x;
+                    BG.ra[st][hc][w] = st * kBigStage + (wm * 128 + i) * kRowBytes + slot_r * 16;
+                    BG.rb[st][hc][w] = st * kBigStage + kBigOperand + (wn * 128 + i) * kRowBytes + slot_r * 16;
+                }
+    }
+
+    f16v acc[4][4];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mt][nt][v] = 0.0f;
+
+    const int n = nb / kRowBytes;                            // chunks per product: even (nb is a multiple of 256)
+    const int tile_bytes = nb * nb;
+    if (kt > 0) {
+        const ConstQuad rec0 = (ConstQuad)(uintptr_t)prod;
+        u32x4 lo = rec0[0], hi = rec0[1];
+        BigSource S;
+        S.a = (uint64_t)lo.x | ((uint64_t)lo.y << 32);
+        S.b = (uint64_t)lo.z | ((uint64_t)lo.w << 32);
+        S.bytes = tile_bytes;
+        S.c = 0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) big_request(S, BG, 0, j);
+        S.c = 1;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) big_request(S, BG, 1, j);
+#if defined(__HIP_DEVICE_COMPILE__)
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");    // chunk 0 has landed
+#endif
+        __syncthreads();
+        i8v f[2][8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) f[0][t] = big_read(BG, lds, 0, 0, t);
+
+        for (int L = 0; L < kt; ++L) {
+            int sa, sb;
+            big_scales((int)hi.x, (int)hi.y, sa, sb);
+            // the following product (descriptors of length zero past the end)
+            u32x4 nlo = lo, nhi = hi;
+            int nbytes = 0;
+            if (L + 1 < kt) {
+                const ConstQuad rec = (ConstQuad)(uintptr_t)(prod + L + 1);
+                nlo = rec[0];
+                nhi = rec[1];
+                nbytes = tile_bytes;
+            }
+            BigSource cur_src, next_src;
+            cur_src.a = (uint64_t)lo.x | ((uint64_t)lo.y << 32);
+            cur_src.b = (uint64_t)lo.z | ((uint64_t)lo.w << 32);
+            cur_src.bytes = tile_bytes;
+            next_src.a = (uint64_t)nlo.x | ((uint64_t)nlo.y << 32);
+            next_src.b = (uint64_t)nlo.z | ((uint64_t)nlo.w << 32);
+            next_src.bytes = nbytes;
+            for (int c = 0; c < n; c += 2) {
+                BigSource S2 = (c + 2 < n) ? cur_src : next_src;
+                S2.c = (c + 2 < n) ? c + 2 : c + 2 - n;
+                big_chunk<0>(acc, f, BG, lds, S2, sa, sb);
+                S2.c += 1;
+                big_chunk<1>(acc, f, BG, lds, S2, sa, sb);
+            }
+            lo = nlo;
+            hi = nhi;
+        }
+#if defined(__HIP_DEVICE_COMPILE__)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the empty requests still write zeros into the stages
+#endif
+    }
+
+    // Epilogue: v = alpha*s (+ beta*c0), two rounded products and one rounded sum in FP32.  A
+    // 32 x 32 accumulator block holds, per register, one row piece of 32 consecutive columns
+    // in each half of the wave: 128-byte row segments straight from the registers.
+    const ArgsPtr K = args();
+    const float alpha = (float)K->alpha, beta = (float)K->beta;
+    const bool use_c = K->beta != 0.0;
+    typedef __attribute__((address_space(1))) float *GlobalF;
+    GlobalF ctile = (GlobalF)(uintptr_t)(K->C.storage + table_u64(K->C.offset, tileC));
+    const int i = lane & 31, g = lane >> 5;
+    GlobalF cbase = ctile + (int64_t)(arow0 + wm * 128 + 4 * g) * nb + brow0 + wn * 128 + i;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            float c0[16];
+            if (use_c) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) c0[v] = cbase[(int64_t)(mt * 32 + 8 * (v >> 2) + (v & 3)) * nb + nt * 32];
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float val = alpha * acc[mt][nt][v];
+                if (use_c) { const float bc = beta * c0[v]; val = val + bc; }
+                cbase[(int64_t)(mt * 32 + 8 * (v >> 2) + (v & 3)) * nb + nt * 32] = val;
+            }
+        }
+}
+
 hipError_t gemm_kernel_setup()
 {
     hipError_t e = hipFuncSetAttribute((const void *)gemm_mp_owner_kernel<double>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void *)gemm_mp_owner_kernel<float>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    e = hipFuncSetAttribute((const void *)gemm_mp_owner_kernel<float>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void *)gemm_mp_fp8_region_kernel,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
 }
 
 // One thread per task (C tile, L): gather what the owner workgroups need into one record.  With
@@ -1361,8 +1606,8 @@ hipError_t launch_convert(const ConvertJob *jobs_dev, int njobs, uint32_t max_n1
     return hipGetLastError();
 }
 
-// The product table, then two launches at most: the owner regions of FP64 C tiles, then those
-// of FP32 C tiles.
+// The product table, then three launches at most: the owner regions of FP64 C tiles, those of
+// FP32 C tiles, and the large regions of FP32 C tiles made of FP8 products only.
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
     const int64_t tasks = (int64_t)a.MT * a.NT * a.KT;
@@ -1371,6 +1616,8 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
         gemm_mp_owner_kernel<double><<<dim3((unsigned)a.n_items64), dim3(kThreads), kLdsBytes, s>>>(a, a.items64);
     if (a.n_items32 > 0)
         gemm_mp_owner_kernel<float><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
+    if (a.n_items8 > 0)
+        gemm_mp_fp8_region_kernel<<<dim3((unsigned)a.n_items8), dim3(kThreads), kBigLdsBytes, s>>>(a, a.items8);
     return hipGetLastError();
 }
 

@@ -64,7 +64,13 @@ def job_tolerances(side, jobs, policy, alpha):
             b = side.By[L * nb:(L + 1) * nb, J * nb + c0:J * nb + c1]
             norm += np.linalg.norm(a) * 2.0 ** float(side.eA[I, L]) * np.linalg.norm(b) * 2.0 ** float(side.eB[L, J])
         u_acc = U[FP64] if all64 else U[FP32]
-        out.append(dict(norm=abs(alpha) * norm, tol=4.0 * K * u_tile, tight=2.0 * K * u_acc, all64=all64))
+        # Gradual underflow: a rounded FP32 operation errs by up to (x op y) u plus half the smallest
+        # subnormal.  The relative bounds above carry no such term; where a C tile's entries lie in
+        # the FP32 subnormal range (products of tiles with tiny scales) two correct evaluations
+        # differ by a few units of 2^-149 per entry: one per fold and epilogue operation plus one
+        # per 32 terms of a reduction carried out at true magnitude.  Frobenius norm over the block.
+        eta = 0.0 if pC == FP64 else (K / 32.0 + KT + 3.0) * 2.0 ** -149 * np.sqrt(float((r1 - r0) * (c1 - c0)))
+        out.append(dict(norm=abs(alpha) * norm, tol=4.0 * K * u_tile, tight=2.0 * K * u_acc, all64=all64, eta=eta))
     return out
 
 
@@ -87,13 +93,13 @@ def compare_jobs(side, jobs, policy, alpha, beta, C_gpu, C_orc):
             worst["rel64"] = max(worst["rel64"], rel)
             assert rel <= 1e-12, "all-FP64 tile (%d,%d): rel Frobenius error %.3e" % (I, J, rel)
         if base == 0.0:
-            assert err == 0.0
+            assert err <= t["eta"]
             continue
         worst["star"] = max(worst["star"], err / (t["tol"] * base))
-        worst["tight"] = max(worst["tight"], err / (t["tight"] * base))
+        worst["tight"] = max(worst["tight"], err / (t["tight"] * base + t["eta"]))
         assert err <= t["tol"] * base, "tile (%d,%d): err %.3e > 4*K*u_tile bound %.3e" % (I, J, err, t["tol"] * base)
-        assert err <= t["tight"] * base, "tile (%d,%d): err %.3e > accumulate-precision bound %.3e" % (
-            I, J, err, t["tight"] * base)
+        assert err <= t["tight"] * base + t["eta"], "tile (%d,%d): err %.3e > accumulate-precision bound %.3e" % (
+            I, J, err, t["tight"] * base + t["eta"])
     return worst
 
 
