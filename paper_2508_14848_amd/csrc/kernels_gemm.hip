@@ -1361,6 +1361,14 @@ __device__ __forceinline__ i8v big_read(const BigGeom &BG, const char *lds, int 
     return i8v{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
 }
 
+// One 16-byte half (w) of the same, into its place in the fragment.
+__device__ __forceinline__ void big_read_half(i8v &f, const BigGeom &BG, const char *lds, int stage, int hc, int t, int w)
+{
+    const char *p = lds + (t < 4 ? BG.ra[stage][hc][w] : BG.rb[stage][hc][w]) + (t & 3) * (32 * kRowBytes);
+    const u32x4 v = *(const u32x4 *)p;
+    f[4 * w] = (int)v.x; f[4 * w + 1] = (int)v.y; f[4 * w + 2] = (int)v.z; f[4 * w + 3] = (int)v.w;
+}
+
 // One chunk held in `STAGE`.  On entry f[0] holds the fragments of its first half; on exit
 // those of the next chunk's first half.  S2: the chunk two ahead, requested into STAGE.
 template <int STAGE>
@@ -1373,8 +1381,8 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
         for (int nt = 0; nt < 4; ++nt) {
             acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
             SCHED_FENCE();
-            const int k = mt * 4 + nt;                       // second half's fragments: B first
-            if (k < 8) f[1][(k + 4) & 7] = big_read(BG, lds, STAGE, 1, (k + 4) & 7);
+            const int k = mt * 4 + nt;                       // second half's fragments, 16 bytes per position: B first
+            big_read_half(f[1][((k >> 1) + 4) & 7], BG, lds, STAGE, 1, ((k >> 1) + 4) & 7, k & 1);
             SCHED_FENCE();
         }
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -1388,7 +1396,7 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
             acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
             SCHED_FENCE();
             const int k = mt * 4 + nt;
-            if (k < 8) f[0][(k + 4) & 7] = big_read(BG, lds, STAGE ^ 1, 0, (k + 4) & 7);
+            big_read_half(f[0][((k >> 1) + 4) & 7], BG, lds, STAGE ^ 1, 0, ((k >> 1) + 4) & 7, k & 1);
             big_request(S2, BG, STAGE, k);
             SCHED_FENCE();
         }
