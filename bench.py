@@ -198,10 +198,11 @@ def main():
         "stages_ms": {k: float(np.mean(v)) for k, v in stage_ms.items()},
         "run_only": {"ms": run_ms, "min_ms": float(np.min(stage_ms["run"])), "effective_tflops": achieved,
                      "roofline_ms": t_roof * 1e3, "frac_of_precision_weighted_peak": t_roof * 1e3 / run_ms},
-        "roofline": {"bound": "mfma", "kernel": "gemm_mp_owner_kernel", "achieved": achieved, "peak": peak_mix,
+        "roofline": {"bound": "mfma", "kernel": "gemm_mp_run: gemm_mp_owner_kernel<double|float> + gemm_mp_fp8_region_kernel", "achieved": achieved, "peak": peak_mix,
                      "unit": "TFLOP/s", "frac": achieved / peak_mix, "traffic": traffic,
                      "note": "peak = 2MNK / sum_q(F_q/P_q), P = 78.6/157.3/2516.6/5033.2 TFLOP/s for f64/f32/f16/f8; "
-                             "achieved = 2MNK / mean event time of gemm_mp_run on its stream"},
+                             "achieved = 2MNK / mean event time of gemm_mp_run on its stream (product table and up to three "
+                             "GEMM launches: FP64 C tiles, FP32 C tiles, FP32 C tiles of FP8 products only)"},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, A, B, C0, args.cpu_seconds)
