@@ -123,6 +123,28 @@ def test_product_precision_and_stats_closed_forms():
     assert g.get_stats()["products"] == [n64 * 16, (256 - n64) * 16, 0, 0]
 
 
+def test_fp8_only_tiles_are_scheduled_in_large_regions():
+    """An FP32 C tile whose every product multiplies two FP8 tiles at FP8 is cut into 256 x 256
+    regions, every other tile into 128 x 128 ones; a tile size that is not a multiple of 256
+    keeps the small regions everywhere."""
+    FP64, FP32, FP16, FP8 = 0, 1, 2, 3
+    for nb, want_big in ((512, True), (384, False)):
+        MT, NT, KT = 3, 2, 2
+        g = G.GemmMP(MT * nb, NT * nb, KT * nb, nb)
+        mA = np.full((MT, KT), FP8, dtype=np.uint16)
+        mB = np.full((KT, NT), FP8, dtype=np.uint16)
+        mC = np.full((MT, NT), FP32, dtype=np.uint16)
+        mA[2, 1] = FP16                       # tile row 2: a converting product, small regions
+        mC[0, 1] = FP64                       # an FP64 tile: small regions
+        for k, m in (("A", mA), ("B", mB), ("C", mC)):
+            g.set_precision_map(k, m)
+        big = 3 if want_big else 0            # tiles (0,0), (1,0), (1,1)
+        small = MT * NT - big
+        assert g.get_stats()["work_items"] == small * (nb // 128) ** 2 + big * (nb // 256) ** 2
+        g.set_policy(G.POLICY_C_TILE)         # every product at FP32 / FP64: no FP8 product left
+        assert g.get_stats()["work_items"] == MT * NT * (nb // 128) ** 2
+
+
 def test_sender_side_conversion_plan_closed_forms():
     """Workspace size = one copy per (tile, product precision != stored precision) that some task
     needs; host logic only."""
