@@ -35,6 +35,7 @@ typedef double d4 __attribute__((ext_vector_type(4)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef int i8v __attribute__((ext_vector_type(8)));
+typedef float f2v __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vectors: these stay in registers
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -298,6 +299,124 @@ __device__ __forceinline__ void store_piece_any(const Raw &r, const Product &pr,
     }
 }
 
+// ---- staging with both stored precisions known at compile time (the steady chunks) -----------
+// The generic staging above fetches the aligned 16 bytes around a segment's source and picks the
+// source out of them at conversion time with per-lane selects, then converts and scales with
+// one instruction each per element: vector-ALU work that FP64 / FP32 MFMAs do not hide.  With
+// the stored precision P a template parameter the source is fetched exactly (2, 4 or 8 bytes:
+// no selects) and conversion and scaling are fused: v_fma_mix_f32 takes an FP16 half straight
+// out of a packed register and multiplies it by 2^e in FP32, v_cvt_scalef32_pk_f32_fp8 turns
+// two FP8 bytes into two scaled FP32 values.  Both were checked on the device against
+// cvt + ldexp over every bit pattern and a range of scales: v_fma_mix_f32 agrees for every
+// scale that is an FP32 number, subnormal ones included (one correct rounding, also into the
+// subnormal range); v_cvt_scalef32 for scales 2^-126 and up.  Towards FP64 the FP32 intermediate
+// must itself be exact, which narrows the range further.  A product with a tile exponent
+// outside these ranges (tiles whose largest entry is below about 1e-26, in FP64 C tiles, or
+// 1e-36) runs its chunks through the generic staging instead.
+struct HiScale {
+    float f;      // 2^e
+};
+__device__ __forceinline__ HiScale hi_scale(int e)
+{
+    HiScale h;
+    h.f = __uint_as_float(e >= -126 ? (uint32_t)(e + 127) << 23 : 1u << ((e + 149) & 31));
+    return h;
+}
+// May an operand stored at precision p with tile exponent e take the fused conversions to Q?
+template <int Q>
+__device__ __forceinline__ bool fused_ok(int p, int e)
+{
+    if (p < Q16) return true;                                  // FP64 / FP32 storage carries no scale
+    if (Q == Q32) return p == Q16 ? (e >= -149 && e <= 127) : (e >= -126 && e <= 127);
+    return p == Q16 ? (e >= -102 && e <= 111) : (e >= -117 && e <= 118);
+}
+// The source of a converted 16-byte segment of precision Q stored at precision P: 16 bytes when
+// P = Q, 32 for the one down-cast, else 16 * size(P) / size(Q).  o.voff is the exact offset here.
+template <int Q, int P>
+__device__ __forceinline__ void load_exact(Raw &r, const Operand &o, int soff)
+{
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)o.base, 0, o.bytes, 0x00020000);
+    constexpr int kBytes = P < Q ? 32 : 16 >> (P - Q);
+    if constexpr (kBytes >= 16) {
+        r.lo = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o.voff, soff, 0);
+        if constexpr (kBytes == 32) r.hi = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o.voff + 16, soff, 0);
+    } else if constexpr (kBytes == 8) {
+        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, o.voff, soff, 0);
+        r.lo.x = v.x; r.lo.y = v.y;
+    } else if constexpr (kBytes == 4) {
+        r.lo.x = __builtin_amdgcn_raw_buffer_load_b32(rsrc, o.voff, soff, 0);
+    } else {
+        r.lo.x = __builtin_amdgcn_raw_buffer_load_b16(rsrc, o.voff, soff, 0);
+    }
+}
+template <int WHICH>
+__device__ __forceinline__ float half_scaled(uint32_t w, float f)     // half WHICH of w, times f, in FP32
+{
+    float x;
+#if defined(__HIP_DEVICE_COMPILE__)
+    // the addend is -0 so that a negative zero stays one
+    const float nz = __uint_as_float(0x80000000u);
+    if constexpr (WHICH == 0) asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(x) : "v"(w), "s"(f), "v"(nz));
+    else asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(x) : "v"(w), "s"(f), "v"(nz));
+#else
+    x = 0.0f; (void)w; (void)f;
+#endif
+    return x;
+}
+template <int Q, int P>
+__device__ __forceinline__ u32x4 convert_exact(const Raw &r, const HiScale &S)
+{
+    static_assert(Q == Q64 || Q == Q32, "FP64 / FP32 products only");
+    if constexpr (P == Q) {
+        return r.lo;
+    } else if constexpr (Q == Q32 && P == Q64) {
+        return u32x4{__float_as_uint((float)as_double(r.lo.x, r.lo.y)), __float_as_uint((float)as_double(r.lo.z, r.lo.w)),
+                     __float_as_uint((float)as_double(r.hi.x, r.hi.y)), __float_as_uint((float)as_double(r.hi.z, r.hi.w))};
+    } else if constexpr (Q == Q32) {
+        float f0, f1, f2, f3;
+        if constexpr (P == Q16) {
+            f0 = half_scaled<0>(r.lo.x, S.f); f1 = half_scaled<1>(r.lo.x, S.f);
+            f2 = half_scaled<0>(r.lo.y, S.f); f3 = half_scaled<1>(r.lo.y, S.f);
+        } else {
+            const f2v a = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(r.lo.x, S.f, false);
+            const f2v b = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(r.lo.x, S.f, true);
+            f0 = a.x; f1 = a.y; f2 = b.x; f3 = b.y;
+        }
+        return u32x4{__float_as_uint(f0), __float_as_uint(f1), __float_as_uint(f2), __float_as_uint(f3)};
+    } else {
+        double a, b;
+        if constexpr (P == Q32) {
+            a = (double)__uint_as_float(r.lo.x); b = (double)__uint_as_float(r.lo.y);
+        } else {
+            float f0, f1;
+            if constexpr (P == Q16) {
+                f0 = half_scaled<0>(r.lo.x, S.f); f1 = half_scaled<1>(r.lo.x, S.f);
+            } else {
+                const f2v v = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(r.lo.x, S.f, false);
+                f0 = v.x; f1 = v.y;
+            }
+            a = (double)f0; b = (double)f1;
+        }
+        const u32x2 ab = dbits(a), bb = dbits(b);
+        return u32x4{ab.x, ab.y, bb.x, bb.y};
+    }
+}
+// Piece i = 2 * (row block) + (0: A, 1: B) of chunk c with the stored precisions PA, PB.
+template <int Q, int PA, int PB>
+__device__ __forceinline__ void load_piece_exact(Raw &r, const Product &pr, int nb, int c, int i)
+{
+    const int eoff = c * chunk_elems(Q) + (i >> 1) * 32 * nb;
+    if (i & 1) load_exact<Q, PB>(r, pr.b, eoff << (3 - PB));
+    else load_exact<Q, PA>(r, pr.a, eoff << (3 - PA));
+}
+template <int Q, int PA, int PB>
+__device__ __forceinline__ void store_piece_exact(const Raw &r, const HiScale &SA, const HiScale &SB, const Geometry &G, char *stage, int i)
+{
+    char *dst = stage + G.wsw + (i >> 1) * (32 * kRowBytes) + (i & 1) * kOperandStage;
+    if (i & 1) *(u32x4 *)dst = convert_exact<Q, PB>(r, SB);
+    else *(u32x4 *)dst = convert_exact<Q, PA>(r, SA);
+}
+
 // Everything that describes a tile product is the same for all lanes of the workgroup; passing
 // it through readfirstlane keeps it in scalar registers and makes every branch on it scalar.
 // Wave-uniform reads of the small descriptor tables (read-only for the whole kernel) through
@@ -518,11 +637,12 @@ __device__ __forceinline__ u32x4 read_frag(const HiFrag &F, int so, int j, int t
 struct ChunkCtx {
     int so, no;        // byte offsets of the stage computed from and of the one being filled
     char *wst;         // the latter's address
+    HiScale sa, sb;    // MODE 0: the operands' scales
 };
 // MODE: 0 = a chunk followed by another of the same product; 1 = the last chunk, which also
 // stages chunk 0 of the next product (conversion chosen at run time); 2 = the last chunk, which
 // only loads it into `r` (the next product's own loop converts and stores it).
-template <int Q, int BASE, int MODE, int u, typename Acc>
+template <int Q, int BASE, int MODE, int PA, int PB, int u, typename Acc>
 __device__ __forceinline__ void chunk_position(Acc (&acc)[4][4], u32x4 (&fr)[2][8], Raw (&r)[8], const Product &pr, int c, const ChunkCtx &X,
                                                const HiFrag &F, const Geometry &G, int nb)
 {
@@ -530,13 +650,15 @@ __device__ __forceinline__ void chunk_position(Acc (&acc)[4][4], u32x4 (&fr)[2][
     SCHED_FENCE();
     if constexpr (u < 16 && (u & 1) == 0) {
         if constexpr (MODE != 0) load_piece_any(r[u >> 1], pr, nb, c, u >> 1);
+        else if constexpr (PA >= 0) load_piece_exact<Q, PA, PB>(r[u >> 1], pr, nb, c, u >> 1);
         else load_piece(r[u >> 1], pr, nb, c, u >> 1);
     } else if constexpr (u < 16) {
         constexpr int t = ((u >> 1) + 4) & 7;                // B0..B3, A0..A3
         fr[1][t] = read_frag(F, X.so, 1, t);
     } else if constexpr (MODE != 2 && u >= 34 && u <= 48 && (u & 1) == 0) {
         constexpr int i = (u - 34) >> 1;
-        if constexpr (MODE == 0) store_piece<Q>(r[i], pr, G, X.wst, i);
+        if constexpr (MODE == 0 && PA >= 0) store_piece_exact<Q, PA, PB>(r[i], X.sa, X.sb, G, X.wst, i);
+        else if constexpr (MODE == 0) store_piece<Q>(r[i], pr, G, X.wst, i);
         else store_piece_any(r[i], pr, G, X.wst, i);   // q < 0 (nothing follows): stores nothing
     } else if constexpr (MODE != 2 && u == 52) {
         __syncthreads();
@@ -546,30 +668,32 @@ __device__ __forceinline__ void chunk_position(Acc (&acc)[4][4], u32x4 (&fr)[2][
     }
     SCHED_FENCE();
 }
-template <int Q, int BASE, int MODE, typename Acc, int... U>
+template <int Q, int BASE, int MODE, int PA, int PB, typename Acc, int... U>
 __device__ __forceinline__ void chunk_positions(Acc (&acc)[4][4], u32x4 (&fr)[2][8], Raw (&r)[8], const Product &pr, int c, const ChunkCtx &X,
                                                 const HiFrag &F, const Geometry &G, int nb, std::integer_sequence<int, U...>)
 {
-    (chunk_position<Q, BASE, MODE, U>(acc, fr, r, pr, c, X, F, G, nb), ...);
+    (chunk_position<Q, BASE, MODE, PA, PB, U>(acc, fr, r, pr, c, X, F, G, nb), ...);
 }
 // STAGE: the LDS stage the chunk computes from when it is known at compile time (0 / 1; the
 // stage offsets then fold into the instructions' immediate offsets instead of costing vector
 // adds every chunk), -1: taken from `stage`.
-template <int Q, int BASE, int MODE, int STAGE = -1, typename Acc>
+template <int Q, int BASE, int MODE, int STAGE = -1, int PA = -1, int PB = -1, typename Acc>
 __device__ __forceinline__ void pipelined_chunk(Acc (&acc)[4][4], u32x4 (&fr)[2][8], Raw (&r)[8], const Product &pr, int c, char *lds, int stage,
-                                                const HiFrag &F, const Geometry &G, int nb)
+                                                const HiFrag &F, const Geometry &G, int nb, const HiScale &sa = HiScale{}, const HiScale &sb = HiScale{})
 {
     if (STAGE >= 0) stage = STAGE;
     ChunkCtx X;
+    X.sa = sa;
+    X.sb = sb;
     X.so = stage * kStage;
     X.no = (stage ^ 1) * kStage;
     X.wst = lds + X.no;
-    chunk_positions<Q, BASE, MODE>(acc, fr, r, pr, c, X, F, G, nb, std::make_integer_sequence<int, 64>{});
+    chunk_positions<Q, BASE, MODE, PA, PB>(acc, fr, r, pr, c, X, F, G, nb, std::make_integer_sequence<int, 64>{});
 }
 
 // All but the last chunk of a product whose operands are stored at precisions PA, PB: with
 // both known at compile time the staging code is straight-line (no conversion at all when
-// PA = PB = Q).  On entry the product's chunk 0 is either staged in LDS stage `stage` or, when
+// PA = PB = Q).  PA = PB = -1: any precisions, any exponents, conversion chosen at run time.  On entry the product's chunk 0 is either staged in LDS stage `stage` or, when
 // `raw`, still in `hand` as loaded by the preceding product's last chunk.
 template <int Q, int BASE, int PA, int PB, typename Acc>
 __device__ __forceinline__ void steady_chunks(Acc (&acc)[4][4], u32x4 (&fr)[2][8], const Product &cur, int n, char *lds, int &stage,
@@ -577,8 +701,10 @@ __device__ __forceinline__ void steady_chunks(Acc (&acc)[4][4], u32x4 (&fr)[2][8
 {
     Product cp = cur;
     cp.q = Q;
-    cp.a.p = PA;
-    cp.b.p = PB;
+    if constexpr (PA >= 0) {
+        cp.a.p = PA;
+        cp.b.p = PB;
+    }
     if (raw) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) store_piece<Q>(hand[i], cp, G, lds + stage * kStage, i);
@@ -589,28 +715,34 @@ __device__ __forceinline__ void steady_chunks(Acc (&acc)[4][4], u32x4 (&fr)[2][8
     acc_fence<BASE>(acc);
     Raw r[8];
     int c = 1;
-    // Pure FP64 products (the slowest MFMAs, nothing to convert) run their chunks in pairs with
-    // the LDS stage a compile-time constant; measured +5 % on them.  The same unrolling slowed
-    // every other operand mix by 1-3 %, so those keep the one-chunk loop.
-    if constexpr (Q == Q64 && PA == Q64 && PB == Q64) {
-        if (stage == 1 && c < n) {                     // bring the loop to stage 0
-            pipelined_chunk<Q, BASE, 0, 1>(acc, fr, r, cp, c, lds, 1, F, G, nb);
-            stage = 0;
-            ++c;
-        }
-        for (; c + 1 < n; c += 2) {                    // pairs of chunks with the stages known
-            pipelined_chunk<Q, BASE, 0, 0>(acc, fr, r, cp, c, lds, 0, F, G, nb);
-            pipelined_chunk<Q, BASE, 0, 1>(acc, fr, r, cp, c + 1, lds, 1, F, G, nb);
-        }
-        if (c < n) {
-            pipelined_chunk<Q, BASE, 0, 0>(acc, fr, r, cp, c, lds, 0, F, G, nb);
-            stage = 1;
-        }
-    } else {
+    if constexpr (PA < 0) {
+        // operands at any stored precision with any exponent: conversion chosen at run time
         for (; c < n; ++c) {
             pipelined_chunk<Q, BASE, 0>(acc, fr, r, cp, c, lds, stage, F, G, nb);
             stage ^= 1;
         }
+        return;
+    }
+    const HiScale sa = hi_scale(cp.a.e), sb = hi_scale(cp.b.e);
+    // from here on the operands' vector offsets are exact (the generic staging keeps them
+    // aligned down to 16 bytes with the remainder in `sub`)
+    cp.a.voff += cp.a.sub;
+    cp.b.voff += cp.b.sub;
+    // Chunks run in pairs with the LDS stage a compile-time constant: the stage offsets fold into
+    // the instructions' immediate fields instead of costing vector adds in every chunk (+2 to
+    // +4 % on every operand mix).
+    if (stage == 1 && c < n) {                         // bring the loop to stage 0
+        pipelined_chunk<Q, BASE, 0, 1, PA, PB>(acc, fr, r, cp, c, lds, 1, F, G, nb, sa, sb);
+        stage = 0;
+        ++c;
+    }
+    for (; c + 1 < n; c += 2) {                        // pairs of chunks with the stages known
+        pipelined_chunk<Q, BASE, 0, 0, PA, PB>(acc, fr, r, cp, c, lds, 0, F, G, nb, sa, sb);
+        pipelined_chunk<Q, BASE, 0, 1, PA, PB>(acc, fr, r, cp, c + 1, lds, 1, F, G, nb, sa, sb);
+    }
+    if (c < n) {
+        pipelined_chunk<Q, BASE, 0, 0, PA, PB>(acc, fr, r, cp, c, lds, 0, F, G, nb, sa, sb);
+        stage = 1;
     }
 }
 
@@ -628,7 +760,10 @@ __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], cons
     // the following product's descriptors: read now, needed only at this product's last chunk
     const Product next = open_product(W.I, W.J, W.tileC, Lnext, G, R);
 #define GMP_STEADY(PA, PB) case (PA) * 4 + (PB): steady_chunks<Q, BASE, PA, PB>(acc, fr, cur, n, lds, stage, F, G, R.nb, hand, raw); break;
-    switch (cur.a.p * 4 + cur.b.p) {
+    // a scaled operand (FP16 / FP8) whose tile exponent is outside the fused conversions' range
+    const bool wide = !fused_ok<Q>(cur.a.p, cur.a.e) || !fused_ok<Q>(cur.b.p, cur.b.e);
+    switch (wide ? 16 : cur.a.p * 4 + cur.b.p) {
+    case 16: steady_chunks<Q, BASE, -1, -1>(acc, fr, cur, n, lds, stage, F, G, R.nb, hand, raw); break;
         GMP_STEADY(0, 0) GMP_STEADY(0, 1) GMP_STEADY(0, 2) GMP_STEADY(0, 3)
         GMP_STEADY(1, 0) GMP_STEADY(1, 1) GMP_STEADY(1, 2) GMP_STEADY(1, 3)
         GMP_STEADY(2, 0) GMP_STEADY(2, 1) GMP_STEADY(2, 2) GMP_STEADY(2, 3)

@@ -263,6 +263,46 @@ def test_fp32_tiles_made_of_fp8_products_only():
     _run_and_compare(w)
 
 
+def test_extreme_tile_exponents_are_exact():
+    """Tiles of small integers times 2^k with k from -140 to +120, paired so that every product
+    of a C tile carries 2^-20: exact in every format, whatever route the conversion takes (the
+    fused convert-and-scale instructions, the generic conversion for exponents outside their
+    range, the block scales of the FP8-only kernel, which split what one E8M0 cannot hold)."""
+    import torch
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(77)
+    ks = np.array([-140, -128, -120, -104, -60, 0, 60, 100], dtype=np.int64)
+    for nb, maps in ((256, "fp8"), (256, "mixed"), (128, "mixed")):
+        MT, NT, KT = 2, 2, len(ks)
+        M, N, K = MT * nb, NT * nb, KT * nb
+        Ai = rng.integers(-3, 4, (M, K)).astype(np.float64)
+        Bi = rng.integers(-3, 4, (K, N)).astype(np.float64)
+        A, B = Ai.copy(), Bi.copy()
+        for L, k in enumerate(ks):
+            A[:, L * nb:(L + 1) * nb] *= 2.0 ** float(k)
+            B[L * nb:(L + 1) * nb, :] *= 2.0 ** float(-20 - k)
+        if maps == "fp8":
+            mA = np.full((MT, KT), FP8, dtype=np.uint16)
+            mB = np.full((KT, NT), FP8, dtype=np.uint16)
+            mC = np.array([[FP32, FP32], [FP32, FP64]], dtype=np.uint16)
+        else:
+            mA = rng.integers(2, 4, (MT, KT)).astype(np.uint16)          # FP16 / FP8
+            mB = rng.integers(1, 4, (KT, NT)).astype(np.uint16)          # FP32 / FP16 / FP8
+            mB[ks < -100, :] = np.where(mB[ks < -100, :] == FP32, FP16, mB[ks < -100, :])   # 2^(-20-k) * 3 fits FP32 anyway
+            mC = np.array([[FP32, FP64], [FP64, FP32]], dtype=np.uint16)
+        _say("extreme exponents", nb, maps)
+        for policy in (0, 1):
+            d = DeviceGemmMP(M, N, K, nb, policy=policy)
+            for which, m, X in (("A", mA, A), ("B", mB, B)):
+                d.set_precision_map(which, m)
+                d.pack_tiles(which, torch.from_numpy(X).cuda())
+            d.set_precision_map("C", mC)
+            d.run(1.0, 0.0)
+            got = d.unpack_tiles("C").cpu().numpy()
+            want = (Ai.astype(np.int64) @ Bi.astype(np.int64)).astype(np.float64) * 2.0 ** -20
+            assert np.array_equal(got, want)
+
+
 @pytest.mark.parametrize("policy", [0, 1])
 def test_mixed_maps_match_the_oracle_per_tile(policy):
     """All (pA, pB, pC) combinations occur; several owner regions per tile; alpha, beta general."""
