@@ -82,8 +82,13 @@ typedef struct gemm_mp_stats {
 } gemm_mp_stats;
 
 /* Create a context for C(MxN) = A(MxK) * B(KxN) with square tiles of tile_nb (Section 4:
- * tiles of one fixed size).  EINVAL unless all sizes are positive, M, N, K are multiples of
- * tile_nb, and tile_nb is a multiple of 128 (the owner workgroup's footprint).  Host only. */
+ * tiles of one fixed size).  EINVAL unless all sizes are positive and tile_nb is a multiple of
+ * 128 (the owner workgroup's footprint).  M, N, K need not be multiples of tile_nb: a matrix
+ * has ceil(rows / tile_nb) x ceil(cols / tile_nb) tiles, and a tile that sticks out over the
+ * edge is that tile of the matrix padded with zeros (the paper's experiments use multiples
+ * only; zeros add nothing to a product, a norm or a maximum).  Dense matrices are row-major with
+ * a leading dimension ld >= cols that is even, 16-byte aligned, rows * ld entries allocated.
+ * Host only. */
 int gemm_mp_create(gemm_mp_ctx **out, int64_t M, int64_t N, int64_t K, int32_t tile_nb);
 
 /* Release the context and its tables (not the bound buffers). */

@@ -101,6 +101,17 @@ def fp8_value(code):
     return float(lib().orc_fp8_value(int(code)))
 
 
+def pad_to_tiles(X, nb):
+    """A matrix whose sizes are no multiples of nb, as this build reads it (the paper's
+    experiments use multiples only): the same matrix extended with zeros to whole tiles.  Zeros
+    add nothing to a tile's sum of squares, to its maximum or to a product, so every function
+    below is applied to the extension.  No arithmetic here."""
+    X = np.asarray(X, dtype=np.float64)
+    rows, cols = X.shape
+    pr, pc = -rows % nb, -cols % nb
+    return X if pr == 0 and pc == 0 else np.pad(X, ((0, pr), (0, pc)))
+
+
 def tile_scan(X, nb):
     """Per-tile sum of squares (fixed order) and max magnitude; arrays [rows/nb][cols/nb]."""
     X = _dense(X)

@@ -14,7 +14,8 @@ using namespace gmp;
 namespace {
 
 struct Matrix {
-    int rows_t = 0, cols_t = 0;
+    int64_t rows = 0, cols = 0;    // entries of the dense matrix
+    int rows_t = 0, cols_t = 0;    // tiles: ceil(rows / nb), ceil(cols / nb)
     bool has_map = false;
     std::vector<uint16_t> map;
     std::vector<uint64_t> offset;
@@ -311,7 +312,7 @@ int run_scan(gemm_mp_ctx *c, Matrix &m, const double *dense, int64_t ld, hipStre
 {
     int rc;
     if ((rc = ensure_scan_buffers(c, m))) return rc;
-    HIP_TRY(launch_scan(dense, ld, m.rows_t, m.cols_t, c->nb, m.d_part_sum, m.d_part_max, m.d_sumsq, m.d_maxabs, s));
+    HIP_TRY(launch_scan(dense, ld, m.rows, m.cols, m.rows_t, m.cols_t, c->nb, m.d_part_sum, m.d_part_max, m.d_sumsq, m.d_maxabs, s));
     return GEMM_MP_OK;
 }
 
@@ -322,16 +323,17 @@ extern "C" {
 int gemm_mp_create(gemm_mp_ctx **out, int64_t M, int64_t N, int64_t K, int32_t nb)
 {
     if (!out || M <= 0 || N <= 0 || K <= 0 || nb <= 0) return GEMM_MP_EINVAL;
-    if (nb % kMacro != 0 || nb > 8192 || M % nb || N % nb || K % nb) return GEMM_MP_EINVAL;
-    if (M / nb > 32767 || N / nb > 32767 || K / nb > 32767) return GEMM_MP_EINVAL;
-    if ((M / nb) * (N / nb) > (int64_t)1 << 24 || (M / nb) * (N / nb) * (K / nb) > (int64_t)1 << 28) return GEMM_MP_EINVAL;
+    if (nb % kMacro != 0 || nb > 8192) return GEMM_MP_EINVAL;
+    const int64_t mt = (M + nb - 1) / nb, nt = (N + nb - 1) / nb, kt = (K + nb - 1) / nb;
+    if (mt > 32767 || nt > 32767 || kt > 32767) return GEMM_MP_EINVAL;
+    if (mt * nt > (int64_t)1 << 24 || mt * nt * kt > (int64_t)1 << 28) return GEMM_MP_EINVAL;
     gemm_mp_ctx *c = new (std::nothrow) gemm_mp_ctx();
     if (!c) return GEMM_MP_ENOMEM;
     c->M = M; c->N = N; c->K = K; c->nb = nb;
-    c->MT = (int)(M / nb); c->NT = (int)(N / nb); c->KT = (int)(K / nb);
-    c->mat[0].rows_t = c->MT; c->mat[0].cols_t = c->KT;
-    c->mat[1].rows_t = c->KT; c->mat[1].cols_t = c->NT;
-    c->mat[2].rows_t = c->MT; c->mat[2].cols_t = c->NT;
+    c->MT = (int)mt; c->NT = (int)nt; c->KT = (int)kt;
+    c->mat[0].rows_t = c->MT; c->mat[0].cols_t = c->KT; c->mat[0].rows = M; c->mat[0].cols = K;
+    c->mat[1].rows_t = c->KT; c->mat[1].cols_t = c->NT; c->mat[1].rows = K; c->mat[1].cols = N;
+    c->mat[2].rows_t = c->MT; c->mat[2].cols_t = c->NT; c->mat[2].rows = M; c->mat[2].cols = N;
     std::memset(&c->stats, 0, sizeof(c->stats));
     *out = c;
     return GEMM_MP_OK;
@@ -376,7 +378,7 @@ int gemm_mp_tile_scan(gemm_mp_ctx *c, char which, const double *dense, int64_t l
     if (!c || w < 0) return GEMM_MP_EINVAL;
     Matrix &m = c->mat[w];
     int rc;
-    if ((rc = check_dense(dense, ld, (int64_t)m.cols_t * c->nb))) return rc;
+    if ((rc = check_dense(dense, ld, m.cols))) return rc;
     hipStream_t s = (hipStream_t)stream;
     if ((rc = run_scan(c, m, dense, ld, s))) return rc;
     HIP_TRY(hipStreamSynchronize(s));
@@ -395,7 +397,7 @@ int gemm_mp_compute_precision_map(gemm_mp_ctx *c, char which, const double *dens
     if (w == 2 && (allowed_mask & 0xCu)) return GEMM_MP_EUNSUPPORTED;
     Matrix &m = c->mat[w];
     int rc;
-    if ((rc = check_dense(dense, ld, (int64_t)m.cols_t * c->nb))) return rc;
+    if ((rc = check_dense(dense, ld, m.cols))) return rc;
     hipStream_t s = (hipStream_t)stream;
     if ((rc = run_scan(c, m, dense, ld, s))) return rc;
     HIP_TRY(hipStreamSynchronize(s));
@@ -459,7 +461,7 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *c, char which, const double *dense, int64_t 
     Matrix &m = c->mat[w];
     if (!m.has_map || !m.storage) return GEMM_MP_ESTATE;
     int rc;
-    if ((rc = check_dense(dense, ld, (int64_t)m.cols_t * c->nb))) return rc;
+    if ((rc = check_dense(dense, ld, m.cols))) return rc;
     hipStream_t s = (hipStream_t)stream;
     if ((rc = ensure_tables(m))) return rc;
     if (!m.exps_from_rule) {
@@ -471,7 +473,7 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *c, char which, const double *dense, int64_t 
         HIP_TRY(launch_exps(m.d_maxabs, m.d_prec, m.d_exp, m.ntiles(), s));
         m.exps_valid = true;
     }
-    HIP_TRY(launch_pack(dense, ld, m.rows_t, m.cols_t, c->nb, w == 1, view_of(m), s));
+    HIP_TRY(launch_pack(dense, ld, m.rows, m.cols, m.rows_t, m.cols_t, c->nb, w == 1, view_of(m), s));
     m.packed = true;
     m.last_stream = s;
     if (w < 2) c->conv_active = false;            // converted copies of the old data are stale
@@ -485,10 +487,10 @@ int gemm_mp_unpack_tiles(gemm_mp_ctx *c, char which, double *dense, int64_t ld, 
     Matrix &m = c->mat[w];
     if (!m.has_map || !m.storage) return GEMM_MP_ESTATE;
     int rc;
-    if ((rc = check_dense(dense, ld, (int64_t)m.cols_t * c->nb))) return rc;
+    if ((rc = check_dense(dense, ld, m.cols))) return rc;
     if ((rc = ensure_tables(m))) return rc;
     hipStream_t s = (hipStream_t)stream;
-    HIP_TRY(launch_unpack(dense, ld, m.rows_t, m.cols_t, c->nb, w == 1, view_of(m), s));
+    HIP_TRY(launch_unpack(dense, ld, m.rows, m.cols, m.rows_t, m.cols_t, c->nb, w == 1, view_of(m), s));
     m.last_stream = s;
     return GEMM_MP_OK;
 }

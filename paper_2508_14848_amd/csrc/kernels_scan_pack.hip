@@ -10,9 +10,11 @@ namespace gmp {
 // 512 contiguous bytes per row.  The 128 column sums of a workgroup are then added pairwise,
 // neighbours first; because nb is a multiple of 128 these seven levels are exactly the lowest
 // seven levels of the pairing over the whole tile.  scan_finish_kernel adds the nb/128 roots
-// of a tile with the same rule (an odd element is carried up).
+// of a tile with the same rule (an odd element is carried up).  The matrix has rows x cols
+// entries; a tile that sticks out over its edge counts the missing entries as zeros (adding
+// fma(0, 0, s) leaves s as it is, so the sums are those of the zero-padded matrix bit for bit).
 __global__ __launch_bounds__(kScanCols) void scan_cols_kernel(const double *__restrict__ X,
-                                                              int64_t ld, int nb, int parts,
+                                                              int64_t ld, int64_t rows, int64_t cols, int nb, int parts,
                                                               int cols_t,
                                                               double *__restrict__ part_sum,
                                                               double *__restrict__ part_max)
@@ -24,7 +26,10 @@ __global__ __launch_bounds__(kScanCols) void scan_cols_kernel(const double *__re
     const int I = blockIdx.y;
     const double *p = X + (int64_t)I * nb * ld + col;
     double s = 0.0, m = 0.0;
-    for (int r = 0; r < nb; r += 8) {
+    const int64_t left = rows - (int64_t)I * nb;                 // rows of the matrix from this tile row on
+    const int rmax = col < cols ? (left < nb ? (int)left : nb) : 0;
+    int r = 0;
+    for (; r + 8 <= rmax; r += 8) {
         double x[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) x[u] = p[(int64_t)(r + u) * ld];
@@ -34,6 +39,12 @@ __global__ __launch_bounds__(kScanCols) void scan_cols_kernel(const double *__re
             const double ax = __builtin_fabs(x[u]);
             if (ax > m) m = ax;      // a NaN never enters m
         }
+    }
+    for (; r < rmax; ++r) {          // the last rows of a matrix whose row count is no multiple of 8
+        const double x = p[(int64_t)r * ld];
+        s = __builtin_fma(x, x, s);
+        const double ax = __builtin_fabs(x);
+        if (ax > m) m = ax;
     }
     vs[tx] = s;
     vm[tx] = m;
@@ -81,13 +92,13 @@ __global__ void scan_finish_kernel(const double *__restrict__ part_sum,
     maxabs[t] = m;
 }
 
-hipError_t launch_scan(const double *X, int64_t ld, int rows_t, int cols_t, int nb,
+hipError_t launch_scan(const double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb,
                        double *part_sum, double *part_max, double *sumsq, double *maxabs,
                        hipStream_t s)
 {
     const int parts = nb / kScanCols;
     dim3 grid((unsigned)((int64_t)cols_t * nb / kScanCols), (unsigned)rows_t);
-    scan_cols_kernel<<<grid, kScanCols, 0, s>>>(X, ld, nb, parts, cols_t, part_sum, part_max);
+    scan_cols_kernel<<<grid, kScanCols, 0, s>>>(X, ld, rows, cols, nb, parts, cols_t, part_sum, part_max);
     const int ntiles = rows_t * cols_t;
     scan_finish_kernel<<<(ntiles + 63) / 64, 64, 0, s>>>(part_sum, part_max, parts, ntiles, sumsq, maxabs);
     return hipGetLastError();
@@ -217,9 +228,11 @@ __device__ inline void store4(char *dst, int p, const uint64_t (&v)[4])
 // Pack: each workgroup converts one 64 x 64 block that lies inside one tile.  Threads read four
 // consecutive FP64 values of a row (coalesced 512 B per 16 lanes); for A and C they store the
 // four converted values directly; for B the block is turned through LDS so that the stores run
-// along the reduction index, which is the contiguous one in a packed B tile.
+// along the reduction index, which is the contiguous one in a packed B tile.  A block on the
+// edge of a rows x cols matrix reads only what exists and stores zeros for the rest, so every
+// packed tile is a full tile of the zero-padded matrix.
 template <bool TRANSPOSE>
-__global__ __launch_bounds__(256) void pack_kernel(const double *__restrict__ X, int64_t ld, int nb,
+__global__ __launch_bounds__(256) void pack_kernel(const double *__restrict__ X, int64_t ld, int64_t rows, int64_t cols, int nb,
                                                    int cols_t, PackedView v)
 {
     __shared__ uint64_t turn[TRANSPOSE ? kPackBlock : 1][TRANSPOSE ? kPackBlock + 1 : 1];
@@ -232,11 +245,21 @@ __global__ __launch_bounds__(256) void pack_kernel(const double *__restrict__ X,
     char *base = v.storage + v.offset[tile];
     const int r_in = (int)(R0 % nb), c_in = (int)(C0 % nb);
     const int es = elem_bytes(p);
+    const bool inside = R0 + kPackBlock <= rows && C0 + kPackBlock <= cols;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
         const int r = t / 16 + 16 * it, c4 = (t % 16) * 4;
         const double2 *src = (const double2 *)(X + (R0 + r) * ld + C0 + c4);
-        const double2 x01 = src[0], x23 = src[1];
+        double2 x01 = make_double2(0.0, 0.0), x23 = x01;
+        if (inside) {
+            x01 = src[0];
+            x23 = src[1];
+        } else if (R0 + r < rows) {
+            // pairs are read whole where the row's allocation (ld entries, ld even) holds them
+            const int64_t c = C0 + c4;
+            if (c < cols) { x01 = src[0]; if (c + 1 >= cols) x01.y = 0.0; }
+            if (c + 2 < cols) { x23 = src[1]; if (c + 3 >= cols) x23.y = 0.0; }
+        }
         uint64_t b[4] = {stored_bits(x01.x, p, e), stored_bits(x01.y, p, e),
                          stored_bits(x23.x, p, e), stored_bits(x23.y, p, e)};
         if (!TRANSPOSE) {
@@ -257,12 +280,12 @@ __global__ __launch_bounds__(256) void pack_kernel(const double *__restrict__ X,
     }
 }
 
-hipError_t launch_pack(const double *X, int64_t ld, int rows_t, int cols_t, int nb, bool transpose,
+hipError_t launch_pack(const double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb, bool transpose,
                        PackedView v, hipStream_t s)
 {
     dim3 grid((unsigned)((int64_t)cols_t * nb / kPackBlock), (unsigned)((int64_t)rows_t * nb / kPackBlock));
-    if (transpose) pack_kernel<true><<<grid, 256, 0, s>>>(X, ld, nb, cols_t, v);
-    else pack_kernel<false><<<grid, 256, 0, s>>>(X, ld, nb, cols_t, v);
+    if (transpose) pack_kernel<true><<<grid, 256, 0, s>>>(X, ld, rows, cols, nb, cols_t, v);
+    else pack_kernel<false><<<grid, 256, 0, s>>>(X, ld, rows, cols, nb, cols_t, v);
     return hipGetLastError();
 }
 
@@ -281,8 +304,9 @@ __device__ inline double stored_value(const char *base, int64_t idx, int p, int 
     }
 }
 
+// Only the rows x cols entries of the matrix are written.
 template <bool TRANSPOSE>
-__global__ __launch_bounds__(256) void unpack_kernel(double *__restrict__ X, int64_t ld, int nb,
+__global__ __launch_bounds__(256) void unpack_kernel(double *__restrict__ X, int64_t ld, int64_t rows, int64_t cols, int nb,
                                                      int cols_t, PackedView v)
 {
     __shared__ double turn[TRANSPOSE ? kPackBlock : 1][TRANSPOSE ? kPackBlock + 1 : 1];
@@ -312,18 +336,24 @@ __global__ __launch_bounds__(256) void unpack_kernel(double *__restrict__ X, int
         for (int j = 0; j < 4; ++j)
             x[j] = TRANSPOSE ? turn[c4 + j][r]
                              : stored_value(base, (int64_t)(r_in + r) * nb + c_in + c4 + j, p, e);
-        double2 *dst = (double2 *)(X + (R0 + r) * ld + C0 + c4);
-        dst[0] = make_double2(x[0], x[1]);
-        dst[1] = make_double2(x[2], x[3]);
+        if (R0 + kPackBlock <= rows && C0 + kPackBlock <= cols) {
+            double2 *dst = (double2 *)(X + (R0 + r) * ld + C0 + c4);
+            dst[0] = make_double2(x[0], x[1]);
+            dst[1] = make_double2(x[2], x[3]);
+        } else if (R0 + r < rows) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (C0 + c4 + j < cols) X[(R0 + r) * ld + C0 + c4 + j] = x[j];
+        }
     }
 }
 
-hipError_t launch_unpack(double *X, int64_t ld, int rows_t, int cols_t, int nb, bool transpose,
+hipError_t launch_unpack(double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb, bool transpose,
                          PackedView v, hipStream_t s)
 {
     dim3 grid((unsigned)((int64_t)cols_t * nb / kPackBlock), (unsigned)((int64_t)rows_t * nb / kPackBlock));
-    if (transpose) unpack_kernel<true><<<grid, 256, 0, s>>>(X, ld, nb, cols_t, v);
-    else unpack_kernel<false><<<grid, 256, 0, s>>>(X, ld, nb, cols_t, v);
+    if (transpose) unpack_kernel<true><<<grid, 256, 0, s>>>(X, ld, rows, cols, nb, cols_t, v);
+    else unpack_kernel<false><<<grid, 256, 0, s>>>(X, ld, rows, cols, nb, cols_t, v);
     return hipGetLastError();
 }
 

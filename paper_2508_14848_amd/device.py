@@ -68,10 +68,9 @@ class DeviceGemmMP:
         self.ctx.clear_conversion()
 
     def unpack_tiles(self, which, out=None):
-        rows, cols = self.ctx.tiles(which)
-        nb = self.ctx.nb
-        if out is None:
-            out = torch.empty((rows * nb, cols * nb), dtype=torch.float64, device=self.device)
+        rows, cols = {"A": (self.ctx.M, self.ctx.K), "B": (self.ctx.K, self.ctx.N), "C": (self.ctx.M, self.ctx.N)}[which]
+        if out is None:                          # rows of an even length, as the library asks
+            out = torch.empty((rows, cols + (cols & 1)), dtype=torch.float64, device=self.device)[:, :cols]
         self.ctx.unpack_tiles(which, out.data_ptr(), out.stride(0), _stream())
         return out
 

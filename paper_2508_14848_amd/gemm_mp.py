@@ -107,7 +107,7 @@ class GemmMP:
         self._h = ctypes.c_void_p()
         _check(lib().gemm_mp_create(ctypes.byref(self._h), M, N, K, tile_nb), "gemm_mp_create")
         self.M, self.N, self.K, self.nb = M, N, K, tile_nb
-        self.MT, self.NT, self.KT = M // tile_nb, N // tile_nb, K // tile_nb
+        self.MT, self.NT, self.KT = -(-M // tile_nb), -(-N // tile_nb), -(-K // tile_nb)
 
     def destroy(self):
         if self._h:

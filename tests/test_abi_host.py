@@ -24,12 +24,25 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_create_rejects_bad_sizes():
-    for args in ((0, 256, 256, 128), (256, 256, 256, 0), (256, 256, 300, 128), (256, 256, 256, 64),
-                 (256, 256, 256, 96), (-256, 256, 256, 128), (1 << 15, 1 << 15, 1 << 15, 16384)):
+    for args in ((0, 256, 256, 128), (256, 256, 256, 0), (256, 0, 300, 128), (256, 256, 256, 64),
+                 (256, 256, 256, 96), (-256, 256, 256, 128), (1 << 15, 1 << 15, 1 << 15, 16384),
+                 (128 * 32768, 128, 128, 128)):
         with pytest.raises(G.GemmMPError) as e:
             G.GemmMP(*args)
         assert e.value.status == G.EINVAL
     G.GemmMP(256, 512, 384, 128).destroy()
+    # sizes off the tile grid: tile counts round up, maps have that shape
+    g = G.GemmMP(300, 520, 777, 128)
+    assert g.tiles("A") == (3, 7) and g.tiles("B") == (7, 5) and g.tiles("C") == (3, 5)
+    g.set_precision_map("A", np.zeros((3, 7), dtype=np.uint16))
+    assert g.storage_bytes("A") == 3 * 7 * 128 * 128 * 8          # whole tiles are stored
+    with pytest.raises(G.GemmMPError) as e:
+        g.set_precision_map("B", np.zeros((6, 5), dtype=np.uint16))
+    assert e.value.status == G.EINVAL
+    g.destroy()
+    g = G.GemmMP(1, 1, 1, 128)
+    assert g.tiles("C") == (1, 1)
+    g.destroy()
 
 
 def test_map_validation_and_call_order():

@@ -303,6 +303,73 @@ def test_extreme_tile_exponents_are_exact():
             assert np.array_equal(got, want)
 
 
+def _even_ld(X):
+    """The array as a device tensor whose rows have an even length (what the library asks)."""
+    import torch
+    rows, cols = X.shape
+    buf = torch.zeros((rows, cols + (cols & 1)), dtype=torch.float64, device="cuda")
+    buf[:, :cols] = torch.from_numpy(X).cuda()
+    return buf[:, :cols]
+
+
+def test_sizes_that_are_no_multiples_of_the_tile_size():
+    """M, N, K off the tile grid: scan, rule and pack agree bit for bit with the oracle on the
+    zero-padded matrices, the product of small integers is exact for random maps, and general
+    data stays within the per-tile bounds; nothing outside the M x N entries of C is written."""
+    import torch
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(123)
+    for (M, N, K, nb) in ((300, 520, 777, 128), (1000, 257, 513, 256), (129, 127, 1, 128)):
+        MT, NT, KT = -(-M // nb), -(-N // nb), -(-K // nb)
+        _say("ragged", (M, N, K, nb))
+        # integers: exact
+        A = rng.integers(-3, 4, (M, K)).astype(np.float64)
+        B = rng.integers(-3, 4, (K, N)).astype(np.float64)
+        C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
+        mA = rng.integers(0, 4, (MT, KT)).astype(np.uint16)
+        mB = rng.integers(0, 4, (KT, NT)).astype(np.uint16)
+        mC = rng.integers(0, 2, (MT, NT)).astype(np.uint16)
+        for policy in (0, 1):
+            d = DeviceGemmMP(M, N, K, nb, policy=policy)
+            for which, m, X in (("A", mA, A), ("B", mB, B), ("C", mC, C0)):
+                d.set_precision_map(which, m)
+                d.pack_tiles(which, _even_ld(X))
+            d.run(2.0, -3.0)
+            out = torch.full((M + 3, N + 4 + (N & 1)), -7.0, dtype=torch.float64, device="cuda")
+            d.unpack_tiles("C", out=out[:M, :N])
+            got = out.cpu().numpy()
+            want = 2 * (A.astype(np.int64) @ B.astype(np.int64)) - 3 * C0.astype(np.int64)
+            assert np.array_equal(got[:M, :N], want.astype(np.float64))
+            assert np.all(got[M:] == -7.0) and np.all(got[:, N:] == -7.0)
+        # general data: scan, rule, pack and product against the oracle on the padded matrices
+        X = {"A": rng.standard_normal((M, K)) * np.exp(rng.uniform(-8, 8, (M, 1))),
+             "B": rng.standard_normal((K, N)) * np.exp(rng.uniform(-8, 8, (1, N)))}
+        d = DeviceGemmMP(M, N, K, nb)
+        maps, stored, exps = {}, {}, {}
+        for which in ("A", "B"):
+            dX = _even_ld(X[which])
+            Xp = orc.pad_to_tiles(X[which], nb)
+            s0, m0 = orc.tile_scan(Xp, nb)
+            s1, m1 = d.tile_scan(which, dX)
+            assert np.array_equal(s0, s1) and np.array_equal(m0, m1)
+            maps[which] = d.compute_precision_map(which, dX, 1e-6, 0b1111)
+            assert np.array_equal(maps[which], orc.precision_rule(s0, 1e-6, 0b1111))
+            d.pack_tiles(which, dX)
+            stored[which], exps[which] = orc.store_tiles(Xp, nb, maps[which], m0)
+            rows, cols = X[which].shape
+            value = np.ldexp(stored[which], np.kron(exps[which], np.ones((nb, nb), dtype=np.int32)))   # y * 2^e per tile
+            assert np.array_equal(d.unpack_tiles(which).cpu().numpy(), value[:rows, :cols])
+        d.set_precision_map("C", mC)
+        d.run(1.0, 0.0)
+        C_gpu = np.zeros((MT * nb, NT * nb))
+        C_gpu[:M, :N] = d.unpack_tiles("C").cpu().numpy()
+        w = W.Workload("ragged", MT * nb, NT * nb, KT * nb, nb, 1.0, 0.0)
+        w.mapA, w.mapB, w.mapC = maps["A"], maps["B"], mC
+        side = OracleSide(w, orc.pad_to_tiles(X["A"], nb), orc.pad_to_tiles(X["B"], nb), None)
+        jobs = _all_jobs(w)
+        compare_jobs(side, jobs, 0, 1.0, 0.0, C_gpu, side.gemm(jobs, alpha=1.0, beta=0.0))
+
+
 @pytest.mark.parametrize("policy", [0, 1])
 def test_mixed_maps_match_the_oracle_per_tile(policy):
     """All (pA, pB, pC) combinations occur; several owner regions per tile; alpha, beta general."""

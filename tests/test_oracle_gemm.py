@@ -292,3 +292,34 @@ def test_stored_tiles_match_library_casts_and_scale_window():
                     # through FP32, which for these seeded values lands on no e4m3 midpoint
                     t = torch.from_numpy(scaled).to(torch.float8_e4m3fn).to(torch.float64).numpy()
                     assert np.array_equal(Y[blk], t)
+
+
+def test_a_ragged_problem_is_its_zero_padded_extension():
+    """Sizes that are no multiples of the tile size: the oracle works on the zero-padded
+    matrices.  Pinned against what does not depend on tiling at all: the exact integer product of
+    the unpadded matrices, numpy's sums of squares and maxima of the partial tiles, and zeros
+    (exactly) in the padding of C."""
+    rng = np.random.default_rng(17)
+    nb, M, N, K = 8, 19, 13, 21
+    A = rng.integers(-3, 4, (M, K)).astype(np.float64)
+    B = rng.integers(-3, 4, (K, N)).astype(np.float64)
+    C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
+    Ap, Bp, Cp = orc.pad_to_tiles(A, nb), orc.pad_to_tiles(B, nb), orc.pad_to_tiles(C0, nb)
+    assert Ap.shape == (24, 24) and Bp.shape == (24, 16) and Cp.shape == (24, 16)
+    assert np.array_equal(Ap[:M, :K], A) and not Ap[M:].any() and not Ap[:, K:].any()
+    MT, NT, KT = 3, 2, 3
+    mA = rng.integers(0, 4, (MT, KT)).astype(np.uint16)
+    mB = rng.integers(0, 4, (KT, NT)).astype(np.uint16)
+    mC = rng.integers(0, 2, (MT, NT)).astype(np.uint16)
+    for policy in (orc.POLICY_OPERAND, orc.POLICY_C_TILE):
+        C = _run(nb, Ap, mA, Bp, mB, Cp, mC, 2.0, -3.0, policy=policy)
+        want = 2 * (A.astype(np.int64) @ B.astype(np.int64)) - 3 * C0.astype(np.int64)
+        assert np.array_equal(C[:M, :N], want.astype(np.float64))
+        assert not C[M:].any() and not C[:, N:].any()
+    X = rng.standard_normal((M, K))
+    s, m = orc.tile_scan(orc.pad_to_tiles(X, nb), nb)
+    for I in range(MT):
+        for L in range(KT):
+            t = X[I * nb:(I + 1) * nb, L * nb:(L + 1) * nb]
+            assert m[I, L] == np.abs(t).max()
+            assert abs(s[I, L] - np.sum(t * t)) <= 1e-14 * np.sum(t * t)
