@@ -97,6 +97,16 @@ int gemm_mp_destroy(gemm_mp_ctx *ctx);
 /* Choose the product-precision policy (see above).  Host only. */
 int gemm_mp_set_policy(gemm_mp_ctx *ctx, int policy);
 
+/* Transposed operands: declare that the dense buffers of matrix `which` ('A' or 'B'; EINVAL for
+ * 'C') hold its transpose, i.e. the K x M array of A^T or the N x K array of B^T, row-major
+ * (the paper's routine and experiments are C = A*B with untransposed operands, Section 4;
+ * BLAS callers have op(A), op(B)).  Maps, tile indices and the packed layout stay those of the
+ * matrix itself, and the tile scan keeps its order of operations (defined on the matrix, not on
+ * the buffer); only the addressing of gemm_mp_tile_scan, gemm_mp_compute_precision_map,
+ * gemm_mp_pack_tiles and gemm_mp_unpack_tiles changes, whose ld must then be >= the matrix's
+ * row count.  Takes effect from the next of those calls.  Host only. */
+int gemm_mp_set_transposed(gemm_mp_ctx *ctx, char which, int transposed);
+
 /* Give the precision map of matrix `which` ('A', 'B' or 'C'): rows x cols codes, row-major,
  * host memory, copied (Section 5.2).  rows/cols must equal the matrix's tile counts (EINVAL),
  * codes must be 0..3 (EINVAL); C tiles may only be FP64 or FP32 (EUNSUPPORTED).  Any earlier

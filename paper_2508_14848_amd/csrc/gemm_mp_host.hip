@@ -16,6 +16,7 @@ namespace {
 struct Matrix {
     int64_t rows = 0, cols = 0;    // entries of the dense matrix
     int rows_t = 0, cols_t = 0;    // tiles: ceil(rows / nb), ceil(cols / nb)
+    bool transposed = false;       // dense buffers of this matrix hold its transpose (cols x rows)
     bool has_map = false;
     std::vector<uint16_t> map;
     std::vector<uint64_t> offset;
@@ -312,7 +313,7 @@ int run_scan(gemm_mp_ctx *c, Matrix &m, const double *dense, int64_t ld, hipStre
 {
     int rc;
     if ((rc = ensure_scan_buffers(c, m))) return rc;
-    HIP_TRY(launch_scan(dense, ld, m.rows, m.cols, m.rows_t, m.cols_t, c->nb, m.d_part_sum, m.d_part_max, m.d_sumsq, m.d_maxabs, s));
+    HIP_TRY(launch_scan(dense, ld, m.transposed, m.rows, m.cols, m.rows_t, m.cols_t, c->nb, m.d_part_sum, m.d_part_max, m.d_sumsq, m.d_maxabs, s));
     return GEMM_MP_OK;
 }
 
@@ -357,6 +358,18 @@ int gemm_mp_set_policy(gemm_mp_ctx *c, int policy)
     return GEMM_MP_OK;
 }
 
+int gemm_mp_set_transposed(gemm_mp_ctx *c, char which, int transposed)
+{
+    const int w = which_index(which);
+    if (!c || w < 0 || w == 2 || (transposed != 0 && transposed != 1)) return GEMM_MP_EINVAL;
+    Matrix &m = c->mat[w];
+    if (m.transposed != (transposed != 0)) {
+        m.transposed = transposed != 0;
+        m.exps_from_rule = false;                  // a scan made under the other layout says nothing now
+    }
+    return GEMM_MP_OK;
+}
+
 int gemm_mp_set_precision_map(gemm_mp_ctx *c, char which, const uint16_t *map, int32_t rows, int32_t cols)
 {
     const int w = which_index(which);
@@ -378,7 +391,7 @@ int gemm_mp_tile_scan(gemm_mp_ctx *c, char which, const double *dense, int64_t l
     if (!c || w < 0) return GEMM_MP_EINVAL;
     Matrix &m = c->mat[w];
     int rc;
-    if ((rc = check_dense(dense, ld, m.cols))) return rc;
+    if ((rc = check_dense(dense, ld, m.transposed ? m.rows : m.cols))) return rc;
     hipStream_t s = (hipStream_t)stream;
     if ((rc = run_scan(c, m, dense, ld, s))) return rc;
     HIP_TRY(hipStreamSynchronize(s));
@@ -397,7 +410,7 @@ int gemm_mp_compute_precision_map(gemm_mp_ctx *c, char which, const double *dens
     if (w == 2 && (allowed_mask & 0xCu)) return GEMM_MP_EUNSUPPORTED;
     Matrix &m = c->mat[w];
     int rc;
-    if ((rc = check_dense(dense, ld, m.cols))) return rc;
+    if ((rc = check_dense(dense, ld, m.transposed ? m.rows : m.cols))) return rc;
     hipStream_t s = (hipStream_t)stream;
     if ((rc = run_scan(c, m, dense, ld, s))) return rc;
     HIP_TRY(hipStreamSynchronize(s));
@@ -461,7 +474,7 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *c, char which, const double *dense, int64_t 
     Matrix &m = c->mat[w];
     if (!m.has_map || !m.storage) return GEMM_MP_ESTATE;
     int rc;
-    if ((rc = check_dense(dense, ld, m.cols))) return rc;
+    if ((rc = check_dense(dense, ld, m.transposed ? m.rows : m.cols))) return rc;
     hipStream_t s = (hipStream_t)stream;
     if ((rc = ensure_tables(m))) return rc;
     if (!m.exps_from_rule) {
@@ -473,7 +486,10 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *c, char which, const double *dense, int64_t 
         HIP_TRY(launch_exps(m.d_maxabs, m.d_prec, m.d_exp, m.ntiles(), s));
         m.exps_valid = true;
     }
-    HIP_TRY(launch_pack(dense, ld, m.rows, m.cols, m.rows_t, m.cols_t, c->nb, w == 1, view_of(m), s));
+    if (m.transposed)
+        HIP_TRY(launch_pack(dense, ld, m.cols, m.rows, m.cols_t, m.rows_t, c->nb, w != 1, true, view_of(m), s));
+    else
+        HIP_TRY(launch_pack(dense, ld, m.rows, m.cols, m.rows_t, m.cols_t, c->nb, w == 1, false, view_of(m), s));
     m.packed = true;
     m.last_stream = s;
     if (w < 2) c->conv_active = false;            // converted copies of the old data are stale
@@ -487,10 +503,13 @@ int gemm_mp_unpack_tiles(gemm_mp_ctx *c, char which, double *dense, int64_t ld, 
     Matrix &m = c->mat[w];
     if (!m.has_map || !m.storage) return GEMM_MP_ESTATE;
     int rc;
-    if ((rc = check_dense(dense, ld, m.cols))) return rc;
+    if ((rc = check_dense(dense, ld, m.transposed ? m.rows : m.cols))) return rc;
     if ((rc = ensure_tables(m))) return rc;
     hipStream_t s = (hipStream_t)stream;
-    HIP_TRY(launch_unpack(dense, ld, m.rows, m.cols, m.rows_t, m.cols_t, c->nb, w == 1, view_of(m), s));
+    if (m.transposed)
+        HIP_TRY(launch_unpack(dense, ld, m.cols, m.rows, m.cols_t, m.rows_t, c->nb, w != 1, true, view_of(m), s));
+    else
+        HIP_TRY(launch_unpack(dense, ld, m.rows, m.cols, m.rows_t, m.cols_t, c->nb, w == 1, false, view_of(m), s));
     m.last_stream = s;
     return GEMM_MP_OK;
 }

@@ -82,15 +82,15 @@ struct GemmArgs {
 
 // rows x cols: the entries the dense matrix has; rows_t x cols_t: its tiles (the last ones may
 // stick out over the edge and are zero-padded).
-hipError_t launch_scan(const double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb,
+hipError_t launch_scan(const double *X, int64_t ld, bool transposed, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb,
                        double *part_sum, double *part_max, double *sumsq, double *maxabs,
                        hipStream_t s);
 hipError_t launch_exps(const double *maxabs, const uint8_t *prec, int32_t *exps, int ntiles,
                        hipStream_t s);
-hipError_t launch_pack(const double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb, bool transpose,
-                       PackedView v, hipStream_t s);
-hipError_t launch_unpack(double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb, bool transpose,
-                         PackedView v, hipStream_t s);
+hipError_t launch_pack(const double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb, bool turn,
+                       bool swap, PackedView v, hipStream_t s);
+hipError_t launch_unpack(double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb, bool turn,
+                         bool swap, PackedView v, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);
 hipError_t launch_convert(const ConvertJob *jobs_dev, int njobs, uint32_t max_n16, const int32_t *expA, const int32_t *expB,
                           hipStream_t s);

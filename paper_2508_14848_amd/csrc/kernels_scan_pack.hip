@@ -13,8 +13,10 @@ namespace gmp {
 // of a tile with the same rule (an odd element is carried up).  The matrix has rows x cols
 // entries; a tile that sticks out over its edge counts the missing entries as zeros (adding
 // fma(0, 0, s) leaves s as it is, so the sums are those of the zero-padded matrix bit for bit).
+// Entry (r, c) of the matrix is X[r * sr + c * sc]: (ld, 1) as given, (1, ld) when the buffer
+// holds the transpose; the order of the sums is that of the matrix, not of the buffer.
 __global__ __launch_bounds__(kScanCols) void scan_cols_kernel(const double *__restrict__ X,
-                                                              int64_t ld, int64_t rows, int64_t cols, int nb, int parts,
+                                                              int64_t sr, int64_t sc, int64_t rows, int64_t cols, int nb, int parts,
                                                               int cols_t,
                                                               double *__restrict__ part_sum,
                                                               double *__restrict__ part_max)
@@ -24,7 +26,7 @@ __global__ __launch_bounds__(kScanCols) void scan_cols_kernel(const double *__re
     const int tx = threadIdx.x;
     const int64_t col = (int64_t)blockIdx.x * kScanCols + tx;
     const int I = blockIdx.y;
-    const double *p = X + (int64_t)I * nb * ld + col;
+    const double *p = X + (int64_t)I * nb * sr + col * sc;
     double s = 0.0, m = 0.0;
     const int64_t left = rows - (int64_t)I * nb;                 // rows of the matrix from this tile row on
     const int rmax = col < cols ? (left < nb ? (int)left : nb) : 0;
@@ -32,7 +34,7 @@ __global__ __launch_bounds__(kScanCols) void scan_cols_kernel(const double *__re
     for (; r + 8 <= rmax; r += 8) {
         double x[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = p[(int64_t)(r + u) * ld];
+        for (int u = 0; u < 8; ++u) x[u] = p[(int64_t)(r + u) * sr];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             s = __builtin_fma(x[u], x[u], s);
@@ -41,7 +43,7 @@ __global__ __launch_bounds__(kScanCols) void scan_cols_kernel(const double *__re
         }
     }
     for (; r < rmax; ++r) {          // the last rows of a matrix whose row count is no multiple of 8
-        const double x = p[(int64_t)r * ld];
+        const double x = p[(int64_t)r * sr];
         s = __builtin_fma(x, x, s);
         const double ax = __builtin_fabs(x);
         if (ax > m) m = ax;
@@ -92,13 +94,14 @@ __global__ void scan_finish_kernel(const double *__restrict__ part_sum,
     maxabs[t] = m;
 }
 
-hipError_t launch_scan(const double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb,
+hipError_t launch_scan(const double *X, int64_t ld, bool transposed, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb,
                        double *part_sum, double *part_max, double *sumsq, double *maxabs,
                        hipStream_t s)
 {
     const int parts = nb / kScanCols;
     dim3 grid((unsigned)((int64_t)cols_t * nb / kScanCols), (unsigned)rows_t);
-    scan_cols_kernel<<<grid, kScanCols, 0, s>>>(X, ld, rows, cols, nb, parts, cols_t, part_sum, part_max);
+    scan_cols_kernel<<<grid, kScanCols, 0, s>>>(X, transposed ? 1 : ld, transposed ? ld : 1, rows, cols, nb, parts, cols_t,
+                                                part_sum, part_max);
     const int ntiles = rows_t * cols_t;
     scan_finish_kernel<<<(ntiles + 63) / 64, 64, 0, s>>>(part_sum, part_max, parts, ntiles, sumsq, maxabs);
     return hipGetLastError();
@@ -233,13 +236,13 @@ __device__ inline void store4(char *dst, int p, const uint64_t (&v)[4])
 // packed tile is a full tile of the zero-padded matrix.
 template <bool TRANSPOSE>
 __global__ __launch_bounds__(256) void pack_kernel(const double *__restrict__ X, int64_t ld, int64_t rows, int64_t cols, int nb,
-                                                   int cols_t, PackedView v)
+                                                   int rows_t, int cols_t, bool swap, PackedView v)
 {
     __shared__ uint64_t turn[TRANSPOSE ? kPackBlock : 1][TRANSPOSE ? kPackBlock + 1 : 1];
     const int t = threadIdx.x;
     const int64_t R0 = (int64_t)blockIdx.y * kPackBlock, C0 = (int64_t)blockIdx.x * kPackBlock;
     const int I = (int)(R0 / nb), J = (int)(C0 / nb);
-    const int tile = I * cols_t + J;
+    const int tile = swap ? J * rows_t + I : I * cols_t + J;      // swap: the buffer holds the matrix's transpose
     const int p = v.prec[tile];
     const int e = v.exp[tile];
     char *base = v.storage + v.offset[tile];
@@ -280,12 +283,14 @@ __global__ __launch_bounds__(256) void pack_kernel(const double *__restrict__ X,
     }
 }
 
-hipError_t launch_pack(const double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb, bool transpose,
-                       PackedView v, hipStream_t s)
+// rows x cols, rows_t x cols_t: the buffer as it lies in memory.  turn: the rows of a packed tile
+// are the buffer's columns; swap: tile (I, J) of the buffer is tile (J, I) of the matrix.
+hipError_t launch_pack(const double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb, bool turn,
+                       bool swap, PackedView v, hipStream_t s)
 {
     dim3 grid((unsigned)((int64_t)cols_t * nb / kPackBlock), (unsigned)((int64_t)rows_t * nb / kPackBlock));
-    if (transpose) pack_kernel<true><<<grid, 256, 0, s>>>(X, ld, rows, cols, nb, cols_t, v);
-    else pack_kernel<false><<<grid, 256, 0, s>>>(X, ld, rows, cols, nb, cols_t, v);
+    if (turn) pack_kernel<true><<<grid, 256, 0, s>>>(X, ld, rows, cols, nb, rows_t, cols_t, swap, v);
+    else pack_kernel<false><<<grid, 256, 0, s>>>(X, ld, rows, cols, nb, rows_t, cols_t, swap, v);
     return hipGetLastError();
 }
 
@@ -307,13 +312,13 @@ __device__ inline double stored_value(const char *base, int64_t idx, int p, int 
 // Only the rows x cols entries of the matrix are written.
 template <bool TRANSPOSE>
 __global__ __launch_bounds__(256) void unpack_kernel(double *__restrict__ X, int64_t ld, int64_t rows, int64_t cols, int nb,
-                                                     int cols_t, PackedView v)
+                                                     int rows_t, int cols_t, bool swap, PackedView v)
 {
     __shared__ double turn[TRANSPOSE ? kPackBlock : 1][TRANSPOSE ? kPackBlock + 1 : 1];
     const int t = threadIdx.x;
     const int64_t R0 = (int64_t)blockIdx.y * kPackBlock, C0 = (int64_t)blockIdx.x * kPackBlock;
     const int I = (int)(R0 / nb), J = (int)(C0 / nb);
-    const int tile = I * cols_t + J;
+    const int tile = swap ? J * rows_t + I : I * cols_t + J;      // swap: the buffer holds the matrix's transpose
     const int p = v.prec[tile];
     const int e = v.exp[tile];
     const char *base = v.storage + v.offset[tile];
@@ -348,12 +353,12 @@ __global__ __launch_bounds__(256) void unpack_kernel(double *__restrict__ X, int
     }
 }
 
-hipError_t launch_unpack(double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb, bool transpose,
-                         PackedView v, hipStream_t s)
+hipError_t launch_unpack(double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb, bool turn,
+                         bool swap, PackedView v, hipStream_t s)
 {
     dim3 grid((unsigned)((int64_t)cols_t * nb / kPackBlock), (unsigned)((int64_t)rows_t * nb / kPackBlock));
-    if (transpose) unpack_kernel<true><<<grid, 256, 0, s>>>(X, ld, rows, cols, nb, cols_t, v);
-    else unpack_kernel<false><<<grid, 256, 0, s>>>(X, ld, rows, cols, nb, cols_t, v);
+    if (turn) unpack_kernel<true><<<grid, 256, 0, s>>>(X, ld, rows, cols, nb, rows_t, cols_t, swap, v);
+    else unpack_kernel<false><<<grid, 256, 0, s>>>(X, ld, rows, cols, nb, rows_t, cols_t, swap, v);
     return hipGetLastError();
 }
 

@@ -33,6 +33,11 @@ class DeviceGemmMP:
         self.ctx.bind_storage(which, buf.data_ptr(), buf.numel())
         self.storage[which] = buf
 
+    def set_transposed(self, which, transposed):
+        self.ctx.set_transposed(which, transposed)
+        self.transposed = getattr(self, "transposed", {})
+        self.transposed[which] = bool(transposed)
+
     def set_precision_map(self, which, pmap):
         self.ctx.set_precision_map(which, pmap)
         self.maps[which] = np.array(pmap, dtype=np.uint16)
@@ -69,6 +74,8 @@ class DeviceGemmMP:
 
     def unpack_tiles(self, which, out=None):
         rows, cols = {"A": (self.ctx.M, self.ctx.K), "B": (self.ctx.K, self.ctx.N), "C": (self.ctx.M, self.ctx.N)}[which]
+        if getattr(self, "transposed", {}).get(which):
+            rows, cols = cols, rows
         if out is None:                          # rows of an even length, as the library asks
             out = torch.empty((rows, cols + (cols & 1)), dtype=torch.float64, device=self.device)[:, :cols]
         self.ctx.unpack_tiles(which, out.data_ptr(), out.stride(0), _stream())

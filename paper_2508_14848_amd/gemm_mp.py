@@ -19,7 +19,7 @@ POLICY_OPERAND, POLICY_C_TILE = 0, 1
 OK, EINVAL, ESTATE, ENOMEM, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = [
-    "gemm_mp_create", "gemm_mp_destroy", "gemm_mp_set_policy", "gemm_mp_set_precision_map",
+    "gemm_mp_create", "gemm_mp_destroy", "gemm_mp_set_policy", "gemm_mp_set_transposed", "gemm_mp_set_precision_map",
     "gemm_mp_tile_scan", "gemm_mp_compute_precision_map", "gemm_mp_storage_bytes",
     "gemm_mp_bind_storage", "gemm_mp_pack_tiles", "gemm_mp_run", "gemm_mp_unpack_tiles",
     "gemm_mp_tile_info", "gemm_mp_get_stats", "gemm_mp_product_precision", "gemm_mp_strerror",
@@ -55,6 +55,7 @@ def lib():
         L.gemm_mp_create.argtypes = [ctypes.POINTER(P), i64, i64, i64, i32]
         L.gemm_mp_destroy.argtypes = [P]
         L.gemm_mp_set_policy.argtypes = [P, ctypes.c_int]
+        L.gemm_mp_set_transposed.argtypes = [P, c, ctypes.c_int]
         L.gemm_mp_set_precision_map.argtypes = [P, c, P, i32, i32]
         L.gemm_mp_tile_scan.argtypes = [P, c, P, i64, P, P, P]
         L.gemm_mp_compute_precision_map.argtypes = [P, c, P, i64, dbl, ctypes.c_uint32, P, P]
@@ -125,6 +126,9 @@ class GemmMP:
 
     def set_policy(self, policy):
         _check(lib().gemm_mp_set_policy(self._h, policy), "gemm_mp_set_policy")
+
+    def set_transposed(self, which, transposed):
+        _check(lib().gemm_mp_set_transposed(self._h, _w(which), int(bool(transposed))), "gemm_mp_set_transposed")
 
     def set_precision_map(self, which, pmap):
         pmap = np.ascontiguousarray(pmap, dtype=np.uint16)

@@ -42,6 +42,11 @@ def test_create_rejects_bad_sizes():
     g.destroy()
     g = G.GemmMP(1, 1, 1, 128)
     assert g.tiles("C") == (1, 1)
+    g.set_transposed("A", 1)
+    g.set_transposed("B", 0)
+    with pytest.raises(G.GemmMPError) as e:
+        g.set_transposed("C", 1)                       # C is always given as it is
+    assert e.value.status == G.EINVAL
     g.destroy()
 
 

@@ -370,6 +370,44 @@ def test_sizes_that_are_no_multiples_of_the_tile_size():
         compare_jobs(side, jobs, 0, 1.0, 0.0, C_gpu, side.gemm(jobs, alpha=1.0, beta=0.0))
 
 
+def test_transposed_operands():
+    """A and / or B given as the buffer of their transpose: scan, rule, stored values and the
+    product are bit for bit those of the same matrices given directly (sizes off the tile grid
+    included), and the unpacked buffer is the transpose again."""
+    import torch
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(9)
+    for (M, N, K, nb) in ((384, 256, 512, 128), (300, 200, 457, 128)):
+        A = rng.standard_normal((M, K)) * np.exp(rng.uniform(-6, 6, (M, 1)))
+        B = rng.standard_normal((K, N)) * np.exp(rng.uniform(-6, 6, (1, N)))
+        mC = rng.integers(0, 2, (-(-M // nb), -(-N // nb))).astype(np.uint16)
+        results = []
+        for (tA, tB) in ((0, 0), (1, 0), (0, 1), (1, 1)):
+            _say("transposed", (M, N, K, nb), tA, tB)
+            d = DeviceGemmMP(M, N, K, nb)
+            d.set_transposed("A", tA)
+            d.set_transposed("B", tB)
+            scans, maps, back = {}, {}, {}
+            for which, X, t in (("A", A, tA), ("B", B, tB)):
+                dX = _even_ld(np.ascontiguousarray(X.T) if t else X)
+                scans[which] = d.tile_scan(which, dX)
+                maps[which] = d.compute_precision_map(which, dX, 1e-5, 0b1111)
+                d.pack_tiles(which, dX)
+                u = d.unpack_tiles(which).cpu().numpy()
+                back[which] = u.T if t else u
+            d.set_precision_map("C", mC)
+            d.run(1.25, 0.0)
+            results.append((scans, maps, back, d.unpack_tiles("C").cpu().numpy()))
+        s0, m0, b0, c0 = results[0]
+        for (s1, m1, b1, c1) in results[1:]:
+            for which in ("A", "B"):
+                assert np.array_equal(s0[which][0], s1[which][0]) and np.array_equal(s0[which][1], s1[which][1])
+                assert np.array_equal(m0[which], m1[which]) and np.array_equal(b0[which], b1[which])
+            assert np.array_equal(c0, c1)
+        sA, mA = orc.tile_scan(orc.pad_to_tiles(A, nb), nb)
+        assert np.array_equal(s0["A"][0], sA) and np.array_equal(s0["A"][1], mA)
+
+
 @pytest.mark.parametrize("policy", [0, 1])
 def test_mixed_maps_match_the_oracle_per_tile(policy):
     """All (pA, pB, pC) combinations occur; several owner regions per tile; alpha, beta general."""
