@@ -1,28 +1,32 @@
-// Owner-workgroup kernel of the tile-centric mixed-precision GEMM for gfx950 (CDNA4).
+// Owner-workgroup kernels of the tile-centric mixed-precision GEMM for gfx950 (CDNA4).
 //
-// One workgroup (256 threads = 4 waves as 2 x 2) owns a 128 x 128 region of one C tile for the
-// whole reduction: it walks the reduction tiles L = 0..KT-1 in ascending order, runs each tile
-// product A(I,L)*B(L,J) on the matrix cores at that task's precision q, and writes C once.
-// Nothing else ever touches that region, so there are no atomics and the result is
-// reproducible.
+// One workgroup (256 threads = 4 waves as 2 x 2) owns a region of one C tile for the whole
+// reduction: it walks the reduction tiles L = 0..KT-1 in ascending order, runs each tile product
+// A(I,L)*B(L,J) on the matrix cores at that task's precision q, and writes C once.  Nothing else
+// ever touches that region, so there are no atomics and the result is reproducible.  Regions
+// are 128 x 128 (gemm_mp_owner_kernel, one instance for FP64 and one for FP32 C tiles), or
+// 256 x 256 for FP32 C tiles whose products are all FP8 x FP8 (gemm_mp_fp8_region_kernel, at
+// the end of this file).
 //
 // Data path of one reduction chunk (128 bytes of converted reduction index per row, i.e.
-// 16 FP64 / 32 FP32 / 64 FP16 / 128 FP8 values):
-//   global (stored precision) -> registers -> convert to q ("receiver-side conversion": exact
-//   up-casts with the tile's 2^e applied, or the one down-cast FP64 -> FP32) -> LDS (rows of
-//   128 B + 8 B pad) -> 16x16 MFMA fragments.  The loads of the next chunk are issued before
-//   the MFMAs of the current one and land in the other LDS stage afterwards; the chunk stream
-//   runs across tile-product boundaries so the pipeline never drains inside a C region.
-// FP16 / FP8 products of FP32 C tiles whose operands need no conversion skip the registers:
+// 16 FP64 / 32 FP32 / 64 FP16 / 128 FP8 values) in the 128 x 128 kernels:
+//   FP64 / FP32 products: global (stored precision) -> registers -> convert to q ("receiver-side
+//   conversion": exact up-casts with the tile's 2^e applied, or the one down-cast FP64 -> FP32)
+//   -> LDS (unpadded rows, 16-byte segments swizzled) -> 16x16 MFMA fragments.  The loads of
+//   the next chunk are issued under the MFMAs of the current one and land in the other LDS
+//   stage; the stream runs across tile-product boundaries so the pipeline never drains inside
+//   a C region.
+//   FP16 / FP8 products of FP32 C tiles whose operands need no conversion skip the registers:
 //   global -> LDS by buffer-load-to-LDS into a ring of five unpadded, swizzled stages.
+//   Other FP16 / FP8 products: a two-stage loop with conversion in registers, rows padded by 8 B.
 //
 // Fragment convention.  Packed A tiles are row-major and packed B tiles are stored transposed,
-// so both operands have the reduction index contiguous.  Lane (i = lane%16, g = lane/16) reads
-// bytes [32g, 32g+32) of row i of a 16-row block for both operands; which reduction index that
-// is does not matter as long as A and B agree, and they do by construction.  The accumulator
-// of a 16x16 FP32-result MFMA holds C[4g+v][i] in register v; the FP64 MFMA holds C[4v+g][i],
-// so on the FP64 path lane i reads A row 4*(i%4) + i/4 instead of row i, which makes both
-// accumulator kinds address the same C element in the same lane and register.
+// so both operands have the reduction index contiguous.  Which reduction index a lane's bytes
+// are does not matter as long as A and B agree, and they do by construction.  The accumulator
+// of a 16x16 FP32-result MFMA holds C[4g+v][i] in register v (i = lane%16, g = lane/16); the
+// FP64 MFMA holds C[4v+g][i], so on the FP64 path lane i reads A row 4*(i%4) + i/4 instead of
+// row i, which makes both accumulator kinds address the same C element in the same lane and
+// register.
 #include <type_traits>
 #include <utility>
 
@@ -40,13 +44,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vectors:
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kRowBytes = 128;                       // converted bytes per row and chunk
-constexpr int kRowStride = 136;                      // + 8 B pad: 17 eight-byte words per row, so the
-                                                     // 16 rows x 4 k-groups of a fragment read and the
-                                                     // 8 rows x 8 parts of a staging write each spread
-                                                     // evenly over the LDS banks
-constexpr int kOperandStage = kMacro * kRowStride;   // 17408 B
+constexpr int kRowStride = 136;                      // padded stages (two-stage FP16 / FP8 loop): + 8 B,
+                                                     // 17 eight-byte words per row, so the 16 rows x 4
+                                                     // k-groups of a fragment read and the 8 rows x 8
+                                                     // parts of a staging write spread over the banks
+constexpr int kOperandStage = kMacro * kRowStride;   // 17408 B: operand pitch of padded and of swizzled stages
 constexpr int kStage = 2 * kOperandStage;            // A then B
-constexpr int kHiLdsBytes = 2 * kStage;              // FP64 / FP32 products: two stages, 69632 B
+constexpr int kHiLdsBytes = 2 * kStage;              // two stages, 69632 B
 
 // FP16 / FP8 products use a ring of five stages of unpadded 128-byte rows whose 16-byte slots
 // are XOR-swizzled with (row & 7): slot = segment ^ (row & 7).
@@ -800,7 +804,7 @@ __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], cons
 // These MFMAs are fast (a chunk is ~530 matrix-core cycles per wave) and, unlike the FP64/FP32
 // ones, overlap with vector-ALU work; what limits them is the latency of global memory and the
 // LDS.  Consecutive FP16/FP8 products of a C region are therefore run as one stream of chunks
-// through a ring of four LDS stages, each chunk requested three chunks ahead.  An operand
+// through a ring of five LDS stages, each chunk requested four chunks ahead.  An operand
 // stored in the product's own precision goes from global memory straight into LDS with the
 // buffer-load-to-LDS instruction (no registers, no vector ALU); an FP8 tile feeding an FP16
 // product goes through registers (exact FP8 -> FP16 conversion) one chunk later.
