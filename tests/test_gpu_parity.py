@@ -408,6 +408,56 @@ def test_transposed_operands():
         assert np.array_equal(s0["A"][0], sA) and np.array_equal(s0["A"][1], mA)
 
 
+def test_random_small_integer_problems_are_exact():
+    """Three hundred seeded problems of small integers: tile sizes 128..512, one to three tiles a
+    side and up to six along the reduction, sizes on and off the tile grid, four styles of maps
+    (anything; FP16 / FP8 only on FP32 C tiles; all FP8 with exceptions; FP64 / FP32 only), both
+    policies, operands given directly or transposed, receiver- or sender-side conversion, integer
+    alpha and beta.  Every format holds the data exactly, so C must equal alpha*A*B + beta*C0
+    bit for bit whichever kernels, chunk loops and hand-overs a problem happens to exercise."""
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(20250814)
+    for case in range(300):
+        nb = int(rng.choice([128, 256, 384, 512]))
+        MT, NT, KT = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.integers(1, 7))
+        ragged = rng.random() < 0.3
+        M = MT * nb - (int(rng.integers(1, nb)) if ragged else 0)
+        N = NT * nb - (int(rng.integers(1, nb)) if ragged else 0)
+        K = KT * nb - (int(rng.integers(1, nb)) if ragged else 0)
+        policy, style = int(rng.integers(0, 2)), int(rng.integers(0, 4))
+        if style == 0:
+            mA, mB, mC = rng.integers(0, 4, (MT, KT)), rng.integers(0, 4, (KT, NT)), rng.integers(0, 2, (MT, NT))
+        elif style == 1:
+            mA, mB, mC = rng.integers(2, 4, (MT, KT)), rng.integers(2, 4, (KT, NT)), np.ones((MT, NT), dtype=np.int64)
+        elif style == 2:
+            mA, mB, mC = np.full((MT, KT), FP8), np.full((KT, NT), FP8), rng.integers(0, 2, (MT, NT))
+            if rng.random() < 0.5:
+                mA[rng.integers(MT), rng.integers(KT)] = rng.integers(0, 3)
+        else:
+            mA, mB, mC = rng.integers(0, 2, (MT, KT)), rng.integers(0, 2, (KT, NT)), rng.integers(0, 2, (MT, NT))
+        alpha, beta = float(rng.integers(-2, 3)), float(rng.integers(-2, 3))
+        A = rng.integers(-3, 4, (M, K)).astype(np.float64)
+        B = rng.integers(-3, 4, (K, N)).astype(np.float64)
+        C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
+        tA, tB, sender = int(rng.integers(0, 2)), int(rng.integers(0, 2)), rng.random() < 0.3
+        what = dict(case=case, nb=nb, M=M, N=N, K=K, policy=policy, style=style, alpha=alpha, beta=beta, tA=tA, tB=tB,
+                    sender=bool(sender))
+        if case % 50 == 0:
+            _say("random integers", what)
+        d = DeviceGemmMP(M, N, K, nb, policy=policy)
+        d.set_transposed("A", tA)
+        d.set_transposed("B", tB)
+        for which, m, X, t in (("A", mA, A, tA), ("B", mB, B, tB), ("C", mC, C0, 0)):
+            d.set_precision_map(which, m.astype(np.uint16))
+            d.pack_tiles(which, _even_ld(np.ascontiguousarray(X.T) if t else X))
+        if sender:
+            d.convert_tiles()
+        d.run(alpha, beta)
+        got = d.unpack_tiles("C").cpu().numpy()
+        want = alpha * (A @ B) + beta * C0               # exact in FP64: small integers
+        assert np.array_equal(got, want), what
+
+
 @pytest.mark.parametrize("policy", [0, 1])
 def test_mixed_maps_match_the_oracle_per_tile(policy):
     """All (pA, pB, pC) combinations occur; several owner regions per tile; alpha, beta general."""
