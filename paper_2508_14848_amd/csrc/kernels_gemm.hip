@@ -16,7 +16,7 @@
 //   the next chunk are issued under the MFMAs of the current one and land in the other LDS
 //   stage; the stream runs across tile-product boundaries so the pipeline never drains inside
 //   a C region.
-//   FP16 / FP8 products of FP32 C tiles whose operands need no conversion skip the registers:
+//   FP16 / FP8 products whose operands need no conversion skip the registers:
 //   global -> LDS by buffer-load-to-LDS into a ring of five unpadded, swizzled stages.
 //   Other FP16 / FP8 products: a two-stage loop with conversion in registers, rows padded by 8 B.
 //
@@ -173,7 +173,7 @@ __device__ __forceinline__ u32x4 convert(const Raw &r, int p, int e, int sub)
 }
 
 struct Geometry {
-    bool ring;                      // FP32 C tiles only: pure FP16 / FP8 products go through the DMA ring
+    bool ring;                      // pure FP16 / FP8 products go through the DMA ring (set for both kernel instances)
     int tid, lane, li, g, wm, wn;
     int seg_row, seg_part;          // staging: this thread's first row and its 16-byte part
     int wbase;                      // byte offset of that segment in a padded LDS operand stage
@@ -186,9 +186,8 @@ struct Region {
     const ProductDesc *prod;        // this C tile's row of the product table: entry L
 };
 
-// On FP32 C tiles, FP16 / FP8 products whose operands are both stored in the product's precision
-// run through the DMA ring (lo_run); every other product expects its first chunk staged by its
-// predecessor.
+// FP16 / FP8 products whose operands are both stored in the product's precision run through the
+// DMA ring (lo_run); every other product expects its first chunk staged by its predecessor.
 __device__ __forceinline__ bool is_ring(const Product &pr, const Geometry &G)
 {
     return G.ring && (pr.q == Q16 || pr.q == Q8) && pr.a.p == pr.q && pr.b.p == pr.q;
@@ -1130,8 +1129,7 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
 }
 
 // ---- FP16 / FP8 products outside the ring: two-stage loop, conversion in registers ----------
-// Used for FP16 products with an FP8 operand and for every FP16 / FP8 product of an FP64 C tile
-// (whose kernel has no registers to spare for the ring's fragment sets).  One chunk = 2 k-steps
+// Used for FP16 products with an FP8 operand (exact FP8 -> FP16 conversion).  One chunk = 2 k-steps
 // of 16x16x32 FP16, or one 16x16x128 FP8 step; the loads of the following chunk are in flight
 // while the MFMAs of a chunk run.
 template <int Q>
@@ -1264,7 +1262,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     Geometry G;
-    G.ring = QT == Q32;
+    G.ring = true;
     G.tid = threadIdx.x;
     G.lane = G.tid & 63;
     G.li = G.lane & 15;
