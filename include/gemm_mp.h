@@ -37,6 +37,16 @@
  * infinities, max finite 448).  FP16 / FP8 tiles hold x * 2^-e with one
  * power-of-two exponent e per tile chosen so that the largest magnitude falls
  * in [2^14,2^15) resp. [2^7,2^8); e = 0 for an all-zero tile.
+ *
+ * C tiles stored in FP16 / FP8 (formats beyond FP64 / FP32 are what the paper's
+ * Section 6 leaves open): such a tile is a storage format only.  Its products
+ * get the precisions an FP32 tile's would and it is accumulated in FP32; when
+ * the tile is finished its largest magnitude fixes a new exponent e by the rule
+ * above and every entry is rounded once more, from FP32, to nearest even.  With
+ * beta != 0 the old tile enters as stored number * 2^e.  The FP32 form lives in
+ * a staging copy per such tile that follows the packed tiles in C's buffer
+ * (gemm_mp_storage_bytes counts it), so the library still allocates no operand
+ * memory; only gemm_mp_run touches the staging area.
  */
 #ifndef GEMM_MP_H
 #define GEMM_MP_H
@@ -65,9 +75,11 @@ enum {
 
 /* How the precision q of the product A(I,L)*B(L,J) that updates C(I,J) is chosen.
  *   OPERAND (default): the better of the two operands' stored precisions, but never above
- *       what the C tile keeps: q = min(cap(pC), max(pA,pB)), cap(FP64)=FP64, else FP32.
+ *       the type the C tile is accumulated in: q = min(cap(pC), max(pA,pB)), cap(FP64)=FP64,
+ *       else FP32.
  *   C_TILE: the paper's literal statement (Section 5.2: the result precision follows the C
- *       tile and operands are converted when their maps differ): q = pC.
+ *       tile and operands are converted when their maps differ): q = cap(pC), which is pC
+ *       itself on the paper's FP64 / FP32 maps.
  * The two agree on FP64/FP32 maps except for (pA,pB,pC) = (FP32,FP32,FP64). */
 enum { GEMM_MP_POLICY_OPERAND = 0, GEMM_MP_POLICY_C_TILE = 1 };
 
@@ -109,8 +121,8 @@ int gemm_mp_set_transposed(gemm_mp_ctx *ctx, char which, int transposed);
 
 /* Give the precision map of matrix `which` ('A', 'B' or 'C'): rows x cols codes, row-major,
  * host memory, copied (Section 5.2).  rows/cols must equal the matrix's tile counts (EINVAL),
- * codes must be 0..3 (EINVAL); C tiles may only be FP64 or FP32 (EUNSUPPORTED).  Any earlier
- * binding and packed data of that matrix are forgotten.  Host only. */
+ * codes must be 0..3 (EINVAL).  Any earlier binding and packed data of that matrix are
+ * forgotten.  Host only. */
 int gemm_mp_set_precision_map(gemm_mp_ctx *ctx, char which, const uint16_t *map_host,
                               int32_t rows, int32_t cols);
 
@@ -136,7 +148,8 @@ int gemm_mp_compute_precision_map(gemm_mp_ctx *ctx, char which, const double *de
                                   int64_t ld, double threshold, uint32_t allowed_mask,
                                   gemm_mp_stream stream, uint16_t *map_out_host);
 
-/* Bytes the packed form of matrix `which` needs; ESTATE before its map is set.  Host only. */
+/* Bytes the packed form of matrix `which` needs (for C: plus 4 * tile_nb^2 bytes of staging per
+ * FP16 / FP8 tile); ESTATE before its map is set.  Host only. */
 int gemm_mp_storage_bytes(gemm_mp_ctx *ctx, char which, size_t *bytes);
 
 /* Bind the caller's device buffer (256-byte aligned, at least storage_bytes) that holds, or

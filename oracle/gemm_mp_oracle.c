@@ -326,7 +326,13 @@ int32_t orc_product_precision(int32_t pA, int32_t pB, int32_t pC, int32_t policy
 /*   v = alpha x_T s  (+_T  beta x_T c0  when beta != 0; c0 is never read     */
 /*   when beta == 0);  alpha, beta are rounded to T;  C = v rounded to pC.    */
 /* alpha == 0 skips the products (s = 0).                                     */
-/* Only pC in {FP64, FP32} is defined.  Returns 0, or -1 on a bad argument.   */
+/* pC in {FP16, FP8} (a reading: the paper has FP64 / FP32 tiles only and     */
+/* leaves further formats to Section 6): the tile is accumulated as an FP32   */
+/* tile (T = FP32, product precisions as for pC = FP32), Cy holds the values   */
+/* the old tile stands for (stored number * 2^e, see orc_stored_values), and  */
+/* what a job returns is v in FP32; the rounding to pC needs the finished     */
+/* tile's largest magnitude, so the caller applies orc_store_tiles to whole   */
+/* tiles of v afterwards.  Returns 0, or -1 on a bad argument.                */
 /*                                                                           */
 /* So that a caller can also walk the loop nest exactly as Algorithm 1 prints */
 /* it (reduction tile index outermost), a call may cover only the tile range  */
@@ -356,8 +362,8 @@ int32_t orc_gemm_jobs(int64_t M, int64_t N, int64_t K, int32_t nb,
             c1 > nb || c0 > c1)
             return -1;
         int pC = mapC[I * NT + J];
-        if (pC != P_FP64 && pC != P_FP32) return -1;
-        int T = pC;                                   /* accumulate type: FP64 or FP32 */
+        if (pC < P_FP64 || pC > P_FP8) return -1;
+        int T = pC == P_FP64 ? P_FP64 : P_FP32;       /* accumulate type: FP64 or FP32 */
         int64_t nr = r1 - r0, nc = c1 - c0;
         if (nr == 0 || nc == 0) continue;
 
@@ -457,11 +463,22 @@ int32_t orc_gemm_jobs(int64_t M, int64_t N, int64_t K, int32_t nb,
                     if (beta != 0.0) { float bc = bf * (float)Cy[gi * ldc0 + gj]; v = (double)(as + bc); }
                     else v = (double)as;
                 }
-                Cout[gi * ldc + gj] = v;     /* already representable at pC */
+                Cout[gi * ldc + gj] = v;     /* representable in T; FP16 / FP8 tiles: see above */
             }
         free(sD); free(sF); free(bD); free(bF);
     }
     return 0;
+}
+
+/* The values a stored matrix stands for: stored number times 2^e of its tile */
+/* (exact in FP64; e = 0 for FP64 / FP32 tiles).                              */
+void orc_stored_values(const double *Y, int64_t ldy, int64_t rows, int64_t cols, int32_t nb,
+                       const int32_t *exps, double *X, int64_t ldx)
+{
+    int64_t CT = cols / nb;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c)
+            X[r * ldx + c] = ldexp(Y[r * ldy + c], exps[(r / nb) * CT + c / nb]);
 }
 
 int32_t orc_num_threads(void)

@@ -57,6 +57,7 @@ def lib():
                                        P, c_i64, P, P, P, c_i64, P, P, P, c_i64, P,
                                        c_dbl, c_dbl, c_i32, c_i64, P, P, c_i64,
                                        c_i64, c_i64, P, c_i32, c_i32]
+        _lib.orc_stored_values.argtypes = [P, c_i64, c_i64, c_i64, c_i32, P, P, c_i64]
         _lib.orc_num_threads.restype = c_i32
     return _lib
 
@@ -150,6 +151,17 @@ def store_tiles(X, nb, pmap, maxabs=None, out=None):
     return Y, exps
 
 
+def stored_values(Y, nb, exps):
+    """The values stored tiles stand for: stored numbers times 2^e of their tile."""
+    Y = _dense(Y)
+    rows, cols = Y.shape
+    exps = np.ascontiguousarray(exps, dtype=np.int32)
+    assert exps.shape == (rows // nb, cols // nb)
+    X = np.empty_like(Y)
+    lib().orc_stored_values(_p(Y), Y.strides[0] // 8, rows, cols, nb, _p(exps), _p(X), X.strides[0] // 8)
+    return X
+
+
 def product_precision(pA, pB, pC, policy=POLICY_OPERAND):
     return int(lib().orc_product_precision(int(pA), int(pB), int(pC), int(policy)))
 
@@ -158,7 +170,9 @@ def gemm_jobs(nb, Ay, mapA, eA, By, mapB, eB, Cy, mapC, alpha, beta, jobs,
               policy=POLICY_OPERAND, out=None, L_range=None, state=None, resume=False, finish=True):
     """Compute the listed jobs (rows of [I, J, r0, r1, c0, c1]) into a dense FP64 C.
 
-    Cy may be None when beta == 0.  Entries of the result outside the jobs are left as
+    Cy may be None when beta == 0; where C tiles are stored in FP16 / FP8 it holds the values
+    they stand for (stored_values), and the result for such tiles is the FP32 form that
+    store_tiles then rounds, whole tile by whole tile.  Entries of the result outside the jobs are left as
     they were in `out` (NaN in a fresh array).  L_range / state / resume / finish let a
     caller split the reduction over several calls (see the C file)."""
     Ay, By = _dense(Ay), _dense(By)

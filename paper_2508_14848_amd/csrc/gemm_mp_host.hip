@@ -31,6 +31,12 @@ struct Matrix {
     uint64_t *d_offset = nullptr;
     int32_t *d_exp = nullptr;
     double *d_sumsq = nullptr, *d_maxabs = nullptr, *d_part_sum = nullptr, *d_part_max = nullptr;
+    // C only: the tiles stored in FP16 / FP8, each with an FP32 staging copy behind the packed
+    // tiles; the offset table the GEMM kernels see points those tiles at their staging copies
+    std::vector<LowTile> low;
+    LowTile *d_low = nullptr;
+    uint64_t *d_offset_run = nullptr;
+    float *d_low_max = nullptr;
     hipStream_t last_stream = nullptr;
     int ntiles() const { return rows_t * cols_t; }
 };
@@ -44,8 +50,9 @@ struct gemm_mp_ctx {
     Matrix mat[3];
     bool sched_current = false;
     std::vector<uint8_t> q;
-    std::vector<WorkItem> items[3];   // regions of [0] FP64 C tiles, [1] FP32 C tiles, [2] FP32 C tiles
-                                      // whose products are all FP8 x FP8 (256 x 256 regions)
+    std::vector<WorkItem> items[3];   // regions of [0] FP64 C tiles, [1] C tiles accumulated in FP32 (stored
+                                      // FP32 / FP16 / FP8), [2] those of them whose products are all
+                                      // FP8 x FP8 (256 x 256 regions)
     uint8_t *d_q = nullptr;
     ProductDesc *d_prod = nullptr;    // one record per task (+ 2 padding records), filled on the device
     WorkItem *d_items = nullptr;      // the three lists, [0] first
@@ -89,12 +96,15 @@ void free_matrix_tables(Matrix &m)
 {
     (void)hipFree(m.d_prec); (void)hipFree(m.d_offset); (void)hipFree(m.d_exp);
     (void)hipFree(m.d_sumsq); (void)hipFree(m.d_maxabs); (void)hipFree(m.d_part_sum); (void)hipFree(m.d_part_max);
+    (void)hipFree(m.d_low); (void)hipFree(m.d_offset_run); (void)hipFree(m.d_low_max);
+    m.d_low = nullptr; m.d_offset_run = nullptr; m.d_low_max = nullptr;
     m.d_prec = nullptr; m.d_offset = nullptr; m.d_exp = nullptr;
     m.d_sumsq = m.d_maxabs = m.d_part_sum = m.d_part_max = nullptr;
 }
 
-// Packed layout: tiles in row-major order, each at a 256-byte aligned offset.
-void layout(gemm_mp_ctx *c, Matrix &m)
+// Packed layout: tiles in row-major order, each at a 256-byte aligned offset.  Behind the tiles
+// of C follows one FP32 staging copy per tile stored in FP16 / FP8, in tile order.
+void layout(gemm_mp_ctx *c, Matrix &m, bool is_c)
 {
     const uint64_t elems = (uint64_t)c->nb * (uint64_t)c->nb;
     m.offset.resize(m.ntiles());
@@ -103,6 +113,16 @@ void layout(gemm_mp_ctx *c, Matrix &m)
         m.offset[t] = off;
         off += (elems * (uint64_t)elem_bytes(m.map[t]) + 255u) & ~(uint64_t)255u;
     }
+    m.low.clear();
+    for (int t = 0; is_c && t < m.ntiles(); ++t)
+        if (m.map[t] >= GEMM_MP_FP16) {
+            LowTile lt;
+            lt.stage = off;
+            lt.tile = (uint32_t)t;
+            lt.pad = 0;
+            m.low.push_back(lt);
+            off += elems * sizeof(float);
+        }
     m.bytes = off;
 }
 
@@ -112,7 +132,7 @@ int install_map(gemm_mp_ctx *c, int w, const uint16_t *map)
     if (m.last_stream || m.d_prec) (void)hipStreamSynchronize(m.last_stream);   // tables may be in use
     m.map.assign(map, map + m.ntiles());
     m.has_map = true;
-    layout(c, m);
+    layout(c, m, w == 2);
     m.storage = nullptr;
     m.storage_bytes = 0;
     m.packed = false;
@@ -139,6 +159,18 @@ int ensure_tables(Matrix &m)
         for (size_t t = 0; t < n; ++t) p8[t] = (uint8_t)m.map[t];
         HIP_TRY(hipMemcpy(m.d_prec, p8.data(), n, hipMemcpyHostToDevice));
         HIP_TRY(hipMemcpy(m.d_offset, m.offset.data(), n * sizeof(uint64_t), hipMemcpyHostToDevice));
+        (void)hipFree(m.d_low); (void)hipFree(m.d_offset_run); (void)hipFree(m.d_low_max);
+        m.d_low = nullptr; m.d_offset_run = nullptr; m.d_low_max = nullptr;
+        if (!m.low.empty()) {
+            const size_t elems = (size_t)((m.bytes - m.low[0].stage) / m.low.size() / sizeof(float));   // nb * nb
+            std::vector<uint64_t> run(m.offset);
+            for (const LowTile &lt : m.low) run[lt.tile] = lt.stage;
+            if ((rc = dev_alloc(&m.d_low, m.low.size()))) return rc;
+            if ((rc = dev_alloc(&m.d_offset_run, n))) return rc;
+            if ((rc = dev_alloc(&m.d_low_max, m.low.size() * (elems / kLowChunk)))) return rc;
+            HIP_TRY(hipMemcpy(m.d_low, m.low.data(), m.low.size() * sizeof(LowTile), hipMemcpyHostToDevice));
+            HIP_TRY(hipMemcpy(m.d_offset_run, run.data(), n * sizeof(uint64_t), hipMemcpyHostToDevice));
+        }
         m.tables_current = true;
     }
     return GEMM_MP_OK;
@@ -235,13 +267,13 @@ void build_schedule(gemm_mp_ctx *c)
         c->stats.packed_bytes[w] = c->mat[w].bytes;
     }
 
-    // An FP32 C tile whose every product multiplies two tiles stored in FP8 at FP8 goes to the
-    // kernel with 256 x 256 regions (the tile size permitting).
+    // A C tile accumulated in FP32 whose every product multiplies two tiles stored in FP8 at FP8
+    // goes to the kernel with 256 x 256 regions (the tile size permitting).
     std::vector<uint8_t> all_fp8((size_t)MT * NT, 0);
     if (c->nb % kMacroFp8 == 0)
         for (int I = 0; I < MT; ++I)
             for (int J = 0; J < NT; ++J) {
-                bool ok = C.map[I * NT + J] == GEMM_MP_FP32 && KT > 0;
+                bool ok = C.map[I * NT + J] != GEMM_MP_FP64 && KT > 0;
                 for (int L = 0; ok && L < KT; ++L)
                     ok = c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_FP8_E4M3 && A.map[I * KT + L] == GEMM_MP_FP8_E4M3 &&
                          B.map[L * NT + J] == GEMM_MP_FP8_E4M3;
@@ -378,9 +410,6 @@ int gemm_mp_set_precision_map(gemm_mp_ctx *c, char which, const uint16_t *map, i
     if (rows != m.rows_t || cols != m.cols_t) return GEMM_MP_EINVAL;
     for (int t = 0; t < m.ntiles(); ++t)
         if (map[t] > GEMM_MP_FP8_E4M3) return GEMM_MP_EINVAL;
-    if (w == 2)
-        for (int t = 0; t < m.ntiles(); ++t)
-            if (map[t] > GEMM_MP_FP32) return GEMM_MP_EUNSUPPORTED;
     return install_map(c, w, map);
 }
 
@@ -407,7 +436,6 @@ int gemm_mp_compute_precision_map(gemm_mp_ctx *c, char which, const double *dens
 {
     const int w = which_index(which);
     if (!c || w < 0 || !(threshold >= 0.0) || (allowed_mask & 0xFu) == 0 || (allowed_mask & ~0xFu)) return GEMM_MP_EINVAL;
-    if (w == 2 && (allowed_mask & 0xCu)) return GEMM_MP_EUNSUPPORTED;
     Matrix &m = c->mat[w];
     int rc;
     if ((rc = check_dense(dense, ld, m.transposed ? m.rows : m.cols))) return rc;
@@ -534,6 +562,12 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
     }
     GemmArgs a;
     a.A = view_of(A); a.B = view_of(B); a.C = view_of(C);
+    const int n_low = (int)C.low.size();
+    if (n_low) {
+        // FP16 / FP8 C tiles: the kernels work on the FP32 staging copies
+        if (beta != 0.0) HIP_TRY(launch_low_expand(C.d_low, n_low, c->nb, a.C, s));
+        a.C.offset = C.d_offset_run;
+    }
     a.q = c->d_q;
     a.prod = c->d_prod;
     a.convA = c->conv_active ? c->d_conv[0] : nullptr;
@@ -549,6 +583,7 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
     a.kt_eff = alpha == 0.0 ? 0 : c->KT;
     a.alpha = alpha; a.beta = beta;
     HIP_TRY(launch_gemm(a, s));
+    if (n_low) HIP_TRY(launch_low_store(C.d_low, n_low, c->nb, view_of(C), C.d_exp, C.d_low_max, s));
     C.packed = true;
     C.exps_valid = true;
     A.last_stream = B.last_stream = C.last_stream = s;

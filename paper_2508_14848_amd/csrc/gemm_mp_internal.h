@@ -13,6 +13,7 @@ constexpr int kMacro = 128;       // rows = cols of C owned by one workgroup
 constexpr int kMacroFp8 = 256;    // the same for C tiles whose products are all FP8 x FP8
 constexpr int kScanCols = 128;    // columns one scan workgroup reduces; a power of two
 constexpr int kPackBlock = 64;    // pack / unpack move 64 x 64 element blocks
+constexpr int kLowChunk = 4096;   // elements one workgroup handles in the passes over FP16 / FP8 C tiles
 
 // Bytes per element of each precision code.
 __host__ __device__ inline int elem_bytes(int p) { return p == 0 ? 8 : p == 1 ? 4 : p == 2 ? 2 : 1; }
@@ -62,6 +63,14 @@ struct ConvertJob {
     uint32_t pad2;
 };
 
+// A C tile stored in FP16 / FP8: its index and the byte offset, in C's buffer, of the FP32
+// staging copy the GEMM kernels accumulate into.
+struct LowTile {
+    uint64_t stage;
+    uint32_t tile;
+    uint32_t pad;
+};
+
 static_assert(sizeof(ProductDesc) == 32, "the kernel reads a record as two 16-byte scalar loads");
 static_assert(sizeof(WorkItem) == 8, "the kernel reads an item as one 8-byte scalar load");
 
@@ -94,6 +103,9 @@ hipError_t launch_unpack(double *X, int64_t ld, int64_t rows, int64_t cols, int 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);
 hipError_t launch_convert(const ConvertJob *jobs_dev, int njobs, uint32_t max_n16, const int32_t *expA, const int32_t *expB,
                           hipStream_t s);
+hipError_t launch_low_expand(const LowTile *low_dev, int n_low, int nb, PackedView c, hipStream_t s);
+hipError_t launch_low_store(const LowTile *low_dev, int n_low, int nb, PackedView c, int32_t *exps, float *part_max,
+                            hipStream_t s);
 hipError_t gemm_kernel_setup();
 
 }  // namespace gmp

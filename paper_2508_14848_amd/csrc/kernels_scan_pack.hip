@@ -362,4 +362,140 @@ hipError_t launch_unpack(double *X, int64_t ld, int64_t rows, int64_t cols, int 
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// C tiles stored in FP16 / FP8.  Such a tile is accumulated like an FP32 tile, in an FP32
+// staging copy behind the packed tiles of C; around the GEMM kernels three streaming passes,
+// one workgroup per kLowChunk consecutive elements of one such tile, connect the two forms:
+//   expand  (only when beta != 0): staging = stored number * 2^e, exact;
+//   maximum: largest magnitude per chunk, then per tile, and from it the tile's new exponent
+//            by the same rule as for packed operands;
+//   round:   stored number = staging * 2^-e rounded once to nearest even (FP8 saturates).
+__global__ __launch_bounds__(256) void low_expand_kernel(const LowTile *__restrict__ low, PackedView v)
+{
+    const LowTile lt = low[blockIdx.y];
+    const int p = v.prec[lt.tile];
+    const int e = v.exp[lt.tile];
+    const char *src = v.storage + v.offset[lt.tile];
+    float *dst = (float *)(v.storage + lt.stage);
+    const int64_t i0 = (int64_t)blockIdx.x * kLowChunk + threadIdx.x * 4;
+#pragma unroll
+    for (int it = 0; it < kLowChunk / 1024; ++it) {
+        const int64_t i = i0 + it * 1024;
+        float4 x;
+        if (p == GEMM_MP_FP16) {
+            const uint2 h = *(const uint2 *)(src + i * 2);
+            const _Float16 *hh = (const _Float16 *)&h;
+            x = make_float4((float)hh[0], (float)hh[1], (float)hh[2], (float)hh[3]);
+        } else {
+            const uint32_t b = *(const uint32_t *)(src + i);
+            x = make_float4(__builtin_amdgcn_cvt_f32_fp8(b, 0), __builtin_amdgcn_cvt_f32_fp8(b, 1),
+                            __builtin_amdgcn_cvt_f32_fp8(b, 2), __builtin_amdgcn_cvt_f32_fp8(b, 3));
+        }
+        x.x = ldexpf(x.x, e); x.y = ldexpf(x.y, e); x.z = ldexpf(x.z, e); x.w = ldexpf(x.w, e);
+        *(float4 *)(dst + i) = x;
+    }
+}
+
+__global__ __launch_bounds__(256) void low_chunk_max_kernel(const LowTile *__restrict__ low, const char *__restrict__ storage,
+                                                            int parts, float *__restrict__ part_max)
+{
+    __shared__ float wm[4];
+    const LowTile lt = low[blockIdx.y];
+    const float *src = (const float *)(storage + lt.stage);
+    const int64_t i0 = (int64_t)blockIdx.x * kLowChunk + threadIdx.x * 4;
+    float m = 0.0f;
+#pragma unroll
+    for (int it = 0; it < kLowChunk / 1024; ++it) {
+        const float4 x = *(const float4 *)(src + i0 + it * 1024);
+        const float a[4] = {__builtin_fabsf(x.x), __builtin_fabsf(x.y), __builtin_fabsf(x.z), __builtin_fabsf(x.w)};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (a[j] > m) m = a[j];          // a NaN never enters m
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const float o = __shfl_xor(m, d);
+        if (o > m) m = o;
+    }
+    if ((threadIdx.x & 63) == 0) wm[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int k = 1; k < 4; ++k)
+            if (wm[k] > m) m = wm[k];
+        part_max[(int64_t)blockIdx.y * parts + blockIdx.x] = m;
+    }
+}
+
+__global__ __launch_bounds__(256) void low_exponent_kernel(const LowTile *__restrict__ low, const uint8_t *__restrict__ prec,
+                                                           int parts, const float *__restrict__ part_max,
+                                                           int32_t *__restrict__ exps)
+{
+    __shared__ float wm[4];
+    const LowTile lt = low[blockIdx.x];
+    float m = 0.0f;
+    for (int k = threadIdx.x; k < parts; k += 256) {
+        const float x = part_max[(int64_t)blockIdx.x * parts + k];
+        if (x > m) m = x;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const float o = __shfl_xor(m, d);
+        if (o > m) m = o;
+    }
+    if ((threadIdx.x & 63) == 0) wm[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int k = 1; k < 4; ++k)
+            if (wm[k] > m) m = wm[k];
+        const uint32_t bits = __float_as_uint(m);
+        const int field = (int)(bits >> 23);
+        const uint32_t man = bits & 0x7fffffu;
+        int e = 0;
+        if (field != 0xff && bits != 0) {
+            const int lg = field ? field - 127 : 31 - __builtin_clz(man) - 149;
+            e = lg - (prec[lt.tile] == GEMM_MP_FP16 ? 14 : 7);
+        }
+        exps[lt.tile] = e;
+    }
+}
+
+__global__ __launch_bounds__(256) void low_round_kernel(const LowTile *__restrict__ low, PackedView v)
+{
+    const LowTile lt = low[blockIdx.y];
+    const int p = v.prec[lt.tile];
+    const int e = v.exp[lt.tile];
+    char *dst = v.storage + v.offset[lt.tile];
+    const float *src = (const float *)(v.storage + lt.stage);
+    const int es = elem_bytes(p);
+    const int64_t i0 = (int64_t)blockIdx.x * kLowChunk + threadIdx.x * 4;
+#pragma unroll
+    for (int it = 0; it < kLowChunk / 1024; ++it) {
+        const int64_t i = i0 + it * 1024;
+        const float4 x = *(const float4 *)(src + i);
+        const uint64_t b[4] = {stored_bits((double)x.x, p, e), stored_bits((double)x.y, p, e),
+                               stored_bits((double)x.z, p, e), stored_bits((double)x.w, p, e)};
+        store4(dst + i * es, p, b);
+    }
+}
+
+hipError_t launch_low_expand(const LowTile *low_dev, int n_low, int nb, PackedView c, hipStream_t s)
+{
+    if (n_low == 0) return hipSuccess;
+    dim3 grid((unsigned)((int64_t)nb * nb / kLowChunk), (unsigned)n_low);
+    low_expand_kernel<<<grid, 256, 0, s>>>(low_dev, c);
+    return hipGetLastError();
+}
+
+hipError_t launch_low_store(const LowTile *low_dev, int n_low, int nb, PackedView c, int32_t *exps, float *part_max,
+                            hipStream_t s)
+{
+    if (n_low == 0) return hipSuccess;
+    const int parts = (int)((int64_t)nb * nb / kLowChunk);
+    dim3 grid((unsigned)parts, (unsigned)n_low);
+    low_chunk_max_kernel<<<grid, 256, 0, s>>>(low_dev, c.storage, parts, part_max);
+    low_exponent_kernel<<<n_low, 256, 0, s>>>(low_dev, c.prec, parts, part_max, exps);
+    low_round_kernel<<<grid, 256, 0, s>>>(low_dev, c);
+    return hipGetLastError();
+}
+
 }  // namespace gmp

@@ -36,7 +36,8 @@ class OracleSide:
             self.By, self.eB = orc.store_tiles(B, nb, self.mapB, mb)
         self.Cy = None
         if C0 is not None and w.beta != 0.0:
-            self.Cy, _ = orc.store_tiles(C0, nb, self.mapC)
+            Cy, eC = orc.store_tiles(C0, nb, self.mapC)
+            self.Cy = orc.stored_values(Cy, nb, eC)       # what the stored C stands for (e = 0 for FP64 / FP32 tiles)
 
     def gemm(self, jobs, policy=orc.POLICY_OPERAND, alpha=None, beta=None):
         w = self.w
@@ -44,6 +45,17 @@ class OracleSide:
         beta = w.beta if beta is None else beta
         return orc.gemm_jobs(w.nb, self.Ay, self.mapA, self.eA, self.By, self.mapB, self.eB,
                              self.Cy if beta != 0.0 else None, self.mapC, alpha, beta, jobs, policy=policy)
+
+
+def finish_low_c_tiles(side, C):
+    """C tiles stored in FP16 / FP8: the oracle's jobs return their FP32 form; storing whole tiles
+    rounds them.  Returns (values the stored C stands for, exponents).  C must hold whole tiles."""
+    Y, eC = orc.store_tiles(np.ascontiguousarray(C), side.w.nb, side.mapC)
+    return orc.stored_values(Y, side.w.nb, eC), eC
+
+
+# exponent offset of the scaled maximum and smallest step of the scaled format
+LOW_FORMAT = {FP16: (14, 2.0 ** -24), FP8: (7, 2.0 ** -9)}
 
 
 def job_tolerances(side, jobs, policy, alpha):
@@ -70,7 +82,9 @@ def job_tolerances(side, jobs, policy, alpha):
         # differ by a few units of 2^-149 per entry: one per fold and epilogue operation plus one
         # per 32 terms of a reduction carried out at true magnitude.  Frobenius norm over the block.
         eta = 0.0 if pC == FP64 else (K / 32.0 + KT + 3.0) * 2.0 ** -149 * np.sqrt(float((r1 - r0) * (c1 - c0)))
-        out.append(dict(norm=abs(alpha) * norm, tol=4.0 * K * u_tile, tight=2.0 * K * u_acc, all64=all64, eta=eta))
+        if pC >= FP16:
+            u_tile = max(u_tile, U[pC])          # the tile's own storage rounding
+        out.append(dict(norm=abs(alpha) * norm, tol=4.0 * K * u_tile, tight=2.0 * K * u_acc, all64=all64, eta=eta, pC=pC))
     return out
 
 
@@ -95,11 +109,18 @@ def compare_jobs(side, jobs, policy, alpha, beta, C_gpu, C_orc):
         if base == 0.0:
             assert err <= t["eta"]
             continue
+        tight = t["tight"] * base + t["eta"]
+        if t["pC"] >= FP16 and np.any(o != 0.0):
+            # storage rounding of the finished tile, on both sides: relative u_p per entry in the
+            # format's normal range, a full smallest step below it, both doubled because the two
+            # sides' exponents may differ by one when their maxima straddle a power of two
+            E, step = LOW_FORMAT[t["pC"]]
+            e_hi = np.floor(np.log2(np.abs(o).max())) - E + 1
+            tight += 2.0 * U[t["pC"]] * np.linalg.norm(o) + np.sqrt(float(o.size)) * step * 2.0 ** e_hi
         worst["star"] = max(worst["star"], err / (t["tol"] * base))
-        worst["tight"] = max(worst["tight"], err / (t["tight"] * base + t["eta"]))
+        worst["tight"] = max(worst["tight"], err / tight)
         assert err <= t["tol"] * base, "tile (%d,%d): err %.3e > 4*K*u_tile bound %.3e" % (I, J, err, t["tol"] * base)
-        assert err <= t["tight"] * base + t["eta"], "tile (%d,%d): err %.3e > accumulate-precision bound %.3e" % (
-            I, J, err, t["tight"] * base + t["eta"])
+        assert err <= tight, "tile (%d,%d): err %.3e > accumulate-precision bound %.3e" % (I, J, err, tight)
     return worst
 
 

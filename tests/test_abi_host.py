@@ -65,9 +65,6 @@ def test_map_validation_and_call_order():
         g.set_precision_map("A", np.full((4, 3), 4, np.uint16))        # code out of range
     assert e.value.status == G.EINVAL
     with pytest.raises(G.GemmMPError) as e:
-        g.set_precision_map("C", np.full((4, 2), G.FP16, np.uint16))   # C tiles: FP64 / FP32 only
-    assert e.value.status == G.EUNSUPPORTED
-    with pytest.raises(G.GemmMPError) as e:
         g.set_precision_map("X", np.zeros((4, 3), np.uint16))
     assert e.value.status == G.EINVAL
     with pytest.raises(G.GemmMPError) as e:
@@ -110,6 +107,32 @@ def test_packed_layout_offsets_and_sizes():
         g.tile_info("A", 0, 2, want_exp=True)        # FP16 tile, exponent unknown before packing
     assert e.value.status == G.ESTATE
     assert g.tile_info("A", 0, 0, want_exp=True)[2] == 0
+
+
+def test_c_tiles_in_fp16_or_fp8_carry_an_fp32_staging_copy_behind_the_packed_tiles():
+    nb = 256
+    g = G.GemmMP(2 * nb, 3 * nb, nb, nb)
+    mC = np.array([[G.FP64, G.FP16, G.FP32], [G.FP8_E4M3, G.FP32, G.FP16]], dtype=np.uint16)
+    g.set_precision_map("C", mC)
+    packed = sum(nb * nb * (8 >> int(p)) for p in mC.ravel())
+    assert g.storage_bytes("C") == packed + 3 * nb * nb * 4
+    off = 0
+    for I in range(2):
+        for J in range(3):
+            o, prec, _ = g.tile_info("C", I, J, want_exp=False)
+            assert o == off and prec == mC[I, J]                   # the packed tiles lie as for A
+            off += nb * nb * (8 >> int(mC[I, J]))
+    # the same codes on A need no staging
+    g.set_precision_map("A", mC[:, :1])
+    assert g.storage_bytes("A") == sum(nb * nb * (8 >> int(p)) for p in mC[:, 0])
+    # products of such tiles are counted as an FP32 tile's, under both policies
+    g.set_precision_map("A", np.full((2, 1), G.FP64, dtype=np.uint16))
+    g.set_precision_map("B", np.full((1, 3), G.FP16, dtype=np.uint16))
+    assert g.get_stats()["products"] == [1, 5, 0, 0]
+    g.set_policy(G.POLICY_C_TILE)
+    assert g.get_stats()["products"] == [1, 5, 0, 0]
+    assert g.get_stats()["tiles"][2] == [1, 2, 2, 1]
+    g.destroy()
 
 
 def test_product_precision_and_stats_closed_forms():

@@ -8,7 +8,7 @@ import pytest
 
 import workloads as W
 from oracle import gemm_mp_oracle as orc
-from tests.harness import (FP8, FP16, FP32, FP64, OracleSide, compare_jobs, gpu_problem,
+from tests.harness import (FP8, FP16, FP32, FP64, OracleSide, compare_jobs, finish_low_c_tiles, gpu_problem,
                            packed_codes_expected)
 
 pytestmark = pytest.mark.gpu
@@ -456,6 +456,99 @@ def test_random_small_integer_problems_are_exact():
         got = d.unpack_tiles("C").cpu().numpy()
         want = alpha * (A @ B) + beta * C0               # exact in FP64: small integers
         assert np.array_equal(got, want), what
+
+
+def test_c_tiles_stored_in_fp16_and_fp8_hold_small_integer_results_exactly():
+    """C tiles in FP16 / FP8 are accumulated in FP32 staging copies and stored with a scale taken
+    from the finished tile.  Results that are integers up to 15 fit every format, so C, the
+    stored codes' values and the exponents must equal the oracle's exactly, old C included."""
+    import torch
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(91)
+    for nb, MT, NT, KT, cut in ((128, 3, 2, 3, (0, 0, 0)), (256, 2, 3, 2, (0, 0, 0)), (512, 2, 2, 1, (0, 0, 0)),
+                                (128, 2, 3, 2, (37, 101, 64))):
+        M, N, K = MT * nb, NT * nb, KT * nb
+        _say("low C tiles, integers:", (M, N, K, nb), "cut", cut)
+        A = np.zeros((M, K))
+        B = np.zeros((K, N))
+        cols = rng.integers(0, nb, (M, KT)) + nb * np.arange(KT)
+        A[np.arange(M)[:, None], cols] = rng.integers(-2, 3, (M, KT))
+        rows = rng.integers(0, nb, (KT, N)) + nb * np.arange(KT)[:, None]
+        B[rows, np.arange(N)[None, :]] = rng.integers(-1, 2, (KT, N))
+        C0 = rng.integers(-3, 4, (M, N)).astype(np.float64)
+        M, N, K = M - cut[0], N - cut[1], K - cut[2]           # sizes off the tile grid: edge tiles zero-padded
+        A, B, C0 = A[:M, :K], B[:K, :N], C0[:M, :N]
+        mA = rng.integers(0, 4, (MT, KT)).astype(np.uint16)
+        mB = rng.integers(0, 4, (KT, NT)).astype(np.uint16)
+        mC = rng.integers(0, 4, (MT, NT)).astype(np.uint16)
+        mC[0, 0], mC[MT - 1, NT - 1] = FP16, FP8
+        if nb == 512:
+            mA[:], mB[:], mC[0, 1] = FP8, FP8, FP8             # a tile of FP8 products only: large regions
+        want = (A.astype(np.int64) @ B.astype(np.int64)) + 2 * C0.astype(np.int64)
+        assert np.abs(want).max() <= 15
+        for policy in (0, 1):
+            d = DeviceGemmMP(M, N, K, nb, policy=policy)
+            for k, m in (("A", mA), ("B", mB), ("C", mC)):
+                d.set_precision_map(k, m)
+            d.pack_tiles("A", _even_ld(A))
+            d.pack_tiles("B", _even_ld(B))
+            d.pack_tiles("C", _even_ld(C0))
+            assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), C0)
+            d.run(1.0, 2.0)
+            got = d.unpack_tiles("C").cpu().numpy()
+            assert np.array_equal(got, want.astype(np.float64))
+            _, eC = orc.store_tiles(orc.pad_to_tiles(want.astype(np.float64), nb), nb, mC)
+            for I in range(MT):
+                for J in range(NT):
+                    assert d.ctx.tile_info("C", I, J)[2] == int(eC[I, J])
+            # a second run on the result: C <- 0*A*B + 1*C leaves it as it is; then C <- -C
+            d.run(0.0, 1.0)
+            assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), want.astype(np.float64))
+            d.run(0.0, -1.0)
+            assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), -want.astype(np.float64))
+            d.run(0.0, 0.0)
+            assert not d.unpack_tiles("C").any()
+            torch.cuda.synchronize()
+
+
+def test_c_tiles_stored_in_fp16_and_fp8_match_the_oracle_on_general_data():
+    """Random data, every map code on A, B and C, alpha and beta at work: per tile within the
+    stated tolerance of the oracle's stored result, and the exponents agree wherever the two
+    sides' largest magnitudes share a binade."""
+    import torch
+    w = W.tiny()
+    rng = np.random.default_rng(92)
+    w.mapC = rng.integers(0, 4, w.mapC.shape).astype(np.uint16)
+    w.mapC[0, :4] = (FP64, FP32, FP16, FP8)
+    w.alpha, w.beta = 0.75, -1.25
+    for policy in (0, 1):
+        _say("low C tiles, general data, policy", policy)
+        A, B, C0 = _dense(w)
+        side = OracleSide(w, A, B, C0)
+        d, dev = gpu_problem(w, A, B, C0, policy=policy)
+        d.run(w.alpha, w.beta)
+        C_gpu = d.unpack_tiles("C").cpu().numpy()
+        torch.cuda.synchronize()
+        jobs = _all_jobs(w)
+        pre = side.gemm(jobs, policy=policy)
+        C_orc, eC = finish_low_c_tiles(side, pre)
+        worst = compare_jobs(side, jobs, policy, w.alpha, w.beta, C_gpu, C_orc)
+        _say("  worst error / bound:", worst)
+        low = 0
+        for I in range(w.MT):
+            for J in range(w.NT):
+                if w.mapC[I, J] < FP16:
+                    continue
+                low += 1
+                blk = (slice(I * w.nb, (I + 1) * w.nb), slice(J * w.nb, (J + 1) * w.nb))
+                if np.floor(np.log2(np.abs(C_gpu[blk]).max())) == np.floor(np.log2(np.abs(pre[blk]).max())):
+                    assert d.ctx.tile_info("C", I, J)[2] == int(eC[I, J])
+                # what the GPU stored is a number of the format at its exponent
+                e = d.ctx.tile_info("C", I, J)[2]
+                scaled = np.ldexp(C_gpu[blk], -e)
+                rounded = (orc.round_fp16 if w.mapC[I, J] == FP16 else orc.round_fp8)(scaled)[0]
+                assert np.array_equal(scaled, rounded)
+        assert low >= 4
 
 
 @pytest.mark.parametrize("policy", [0, 1])

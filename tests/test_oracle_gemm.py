@@ -323,3 +323,78 @@ def test_a_ragged_problem_is_its_zero_padded_extension():
             t = X[I * nb:(I + 1) * nb, L * nb:(L + 1) * nb]
             assert m[I, L] == np.abs(t).max()
             assert abs(s[I, L] - np.sum(t * t)) <= 1e-14 * np.sum(t * t)
+
+
+@pytest.mark.parametrize("policy", [orc.POLICY_OPERAND, orc.POLICY_C_TILE])
+def test_c_tiles_stored_in_fp16_or_fp8_hold_small_integer_results_exactly(policy):
+    """C tiles in FP16 / FP8 (a reading, the paper's tiles are FP64 / FP32): accumulated as an
+    FP32 tile, then stored with the tile's own scale.  With the largest entry of a tile scaled
+    into [2^14,2^15) an FP16 tile holds every integer up to 2047 and an FP8 tile (largest entry
+    in [2^7,2^8), four significant bits) every integer up to 15 exactly, so on such results the
+    whole path, old C tile included, must return the exact integer matrix; and before the
+    storage step a job's result must not depend on whether the tile is FP32, FP16 or FP8."""
+    rng = np.random.default_rng(77)
+    nb, MT, NT, KT = 8, 3, 3, 2
+    M, N, K = MT * nb, NT * nb, KT * nb
+    for trial in range(6):
+        A = np.zeros((M, K))
+        B = np.zeros((K, N))
+        # one nonzero per row of A and per column of B inside each reduction tile keeps |C| small
+        for r in range(M):
+            for L in range(KT):
+                A[r, L * nb + rng.integers(nb)] = rng.integers(-2, 3)
+        for c in range(N):
+            for L in range(KT):
+                B[L * nb + rng.integers(nb), c] = rng.integers(-1, 2)
+        C0 = rng.integers(-3, 4, (M, N)).astype(np.float64)
+        mA = rng.integers(0, 4, (MT, KT)).astype(np.uint16)
+        mB = rng.integers(0, 4, (KT, NT)).astype(np.uint16)
+        mC = rng.integers(0, 4, (MT, NT)).astype(np.uint16)
+        mC[0, 0], mC[1, 1] = FP16, FP8
+        want = (A.astype(np.int64) @ B.astype(np.int64)) + 2 * C0.astype(np.int64)
+        assert np.abs(want).max() <= 15
+        Ay, eA = _store(A, nb, mA)
+        By, eB = _store(B, nb, mB)
+        Cy, eC = _store(C0, nb, mC)
+        Cv = orc.stored_values(Cy, nb, eC)
+        assert np.array_equal(Cv, C0)
+        jobs = orc.whole_tile_jobs(nb, [(i, j) for i in range(MT) for j in range(NT)])
+        pre = orc.gemm_jobs(nb, Ay, mA, eA, By, mB, eB, Cv, mC, 1.0, 2.0, jobs, policy=policy)
+        as32 = np.where(mC >= FP16, FP32, mC).astype(np.uint16)
+        assert np.array_equal(pre, orc.gemm_jobs(nb, Ay, mA, eA, By, mB, eB, Cv, as32, 1.0, 2.0, jobs, policy=policy))
+        Y, e = _store(pre, nb, mC)
+        got = orc.stored_values(Y, nb, e)
+        assert np.array_equal(got, want.astype(np.float64))
+        # the stored numbers lie in the scale window of their format
+        for I in range(MT):
+            for J in range(NT):
+                m = np.abs(Y[I * nb:(I + 1) * nb, J * nb:(J + 1) * nb]).max()
+                if mC[I, J] == FP16 and m:
+                    assert 2.0 ** 14 <= m < 2.0 ** 15
+                if mC[I, J] == FP8 and m:
+                    assert 2.0 ** 7 <= m < 2.0 ** 8
+
+
+def test_c_tiles_stored_in_fp16_or_fp8_round_once_within_their_unit_roundoff():
+    """General data: the stored tile differs from the FP32 form of the same job by at most
+    u_p relative per entry in the normal range (FP16 2^-11, FP8 2^-4), and the FP32 form is that
+    of an FP32 tile, which the pins above tie to exact arithmetic."""
+    rng = np.random.default_rng(78)
+    nb, MT, NT, KT = 8, 2, 2, 3
+    A = rng.standard_normal((MT * nb, KT * nb))
+    B = rng.standard_normal((KT * nb, NT * nb))
+    mA = rng.integers(0, 4, (MT, KT)).astype(np.uint16)
+    mB = rng.integers(0, 4, (KT, NT)).astype(np.uint16)
+    mC = np.array([[FP16, FP8], [FP8, FP16]], dtype=np.uint16)
+    pre = _run(nb, A, mA, B, mB, None, mC, 1.5, 0.0)
+    assert np.array_equal(pre, pre.astype(np.float32).astype(np.float64))        # FP32 numbers
+    Y, e = _store(pre, nb, mC)
+    got = orc.stored_values(Y, nb, e)
+    for I in range(MT):
+        for J in range(NT):
+            blk = (slice(I * nb, (I + 1) * nb), slice(J * nb, (J + 1) * nb))
+            p = int(mC[I, J])
+            big = np.abs(pre[blk]) >= np.abs(pre[blk]).max() * 2.0 ** -8      # well inside the normal range
+            rel = np.abs(got[blk] - pre[blk])[big] / np.abs(pre[blk])[big]
+            assert rel.max() <= U[p]
+            assert rel.max() > U[p] / 16                                       # and it did round
