@@ -57,6 +57,7 @@ struct gemm_mp_ctx {
     ProductDesc *d_prod = nullptr;    // one record per task (+ 2 padding records), filled on the device
     WorkItem *d_items = nullptr;      // the three lists, [0] first
     gemm_mp_stats stats;
+    bool mixed32 = false;             // list [1] holds an FP16 product with an operand stored in FP8
     bool kernel_ready = false;
     // sender-side conversion: per tile of A / B and product precision q, the offset of the copy
     // in precision q inside the workspace (kNoCopy: no task needs one)
@@ -279,6 +280,14 @@ void build_schedule(gemm_mp_ctx *c)
                          B.map[L * NT + J] == GEMM_MP_FP8_E4M3;
                 all_fp8[(size_t)I * NT + J] = ok;
             }
+    c->mixed32 = false;
+    for (int I = 0; I < MT; ++I)
+        for (int J = 0; J < NT; ++J) {
+            if (C.map[I * NT + J] == GEMM_MP_FP64 || all_fp8[(size_t)I * NT + J]) continue;
+            for (int L = 0; L < KT; ++L)
+                c->mixed32 |= c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_FP16 &&
+                              (A.map[I * KT + L] == GEMM_MP_FP8_E4M3 || B.map[L * NT + J] == GEMM_MP_FP8_E4M3);
+        }
     constexpr int kBins = 8;
     for (int list = 0; list < 3; ++list) {
         const int mr = c->nb / (list == 2 ? kMacroFp8 : kMacro);
@@ -578,7 +587,7 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
     a.n_items64 = (int32_t)c->items[0].size();
     a.n_items32 = (int32_t)c->items[1].size();
     a.n_items8 = (int32_t)c->items[2].size();
-    a.pad_items = 0;
+    a.mixed32 = c->mixed32 ? 1 : 0;
     a.nb = c->nb; a.MT = c->MT; a.NT = c->NT; a.KT = c->KT;
     a.kt_eff = alpha == 0.0 ? 0 : c->KT;
     a.alpha = alpha; a.beta = beta;

@@ -83,7 +83,8 @@ struct GemmArgs {
     const WorkItem *items64;  // owner regions of FP64 C tiles, launch order
     const WorkItem *items32;  // owner regions of FP32 C tiles, launch order
     const WorkItem *items8;   // 256 x 256 regions of FP32 C tiles made of FP8 x FP8 products only
-    int32_t n_items64, n_items32, n_items8, pad_items;
+    int32_t n_items64, n_items32, n_items8;
+    int32_t mixed32;         // some region of items32 has an FP16 product with an operand stored in FP8
     int32_t nb, MT, NT, KT;
     int32_t kt_eff;          // KT, or 0 when alpha == 0
     double alpha, beta;

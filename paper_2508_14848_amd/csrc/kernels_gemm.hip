@@ -4,7 +4,7 @@
 // reduction: it walks the reduction tiles L = 0..KT-1 in ascending order, runs each tile product
 // A(I,L)*B(L,J) on the matrix cores at that task's precision q, and writes C once.  Nothing else
 // ever touches that region, so there are no atomics and the result is reproducible.  Regions
-// are 128 x 128 (gemm_mp_owner_kernel, one instance for FP64 and one for FP32 C tiles), or
+// are 128 x 128 (gemm_mp_owner_kernel: one instance for FP64 C tiles, two for FP32 C tiles), or
 // 256 x 256 for FP32 C tiles whose products are all FP8 x FP8 (gemm_mp_fp8_region_kernel, at
 // the end of this file).
 //
@@ -18,7 +18,10 @@
 //   a C region.
 //   FP16 / FP8 products whose operands need no conversion skip the registers:
 //   global -> LDS by buffer-load-to-LDS into a ring of five unpadded, swizzled stages.
-//   Other FP16 / FP8 products: a two-stage loop with conversion in registers, rows padded by 8 B.
+//   FP16 products with an operand stored in FP8: in the MIXED instance (FP32 C tiles, launched
+//   when such products exist) the FP8 operand takes the ring as it is and is converted between
+//   the fragment read and the MFMA; elsewhere a two-stage loop with conversion in registers on
+//   the way to LDS, rows padded by 8 B.
 //
 // Fragment convention.  Packed A tiles are row-major and packed B tiles are stored transposed,
 // so both operands have the reduction index contiguous.  Which reduction index a lane's bytes
@@ -38,6 +41,7 @@ namespace gmp {
 typedef double d4 __attribute__((ext_vector_type(4)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h2v __attribute__((ext_vector_type(2)));
 typedef int i8v __attribute__((ext_vector_type(8)));
 typedef float f2v __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vectors: these stay in registers
@@ -187,12 +191,22 @@ struct Region {
 };
 
 // FP16 / FP8 products whose operands are both stored in the product's precision run through the
-// DMA ring (lo_run); every other product expects its first chunk staged by its predecessor.
+// DMA ring (lo_run); in the kernel instance built with MIXED so do FP16 products one of whose
+// operands is stored in FP8; every other product expects its first chunk staged by its
+// predecessor.  ring_mix: which operand of an FP16 product is stored in FP8 (0 none, 1 A, 2 B).
+__device__ __forceinline__ int ring_mix(int q, int pa, int pb) { return q != Q16 ? 0 : pa == Q8 ? 1 : pb == Q8 ? 2 : 0; }
+template <bool MIXED>
 __device__ __forceinline__ bool is_ring(const Product &pr, const Geometry &G)
 {
-    return G.ring && (pr.q == Q16 || pr.q == Q8) && pr.a.p == pr.q && pr.b.p == pr.q;
+    if constexpr (MIXED) {
+        if (pr.q == Q8) return pr.a.p == Q8 && pr.b.p == Q8;
+        return pr.q == Q16 && (pr.a.p == Q16 || pr.b.p == Q16);
+    } else {
+        return G.ring && (pr.q == Q16 || pr.q == Q8) && pr.a.p == pr.q && pr.b.p == pr.q;
+    }
 }
-__device__ __forceinline__ bool wants_first_chunk(const Product &pr, const Geometry &G) { return pr.q >= 0 && !is_ring(pr, G); }
+template <bool MIXED>
+__device__ __forceinline__ bool wants_first_chunk(const Product &pr, const Geometry &G) { return pr.q >= 0 && !is_ring<MIXED>(pr, G); }
 
 
 __device__ __forceinline__ int chunk_elems(int q) { return kRowBytes >> (3 - q); }   // 16, 32, 64, 128
@@ -752,7 +766,7 @@ __device__ __forceinline__ void steady_chunks(Acc (&acc)[4][4], u32x4 (&fr)[2][8
 // All chunks of one FP64 / FP32 tile product; returns the next product.  On exit that one's
 // chunk 0 is in `hand` (raw = true: it is an FP64 / FP32 product too), or staged in LDS stage
 // `stage` (any other product that wants it).
-template <int Q, int BASE, bool LATE, typename Acc>
+template <int Q, int BASE, bool LATE, bool MIXED, typename Acc>
 __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
                                                           const Geometry &G0, const Region &R, Raw (&hand)[8], bool &raw)
 {
@@ -775,7 +789,7 @@ __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], cons
     }
 #undef GMP_STEADY
     acc_fence<BASE>(acc);
-    const bool want = wants_first_chunk(next, G);
+    const bool want = wants_first_chunk<MIXED>(next, G);
     Product ld = next;                                 // nothing to fetch: descriptors of length zero
     ld.a.bytes = want ? next.a.bytes : 0;
     ld.b.bytes = want ? next.b.bytes : 0;
@@ -805,14 +819,24 @@ __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], cons
 // LDS.  Consecutive FP16/FP8 products of a C region are therefore run as one stream of chunks
 // through a ring of five LDS stages, each chunk requested four chunks ahead.  An operand
 // stored in the product's own precision goes from global memory straight into LDS with the
-// buffer-load-to-LDS instruction (no registers, no vector ALU); an FP8 tile feeding an FP16
-// product goes through registers (exact FP8 -> FP16 conversion) one chunk later.
+// buffer-load-to-LDS instruction (no registers, no vector ALU).  An FP8 tile feeding an FP16
+// product travels the same way, as FP8: its chunk rows are 64 bytes (the same 64 reduction
+// indices), a DMA instruction covers 16 of them, so two of a wave's four instructions per
+// operand carry data and the other two are empty; row r of the chunk lies at
+// (r / 32) * 4096 + (r % 32) * 64 of the operand's stage.  A lane's fragments of both k-steps
+// are then one 16-byte read (segment g of the row), converted to FP16 in registers, exactly
+// (every e4m3 number is a binary16 number), in the shadow of the MFMAs.
 struct LoGeom {
     int dma_row;      // tile row this lane fetches in DMA instruction j = 0 of its wave (+ 8 j)
     int dma_seg;      // byte offset of its 16-byte segment in the 128-byte chunk row
     int wbase;        // register path: swizzled LDS offset of (seg_row, seg_part); + 4096 j
     int fa0, fa1;     // fragment reads, A rows of this wave, row block 0: the lane's two 16-byte halves
     int fb0, fb1;     // same for B (includes the operand offset)
+};
+struct MixGeom {      // FP8 operand of an FP16 product
+    int row;          // tile row this lane fetches in DMA instruction j = 0 of its wave (+ 16 j) ...
+    int seg;          // ... and the byte offset of its 16-byte segment in the 64-byte chunk row
+    int ma, mb;       // fragment reads: the lane's 16 bytes of row block 0 of A / of B
 };
 
 __device__ __forceinline__ LoGeom lo_geometry(const Geometry &G)
@@ -827,6 +851,16 @@ __device__ __forceinline__ LoGeom lo_geometry(const Geometry &G)
     g.fa1 = (G.wm * 64 + G.li) * kRowBytes + (((2 * G.g + 1) ^ x) * 16);
     g.fb0 = kLoOperand + (G.wn * 64 + G.li) * kRowBytes + (((2 * G.g) ^ x) * 16);
     g.fb1 = kLoOperand + (G.wn * 64 + G.li) * kRowBytes + (((2 * G.g + 1) ^ x) * 16);
+    return g;
+}
+
+__device__ __forceinline__ MixGeom mix_geometry(const Geometry &G)
+{
+    MixGeom g;
+    g.row = (G.tid >> 6) * 32 + (G.lane >> 2);
+    g.seg = (G.lane & 3) * 16;
+    g.ma = G.wm * 8192 + G.li * 64 + G.g * 16;
+    g.mb = kLoOperand + G.wn * 8192 + G.li * 64 + G.g * 16;
     return g;
 }
 
@@ -855,13 +889,19 @@ struct LoCursor {
     int L, c, n;    // its reduction tile, the next chunk to stage, chunks per product
 };
 
-// Prepare an operand for this path: an operand in the product's precision is fetched by DMA.
+// Prepare an operand for this path: this lane's address in chunk 0, DMA instruction 0.
 __device__ __forceinline__ void lo_operand(Operand &o, int q, int row0, int nb, const LoGeom &LG)
 {
     if (o.p == q) {
         o.voff = (((row0 + LG.dma_row) * nb) << (3 - q)) + LG.dma_seg;
         o.sub = 0;
     }
+}
+__device__ __forceinline__ void lo_operand(Operand &o, int q, int row0, int nb, const LoGeom &LG, const MixGeom &MG)
+{
+    if (o.p == q) o.voff = (((row0 + LG.dma_row) * nb) << (3 - q)) + LG.dma_seg;
+    else o.voff = (row0 + MG.row) * nb + MG.seg;                // FP8 operand of an FP16 product
+    o.sub = 0;
 }
 
 // One buffer-load-to-LDS instruction of a chunk request: k = 0..3 are the four 8-row blocks of
@@ -871,17 +911,22 @@ __device__ __forceinline__ void lo_operand(Operand &o, int q, int row0, int nb, 
 // a later LDS read touches, would wait for all of them before every read; completion is awaited
 // explicitly (lo_wait_dma) before the barrier that publishes the stage.  They write no
 // register, so nothing the compiler allocates depends on their completion.
+// An FP8 operand of an FP16 product (o.p != pr.q): a chunk is 64 bytes of each row, an
+// instruction covers 16 rows, which are as many bytes of the tile as 8 rows of an FP16 operand
+// (rows8_bytes holds for both), and instructions j = 2, 3 get a descriptor of length zero.
+template <bool MIXED>
 __device__ __forceinline__ void lo_dma_one(const Product &pr, int soff0, int rows8_bytes, unsigned dst, int k)
 {
     const Operand &o = k < 4 ? pr.a : pr.b;
     const int j = k & 3;
+    const bool narrow = MIXED && o.p != pr.q;
     const uint64_t b = (uint64_t)o.base;
-    const i32x4 rsrc = {(int)(uint32_t)b, (int)((uint32_t)(b >> 32) & 0xffffu), o.bytes, 0x00020000};
+    const i32x4 rsrc = {(int)(uint32_t)b, (int)((uint32_t)(b >> 32) & 0xffffu), (narrow && j >= 2) ? 0 : o.bytes, 0x00020000};
 #if defined(__HIP_DEVICE_COMPILE__)
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(dst + (k < 4 ? 0u : (unsigned)kLoOperand) + 1024u * j), "v"(o.voff), "s"(rsrc),
-                   "s"(__builtin_amdgcn_readfirstlane(soff0 + j * rows8_bytes))
+                   "s"(__builtin_amdgcn_readfirstlane((narrow ? soff0 >> 1 : soff0) + j * rows8_bytes))
                  : "memory", "m0");
 #else
     (void)rsrc; (void)soff0; (void)rows8_bytes; (void)dst; (void)j;
@@ -904,6 +949,48 @@ __device__ __forceinline__ void lo_read_slot(u32x4 (&f)[16], const char *stage, 
     for (int r = 4 * slot; r < 4 * slot + 4; ++r) lo_read_one(f, stage, LG, r);
 }
 
+// FP16 product with an FP8 operand (MIX = 1: A, 2: B).  Row block t of that operand: the lane's
+// 16 bytes hold its fragment of k-step 0 (bytes 0..7) and of k-step 1 (bytes 8..15).
+template <int MIX>
+__device__ __forceinline__ u32x4 lo_read_narrow(const char *stage, const MixGeom &MG, int t)
+{
+    return *(const u32x4 *)(stage + (MIX == 1 ? MG.ma : MG.mb) + (t >> 1) * 4096 + (t & 1) * 1024);
+}
+// Conversion i = 0..31 of a chunk: two FP8 bytes of row block i / 8 become one register of FP16 pairs.
+template <int MIX>
+__device__ __forceinline__ void lo_convert_one(u32x4 (&f)[16], const u32x4 (&raw)[4], int i)
+{
+    const int t = i >> 3, kk = (i >> 2) & 1, word = (i >> 1) & 1, sel = i & 1;
+    const int w = (int)raw[t][2 * kk + word];
+    const h2v h = sel ? __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, true) : __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, false);
+    f[((MIX == 1 ? 0 : 4) + t) * 2 + kk][2 * word + sel] = __builtin_bit_cast(uint32_t, h);
+}
+// All fragments of the chunk in `stage`, outside the chunk stream (first chunk of a run, and
+// where the product that follows keeps its operands differently from the one that ends).
+__device__ __forceinline__ void lo_read_all(u32x4 (&f)[16], const char *stage, const LoGeom &LG, const MixGeom &MG, int mix)
+{
+    if (mix == 0) {
+#pragma unroll
+        for (int slot = 0; slot < 4; ++slot) lo_read_slot(f, stage, LG, slot);
+    } else if (mix == 1) {
+        u32x4 raw[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) raw[t] = lo_read_narrow<1>(stage, MG, t);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) lo_read_one(f, stage, LG, r);
+#pragma unroll
+        for (int i = 0; i < 32; ++i) lo_convert_one<1>(f, raw, i);
+    } else {
+        u32x4 raw[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) raw[t] = lo_read_narrow<2>(stage, MG, t);
+#pragma unroll
+        for (int r = 8; r < 16; ++r) lo_read_one(f, stage, LG, r);
+#pragma unroll
+        for (int i = 0; i < 32; ++i) lo_convert_one<2>(f, raw, i);
+    }
+}
+
 // One step of the chunk stream: the MFMAs of a chunk from fragment set PAR.  These MFMAs leave
 // issue slots free while they execute (16 or 32 cycles each), and everything else the step has
 // to do is placed into those slots, one or two instructions behind each MFMA: first the reads
@@ -911,11 +998,14 @@ __device__ __forceinline__ void lo_read_slot(u32x4 (&f)[16], const char *stage, 
 // DMA instructions that request a later chunk of product `pr` into the stage at `dst`, and the
 // scalar bookkeeping of the step (`book`, straight-line code).
 // The MFMAs are asm in place, see mfma_group.
-template <int Q, int PAR, bool FIRST, typename Book>
-__device__ __forceinline__ void lo_chunk(f4 (&acc)[4][4], u32x4 (&fr)[2][16], const char *next, const LoGeom &LG,
+// MIX != 0 (FP16 product with an FP8 operand): the next chunk's reads are the four of the FP8
+// operand, then the eight of the other one; the 32 conversions follow two per MFMA.
+template <int Q, int PAR, bool FIRST, bool MIXED, int MIX, typename Book>
+__device__ __forceinline__ void lo_chunk(f4 (&acc)[4][4], u32x4 (&fr)[2][16], const char *next, const LoGeom &LG, const MixGeom &MG,
                                          const Product &pr, int soff0, int rows8_bytes, unsigned dst, Book book)
 {
     constexpr int kMfmas = Q == Q16 ? 32 : 16;
+    u32x4 raw[4];
     constexpr int kBookSlot = Q == Q16 ? 26 : 13;    // a slot with little else in it
 #pragma unroll
     for (int m = 0; m < kMfmas; ++m) {
@@ -950,15 +1040,23 @@ __device__ __forceinline__ void lo_chunk(f4 (&acc)[4][4], u32x4 (&fr)[2][16], co
         }
         SCHED_FENCE();
         if (m == kBookSlot) book();                  // the step's scalar bookkeeping (branch-free)
-        if constexpr (Q == Q16) {
+        if constexpr (Q == Q16 && MIX != 0) {
+            if (m < 4) raw[m] = lo_read_narrow<MIX>(next, MG, m);
+            else if (m < 12) lo_read_one(fr[PAR ^ 1], next, LG, (MIX == 1 ? 0 : 8) + m - 4);
+            if (m >= 8 && m < 24) {
+                lo_convert_one<MIX>(fr[PAR ^ 1], raw, 2 * (m - 8));
+                lo_convert_one<MIX>(fr[PAR ^ 1], raw, 2 * (m - 8) + 1);
+            }
+            if (m >= 16 && m < 24) lo_dma_one<MIXED>(pr, soff0, rows8_bytes, dst, m - 16);
+        } else if constexpr (Q == Q16) {
             if (m < 16) lo_read_one(fr[PAR ^ 1], next, LG, m);
-            else if (m < 24) lo_dma_one(pr, soff0, rows8_bytes, dst, m - 16);
+            else if (m < 24) lo_dma_one<MIXED>(pr, soff0, rows8_bytes, dst, m - 16);
         } else {
             if (m < 8) {
                 lo_read_one(fr[PAR ^ 1], next, LG, 2 * m);
                 lo_read_one(fr[PAR ^ 1], next, LG, 2 * m + 1);
             } else {
-                lo_dma_one(pr, soff0, rows8_bytes, dst, m - 8);
+                lo_dma_one<MIXED>(pr, soff0, rows8_bytes, dst, m - 8);
             }
         }
         SCHED_FENCE();
@@ -971,12 +1069,18 @@ __device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int e
 // A run of consecutive ring products starting at product `cur` (reduction tile L).  On return
 // `cur` is the first product after the run (q = -1: none) and L its index; if that product wants
 // its first chunk staged, it is in stage 0 of the two-stage layout.
-template <typename AccS>
+template <typename AccS, bool MIXED>
 __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, const Walk &W, char *lds, const Geometry &G0,
                                        const Region &R)
 {
     const Geometry G = fresh(G0);
     const LoGeom LG = lo_geometry(G);
+    MixGeom MG{};
+    if constexpr (MIXED) MG = mix_geometry(G);
+    auto prepare = [&](Operand &o, int q, int row0) __attribute__((always_inline)) {
+        if constexpr (MIXED) lo_operand(o, q, row0, R.nb, LG, MG);
+        else lo_operand(o, q, row0, R.nb, LG);
+    };
     const int wave = G.tid >> 6;
     f4 t[4][4];               // set by the first chunk of every product
 
@@ -986,8 +1090,8 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
     pf.L = L;
     pf.c = 0;
     pf.n = R.nb / chunk_elems(cur.q);
-    lo_operand(pf.pr.a, pf.pr.q, R.arow0, R.nb, LG);
-    lo_operand(pf.pr.b, pf.pr.q, R.brow0, R.nb, LG);
+    prepare(pf.pr.a, pf.pr.q, R.arow0);
+    prepare(pf.pr.b, pf.pr.q, R.brow0);
     bool pf_valid = true;
     // Descriptors of the product after the one being staged: opened one product ahead so that the
     // latency of the table reads is not paid when the cursor moves on.  When the run ends this is
@@ -1024,10 +1128,10 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
         }
         if (pf_valid && pf.c == pf.n) {             // next product: does it continue the run?
             ++pf.L;
-            if (is_ring(nx, G)) {
+            if (is_ring<MIXED>(nx, G)) {
                 pf.pr = nx;
-                lo_operand(pf.pr.a, nx.q, R.arow0, R.nb, LG);
-                lo_operand(pf.pr.b, nx.q, R.brow0, R.nb, LG);
+                prepare(pf.pr.a, nx.q, R.arow0);
+                prepare(pf.pr.b, nx.q, R.brow0);
                 pf.n = R.nb / chunk_elems(nx.q);
                 need_open = true;
             } else {
@@ -1044,15 +1148,19 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
 #pragma unroll 1
     for (int i = 0; i < kLoStages; ++i) {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) lo_dma_one(GMP_LO_REQ_ARGS, k);
+        for (int k = 0; k < 8; ++k) lo_dma_one<MIXED>(GMP_LO_REQ_ARGS, k);
         advance();
         if (slow) turn();
     }
     lo_wait_dma(8 * (kLoStages - 2));
     __syncthreads();
     u32x4 fr[2][16];
+    int cmix = MIXED ? ring_mix(cur.q, cur.a.p, cur.b.p) : 0;
+    if constexpr (MIXED) lo_read_all(fr[0], lds, LG, MG, cmix);
+    else {
 #pragma unroll
-    for (int slot = 0; slot < 4; ++slot) lo_read_slot(fr[0], lds, LG, slot);
+        for (int slot = 0; slot < 4; ++slot) lo_read_slot(fr[0], lds, LG, slot);
+    }
 
     // compute: product by product; inside a product the accumulators are touched by MFMAs only
     int cL = L;
@@ -1069,9 +1177,9 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
         ++done;
         st_next = st_next + kLoStage == kLoLdsBytes ? 0 : st_next + kLoStage;
     };
-#define GMP_LO_STEP(QQ, PAR, FIRST)                                                  \
+#define GMP_LO_STEP(QQ, PAR, FIRST, MIX)                                             \
     do {                                                                             \
-        lo_chunk<QQ, PAR, FIRST>(t, fr, lds + st_next, LG, GMP_LO_REQ_ARGS, step_book); \
+        lo_chunk<QQ, PAR, FIRST, MIXED, MIX>(t, fr, lds + st_next, LG, MG, GMP_LO_REQ_ARGS, step_book); \
         if (slow) turn();                                                            \
         lo_wait_dma(8 * (kLoStages - 2));                                            \
         __syncthreads();                                                             \
@@ -1083,22 +1191,39 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
         const u32x4 nrec = more ? ((ConstQuad)(uintptr_t)(R.prod + cL + 1))[1] : u32x4{0, 0, 0xff0000u, 0};
         const int nq = more ? (int)((nrec.z >> 16) & 0xffu) : -1;
         const int nesum = (int)nrec.x + (int)nrec.y;
+        const int nmix = MIXED ? ring_mix(nq, (int)(nrec.z & 0xffu), (int)((nrec.z >> 8) & 0xffu)) : 0;
         if (cq == Q16) {                           // 64 elements per chunk: always an even count
-            GMP_LO_STEP(Q16, 0, true);
-            GMP_LO_STEP(Q16, 1, false);
-            for (int cc = 2; cc < cn; cc += 2) {
-                GMP_LO_STEP(Q16, 0, false);
-                GMP_LO_STEP(Q16, 1, false);
+            if (!MIXED || cmix == 0) {
+                GMP_LO_STEP(Q16, 0, true, 0);
+                GMP_LO_STEP(Q16, 1, false, 0);
+                for (int cc = 2; cc < cn; cc += 2) {
+                    GMP_LO_STEP(Q16, 0, false, 0);
+                    GMP_LO_STEP(Q16, 1, false, 0);
+                }
+            } else if (MIXED && cmix == 1) {
+                GMP_LO_STEP(Q16, 0, true, 1);
+                GMP_LO_STEP(Q16, 1, false, 1);
+                for (int cc = 2; cc < cn; cc += 2) {
+                    GMP_LO_STEP(Q16, 0, false, 1);
+                    GMP_LO_STEP(Q16, 1, false, 1);
+                }
+            } else if (MIXED) {
+                GMP_LO_STEP(Q16, 0, true, 2);
+                GMP_LO_STEP(Q16, 1, false, 2);
+                for (int cc = 2; cc < cn; cc += 2) {
+                    GMP_LO_STEP(Q16, 0, false, 2);
+                    GMP_LO_STEP(Q16, 1, false, 2);
+                }
             }
         } else {
-            GMP_LO_STEP(Q8, 0, true);
+            GMP_LO_STEP(Q8, 0, true, 0);
             if (cn > 1) {
-                GMP_LO_STEP(Q8, 1, false);
+                GMP_LO_STEP(Q8, 1, false, 0);
                 for (int cc = 2; cc + 2 <= cn; cc += 2) {
-                    GMP_LO_STEP(Q8, 0, false);
-                    GMP_LO_STEP(Q8, 1, false);
+                    GMP_LO_STEP(Q8, 0, false, 0);
+                    GMP_LO_STEP(Q8, 1, false, 0);
                 }
-                if (cn & 1) GMP_LO_STEP(Q8, 0, false);
+                if (cn & 1) GMP_LO_STEP(Q8, 0, false, 0);
             }
             if (cn & 1) {                          // odd count: bring the fragments back to set 0
 #pragma unroll
@@ -1107,8 +1232,15 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
         }
         // the product is complete: it joins the running sum
         fold(s, t, cesum);
+        // The last step read the fragments of the next product's first chunk the way this product
+        // keeps its operands; where the next one keeps them differently they are read again (that
+        // chunk is complete in its stage since the barrier that ended the step).
+        if constexpr (MIXED)
+            if (nmix != cmix && done < staged)
+                lo_read_all(fr[0], lds + (st_next == 0 ? kLoLdsBytes - kLoStage : st_next - kLoStage), LG, MG, nmix);
         ++cL;
         cq = nq;
+        cmix = nmix;
         cesum = nesum;
     }
 #undef GMP_LO_STEP
@@ -1118,7 +1250,7 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
 
     L = cL;
     cur = nx;
-    if (wants_first_chunk(nx, G)) {                // hand over to the two-stage layout
+    if (wants_first_chunk<MIXED>(nx, G)) {         // hand over to the two-stage layout
         Raw xa[4], xb[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) load_pair(xa[j], xb[j], nx, R.nb, 0, j);
@@ -1201,7 +1333,7 @@ __device__ __forceinline__ void simple_chunks(f4 (&acc)[4][4], const Product &cu
 
 // On entry LDS stage `stage` holds the product's first chunk; on exit it holds the first chunk
 // of the next product if that one wants it.
-template <int Q>
+template <int Q, bool MIXED>
 __device__ __forceinline__ Product product_loop_simple(f4 (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
                                                        const Geometry &G0, const Region &R)
 {
@@ -1217,7 +1349,7 @@ __device__ __forceinline__ Product product_loop_simple(f4 (&acc)[4][4], const Pr
     }
     Raw ra[4], rb[4];
     const Product next = open_product(W.I, W.J, W.tileC, Lnext, G, R);
-    const bool give = wants_first_chunk(next, G);
+    const bool give = wants_first_chunk<MIXED>(next, G);
     if (give) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) load_pair(ra[j], rb[j], next, R.nb, 0, j);
@@ -1253,7 +1385,7 @@ __device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int e
 // T = double: FP64 C tiles; the running sum s is FP64 and every product below FP64 is formed
 //             in the FP32 accumulator t first.
 // T = float : FP32 C tiles; FP32 products continue s, FP16 / FP8 products go through t.
-template <typename T>
+template <typename T, bool MIXED>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 {
@@ -1296,7 +1428,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 
     int stage = 0;
     Product cur = open_product(I, J, tileC, 0, G, R);
-    if (wants_first_chunk(cur, G)) {
+    if (wants_first_chunk<MIXED>(cur, G)) {
         Raw ra[4], rb[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) load_pair(ra[j], rb[j], cur, R.nb, 0, j);
@@ -1314,8 +1446,8 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     int L = 0;
     while (L < R.kt_eff) {
         const int q = cur.q;
-        if (is_ring(cur, G)) {
-            lo_run(s, cur, L, W, lds, G, R);       // all consecutive products of that kind
+        if (is_ring<MIXED>(cur, G)) {
+            lo_run<AccS, MIXED>(s, cur, L, W, lds, G, R);   // all consecutive products of that kind
             stage = 0;
             continue;
         }
@@ -1327,15 +1459,15 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
             const int esum = cur.a.e + cur.b.e;
-            if (q == Q16) next = product_loop_simple<Q16>(t, cur, W, L + 1, lds, stage, G, R);
-            else next = product_loop_simple<Q8>(t, cur, W, L + 1, lds, stage, G, R);
+            if (q == Q16) next = product_loop_simple<Q16, MIXED>(t, cur, W, L + 1, lds, stage, G, R);
+            else next = product_loop_simple<Q8, MIXED>(t, cur, W, L + 1, lds, stage, G, R);
             fold(s, t, esum);
             cur = next;
             ++L;
             continue;
         }
         if (q == QT) {
-            next = product_loop_pipelined<QT, (QT == Q32 ? 192 : -1), QT == Q32>(s, cur, W, L + 1, lds, stage, G, R, hand, raw);
+            next = product_loop_pipelined<QT, (QT == Q32 ? 192 : -1), QT == Q32, MIXED>(s, cur, W, L + 1, lds, stage, G, R, hand, raw);
         } else {
             if constexpr (QT == Q64) {
                 // an FP32 product of an FP64 C tile: its FP32 accumulator lives only for that product
@@ -1344,7 +1476,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
-                next = product_loop_pipelined<Q32, -1, false>(t, cur, W, L + 1, lds, stage, G, R, hand, raw);
+                next = product_loop_pipelined<Q32, -1, false, MIXED>(t, cur, W, L + 1, lds, stage, G, R, hand, raw);
                 fold(s, t, 0);
             } else {
                 next = cur;                        // not reachable: the host never schedules FP64 products on FP32 tiles
@@ -1671,10 +1803,13 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 
 hipError_t gemm_kernel_setup()
 {
-    hipError_t e = hipFuncSetAttribute((const void *)gemm_mp_owner_kernel<double>,
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_mp_owner_kernel<double, false>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)gemm_mp_owner_kernel<float>,
+    e = hipFuncSetAttribute((const void *)gemm_mp_owner_kernel<float, false>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)gemm_mp_owner_kernel<float, true>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     return hipFuncSetAttribute((const void *)gemm_mp_fp8_region_kernel,
@@ -1758,9 +1893,12 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     const int64_t tasks = (int64_t)a.MT * a.NT * a.KT;
     product_table_kernel<<<dim3((unsigned)((tasks + 255) / 256)), dim3(256), 0, s>>>(a.A, a.B, a.q, a.MT, a.NT, a.KT, a.convA, a.convB, a.prod);
     if (a.n_items64 > 0)
-        gemm_mp_owner_kernel<double><<<dim3((unsigned)a.n_items64), dim3(kThreads), kLdsBytes, s>>>(a, a.items64);
-    if (a.n_items32 > 0)
-        gemm_mp_owner_kernel<float><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
+        gemm_mp_owner_kernel<double, false><<<dim3((unsigned)a.n_items64), dim3(kThreads), kLdsBytes, s>>>(a, a.items64);
+    if (a.n_items32 > 0) {
+        // the instance whose DMA ring also takes FP16 products with an FP8 operand only where such products exist
+        if (a.mixed32) gemm_mp_owner_kernel<float, true><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
+        else gemm_mp_owner_kernel<float, false><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
+    }
     if (a.n_items8 > 0)
         gemm_mp_fp8_region_kernel<<<dim3((unsigned)a.n_items8), dim3(kThreads), kBigLdsBytes, s>>>(a, a.items8);
     return hipGetLastError();
