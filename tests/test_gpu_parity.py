@@ -551,6 +551,40 @@ def test_c_tiles_stored_in_fp16_and_fp8_match_the_oracle_on_general_data():
         assert low >= 4
 
 
+def test_c_map_from_the_norm_rule_with_all_formats_and_sender_side_conversion():
+    """C's own map made by the norm rule over all four formats from the old C (whose tiles decay
+    away from the diagonal, so the rule picks every format), A and B likewise, operands converted
+    once on the sender side, beta at work: the map and the packed old C must be the oracle's bit
+    for bit, the result within tolerance, and equal to the receiver-side result bit for bit."""
+    import torch
+    w = W.tiny()
+    w.alpha, w.beta = 1.0, 0.5
+    w.rule = dict(eps=1e-4, allowed=orc.ALL_PRECISIONS_MASK)
+    A, B, C0 = _dense(w)
+    sc, mc = orc.tile_scan(C0, w.nb)
+    w.mapC = orc.precision_rule(sc, w.rule["eps"], w.rule["allowed"])
+    assert len(set(w.mapC.ravel().tolist())) >= 3, w.mapC
+    side = OracleSide(w, A, B, C0)
+    results = []
+    for sender in (False, True):
+        d, dev = gpu_problem(w, A, B, None)
+        assert np.array_equal(d.maps["A"], side.mapA) and np.array_equal(d.maps["B"], side.mapB)
+        got_map = d.compute_precision_map("C", torch.from_numpy(C0).cuda(), w.rule["eps"], w.rule["allowed"])
+        assert np.array_equal(got_map, w.mapC)
+        d.pack_tiles("C", torch.from_numpy(C0).cuda())
+        assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), side.Cy)
+        if sender:
+            assert d.convert_tiles() > 0
+        d.run(w.alpha, w.beta)
+        results.append(d.unpack_tiles("C").cpu().numpy())
+        torch.cuda.synchronize()
+    assert np.array_equal(results[0], results[1])
+    jobs = _all_jobs(w)
+    C_orc, _ = finish_low_c_tiles(side, side.gemm(jobs))
+    worst = compare_jobs(side, jobs, 0, w.alpha, w.beta, results[0], C_orc)
+    _say("  worst error / bound:", worst)
+
+
 @pytest.mark.parametrize("policy", [0, 1])
 def test_mixed_maps_match_the_oracle_per_tile(policy):
     """All (pA, pB, pC) combinations occur; several owner regions per tile; alpha, beta general."""
