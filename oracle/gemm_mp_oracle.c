@@ -42,8 +42,10 @@
 
 /* Precision codes: 0/1 as in the paper's (commented) description of the map
  * in Section 5.2; 2 and 3 extend it to FP16 and FP8 (OCP e4m3, "fn" variant:
- * no infinities, one NaN code per sign, max finite 448). */
-enum { P_FP64 = 0, P_FP32 = 1, P_FP16 = 2, P_FP8 = 3 };
+ * no infinities, one NaN code per sign, max finite 448), 4 to BF16 (8 exponent
+ * bits as FP32, 7 fraction bits).  The code is a name, not a rank: by unit
+ * roundoff the formats order FP64 < FP32 < FP16 < BF16 < FP8. */
+enum { P_FP64 = 0, P_FP32 = 1, P_FP16 = 2, P_FP8 = 3, P_BF16 = 4 };
 
 /* Which product-precision reading is applied (see orc_product_precision). */
 enum { POLICY_OPERAND = 0, POLICY_C_TILE = 1 };
@@ -90,7 +92,40 @@ double orc_round_fp8(double x)
     return r;
 }
 
+/* BF16: 7 fraction bits, FP32's exponent range (emin -126), max finite
+ * (2 - 2^-7) * 2^127; overflow goes to infinity, underflow is gradual. */
+double orc_round_bf16(double x)
+{
+    if (isnan(x) || isinf(x)) return x;
+    double r = round_to_format(x, 7, -126);
+    if (fabs(r) > ldexp(2.0 - ldexp(1.0, -7), 127)) r = copysign(INFINITY, x);
+    return r;
+}
+
 /* Bit patterns of values that are already exactly representable. */
+uint16_t orc_bf16_bits(double y)
+{
+    uint16_t s = signbit(y) ? 0x8000u : 0u;
+    if (isnan(y)) return (uint16_t)(s | 0x7fc0u);
+    if (isinf(y)) return (uint16_t)(s | 0x7f80u);
+    double a = fabs(y);
+    if (a == 0.0) return s;
+    int e = ilogb(a);
+    if (e < -126) return (uint16_t)(s | (uint16_t)ldexp(a, 133));        /* subnormal: a / 2^-133 */
+    double frac = ldexp(a, -e) - 1.0;
+    return (uint16_t)(s | ((uint16_t)(e + 127) << 7) | (uint16_t)ldexp(frac, 7));
+}
+
+double orc_bf16_value(uint16_t h)
+{
+    int s = h >> 15, e = (h >> 7) & 255, m = h & 127;
+    double v;
+    if (e == 255) v = m ? NAN : INFINITY;
+    else if (e == 0) v = ldexp((double)m, -133);
+    else v = ldexp(1.0 + (double)m / 128.0, e - 127);
+    return s ? -v : v;
+}
+
 uint16_t orc_fp16_bits(double y)
 {
     uint16_t s = signbit(y) ? 0x8000u : 0u;
@@ -142,6 +177,13 @@ void orc_round_fp16_array(const double *x, int64_t n, double *y, uint16_t *bits)
     for (int64_t i = 0; i < n; ++i) {
         y[i] = orc_round_fp16(x[i]);
         if (bits) bits[i] = orc_fp16_bits(y[i]);
+    }
+}
+void orc_round_bf16_array(const double *x, int64_t n, double *y, uint16_t *bits)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        y[i] = orc_round_bf16(x[i]);
+        if (bits) bits[i] = orc_bf16_bits(y[i]);
     }
 }
 void orc_round_fp8_array(const double *x, int64_t n, double *y, uint8_t *bits)
@@ -206,6 +248,7 @@ static double unit_roundoff(int p)
     case P_FP64: return ldexp(1.0, -53);
     case P_FP32: return ldexp(1.0, -24);
     case P_FP16: return ldexp(1.0, -11);
+    case P_BF16: return ldexp(1.0, -8);
     default:     return ldexp(1.0, -4);      /* e4m3: 3 fraction bits */
     }
 }
@@ -219,18 +262,22 @@ static double unit_roundoff(int p)
  * The test is evaluated on squares, in FP64, in exactly this order:
  *     lhs = (S_T * ntiles) * (u_p * u_p);   rhs = (eps * eps) * S;
  * with S the sum of the S_T in row-major tile order.
- * allowed_mask: bit p set = precision code p may be used. */
+ * allowed_mask: bit p set = precision code p may be used.  "Lowest" and
+ * "highest" go by unit roundoff: FP8, BF16, FP16, FP32, FP64 from the lowest. */
 void orc_precision_rule(const double *sumsq, int64_t ntiles, double eps, uint32_t allowed_mask,
                         uint16_t *map)
 {
+    static const int from_lowest[5] = {P_FP8, P_BF16, P_FP16, P_FP32, P_FP64};
     double S = 0.0;
     for (int64_t t = 0; t < ntiles; ++t) S = S + sumsq[t];
-    int highest = 0;
-    while (highest < 4 && !(allowed_mask & (1u << highest))) ++highest;
+    int highest = P_FP64;
+    for (int k = 0; k < 5; ++k)
+        if (allowed_mask & (1u << from_lowest[k])) highest = from_lowest[k];
     double rhs = (eps * eps) * S;
     for (int64_t t = 0; t < ntiles; ++t) {
         int chosen = highest;
-        for (int p = P_FP8; p >= P_FP64; --p) {
+        for (int k = 0; k < 5; ++k) {
+            int p = from_lowest[k];
             if (!(allowed_mask & (1u << p))) continue;
             double u = unit_roundoff(p);
             double lhs = (sumsq[t] * (double)ntiles) * (u * u);
@@ -244,7 +291,8 @@ void orc_precision_rule(const double *sumsq, int64_t ntiles, double eps, uint32_
  * not treat these formats): the tile is stored as x * 2^-e with
  * e = floor(log2 max|x|) - E_p, E_FP16 = 14, E_FP8 = 7, so the largest scaled
  * magnitude lies in [2^14,2^15) resp. [2^7,2^8); e = 0 for an all-zero tile
- * or a non-finite maximum, and for FP64 / FP32 tiles. */
+ * or a non-finite maximum, and for FP64 / FP32 / BF16 tiles (BF16 has FP32's
+ * range and needs no scale). */
 int32_t orc_scale_exponent(double maxabs, int32_t p)
 {
     if (p != P_FP16 && p != P_FP8) return 0;
@@ -277,6 +325,7 @@ void orc_store_tiles(const double *X, int64_t ld, int64_t rows, int64_t cols, in
                     if (p == P_FP64) y = x;
                     else if (p == P_FP32) y = (double)(float)x;
                     else if (p == P_FP16) y = orc_round_fp16(ldexp(x, -e));
+                    else if (p == P_BF16) y = orc_round_bf16(x);
                     else y = orc_round_fp8(ldexp(x, -e));
                     Y[(I * nb + r) * ldy + J * nb + c] = y;
                 }
@@ -290,14 +339,27 @@ void orc_store_tiles(const double *X, int64_t ld, int64_t rows, int64_t cols, in
  * POLICY_OPERAND (default) is this build's reading once FP16 / FP8 exist:
  * compute at the precision of the better-stored operand, but never above
  * what the C tile keeps:  q = min(cap(pC), max(pA, pB)) in precision rank,
- * cap(FP64) = FP64 and FP32 otherwise.  In codes (larger = coarser):
- * q = max(capcode, min(pA, pB)). */
+ * cap(FP64) = FP64 and FP32 otherwise.  With BF16 the formats no longer form a
+ * chain (FP16 has more fraction bits, BF16 more range; neither holds the
+ * other's numbers), so "the better of the two" becomes the smallest format
+ * that holds both operands' numbers exactly: FP64 > FP32 > {FP16, BF16} > FP8,
+ * and FP32 for the pair FP16, BF16. */
+static int holds_both(int pA, int pB)
+{
+    if (pA == P_FP64 || pB == P_FP64) return P_FP64;
+    if (pA == P_FP32 || pB == P_FP32) return P_FP32;
+    int h = (pA == P_FP16) || (pB == P_FP16), b = (pA == P_BF16) || (pB == P_BF16);
+    if (h && b) return P_FP32;
+    if (h) return P_FP16;
+    if (b) return P_BF16;
+    return P_FP8;
+}
 int32_t orc_product_precision(int32_t pA, int32_t pB, int32_t pC, int32_t policy)
 {
     int cap = (pC == P_FP64) ? P_FP64 : P_FP32;
     if (policy == POLICY_C_TILE) return cap;
-    int better = pA < pB ? pA : pB;
-    return better > cap ? better : cap;
+    int q = holds_both(pA, pB);
+    return (q == P_FP64 && cap == P_FP32) ? P_FP32 : q;
 }
 
 /* ------------------------------------------------------------------------ */
@@ -317,8 +379,10 @@ int32_t orc_product_precision(int32_t pA, int32_t pB, int32_t pC, int32_t policy
 /*     receiver-side conversion of both operand tiles to q:                   */
 /*       q in {FP64,FP32}: value y*2^e formed in q (an up-cast is exact; the  */
 /*                         only down-cast, FP64 -> FP32, rounds to nearest)   */
-/*       q in {FP16,FP8} : operands stay in scaled form y; 2^(eA+eB) is       */
-/*                         applied to the finished tile product               */
+/*       q in {FP16,BF16,FP8}: operands stay in scaled form y; 2^(eA+eB) is   */
+/*                         applied to the finished tile product (an FP8 tile  */
+/*                         under a BF16 product keeps its scale, a BF16 tile  */
+/*                         has none)                                          */
 /*     q == T : s = fma_T(a, b, s) for k ascending (the running sum goes on)  */
 /*     else   : t = 0 in FP32; t = fmaf(a, b, t) for k ascending;             */
 /*              s = s +_T ldexp_T((T)t, eA+eB)   (the exponent sum is 0 when  */
@@ -326,7 +390,7 @@ int32_t orc_product_precision(int32_t pA, int32_t pB, int32_t pC, int32_t policy
 /*   v = alpha x_T s  (+_T  beta x_T c0  when beta != 0; c0 is never read     */
 /*   when beta == 0);  alpha, beta are rounded to T;  C = v rounded to pC.    */
 /* alpha == 0 skips the products (s = 0).                                     */
-/* pC in {FP16, FP8} (a reading: the paper has FP64 / FP32 tiles only and     */
+/* pC in {FP16, FP8, BF16} (a reading: the paper has FP64 / FP32 tiles only and     */
 /* leaves further formats to Section 6): the tile is accumulated as an FP32   */
 /* tile (T = FP32, product precisions as for pC = FP32), Cy holds the values   */
 /* the old tile stands for (stored number * 2^e, see orc_stored_values), and  */
@@ -362,7 +426,7 @@ int32_t orc_gemm_jobs(int64_t M, int64_t N, int64_t K, int32_t nb,
             c1 > nb || c0 > c1)
             return -1;
         int pC = mapC[I * NT + J];
-        if (pC < P_FP64 || pC > P_FP8) return -1;
+        if (pC < P_FP64 || pC > P_BF16) return -1;
         int T = pC == P_FP64 ? P_FP64 : P_FP32;       /* accumulate type: FP64 or FP32 */
         int64_t nr = r1 - r0, nc = c1 - c0;
         if (nr == 0 || nc == 0) continue;
@@ -383,7 +447,7 @@ int32_t orc_gemm_jobs(int64_t M, int64_t N, int64_t K, int32_t nb,
             int pA = mapA[I * KT + L], pB = mapB[L * NT + J];
             int q = orc_product_precision(pA, pB, pC, policy);
             int ea = eA[I * KT + L], eb = eB[L * NT + J];
-            int esum = (q == P_FP16 || q == P_FP8) ? ea + eb : 0;
+            int esum = (q == P_FP16 || q == P_FP8 || q == P_BF16) ? ea + eb : 0;
 
             /* receiver-side conversion of the B tile columns this job needs */
 #pragma omp parallel for schedule(static)

@@ -15,9 +15,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gemm_mp_oracle.c")
 _LIB = os.path.join(_HERE, "libgemm_mp_oracle.so")
 
-FP64, FP32, FP16, FP8 = 0, 1, 2, 3
+FP64, FP32, FP16, FP8, BF16 = 0, 1, 2, 3, 4
 POLICY_OPERAND, POLICY_C_TILE = 0, 1
-ALL_PRECISIONS_MASK = 0xF
+ALL_PRECISIONS_MASK = 0xF          # the four formats of the configurations
+ALL_FORMATS_MASK = 0x1F            # ... and BF16
 
 
 def build(force=False):
@@ -41,6 +42,9 @@ def lib():
         P = ctypes.c_void_p
         _lib.orc_round_fp16_array.argtypes = [P, c_i64, P, P]
         _lib.orc_round_fp8_array.argtypes = [P, c_i64, P, P]
+        _lib.orc_round_bf16_array.argtypes = [P, c_i64, P, P]
+        _lib.orc_bf16_value.restype = c_dbl
+        _lib.orc_bf16_value.argtypes = [ctypes.c_uint16]
         _lib.orc_fp16_value.restype = c_dbl
         _lib.orc_fp16_value.argtypes = [ctypes.c_uint16]
         _lib.orc_fp8_value.restype = c_dbl
@@ -92,6 +96,19 @@ def round_fp8(x):
     bits = np.empty(x.shape, dtype=np.uint8)
     lib().orc_round_fp8_array(_p(x), x.size, _p(y), _p(bits))
     return y, bits
+
+
+def round_bf16(x):
+    """FP64 -> BF16 by one rounding.  Returns (values as FP64, bit patterns)."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    y = np.empty_like(x)
+    bits = np.empty(x.shape, dtype=np.uint16)
+    lib().orc_round_bf16_array(_p(x), x.size, _p(y), _p(bits))
+    return y, bits
+
+
+def bf16_value(code):
+    return float(lib().orc_bf16_value(int(code)))
 
 
 def fp16_value(code):

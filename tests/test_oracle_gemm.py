@@ -11,8 +11,8 @@ import pytest
 from oracle import gemm_mp_oracle as orc
 from tests.exact import fma32, fma64
 
-FP64, FP32, FP16, FP8 = 0, 1, 2, 3
-U = {FP64: 2.0 ** -53, FP32: 2.0 ** -24, FP16: 2.0 ** -11, FP8: 2.0 ** -4}
+FP64, FP32, FP16, FP8, BF16 = 0, 1, 2, 3, 4
+U = {FP64: 2.0 ** -53, FP32: 2.0 ** -24, FP16: 2.0 ** -11, FP8: 2.0 ** -4, BF16: 2.0 ** -8}
 
 
 def _store(X, nb, pmap):
@@ -398,3 +398,62 @@ def test_c_tiles_stored_in_fp16_or_fp8_round_once_within_their_unit_roundoff():
             rel = np.abs(got[blk] - pre[blk])[big] / np.abs(pre[blk])[big]
             assert rel.max() <= U[p]
             assert rel.max() > U[p] / 16                                       # and it did round
+
+
+def test_product_precision_with_bf16_is_the_smallest_format_holding_both_operands():
+    """BF16 and FP16 hold different numbers, so the formats form a lattice, written out here as
+    sets of (fraction bits, least exponent, greatest exponent) of what each can hold once a tile
+    scale is allowed for FP16 / FP8: a format holds another's numbers if it has at least its
+    fraction bits and, unless one of them is scaled per tile, its exponent range."""
+    frac = {FP64: 52, FP32: 23, FP16: 10, BF16: 7, FP8: 3}
+    wide = {FP64: 3, FP32: 2, BF16: 2, FP16: 1, FP8: 0}              # exponent range classes
+    def holds(big, small):
+        if frac[big] < frac[small]:
+            return False
+        return wide[big] >= wide[small] or small == FP8             # an FP8 tile keeps its scale under FP16 / BF16
+    fmts = [FP64, FP32, FP16, BF16, FP8]
+    for pA, pB in itertools.product(fmts, fmts):
+        cands = [f for f in fmts if holds(f, pA) and holds(f, pB)]
+        want = max(cands, key=lambda f: -frac[f])                    # the one with the fewest fraction bits
+        assert orc.product_precision(pA, pB, FP64, orc.POLICY_OPERAND) == want, (pA, pB)
+        capped = FP32 if want == FP64 else want
+        for pC in (FP32, FP16, FP8, BF16):
+            assert orc.product_precision(pA, pB, pC, orc.POLICY_OPERAND) == capped
+            assert orc.product_precision(pA, pB, pC, orc.POLICY_C_TILE) == FP32
+    assert orc.product_precision(FP16, BF16, FP64) == FP32 and orc.product_precision(BF16, FP8, FP32) == BF16
+
+
+def test_bf16_tiles_small_integers_are_exact_and_general_data_within_bound():
+    """Integers up to 255 fit BF16 exactly, so a problem of small integers with BF16 tiles
+    anywhere (C included: stored BF16 after FP32 accumulation) must give the exact product; on
+    general data an all-BF16 product agrees with an FP64 product of the BF16-rounded operands
+    (rounded with torch's cast) to FP32 accumulation accuracy."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(41)
+    nb, MT, NT, KT = 8, 3, 3, 3
+    M, N, K = MT * nb, NT * nb, KT * nb
+    for trial in range(6):
+        A = rng.integers(-3, 4, (M, K)).astype(np.float64)
+        B = rng.integers(-3, 4, (K, N)).astype(np.float64)
+        C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
+        mA = rng.integers(0, 5, (MT, KT)).astype(np.uint16)
+        mB = rng.integers(0, 5, (KT, NT)).astype(np.uint16)
+        mC = rng.choice([FP64, FP32, BF16], (MT, NT)).astype(np.uint16)
+        mA[0, 0], mB[0, 0], mC[0, 0] = BF16, BF16, BF16
+        pre = _run(nb, A, mA, B, mB, C0, mC, 1.0, 1.0)
+        Y, e = _store(pre, nb, mC)
+        got = orc.stored_values(Y, nb, e)
+        want = (A.astype(np.int64) @ B.astype(np.int64)) + C0.astype(np.int64)
+        assert np.abs(want).max() < 256
+        assert np.array_equal(got, want.astype(np.float64))
+        assert not e.any()                                           # no BF16 / FP32 / FP64 tile has a scale
+    A = rng.standard_normal((M, K)) * np.exp(rng.uniform(-20, 20, (M, K)))
+    B = rng.standard_normal((K, N))
+    full = lambda shape: np.full(shape, BF16, dtype=np.uint16)
+    got = _run(nb, A, full((MT, KT)), B, full((KT, NT)), None, np.full((MT, NT), FP64, dtype=np.uint16), 1.0, 0.0)
+    cast = lambda X: torch.from_numpy(X.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    Ab, Bb = cast(A), cast(B)                       # FP32 first is harmless here only if no tie changes: compare loosely
+    ref = Ab @ Bb
+    bound = 2 * K * 2.0 ** -24 * (np.abs(Ab) @ np.abs(Bb)) + 2.0 ** -8 * 1e-3 * (np.abs(Ab) @ np.abs(Bb))
+    assert np.all(np.abs(got - ref) <= bound)
+    assert np.abs(got - A @ B).max() > 0                              # and it did round the operands

@@ -114,3 +114,45 @@ def test_fp8_decode_and_round_agree_with_torch_e4m3fn():
     tb = torch.from_numpy(x32).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
     _, bits = orc.round_fp8(x32.astype(np.float64))
     assert np.array_equal(bits, tb)
+
+
+def test_bf16_matches_nearest_search_over_all_codes_and_torch():
+    """BF16 (8 exponent bits, 7 fraction bits): the rounded value must be the nearest of all
+    finite BF16 numbers (decoded here from the bit fields, ties to the even code), for doubles
+    that FP32 cannot hold too (no detour through FP32); on FP32 inputs it must equal torch's
+    cast; every code decodes to what torch decodes it to."""
+    torch = pytest.importorskip("torch")
+    codes = np.arange(0x7F80, dtype=np.int64)                      # non-negative finite codes, ascending in value
+    e, m = codes >> 7, codes & 127
+    table = np.where(e == 0, np.ldexp(m.astype(np.float64), -133), np.ldexp(1.0 + m / 128.0, (e - 127).astype(np.int64)))
+    assert np.all(np.diff(table) > 0)
+    got = np.array([orc.bf16_value(int(c)) for c in range(0, 0x7F80, 37)])
+    assert np.array_equal(got, table[::37])
+    want_t = torch.arange(0, 0x7F80, 37, dtype=torch.int32).to(torch.int16).view(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(got, want_t)
+    rng = np.random.default_rng(5)
+    x = np.concatenate([
+        np.exp(rng.uniform(np.log(1e-42), np.log(3e38), 20000)),
+        (table[1000:3000] + table[1001:3001]) / 2,                      # midpoints: ties
+        np.nextafter((table[1000:3000] + table[1001:3001]) / 2, np.inf),
+        np.nextafter((table[1000:3000] + table[1001:3001]) / 2, -np.inf),
+        (table[:300] + table[1:301]) / 2,                               # the subnormal range
+        1.0 + 2.0 ** -8 + np.array([0.0, 2.0 ** -40, -2.0 ** -40]),     # a tie FP32 would break the other way
+        [0.0, 2.0 ** -134, 2.0 ** -134 * 1.0001, 2.0 ** -140]])
+    y, bits = orc.round_bf16(x)
+    idx = np.searchsorted(table, x)
+    lo = np.clip(idx - 1, 0, len(table) - 1)
+    hi = np.clip(idx, 0, len(table) - 1)
+    dlo, dhi = x - table[lo], table[hi] - x                             # exact: neighbours within a factor of two
+    pick_hi = (dhi < dlo) | ((dhi == dlo) & (hi % 2 == 0))
+    want = np.where(pick_hi, hi, lo)
+    assert np.array_equal(bits.astype(np.int64), want)
+    assert np.array_equal(y, table[want])
+    y, bits = orc.round_bf16(-x)
+    assert np.array_equal(bits.astype(np.int64), want | 0x8000)
+    x32 = (np.exp(rng.uniform(np.log(1e-30), np.log(1e30), 100000)) * rng.choice([-1, 1], 100000)).astype(np.float32)
+    tb = torch.from_numpy(x32).to(torch.bfloat16).view(torch.int16).numpy().astype(np.uint16)
+    assert np.array_equal(orc.round_bf16(x32.astype(np.float64))[1], tb)
+    y, bits = orc.round_bf16(np.array([np.inf, -np.inf, np.nan, 3.4e38, -3.4e38, 3.39e38]))
+    assert list(bits[:2]) == [0x7F80, 0xFF80] and np.isnan(y[2])
+    assert y[3] == np.inf and y[4] == -np.inf and np.isfinite(y[5])
