@@ -36,7 +36,9 @@
  * Element types: FP64 / FP32 IEEE; FP16 IEEE binary16; FP8 OCP e4m3 ("fn": no
  * infinities, max finite 448).  FP16 / FP8 tiles hold x * 2^-e with one
  * power-of-two exponent e per tile chosen so that the largest magnitude falls
- * in [2^14,2^15) resp. [2^7,2^8); e = 0 for an all-zero tile.
+ * in [2^14,2^15) resp. [2^7,2^8); e = 0 for an all-zero tile.  BF16 tiles (8
+ * exponent bits as FP32, 7 fraction bits, overflow to infinity) have FP32's
+ * range and carry no scale (e = 0).
  *
  * C tiles stored in FP16 / FP8 (formats beyond FP64 / FP32 are what the paper's
  * Section 6 leaves open): such a tile is a storage format only.  Its products
@@ -61,8 +63,10 @@ extern "C" {
 typedef struct gemm_mp_ctx gemm_mp_ctx; /* opaque; created and destroyed by the library */
 typedef void *gemm_mp_stream;           /* a hipStream_t */
 
-/* Precision codes of a map entry: 0 and 1 as in the paper (Section 5.2); 2, 3 extend them. */
-enum { GEMM_MP_FP64 = 0, GEMM_MP_FP32 = 1, GEMM_MP_FP16 = 2, GEMM_MP_FP8_E4M3 = 3 };
+/* Precision codes of a map entry: 0 and 1 as in the paper (Section 5.2); 2, 3, 4 extend them.
+ * The code is a name, not a rank: by unit roundoff (2^-53, 2^-24, 2^-11, 2^-8, 2^-4) the formats
+ * order FP64, FP32, FP16, BF16, FP8. */
+enum { GEMM_MP_FP64 = 0, GEMM_MP_FP32 = 1, GEMM_MP_FP16 = 2, GEMM_MP_FP8_E4M3 = 3, GEMM_MP_BF16 = 4 };
 
 enum {
     GEMM_MP_OK = 0,
@@ -76,7 +80,10 @@ enum {
 /* How the precision q of the product A(I,L)*B(L,J) that updates C(I,J) is chosen.
  *   OPERAND (default): the better of the two operands' stored precisions, but never above
  *       the type the C tile is accumulated in: q = min(cap(pC), max(pA,pB)), cap(FP64)=FP64,
- *       else FP32.
+ *       else FP32.  With BF16 "the better" is the smallest format that holds both operands'
+ *       numbers exactly, FP64 > FP32 > {FP16, BF16} > FP8: FP32 for an FP16 with a BF16 tile,
+ *       BF16 for a BF16 with a BF16 or an FP8 tile.  A BF16 product multiplies on the BF16
+ *       matrix instruction with FP32 accumulation, like an FP16 one.
  *   C_TILE: the paper's literal statement (Section 5.2: the result precision follows the C
  *       tile and operands are converted when their maps differ): q = cap(pC), which is pC
  *       itself on the paper's FP64 / FP32 maps.
@@ -91,6 +98,9 @@ typedef struct gemm_mp_stats {
     int64_t work_items;      /* owner workgroups launched by gemm_mp_run */
     int64_t converted_tiles; /* tile copies the sender-side workspace holds (0: receiver-side) */
     uint64_t converted_bytes;/* their total size */
+    int64_t products_bf16;   /* the same counts for precision code 4, kept apart so that the */
+    double flops_bf16;       /* arrays above stay indexed by the codes 0..3 */
+    int64_t tiles_bf16[3];
 } gemm_mp_stats;
 
 /* Create a context for C(MxN) = A(MxK) * B(KxN) with square tiles of tile_nb (Section 4:
@@ -121,7 +131,7 @@ int gemm_mp_set_transposed(gemm_mp_ctx *ctx, char which, int transposed);
 
 /* Give the precision map of matrix `which` ('A', 'B' or 'C'): rows x cols codes, row-major,
  * host memory, copied (Section 5.2).  rows/cols must equal the matrix's tile counts (EINVAL),
- * codes must be 0..3 (EINVAL).  Any earlier binding and packed data of that matrix are
+ * codes must be 0..4 (EINVAL).  Any earlier binding and packed data of that matrix are
  * forgotten.  Host only. */
 int gemm_mp_set_precision_map(gemm_mp_ctx *ctx, char which, const uint16_t *map_host,
                               int32_t rows, int32_t cols);
@@ -136,7 +146,8 @@ int gemm_mp_tile_scan(gemm_mp_ctx *ctx, char which, const double *dense_dev, int
 
 /* Norm-based precision map [sync]: scan the dense device matrix and store tile T at the lowest
  * precision p allowed by `allowed_mask` (bit p = code p) that satisfies
- *     |T|_F * sqrt(#tiles) / |X|_F <= threshold / u_p        (u = 2^-53, 2^-24, 2^-11, 2^-4),
+ *     |T|_F * sqrt(#tiles) / |X|_F <= threshold / u_p   (u = 2^-53, 2^-24, 2^-11, 2^-4, 2^-8
+ * for codes 0..4; "lowest" and "highest" go by u),
  * else at the highest allowed one; evaluated on squares in FP64 as
  *     (S_T * #tiles) * (u_p*u_p) <= (threshold*threshold) * S,  S = sum of S_T in tile order.
  * This is the Frobenius-norm tile criterion of the tile-adaptive work the paper builds on
@@ -172,7 +183,11 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *ctx, char which, const double *dense_dev, in
  * products use FP32-accumulating matrix instructions on the scaled operands; 2^(eA+eB) is
  * applied to the finished tile product.  alpha, beta are rounded to the accumulate type.
  * beta == 0: C is not read.  alpha == 0: no product is formed.
- * ESTATE unless A and B are packed, C's map and buffer are set, and (beta != 0) C is packed. */
+ * ESTATE unless A and B are packed, C's map and buffer are set, and (beta != 0) C is packed.
+ * BF16 tiles: the kernels multiply BF16 data only as both operands of a BF16 product; where a
+ * BF16 tile meets another precision in a product (a BF16 tile under an FP32 / FP64 product, an
+ * FP8 tile under a BF16 product) the widened copy is taken from the sender-side workspace, and
+ * the call is ESTATE until gemm_mp_convert_tiles has filled it. */
 int gemm_mp_run(gemm_mp_ctx *ctx, double alpha, double beta, gemm_mp_stream stream);
 
 /* Sender-side conversion (optional).  The paper converts at the receiver: a tile travels in its

@@ -57,7 +57,9 @@ struct gemm_mp_ctx {
     ProductDesc *d_prod = nullptr;    // one record per task (+ 2 padding records), filled on the device
     WorkItem *d_items = nullptr;      // the three lists, [0] first
     gemm_mp_stats stats;
-    bool mixed32 = false;             // list [1] holds an FP16 product with an operand stored in FP8
+    bool mixed32 = false;             // list [1] holds an FP16 / BF16 product with an operand stored in FP8
+    bool has_bf16 = false;            // A or B has a BF16 tile
+    bool bf16_needs_copies = false;   // ... that meets another precision in some product (see gemm_mp_run)
     bool kernel_ready = false;
     // sender-side conversion: per tile of A / B and product precision q, the offset of the copy
     // in precision q inside the workspace (kNoCopy: no task needs one)
@@ -65,7 +67,7 @@ struct gemm_mp_ctx {
     uint64_t conv_bytes = 0;
     int64_t conv_tiles = 0;
     bool conv_active = false;         // the workspace holds copies that match maps, policy and packed data
-    uint64_t *d_conv[2] = {nullptr, nullptr};   // [tiles][4] device addresses of the copies, 0 = none
+    uint64_t *d_conv[2] = {nullptr, nullptr};   // [tiles][8] device addresses of the copies, 0 = none
     ConvertJob *d_jobs = nullptr;
 };
 
@@ -206,14 +208,14 @@ int check_dense(const void *p, int64_t ld, int64_t cols)
 
 double unit_roundoff(int p)
 {
-    static const double u[4] = {0x1p-53, 0x1p-24, 0x1p-11, 0x1p-4};
+    static const double u[5] = {0x1p-53, 0x1p-24, 0x1p-11, 0x1p-4, 0x1p-8};
     return u[p];
 }
 
 // Relative cost of one tile product by precision: inverse matrix-core peak (FP64 : FP32 :
 // FP16 : FP8 = 1/78.6 : 1/157.3 : 1/2516.6 : 1/5033.2 TFLOP/s) plus a floor for the operand
 // traffic that the low precisions cannot hide.
-const double kCost[4] = {64.0, 32.0, 3.0, 2.0};
+const double kCost[5] = {64.0, 32.0, 3.0, 2.0, 3.0};
 
 // The schedule.  Every C tile is cut into (nb/128)^2 owner regions; a region's cost is the
 // sum over its reduction tiles of the cost of that product's precision.  C tiles are sorted by
@@ -234,37 +236,51 @@ void build_schedule(gemm_mp_ctx *c)
             for (int L = 0; L < KT; ++L) {
                 const int q = product_precision(A.map[I * KT + L], B.map[L * NT + J], pC, c->policy);
                 c->q[((size_t)I * NT + J) * KT + L] = (uint8_t)q;
-                c->stats.products[q] += 1;
+                if (q == GEMM_MP_BF16) c->stats.products_bf16 += 1;
+                else c->stats.products[q] += 1;
                 cost[(size_t)I * NT + J] += kCost[q];
             }
         }
     const double f = 2.0 * (double)c->nb * (double)c->nb * (double)c->nb;
     for (int q = 0; q < 4; ++q) c->stats.flops[q] = f * (double)c->stats.products[q];
+    c->stats.flops_bf16 = f * (double)c->stats.products_bf16;
+    c->has_bf16 = false;
+    for (int w = 0; w < 2; ++w)
+        for (uint16_t p : c->mat[w].map) c->has_bf16 |= p == GEMM_MP_BF16;
 
     // Sender-side conversion plan: which (tile, q) copies the tasks would need, and where each
     // would live in the workspace (256-byte aligned, A's copies first).
-    c->conv_off[0].assign((size_t)MT * KT * 4, kNoCopy);
-    c->conv_off[1].assign((size_t)KT * NT * 4, kNoCopy);
+    c->conv_off[0].assign((size_t)MT * KT * kConvSlots, kNoCopy);
+    c->conv_off[1].assign((size_t)KT * NT * kConvSlots, kNoCopy);
+    c->bf16_needs_copies = false;
     for (int I = 0; I < MT; ++I)
         for (int J = 0; J < NT; ++J)
             for (int L = 0; L < KT; ++L) {
                 const int q = c->q[((size_t)I * NT + J) * KT + L];
-                if (A.map[I * KT + L] != q) c->conv_off[0][((size_t)I * KT + L) * 4 + q] = 0;
-                if (B.map[L * NT + J] != q) c->conv_off[1][((size_t)L * NT + J) * 4 + q] = 0;
+                const int pa = A.map[I * KT + L], pb = B.map[L * NT + J];
+                if (pa != q) c->conv_off[0][((size_t)I * KT + L) * kConvSlots + q] = 0;
+                if (pb != q) c->conv_off[1][((size_t)L * NT + J) * kConvSlots + q] = 0;
+                // the GEMM kernels take BF16 data only as both operands of a BF16 product
+                c->bf16_needs_copies |= (pa != q && (pa == GEMM_MP_BF16 || q == GEMM_MP_BF16)) ||
+                                        (pb != q && (pb == GEMM_MP_BF16 || q == GEMM_MP_BF16));
             }
     c->conv_bytes = 0;
     c->conv_tiles = 0;
     for (int w = 0; w < 2; ++w)
         for (size_t k = 0; k < c->conv_off[w].size(); ++k)
             if (c->conv_off[w][k] != kNoCopy) {
-                const int q = (int)(k & 3);
+                const int q = (int)(k % kConvSlots);
                 c->conv_off[w][k] = c->conv_bytes;
                 c->conv_bytes += (((uint64_t)c->nb * c->nb * elem_bytes(q)) + 255) & ~(uint64_t)255;
                 c->conv_tiles += 1;
             }
     c->conv_active = false;
     for (int w = 0; w < 3; ++w) {
-        for (int t = 0; t < c->mat[w].ntiles(); ++t) c->stats.tiles[w][c->mat[w].map[t]] += 1;
+        for (int t = 0; t < c->mat[w].ntiles(); ++t) {
+            const int p = c->mat[w].map[t];
+            if (p == GEMM_MP_BF16) c->stats.tiles_bf16[w] += 1;
+            else c->stats.tiles[w][p] += 1;
+        }
         c->stats.packed_bytes[w] = c->mat[w].bytes;
     }
 
@@ -285,7 +301,7 @@ void build_schedule(gemm_mp_ctx *c)
         for (int J = 0; J < NT; ++J) {
             if (C.map[I * NT + J] == GEMM_MP_FP64 || all_fp8[(size_t)I * NT + J]) continue;
             for (int L = 0; L < KT; ++L)
-                c->mixed32 |= c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_FP16 &&
+                c->mixed32 |= (c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_FP16 || c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_BF16) &&
                               (A.map[I * KT + L] == GEMM_MP_FP8_E4M3 || B.map[L * NT + J] == GEMM_MP_FP8_E4M3);
         }
     constexpr int kBins = 8;
@@ -418,7 +434,7 @@ int gemm_mp_set_precision_map(gemm_mp_ctx *c, char which, const uint16_t *map, i
     Matrix &m = c->mat[w];
     if (rows != m.rows_t || cols != m.cols_t) return GEMM_MP_EINVAL;
     for (int t = 0; t < m.ntiles(); ++t)
-        if (map[t] > GEMM_MP_FP8_E4M3) return GEMM_MP_EINVAL;
+        if (map[t] > GEMM_MP_BF16) return GEMM_MP_EINVAL;
     return install_map(c, w, map);
 }
 
@@ -444,7 +460,7 @@ int gemm_mp_compute_precision_map(gemm_mp_ctx *c, char which, const double *dens
                                   uint32_t allowed_mask, gemm_mp_stream stream, uint16_t *map_out)
 {
     const int w = which_index(which);
-    if (!c || w < 0 || !(threshold >= 0.0) || (allowed_mask & 0xFu) == 0 || (allowed_mask & ~0xFu)) return GEMM_MP_EINVAL;
+    if (!c || w < 0 || !(threshold >= 0.0) || (allowed_mask & 0x1Fu) == 0 || (allowed_mask & ~0x1Fu)) return GEMM_MP_EINVAL;
     Matrix &m = c->mat[w];
     int rc;
     if ((rc = check_dense(dense, ld, m.transposed ? m.rows : m.cols))) return rc;
@@ -459,12 +475,15 @@ int gemm_mp_compute_precision_map(gemm_mp_ctx *c, char which, const double *dens
     double S = 0.0;
     for (int t = 0; t < n; ++t) S = S + sumsq[t];
     const double rhs = (threshold * threshold) * S;
-    int highest = 0;
-    while (!(allowed_mask & (1u << highest))) ++highest;
+    static const int from_lowest[5] = {GEMM_MP_FP8_E4M3, GEMM_MP_BF16, GEMM_MP_FP16, GEMM_MP_FP32, GEMM_MP_FP64};
+    int highest = GEMM_MP_FP64;
+    for (int k = 0; k < 5; ++k)
+        if (allowed_mask & (1u << from_lowest[k])) highest = from_lowest[k];
     std::vector<uint16_t> map(n);
     for (int t = 0; t < n; ++t) {
         int chosen = highest;
-        for (int p = GEMM_MP_FP8_E4M3; p >= GEMM_MP_FP64; --p) {
+        for (int k = 0; k < 5; ++k) {
+            const int p = from_lowest[k];
             if (!(allowed_mask & (1u << p))) continue;
             const double u = unit_roundoff(p);
             const double lhs = (sumsq[t] * (double)n) * (u * u);
@@ -516,7 +535,7 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *c, char which, const double *dense, int64_t 
     if ((rc = ensure_tables(m))) return rc;
     if (!m.exps_from_rule) {
         bool low = false;
-        for (uint16_t p : m.map) low |= p >= GEMM_MP_FP16;
+        for (uint16_t p : m.map) low |= p == GEMM_MP_FP16 || p == GEMM_MP_FP8_E4M3;
         if (low) {
             if ((rc = run_scan(c, m, dense, ld, s))) return rc;
         } else if ((rc = ensure_scan_buffers(c, m))) return rc;
@@ -557,14 +576,17 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
     Matrix &A = c->mat[0], &B = c->mat[1], &C = c->mat[2];
     if (!all_maps(c) || !A.packed || !B.packed || !C.storage) return GEMM_MP_ESTATE;
     if (beta != 0.0 && !C.packed) return GEMM_MP_ESTATE;
-    int rc;
-    hipStream_t s = (hipStream_t)stream;
-    if ((rc = ensure_tables(C))) return rc;
     if (!c->sched_current) {
         if (c->d_q) (void)hipStreamSynchronize(C.last_stream);
         build_schedule(c);
-        if ((rc = upload_schedule(c))) return rc;
-    } else if (!c->d_q && (rc = upload_schedule(c))) return rc;
+        (void)hipFree(c->d_q); (void)hipFree(c->d_items); (void)hipFree(c->d_prod);     // of the old schedule
+        c->d_q = nullptr; c->d_items = nullptr; c->d_prod = nullptr;
+    }
+    if (c->bf16_needs_copies && !c->conv_active) return GEMM_MP_ESTATE;
+    int rc;
+    hipStream_t s = (hipStream_t)stream;
+    if ((rc = ensure_tables(C))) return rc;
+    if (!c->d_q && (rc = upload_schedule(c))) return rc;
     if (!c->kernel_ready) {
         HIP_TRY(gemm_kernel_setup());
         c->kernel_ready = true;
@@ -588,6 +610,7 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
     a.n_items32 = (int32_t)c->items[1].size();
     a.n_items8 = (int32_t)c->items[2].size();
     a.mixed32 = c->mixed32 ? 1 : 0;
+    a.bf16 = c->has_bf16 ? 1 : 0;
     a.nb = c->nb; a.MT = c->MT; a.NT = c->NT; a.KT = c->KT;
     a.kt_eff = alpha == 0.0 ? 0 : c->KT;
     a.alpha = alpha; a.beta = beta;
@@ -633,8 +656,8 @@ int gemm_mp_convert_tiles(gemm_mp_ctx *c, void *workspace, size_t bytes, gemm_mp
         addr[w].assign(c->conv_off[w].size(), 0);
         for (size_t k = 0; k < c->conv_off[w].size(); ++k) {
             if (c->conv_off[w][k] == kNoCopy) continue;
-            const size_t tile = k >> 2;
-            const int q = (int)(k & 3);
+            const size_t tile = k / kConvSlots;
+            const int q = (int)(k % kConvSlots);
             ConvertJob j;
             j.src = (uint64_t)(uintptr_t)((char *)m.storage + m.offset[tile]);
             j.dst = (uint64_t)(uintptr_t)((char *)workspace + c->conv_off[w][k]);
@@ -685,7 +708,7 @@ int gemm_mp_tile_info(gemm_mp_ctx *c, char which, int32_t I, int32_t J, size_t *
     const int t = I * m.cols_t + J;
     int e = 0;
     if (scale_exp) {
-        if (m.map[t] >= GEMM_MP_FP16) {
+        if (m.map[t] == GEMM_MP_FP16 || m.map[t] == GEMM_MP_FP8_E4M3) {
             if (!m.exps_valid) return GEMM_MP_ESTATE;
             HIP_TRY(hipStreamSynchronize(m.last_stream));
             HIP_TRY(hipMemcpy(&e, m.d_exp + t, sizeof(int), hipMemcpyDeviceToHost));
@@ -715,7 +738,7 @@ int gemm_mp_get_stats(gemm_mp_ctx *c, gemm_mp_stats *out)
 
 int gemm_mp_product_precision(int pA, int pB, int pC, int policy)
 {
-    if (pA < 0 || pA > 3 || pB < 0 || pB > 3 || pC < 0 || pC > 3) return -1;
+    if (pA < 0 || pA > 4 || pB < 0 || pB > 4 || pC < 0 || pC > 4) return -1;
     if (policy != GEMM_MP_POLICY_OPERAND && policy != GEMM_MP_POLICY_C_TILE) return -1;
     return product_precision(pA, pB, pC, policy);
 }

@@ -13,18 +13,24 @@ constexpr int kMacro = 128;       // rows = cols of C owned by one workgroup
 constexpr int kMacroFp8 = 256;    // the same for C tiles whose products are all FP8 x FP8
 constexpr int kScanCols = 128;    // columns one scan workgroup reduces; a power of two
 constexpr int kPackBlock = 64;    // pack / unpack move 64 x 64 element blocks
+constexpr int kConvSlots = 8;     // sender-side copies of a tile: one slot per product precision code (0..4 used)
 constexpr int kLowChunk = 4096;   // elements one workgroup handles in the passes over FP16 / FP8 C tiles
 
 // Bytes per element of each precision code.
-__host__ __device__ inline int elem_bytes(int p) { return p == 0 ? 8 : p == 1 ? 4 : p == 2 ? 2 : 1; }
+__host__ __device__ inline int elem_bytes(int p) { return p == 0 ? 8 : p == 1 ? 4 : (p == 2 || p == 4) ? 2 : 1; }
 
 // Product precision (code) for stored precisions pA, pB, C tile precision pC.
 __host__ __device__ inline int product_precision(int pA, int pB, int pC, int policy)
 {
     const int cap = (pC == GEMM_MP_FP64) ? GEMM_MP_FP64 : GEMM_MP_FP32;
     if (policy == GEMM_MP_POLICY_C_TILE) return cap;
-    const int better = pA < pB ? pA : pB;       // smaller code = finer format
-    return better > cap ? better : cap;
+    // the smallest format that holds both operands' numbers: FP64 > FP32 > {FP16, BF16} > FP8
+    int q;
+    const bool h = pA == GEMM_MP_FP16 || pB == GEMM_MP_FP16, b = pA == GEMM_MP_BF16 || pB == GEMM_MP_BF16;
+    if (pA == GEMM_MP_FP64 || pB == GEMM_MP_FP64) q = GEMM_MP_FP64;
+    else if (pA == GEMM_MP_FP32 || pB == GEMM_MP_FP32 || (h && b)) q = GEMM_MP_FP32;
+    else q = h ? GEMM_MP_FP16 : b ? GEMM_MP_BF16 : GEMM_MP_FP8_E4M3;
+    return (q == GEMM_MP_FP64 && cap == GEMM_MP_FP32) ? GEMM_MP_FP32 : q;
 }
 
 // Device-side view of one packed matrix.
@@ -49,7 +55,8 @@ struct ProductDesc {
     uint64_t a_ptr, b_ptr;   // device addresses of the two operand tiles (packed storage, or the
                              // sender-side workspace when a converted copy exists)
     int32_t ea, eb;          // their scale exponents
-    uint32_t codes;          // pA | pB << 8 | q << 16, pA / pB as the kernel finds them there
+    uint32_t codes;          // pA | pB << 8 | q << 16, pA / pB as the kernel finds them there; BF16 is
+                             // written as FP16 (the same element size) with a flag: bit 24 A, 25 B, 26 q
     uint32_t pad;
 };
 
@@ -78,13 +85,14 @@ struct GemmArgs {
     PackedView A, B, C;
     const uint8_t *q;        // [MT*NT][KT] product precision of every task
     ProductDesc *prod;       // [MT*NT][KT] (+ padding records), written by launch_gemm
-    const uint64_t *convA;   // [tiles of A][4] address of the copy converted to q, 0 = none; or null
+    const uint64_t *convA;   // [tiles of A][kConvSlots] address of the copy converted to q, 0 = none; or null
     const uint64_t *convB;   // same for B
     const WorkItem *items64;  // owner regions of FP64 C tiles, launch order
     const WorkItem *items32;  // owner regions of FP32 C tiles, launch order
     const WorkItem *items8;   // 256 x 256 regions of FP32 C tiles made of FP8 x FP8 products only
     int32_t n_items64, n_items32, n_items8;
-    int32_t mixed32;         // some region of items32 has an FP16 product with an operand stored in FP8
+    int32_t mixed32;         // some region of items32 has an FP16 / BF16 product with an operand stored in FP8
+    int32_t bf16;            // some tile of A or B is stored in BF16
     int32_t nb, MT, NT, KT;
     int32_t kt_eff;          // KT, or 0 when alpha == 0
     double alpha, beta;

@@ -4,7 +4,8 @@
 // reduction: it walks the reduction tiles L = 0..KT-1 in ascending order, runs each tile product
 // A(I,L)*B(L,J) on the matrix cores at that task's precision q, and writes C once.  Nothing else
 // ever touches that region, so there are no atomics and the result is reproducible.  Regions
-// are 128 x 128 (gemm_mp_owner_kernel: one instance for FP64 C tiles, two for FP32 C tiles), or
+// are 128 x 128 (gemm_mp_owner_kernel: instances for FP64 and for FP32 C tiles, with and without
+// the two options described below), or
 // 256 x 256 for FP32 C tiles whose products are all FP8 x FP8 (gemm_mp_fp8_region_kernel, at
 // the end of this file).
 //
@@ -22,6 +23,9 @@
 //   when such products exist) the FP8 operand takes the ring as it is and is converted between
 //   the fragment read and the MFMA; elsewhere a two-stage loop with conversion in registers on
 //   the way to LDS, rows padded by 8 B.
+//   BF16 products (BF instances, launched when A or B has BF16 tiles): the FP16 ring with the
+//   BF16 matrix instruction; both operands are BF16 data (a tile stored otherwise comes as a
+//   BF16 copy from the sender-side workspace), marked by a flag in the product's table record.
 //
 // Fragment convention.  Packed A tiles are row-major and packed B tiles are stored transposed,
 // so both operands have the reduction index contiguous.  Which reduction index a lane's bytes
@@ -1000,7 +1004,8 @@ __device__ __forceinline__ void lo_read_all(u32x4 (&f)[16], const char *stage, c
 // The MFMAs are asm in place, see mfma_group.
 // MIX != 0 (FP16 product with an FP8 operand): the next chunk's reads are the four of the FP8
 // operand, then the eight of the other one; the 32 conversions follow two per MFMA.
-template <int Q, int PAR, bool FIRST, bool MIXED, int MIX, typename Book>
+// BFQ: the product multiplies BF16 numbers (operands as for FP16, the other matrix instruction).
+template <int Q, int PAR, bool FIRST, bool MIXED, int MIX, bool BFQ, typename Book>
 __device__ __forceinline__ void lo_chunk(f4 (&acc)[4][4], u32x4 (&fr)[2][16], const char *next, const LoGeom &LG, const MixGeom &MG,
                                          const Product &pr, int soff0, int rows8_bytes, unsigned dst, Book book)
 {
@@ -1013,7 +1018,17 @@ __device__ __forceinline__ void lo_chunk(f4 (&acc)[4][4], u32x4 (&fr)[2][16], co
         const bool first = m == 0, last = m == kMfmas - 1;
         // FIRST: the product's first chunk starts its accumulators from zero (C operand 0)
         const bool zero = FIRST && (Q == Q8 || m < 16);
-        if constexpr (Q == Q16) {
+        if constexpr (Q == Q16 && BFQ) {
+            const u32x4 x = fr[PAR][mt * 2 + kk], y = fr[PAR][(4 + nt) * 2 + kk];
+            if (zero) {
+                if (first) asm volatile("s_nop 3\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=a"(acc[mt][nt]) : "v"(x), "v"(y));
+                else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=a"(acc[mt][nt]) : "v"(x), "v"(y));
+            } else {
+                if (first) asm volatile("s_nop 3\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+                else if (last) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0\n\ts_nop 11" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+                else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[mt][nt]) : "v"(x), "v"(y));
+            }
+        } else if constexpr (Q == Q16) {
             const u32x4 x = fr[PAR][mt * 2 + kk], y = fr[PAR][(4 + nt) * 2 + kk];
             if (zero) {
                 if (first) asm volatile("s_nop 3\n\tv_mfma_f32_16x16x32_f16 %0, %1, %2, 0" : "=a"(acc[mt][nt]) : "v"(x), "v"(y));
@@ -1069,7 +1084,7 @@ __device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int e
 // A run of consecutive ring products starting at product `cur` (reduction tile L).  On return
 // `cur` is the first product after the run (q = -1: none) and L its index; if that product wants
 // its first chunk staged, it is in stage 0 of the two-stage layout.
-template <typename AccS, bool MIXED>
+template <typename AccS, bool MIXED, bool BF>
 __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, const Walk &W, char *lds, const Geometry &G0,
                                        const Region &R)
 {
@@ -1156,6 +1171,8 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
     __syncthreads();
     u32x4 fr[2][16];
     int cmix = MIXED ? ring_mix(cur.q, cur.a.p, cur.b.p) : 0;
+    bool cbf = false;              // the product being computed is a BF16 one (flag in its table record)
+    if constexpr (BF) cbf = ((((ConstQuad)(uintptr_t)(R.prod + L))[1].z >> 26) & 1u) != 0;
     if constexpr (MIXED) lo_read_all(fr[0], lds, LG, MG, cmix);
     else {
 #pragma unroll
@@ -1177,9 +1194,10 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
         ++done;
         st_next = st_next + kLoStage == kLoLdsBytes ? 0 : st_next + kLoStage;
     };
-#define GMP_LO_STEP(QQ, PAR, FIRST, MIX)                                             \
+#define GMP_LO_STEP(QQ, PAR, FIRST, MIX) GMP_LO_STEP_AS(QQ, PAR, FIRST, MIX, false)
+#define GMP_LO_STEP_AS(QQ, PAR, FIRST, MIX, BFQ)                                     \
     do {                                                                             \
-        lo_chunk<QQ, PAR, FIRST, MIXED, MIX>(t, fr, lds + st_next, LG, MG, GMP_LO_REQ_ARGS, step_book); \
+        lo_chunk<QQ, PAR, FIRST, MIXED, MIX, BFQ>(t, fr, lds + st_next, LG, MG, GMP_LO_REQ_ARGS, step_book); \
         if (slow) turn();                                                            \
         lo_wait_dma(8 * (kLoStages - 2));                                            \
         __syncthreads();                                                             \
@@ -1192,7 +1210,15 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
         const int nq = more ? (int)((nrec.z >> 16) & 0xffu) : -1;
         const int nesum = (int)nrec.x + (int)nrec.y;
         const int nmix = MIXED ? ring_mix(nq, (int)(nrec.z & 0xffu), (int)((nrec.z >> 8) & 0xffu)) : 0;
-        if (cq == Q16) {                           // 64 elements per chunk: always an even count
+        const bool nbf = BF && ((nrec.z >> 26) & 1u) != 0;
+        if (BF && cq == Q16 && cbf) {              // a BF16 product: both operands BF16 (copies where they were not)
+            GMP_LO_STEP_AS(Q16, 0, true, 0, true);
+            GMP_LO_STEP_AS(Q16, 1, false, 0, true);
+            for (int cc = 2; cc < cn; cc += 2) {
+                GMP_LO_STEP_AS(Q16, 0, false, 0, true);
+                GMP_LO_STEP_AS(Q16, 1, false, 0, true);
+            }
+        } else if (cq == Q16) {                    // 64 elements per chunk: always an even count
             if (!MIXED || cmix == 0) {
                 GMP_LO_STEP(Q16, 0, true, 0);
                 GMP_LO_STEP(Q16, 1, false, 0);
@@ -1241,9 +1267,11 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
         ++cL;
         cq = nq;
         cmix = nmix;
+        cbf = nbf;
         cesum = nesum;
     }
 #undef GMP_LO_STEP
+#undef GMP_LO_STEP_AS
 #undef GMP_LO_REQ_ARGS
     lo_wait_dma(0);                                // the empty requests still write (zeros) into the ring
     __syncthreads();
@@ -1385,7 +1413,7 @@ __device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int e
 // T = double: FP64 C tiles; the running sum s is FP64 and every product below FP64 is formed
 //             in the FP32 accumulator t first.
 // T = float : FP32 C tiles; FP32 products continue s, FP16 / FP8 products go through t.
-template <typename T, bool MIXED>
+template <typename T, bool MIXED, bool BF>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 {
@@ -1447,7 +1475,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     while (L < R.kt_eff) {
         const int q = cur.q;
         if (is_ring<MIXED>(cur, G)) {
-            lo_run<AccS, MIXED>(s, cur, L, W, lds, G, R);   // all consecutive products of that kind
+            lo_run<AccS, MIXED, BF>(s, cur, L, W, lds, G, R);   // all consecutive products of that kind
             stage = 0;
             continue;
         }
@@ -1803,15 +1831,13 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 
 hipError_t gemm_kernel_setup()
 {
-    hipError_t e = hipFuncSetAttribute((const void *)gemm_mp_owner_kernel<double, false>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)gemm_mp_owner_kernel<float, false>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)gemm_mp_owner_kernel<float, true>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
+    const void *owners[5] = {(const void *)gemm_mp_owner_kernel<double, false, false>, (const void *)gemm_mp_owner_kernel<float, false, false>,
+                             (const void *)gemm_mp_owner_kernel<float, true, false>, (const void *)gemm_mp_owner_kernel<double, false, true>,
+                             (const void *)gemm_mp_owner_kernel<float, false, true>};
+    for (const void *k : owners) {
+        const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+    }
     return hipFuncSetAttribute((const void *)gemm_mp_fp8_region_kernel,
                                hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
 }
@@ -1837,17 +1863,21 @@ __global__ void product_table_kernel(PackedView A, PackedView B, const uint8_t *
     d.b_ptr = (uint64_t)(uintptr_t)(B.storage + B.offset[tb]);
     d.ea = A.exp[ta];
     d.eb = B.exp[tb];
-    if (convA && pa != qq && convA[ta * 4 + qq]) {
-        d.a_ptr = convA[ta * 4 + qq];
+    if (convA && pa != qq && convA[ta * kConvSlots + qq]) {
+        d.a_ptr = convA[ta * kConvSlots + qq];
         pa = qq;
         if (qq <= (uint32_t)Q32) d.ea = 0;
     }
-    if (convB && pb != qq && convB[tb * 4 + qq]) {
-        d.b_ptr = convB[tb * 4 + qq];
+    if (convB && pb != qq && convB[tb * kConvSlots + qq]) {
+        d.b_ptr = convB[tb * kConvSlots + qq];
         pb = qq;
         if (qq <= (uint32_t)Q32) d.eb = 0;
     }
-    d.codes = pa | (pb << 8) | (qq << 16);
+    // BF16 (code 4) has FP16's element size: the kernels see it as FP16 with a flag
+    const uint32_t flags = (pa == GEMM_MP_BF16 ? 1u : 0u) | (pb == GEMM_MP_BF16 ? 2u : 0u) | (qq == GEMM_MP_BF16 ? 4u : 0u);
+    const uint32_t ia = pa == GEMM_MP_BF16 ? (uint32_t)Q16 : pa, ib = pb == GEMM_MP_BF16 ? (uint32_t)Q16 : pb;
+    const uint32_t iq = qq == GEMM_MP_BF16 ? (uint32_t)Q16 : qq;
+    d.codes = ia | (ib << 8) | (iq << 16) | (flags << 24);
     d.pad = 0;
     out[idx] = d;
 }
@@ -1862,6 +1892,29 @@ __global__ __launch_bounds__(256) void convert_tiles_kernel(const ConvertJob *__
     const uint32_t seg = blockIdx.x * 256u + threadIdx.x;
     if (seg >= job.n16) return;
     const int p = job.p, q = job.q;
+    if (p == GEMM_MP_BF16 || q == GEMM_MP_BF16) {
+        // BF16 tile to FP32 / FP64 (a shift: exact), or FP8 tile to BF16 keeping its scale (exact:
+        // every e4m3 number is a BF16 number).  No other pair occurs: FP16 and BF16 meet in FP32.
+        const char *sb = (const char *)(uintptr_t)job.src;
+        u32x4 o;
+        if (q == GEMM_MP_BF16) {
+            const u32x2 w = *(const u32x2 *)(sb + (uint64_t)seg * 8);
+            const int w0 = (int)w.x, w1 = (int)w.y;
+            o.x = (__float_as_uint(__builtin_amdgcn_cvt_f32_fp8(w0, 0)) >> 16) | (__float_as_uint(__builtin_amdgcn_cvt_f32_fp8(w0, 1)) & 0xffff0000u);
+            o.y = (__float_as_uint(__builtin_amdgcn_cvt_f32_fp8(w0, 2)) >> 16) | (__float_as_uint(__builtin_amdgcn_cvt_f32_fp8(w0, 3)) & 0xffff0000u);
+            o.z = (__float_as_uint(__builtin_amdgcn_cvt_f32_fp8(w1, 0)) >> 16) | (__float_as_uint(__builtin_amdgcn_cvt_f32_fp8(w1, 1)) & 0xffff0000u);
+            o.w = (__float_as_uint(__builtin_amdgcn_cvt_f32_fp8(w1, 2)) >> 16) | (__float_as_uint(__builtin_amdgcn_cvt_f32_fp8(w1, 3)) & 0xffff0000u);
+        } else if (q == Q32) {
+            const u32x2 w = *(const u32x2 *)(sb + (uint64_t)seg * 8);
+            o = u32x4{w.x << 16, w.x & 0xffff0000u, w.y << 16, w.y & 0xffff0000u};
+        } else {
+            const uint32_t w = *(const uint32_t *)(sb + (uint64_t)seg * 4);
+            const u32x2 a = dbits((double)__uint_as_float(w << 16)), b = dbits((double)__uint_as_float(w & 0xffff0000u));
+            o = u32x4{a.x, a.y, b.x, b.y};
+        }
+        *(u32x4 *)((char *)(uintptr_t)job.dst + (uint64_t)seg * 16) = o;
+        return;
+    }
     const int e = (job.which == 0 ? expA : expB)[job.tile];
     const uint64_t src_byte = ((uint64_t)seg * (uint64_t)(2u << q)) << (3 - p);   // first source byte of this segment
     const char *src = (const char *)(uintptr_t)job.src + (src_byte & ~(uint64_t)15);
@@ -1892,12 +1945,16 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
     const int64_t tasks = (int64_t)a.MT * a.NT * a.KT;
     product_table_kernel<<<dim3((unsigned)((tasks + 255) / 256)), dim3(256), 0, s>>>(a.A, a.B, a.q, a.MT, a.NT, a.KT, a.convA, a.convB, a.prod);
-    if (a.n_items64 > 0)
-        gemm_mp_owner_kernel<double, false><<<dim3((unsigned)a.n_items64), dim3(kThreads), kLdsBytes, s>>>(a, a.items64);
+    if (a.n_items64 > 0) {
+        // BF16 tiles among the operands: the instances that know the BF16 matrix instruction
+        if (a.bf16) gemm_mp_owner_kernel<double, false, true><<<dim3((unsigned)a.n_items64), dim3(kThreads), kLdsBytes, s>>>(a, a.items64);
+        else gemm_mp_owner_kernel<double, false, false><<<dim3((unsigned)a.n_items64), dim3(kThreads), kLdsBytes, s>>>(a, a.items64);
+    }
     if (a.n_items32 > 0) {
         // the instance whose DMA ring also takes FP16 products with an FP8 operand only where such products exist
-        if (a.mixed32) gemm_mp_owner_kernel<float, true><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
-        else gemm_mp_owner_kernel<float, false><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
+        if (a.bf16) gemm_mp_owner_kernel<float, false, true><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
+        else if (a.mixed32) gemm_mp_owner_kernel<float, true, false><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
+        else gemm_mp_owner_kernel<float, false, false><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
     }
     if (a.n_items8 > 0)
         gemm_mp_fp8_region_kernel<<<dim3((unsigned)a.n_items8), dim3(kThreads), kBigLdsBytes, s>>>(a, a.items8);

@@ -192,6 +192,19 @@ __device__ inline uint32_t to_fp8_bits(double x, int e)
     return sign | r;
 }
 
+// BF16 has FP32's exponent range: no tile scale, overflow to infinity.
+__device__ inline uint32_t to_bf16_bits(double x)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint32_t sign = (uint32_t)(b >> 48) & 0x8000u;
+    const uint64_t mag = b & 0x7fffffffffffffffull;
+    if (mag > 0x7ff0000000000000ull) return sign | 0x7fc0u;    // NaN
+    if (mag == 0x7ff0000000000000ull) return sign | 0x7f80u;   // infinity
+    uint32_t r = round_magnitude<7, -126, 127>(mag, 0);
+    if (r > 0x7f80u) r = 0x7f80u;                              // overflow -> infinity
+    return sign | r;
+}
+
 // The stored bit pattern of one element, right-aligned in 64 bits.
 __device__ inline uint64_t stored_bits(double x, int p, int e)
 {
@@ -199,6 +212,7 @@ __device__ inline uint64_t stored_bits(double x, int p, int e)
     case GEMM_MP_FP64: return (uint64_t)__double_as_longlong(x);
     case GEMM_MP_FP32: return (uint64_t)__float_as_uint((float)x);     // v_cvt_f32_f64, nearest even
     case GEMM_MP_FP16: return to_fp16_bits(x, e);
+    case GEMM_MP_BF16: return to_bf16_bits(x);
     default:           return to_fp8_bits(x, e);
     }
 }
@@ -217,7 +231,8 @@ __device__ inline void store4(char *dst, int p, const uint64_t (&v)[4])
         a.x = (uint32_t)v[0]; a.y = (uint32_t)v[1]; a.z = (uint32_t)v[2]; a.w = (uint32_t)v[3];
         *(uint4 *)dst = a;
     } break;
-    case GEMM_MP_FP16: {
+    case GEMM_MP_FP16:
+    case GEMM_MP_BF16: {
         uint2 a;
         a.x = (uint32_t)v[0] | ((uint32_t)v[1] << 16);
         a.y = (uint32_t)v[2] | ((uint32_t)v[3] << 16);
@@ -302,6 +317,7 @@ __device__ inline double stored_value(const char *base, int64_t idx, int p, int 
     case GEMM_MP_FP64: return ((const double *)base)[idx];
     case GEMM_MP_FP32: return (double)((const float *)base)[idx];
     case GEMM_MP_FP16: return ldexp((double)(float)((const _Float16 *)base)[idx], e);
+    case GEMM_MP_BF16: return (double)__uint_as_float((uint32_t)((const uint16_t *)base)[idx] << 16);
     default: {
         const int code = ((const uint8_t *)base)[idx];
         return ldexp((double)__builtin_amdgcn_cvt_f32_fp8(code, 0), e);
@@ -386,6 +402,10 @@ __global__ __launch_bounds__(256) void low_expand_kernel(const LowTile *__restri
             const uint2 h = *(const uint2 *)(src + i * 2);
             const _Float16 *hh = (const _Float16 *)&h;
             x = make_float4((float)hh[0], (float)hh[1], (float)hh[2], (float)hh[3]);
+        } else if (p == GEMM_MP_BF16) {
+            const uint2 h = *(const uint2 *)(src + i * 2);
+            x = make_float4(__uint_as_float(h.x << 16), __uint_as_float(h.x & 0xffff0000u),
+                            __uint_as_float(h.y << 16), __uint_as_float(h.y & 0xffff0000u));
         } else {
             const uint32_t b = *(const uint32_t *)(src + i);
             x = make_float4(__builtin_amdgcn_cvt_f32_fp8(b, 0), __builtin_amdgcn_cvt_f32_fp8(b, 1),
@@ -451,7 +471,7 @@ __global__ __launch_bounds__(256) void low_exponent_kernel(const LowTile *__rest
         const int field = (int)(bits >> 23);
         const uint32_t man = bits & 0x7fffffu;
         int e = 0;
-        if (field != 0xff && bits != 0) {
+        if (field != 0xff && bits != 0 && prec[lt.tile] != GEMM_MP_BF16) {      // BF16 tiles carry no scale
             const int lg = field ? field - 127 : 31 - __builtin_clz(man) - 149;
             e = lg - (prec[lt.tile] == GEMM_MP_FP16 ? 14 : 7);
         }

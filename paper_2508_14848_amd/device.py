@@ -84,7 +84,7 @@ class DeviceGemmMP:
     def tile_bytes(self, which, I, J):
         """Raw stored bytes of one tile as a uint8 host array (for bit-exact checks)."""
         off, prec, _ = self.ctx.tile_info(which, I, J, want_exp=False)
-        n = self.ctx.nb * self.ctx.nb * (8 >> prec)
+        n = self.ctx.nb * self.ctx.nb * (2 if prec == 4 else 8 >> prec)
         torch.cuda.synchronize()
         return self.storage[which][off:off + n].cpu().numpy(), prec
 

@@ -4,8 +4,8 @@ import numpy as np
 
 from oracle import gemm_mp_oracle as orc
 
-FP64, FP32, FP16, FP8 = 0, 1, 2, 3
-U = {FP64: 2.0 ** -53, FP32: 2.0 ** -24, FP16: 2.0 ** -11, FP8: 2.0 ** -4}
+FP64, FP32, FP16, FP8, BF16 = 0, 1, 2, 3, 4
+U = {FP64: 2.0 ** -53, FP32: 2.0 ** -24, FP16: 2.0 ** -11, FP8: 2.0 ** -4, BF16: 2.0 ** -8}
 
 
 class OracleSide:
@@ -114,9 +114,11 @@ def compare_jobs(side, jobs, policy, alpha, beta, C_gpu, C_orc):
             # storage rounding of the finished tile, on both sides: relative u_p per entry in the
             # format's normal range, a full smallest step below it, both doubled because the two
             # sides' exponents may differ by one when their maxima straddle a power of two
-            E, step = LOW_FORMAT[t["pC"]]
-            e_hi = np.floor(np.log2(np.abs(o).max())) - E + 1
-            tight += 2.0 * U[t["pC"]] * np.linalg.norm(o) + np.sqrt(float(o.size)) * step * 2.0 ** e_hi
+            tight += 2.0 * U[t["pC"]] * np.linalg.norm(o)
+            if t["pC"] != BF16:                     # BF16 has no tile scale; its subnormals lie below FP32's normal range
+                E, step = LOW_FORMAT[t["pC"]]
+                e_hi = np.floor(np.log2(np.abs(o).max())) - E + 1
+                tight += np.sqrt(float(o.size)) * step * 2.0 ** e_hi
         worst["star"] = max(worst["star"], err / (t["tol"] * base))
         worst["tight"] = max(worst["tight"], err / tight)
         assert err <= t["tol"] * base, "tile (%d,%d): err %.3e > 4*K*u_tile bound %.3e" % (I, J, err, t["tol"] * base)
@@ -165,4 +167,6 @@ def packed_codes_expected(side, which, I, J):
         return tile.astype(np.float32).view(np.uint8).ravel()
     if p == FP16:
         return orc.round_fp16(tile)[1].view(np.uint8).ravel()
+    if p == BF16:
+        return orc.round_bf16(tile)[1].view(np.uint8).ravel()
     return orc.round_fp8(tile)[1].ravel()

@@ -62,7 +62,7 @@ def test_map_validation_and_call_order():
         g.set_precision_map("A", np.zeros((3, 4), np.uint16))          # A is 4 x 3 tiles
     assert e.value.status == G.EINVAL
     with pytest.raises(G.GemmMPError) as e:
-        g.set_precision_map("A", np.full((4, 3), 4, np.uint16))        # code out of range
+        g.set_precision_map("A", np.full((4, 3), 5, np.uint16))        # code out of range
     assert e.value.status == G.EINVAL
     with pytest.raises(G.GemmMPError) as e:
         g.set_precision_map("X", np.zeros((4, 3), np.uint16))
@@ -132,6 +132,38 @@ def test_c_tiles_in_fp16_or_fp8_carry_an_fp32_staging_copy_behind_the_packed_til
     g.set_policy(G.POLICY_C_TILE)
     assert g.get_stats()["products"] == [1, 5, 0, 0]
     assert g.get_stats()["tiles"][2] == [1, 2, 2, 1]
+    g.destroy()
+
+
+def test_bf16_codes_layout_products_and_conversion_plan():
+    """BF16 (code 4): two bytes per element, no staging on A or B; the product precision equals
+    the oracle's for every triple and both policies; BF16 products are counted apart; the
+    sender-side plan holds an FP32 copy of a BF16 tile that meets an FP32 tile and a BF16 copy
+    of an FP8 tile that meets a BF16 tile."""
+    from oracle import gemm_mp_oracle as orc
+    for pA in range(5):
+        for pB in range(5):
+            for pC in range(5):
+                for policy in (G.POLICY_OPERAND, G.POLICY_C_TILE):
+                    assert G.product_precision(pA, pB, pC, policy) == orc.product_precision(pA, pB, pC, policy)
+    nb = 128
+    g = G.GemmMP(2 * nb, 2 * nb, 2 * nb, nb)
+    full = lambda p: np.full((2, 2), p, dtype=np.uint16)
+    g.set_precision_map("A", full(G.BF16))
+    assert g.storage_bytes("A") == 4 * nb * nb * 2
+    g.set_precision_map("B", full(G.BF16))
+    g.set_precision_map("C", full(G.FP32))
+    st = g.get_stats()
+    assert st["products"] == [0, 0, 0, 0] and st["products_bf16"] == 8 and st["flops_bf16"] == 8 * 2.0 * nb ** 3
+    assert st["tiles_bf16"] == [4, 4, 0] and g.conversion_bytes() == 0
+    g.set_precision_map("B", full(G.FP32))                    # FP32 products: A's tiles need FP32 copies
+    assert g.get_stats()["products"] == [0, 8, 0, 0] and g.conversion_bytes() == 4 * nb * nb * 4
+    g.set_precision_map("B", full(G.FP16))                    # FP16 with BF16: FP32 products, copies of both
+    assert g.get_stats()["products"] == [0, 8, 0, 0] and g.conversion_bytes() == 8 * nb * nb * 4
+    g.set_precision_map("B", full(G.FP8_E4M3))                # BF16 products: B's tiles need BF16 copies
+    assert g.get_stats()["products_bf16"] == 8 and g.conversion_bytes() == 4 * nb * nb * 2
+    g.set_precision_map("C", full(G.BF16))                    # a BF16 C tile: stored BF16 behind FP32 staging
+    assert g.storage_bytes("C") == 4 * nb * nb * (2 + 4) and g.get_stats()["products_bf16"] == 8
     g.destroy()
 
 

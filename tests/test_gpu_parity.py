@@ -8,7 +8,7 @@ import pytest
 
 import workloads as W
 from oracle import gemm_mp_oracle as orc
-from tests.harness import (FP8, FP16, FP32, FP64, OracleSide, compare_jobs, finish_low_c_tiles, gpu_problem,
+from tests.harness import (BF16, FP8, FP16, FP32, FP64, OracleSide, compare_jobs, finish_low_c_tiles, gpu_problem,
                            packed_codes_expected)
 
 pytestmark = pytest.mark.gpu
@@ -582,6 +582,135 @@ def test_c_map_from_the_norm_rule_with_all_formats_and_sender_side_conversion():
     jobs = _all_jobs(w)
     C_orc, _ = finish_low_c_tiles(side, side.gemm(jobs))
     worst = compare_jobs(side, jobs, 0, w.alpha, w.beta, results[0], C_orc)
+    _say("  worst error / bound:", worst)
+
+
+def test_bf16_tiles_pack_bit_for_bit_and_the_rule_ranks_them_between_fp16_and_fp8():
+    """BF16 storage: packed codes equal the oracle's single rounding from FP64 (values spread over
+    FP32's whole range, ties, subnormals, overflow to infinity), A row-major and B transposed;
+    unpack returns the stored values; the norm rule over all five formats gives the oracle's map."""
+    import torch
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(55)
+    nb, T = 128, 2
+    n = nb * T
+    X = rng.standard_normal((n, n)) * np.exp(rng.uniform(-80, 80, (n, n)))
+    X[0, :8] = [1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -40, 3.4e38, -3.4e38, 1e-40, 2.0 ** -134, 0.0]
+    d = DeviceGemmMP(n, n, n, nb)
+    pm = np.full((T, T), BF16, dtype=np.uint16)
+    dX = torch.from_numpy(X).cuda()
+    Y, bits = orc.round_bf16(X)
+    for which in ("A", "B"):
+        d.set_precision_map(which, pm)
+        d.pack_tiles(which, dX)
+        for I in range(T):
+            for J in range(T):
+                got, prec = d.tile_bytes(which, I, J)
+                tile = bits[I * nb:(I + 1) * nb, J * nb:(J + 1) * nb]
+                want = np.ascontiguousarray(tile.T if which == "B" else tile).view(np.uint8).ravel()
+                assert prec == BF16 and np.array_equal(got, want)
+                assert d.ctx.tile_info(which, I, J)[2] == 0
+        U = d.unpack_tiles(which).cpu().numpy()
+        assert np.array_equal(U, Y)
+    # the rule: decaying tiles, every format allowed
+    w = W.tiny()
+    A = w.dense("A")
+    sa, _ = orc.tile_scan(A, w.nb)
+    for eps in (1e-2, 1e-4, 1e-6):
+        want = orc.precision_rule(sa, eps, orc.ALL_FORMATS_MASK)
+        d2 = DeviceGemmMP(w.M, w.N, w.K, w.nb)
+        got = d2.compute_precision_map("A", torch.from_numpy(A).cuda(), eps, orc.ALL_FORMATS_MASK)
+        assert np.array_equal(got, want)
+    assert BF16 in set(orc.precision_rule(sa, 1e-4, orc.ALL_FORMATS_MASK).ravel().tolist())
+    torch.cuda.synchronize()
+
+
+def test_bf16_tiles_small_integer_problems_are_exact():
+    """Maps over all five formats on A and B, C tiles FP64 / FP32 / BF16 / FP16 / FP8, both policies.
+    BF16 tiles that meet another precision in a product need the sender-side copies (the call
+    order error says so); with them every result must be the exact integer matrix: BF16
+    products on the BF16 matrix instruction, BF16 tiles widened to FP32 / FP64 copies, FP8 tiles
+    widened to BF16 copies, a BF16 C tile rounded from its FP32 staging copy."""
+    import torch
+    from paper_2508_14848_amd import gemm_mp as G
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(56)
+    for case in range(24):
+        nb = int(rng.choice([128, 256]))
+        MT, NT, KT = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        M, N, K = MT * nb, NT * nb, KT * nb
+        A = np.zeros((M, K))
+        B = np.zeros((K, N))
+        cols = rng.integers(0, nb, (M, KT)) + nb * np.arange(KT)
+        A[np.arange(M)[:, None], cols] = rng.integers(-2, 3, (M, KT))
+        rows = rng.integers(0, nb, (KT, N)) + nb * np.arange(KT)[:, None]
+        B[rows, np.arange(N)[None, :]] = rng.integers(-1, 2, (KT, N))
+        C0 = rng.integers(-3, 4, (M, N)).astype(np.float64)
+        style = case % 3
+        if style == 0:                                   # anything
+            mA, mB = rng.integers(0, 5, (MT, KT)), rng.integers(0, 5, (KT, NT))
+        elif style == 1:                                 # BF16 and FP8 only: BF16 and FP8 products
+            mA, mB = rng.choice([BF16, FP8], (MT, KT)), rng.choice([BF16, FP8], (KT, NT))
+        else:                                            # all BF16: no copies needed
+            mA, mB = np.full((MT, KT), BF16), np.full((KT, NT), BF16)
+        mC = rng.integers(0, 5, (MT, NT))
+        policy = case % 2
+        what = dict(case=case, nb=nb, MT=MT, NT=NT, KT=KT, style=style, policy=policy)
+        if case % 6 == 0:
+            _say("BF16 integers", what)
+        want = 2 * (A.astype(np.int64) @ B.astype(np.int64)) - C0.astype(np.int64)
+        assert np.abs(want).max() <= 15
+        d = DeviceGemmMP(M, N, K, nb, policy=policy)
+        for which, m, X in (("A", mA, A), ("B", mB, B), ("C", mC, C0)):
+            d.set_precision_map(which, m.astype(np.uint16))
+            d.pack_tiles(which, torch.from_numpy(X).cuda())
+        need = d.ctx.conversion_bytes()
+        if style == 2 and policy == 0:
+            assert need == 0
+        if need:
+            def bf16_meets_another_precision():
+                for I in range(MT):
+                    for J in range(NT):
+                        for L in range(KT):
+                            q = orc.product_precision(mA[I, L], mB[L, J], mC[I, J], policy)
+                            if any(p != q and BF16 in (p, q) for p in (mA[I, L], mB[L, J])):
+                                return True
+                return False
+            if bf16_meets_another_precision():
+                with pytest.raises(G.GemmMPError) as e:
+                    d.run(2.0, -1.0)
+                assert e.value.status == G.ESTATE, what
+            d.convert_tiles()
+        d.run(2.0, -1.0)
+        got = d.unpack_tiles("C").cpu().numpy()
+        assert np.array_equal(got, want.astype(np.float64)), what
+        torch.cuda.synchronize()
+
+
+def test_bf16_products_match_the_oracle_on_general_data():
+    """A and B all BF16 (no conversion anywhere: receiver-side run), C tiles of every kind: per
+    tile within 4*K*u_tile with u = 2^-8, and within the FP32-accumulation bound of the oracle,
+    whose BF16 products are exact FP32 multiplications of the stored operands."""
+    import torch
+    w = W.tiny()
+    w.mapA = np.full_like(w.mapA, BF16)
+    w.mapB = np.full_like(w.mapB, BF16)
+    rng = np.random.default_rng(57)
+    w.mapC = rng.integers(0, 5, w.mapC.shape).astype(np.uint16)
+    w.mapC[0, :] = (FP64, FP32, BF16, FP8)
+    w.alpha, w.beta = 1.0, 0.0
+    A, B, C0 = _dense(w)
+    side = OracleSide(w, A, B, None)
+    d, dev = gpu_problem(w, A, B, None)
+    _check_storage(d, side, "A", [(0, 0), (1, 2)])
+    _check_storage(d, side, "B", [(0, 0), (2, 1)])
+    assert d.ctx.get_stats()["products_bf16"] == w.MT * w.NT * w.KT
+    d.run(w.alpha, w.beta)
+    C_gpu = d.unpack_tiles("C").cpu().numpy()
+    torch.cuda.synchronize()
+    jobs = _all_jobs(w)
+    C_orc, _ = finish_low_c_tiles(side, side.gemm(jobs))
+    worst = compare_jobs(side, jobs, 0, w.alpha, w.beta, C_gpu, C_orc)
     _say("  worst error / bound:", worst)
 
 
