@@ -57,9 +57,27 @@ def test_morton_points_are_sorted_and_cluster_neighbours():
     assert np.all(np.diag(norms) > 5 * norms[0, 7])       # off-diagonal tiles decay
 
 
+def _paper_settings():
+    """The ratios and the tile size the paper states (tests/golden/paper_ratio_settings.txt)."""
+    import os
+    rows, tile = [], None
+    for line in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_ratio_settings.txt")):
+        f = line.split()
+        if not f or f[0].startswith("#"):
+            continue
+        if f[0] == "tile":
+            tile = int(f[1])
+        else:
+            rows.append(tuple(int(x) for x in f))
+    return rows, tile
+
+
 def test_paper_ratio_maps_have_the_exact_ratio_and_a_random_pattern():
     """The paper's aD:bS runs: a % of the tiles of A, B and C FP64, the rest FP32 (Section 5.1)."""
-    for pct in (100, 80, 50, 20, 0):
+    rows, tile = _paper_settings()
+    assert all(a + b == 100 for a, b, _ in rows) and [a for a, _, _ in rows] == [100, 80, 50, 20, 0]
+    assert W.paper_ratio(50).nb == tile and W.paper_ratio(50).M == 16 * tile
+    for pct, _, _ in rows:
         w = W.paper_ratio(pct, n=4096, nb=256)
         for m in (w.mapA, w.mapB, w.mapC):
             assert m.shape == (16, 16) and m.dtype == np.uint16
