@@ -184,10 +184,10 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *ctx, char which, const double *dense_dev, in
  * applied to the finished tile product.  alpha, beta are rounded to the accumulate type.
  * beta == 0: C is not read.  alpha == 0: no product is formed.
  * ESTATE unless A and B are packed, C's map and buffer are set, and (beta != 0) C is packed.
- * BF16 tiles: the kernels multiply BF16 data only as both operands of a BF16 product; where a
- * BF16 tile meets another precision in a product (a BF16 tile under an FP32 / FP64 product, an
- * FP8 tile under a BF16 product) the widened copy is taken from the sender-side workspace, and
- * the call is ESTATE until gemm_mp_convert_tiles has filled it. */
+ * BF16 tiles: the kernels take BF16 data only as an operand of a BF16 product (whose other
+ * operand is BF16, or FP8 converted on the way like under an FP16 product); a BF16 tile under
+ * an FP32 / FP64 product is read as the widened copy in the sender-side workspace, and the call
+ * is ESTATE until gemm_mp_convert_tiles has filled it. */
 int gemm_mp_run(gemm_mp_ctx *ctx, double alpha, double beta, gemm_mp_stream stream);
 
 /* Sender-side conversion (optional).  The paper converts at the receiver: a tile travels in its

@@ -58,6 +58,7 @@ struct gemm_mp_ctx {
     WorkItem *d_items = nullptr;      // the three lists, [0] first
     gemm_mp_stats stats;
     bool mixed32 = false;             // list [1] holds an FP16 / BF16 product with an operand stored in FP8
+    bool mixed64 = false;             // the same for list [0]
     bool has_bf16 = false;            // A or B has a BF16 tile
     bool bf16_needs_copies = false;   // ... that meets another precision in some product (see gemm_mp_run)
     bool kernel_ready = false;
@@ -260,9 +261,8 @@ void build_schedule(gemm_mp_ctx *c)
                 const int pa = A.map[I * KT + L], pb = B.map[L * NT + J];
                 if (pa != q) c->conv_off[0][((size_t)I * KT + L) * kConvSlots + q] = 0;
                 if (pb != q) c->conv_off[1][((size_t)L * NT + J) * kConvSlots + q] = 0;
-                // the GEMM kernels take BF16 data only as both operands of a BF16 product
-                c->bf16_needs_copies |= (pa != q && (pa == GEMM_MP_BF16 || q == GEMM_MP_BF16)) ||
-                                        (pb != q && (pb == GEMM_MP_BF16 || q == GEMM_MP_BF16));
+                // the GEMM kernels take BF16 data only as operands of a BF16 product
+                c->bf16_needs_copies |= (pa == GEMM_MP_BF16 && q != GEMM_MP_BF16) || (pb == GEMM_MP_BF16 && q != GEMM_MP_BF16);
             }
     c->conv_bytes = 0;
     c->conv_tiles = 0;
@@ -296,13 +296,18 @@ void build_schedule(gemm_mp_ctx *c)
                          B.map[L * NT + J] == GEMM_MP_FP8_E4M3;
                 all_fp8[(size_t)I * NT + J] = ok;
             }
-    c->mixed32 = false;
+    c->mixed32 = c->mixed64 = false;
     for (int I = 0; I < MT; ++I)
         for (int J = 0; J < NT; ++J) {
-            if (C.map[I * NT + J] == GEMM_MP_FP64 || all_fp8[(size_t)I * NT + J]) continue;
-            for (int L = 0; L < KT; ++L)
-                c->mixed32 |= (c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_FP16 || c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_BF16) &&
-                              (A.map[I * KT + L] == GEMM_MP_FP8_E4M3 || B.map[L * NT + J] == GEMM_MP_FP8_E4M3);
+            if (all_fp8[(size_t)I * NT + J]) continue;
+            bool mixed = false;
+            for (int L = 0; L < KT; ++L) {
+                const int q = c->q[((size_t)I * NT + J) * KT + L];
+                mixed |= (q == GEMM_MP_FP16 || q == GEMM_MP_BF16) &&
+                         (A.map[I * KT + L] == GEMM_MP_FP8_E4M3 || B.map[L * NT + J] == GEMM_MP_FP8_E4M3);
+            }
+            if (C.map[I * NT + J] == GEMM_MP_FP64) c->mixed64 |= mixed;
+            else c->mixed32 |= mixed;
         }
     constexpr int kBins = 8;
     for (int list = 0; list < 3; ++list) {
@@ -610,6 +615,7 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
     a.n_items32 = (int32_t)c->items[1].size();
     a.n_items8 = (int32_t)c->items[2].size();
     a.mixed32 = c->mixed32 ? 1 : 0;
+    a.mixed64 = c->mixed64 ? 1 : 0;
     a.bf16 = c->has_bf16 ? 1 : 0;
     a.nb = c->nb; a.MT = c->MT; a.NT = c->NT; a.KT = c->KT;
     a.kt_eff = alpha == 0.0 ? 0 : c->KT;

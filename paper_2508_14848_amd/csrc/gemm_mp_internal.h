@@ -92,6 +92,7 @@ struct GemmArgs {
     const WorkItem *items8;   // 256 x 256 regions of FP32 C tiles made of FP8 x FP8 products only
     int32_t n_items64, n_items32, n_items8;
     int32_t mixed32;         // some region of items32 has an FP16 / BF16 product with an operand stored in FP8
+    int32_t mixed64;         // the same for items64
     int32_t bf16;            // some tile of A or B is stored in BF16
     int32_t nb, MT, NT, KT;
     int32_t kt_eff;          // KT, or 0 when alpha == 0

@@ -19,13 +19,13 @@
 //   a C region.
 //   FP16 / FP8 products whose operands need no conversion skip the registers:
 //   global -> LDS by buffer-load-to-LDS into a ring of five unpadded, swizzled stages.
-//   FP16 products with an operand stored in FP8: in the MIXED instance (FP32 C tiles, launched
-//   when such products exist) the FP8 operand takes the ring as it is and is converted between
-//   the fragment read and the MFMA; elsewhere a two-stage loop with conversion in registers on
+//   FP16 products with an operand stored in FP8: in the MIXED instances (launched when such
+//   products exist) the FP8 operand takes the ring as it is and is converted between the
+//   fragment read and the MFMA; in the others a two-stage loop with conversion in registers on
 //   the way to LDS, rows padded by 8 B.
 //   BF16 products (BF instances, launched when A or B has BF16 tiles): the FP16 ring with the
-//   BF16 matrix instruction; both operands are BF16 data (a tile stored otherwise comes as a
-//   BF16 copy from the sender-side workspace), marked by a flag in the product's table record.
+//   BF16 matrix instruction and, for an FP8 operand, the BF16 form of the conversion; marked by
+//   a flag in the product's table record.
 //
 // Fragment convention.  Packed A tiles are row-major and packed B tiles are stored transposed,
 // so both operands have the reduction index contiguous.  Which reduction index a lane's bytes
@@ -46,6 +46,7 @@ typedef double d4 __attribute__((ext_vector_type(4)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2v __attribute__((ext_vector_type(2)));
 typedef int i8v __attribute__((ext_vector_type(8)));
 typedef float f2v __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vectors: these stay in registers
@@ -961,17 +962,25 @@ __device__ __forceinline__ u32x4 lo_read_narrow(const char *stage, const MixGeom
     return *(const u32x4 *)(stage + (MIX == 1 ? MG.ma : MG.mb) + (t >> 1) * 4096 + (t & 1) * 1024);
 }
 // Conversion i = 0..31 of a chunk: two FP8 bytes of row block i / 8 become one register of FP16 pairs.
-template <int MIX>
+// BFQ: a BF16 product, the FP8 bytes become BF16 pairs (as exact: every e4m3 number is a BF16 number).
+template <int MIX, bool BFQ>
 __device__ __forceinline__ void lo_convert_one(u32x4 (&f)[16], const u32x4 (&raw)[4], int i)
 {
     const int t = i >> 3, kk = (i >> 2) & 1, word = (i >> 1) & 1, sel = i & 1;
     const int w = (int)raw[t][2 * kk + word];
-    const h2v h = sel ? __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, true) : __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, false);
-    f[((MIX == 1 ? 0 : 4) + t) * 2 + kk][2 * word + sel] = __builtin_bit_cast(uint32_t, h);
+    uint32_t r;
+    if constexpr (BFQ) {
+        const bf2v h = sel ? __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true) : __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
+        r = __builtin_bit_cast(uint32_t, h);
+    } else {
+        const h2v h = sel ? __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, true) : __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, false);
+        r = __builtin_bit_cast(uint32_t, h);
+    }
+    f[((MIX == 1 ? 0 : 4) + t) * 2 + kk][2 * word + sel] = r;
 }
 // All fragments of the chunk in `stage`, outside the chunk stream (first chunk of a run, and
 // where the product that follows keeps its operands differently from the one that ends).
-__device__ __forceinline__ void lo_read_all(u32x4 (&f)[16], const char *stage, const LoGeom &LG, const MixGeom &MG, int mix)
+__device__ __forceinline__ void lo_read_all(u32x4 (&f)[16], const char *stage, const LoGeom &LG, const MixGeom &MG, int mix, bool bf)
 {
     if (mix == 0) {
 #pragma unroll
@@ -982,16 +991,26 @@ __device__ __forceinline__ void lo_read_all(u32x4 (&f)[16], const char *stage, c
         for (int t = 0; t < 4; ++t) raw[t] = lo_read_narrow<1>(stage, MG, t);
 #pragma unroll
         for (int r = 0; r < 8; ++r) lo_read_one(f, stage, LG, r);
+        if (bf) {
 #pragma unroll
-        for (int i = 0; i < 32; ++i) lo_convert_one<1>(f, raw, i);
+            for (int i = 0; i < 32; ++i) lo_convert_one<1, true>(f, raw, i);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 32; ++i) lo_convert_one<1, false>(f, raw, i);
+        }
     } else {
         u32x4 raw[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) raw[t] = lo_read_narrow<2>(stage, MG, t);
 #pragma unroll
         for (int r = 8; r < 16; ++r) lo_read_one(f, stage, LG, r);
+        if (bf) {
 #pragma unroll
-        for (int i = 0; i < 32; ++i) lo_convert_one<2>(f, raw, i);
+            for (int i = 0; i < 32; ++i) lo_convert_one<2, true>(f, raw, i);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 32; ++i) lo_convert_one<2, false>(f, raw, i);
+        }
     }
 }
 
@@ -1059,8 +1078,8 @@ __device__ __forceinline__ void lo_chunk(f4 (&acc)[4][4], u32x4 (&fr)[2][16], co
             if (m < 4) raw[m] = lo_read_narrow<MIX>(next, MG, m);
             else if (m < 12) lo_read_one(fr[PAR ^ 1], next, LG, (MIX == 1 ? 0 : 8) + m - 4);
             if (m >= 8 && m < 24) {
-                lo_convert_one<MIX>(fr[PAR ^ 1], raw, 2 * (m - 8));
-                lo_convert_one<MIX>(fr[PAR ^ 1], raw, 2 * (m - 8) + 1);
+                lo_convert_one<MIX, BFQ>(fr[PAR ^ 1], raw, 2 * (m - 8));
+                lo_convert_one<MIX, BFQ>(fr[PAR ^ 1], raw, 2 * (m - 8) + 1);
             }
             if (m >= 16 && m < 24) lo_dma_one<MIXED>(pr, soff0, rows8_bytes, dst, m - 16);
         } else if constexpr (Q == Q16) {
@@ -1173,7 +1192,7 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
     int cmix = MIXED ? ring_mix(cur.q, cur.a.p, cur.b.p) : 0;
     bool cbf = false;              // the product being computed is a BF16 one (flag in its table record)
     if constexpr (BF) cbf = ((((ConstQuad)(uintptr_t)(R.prod + L))[1].z >> 26) & 1u) != 0;
-    if constexpr (MIXED) lo_read_all(fr[0], lds, LG, MG, cmix);
+    if constexpr (MIXED) lo_read_all(fr[0], lds, LG, MG, cmix, BF && cbf);
     else {
 #pragma unroll
         for (int slot = 0; slot < 4; ++slot) lo_read_slot(fr[0], lds, LG, slot);
@@ -1211,36 +1230,23 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
         const int nesum = (int)nrec.x + (int)nrec.y;
         const int nmix = MIXED ? ring_mix(nq, (int)(nrec.z & 0xffu), (int)((nrec.z >> 8) & 0xffu)) : 0;
         const bool nbf = BF && ((nrec.z >> 26) & 1u) != 0;
-        if (BF && cq == Q16 && cbf) {              // a BF16 product: both operands BF16 (copies where they were not)
-            GMP_LO_STEP_AS(Q16, 0, true, 0, true);
-            GMP_LO_STEP_AS(Q16, 1, false, 0, true);
-            for (int cc = 2; cc < cn; cc += 2) {
-                GMP_LO_STEP_AS(Q16, 0, false, 0, true);
-                GMP_LO_STEP_AS(Q16, 1, false, 0, true);
-            }
+#define GMP_LO_PRODUCT16(MIX, BFQ)                          \
+    do {                                                   \
+        GMP_LO_STEP_AS(Q16, 0, true, MIX, BFQ);            \
+        GMP_LO_STEP_AS(Q16, 1, false, MIX, BFQ);           \
+        for (int cc = 2; cc < cn; cc += 2) {               \
+            GMP_LO_STEP_AS(Q16, 0, false, MIX, BFQ);       \
+            GMP_LO_STEP_AS(Q16, 1, false, MIX, BFQ);       \
+        }                                                  \
+    } while (0)
+        if (BF && cq == Q16 && cbf) {              // a BF16 product: the BF16 matrix instruction
+            if (!MIXED || cmix == 0) GMP_LO_PRODUCT16(0, true);
+            else if (MIXED && cmix == 1) GMP_LO_PRODUCT16(1, true);
+            else if (MIXED) GMP_LO_PRODUCT16(2, true);
         } else if (cq == Q16) {                    // 64 elements per chunk: always an even count
-            if (!MIXED || cmix == 0) {
-                GMP_LO_STEP(Q16, 0, true, 0);
-                GMP_LO_STEP(Q16, 1, false, 0);
-                for (int cc = 2; cc < cn; cc += 2) {
-                    GMP_LO_STEP(Q16, 0, false, 0);
-                    GMP_LO_STEP(Q16, 1, false, 0);
-                }
-            } else if (MIXED && cmix == 1) {
-                GMP_LO_STEP(Q16, 0, true, 1);
-                GMP_LO_STEP(Q16, 1, false, 1);
-                for (int cc = 2; cc < cn; cc += 2) {
-                    GMP_LO_STEP(Q16, 0, false, 1);
-                    GMP_LO_STEP(Q16, 1, false, 1);
-                }
-            } else if (MIXED) {
-                GMP_LO_STEP(Q16, 0, true, 2);
-                GMP_LO_STEP(Q16, 1, false, 2);
-                for (int cc = 2; cc < cn; cc += 2) {
-                    GMP_LO_STEP(Q16, 0, false, 2);
-                    GMP_LO_STEP(Q16, 1, false, 2);
-                }
-            }
+            if (!MIXED || cmix == 0) GMP_LO_PRODUCT16(0, false);
+            else if (MIXED && cmix == 1) GMP_LO_PRODUCT16(1, false);
+            else if (MIXED) GMP_LO_PRODUCT16(2, false);
         } else {
             GMP_LO_STEP(Q8, 0, true, 0);
             if (cn > 1) {
@@ -1262,14 +1268,15 @@ __device__ __forceinline__ void lo_run(AccS (&s)[4][4], Product &cur, int &L, co
         // keeps its operands; where the next one keeps them differently they are read again (that
         // chunk is complete in its stage since the barrier that ended the step).
         if constexpr (MIXED)
-            if (nmix != cmix && done < staged)
-                lo_read_all(fr[0], lds + (st_next == 0 ? kLoLdsBytes - kLoStage : st_next - kLoStage), LG, MG, nmix);
+            if ((nmix != cmix || (BF && nmix != 0 && nbf != cbf)) && done < staged)
+                lo_read_all(fr[0], lds + (st_next == 0 ? kLoLdsBytes - kLoStage : st_next - kLoStage), LG, MG, nmix, BF && nbf);
         ++cL;
         cq = nq;
         cmix = nmix;
         cbf = nbf;
         cesum = nesum;
     }
+#undef GMP_LO_PRODUCT16
 #undef GMP_LO_STEP
 #undef GMP_LO_STEP_AS
 #undef GMP_LO_REQ_ARGS
@@ -1831,9 +1838,9 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 
 hipError_t gemm_kernel_setup()
 {
-    const void *owners[5] = {(const void *)gemm_mp_owner_kernel<double, false, false>, (const void *)gemm_mp_owner_kernel<float, false, false>,
-                             (const void *)gemm_mp_owner_kernel<float, true, false>, (const void *)gemm_mp_owner_kernel<double, false, true>,
-                             (const void *)gemm_mp_owner_kernel<float, false, true>};
+    const void *owners[6] = {(const void *)gemm_mp_owner_kernel<double, false, false>, (const void *)gemm_mp_owner_kernel<double, true, false>,
+                             (const void *)gemm_mp_owner_kernel<float, false, false>, (const void *)gemm_mp_owner_kernel<float, true, false>,
+                             (const void *)gemm_mp_owner_kernel<double, true, true>, (const void *)gemm_mp_owner_kernel<float, true, true>};
     for (const void *k : owners) {
         const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
@@ -1946,13 +1953,15 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     const int64_t tasks = (int64_t)a.MT * a.NT * a.KT;
     product_table_kernel<<<dim3((unsigned)((tasks + 255) / 256)), dim3(256), 0, s>>>(a.A, a.B, a.q, a.MT, a.NT, a.KT, a.convA, a.convB, a.prod);
     if (a.n_items64 > 0) {
-        // BF16 tiles among the operands: the instances that know the BF16 matrix instruction
-        if (a.bf16) gemm_mp_owner_kernel<double, false, true><<<dim3((unsigned)a.n_items64), dim3(kThreads), kLdsBytes, s>>>(a, a.items64);
+        // BF16 tiles among the operands: the instances that know the BF16 matrix instruction; FP16 /
+        // BF16 products with an FP8 operand: the instances whose DMA ring takes them
+        if (a.bf16) gemm_mp_owner_kernel<double, true, true><<<dim3((unsigned)a.n_items64), dim3(kThreads), kLdsBytes, s>>>(a, a.items64);
+        else if (a.mixed64) gemm_mp_owner_kernel<double, true, false><<<dim3((unsigned)a.n_items64), dim3(kThreads), kLdsBytes, s>>>(a, a.items64);
         else gemm_mp_owner_kernel<double, false, false><<<dim3((unsigned)a.n_items64), dim3(kThreads), kLdsBytes, s>>>(a, a.items64);
     }
     if (a.n_items32 > 0) {
         // the instance whose DMA ring also takes FP16 products with an FP8 operand only where such products exist
-        if (a.bf16) gemm_mp_owner_kernel<float, false, true><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
+        if (a.bf16) gemm_mp_owner_kernel<float, true, true><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
         else if (a.mixed32) gemm_mp_owner_kernel<float, true, false><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
         else gemm_mp_owner_kernel<float, false, false><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
     }

@@ -627,10 +627,11 @@ def test_bf16_tiles_pack_bit_for_bit_and_the_rule_ranks_them_between_fp16_and_fp
 
 def test_bf16_tiles_small_integer_problems_are_exact():
     """Maps over all five formats on A and B, C tiles FP64 / FP32 / BF16 / FP16 / FP8, both policies.
-    BF16 tiles that meet another precision in a product need the sender-side copies (the call
-    order error says so); with them every result must be the exact integer matrix: BF16
-    products on the BF16 matrix instruction, BF16 tiles widened to FP32 / FP64 copies, FP8 tiles
-    widened to BF16 copies, a BF16 C tile rounded from its FP32 staging copy."""
+    BF16 tiles under an FP32 / FP64 product need the sender-side copies (the call order error says
+    so); every result must be the exact integer matrix: BF16 products on the BF16 matrix
+    instruction, with an FP8 operand converted in the ring (receiver side) or taken as a BF16 copy
+    (sender side), BF16 tiles widened to FP32 / FP64 copies, a BF16 C tile rounded from its FP32
+    staging copy."""
     import torch
     from paper_2508_14848_amd import gemm_mp as G
     from paper_2508_14848_amd.device import DeviceGemmMP
@@ -673,14 +674,19 @@ def test_bf16_tiles_small_integer_problems_are_exact():
                     for J in range(NT):
                         for L in range(KT):
                             q = orc.product_precision(mA[I, L], mB[L, J], mC[I, J], policy)
-                            if any(p != q and BF16 in (p, q) for p in (mA[I, L], mB[L, J])):
+                            if any(p == BF16 and q != BF16 for p in (mA[I, L], mB[L, J])):
                                 return True
                 return False
             if bf16_meets_another_precision():
                 with pytest.raises(G.GemmMPError) as e:
                     d.run(2.0, -1.0)
                 assert e.value.status == G.ESTATE, what
-            d.convert_tiles()
+                d.convert_tiles()
+            else:                                        # nothing forces the copies: both strategies must agree
+                d.run(2.0, -1.0)
+                assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), want.astype(np.float64)), what
+                d.pack_tiles("C", torch.from_numpy(C0).cuda())
+                d.convert_tiles()
         d.run(2.0, -1.0)
         got = d.unpack_tiles("C").cpu().numpy()
         assert np.array_equal(got, want.astype(np.float64)), what
