@@ -182,7 +182,7 @@ __device__ __forceinline__ u32x4 convert(const Raw &r, int p, int e, int sub)
 }
 
 struct Geometry {
-    bool ring;                      // pure FP16 / FP8 products go through the DMA ring (set for both kernel instances)
+    bool ring;                      // pure FP16 / FP8 products go through the DMA ring (set in every kernel instance)
     int tid, lane, li, g, wm, wn;
     int seg_row, seg_part;          // staging: this thread's first row and its 16-byte part
     int wbase;                      // byte offset of that segment in a padded LDS operand stage
