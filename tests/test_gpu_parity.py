@@ -693,6 +693,60 @@ def test_bf16_tiles_small_integer_problems_are_exact():
         torch.cuda.synchronize()
 
 
+def test_random_small_integer_problems_over_all_five_formats_are_exact():
+    """A hundred seeded problems with every format on A, B and C (FP16 / FP8 / BF16 C tiles
+    included), sizes on and off the tile grid, operands given directly or transposed, both
+    policies, copies made on the sender side where a BF16 tile needs them or at random.  One
+    nonzero per row of A and per column of B inside each reduction tile keeps every result an
+    integer of magnitude at most 15, which every format holds, so C must be exact."""
+    import torch
+    from paper_2508_14848_amd import gemm_mp as G
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(20250815)
+    for case in range(100):
+        nb = int(rng.choice([128, 256, 384]))
+        MT, NT, KT = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        Mf, Nf, Kf = MT * nb, NT * nb, KT * nb
+        A = np.zeros((Mf, Kf))
+        B = np.zeros((Kf, Nf))
+        cols = rng.integers(0, nb, (Mf, KT)) + nb * np.arange(KT)
+        A[np.arange(Mf)[:, None], cols] = rng.integers(-2, 3, (Mf, KT))
+        rows = rng.integers(0, nb, (KT, Nf)) + nb * np.arange(KT)[:, None]
+        B[rows, np.arange(Nf)[None, :]] = rng.integers(-1, 2, (KT, Nf))
+        ragged = rng.random() < 0.3
+        M = Mf - (int(rng.integers(1, nb)) if ragged else 0)
+        N = Nf - (int(rng.integers(1, nb)) if ragged else 0)
+        K = Kf - (int(rng.integers(1, nb)) if ragged else 0)
+        A, B = np.ascontiguousarray(A[:M, :K]), np.ascontiguousarray(B[:K, :N])
+        C0 = rng.integers(-3, 4, (M, N)).astype(np.float64)
+        mA, mB, mC = rng.integers(0, 5, (MT, KT)), rng.integers(0, 5, (KT, NT)), rng.integers(0, 5, (MT, NT))
+        policy, tA, tB = int(rng.integers(0, 2)), int(rng.integers(0, 2)), int(rng.integers(0, 2))
+        alpha, beta = float(rng.choice([-2, -1, 1, 2])), float(rng.choice([-1, 0, 1]))
+        what = dict(case=case, nb=nb, M=M, N=N, K=K, policy=policy, tA=tA, tB=tB, alpha=alpha, beta=beta)
+        if case % 20 == 0:
+            _say("five formats, random integers", what)
+        want = alpha * (A @ B) + beta * C0
+        assert np.abs(want).max() <= 15
+        d = DeviceGemmMP(M, N, K, nb, policy=policy)
+        d.set_transposed("A", tA)
+        d.set_transposed("B", tB)
+        for which, m, X, t in (("A", mA, A, tA), ("B", mB, B, tB), ("C", mC, C0, 0)):
+            d.set_precision_map(which, m.astype(np.uint16))
+            d.pack_tiles(which, _even_ld(np.ascontiguousarray(X.T) if t else X))
+        sender = rng.random() < 0.3
+        try:
+            if sender and d.ctx.conversion_bytes():
+                d.convert_tiles()
+            d.run(alpha, beta)
+        except G.GemmMPError as e:                     # a BF16 tile under an FP32 / FP64 product
+            assert e.status == G.ESTATE and BF16 in set(mA.ravel()) | set(mB.ravel()), what
+            d.convert_tiles()
+            d.run(alpha, beta)
+        got = d.unpack_tiles("C").cpu().numpy()
+        assert np.array_equal(got, want), what
+    torch.cuda.synchronize()
+
+
 def test_bf16_products_match_the_oracle_on_general_data():
     """A and B all BF16 (no conversion anywhere: receiver-side run), C tiles of every kind: per
     tile within 4*K*u_tile with u = 2^-8, and within the FP32-accumulation bound of the oracle,
