@@ -44,8 +44,11 @@
  * in Section 5.2; 2 and 3 extend it to FP16 and FP8 (OCP e4m3, "fn" variant:
  * no infinities, one NaN code per sign, max finite 448), 4 to BF16 (8 exponent
  * bits as FP32, 7 fraction bits).  The code is a name, not a rank: by unit
- * roundoff the formats order FP64 < FP32 < FP16 < BF16 < FP8. */
-enum { P_FP64 = 0, P_FP32 = 1, P_FP16 = 2, P_FP8 = 3, P_BF16 = 4 };
+ * roundoff the formats order FP64 < FP32 < FP16 < BF16 < FP8.  5 is MXFP8: e4m3
+ * elements with one power-of-two scale per block of 32 consecutive reduction
+ * indices (the block-scaled format of the OCP microscaling specification)
+ * instead of one per tile. */
+enum { P_FP64 = 0, P_FP32 = 1, P_FP16 = 2, P_FP8 = 3, P_BF16 = 4, P_MXFP8 = 5 };
 
 /* Which product-precision reading is applied (see orc_product_precision). */
 enum { POLICY_OPERAND = 0, POLICY_C_TILE = 1 };
@@ -171,7 +174,35 @@ double orc_fp8_value(uint8_t b)
     return s ? -v : v;
 }
 
+/* MXFP8: one block of 32 numbers.  Reading (the paper names further formats
+ * only as future work, Section 6; the format is the OCP microscaling one):
+ * shared scale 2^s with s = floor(log2 max|x|) - 8 (8 = exponent of the
+ * largest e4m3 binade), kept within the E8M0 range [-127, 127]; s = 0 for an
+ * all-zero block or a non-finite maximum; elements = x * 2^-s rounded once to
+ * e4m3, saturating.  y receives the element numbers, the return value is s. */
+int32_t orc_mx_block(const double *x, int64_t stride, double *y, int64_t ystride)
+{
+    double mx = 0.0;
+    for (int k = 0; k < 32; ++k) { double a = fabs(x[k * stride]); if (a > mx) mx = a; }   /* NaN never enters */
+    int s = 0;
+    if (mx != 0.0 && !isinf(mx)) {
+        s = ilogb(mx) - 8;
+        if (s < -127) s = -127;
+        if (s > 127) s = 127;
+    }
+    for (int k = 0; k < 32; ++k) y[k * ystride] = orc_round_fp8(ldexp(x[k * stride], -s));
+    return s;
+}
+
 /* Vector forms for the tests. */
+void orc_mx_blocks_array(const double *x, int64_t nblocks, double *y, uint8_t *codes, uint8_t *scale_codes)
+{
+    for (int64_t b = 0; b < nblocks; ++b) {
+        int32_t s = orc_mx_block(x + 32 * b, 1, y + 32 * b, 1);
+        scale_codes[b] = (uint8_t)(s + 127);
+        for (int k = 0; k < 32; ++k) codes[32 * b + k] = orc_fp8_bits(y[32 * b + k]);
+    }
+}
 void orc_round_fp16_array(const double *x, int64_t n, double *y, uint16_t *bits)
 {
     for (int64_t i = 0; i < n; ++i) {
@@ -249,6 +280,7 @@ static double unit_roundoff(int p)
     case P_FP32: return ldexp(1.0, -24);
     case P_FP16: return ldexp(1.0, -11);
     case P_BF16: return ldexp(1.0, -8);
+    case P_MXFP8: return ldexp(1.0, -4);
     default:     return ldexp(1.0, -4);      /* e4m3: 3 fraction bits */
     }
 }
@@ -307,10 +339,14 @@ int32_t orc_scale_exponent(double maxabs, int32_t p)
  * FP64: copy.  FP32: C cast (round to nearest even, IEEE overflow / gradual
  * underflow).  FP16 / FP8: one direct rounding of x * 2^-e from FP64.
  * X and Y may be the same array. */
+static int g_mx_axis = 0;   /* blocks of MXFP8 tiles run along a row (0: A, C) or down a column (1: B) */
+void orc_set_mx_axis(int32_t axis) { g_mx_axis = axis; }
+
 void orc_store_tiles(const double *X, int64_t ld, int64_t rows, int64_t cols, int32_t nb,
                      const uint16_t *map, const double *maxabs, double *Y, int64_t ldy,
                      int32_t *exps)
 {
+    const int mx_axis = g_mx_axis;
     int64_t RT = rows / nb, CT = cols / nb;
 #pragma omp parallel for collapse(2) schedule(dynamic)
     for (int64_t I = 0; I < RT; ++I)
@@ -318,6 +354,21 @@ void orc_store_tiles(const double *X, int64_t ld, int64_t rows, int64_t cols, in
             int p = map[I * CT + J];
             int32_t e = orc_scale_exponent(maxabs[I * CT + J], p);
             exps[I * CT + J] = e;
+            if (p == P_MXFP8) {
+                /* the blocks run along the reduction index; Y receives the values the stored
+                 * elements stand for, element * 2^s, which are exact in FP64 (and in FP32) */
+                double yb[32];
+                for (int32_t u = 0; u < nb; ++u)
+                    for (int32_t k0 = 0; k0 < nb; k0 += 32) {
+                        const double *x0 = mx_axis ? X + (I * nb + k0) * ld + J * nb + u : X + (I * nb + u) * ld + J * nb + k0;
+                        int32_t s = orc_mx_block(x0, mx_axis ? ld : 1, yb, 1);
+                        for (int k = 0; k < 32; ++k) {
+                            double *y0 = mx_axis ? Y + (I * nb + k0 + k) * ldy + J * nb + u : Y + (I * nb + u) * ldy + J * nb + k0 + k;
+                            *y0 = ldexp(yb[k], s);
+                        }
+                    }
+                continue;
+            }
             for (int32_t r = 0; r < nb; ++r)
                 for (int32_t c = 0; c < nb; ++c) {
                     double x = X[(I * nb + r) * ld + J * nb + c];
@@ -346,6 +397,9 @@ void orc_store_tiles(const double *X, int64_t ld, int64_t rows, int64_t cols, in
  * and FP32 for the pair FP16, BF16. */
 static int holds_both(int pA, int pB)
 {
+    if (pA == P_MXFP8 && pB == P_MXFP8) return P_MXFP8;
+    if (pA == P_MXFP8) pA = P_FP32;        /* block-scaled e4m3 numbers are FP32 numbers, and of no */
+    if (pB == P_MXFP8) pB = P_FP32;        /* smaller format here                                  */
     if (pA == P_FP64 || pB == P_FP64) return P_FP64;
     if (pA == P_FP32 || pB == P_FP32) return P_FP32;
     int h = (pA == P_FP16) || (pB == P_FP16), b = (pA == P_BF16) || (pB == P_BF16);
@@ -426,7 +480,7 @@ int32_t orc_gemm_jobs(int64_t M, int64_t N, int64_t K, int32_t nb,
             c1 > nb || c0 > c1)
             return -1;
         int pC = mapC[I * NT + J];
-        if (pC < P_FP64 || pC > P_BF16) return -1;
+        if (pC < P_FP64 || pC > P_BF16) return -1;      /* no MXFP8 C tiles */
         int T = pC == P_FP64 ? P_FP64 : P_FP32;       /* accumulate type: FP64 or FP32 */
         int64_t nr = r1 - r0, nc = c1 - c0;
         if (nr == 0 || nc == 0) continue;
@@ -447,7 +501,9 @@ int32_t orc_gemm_jobs(int64_t M, int64_t N, int64_t K, int32_t nb,
             int pA = mapA[I * KT + L], pB = mapB[L * NT + J];
             int q = orc_product_precision(pA, pB, pC, policy);
             int ea = eA[I * KT + L], eb = eB[L * NT + J];
-            int esum = (q == P_FP16 || q == P_FP8 || q == P_BF16) ? ea + eb : 0;
+            /* an MXFP8 product multiplies the values its operands stand for (Ay, By hold them,
+             * exponents 0) exactly and accumulates in FP32, like the other low products */
+            int esum = (q == P_FP16 || q == P_FP8 || q == P_BF16 || q == P_MXFP8) ? ea + eb : 0;
 
             /* receiver-side conversion of the B tile columns this job needs */
 #pragma omp parallel for schedule(static)

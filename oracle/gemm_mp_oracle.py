@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gemm_mp_oracle.c")
 _LIB = os.path.join(_HERE, "libgemm_mp_oracle.so")
 
-FP64, FP32, FP16, FP8, BF16 = 0, 1, 2, 3, 4
+FP64, FP32, FP16, FP8, BF16, MXFP8 = 0, 1, 2, 3, 4, 5
 POLICY_OPERAND, POLICY_C_TILE = 0, 1
 ALL_PRECISIONS_MASK = 0xF          # the four formats of the configurations
 ALL_FORMATS_MASK = 0x1F            # ... and BF16
@@ -43,6 +43,8 @@ def lib():
         _lib.orc_round_fp16_array.argtypes = [P, c_i64, P, P]
         _lib.orc_round_fp8_array.argtypes = [P, c_i64, P, P]
         _lib.orc_round_bf16_array.argtypes = [P, c_i64, P, P]
+        _lib.orc_mx_blocks_array.argtypes = [P, c_i64, P, P, P]
+        _lib.orc_set_mx_axis.argtypes = [c_i32]
         _lib.orc_bf16_value.restype = c_dbl
         _lib.orc_bf16_value.argtypes = [ctypes.c_uint16]
         _lib.orc_fp16_value.restype = c_dbl
@@ -96,6 +98,18 @@ def round_fp8(x):
     bits = np.empty(x.shape, dtype=np.uint8)
     lib().orc_round_fp8_array(_p(x), x.size, _p(y), _p(bits))
     return y, bits
+
+
+def mx_blocks(x):
+    """MXFP8 quantisation of consecutive blocks of 32 numbers (x.size a multiple of 32).
+    Returns (element numbers as FP64, element codes, scale codes = s + 127)."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    assert x.size % 32 == 0
+    y = np.empty_like(x)
+    codes = np.empty(x.shape, dtype=np.uint8)
+    scales = np.empty(x.size // 32, dtype=np.uint8)
+    lib().orc_mx_blocks_array(_p(x), x.size // 32, _p(y), _p(codes), _p(scales))
+    return y, codes, scales
 
 
 def round_bf16(x):
@@ -152,8 +166,10 @@ def scale_exponent(maxabs, p):
     return int(lib().orc_scale_exponent(float(maxabs), int(p)))
 
 
-def store_tiles(X, nb, pmap, maxabs=None, out=None):
-    """Storage rounding of every tile.  Returns (Y stored numbers as FP64, exps int32 per tile)."""
+def store_tiles(X, nb, pmap, maxabs=None, out=None, mx_axis=0):
+    """Storage rounding of every tile.  Returns (Y stored numbers as FP64, exps int32 per tile).
+    mx_axis: the blocks of MXFP8 tiles run along the rows (0: A) or down the columns (1: B), i.e.
+    along the reduction index; such tiles come back as the values they stand for, exponent 0."""
     X = _dense(X)
     rows, cols = X.shape
     pmap = np.ascontiguousarray(pmap, dtype=np.uint16)
@@ -163,6 +179,7 @@ def store_tiles(X, nb, pmap, maxabs=None, out=None):
     maxabs = np.ascontiguousarray(maxabs, dtype=np.float64)
     Y = np.empty_like(X) if out is None else _dense(out)
     exps = np.empty(pmap.shape, dtype=np.int32)
+    lib().orc_set_mx_axis(int(mx_axis))
     lib().orc_store_tiles(_p(X), X.strides[0] // 8, rows, cols, nb, _p(pmap), _p(maxabs),
                           _p(Y), Y.strides[0] // 8, _p(exps))
     return Y, exps

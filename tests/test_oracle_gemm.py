@@ -11,7 +11,7 @@ import pytest
 from oracle import gemm_mp_oracle as orc
 from tests.exact import fma32, fma64
 
-FP64, FP32, FP16, FP8, BF16 = 0, 1, 2, 3, 4
+FP64, FP32, FP16, FP8, BF16, MXFP8 = 0, 1, 2, 3, 4, 5
 U = {FP64: 2.0 ** -53, FP32: 2.0 ** -24, FP16: 2.0 ** -11, FP8: 2.0 ** -4, BF16: 2.0 ** -8}
 
 
@@ -457,3 +457,41 @@ def test_bf16_tiles_small_integers_are_exact_and_general_data_within_bound():
     bound = 2 * K * 2.0 ** -24 * (np.abs(Ab) @ np.abs(Bb)) + 2.0 ** -8 * 1e-3 * (np.abs(Ab) @ np.abs(Bb))
     assert np.all(np.abs(got - ref) <= bound)
     assert np.abs(got - A @ B).max() > 0                              # and it did round the operands
+
+
+def test_mxfp8_tiles_follow_the_reduction_index_and_give_exact_integer_products():
+    """MXFP8 tiles: the blocks of 32 run along the reduction index (rows of A, columns of B), so
+    storing B with blocks down its columns equals storing its transpose with blocks along rows;
+    MXFP8 with MXFP8 is an MXFP8 product, with anything else FP32 (FP64 if the other is FP64 and C
+    allows); small integers come through exactly whatever the maps."""
+    rng = np.random.default_rng(43)
+    nb, MT, NT, KT = 32, 2, 2, 3
+    M, N, K = MT * nb, NT * nb, KT * nb
+    X = rng.standard_normal((K, N)) * np.exp(rng.uniform(-5, 5, (K, N)))
+    mx = np.full((KT, NT), MXFP8, dtype=np.uint16)
+    Yb, eb = orc.store_tiles(X, nb, mx, mx_axis=1)
+    Yt, et = orc.store_tiles(np.ascontiguousarray(X.T), nb, np.ascontiguousarray(mx.T), mx_axis=0)
+    assert np.array_equal(Yb, Yt.T) and not eb.any()
+    Ya, _ = orc.store_tiles(X, nb, mx, mx_axis=0)
+    assert not np.array_equal(Ya, Yb)                     # the orientation matters
+    rel = np.abs(Yb - X) / np.abs(X)
+    assert rel[np.abs(X) > np.abs(X).max() * 2.0 ** -60].max() <= 1.0 and np.median(rel) < 2.0 ** -4
+    for pA, pB, pC, want in ((MXFP8, MXFP8, FP32, MXFP8), (MXFP8, MXFP8, FP64, MXFP8), (MXFP8, FP8, FP32, FP32), (MXFP8, FP16, FP64, FP32),
+                             (FP64, MXFP8, FP64, FP64), (FP64, MXFP8, FP32, FP32), (BF16, MXFP8, FP32, FP32)):
+        assert orc.product_precision(pA, pB, pC, orc.POLICY_OPERAND) == want
+    for trial in range(4):
+        A = rng.integers(-3, 4, (M, K)).astype(np.float64)
+        B = rng.integers(-3, 4, (K, N)).astype(np.float64)
+        C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
+        mA = rng.choice([FP64, FP32, FP16, FP8, BF16, MXFP8], (MT, KT)).astype(np.uint16)
+        mB = rng.choice([FP64, FP32, FP16, FP8, BF16, MXFP8], (KT, NT)).astype(np.uint16)
+        if trial == 0:
+            mA[:], mB[:] = MXFP8, MXFP8
+        mC = rng.integers(0, 2, (MT, NT)).astype(np.uint16)
+        Ay, eA = orc.store_tiles(A, nb, mA, mx_axis=0)
+        By, eB = orc.store_tiles(B, nb, mB, mx_axis=1)
+        Cy, _ = orc.store_tiles(C0, nb, mC)
+        jobs = orc.whole_tile_jobs(nb, [(i, j) for i in range(MT) for j in range(NT)])
+        got = orc.gemm_jobs(nb, Ay, mA, eA, By, mB, eB, Cy, mC, 2.0, -1.0, jobs)
+        want = 2 * (A.astype(np.int64) @ B.astype(np.int64)) - C0.astype(np.int64)
+        assert np.array_equal(got, want.astype(np.float64))

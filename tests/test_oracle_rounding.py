@@ -156,3 +156,32 @@ def test_bf16_matches_nearest_search_over_all_codes_and_torch():
     y, bits = orc.round_bf16(np.array([np.inf, -np.inf, np.nan, 3.4e38, -3.4e38, 3.39e38]))
     assert list(bits[:2]) == [0x7F80, 0xFF80] and np.isnan(y[2])
     assert y[3] == np.inf and y[4] == -np.inf and np.isfinite(y[5])
+
+
+def test_mxfp8_blocks_scale_window_nearest_elements_and_exactness():
+    """MXFP8 (block of 32, one power-of-two scale): the scale is floor(log2 max) - 8, so the largest
+    scaled magnitude lies in [2^8, 2^9) (and saturates at 448 above it); every element is the
+    e4m3 number nearest to x * 2^-s (brute force over the code table); blocks of integers up to
+    15 in magnitude come back exactly; zero blocks have scale code 127."""
+    table = e4m3_table()
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((200, 32)) * np.exp(rng.uniform(-60, 60, (200, 1))) * np.exp(rng.uniform(-6, 0, (200, 32)))
+    y, codes, scales = orc.mx_blocks(x)
+    for b in range(200):
+        s = int(scales[b]) - 127
+        m = np.abs(x[b]).max()
+        assert s == int(np.floor(np.log2(m))) - 8
+        assert 2.0 ** 8 <= m * 2.0 ** -s < 2.0 ** 9
+        for k in range(0, 32, 5):
+            code, val = _brute_force_e4m3(float(np.ldexp(x[b, k], -s)), table)
+            assert codes[b, k] == code and Fraction(float(y[b, k])) == val
+    ints = rng.integers(-14, 15, (50, 32)).astype(np.float64)
+    ints[0] = 0.0
+    y, codes, scales = orc.mx_blocks(ints)
+    assert scales[0] == 127 and not y[0].any()
+    assert np.array_equal(np.ldexp(y, (scales.astype(np.int64) - 127)[:, None]), ints)
+    y, codes, scales = orc.mx_blocks(np.array([15.0] + [1.0] * 31))
+    assert y[0] * 2.0 ** (int(scales[0]) - 127) == 14.0 and y[1] * 2.0 ** (int(scales[0]) - 127) == 1.0
+    # the E8M0 range is kept
+    y, codes, scales = orc.mx_blocks(np.full(32, 1e-60))
+    assert scales[0] == 0
