@@ -38,7 +38,13 @@
  * power-of-two exponent e per tile chosen so that the largest magnitude falls
  * in [2^14,2^15) resp. [2^7,2^8); e = 0 for an all-zero tile.  BF16 tiles (8
  * exponent bits as FP32, 7 fraction bits, overflow to infinity) have FP32's
- * range and carry no scale (e = 0).
+ * range and carry no scale (e = 0).  MXFP8 tiles (code 5; A and B only) are the block-scaled
+ * format of the OCP microscaling specification: e4m3 elements, tile_nb^2 bytes laid out like an
+ * FP8 tile, followed by one scale byte (E8M0: 2^(code-127)) per 32 consecutive reduction
+ * indices, row by row, tile_nb^2/32 bytes; scale = 2^(floor(log2 max|x|) - 8) of its block,
+ * elements rounded once and saturating; no tile scale.  This build multiplies MXFP8 tiles only
+ * with MXFP8 tiles, on the block-scaled matrix instruction, and only where that covers every
+ * product of the C tiles concerned (C tile not FP64, tile_nb a multiple of 256): see gemm_mp_run.
  *
  * C tiles stored in FP16 / FP8 (formats beyond FP64 / FP32 are what the paper's
  * Section 6 leaves open): such a tile is a storage format only.  Its products
@@ -66,7 +72,8 @@ typedef void *gemm_mp_stream;           /* a hipStream_t */
 /* Precision codes of a map entry: 0 and 1 as in the paper (Section 5.2); 2, 3, 4 extend them.
  * The code is a name, not a rank: by unit roundoff (2^-53, 2^-24, 2^-11, 2^-8, 2^-4) the formats
  * order FP64, FP32, FP16, BF16, FP8. */
-enum { GEMM_MP_FP64 = 0, GEMM_MP_FP32 = 1, GEMM_MP_FP16 = 2, GEMM_MP_FP8_E4M3 = 3, GEMM_MP_BF16 = 4 };
+enum { GEMM_MP_FP64 = 0, GEMM_MP_FP32 = 1, GEMM_MP_FP16 = 2, GEMM_MP_FP8_E4M3 = 3, GEMM_MP_BF16 = 4,
+       GEMM_MP_MXFP8 = 5 };
 
 enum {
     GEMM_MP_OK = 0,
@@ -101,6 +108,9 @@ typedef struct gemm_mp_stats {
     int64_t products_bf16;   /* the same counts for precision code 4, kept apart so that the */
     double flops_bf16;       /* arrays above stay indexed by the codes 0..3 */
     int64_t tiles_bf16[3];
+    int64_t products_mxfp8;  /* the same for precision code 5 */
+    double flops_mxfp8;
+    int64_t tiles_mxfp8[3];
 } gemm_mp_stats;
 
 /* Create a context for C(MxN) = A(MxK) * B(KxN) with square tiles of tile_nb (Section 4:
@@ -131,8 +141,8 @@ int gemm_mp_set_transposed(gemm_mp_ctx *ctx, char which, int transposed);
 
 /* Give the precision map of matrix `which` ('A', 'B' or 'C'): rows x cols codes, row-major,
  * host memory, copied (Section 5.2).  rows/cols must equal the matrix's tile counts (EINVAL),
- * codes must be 0..4 (EINVAL).  Any earlier binding and packed data of that matrix are
- * forgotten.  Host only. */
+ * codes must be 0..5 (EINVAL); MXFP8 C tiles are EUNSUPPORTED.  Any earlier binding and packed
+ * data of that matrix are forgotten.  Host only. */
 int gemm_mp_set_precision_map(gemm_mp_ctx *ctx, char which, const uint16_t *map_host,
                               int32_t rows, int32_t cols);
 
@@ -187,7 +197,9 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *ctx, char which, const double *dense_dev, in
  * BF16 tiles: the kernels take BF16 data only as an operand of a BF16 product (whose other
  * operand is BF16, or FP8 converted on the way like under an FP16 product); a BF16 tile under
  * an FP32 / FP64 product is read as the widened copy in the sender-side workspace, and the call
- * is ESTATE until gemm_mp_convert_tiles has filled it. */
+ * is ESTATE until gemm_mp_convert_tiles has filled it.
+ * MXFP8 tiles: EUNSUPPORTED unless every C tile that has an MXFP8 operand tile in one of its
+ * products has MXFP8 x MXFP8 products only, is not an FP64 tile, and tile_nb is a multiple of 256. */
 int gemm_mp_run(gemm_mp_ctx *ctx, double alpha, double beta, gemm_mp_stream stream);
 
 /* Sender-side conversion (optional).  The paper converts at the receiver: a tile travels in its

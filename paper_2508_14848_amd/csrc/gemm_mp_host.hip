@@ -50,9 +50,9 @@ struct gemm_mp_ctx {
     Matrix mat[3];
     bool sched_current = false;
     std::vector<uint8_t> q;
-    std::vector<WorkItem> items[3];   // regions of [0] FP64 C tiles, [1] C tiles accumulated in FP32 (stored
+    std::vector<WorkItem> items[4];   // regions of [0] FP64 C tiles, [1] C tiles accumulated in FP32 (stored
                                       // FP32 / FP16 / FP8), [2] those of them whose products are all
-                                      // FP8 x FP8 (256 x 256 regions)
+                                      // FP8 x FP8 (256 x 256 regions), [3] the same for MXFP8 x MXFP8
     uint8_t *d_q = nullptr;
     ProductDesc *d_prod = nullptr;    // one record per task (+ 2 padding records), filled on the device
     WorkItem *d_items = nullptr;      // the three lists, [0] first
@@ -60,6 +60,7 @@ struct gemm_mp_ctx {
     bool mixed32 = false;             // list [1] holds an FP16 / BF16 product with an operand stored in FP8
     bool mixed64 = false;             // the same for list [0]
     bool has_bf16 = false;            // A or B has a BF16 tile
+    bool mx_unsupported = false;      // an MXFP8 tile takes part in a product this build has no kernel for
     bool bf16_needs_copies = false;   // ... that meets another precision in some product (see gemm_mp_run)
     bool kernel_ready = false;
     // sender-side conversion: per tile of A / B and product precision q, the offset of the copy
@@ -115,7 +116,9 @@ void layout(gemm_mp_ctx *c, Matrix &m, bool is_c)
     uint64_t off = 0;
     for (int t = 0; t < m.ntiles(); ++t) {
         m.offset[t] = off;
-        off += (elems * (uint64_t)elem_bytes(m.map[t]) + 255u) & ~(uint64_t)255u;
+        uint64_t bytes = elems * (uint64_t)elem_bytes(m.map[t]);
+        if (m.map[t] == GEMM_MP_MXFP8) bytes += elems / 32;              // the block scales follow the elements
+        off += (bytes + 255u) & ~(uint64_t)255u;
     }
     m.low.clear();
     for (int t = 0; is_c && t < m.ntiles(); ++t)
@@ -209,14 +212,14 @@ int check_dense(const void *p, int64_t ld, int64_t cols)
 
 double unit_roundoff(int p)
 {
-    static const double u[5] = {0x1p-53, 0x1p-24, 0x1p-11, 0x1p-4, 0x1p-8};
+    static const double u[6] = {0x1p-53, 0x1p-24, 0x1p-11, 0x1p-4, 0x1p-8, 0x1p-4};
     return u[p];
 }
 
 // Relative cost of one tile product by precision: inverse matrix-core peak (FP64 : FP32 :
 // FP16 : FP8 = 1/78.6 : 1/157.3 : 1/2516.6 : 1/5033.2 TFLOP/s) plus a floor for the operand
 // traffic that the low precisions cannot hide.
-const double kCost[5] = {64.0, 32.0, 3.0, 2.0, 3.0};
+const double kCost[6] = {64.0, 32.0, 3.0, 2.0, 3.0, 2.0};
 
 // The schedule.  Every C tile is cut into (nb/128)^2 owner regions; a region's cost is the
 // sum over its reduction tiles of the cost of that product's precision.  C tiles are sorted by
@@ -238,6 +241,7 @@ void build_schedule(gemm_mp_ctx *c)
                 const int q = product_precision(A.map[I * KT + L], B.map[L * NT + J], pC, c->policy);
                 c->q[((size_t)I * NT + J) * KT + L] = (uint8_t)q;
                 if (q == GEMM_MP_BF16) c->stats.products_bf16 += 1;
+                else if (q == GEMM_MP_MXFP8) c->stats.products_mxfp8 += 1;
                 else c->stats.products[q] += 1;
                 cost[(size_t)I * NT + J] += kCost[q];
             }
@@ -245,6 +249,7 @@ void build_schedule(gemm_mp_ctx *c)
     const double f = 2.0 * (double)c->nb * (double)c->nb * (double)c->nb;
     for (int q = 0; q < 4; ++q) c->stats.flops[q] = f * (double)c->stats.products[q];
     c->stats.flops_bf16 = f * (double)c->stats.products_bf16;
+    c->stats.flops_mxfp8 = f * (double)c->stats.products_mxfp8;
     c->has_bf16 = false;
     for (int w = 0; w < 2; ++w)
         for (uint16_t p : c->mat[w].map) c->has_bf16 |= p == GEMM_MP_BF16;
@@ -259,6 +264,7 @@ void build_schedule(gemm_mp_ctx *c)
             for (int L = 0; L < KT; ++L) {
                 const int q = c->q[((size_t)I * NT + J) * KT + L];
                 const int pa = A.map[I * KT + L], pb = B.map[L * NT + J];
+                if (pa == GEMM_MP_MXFP8 || pb == GEMM_MP_MXFP8) continue;     // no copies of or for MXFP8 tiles
                 if (pa != q) c->conv_off[0][((size_t)I * KT + L) * kConvSlots + q] = 0;
                 if (pb != q) c->conv_off[1][((size_t)L * NT + J) * kConvSlots + q] = 0;
                 // the GEMM kernels take BF16 data only as operands of a BF16 product
@@ -279,6 +285,7 @@ void build_schedule(gemm_mp_ctx *c)
         for (int t = 0; t < c->mat[w].ntiles(); ++t) {
             const int p = c->mat[w].map[t];
             if (p == GEMM_MP_BF16) c->stats.tiles_bf16[w] += 1;
+            else if (p == GEMM_MP_MXFP8) c->stats.tiles_mxfp8[w] += 1;
             else c->stats.tiles[w][p] += 1;
         }
         c->stats.packed_bytes[w] = c->mat[w].bytes;
@@ -296,6 +303,21 @@ void build_schedule(gemm_mp_ctx *c)
                          B.map[L * NT + J] == GEMM_MP_FP8_E4M3;
                 all_fp8[(size_t)I * NT + J] = ok;
             }
+    // A C tile accumulated in FP32 whose every product multiplies two MXFP8 tiles goes to the same
+    // kernel's block-scaled instance; MXFP8 tiles anywhere else have no kernel in this build.
+    std::vector<uint8_t> all_mx((size_t)MT * NT, 0);
+    c->mx_unsupported = false;
+    for (int I = 0; I < MT; ++I)
+        for (int J = 0; J < NT; ++J) {
+            bool all = C.map[I * NT + J] != GEMM_MP_FP64 && KT > 0 && c->nb % kMacroFp8 == 0, any = false;
+            for (int L = 0; L < KT; ++L) {
+                const bool mx = A.map[I * KT + L] == GEMM_MP_MXFP8 || B.map[L * NT + J] == GEMM_MP_MXFP8;
+                any |= mx;
+                all &= c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_MXFP8;
+            }
+            all_mx[(size_t)I * NT + J] = all;
+            c->mx_unsupported |= any && !all;
+        }
     c->mixed32 = c->mixed64 = false;
     for (int I = 0; I < MT; ++I)
         for (int J = 0; J < NT; ++J) {
@@ -310,12 +332,12 @@ void build_schedule(gemm_mp_ctx *c)
             else c->mixed32 |= mixed;
         }
     constexpr int kBins = 8;
-    for (int list = 0; list < 3; ++list) {
-        const int mr = c->nb / (list == 2 ? kMacroFp8 : kMacro);
+    for (int list = 0; list < 4; ++list) {
+        const int mr = c->nb / (list >= 2 ? kMacroFp8 : kMacro);
         const size_t per_tile = (size_t)mr * mr;
         std::vector<int> order;
         for (int t = 0; t < MT * NT; ++t) {
-            const int which = C.map[t] == GEMM_MP_FP64 ? 0 : all_fp8[t] ? 2 : 1;
+            const int which = C.map[t] == GEMM_MP_FP64 ? 0 : all_fp8[t] ? 2 : all_mx[t] ? 3 : 1;
             if (which == list) order.push_back(t);
         }
         std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cost[a] > cost[b]; });
@@ -348,7 +370,7 @@ void build_schedule(gemm_mp_ctx *c)
             }
         }
     }
-    c->stats.work_items = (int64_t)(c->items[0].size() + c->items[1].size() + c->items[2].size());
+    c->stats.work_items = (int64_t)(c->items[0].size() + c->items[1].size() + c->items[2].size() + c->items[3].size());
     c->sched_current = true;
 }
 
@@ -360,12 +382,13 @@ int upload_schedule(gemm_mp_ctx *c)
     if ((rc = dev_alloc(&c->d_q, c->q.size()))) return rc;
     if ((rc = dev_alloc(&c->d_prod, c->q.size() + 2))) return rc;
     HIP_TRY(hipMemset(c->d_prod, 0, (c->q.size() + 2) * sizeof(ProductDesc)));
-    const size_t n0 = c->items[0].size(), n1 = c->items[1].size(), n2 = c->items[2].size();
-    if ((rc = dev_alloc(&c->d_items, n0 + n1 + n2))) return rc;
+    const size_t n0 = c->items[0].size(), n1 = c->items[1].size(), n2 = c->items[2].size(), n3 = c->items[3].size();
+    if ((rc = dev_alloc(&c->d_items, n0 + n1 + n2 + n3))) return rc;
     HIP_TRY(hipMemcpy(c->d_q, c->q.data(), c->q.size(), hipMemcpyHostToDevice));
     if (n0) HIP_TRY(hipMemcpy(c->d_items, c->items[0].data(), n0 * sizeof(WorkItem), hipMemcpyHostToDevice));
     if (n1) HIP_TRY(hipMemcpy(c->d_items + n0, c->items[1].data(), n1 * sizeof(WorkItem), hipMemcpyHostToDevice));
     if (n2) HIP_TRY(hipMemcpy(c->d_items + n0 + n1, c->items[2].data(), n2 * sizeof(WorkItem), hipMemcpyHostToDevice));
+    if (n3) HIP_TRY(hipMemcpy(c->d_items + n0 + n1 + n2, c->items[3].data(), n3 * sizeof(WorkItem), hipMemcpyHostToDevice));
     return GEMM_MP_OK;
 }
 
@@ -439,7 +462,10 @@ int gemm_mp_set_precision_map(gemm_mp_ctx *c, char which, const uint16_t *map, i
     Matrix &m = c->mat[w];
     if (rows != m.rows_t || cols != m.cols_t) return GEMM_MP_EINVAL;
     for (int t = 0; t < m.ntiles(); ++t)
-        if (map[t] > GEMM_MP_BF16) return GEMM_MP_EINVAL;
+        if (map[t] > GEMM_MP_MXFP8) return GEMM_MP_EINVAL;
+    if (w == 2)
+        for (int t = 0; t < m.ntiles(); ++t)
+            if (map[t] == GEMM_MP_MXFP8) return GEMM_MP_EUNSUPPORTED;
     return install_map(c, w, map);
 }
 
@@ -551,6 +577,11 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *c, char which, const double *dense, int64_t 
         HIP_TRY(launch_pack(dense, ld, m.cols, m.rows, m.cols_t, m.rows_t, c->nb, w != 1, true, view_of(m), s));
     else
         HIP_TRY(launch_pack(dense, ld, m.rows, m.cols, m.rows_t, m.cols_t, c->nb, w == 1, false, view_of(m), s));
+    bool has_mx = false;
+    for (uint16_t p : m.map) has_mx |= p == GEMM_MP_MXFP8;
+    if (has_mx)
+        HIP_TRY(launch_pack_mx(dense, m.transposed ? 1 : ld, m.transposed ? ld : 1, m.rows, m.cols, m.rows_t, m.cols_t, c->nb, w == 1,
+                               view_of(m), s));
     m.packed = true;
     m.last_stream = s;
     if (w < 2) c->conv_active = false;            // converted copies of the old data are stale
@@ -587,6 +618,7 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
         (void)hipFree(c->d_q); (void)hipFree(c->d_items); (void)hipFree(c->d_prod);     // of the old schedule
         c->d_q = nullptr; c->d_items = nullptr; c->d_prod = nullptr;
     }
+    if (c->mx_unsupported) return GEMM_MP_EUNSUPPORTED;
     if (c->bf16_needs_copies && !c->conv_active) return GEMM_MP_ESTATE;
     int rc;
     hipStream_t s = (hipStream_t)stream;
@@ -614,6 +646,8 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
     a.n_items64 = (int32_t)c->items[0].size();
     a.n_items32 = (int32_t)c->items[1].size();
     a.n_items8 = (int32_t)c->items[2].size();
+    a.items_mx = a.items8 + c->items[2].size();
+    a.n_items_mx = (int32_t)c->items[3].size();
     a.mixed32 = c->mixed32 ? 1 : 0;
     a.mixed64 = c->mixed64 ? 1 : 0;
     a.bf16 = c->has_bf16 ? 1 : 0;
@@ -744,7 +778,7 @@ int gemm_mp_get_stats(gemm_mp_ctx *c, gemm_mp_stats *out)
 
 int gemm_mp_product_precision(int pA, int pB, int pC, int policy)
 {
-    if (pA < 0 || pA > 4 || pB < 0 || pB > 4 || pC < 0 || pC > 4) return -1;
+    if (pA < 0 || pA > 5 || pB < 0 || pB > 5 || pC < 0 || pC > 4) return -1;
     if (policy != GEMM_MP_POLICY_OPERAND && policy != GEMM_MP_POLICY_C_TILE) return -1;
     return product_precision(pA, pB, pC, policy);
 }

@@ -25,6 +25,9 @@ __host__ __device__ inline int product_precision(int pA, int pB, int pC, int pol
     const int cap = (pC == GEMM_MP_FP64) ? GEMM_MP_FP64 : GEMM_MP_FP32;
     if (policy == GEMM_MP_POLICY_C_TILE) return cap;
     // the smallest format that holds both operands' numbers: FP64 > FP32 > {FP16, BF16} > FP8
+    if (pA == GEMM_MP_MXFP8 && pB == GEMM_MP_MXFP8) return GEMM_MP_MXFP8;
+    if (pA == GEMM_MP_MXFP8) pA = GEMM_MP_FP32;      // block-scaled e4m3 numbers are FP32 numbers
+    if (pB == GEMM_MP_MXFP8) pB = GEMM_MP_FP32;
     int q;
     const bool h = pA == GEMM_MP_FP16 || pB == GEMM_MP_FP16, b = pA == GEMM_MP_BF16 || pB == GEMM_MP_BF16;
     if (pA == GEMM_MP_FP64 || pB == GEMM_MP_FP64) q = GEMM_MP_FP64;
@@ -90,7 +93,8 @@ struct GemmArgs {
     const WorkItem *items64;  // owner regions of FP64 C tiles, launch order
     const WorkItem *items32;  // owner regions of FP32 C tiles, launch order
     const WorkItem *items8;   // 256 x 256 regions of FP32 C tiles made of FP8 x FP8 products only
-    int32_t n_items64, n_items32, n_items8;
+    const WorkItem *items_mx; // the same of tiles made of MXFP8 x MXFP8 products only
+    int32_t n_items64, n_items32, n_items8, n_items_mx;
     int32_t mixed32;         // some region of items32 has an FP16 / BF16 product with an operand stored in FP8
     int32_t mixed64;         // the same for items64
     int32_t bf16;            // some tile of A or B is stored in BF16
@@ -108,6 +112,10 @@ hipError_t launch_exps(const double *maxabs, const uint8_t *prec, int32_t *exps,
                        hipStream_t s);
 hipError_t launch_pack(const double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb, bool turn,
                        bool swap, PackedView v, hipStream_t s);
+// MXFP8 tiles of a matrix: block quantisation along the reduction index (is_b: down the columns).
+// Entry (r, c) of the matrix is X[r * sr + c * sc].
+hipError_t launch_pack_mx(const double *X, int64_t sr, int64_t sc, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb,
+                          bool is_b, PackedView v, hipStream_t s);
 hipError_t launch_unpack(double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb, bool turn,
                          bool swap, PackedView v, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);

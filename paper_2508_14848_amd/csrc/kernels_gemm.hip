@@ -6,8 +6,8 @@
 // ever touches that region, so there are no atomics and the result is reproducible.  Regions
 // are 128 x 128 (gemm_mp_owner_kernel: instances for FP64 and for FP32 C tiles, with and without
 // the two options described below), or
-// 256 x 256 for FP32 C tiles whose products are all FP8 x FP8 (gemm_mp_fp8_region_kernel, at
-// the end of this file).
+// 256 x 256 for FP32 C tiles whose products are all FP8 x FP8 or all MXFP8 x MXFP8
+// (gemm_mp_fp8_region_kernel, at the end of this file).
 //
 // Data path of one reduction chunk (128 bytes of converted reduction index per row, i.e.
 // 16 FP64 / 32 FP32 / 64 FP16 / 128 FP8 values) in the 128 x 128 kernels:
@@ -1673,17 +1673,37 @@ __device__ __forceinline__ void big_read_half(i8v &f, const BigGeom &BG, const c
     f[4 * w] = (int)v.x; f[4 * w + 1] = (int)v.y; f[4 * w + 2] = (int)v.z; f[4 * w + 3] = (int)v.w;
 }
 
+// Block scales of an MXFP8 chunk: per A row block (0..3) and B row block (4..7) the four scale
+// bytes of this lane's row (one per 32 reduction indices of the chunk), shifted so that byte 0
+// is the block this lane answers for in the chunk's first half and byte 2 in its second (the
+// instruction takes the scale of the first 32 indices of its 64 from lanes 0..31 and that of
+// the second 32 from lanes 32..63).
+struct BigScaleGeom {
+    int soa, sob;        // byte offset of this lane's scale row, A block 0 / B block 0, from the tile's start
+    int shift;           // 8 * (lane / 32)
+};
+__device__ __forceinline__ void big_load_scales(int (&d)[8], const BigScaleGeom &SG, uint64_t a, uint64_t b, int nb, int c)
+{
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        d[t] = (int)*(const uint32_t *)(uintptr_t)(a + (uint64_t)(SG.soa + t * nb + 4 * c));
+        d[4 + t] = (int)*(const uint32_t *)(uintptr_t)(b + (uint64_t)(SG.sob + t * nb + 4 * c));
+    }
+}
+
 // One chunk held in `STAGE`.  On entry f[0] holds the fragments of its first half; on exit
 // those of the next chunk's first half.  S2: the chunk two ahead, requested into STAGE.
-template <int STAGE>
+// MX: sc holds this chunk's block scales (see big_load_scales), sa / sb are not used.
+template <int STAGE, bool MX>
 __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], const BigGeom &BG, const char *lds, const BigSource &S2,
-                                          int sa, int sb)
+                                          int sa, int sb, const int (&sc)[8])
 {
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
-            acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
+            if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sc[mt], 0, sc[4 + nt]);
+            else acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
             SCHED_FENCE();
             const int k = mt * 4 + nt;                       // second half's fragments, 16 bytes per position: B first
             big_read_half(f[1][((k >> 1) + 4) & 7], BG, lds, STAGE, 1, ((k >> 1) + 4) & 7, k & 1);
@@ -1697,7 +1717,8 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
-            acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
+            if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 2, sc[mt], 2, sc[4 + nt]);
+            else acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
             SCHED_FENCE();
             const int k = mt * 4 + nt;
             big_read_half(f[0][((k >> 1) + 4) & 7], BG, lds, STAGE ^ 1, 0, ((k >> 1) + 4) & 7, k & 1);
@@ -1706,6 +1727,11 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
         }
 }
 
+// MX: the operand tiles are MXFP8 (block scales behind the elements, no tile scale).  A lane's 32
+// operand bytes of a 64-index step are then the 16 bytes at index 16 g of the step's first 32
+// indices and the 16 bytes at 16 g of its second 32 (that is how the instruction pairs data
+// with block scales), instead of 32 consecutive ones.
+template <bool MX>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 {
@@ -1737,10 +1763,17 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
             for (int hc = 0; hc < 2; ++hc)
 #pragma unroll
                 for (int w = 0; w < 2; ++w) {
-                    const int slot_r = (4 * hc + 2 * g + w) ^ x;
+                    const int slot_r = (MX ? 4 * hc + g + 2 * w : 4 * hc + 2 * g + w) ^ x;
                     BG.ra[st][hc][w] = st * kBigStage + (wm * 128 + i) * kRowBytes + slot_r * 16;
                     BG.rb[st][hc][w] = st * kBigStage + kBigOperand + (wn * 128 + i) * kRowBytes + slot_r * 16;
                 }
+    }
+
+    BigScaleGeom SG{};
+    if constexpr (MX) {
+        SG.soa = nb * nb + (arow0 + wm * 128 + (lane & 31)) * (nb / 32);
+        SG.sob = nb * nb + (brow0 + wn * 128 + (lane & 31)) * (nb / 32);
+        SG.shift = 8 * (lane >> 5);
     }
 
     f16v acc[4][4];
@@ -1773,6 +1806,12 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
         i8v f[2][8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) f[0][t] = big_read(BG, lds, 0, 0, t);
+        int sc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, nsc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if constexpr (MX) {
+            big_load_scales(sc, SG, S.a, S.b, nb, 0);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) sc[t] = (int)((uint32_t)sc[t] >> SG.shift);
+        }
 
         for (int L = 0; L < kt; ++L) {
             int sa, sb;
@@ -1796,9 +1835,22 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
             for (int c = 0; c < n; c += 2) {
                 BigSource S2 = (c + 2 < n) ? cur_src : next_src;
                 S2.c = (c + 2 < n) ? c + 2 : c + 2 - n;
-                big_chunk<0>(acc, f, BG, lds, S2, sa, sb);
+                // MX: the scales of the chunk after the one being computed are fetched under it
+                // (past the end of the reduction: those of the last chunk again, unused)
+                if constexpr (MX) big_load_scales(nsc, SG, cur_src.a, cur_src.b, nb, c + 1);
+                big_chunk<0, MX>(acc, f, BG, lds, S2, sa, sb, sc);
+                if constexpr (MX) {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) sc[t] = (int)((uint32_t)nsc[t] >> SG.shift);
+                    const bool wrap = c + 2 >= n && nbytes != 0;
+                    big_load_scales(nsc, SG, wrap ? next_src.a : cur_src.a, wrap ? next_src.b : cur_src.b, nb, c + 2 < n ? c + 2 : wrap ? 0 : n - 1);
+                }
                 S2.c += 1;
-                big_chunk<1>(acc, f, BG, lds, S2, sa, sb);
+                big_chunk<1, MX>(acc, f, BG, lds, S2, sa, sb, sc);
+                if constexpr (MX) {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) sc[t] = (int)((uint32_t)nsc[t] >> SG.shift);
+                }
             }
             lo = nlo;
             hi = nhi;
@@ -1845,7 +1897,10 @@ hipError_t gemm_kernel_setup()
         const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
     }
-    return hipFuncSetAttribute((const void *)gemm_mp_fp8_region_kernel,
+    const hipError_t e = hipFuncSetAttribute((const void *)gemm_mp_fp8_region_kernel<false>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void *)gemm_mp_fp8_region_kernel<true>,
                                hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
 }
 
@@ -1966,7 +2021,9 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
         else gemm_mp_owner_kernel<float, false, false><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
     }
     if (a.n_items8 > 0)
-        gemm_mp_fp8_region_kernel<<<dim3((unsigned)a.n_items8), dim3(kThreads), kBigLdsBytes, s>>>(a, a.items8);
+        gemm_mp_fp8_region_kernel<false><<<dim3((unsigned)a.n_items8), dim3(kThreads), kBigLdsBytes, s>>>(a, a.items8);
+    if (a.n_items_mx > 0)
+        gemm_mp_fp8_region_kernel<true><<<dim3((unsigned)a.n_items_mx), dim3(kThreads), kBigLdsBytes, s>>>(a, a.items_mx);
     return hipGetLastError();
 }
 

@@ -259,6 +259,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const double *__restrict__ X,
     const int I = (int)(R0 / nb), J = (int)(C0 / nb);
     const int tile = swap ? J * rows_t + I : I * cols_t + J;      // swap: the buffer holds the matrix's transpose
     const int p = v.prec[tile];
+    if (p == GEMM_MP_MXFP8) return;                              // block-scaled tiles: pack_mx_kernel
     const int e = v.exp[tile];
     char *base = v.storage + v.offset[tile];
     const int r_in = (int)(R0 % nb), c_in = (int)(C0 % nb);
@@ -309,11 +310,71 @@ hipError_t launch_pack(const double *X, int64_t ld, int64_t rows, int64_t cols, 
     return hipGetLastError();
 }
 
+// MXFP8 tiles (the block-scaled format of the OCP microscaling specification): one thread per
+// block of 32 consecutive reduction indices of one packed row (a row of an A tile, a column of a
+// B tile).  Scale 2^s, s = floor(log2 max|x|) - 8 within [-127, 127] (0 for a zero block or a
+// non-finite maximum); elements x * 2^-s rounded once to e4m3, saturating; the scale bytes
+// (s + 127) follow the tile's nb * nb element bytes, nb / 32 per packed row.  Entries outside the
+// rows x cols matrix count as zeros.
+__global__ __launch_bounds__(256) void pack_mx_kernel(const double *__restrict__ X, int64_t sr, int64_t sc, int64_t rows, int64_t cols,
+                                                      int cols_t, int nb, bool is_b, PackedView v)
+{
+    const int tile = blockIdx.y;
+    if (v.prec[tile] != GEMM_MP_MXFP8) return;
+    const int I = tile / cols_t, J = tile % cols_t;
+    const int per_row = nb / 32;
+    const int idx = blockIdx.x * 256 + threadIdx.x;              // (packed row, block): nb * nb / 32 of them, a multiple of 256
+    const int u = idx / per_row, kb = idx % per_row;
+    double x[32];
+    double m = 0.0;
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+        const int64_t r = (int64_t)I * nb + (is_b ? 32 * kb + k : u), c = (int64_t)J * nb + (is_b ? u : 32 * kb + k);
+        x[k] = (r < rows && c < cols) ? X[r * sr + c * sc] : 0.0;
+        const double a = __builtin_fabs(x[k]);
+        if (a > m) m = a;                                        // a NaN never enters m
+    }
+    int s = 0;
+    {
+        const uint64_t bits = (uint64_t)__double_as_longlong(m);
+        const int field = (int)(bits >> 52);
+        const uint64_t man = bits & 0xfffffffffffffull;
+        if (field != 0x7ff && bits != 0) {
+            const int lg = field ? field - 1023 : 63 - __builtin_clzll(man) - 1074;
+            s = lg - 8;
+            s = s < -127 ? -127 : s > 127 ? 127 : s;
+        }
+    }
+    char *base = v.storage + v.offset[tile];
+    uint32_t w[8];
+#pragma unroll
+    for (int k = 0; k < 32; k += 4)
+        w[k / 4] = to_fp8_bits(x[k], s) | (to_fp8_bits(x[k + 1], s) << 8) | (to_fp8_bits(x[k + 2], s) << 16) | (to_fp8_bits(x[k + 3], s) << 24);
+    uint4 *dst = (uint4 *)(base + (int64_t)u * nb + 32 * kb);
+    dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+    dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+    ((uint8_t *)base)[(int64_t)nb * nb + (int64_t)u * per_row + kb] = (uint8_t)(s + 127);
+}
+
+hipError_t launch_pack_mx(const double *X, int64_t sr, int64_t sc, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb,
+                          bool is_b, PackedView v, hipStream_t s)
+{
+    dim3 grid((unsigned)((int64_t)nb * nb / 32 / 256), (unsigned)(rows_t * cols_t));
+    pack_mx_kernel<<<grid, 256, 0, s>>>(X, sr, sc, rows, cols, cols_t, nb, is_b, v);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------------
-// Unpack: the exact FP64 value of every stored element (stored number times 2^e).
-__device__ inline double stored_value(const char *base, int64_t idx, int p, int e)
+// Unpack: the exact FP64 value of every stored element (stored number times 2^e; for an MXFP8
+// tile of size nb, times the scale of its block of 32).
+__device__ inline double stored_value(const char *base, int64_t idx, int p, int e, int nb)
 {
     switch (p) {
+    case GEMM_MP_MXFP8: {
+        const int code = ((const uint8_t *)base)[idx];
+        const int sc = ((const uint8_t *)base)[(int64_t)nb * nb + (idx >> 5)];
+        return ldexp((double)__builtin_amdgcn_cvt_f32_fp8(code, 0), sc - 127);
+    }
     case GEMM_MP_FP64: return ((const double *)base)[idx];
     case GEMM_MP_FP32: return (double)((const float *)base)[idx];
     case GEMM_MP_FP16: return ldexp((double)(float)((const _Float16 *)base)[idx], e);
@@ -345,7 +406,7 @@ __global__ __launch_bounds__(256) void unpack_kernel(double *__restrict__ X, int
             const int c = t / 16 + 16 * it, r4 = (t % 16) * 4;
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                turn[c][r4 + j] = stored_value(base, (int64_t)(c_in + c) * nb + r_in + r4 + j, p, e);
+                turn[c][r4 + j] = stored_value(base, (int64_t)(c_in + c) * nb + r_in + r4 + j, p, e, nb);
         }
         __syncthreads();
     }
@@ -356,7 +417,7 @@ __global__ __launch_bounds__(256) void unpack_kernel(double *__restrict__ X, int
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             x[j] = TRANSPOSE ? turn[c4 + j][r]
-                             : stored_value(base, (int64_t)(r_in + r) * nb + c_in + c4 + j, p, e);
+                             : stored_value(base, (int64_t)(r_in + r) * nb + c_in + c4 + j, p, e, nb);
         if (R0 + kPackBlock <= rows && C0 + kPackBlock <= cols) {
             double2 *dst = (double2 *)(X + (R0 + r) * ld + C0 + c4);
             dst[0] = make_double2(x[0], x[1]);

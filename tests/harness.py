@@ -4,8 +4,8 @@ import numpy as np
 
 from oracle import gemm_mp_oracle as orc
 
-FP64, FP32, FP16, FP8, BF16 = 0, 1, 2, 3, 4
-U = {FP64: 2.0 ** -53, FP32: 2.0 ** -24, FP16: 2.0 ** -11, FP8: 2.0 ** -4, BF16: 2.0 ** -8}
+FP64, FP32, FP16, FP8, BF16, MXFP8 = 0, 1, 2, 3, 4, 5
+U = {FP64: 2.0 ** -53, FP32: 2.0 ** -24, FP16: 2.0 ** -11, FP8: 2.0 ** -4, BF16: 2.0 ** -8, MXFP8: 2.0 ** -4}
 
 
 class OracleSide:
@@ -33,7 +33,7 @@ class OracleSide:
         if w.a_equals_b:
             self.By, self.eB = self.Ay, self.eA
         else:
-            self.By, self.eB = orc.store_tiles(B, nb, self.mapB, mb)
+            self.By, self.eB = orc.store_tiles(B, nb, self.mapB, mb, mx_axis=1)     # blocks of MXFP8 tiles: down B's columns
         self.Cy = None
         if C0 is not None and w.beta != 0.0:
             Cy, eC = orc.store_tiles(C0, nb, self.mapC)

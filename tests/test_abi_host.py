@@ -62,7 +62,7 @@ def test_map_validation_and_call_order():
         g.set_precision_map("A", np.zeros((3, 4), np.uint16))          # A is 4 x 3 tiles
     assert e.value.status == G.EINVAL
     with pytest.raises(G.GemmMPError) as e:
-        g.set_precision_map("A", np.full((4, 3), 5, np.uint16))        # code out of range
+        g.set_precision_map("A", np.full((4, 3), 6, np.uint16))        # code out of range
     assert e.value.status == G.EINVAL
     with pytest.raises(G.GemmMPError) as e:
         g.set_precision_map("X", np.zeros((4, 3), np.uint16))
@@ -167,13 +167,41 @@ def test_bf16_codes_layout_products_and_conversion_plan():
     g.destroy()
 
 
+def test_mxfp8_codes_layout_and_where_this_build_runs_them():
+    """MXFP8 (code 5): nb^2 element bytes plus nb^2/32 scale bytes per tile, A and B only; the
+    product precision equals the oracle's; tiles made of MXFP8 x MXFP8 products only are cut into
+    256 x 256 regions; statistics count such products apart."""
+    from oracle import gemm_mp_oracle as orc
+    for pA in range(6):
+        for pB in range(6):
+            for pC in range(5):
+                for policy in (G.POLICY_OPERAND, G.POLICY_C_TILE):
+                    assert G.product_precision(pA, pB, pC, policy) == orc.product_precision(pA, pB, pC, policy)
+    nb = 512
+    g = G.GemmMP(2 * nb, 2 * nb, 3 * nb, nb)
+    g.set_precision_map("A", np.full((2, 3), G.MXFP8, dtype=np.uint16))
+    assert g.storage_bytes("A") == 6 * (nb * nb + nb * nb // 32)
+    o, prec, _ = g.tile_info("A", 0, 1, want_exp=False)
+    assert o == nb * nb + nb * nb // 32 and prec == G.MXFP8
+    with pytest.raises(G.GemmMPError) as e:
+        g.set_precision_map("C", np.full((2, 2), G.MXFP8, dtype=np.uint16))
+    assert e.value.status == G.EUNSUPPORTED
+    g.set_precision_map("B", np.full((3, 2), G.MXFP8, dtype=np.uint16))
+    g.set_precision_map("C", np.full((2, 2), G.FP32, dtype=np.uint16))
+    st = g.get_stats()
+    assert st["products_mxfp8"] == 12 and st["products"] == [0, 0, 0, 0] and st["tiles_mxfp8"] == [6, 6, 0]
+    assert st["flops_mxfp8"] == 12 * 2.0 * nb ** 3 and st["work_items"] == 4 * (nb // 256) ** 2
+    assert g.conversion_bytes() == 0
+    g.destroy()
+
+
 def test_product_precision_and_stats_closed_forms():
     for pA in range(4):
         for pB in range(4):
             for pC in range(2):
                 assert G.product_precision(pA, pB, pC, G.POLICY_C_TILE) == pC
                 assert G.product_precision(pA, pB, pC, G.POLICY_OPERAND) == max(pC and 1, min(pA, pB))
-    assert G.product_precision(5, 0, 0) == -1
+    assert G.product_precision(6, 0, 0) == -1 and G.product_precision(0, 0, 5) == -1
     w = W.tiny()
     g = G.GemmMP(w.M, w.N, w.K, w.nb)
     for k, m in (("A", w.mapA), ("B", w.mapB), ("C", w.mapC)):

@@ -8,7 +8,7 @@ import pytest
 
 import workloads as W
 from oracle import gemm_mp_oracle as orc
-from tests.harness import (BF16, FP8, FP16, FP32, FP64, OracleSide, compare_jobs, finish_low_c_tiles, gpu_problem,
+from tests.harness import (BF16, FP8, FP16, FP32, FP64, MXFP8, OracleSide, compare_jobs, finish_low_c_tiles, gpu_problem,
                            packed_codes_expected)
 
 pytestmark = pytest.mark.gpu
@@ -744,6 +744,92 @@ def test_random_small_integer_problems_over_all_five_formats_are_exact():
             d.run(alpha, beta)
         got = d.unpack_tiles("C").cpu().numpy()
         assert np.array_equal(got, want), what
+    torch.cuda.synchronize()
+
+
+def test_mxfp8_tiles_pack_bit_for_bit_and_multiply_on_the_block_scaled_instruction():
+    """MXFP8 tiles: element and scale bytes equal the oracle's block quantisation (blocks along the
+    rows of A tiles and down the columns of B tiles, i.e. along the reduction index; a size off
+    the tile grid included), unpack returns the values they stand for; all-MXFP8 products of small
+    integers are exact through the block-scaled matrix instruction (scales differ from block to
+    block by construction), and general data stays within the per-tile bounds of the oracle."""
+    import torch
+    from paper_2508_14848_amd import gemm_mp as G
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(61)
+    # storage
+    nb = 256
+    M, N, K = 2 * nb, 2 * nb - 70, 3 * nb - 33
+    A = rng.standard_normal((M, K)) * np.exp(rng.uniform(-30, 30, (M, K)))
+    B = rng.standard_normal((K, N)) * np.exp(rng.uniform(-30, 30, (K, N)))
+    A[5, 64:96] = 0.0                                            # a zero block
+    d = DeviceGemmMP(M, N, K, nb)
+    d.set_precision_map("A", np.full((2, 3), MXFP8, dtype=np.uint16))
+    d.set_precision_map("B", np.full((3, 2), MXFP8, dtype=np.uint16))
+    d.pack_tiles("A", _even_ld(A))
+    d.pack_tiles("B", _even_ld(B))
+    Ap, Bp = orc.pad_to_tiles(A, nb), orc.pad_to_tiles(B, nb)
+    for which, Xp, tiles in (("A", Ap, [(0, 0), (1, 2)]), ("B", Bp, [(0, 0), (2, 1)])):
+        for (I, J) in tiles:
+            got, prec = d.tile_bytes(which, I, J)
+            tile = Xp[I * nb:(I + 1) * nb, J * nb:(J + 1) * nb]
+            rows = np.ascontiguousarray(tile.T if which == "B" else tile)        # packed rows: the reduction index runs along them
+            _, codes, scales = orc.mx_blocks(rows)
+            assert prec == MXFP8
+            assert np.array_equal(got[:nb * nb], codes.ravel()), (which, I, J)
+            assert np.array_equal(got[nb * nb:], scales), (which, I, J)
+    Ya, _ = orc.store_tiles(Ap, nb, np.full((2, 3), MXFP8, dtype=np.uint16), mx_axis=0)
+    Yb, _ = orc.store_tiles(Bp, nb, np.full((3, 2), MXFP8, dtype=np.uint16), mx_axis=1)
+    assert np.array_equal(d.unpack_tiles("A").cpu().numpy(), Ya[:M, :K])
+    assert np.array_equal(d.unpack_tiles("B").cpu().numpy(), Yb[:K, :N])
+    # what this build does not run
+    d.set_precision_map("C", np.full((2, 2), FP64, dtype=np.uint16))
+    with pytest.raises(G.GemmMPError) as e:
+        d.run(1.0, 0.0)
+    assert e.value.status == G.EUNSUPPORTED
+    # integers: exact; every block gets its own scale from a different largest entry
+    for nb, MT, NT, KT in ((256, 2, 1, 3), (512, 1, 2, 2)):
+        M, N, K = MT * nb, NT * nb, KT * nb
+        _say("MXFP8 integers", (M, N, K, nb))
+        mag = 2.0 ** rng.integers(0, 3, (M, K // 32)).repeat(32, axis=1)         # 1, 2 or 4 per block of A's rows
+        A = rng.integers(-3, 4, (M, K)) * mag
+        magb = 2.0 ** rng.integers(0, 3, (K // 32, N)).repeat(32, axis=0)
+        B = rng.integers(-3, 4, (K, N)) * magb
+        C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
+        for pC in (FP32, FP16 if nb == 256 else BF16):
+            d = DeviceGemmMP(M, N, K, nb)
+            d.set_precision_map("A", np.full((MT, KT), MXFP8, dtype=np.uint16))
+            d.set_precision_map("B", np.full((KT, NT), MXFP8, dtype=np.uint16))
+            d.set_precision_map("C", np.full((MT, NT), pC, dtype=np.uint16))
+            for which, X in (("A", A), ("B", B), ("C", C0)):
+                d.pack_tiles(which, torch.from_numpy(np.ascontiguousarray(X, dtype=np.float64)).cuda())
+            assert np.array_equal(d.unpack_tiles("A").cpu().numpy(), A) and np.array_equal(d.unpack_tiles("B").cpu().numpy(), B)
+            st = d.ctx.get_stats()
+            assert st["products_mxfp8"] == MT * NT * KT and st["work_items"] == MT * NT * (nb // 256) ** 2
+            if pC == FP32:
+                d.run(1.0, -1.0)
+                want = A @ B - C0
+                assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), want)
+            else:                                      # a low-precision C tile cannot hold these sums exactly
+                d.run(1.0, 0.0)
+                want = A @ B
+                got = d.unpack_tiles("C").cpu().numpy()
+                assert np.abs(got - want).max() <= (2.0 ** -11 if pC == FP16 else 2.0 ** -8) * np.abs(want).max()
+    # general data against the oracle
+    w = W.tiny()
+    w.mapA = np.full_like(w.mapA, MXFP8)
+    w.mapB = np.full_like(w.mapB, MXFP8)
+    w.mapC = np.full_like(w.mapC, FP32)
+    w.alpha, w.beta = 1.0, 0.0
+    A, B, _ = _dense(w)
+    side = OracleSide(w, A, B, None)
+    d, dev = gpu_problem(w, A, B, None)
+    assert np.array_equal(d.unpack_tiles("A").cpu().numpy(), side.Ay) and np.array_equal(d.unpack_tiles("B").cpu().numpy(), side.By)
+    d.run(1.0, 0.0)
+    C_gpu = d.unpack_tiles("C").cpu().numpy()
+    jobs = _all_jobs(w)
+    worst = compare_jobs(side, jobs, 0, 1.0, 0.0, C_gpu, side.gemm(jobs))
+    _say("  worst error / bound:", worst)
     torch.cuda.synchronize()
 
 
