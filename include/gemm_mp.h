@@ -42,9 +42,10 @@
  * format of the OCP microscaling specification: e4m3 elements, tile_nb^2 bytes laid out like an
  * FP8 tile, followed by one scale byte (E8M0: 2^(code-127)) per 32 consecutive reduction
  * indices, row by row, tile_nb^2/32 bytes; scale = 2^(floor(log2 max|x|) - 8) of its block,
- * elements rounded once and saturating; no tile scale.  This build multiplies MXFP8 tiles only
- * with MXFP8 tiles, on the block-scaled matrix instruction, and only where that covers every
- * product of the C tiles concerned (C tile not FP64, tile_nb a multiple of 256): see gemm_mp_run.
+ * elements rounded once and saturating; no tile scale.  Where every product of a C tile is
+ * MXFP8 x MXFP8 (C tile not FP64, tile_nb a multiple of 256) the tile runs on the block-scaled
+ * matrix instruction; any other product with an MXFP8 operand reads widened copies of the MXFP8
+ * tiles from the sender-side workspace: see gemm_mp_run.
  *
  * C tiles stored in FP16 / FP8 (formats beyond FP64 / FP32 are what the paper's
  * Section 6 leaves open): such a tile is a storage format only.  Its products
@@ -198,8 +199,11 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *ctx, char which, const double *dense_dev, in
  * operand is BF16, or FP8 converted on the way like under an FP16 product); a BF16 tile under
  * an FP32 / FP64 product is read as the widened copy in the sender-side workspace, and the call
  * is ESTATE until gemm_mp_convert_tiles has filled it.
- * MXFP8 tiles: EUNSUPPORTED unless every C tile that has an MXFP8 operand tile in one of its
- * products has MXFP8 x MXFP8 products only, is not an FP64 tile, and tile_nb is a multiple of 256. */
+ * MXFP8 tiles: a C tile whose products are all MXFP8 x MXFP8 (not an FP64 tile, tile_nb a
+ * multiple of 256) needs nothing; any other product with an MXFP8 operand is computed from the
+ * exact FP32 / FP64 copies of the MXFP8 tiles in the sender-side workspace (an MXFP8 x MXFP8
+ * product then as exact FP32 products with FP32 accumulation, which is what it is), and the
+ * call is ESTATE until gemm_mp_convert_tiles has filled it. */
 int gemm_mp_run(gemm_mp_ctx *ctx, double alpha, double beta, gemm_mp_stream stream);
 
 /* Sender-side conversion (optional).  The paper converts at the receiver: a tile travels in its

@@ -60,7 +60,7 @@ struct gemm_mp_ctx {
     bool mixed32 = false;             // list [1] holds an FP16 / BF16 product with an operand stored in FP8
     bool mixed64 = false;             // the same for list [0]
     bool has_bf16 = false;            // A or B has a BF16 tile
-    bool mx_unsupported = false;      // an MXFP8 tile takes part in a product this build has no kernel for
+    bool mx_needs_copies = false;     // an MXFP8 tile takes part in a product outside the block-scaled kernel
     bool bf16_needs_copies = false;   // ... that meets another precision in some product (see gemm_mp_run)
     bool kernel_ready = false;
     // sender-side conversion: per tile of A / B and product precision q, the offset of the copy
@@ -254,6 +254,31 @@ void build_schedule(gemm_mp_ctx *c)
     for (int w = 0; w < 2; ++w)
         for (uint16_t p : c->mat[w].map) c->has_bf16 |= p == GEMM_MP_BF16;
 
+    // A C tile accumulated in FP32 whose every product multiplies two MXFP8 tiles goes to the
+    // block-scaled instance of the 256 x 256 kernel.  Every other product with an MXFP8 operand
+    // is run by the 128 x 128 kernels on widened copies of the MXFP8 tiles (sender-side workspace):
+    // at FP32 where both operands are MXFP8 (exact products, FP32 accumulation: what an MXFP8
+    // product is), at the product's own FP32 / FP64 otherwise.  c->q then holds the precision
+    // the kernels work at, the statistics keep the product's nominal one.
+    std::vector<uint8_t> all_mx((size_t)MT * NT, 0);
+    c->mx_needs_copies = false;
+    for (int I = 0; I < MT; ++I)
+        for (int J = 0; J < NT; ++J) {
+            bool all = C.map[I * NT + J] != GEMM_MP_FP64 && KT > 0 && c->nb % kMacroFp8 == 0, any = false;
+            for (int L = 0; L < KT; ++L) {
+                const bool mx = A.map[I * KT + L] == GEMM_MP_MXFP8 || B.map[L * NT + J] == GEMM_MP_MXFP8;
+                any |= mx;
+                all &= c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_MXFP8;
+            }
+            all_mx[(size_t)I * NT + J] = all;
+            c->mx_needs_copies |= any && !all;
+            if (!all)
+                for (int L = 0; L < KT; ++L) {
+                    uint8_t &q = c->q[((size_t)I * NT + J) * KT + L];
+                    if (q == GEMM_MP_MXFP8) q = GEMM_MP_FP32;
+                }
+        }
+
     // Sender-side conversion plan: which (tile, q) copies the tasks would need, and where each
     // would live in the workspace (256-byte aligned, A's copies first).
     c->conv_off[0].assign((size_t)MT * KT * kConvSlots, kNoCopy);
@@ -264,7 +289,7 @@ void build_schedule(gemm_mp_ctx *c)
             for (int L = 0; L < KT; ++L) {
                 const int q = c->q[((size_t)I * NT + J) * KT + L];
                 const int pa = A.map[I * KT + L], pb = B.map[L * NT + J];
-                if (pa == GEMM_MP_MXFP8 || pb == GEMM_MP_MXFP8) continue;     // no copies of or for MXFP8 tiles
+                if (q == GEMM_MP_MXFP8) continue;                             // block-scaled kernel: no copies
                 if (pa != q) c->conv_off[0][((size_t)I * KT + L) * kConvSlots + q] = 0;
                 if (pb != q) c->conv_off[1][((size_t)L * NT + J) * kConvSlots + q] = 0;
                 // the GEMM kernels take BF16 data only as operands of a BF16 product
@@ -303,21 +328,6 @@ void build_schedule(gemm_mp_ctx *c)
                          B.map[L * NT + J] == GEMM_MP_FP8_E4M3;
                 all_fp8[(size_t)I * NT + J] = ok;
             }
-    // A C tile accumulated in FP32 whose every product multiplies two MXFP8 tiles goes to the same
-    // kernel's block-scaled instance; MXFP8 tiles anywhere else have no kernel in this build.
-    std::vector<uint8_t> all_mx((size_t)MT * NT, 0);
-    c->mx_unsupported = false;
-    for (int I = 0; I < MT; ++I)
-        for (int J = 0; J < NT; ++J) {
-            bool all = C.map[I * NT + J] != GEMM_MP_FP64 && KT > 0 && c->nb % kMacroFp8 == 0, any = false;
-            for (int L = 0; L < KT; ++L) {
-                const bool mx = A.map[I * KT + L] == GEMM_MP_MXFP8 || B.map[L * NT + J] == GEMM_MP_MXFP8;
-                any |= mx;
-                all &= c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_MXFP8;
-            }
-            all_mx[(size_t)I * NT + J] = all;
-            c->mx_unsupported |= any && !all;
-        }
     c->mixed32 = c->mixed64 = false;
     for (int I = 0; I < MT; ++I)
         for (int J = 0; J < NT; ++J) {
@@ -618,8 +628,7 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
         (void)hipFree(c->d_q); (void)hipFree(c->d_items); (void)hipFree(c->d_prod);     // of the old schedule
         c->d_q = nullptr; c->d_items = nullptr; c->d_prod = nullptr;
     }
-    if (c->mx_unsupported) return GEMM_MP_EUNSUPPORTED;
-    if (c->bf16_needs_copies && !c->conv_active) return GEMM_MP_ESTATE;
+    if ((c->bf16_needs_copies || c->mx_needs_copies) && !c->conv_active) return GEMM_MP_ESTATE;
     int rc;
     hipStream_t s = (hipStream_t)stream;
     if ((rc = ensure_tables(C))) return rc;

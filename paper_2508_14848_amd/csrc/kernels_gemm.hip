@@ -1954,6 +1954,27 @@ __global__ __launch_bounds__(256) void convert_tiles_kernel(const ConvertJob *__
     const uint32_t seg = blockIdx.x * 256u + threadIdx.x;
     if (seg >= job.n16) return;
     const int p = job.p, q = job.q;
+    if (p == GEMM_MP_MXFP8) {
+        // MXFP8 tile to FP32 / FP64: element times the scale of its block of 32 (exact)
+        const uint8_t *sb = (const uint8_t *)(uintptr_t)job.src;
+        const uint64_t elems = (uint64_t)job.n16 * (q == Q32 ? 4u : 2u);         // nb * nb; the scale bytes follow them
+        u32x4 o;
+        if (q == Q32) {
+            const uint64_t idx = (uint64_t)seg * 4;
+            const int w = (int)*(const uint32_t *)(sb + idx);
+            const int sc = (int)sb[elems + (idx >> 5)] - 127;
+            o = u32x4{__float_as_uint(ldexpf(__builtin_amdgcn_cvt_f32_fp8(w, 0), sc)), __float_as_uint(ldexpf(__builtin_amdgcn_cvt_f32_fp8(w, 1), sc)),
+                      __float_as_uint(ldexpf(__builtin_amdgcn_cvt_f32_fp8(w, 2), sc)), __float_as_uint(ldexpf(__builtin_amdgcn_cvt_f32_fp8(w, 3), sc))};
+        } else {
+            const uint64_t idx = (uint64_t)seg * 2;
+            const int w = (int)*(const uint16_t *)(sb + idx);
+            const int sc = (int)sb[elems + (idx >> 5)] - 127;
+            const u32x2 a = dbits(ldexp((double)__builtin_amdgcn_cvt_f32_fp8(w, 0), sc)), b = dbits(ldexp((double)__builtin_amdgcn_cvt_f32_fp8(w, 1), sc));
+            o = u32x4{a.x, a.y, b.x, b.y};
+        }
+        *(u32x4 *)((char *)(uintptr_t)job.dst + (uint64_t)seg * 16) = o;
+        return;
+    }
     if (p == GEMM_MP_BF16 || q == GEMM_MP_BF16) {
         // BF16 tile to FP32 / FP64 (a shift: exact), or FP8 tile to BF16 keeping its scale (exact:
         // every e4m3 number is a BF16 number).  No other pair occurs: FP16 and BF16 meet in FP32.

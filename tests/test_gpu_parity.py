@@ -693,10 +693,10 @@ def test_bf16_tiles_small_integer_problems_are_exact():
         torch.cuda.synchronize()
 
 
-def test_random_small_integer_problems_over_all_five_formats_are_exact():
-    """A hundred seeded problems with every format on A, B and C (FP16 / FP8 / BF16 C tiles
-    included), sizes on and off the tile grid, operands given directly or transposed, both
-    policies, copies made on the sender side where a BF16 tile needs them or at random.  One
+def test_random_small_integer_problems_over_all_formats_are_exact():
+    """A hundred seeded problems with every format on A, B (MXFP8 included) and C (FP16 / FP8 /
+    BF16 C tiles included), sizes on and off the tile grid, operands given directly or transposed, both
+    policies, copies made on the sender side where a BF16 or MXFP8 tile needs them or at random.  One
     nonzero per row of A and per column of B inside each reduction tile keeps every result an
     integer of magnitude at most 15, which every format holds, so C must be exact."""
     import torch
@@ -719,12 +719,15 @@ def test_random_small_integer_problems_over_all_five_formats_are_exact():
         K = Kf - (int(rng.integers(1, nb)) if ragged else 0)
         A, B = np.ascontiguousarray(A[:M, :K]), np.ascontiguousarray(B[:K, :N])
         C0 = rng.integers(-3, 4, (M, N)).astype(np.float64)
-        mA, mB, mC = rng.integers(0, 5, (MT, KT)), rng.integers(0, 5, (KT, NT)), rng.integers(0, 5, (MT, NT))
+        mA, mB, mC = rng.integers(0, 6, (MT, KT)), rng.integers(0, 6, (KT, NT)), rng.integers(0, 5, (MT, NT))
+        if case % 10 == 3:                               # MXFP8 everywhere: the block-scaled kernel where the tile size allows
+            mA[:], mB[:] = MXFP8, MXFP8
+            mC[:] = rng.integers(1, 5, (MT, NT))
         policy, tA, tB = int(rng.integers(0, 2)), int(rng.integers(0, 2)), int(rng.integers(0, 2))
         alpha, beta = float(rng.choice([-2, -1, 1, 2])), float(rng.choice([-1, 0, 1]))
         what = dict(case=case, nb=nb, M=M, N=N, K=K, policy=policy, tA=tA, tB=tB, alpha=alpha, beta=beta)
         if case % 20 == 0:
-            _say("five formats, random integers", what)
+            _say("all formats, random integers", what)
         want = alpha * (A @ B) + beta * C0
         assert np.abs(want).max() <= 15
         d = DeviceGemmMP(M, N, K, nb, policy=policy)
@@ -738,8 +741,8 @@ def test_random_small_integer_problems_over_all_five_formats_are_exact():
             if sender and d.ctx.conversion_bytes():
                 d.convert_tiles()
             d.run(alpha, beta)
-        except G.GemmMPError as e:                     # a BF16 tile under an FP32 / FP64 product
-            assert e.status == G.ESTATE and BF16 in set(mA.ravel()) | set(mB.ravel()), what
+        except G.GemmMPError as e:                     # a BF16 tile under an FP32 / FP64 product, an MXFP8 tile outside the block-scaled kernel
+            assert e.status == G.ESTATE and {BF16, MXFP8} & (set(mA.ravel()) | set(mB.ravel())), what
             d.convert_tiles()
             d.run(alpha, beta)
         got = d.unpack_tiles("C").cpu().numpy()
@@ -782,11 +785,21 @@ def test_mxfp8_tiles_pack_bit_for_bit_and_multiply_on_the_block_scaled_instructi
     Yb, _ = orc.store_tiles(Bp, nb, np.full((3, 2), MXFP8, dtype=np.uint16), mx_axis=1)
     assert np.array_equal(d.unpack_tiles("A").cpu().numpy(), Ya[:M, :K])
     assert np.array_equal(d.unpack_tiles("B").cpu().numpy(), Yb[:K, :N])
-    # what this build does not run
+    # outside the block-scaled kernel (here: FP64 C tiles) the products need the widened copies
     d.set_precision_map("C", np.full((2, 2), FP64, dtype=np.uint16))
     with pytest.raises(G.GemmMPError) as e:
         d.run(1.0, 0.0)
-    assert e.value.status == G.EUNSUPPORTED
+    assert e.value.status == G.ESTATE
+    assert d.convert_tiles() == (6 + 6) * nb * nb * 4            # an FP32 copy of every MXFP8 tile
+    d.run(1.0, 0.0)
+    Cg = np.zeros((2 * nb, 2 * nb))
+    Cg[:M, :N] = d.unpack_tiles("C").cpu().numpy()
+    w = W.Workload("mx64", 2 * nb, 2 * nb, 3 * nb, nb, 1.0, 0.0)
+    w.mapA, w.mapB = np.full((2, 3), MXFP8, dtype=np.uint16), np.full((3, 2), MXFP8, dtype=np.uint16)
+    w.mapC = np.full((2, 2), FP64, dtype=np.uint16)
+    side = OracleSide(w, Ap, Bp, None)
+    jobs = _all_jobs(w)
+    compare_jobs(side, jobs, 0, 1.0, 0.0, Cg, side.gemm(jobs, alpha=1.0, beta=0.0))
     # integers: exact; every block gets its own scale from a different largest entry
     for nb, MT, NT, KT in ((256, 2, 1, 3), (512, 1, 2, 2)):
         M, N, K = MT * nb, NT * nb, KT * nb
