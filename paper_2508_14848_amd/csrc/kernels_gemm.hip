@@ -1693,10 +1693,13 @@ __device__ __forceinline__ void big_load_scales(int (&d)[8], const BigScaleGeom 
 
 // One chunk held in `STAGE`.  On entry f[0] holds the fragments of its first half; on exit
 // those of the next chunk's first half.  S2: the chunk two ahead, requested into STAGE.
-// MX: sc holds this chunk's block scales (see big_load_scales), sa / sb are not used.
+// MX: sc holds this chunk's block scales (see big_load_scales), sa / sb are not used; `raw` are
+// the scale words of the following chunk, loaded by the caller just before this call: they are
+// taken over (shifted into place, into `nx`) right behind the wait in the middle of the chunk,
+// the one point where nothing else is in flight, so that no other wait for them is needed.
 template <int STAGE, bool MX>
 __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], const BigGeom &BG, const char *lds, const BigSource &S2,
-                                          int sa, int sb, const int (&sc)[8])
+                                          int sa, int sb, const int (&sc)[8], const int (&raw)[8], int (&nx)[8], int shift)
 {
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
@@ -1713,6 +1716,13 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // the next chunk, requested a chunk ago, has landed
 #endif
     __syncthreads();                                         // ... in every wave; and all are done reading this stage
+    if constexpr (MX) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) nx[t] = (int)((uint32_t)raw[t] >> shift);
+#if defined(__HIP_DEVICE_COMPILE__)
+        asm volatile("" : "+v"(nx[0]), "+v"(nx[1]), "+v"(nx[2]), "+v"(nx[3]), "+v"(nx[4]), "+v"(nx[5]), "+v"(nx[6]), "+v"(nx[7]));
+#endif
+    }
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
@@ -1837,19 +1847,20 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
                 S2.c = (c + 2 < n) ? c + 2 : c + 2 - n;
                 // MX: the scales of the chunk after the one being computed are fetched under it
                 // (past the end of the reduction: those of the last chunk again, unused)
+                int nx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
                 if constexpr (MX) big_load_scales(nsc, SG, cur_src.a, cur_src.b, nb, c + 1);
-                big_chunk<0, MX>(acc, f, BG, lds, S2, sa, sb, sc);
+                big_chunk<0, MX>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
                 if constexpr (MX) {
 #pragma unroll
-                    for (int t = 0; t < 8; ++t) sc[t] = (int)((uint32_t)nsc[t] >> SG.shift);
+                    for (int t = 0; t < 8; ++t) sc[t] = nx[t];
                     const bool wrap = c + 2 >= n && nbytes != 0;
                     big_load_scales(nsc, SG, wrap ? next_src.a : cur_src.a, wrap ? next_src.b : cur_src.b, nb, c + 2 < n ? c + 2 : wrap ? 0 : n - 1);
                 }
                 S2.c += 1;
-                big_chunk<1, MX>(acc, f, BG, lds, S2, sa, sb, sc);
+                big_chunk<1, MX>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
                 if constexpr (MX) {
 #pragma unroll
-                    for (int t = 0; t < 8; ++t) sc[t] = (int)((uint32_t)nsc[t] >> SG.shift);
+                    for (int t = 0; t < 8; ++t) sc[t] = nx[t];
                 }
             }
             lo = nlo;
