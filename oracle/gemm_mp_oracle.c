@@ -47,8 +47,9 @@
  * roundoff the formats order FP64 < FP32 < FP16 < BF16 < FP8.  5 is MXFP8: e4m3
  * elements with one power-of-two scale per block of 32 consecutive reduction
  * indices (the block-scaled format of the OCP microscaling specification)
- * instead of one per tile. */
-enum { P_FP64 = 0, P_FP32 = 1, P_FP16 = 2, P_FP8 = 3, P_BF16 = 4, P_MXFP8 = 5 };
+ * instead of one per tile; 6 is MXFP4, the same with e2m1 elements (magnitudes
+ * 0, 0.5, 1, 1.5, 2, 3, 4, 6). */
+enum { P_FP64 = 0, P_FP32 = 1, P_FP16 = 2, P_FP8 = 3, P_BF16 = 4, P_MXFP8 = 5, P_MXFP4 = 6 };
 
 /* Which product-precision reading is applied (see orc_product_precision). */
 enum { POLICY_OPERAND = 0, POLICY_C_TILE = 1 };
@@ -194,7 +195,49 @@ int32_t orc_mx_block(const double *x, int64_t stride, double *y, int64_t ystride
     return s;
 }
 
+/* FP4 e2m1: 1 fraction bit, emin 0, max finite 6, no infinity or NaN codes:
+ * overflow and infinities saturate to +-6; a NaN has no code and is stored as 0. */
+double orc_round_fp4(double x)
+{
+    if (isnan(x)) return 0.0;
+    if (isinf(x)) return copysign(6.0, x);
+    double r = round_to_format(x, 1, 0);
+    if (fabs(r) > 6.0) r = copysign(6.0, x);
+    return r;
+}
+uint8_t orc_fp4_bits(double y)
+{
+    uint8_t s = signbit(y) ? 8u : 0u;
+    double a = fabs(y);
+    if (a == 0.0) return s;
+    if (a == 0.5) return (uint8_t)(s | 1u);
+    int e = ilogb(a);
+    return (uint8_t)(s | ((uint8_t)(e + 1) << 1) | (ldexp(a, -e) > 1.0 ? 1u : 0u));
+}
+/* MXFP4: as orc_mx_block with e2m1 elements; 2 = exponent of the largest e2m1 binade. */
+int32_t orc_mx4_block(const double *x, int64_t stride, double *y, int64_t ystride)
+{
+    double mx = 0.0;
+    for (int k = 0; k < 32; ++k) { double a = fabs(x[k * stride]); if (a > mx) mx = a; }
+    int s = 0;
+    if (mx != 0.0 && !isinf(mx)) {
+        s = ilogb(mx) - 2;
+        if (s < -127) s = -127;
+        if (s > 127) s = 127;
+    }
+    for (int k = 0; k < 32; ++k) y[k * ystride] = orc_round_fp4(ldexp(x[k * stride], -s));
+    return s;
+}
+
 /* Vector forms for the tests. */
+void orc_mx4_blocks_array(const double *x, int64_t nblocks, double *y, uint8_t *codes, uint8_t *scale_codes)
+{
+    for (int64_t b = 0; b < nblocks; ++b) {
+        int32_t s = orc_mx4_block(x + 32 * b, 1, y + 32 * b, 1);
+        scale_codes[b] = (uint8_t)(s + 127);
+        for (int k = 0; k < 32; ++k) codes[32 * b + k] = orc_fp4_bits(y[32 * b + k]);
+    }
+}
 void orc_mx_blocks_array(const double *x, int64_t nblocks, double *y, uint8_t *codes, uint8_t *scale_codes)
 {
     for (int64_t b = 0; b < nblocks; ++b) {
@@ -281,6 +324,7 @@ static double unit_roundoff(int p)
     case P_FP16: return ldexp(1.0, -11);
     case P_BF16: return ldexp(1.0, -8);
     case P_MXFP8: return ldexp(1.0, -4);
+    case P_MXFP4: return ldexp(1.0, -2);
     default:     return ldexp(1.0, -4);      /* e4m3: 3 fraction bits */
     }
 }
@@ -354,14 +398,14 @@ void orc_store_tiles(const double *X, int64_t ld, int64_t rows, int64_t cols, in
             int p = map[I * CT + J];
             int32_t e = orc_scale_exponent(maxabs[I * CT + J], p);
             exps[I * CT + J] = e;
-            if (p == P_MXFP8) {
+            if (p == P_MXFP8 || p == P_MXFP4) {
                 /* the blocks run along the reduction index; Y receives the values the stored
                  * elements stand for, element * 2^s, which are exact in FP64 (and in FP32) */
                 double yb[32];
                 for (int32_t u = 0; u < nb; ++u)
                     for (int32_t k0 = 0; k0 < nb; k0 += 32) {
                         const double *x0 = mx_axis ? X + (I * nb + k0) * ld + J * nb + u : X + (I * nb + u) * ld + J * nb + k0;
-                        int32_t s = orc_mx_block(x0, mx_axis ? ld : 1, yb, 1);
+                        int32_t s = p == P_MXFP8 ? orc_mx_block(x0, mx_axis ? ld : 1, yb, 1) : orc_mx4_block(x0, mx_axis ? ld : 1, yb, 1);
                         for (int k = 0; k < 32; ++k) {
                             double *y0 = mx_axis ? Y + (I * nb + k0 + k) * ldy + J * nb + u : Y + (I * nb + u) * ldy + J * nb + k0 + k;
                             *y0 = ldexp(yb[k], s);
@@ -398,8 +442,9 @@ void orc_store_tiles(const double *X, int64_t ld, int64_t rows, int64_t cols, in
 static int holds_both(int pA, int pB)
 {
     if (pA == P_MXFP8 && pB == P_MXFP8) return P_MXFP8;
-    if (pA == P_MXFP8) pA = P_FP32;        /* block-scaled e4m3 numbers are FP32 numbers, and of no */
-    if (pB == P_MXFP8) pB = P_FP32;        /* smaller format here                                  */
+    if (pA == P_MXFP4 && pB == P_MXFP4) return P_MXFP4;
+    if (pA == P_MXFP8 || pA == P_MXFP4) pA = P_FP32;     /* block-scaled numbers are FP32 numbers, and of */
+    if (pB == P_MXFP8 || pB == P_MXFP4) pB = P_FP32;     /* no smaller format here                        */
     if (pA == P_FP64 || pB == P_FP64) return P_FP64;
     if (pA == P_FP32 || pB == P_FP32) return P_FP32;
     int h = (pA == P_FP16) || (pB == P_FP16), b = (pA == P_BF16) || (pB == P_BF16);
@@ -503,7 +548,7 @@ int32_t orc_gemm_jobs(int64_t M, int64_t N, int64_t K, int32_t nb,
             int ea = eA[I * KT + L], eb = eB[L * NT + J];
             /* an MXFP8 product multiplies the values its operands stand for (Ay, By hold them,
              * exponents 0) exactly and accumulates in FP32, like the other low products */
-            int esum = (q == P_FP16 || q == P_FP8 || q == P_BF16 || q == P_MXFP8) ? ea + eb : 0;
+            int esum = (q == P_FP16 || q == P_FP8 || q == P_BF16 || q == P_MXFP8 || q == P_MXFP4) ? ea + eb : 0;
 
             /* receiver-side conversion of the B tile columns this job needs */
 #pragma omp parallel for schedule(static)

@@ -11,7 +11,7 @@ import pytest
 from oracle import gemm_mp_oracle as orc
 from tests.exact import fma32, fma64
 
-FP64, FP32, FP16, FP8, BF16, MXFP8 = 0, 1, 2, 3, 4, 5
+FP64, FP32, FP16, FP8, BF16, MXFP8, MXFP4 = 0, 1, 2, 3, 4, 5, 6
 U = {FP64: 2.0 ** -53, FP32: 2.0 ** -24, FP16: 2.0 ** -11, FP8: 2.0 ** -4, BF16: 2.0 ** -8}
 
 
@@ -477,16 +477,19 @@ def test_mxfp8_tiles_follow_the_reduction_index_and_give_exact_integer_products(
     rel = np.abs(Yb - X) / np.abs(X)
     assert rel[np.abs(X) > np.abs(X).max() * 2.0 ** -60].max() <= 1.0 and np.median(rel) < 2.0 ** -4
     for pA, pB, pC, want in ((MXFP8, MXFP8, FP32, MXFP8), (MXFP8, MXFP8, FP64, MXFP8), (MXFP8, FP8, FP32, FP32), (MXFP8, FP16, FP64, FP32),
-                             (FP64, MXFP8, FP64, FP64), (FP64, MXFP8, FP32, FP32), (BF16, MXFP8, FP32, FP32)):
+                             (FP64, MXFP8, FP64, FP64), (FP64, MXFP8, FP32, FP32), (BF16, MXFP8, FP32, FP32),
+                             (MXFP4, MXFP4, FP32, MXFP4), (MXFP4, MXFP8, FP32, FP32), (MXFP4, FP64, FP64, FP64), (FP8, MXFP4, FP64, FP32)):
         assert orc.product_precision(pA, pB, pC, orc.POLICY_OPERAND) == want
     for trial in range(4):
         A = rng.integers(-3, 4, (M, K)).astype(np.float64)
         B = rng.integers(-3, 4, (K, N)).astype(np.float64)
         C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
-        mA = rng.choice([FP64, FP32, FP16, FP8, BF16, MXFP8], (MT, KT)).astype(np.uint16)
-        mB = rng.choice([FP64, FP32, FP16, FP8, BF16, MXFP8], (KT, NT)).astype(np.uint16)
+        mA = rng.choice([FP64, FP32, FP16, FP8, BF16, MXFP8, MXFP4], (MT, KT)).astype(np.uint16)
+        mB = rng.choice([FP64, FP32, FP16, FP8, BF16, MXFP8, MXFP4], (KT, NT)).astype(np.uint16)
         if trial == 0:
             mA[:], mB[:] = MXFP8, MXFP8
+        if trial == 1:
+            mA[:], mB[:] = MXFP4, MXFP4
         mC = rng.integers(0, 2, (MT, NT)).astype(np.uint16)
         Ay, eA = orc.store_tiles(A, nb, mA, mx_axis=0)
         By, eB = orc.store_tiles(B, nb, mB, mx_axis=1)

@@ -185,3 +185,30 @@ def test_mxfp8_blocks_scale_window_nearest_elements_and_exactness():
     # the E8M0 range is kept
     y, codes, scales = orc.mx_blocks(np.full(32, 1e-60))
     assert scales[0] == 0
+
+
+def test_mxfp4_blocks_scale_window_and_nearest_e2m1_elements():
+    """MXFP4: e2m1 elements (magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6; code = sign, two exponent bits,
+    one fraction bit), scale 2^(floor(log2 max) - 2); every element is the grid value nearest to
+    x * 2^-s with ties to the even code and saturation at 6 (the grid is written out here)."""
+    grid = [Fraction(0), Fraction(1, 2), Fraction(1), Fraction(3, 2), Fraction(2), Fraction(3), Fraction(4), Fraction(6)]
+    rng = np.random.default_rng(10)
+    x = rng.standard_normal((300, 32)) * np.exp(rng.uniform(-40, 40, (300, 1))) * np.exp(rng.uniform(-3, 0, (300, 32)))
+    x[0, :8] = [0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0, 4.0]       # ties of the grid at scale 1 (largest entry 5 -> s = 0)
+    x[0, 8:] = 0.0
+    y, codes, scales = orc.mx4_blocks(x)
+    for b in range(300):
+        s = int(scales[b]) - 127
+        m = np.abs(x[b]).max()
+        assert s == int(np.floor(np.log2(m))) - 2 and 4.0 <= m * 2.0 ** -s < 8.0
+        for k in range(32):
+            v = abs(Fraction(float(np.ldexp(x[b, k], -s))))
+            best = min(range(8), key=lambda c: (abs(grid[c] - v), c & 1))          # nearest, ties to the even code
+            if v > 6:
+                best = 7
+            assert int(codes[b, k]) & 7 == best and Fraction(float(abs(y[b, k]))) == grid[best], (b, k, float(v))
+            assert (int(codes[b, k]) >> 3) == (1 if x[b, k] < 0 and best else int(codes[b, k]) >> 3)
+    assert list(y[0, :8]) == [0.0, 1.0, 1.0, 2.0, 2.0, 4.0, 4.0, 4.0]
+    ints = rng.integers(-3, 4, (40, 32)).astype(np.float64)
+    y, codes, scales = orc.mx4_blocks(ints)
+    assert np.array_equal(np.ldexp(y, (scales.astype(np.int64) - 127)[:, None]), ints)
