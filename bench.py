@@ -170,10 +170,11 @@ def main():
 
     st = d.ctx.get_stats()
     flops_total = 2.0 * w.M * w.N * w.K
-    assert abs(sum(st["flops"]) + st["flops_bf16"] + st["flops_mxfp8"] - flops_total) < 1e-6 * flops_total
+    assert abs(sum(st["flops"]) + st["flops_bf16"] + st["flops_mxfp8"] + st["flops_mxfp4"] - flops_total) < 1e-6 * flops_total
     t_roof = sum(f / (p * 1e12) for f, p in zip(st["flops"], PEAK_TFLOPS))          # seconds
     t_roof += st["flops_bf16"] / (PEAK_TFLOPS[2] * 1e12)                             # BF16 peak = FP16 peak
     t_roof += st["flops_mxfp8"] / (PEAK_TFLOPS[3] * 1e12)                            # block-scaled FP8: the FP8 peak
+    t_roof += st["flops_mxfp4"] / (10066.4 * 1e12)                                   # block-scaled FP4: 10.1 PFLOP/s
     run_ms = float(np.mean(stage_ms["run"]))
     achieved = flops_total / (run_ms * 1e-3) / 1e12
     peak_mix = flops_total / t_roof / 1e12

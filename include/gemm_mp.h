@@ -45,7 +45,11 @@
  * elements rounded once and saturating; no tile scale.  Where every product of a C tile is
  * MXFP8 x MXFP8 (C tile not FP64, tile_nb a multiple of 256) the tile runs on the block-scaled
  * matrix instruction; any other product with an MXFP8 operand reads widened copies of the MXFP8
- * tiles from the sender-side workspace: see gemm_mp_run.
+ * tiles from the sender-side workspace: see gemm_mp_run.  MXFP4 tiles (code 6; A and B only)
+ * are the same with e2m1 elements (magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6; scale
+ * 2^(floor(log2 max|x|) - 2)): tile_nb^2/2 element bytes, two elements per byte with the lower
+ * reduction index in the low four bits, then the tile_nb^2/32 scale bytes; block-scaled
+ * instruction where every product of a C tile is MXFP4 x MXFP4 and tile_nb is a multiple of 512.
  *
  * C tiles stored in FP16 / FP8 (formats beyond FP64 / FP32 are what the paper's
  * Section 6 leaves open): such a tile is a storage format only.  Its products
@@ -74,7 +78,7 @@ typedef void *gemm_mp_stream;           /* a hipStream_t */
  * The code is a name, not a rank: by unit roundoff (2^-53, 2^-24, 2^-11, 2^-8, 2^-4) the formats
  * order FP64, FP32, FP16, BF16, FP8. */
 enum { GEMM_MP_FP64 = 0, GEMM_MP_FP32 = 1, GEMM_MP_FP16 = 2, GEMM_MP_FP8_E4M3 = 3, GEMM_MP_BF16 = 4,
-       GEMM_MP_MXFP8 = 5 };
+       GEMM_MP_MXFP8 = 5, GEMM_MP_MXFP4 = 6 };
 
 enum {
     GEMM_MP_OK = 0,
@@ -112,6 +116,9 @@ typedef struct gemm_mp_stats {
     int64_t products_mxfp8;  /* the same for precision code 5 */
     double flops_mxfp8;
     int64_t tiles_mxfp8[3];
+    int64_t products_mxfp4;  /* the same for precision code 6 */
+    double flops_mxfp4;
+    int64_t tiles_mxfp4[3];
 } gemm_mp_stats;
 
 /* Create a context for C(MxN) = A(MxK) * B(KxN) with square tiles of tile_nb (Section 4:
@@ -142,7 +149,7 @@ int gemm_mp_set_transposed(gemm_mp_ctx *ctx, char which, int transposed);
 
 /* Give the precision map of matrix `which` ('A', 'B' or 'C'): rows x cols codes, row-major,
  * host memory, copied (Section 5.2).  rows/cols must equal the matrix's tile counts (EINVAL),
- * codes must be 0..5 (EINVAL); MXFP8 C tiles are EUNSUPPORTED.  Any earlier binding and packed
+ * codes must be 0..6 (EINVAL); MXFP8 / MXFP4 C tiles are EUNSUPPORTED.  Any earlier binding and packed
  * data of that matrix are forgotten.  Host only. */
 int gemm_mp_set_precision_map(gemm_mp_ctx *ctx, char which, const uint16_t *map_host,
                               int32_t rows, int32_t cols);
@@ -199,11 +206,12 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *ctx, char which, const double *dense_dev, in
  * operand is BF16, or FP8 converted on the way like under an FP16 product); a BF16 tile under
  * an FP32 / FP64 product is read as the widened copy in the sender-side workspace, and the call
  * is ESTATE until gemm_mp_convert_tiles has filled it.
- * MXFP8 tiles: a C tile whose products are all MXFP8 x MXFP8 (not an FP64 tile, tile_nb a
- * multiple of 256) needs nothing; any other product with an MXFP8 operand is computed from the
- * exact FP32 / FP64 copies of the MXFP8 tiles in the sender-side workspace (an MXFP8 x MXFP8
- * product then as exact FP32 products with FP32 accumulation, which is what it is), and the
- * call is ESTATE until gemm_mp_convert_tiles has filled it. */
+ * MXFP8 / MXFP4 tiles: a C tile whose products are all MXFP8 x MXFP8 or all MXFP4 x MXFP4 (not an
+ * FP64 tile, tile_nb a multiple of 256 resp. 512) needs nothing; any other product with such an
+ * operand is computed from the exact FP32 / FP64 copies of those tiles in the sender-side
+ * workspace (a product of two block-scaled tiles then as exact FP32 products with FP32
+ * accumulation, which is what it is), and the call is ESTATE until gemm_mp_convert_tiles has
+ * filled it. */
 int gemm_mp_run(gemm_mp_ctx *ctx, double alpha, double beta, gemm_mp_stream stream);
 
 /* Sender-side conversion (optional).  The paper converts at the receiver: a tile travels in its

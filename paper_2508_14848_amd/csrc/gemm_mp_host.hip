@@ -50,9 +50,9 @@ struct gemm_mp_ctx {
     Matrix mat[3];
     bool sched_current = false;
     std::vector<uint8_t> q;
-    std::vector<WorkItem> items[4];   // regions of [0] FP64 C tiles, [1] C tiles accumulated in FP32 (stored
+    std::vector<WorkItem> items[5];   // regions of [0] FP64 C tiles, [1] C tiles accumulated in FP32 (stored
                                       // FP32 / FP16 / FP8), [2] those of them whose products are all
-                                      // FP8 x FP8 (256 x 256 regions), [3] the same for MXFP8 x MXFP8
+                                      // FP8 x FP8 (256 x 256 regions), [3] / [4] the same for MXFP8 x MXFP8 / MXFP4 x MXFP4
     uint8_t *d_q = nullptr;
     ProductDesc *d_prod = nullptr;    // one record per task (+ 2 padding records), filled on the device
     WorkItem *d_items = nullptr;      // the three lists, [0] first
@@ -116,9 +116,7 @@ void layout(gemm_mp_ctx *c, Matrix &m, bool is_c)
     uint64_t off = 0;
     for (int t = 0; t < m.ntiles(); ++t) {
         m.offset[t] = off;
-        uint64_t bytes = elems * (uint64_t)elem_bytes(m.map[t]);
-        if (m.map[t] == GEMM_MP_MXFP8) bytes += elems / 32;              // the block scales follow the elements
-        off += (bytes + 255u) & ~(uint64_t)255u;
+        off += (tile_bytes_of(m.map[t], elems) + 255u) & ~(uint64_t)255u;
     }
     m.low.clear();
     for (int t = 0; is_c && t < m.ntiles(); ++t)
@@ -212,14 +210,14 @@ int check_dense(const void *p, int64_t ld, int64_t cols)
 
 double unit_roundoff(int p)
 {
-    static const double u[6] = {0x1p-53, 0x1p-24, 0x1p-11, 0x1p-4, 0x1p-8, 0x1p-4};
+    static const double u[7] = {0x1p-53, 0x1p-24, 0x1p-11, 0x1p-4, 0x1p-8, 0x1p-4, 0x1p-2};
     return u[p];
 }
 
 // Relative cost of one tile product by precision: inverse matrix-core peak (FP64 : FP32 :
 // FP16 : FP8 = 1/78.6 : 1/157.3 : 1/2516.6 : 1/5033.2 TFLOP/s) plus a floor for the operand
 // traffic that the low precisions cannot hide.
-const double kCost[6] = {64.0, 32.0, 3.0, 2.0, 3.0, 2.0};
+const double kCost[7] = {64.0, 32.0, 3.0, 2.0, 3.0, 2.0, 1.5};
 
 // The schedule.  Every C tile is cut into (nb/128)^2 owner regions; a region's cost is the
 // sum over its reduction tiles of the cost of that product's precision.  C tiles are sorted by
@@ -242,6 +240,7 @@ void build_schedule(gemm_mp_ctx *c)
                 c->q[((size_t)I * NT + J) * KT + L] = (uint8_t)q;
                 if (q == GEMM_MP_BF16) c->stats.products_bf16 += 1;
                 else if (q == GEMM_MP_MXFP8) c->stats.products_mxfp8 += 1;
+                else if (q == GEMM_MP_MXFP4) c->stats.products_mxfp4 += 1;
                 else c->stats.products[q] += 1;
                 cost[(size_t)I * NT + J] += kCost[q];
             }
@@ -250,6 +249,7 @@ void build_schedule(gemm_mp_ctx *c)
     for (int q = 0; q < 4; ++q) c->stats.flops[q] = f * (double)c->stats.products[q];
     c->stats.flops_bf16 = f * (double)c->stats.products_bf16;
     c->stats.flops_mxfp8 = f * (double)c->stats.products_mxfp8;
+    c->stats.flops_mxfp4 = f * (double)c->stats.products_mxfp4;
     c->has_bf16 = false;
     for (int w = 0; w < 2; ++w)
         for (uint16_t p : c->mat[w].map) c->has_bf16 |= p == GEMM_MP_BF16;
@@ -260,22 +260,23 @@ void build_schedule(gemm_mp_ctx *c)
     // at FP32 where both operands are MXFP8 (exact products, FP32 accumulation: what an MXFP8
     // product is), at the product's own FP32 / FP64 otherwise.  c->q then holds the precision
     // the kernels work at, the statistics keep the product's nominal one.
-    std::vector<uint8_t> all_mx((size_t)MT * NT, 0);
+    std::vector<uint8_t> all_mx((size_t)MT * NT, 0);         // 1: all MXFP8 x MXFP8, 2: all MXFP4 x MXFP4 (tile size a multiple of 512)
     c->mx_needs_copies = false;
     for (int I = 0; I < MT; ++I)
         for (int J = 0; J < NT; ++J) {
-            bool all = C.map[I * NT + J] != GEMM_MP_FP64 && KT > 0 && c->nb % kMacroFp8 == 0, any = false;
+            const bool fits = C.map[I * NT + J] != GEMM_MP_FP64 && KT > 0;
+            bool all8 = fits && c->nb % kMacroFp8 == 0, all4 = fits && c->nb % (2 * kMacroFp8) == 0, any = false;
             for (int L = 0; L < KT; ++L) {
-                const bool mx = A.map[I * KT + L] == GEMM_MP_MXFP8 || B.map[L * NT + J] == GEMM_MP_MXFP8;
-                any |= mx;
-                all &= c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_MXFP8;
+                any |= is_block_scaled(A.map[I * KT + L]) || is_block_scaled(B.map[L * NT + J]);
+                all8 &= c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_MXFP8;
+                all4 &= c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_MXFP4;
             }
-            all_mx[(size_t)I * NT + J] = all;
-            c->mx_needs_copies |= any && !all;
-            if (!all)
+            all_mx[(size_t)I * NT + J] = all8 ? 1 : all4 ? 2 : 0;
+            c->mx_needs_copies |= any && !all8 && !all4;
+            if (!all8 && !all4)
                 for (int L = 0; L < KT; ++L) {
                     uint8_t &q = c->q[((size_t)I * NT + J) * KT + L];
-                    if (q == GEMM_MP_MXFP8) q = GEMM_MP_FP32;
+                    if (is_block_scaled(q)) q = GEMM_MP_FP32;
                 }
         }
 
@@ -289,7 +290,7 @@ void build_schedule(gemm_mp_ctx *c)
             for (int L = 0; L < KT; ++L) {
                 const int q = c->q[((size_t)I * NT + J) * KT + L];
                 const int pa = A.map[I * KT + L], pb = B.map[L * NT + J];
-                if (q == GEMM_MP_MXFP8) continue;                             // block-scaled kernel: no copies
+                if (is_block_scaled(q)) continue;                             // block-scaled kernel: no copies
                 if (pa != q) c->conv_off[0][((size_t)I * KT + L) * kConvSlots + q] = 0;
                 if (pb != q) c->conv_off[1][((size_t)L * NT + J) * kConvSlots + q] = 0;
                 // the GEMM kernels take BF16 data only as operands of a BF16 product
@@ -311,6 +312,7 @@ void build_schedule(gemm_mp_ctx *c)
             const int p = c->mat[w].map[t];
             if (p == GEMM_MP_BF16) c->stats.tiles_bf16[w] += 1;
             else if (p == GEMM_MP_MXFP8) c->stats.tiles_mxfp8[w] += 1;
+            else if (p == GEMM_MP_MXFP4) c->stats.tiles_mxfp4[w] += 1;
             else c->stats.tiles[w][p] += 1;
         }
         c->stats.packed_bytes[w] = c->mat[w].bytes;
@@ -342,12 +344,12 @@ void build_schedule(gemm_mp_ctx *c)
             else c->mixed32 |= mixed;
         }
     constexpr int kBins = 8;
-    for (int list = 0; list < 4; ++list) {
+    for (int list = 0; list < 5; ++list) {
         const int mr = c->nb / (list >= 2 ? kMacroFp8 : kMacro);
         const size_t per_tile = (size_t)mr * mr;
         std::vector<int> order;
         for (int t = 0; t < MT * NT; ++t) {
-            const int which = C.map[t] == GEMM_MP_FP64 ? 0 : all_fp8[t] ? 2 : all_mx[t] ? 3 : 1;
+            const int which = C.map[t] == GEMM_MP_FP64 ? 0 : all_fp8[t] ? 2 : all_mx[t] ? 2 + all_mx[t] : 1;
             if (which == list) order.push_back(t);
         }
         std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cost[a] > cost[b]; });
@@ -380,7 +382,7 @@ void build_schedule(gemm_mp_ctx *c)
             }
         }
     }
-    c->stats.work_items = (int64_t)(c->items[0].size() + c->items[1].size() + c->items[2].size() + c->items[3].size());
+    c->stats.work_items = (int64_t)(c->items[0].size() + c->items[1].size() + c->items[2].size() + c->items[3].size() + c->items[4].size());
     c->sched_current = true;
 }
 
@@ -392,13 +394,14 @@ int upload_schedule(gemm_mp_ctx *c)
     if ((rc = dev_alloc(&c->d_q, c->q.size()))) return rc;
     if ((rc = dev_alloc(&c->d_prod, c->q.size() + 2))) return rc;
     HIP_TRY(hipMemset(c->d_prod, 0, (c->q.size() + 2) * sizeof(ProductDesc)));
-    const size_t n0 = c->items[0].size(), n1 = c->items[1].size(), n2 = c->items[2].size(), n3 = c->items[3].size();
-    if ((rc = dev_alloc(&c->d_items, n0 + n1 + n2 + n3))) return rc;
+    const size_t n0 = c->items[0].size(), n1 = c->items[1].size(), n2 = c->items[2].size(), n3 = c->items[3].size(), n4 = c->items[4].size();
+    if ((rc = dev_alloc(&c->d_items, n0 + n1 + n2 + n3 + n4))) return rc;
     HIP_TRY(hipMemcpy(c->d_q, c->q.data(), c->q.size(), hipMemcpyHostToDevice));
     if (n0) HIP_TRY(hipMemcpy(c->d_items, c->items[0].data(), n0 * sizeof(WorkItem), hipMemcpyHostToDevice));
     if (n1) HIP_TRY(hipMemcpy(c->d_items + n0, c->items[1].data(), n1 * sizeof(WorkItem), hipMemcpyHostToDevice));
     if (n2) HIP_TRY(hipMemcpy(c->d_items + n0 + n1, c->items[2].data(), n2 * sizeof(WorkItem), hipMemcpyHostToDevice));
     if (n3) HIP_TRY(hipMemcpy(c->d_items + n0 + n1 + n2, c->items[3].data(), n3 * sizeof(WorkItem), hipMemcpyHostToDevice));
+    if (n4) HIP_TRY(hipMemcpy(c->d_items + n0 + n1 + n2 + n3, c->items[4].data(), n4 * sizeof(WorkItem), hipMemcpyHostToDevice));
     return GEMM_MP_OK;
 }
 
@@ -472,10 +475,10 @@ int gemm_mp_set_precision_map(gemm_mp_ctx *c, char which, const uint16_t *map, i
     Matrix &m = c->mat[w];
     if (rows != m.rows_t || cols != m.cols_t) return GEMM_MP_EINVAL;
     for (int t = 0; t < m.ntiles(); ++t)
-        if (map[t] > GEMM_MP_MXFP8) return GEMM_MP_EINVAL;
+        if (map[t] > GEMM_MP_MXFP4) return GEMM_MP_EINVAL;
     if (w == 2)
         for (int t = 0; t < m.ntiles(); ++t)
-            if (map[t] == GEMM_MP_MXFP8) return GEMM_MP_EUNSUPPORTED;
+            if (is_block_scaled(map[t])) return GEMM_MP_EUNSUPPORTED;
     return install_map(c, w, map);
 }
 
@@ -588,7 +591,7 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *c, char which, const double *dense, int64_t 
     else
         HIP_TRY(launch_pack(dense, ld, m.rows, m.cols, m.rows_t, m.cols_t, c->nb, w == 1, false, view_of(m), s));
     bool has_mx = false;
-    for (uint16_t p : m.map) has_mx |= p == GEMM_MP_MXFP8;
+    for (uint16_t p : m.map) has_mx |= is_block_scaled(p);
     if (has_mx)
         HIP_TRY(launch_pack_mx(dense, m.transposed ? 1 : ld, m.transposed ? ld : 1, m.rows, m.cols, m.rows_t, m.cols_t, c->nb, w == 1,
                                view_of(m), s));
@@ -657,6 +660,8 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
     a.n_items8 = (int32_t)c->items[2].size();
     a.items_mx = a.items8 + c->items[2].size();
     a.n_items_mx = (int32_t)c->items[3].size();
+    a.items_mx4 = a.items_mx + c->items[3].size();
+    a.n_items_mx4 = (int32_t)c->items[4].size();
     a.mixed32 = c->mixed32 ? 1 : 0;
     a.mixed64 = c->mixed64 ? 1 : 0;
     a.bf16 = c->has_bf16 ? 1 : 0;
@@ -787,7 +792,7 @@ int gemm_mp_get_stats(gemm_mp_ctx *c, gemm_mp_stats *out)
 
 int gemm_mp_product_precision(int pA, int pB, int pC, int policy)
 {
-    if (pA < 0 || pA > 5 || pB < 0 || pB > 5 || pC < 0 || pC > 4) return -1;
+    if (pA < 0 || pA > 6 || pB < 0 || pB > 6 || pC < 0 || pC > 4) return -1;
     if (policy != GEMM_MP_POLICY_OPERAND && policy != GEMM_MP_POLICY_C_TILE) return -1;
     return product_precision(pA, pB, pC, policy);
 }

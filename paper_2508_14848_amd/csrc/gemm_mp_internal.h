@@ -18,6 +18,14 @@ constexpr int kLowChunk = 4096;   // elements one workgroup handles in the passe
 
 // Bytes per element of each precision code.
 __host__ __device__ inline int elem_bytes(int p) { return p == 0 ? 8 : p == 1 ? 4 : (p == 2 || p == 4) ? 2 : 1; }
+// Bytes of a packed tile of nb x nb elements (block-scaled tiles: elements, then one scale byte per 32).
+__host__ __device__ inline uint64_t tile_bytes_of(int p, uint64_t elems)
+{
+    if (p == GEMM_MP_MXFP8) return elems + elems / 32;
+    if (p == GEMM_MP_MXFP4) return elems / 2 + elems / 32;
+    return elems * (uint64_t)elem_bytes(p);
+}
+__host__ __device__ inline bool is_block_scaled(int p) { return p == GEMM_MP_MXFP8 || p == GEMM_MP_MXFP4; }
 
 // Product precision (code) for stored precisions pA, pB, C tile precision pC.
 __host__ __device__ inline int product_precision(int pA, int pB, int pC, int policy)
@@ -26,8 +34,9 @@ __host__ __device__ inline int product_precision(int pA, int pB, int pC, int pol
     if (policy == GEMM_MP_POLICY_C_TILE) return cap;
     // the smallest format that holds both operands' numbers: FP64 > FP32 > {FP16, BF16} > FP8
     if (pA == GEMM_MP_MXFP8 && pB == GEMM_MP_MXFP8) return GEMM_MP_MXFP8;
-    if (pA == GEMM_MP_MXFP8) pA = GEMM_MP_FP32;      // block-scaled e4m3 numbers are FP32 numbers
-    if (pB == GEMM_MP_MXFP8) pB = GEMM_MP_FP32;
+    if (pA == GEMM_MP_MXFP4 && pB == GEMM_MP_MXFP4) return GEMM_MP_MXFP4;
+    if (pA == GEMM_MP_MXFP8 || pA == GEMM_MP_MXFP4) pA = GEMM_MP_FP32;      // block-scaled numbers are FP32 numbers
+    if (pB == GEMM_MP_MXFP8 || pB == GEMM_MP_MXFP4) pB = GEMM_MP_FP32;
     int q;
     const bool h = pA == GEMM_MP_FP16 || pB == GEMM_MP_FP16, b = pA == GEMM_MP_BF16 || pB == GEMM_MP_BF16;
     if (pA == GEMM_MP_FP64 || pB == GEMM_MP_FP64) q = GEMM_MP_FP64;
@@ -94,7 +103,8 @@ struct GemmArgs {
     const WorkItem *items32;  // owner regions of FP32 C tiles, launch order
     const WorkItem *items8;   // 256 x 256 regions of FP32 C tiles made of FP8 x FP8 products only
     const WorkItem *items_mx; // the same of tiles made of MXFP8 x MXFP8 products only
-    int32_t n_items64, n_items32, n_items8, n_items_mx;
+    const WorkItem *items_mx4;// ... of MXFP4 x MXFP4 products only
+    int32_t n_items64, n_items32, n_items8, n_items_mx, n_items_mx4;
     int32_t mixed32;         // some region of items32 has an FP16 / BF16 product with an operand stored in FP8
     int32_t mixed64;         // the same for items64
     int32_t bf16;            // some tile of A or B is stored in BF16

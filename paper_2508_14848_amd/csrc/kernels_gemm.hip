@@ -6,8 +6,8 @@
 // ever touches that region, so there are no atomics and the result is reproducible.  Regions
 // are 128 x 128 (gemm_mp_owner_kernel: instances for FP64 and for FP32 C tiles, with and without
 // the two options described below), or
-// 256 x 256 for FP32 C tiles whose products are all FP8 x FP8 or all MXFP8 x MXFP8
-// (gemm_mp_fp8_region_kernel, at the end of this file).
+// 256 x 256 for FP32 C tiles whose products are all FP8 x FP8, all MXFP8 x MXFP8 or all
+// MXFP4 x MXFP4 (gemm_mp_fp8_region_kernel, at the end of this file).
 //
 // Data path of one reduction chunk (128 bytes of converted reduction index per row, i.e.
 // 16 FP64 / 32 FP32 / 64 FP16 / 128 FP8 values) in the 128 x 128 kernels:
@@ -1682,52 +1682,81 @@ struct BigScaleGeom {
     int soa, sob;        // byte offset of this lane's scale row, A block 0 / B block 0, from the tile's start
     int shift;           // 8 * (lane / 32)
 };
-__device__ __forceinline__ void big_load_scales(int (&d)[8], const BigScaleGeom &SG, uint64_t a, uint64_t b, int nb, int c)
+// FMT 1 (MXFP8): four scale bytes per row and chunk, d[0..7].  FMT 2 (MXFP4): a chunk holds 256
+// reduction indices, eight scale bytes per row: those of its first half in d[0..7], of its second
+// in d[8..15].
+template <int FMT>
+__device__ __forceinline__ void big_load_scales(int (&d)[16], const BigScaleGeom &SG, uint64_t a, uint64_t b, int nb, int c)
 {
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        d[t] = (int)*(const uint32_t *)(uintptr_t)(a + (uint64_t)(SG.soa + t * nb + 4 * c));
-        d[4 + t] = (int)*(const uint32_t *)(uintptr_t)(b + (uint64_t)(SG.sob + t * nb + 4 * c));
+        if constexpr (FMT == 2) {
+            const u32x2 x = *(const u32x2 *)(uintptr_t)(a + (uint64_t)(SG.soa + t * nb + 8 * c));
+            const u32x2 y = *(const u32x2 *)(uintptr_t)(b + (uint64_t)(SG.sob + t * nb + 8 * c));
+            d[t] = (int)x.x; d[8 + t] = (int)x.y; d[4 + t] = (int)y.x; d[12 + t] = (int)y.y;
+        } else {
+            d[t] = (int)*(const uint32_t *)(uintptr_t)(a + (uint64_t)(SG.soa + t * nb + 4 * c));
+            d[4 + t] = (int)*(const uint32_t *)(uintptr_t)(b + (uint64_t)(SG.sob + t * nb + 4 * c));
+        }
     }
+}
+// The FP4 operand of reduction step j (0, 1) of a half: 16 of the fragment's 32 bytes.
+__device__ __forceinline__ i8v big_fp4_operand(const i8v &f, int j)
+{
+    return j ? i8v{f[4], f[5], f[6], f[7], 0, 0, 0, 0} : i8v{f[0], f[1], f[2], f[3], 0, 0, 0, 0};
 }
 
 // One chunk held in `STAGE`.  On entry f[0] holds the fragments of its first half; on exit
 // those of the next chunk's first half.  S2: the chunk two ahead, requested into STAGE.
-// MX: sc holds this chunk's block scales (see big_load_scales), sa / sb are not used; `raw` are
+// FMT 2 (MXFP4): a half holds two reduction steps of 64 four-bit elements; the first step's MFMAs
+// carry the half's other instructions, the second step's follow.
+// FMT != 0: sc holds this chunk's block scales (see big_load_scales), sa / sb are not used; `raw` are
 // the scale words of the following chunk, loaded by the caller just before this call: they are
 // taken over (shifted into place, into `nx`) right behind the wait in the middle of the chunk,
 // the one point where nothing else is in flight, so that no other wait for them is needed.
-template <int STAGE, bool MX>
+template <int STAGE, int FMT>
 __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], const BigGeom &BG, const char *lds, const BigSource &S2,
-                                          int sa, int sb, const int (&sc)[8], const int (&raw)[8], int (&nx)[8], int shift)
+                                          int sa, int sb, const int (&sc)[16], const int (&raw)[16], int (&nx)[16], int shift)
 {
+    constexpr bool MX = FMT == 1;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
-            if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sc[mt], 0, sc[4 + nt]);
+            if constexpr (FMT == 2) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[0][mt], 0), big_fp4_operand(f[0][4 + nt], 0), acc[mt][nt], 4, 4, 0, sc[mt], 0, sc[4 + nt]);
+            else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sc[mt], 0, sc[4 + nt]);
             else acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
             SCHED_FENCE();
             const int k = mt * 4 + nt;                       // second half's fragments, 16 bytes per position: B first
             big_read_half(f[1][((k >> 1) + 4) & 7], BG, lds, STAGE, 1, ((k >> 1) + 4) & 7, k & 1);
             SCHED_FENCE();
         }
+    if constexpr (FMT == 2) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[0][mt], 1), big_fp4_operand(f[0][4 + nt], 1), acc[mt][nt], 4, 4, 2, sc[mt], 2, sc[4 + nt]);
+    }
 #if defined(__HIP_DEVICE_COMPILE__)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // the next chunk, requested a chunk ago, has landed
 #endif
     __syncthreads();                                         // ... in every wave; and all are done reading this stage
-    if constexpr (MX) {
+    if constexpr (FMT != 0) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) nx[t] = (int)((uint32_t)raw[t] >> shift);
+        for (int t = 0; t < (FMT == 2 ? 16 : 8); ++t) nx[t] = (int)((uint32_t)raw[t] >> shift);
 #if defined(__HIP_DEVICE_COMPILE__)
         asm volatile("" : "+v"(nx[0]), "+v"(nx[1]), "+v"(nx[2]), "+v"(nx[3]), "+v"(nx[4]), "+v"(nx[5]), "+v"(nx[6]), "+v"(nx[7]));
+        if constexpr (FMT == 2)
+            asm volatile("" : "+v"(nx[8]), "+v"(nx[9]), "+v"(nx[10]), "+v"(nx[11]), "+v"(nx[12]), "+v"(nx[13]), "+v"(nx[14]), "+v"(nx[15]));
 #endif
     }
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
-            if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 2, sc[mt], 2, sc[4 + nt]);
+            if constexpr (FMT == 2) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[1][mt], 0), big_fp4_operand(f[1][4 + nt], 0), acc[mt][nt], 4, 4, 0, sc[8 + mt], 0, sc[12 + nt]);
+            else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 2, sc[mt], 2, sc[4 + nt]);
             else acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
             SCHED_FENCE();
             const int k = mt * 4 + nt;
@@ -1735,13 +1764,23 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
             big_request(S2, BG, STAGE, k);
             SCHED_FENCE();
         }
+    if constexpr (FMT == 2) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[1][mt], 1), big_fp4_operand(f[1][4 + nt], 1), acc[mt][nt], 4, 4, 2, sc[8 + mt], 2, sc[12 + nt]);
+    }
 }
 
 // MX: the operand tiles are MXFP8 (block scales behind the elements, no tile scale).  A lane's 32
 // operand bytes of a 64-index step are then the 16 bytes at index 16 g of the step's first 32
 // indices and the 16 bytes at 16 g of its second 32 (that is how the instruction pairs data
 // with block scales), instead of 32 consecutive ones.
-template <bool MX>
+// FMT 2: MXFP4 tiles: half a byte per element, so a tile row is nb / 2 bytes and a chunk (128
+// bytes of each row) 256 reduction indices; a lane's 16 bytes per reduction step are one block of
+// 32 elements, scaled by that lane's own byte, and the fragment reads are those of FMT 1.
+template <int FMT>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 {
@@ -1753,6 +1792,8 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     const int tileC = (int)(uint32_t)itw;
     const ArgsPtr K0 = args();
     const int nb = K0->nb, kt = K0->kt_eff;
+    constexpr bool MX = FMT != 0;
+    const int pitch = FMT == 2 ? nb / 2 : nb;                // bytes of a tile row
     const int arow0 = (int)((itw >> 32) & 0xffffu) * kBigMacro, brow0 = (int)((itw >> 48) & 0xffffu) * kBigMacro;
     const ProductDesc *prod = K0->prod + (int64_t)tileC * K0->KT;
 
@@ -1760,12 +1801,12 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     {
         const int r = lane >> 3, slot = lane & 7;
         const int seg = slot ^ (r >> 1);                     // instruction 0; odd instructions: ^ 4
-        BG.voff[0][0] = (arow0 + wave * 64 + r) * nb + seg * 16;
-        BG.voff[1][0] = (brow0 + wave * 64 + r) * nb + seg * 16;
+        BG.voff[0][0] = (arow0 + wave * 64 + r) * pitch + seg * 16;
+        BG.voff[1][0] = (brow0 + wave * 64 + r) * pitch + seg * 16;
         BG.voff[0][1] = BG.voff[0][0] ^ 64;
         BG.voff[1][1] = BG.voff[1][0] ^ 64;
         BG.dst = (unsigned)uni(wave * (64 * kRowBytes));
-        BG.rows8 = 8 * nb;
+        BG.rows8 = 8 * pitch;
         const int i = lane & 31, g = lane >> 5, x = (i >> 1) & 7;
 #pragma unroll
         for (int st = 0; st < 2; ++st)
@@ -1781,8 +1822,8 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 
     BigScaleGeom SG{};
     if constexpr (MX) {
-        SG.soa = nb * nb + (arow0 + wm * 128 + (lane & 31)) * (nb / 32);
-        SG.sob = nb * nb + (brow0 + wn * 128 + (lane & 31)) * (nb / 32);
+        SG.soa = nb * pitch + (arow0 + wm * 128 + (lane & 31)) * (nb / 32);
+        SG.sob = nb * pitch + (brow0 + wn * 128 + (lane & 31)) * (nb / 32);
         SG.shift = 8 * (lane >> 5);
     }
 
@@ -1794,8 +1835,8 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mt][nt][v] = 0.0f;
 
-    const int n = nb / kRowBytes;                            // chunks per product: even (nb is a multiple of 256)
-    const int tile_bytes = nb * nb;
+    const int n = pitch / kRowBytes;                         // chunks per product: even (the host sees to that)
+    const int tile_bytes = nb * pitch;
     if (kt > 0) {
         const ConstQuad rec0 = (ConstQuad)(uintptr_t)prod;
         u32x4 lo = rec0[0], hi = rec0[1];
@@ -1816,11 +1857,11 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
         i8v f[2][8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) f[0][t] = big_read(BG, lds, 0, 0, t);
-        int sc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, nsc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        int sc[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, nsc[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
         if constexpr (MX) {
-            big_load_scales(sc, SG, S.a, S.b, nb, 0);
+            big_load_scales<FMT>(sc, SG, S.a, S.b, nb, 0);
 #pragma unroll
-            for (int t = 0; t < 8; ++t) sc[t] = (int)((uint32_t)sc[t] >> SG.shift);
+            for (int t = 0; t < 16; ++t) sc[t] = (int)((uint32_t)sc[t] >> SG.shift);
         }
 
         for (int L = 0; L < kt; ++L) {
@@ -1847,20 +1888,20 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
                 S2.c = (c + 2 < n) ? c + 2 : c + 2 - n;
                 // MX: the scales of the chunk after the one being computed are fetched under it
                 // (past the end of the reduction: those of the last chunk again, unused)
-                int nx[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-                if constexpr (MX) big_load_scales(nsc, SG, cur_src.a, cur_src.b, nb, c + 1);
-                big_chunk<0, MX>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
+                int nx[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                if constexpr (MX) big_load_scales<FMT>(nsc, SG, cur_src.a, cur_src.b, nb, c + 1);
+                big_chunk<0, FMT>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
                 if constexpr (MX) {
 #pragma unroll
-                    for (int t = 0; t < 8; ++t) sc[t] = nx[t];
+                    for (int t = 0; t < 16; ++t) sc[t] = nx[t];
                     const bool wrap = c + 2 >= n && nbytes != 0;
-                    big_load_scales(nsc, SG, wrap ? next_src.a : cur_src.a, wrap ? next_src.b : cur_src.b, nb, c + 2 < n ? c + 2 : wrap ? 0 : n - 1);
+                    big_load_scales<FMT>(nsc, SG, wrap ? next_src.a : cur_src.a, wrap ? next_src.b : cur_src.b, nb, c + 2 < n ? c + 2 : wrap ? 0 : n - 1);
                 }
                 S2.c += 1;
-                big_chunk<1, MX>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
+                big_chunk<1, FMT>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
                 if constexpr (MX) {
 #pragma unroll
-                    for (int t = 0; t < 8; ++t) sc[t] = nx[t];
+                    for (int t = 0; t < 16; ++t) sc[t] = nx[t];
                 }
             }
             lo = nlo;
@@ -1908,11 +1949,13 @@ hipError_t gemm_kernel_setup()
         const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
     }
-    const hipError_t e = hipFuncSetAttribute((const void *)gemm_mp_fp8_region_kernel<false>,
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void *)gemm_mp_fp8_region_kernel<true>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
+    const void *regions[3] = {(const void *)gemm_mp_fp8_region_kernel<0>, (const void *)gemm_mp_fp8_region_kernel<1>,
+                              (const void *)gemm_mp_fp8_region_kernel<2>};
+    for (const void *k : regions) {
+        const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // One thread per task (C tile, L): gather what the owner workgroups need into one record.  With
@@ -1965,6 +2008,29 @@ __global__ __launch_bounds__(256) void convert_tiles_kernel(const ConvertJob *__
     const uint32_t seg = blockIdx.x * 256u + threadIdx.x;
     if (seg >= job.n16) return;
     const int p = job.p, q = job.q;
+    if (p == GEMM_MP_MXFP4) {
+        // MXFP4 tile to FP32 / FP64: e2m1 element times the scale of its block of 32 (exact)
+        const uint8_t *sb = (const uint8_t *)(uintptr_t)job.src;
+        const uint64_t elems = (uint64_t)job.n16 * (q == Q32 ? 4u : 2u);         // nb * nb
+        const uint64_t idx = (uint64_t)seg * (q == Q32 ? 4u : 2u);                // first element of this segment: even
+        const int sc = (int)sb[elems / 2 + (idx >> 5)] - 127;
+        const uint32_t w = *(const uint16_t *)(sb + idx / 2 - ((idx / 2) & 1)) >> (8 * (int)((idx / 2) & 1));
+        float v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int code = (int)(w >> (4 * k)) & 15, ef = (code >> 1) & 3, mf = code & 1;
+            const float mag = ef ? ldexpf(1.0f + 0.5f * mf, ef - 1) : 0.5f * mf;
+            v[k] = ldexpf((code & 8) ? -mag : mag, sc);
+        }
+        u32x4 o;
+        if (q == Q32) o = u32x4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+        else {
+            const u32x2 a = dbits((double)v[0]), b = dbits((double)v[1]);
+            o = u32x4{a.x, a.y, b.x, b.y};
+        }
+        *(u32x4 *)((char *)(uintptr_t)job.dst + (uint64_t)seg * 16) = o;
+        return;
+    }
     if (p == GEMM_MP_MXFP8) {
         // MXFP8 tile to FP32 / FP64: element times the scale of its block of 32 (exact)
         const uint8_t *sb = (const uint8_t *)(uintptr_t)job.src;
@@ -2053,9 +2119,11 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
         else gemm_mp_owner_kernel<float, false, false><<<dim3((unsigned)a.n_items32), dim3(kThreads), kLdsBytes, s>>>(a, a.items32);
     }
     if (a.n_items8 > 0)
-        gemm_mp_fp8_region_kernel<false><<<dim3((unsigned)a.n_items8), dim3(kThreads), kBigLdsBytes, s>>>(a, a.items8);
+        gemm_mp_fp8_region_kernel<0><<<dim3((unsigned)a.n_items8), dim3(kThreads), kBigLdsBytes, s>>>(a, a.items8);
     if (a.n_items_mx > 0)
-        gemm_mp_fp8_region_kernel<true><<<dim3((unsigned)a.n_items_mx), dim3(kThreads), kBigLdsBytes, s>>>(a, a.items_mx);
+        gemm_mp_fp8_region_kernel<1><<<dim3((unsigned)a.n_items_mx), dim3(kThreads), kBigLdsBytes, s>>>(a, a.items_mx);
+    if (a.n_items_mx4 > 0)
+        gemm_mp_fp8_region_kernel<2><<<dim3((unsigned)a.n_items_mx4), dim3(kThreads), kBigLdsBytes, s>>>(a, a.items_mx4);
     return hipGetLastError();
 }
 

@@ -205,6 +205,20 @@ __device__ inline uint32_t to_bf16_bits(double x)
     return sign | r;
 }
 
+// FP4 e2m1 (1 fraction bit, smallest normal 1, largest 6; no infinity or NaN codes: both
+// saturate resp. become 0), after scaling by 2^-e.
+__device__ inline uint32_t to_fp4_bits(double x, int e)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint32_t sign = (uint32_t)(b >> 60) & 0x8u;
+    const uint64_t mag = b & 0x7fffffffffffffffull;
+    if (mag > 0x7ff0000000000000ull) return 0;                 // NaN has no code
+    if (mag == 0x7ff0000000000000ull) return sign | 7u;
+    uint32_t r = round_magnitude<1, 0, 1>(mag, e);
+    if (r > 7u) r = 7u;                                        // beyond 6 -> 6
+    return r ? (sign | r) : sign;
+}
+
 // The stored bit pattern of one element, right-aligned in 64 bits.
 __device__ inline uint64_t stored_bits(double x, int p, int e)
 {
@@ -259,7 +273,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const double *__restrict__ X,
     const int I = (int)(R0 / nb), J = (int)(C0 / nb);
     const int tile = swap ? J * rows_t + I : I * cols_t + J;      // swap: the buffer holds the matrix's transpose
     const int p = v.prec[tile];
-    if (p == GEMM_MP_MXFP8) return;                              // block-scaled tiles: pack_mx_kernel
+    if (is_block_scaled(p)) return;                              // block-scaled tiles: pack_mx_kernel
     const int e = v.exp[tile];
     char *base = v.storage + v.offset[tile];
     const int r_in = (int)(R0 % nb), c_in = (int)(C0 % nb);
@@ -320,7 +334,9 @@ __global__ __launch_bounds__(256) void pack_mx_kernel(const double *__restrict__
                                                       int cols_t, int nb, bool is_b, PackedView v)
 {
     const int tile = blockIdx.y;
-    if (v.prec[tile] != GEMM_MP_MXFP8) return;
+    const int p = v.prec[tile];
+    if (!is_block_scaled(p)) return;
+    const bool fp4 = p == GEMM_MP_MXFP4;
     const int I = tile / cols_t, J = tile % cols_t;
     const int per_row = nb / 32;
     const int idx = blockIdx.x * 256 + threadIdx.x;              // (packed row, block): nb * nb / 32 of them, a multiple of 256
@@ -341,11 +357,19 @@ __global__ __launch_bounds__(256) void pack_mx_kernel(const double *__restrict__
         const uint64_t man = bits & 0xfffffffffffffull;
         if (field != 0x7ff && bits != 0) {
             const int lg = field ? field - 1023 : 63 - __builtin_clzll(man) - 1074;
-            s = lg - 8;
+            s = lg - (fp4 ? 2 : 8);                              // exponent of the element format's largest binade
             s = s < -127 ? -127 : s > 127 ? 127 : s;
         }
     }
     char *base = v.storage + v.offset[tile];
+    if (fp4) {                                                   // two elements a byte, the lower index in the low four bits
+        uint32_t w[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < 32; ++k) w[k / 8] |= to_fp4_bits(x[k], s) << (4 * (k % 8));
+        *(uint4 *)(base + ((int64_t)u * nb + 32 * kb) / 2) = make_uint4(w[0], w[1], w[2], w[3]);
+        ((uint8_t *)base)[(int64_t)nb * nb / 2 + (int64_t)u * per_row + kb] = (uint8_t)(s + 127);
+        return;
+    }
     uint32_t w[8];
 #pragma unroll
     for (int k = 0; k < 32; k += 4)
@@ -374,6 +398,13 @@ __device__ inline double stored_value(const char *base, int64_t idx, int p, int 
         const int code = ((const uint8_t *)base)[idx];
         const int sc = ((const uint8_t *)base)[(int64_t)nb * nb + (idx >> 5)];
         return ldexp((double)__builtin_amdgcn_cvt_f32_fp8(code, 0), sc - 127);
+    }
+    case GEMM_MP_MXFP4: {
+        const int code = (((const uint8_t *)base)[idx >> 1] >> (4 * (int)(idx & 1))) & 15;
+        const int sc = ((const uint8_t *)base)[(int64_t)nb * nb / 2 + (idx >> 5)];
+        const int ef = (code >> 1) & 3, mf = code & 1;
+        const double mag = ef ? ldexp(1.0 + 0.5 * mf, ef - 1) : 0.5 * mf;
+        return ldexp((code & 8) ? -mag : mag, sc - 127);
     }
     case GEMM_MP_FP64: return ((const double *)base)[idx];
     case GEMM_MP_FP32: return (double)((const float *)base)[idx];

@@ -84,9 +84,8 @@ class DeviceGemmMP:
     def tile_bytes(self, which, I, J):
         """Raw stored bytes of one tile as a uint8 host array (for bit-exact checks)."""
         off, prec, _ = self.ctx.tile_info(which, I, J, want_exp=False)
-        n = self.ctx.nb * self.ctx.nb * (2 if prec == 4 else 1 if prec == 5 else 8 >> prec)
-        if prec == 5:
-            n += n // 32                           # MXFP8: the block scales follow the elements
+        e = self.ctx.nb * self.ctx.nb
+        n = {4: 2 * e, 5: e + e // 32, 6: e // 2 + e // 32}.get(prec, e * (8 >> min(prec, 3)))   # MX: block scales follow the elements
         torch.cuda.synchronize()
         return self.storage[which][off:off + n].cpu().numpy(), prec
 

@@ -14,7 +14,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgemm_mp.so")
 
-FP64, FP32, FP16, FP8_E4M3, BF16, MXFP8 = 0, 1, 2, 3, 4, 5
+FP64, FP32, FP16, FP8_E4M3, BF16, MXFP8, MXFP4 = 0, 1, 2, 3, 4, 5, 6
 POLICY_OPERAND, POLICY_C_TILE = 0, 1
 OK, EINVAL, ESTATE, ENOMEM, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5
 
@@ -33,7 +33,8 @@ class Stats(ctypes.Structure):
                 ("work_items", ctypes.c_int64), ("converted_tiles", ctypes.c_int64),
                 ("converted_bytes", ctypes.c_uint64), ("products_bf16", ctypes.c_int64),
                 ("flops_bf16", ctypes.c_double), ("tiles_bf16", ctypes.c_int64 * 3),
-                ("products_mxfp8", ctypes.c_int64), ("flops_mxfp8", ctypes.c_double), ("tiles_mxfp8", ctypes.c_int64 * 3)]
+                ("products_mxfp8", ctypes.c_int64), ("flops_mxfp8", ctypes.c_double), ("tiles_mxfp8", ctypes.c_int64 * 3),
+                ("products_mxfp4", ctypes.c_int64), ("flops_mxfp4", ctypes.c_double), ("tiles_mxfp4", ctypes.c_int64 * 3)]
 
 
 class GemmMPError(RuntimeError):
@@ -195,4 +196,5 @@ class GemmMP:
                 "work_items": s.work_items, "converted_tiles": s.converted_tiles,
                 "converted_bytes": s.converted_bytes, "products_bf16": s.products_bf16,
                 "flops_bf16": s.flops_bf16, "tiles_bf16": list(s.tiles_bf16), "products_mxfp8": s.products_mxfp8,
-                "flops_mxfp8": s.flops_mxfp8, "tiles_mxfp8": list(s.tiles_mxfp8)}
+                "flops_mxfp8": s.flops_mxfp8, "tiles_mxfp8": list(s.tiles_mxfp8), "products_mxfp4": s.products_mxfp4,
+                "flops_mxfp4": s.flops_mxfp4, "tiles_mxfp4": list(s.tiles_mxfp4)}

@@ -4,8 +4,8 @@ import numpy as np
 
 from oracle import gemm_mp_oracle as orc
 
-FP64, FP32, FP16, FP8, BF16, MXFP8 = 0, 1, 2, 3, 4, 5
-U = {FP64: 2.0 ** -53, FP32: 2.0 ** -24, FP16: 2.0 ** -11, FP8: 2.0 ** -4, BF16: 2.0 ** -8, MXFP8: 2.0 ** -4}
+FP64, FP32, FP16, FP8, BF16, MXFP8, MXFP4 = 0, 1, 2, 3, 4, 5, 6
+U = {FP64: 2.0 ** -53, FP32: 2.0 ** -24, FP16: 2.0 ** -11, FP8: 2.0 ** -4, BF16: 2.0 ** -8, MXFP8: 2.0 ** -4, MXFP4: 2.0 ** -2}
 
 
 class OracleSide:

@@ -62,7 +62,7 @@ def test_map_validation_and_call_order():
         g.set_precision_map("A", np.zeros((3, 4), np.uint16))          # A is 4 x 3 tiles
     assert e.value.status == G.EINVAL
     with pytest.raises(G.GemmMPError) as e:
-        g.set_precision_map("A", np.full((4, 3), 6, np.uint16))        # code out of range
+        g.set_precision_map("A", np.full((4, 3), 7, np.uint16))        # code out of range
     assert e.value.status == G.EINVAL
     with pytest.raises(G.GemmMPError) as e:
         g.set_precision_map("X", np.zeros((4, 3), np.uint16))
@@ -172,8 +172,8 @@ def test_mxfp8_codes_layout_and_where_this_build_runs_them():
     product precision equals the oracle's; tiles made of MXFP8 x MXFP8 products only are cut into
     256 x 256 regions; statistics count such products apart."""
     from oracle import gemm_mp_oracle as orc
-    for pA in range(6):
-        for pB in range(6):
+    for pA in range(7):
+        for pB in range(7):
             for pC in range(5):
                 for policy in (G.POLICY_OPERAND, G.POLICY_C_TILE):
                     assert G.product_precision(pA, pB, pC, policy) == orc.product_precision(pA, pB, pC, policy)
@@ -192,6 +192,21 @@ def test_mxfp8_codes_layout_and_where_this_build_runs_them():
     assert st["products_mxfp8"] == 12 and st["products"] == [0, 0, 0, 0] and st["tiles_mxfp8"] == [6, 6, 0]
     assert st["flops_mxfp8"] == 12 * 2.0 * nb ** 3 and st["work_items"] == 4 * (nb // 256) ** 2
     assert g.conversion_bytes() == 0
+    # MXFP4 (code 6): half a byte per element; block-scaled kernel at tile sizes that are multiples of 512
+    g.set_precision_map("A", np.full((2, 3), G.MXFP4, dtype=np.uint16))
+    g.set_precision_map("B", np.full((3, 2), G.MXFP4, dtype=np.uint16))
+    assert g.storage_bytes("A") == 6 * (nb * nb // 2 + nb * nb // 32)
+    st = g.get_stats()
+    assert st["products_mxfp4"] == 12 and st["tiles_mxfp4"] == [6, 6, 0] and st["work_items"] == 4 * (nb // 256) ** 2
+    assert g.conversion_bytes() == 0
+    g.set_precision_map("B", np.full((3, 2), G.MXFP8, dtype=np.uint16))      # MXFP4 with MXFP8: FP32 on copies of both
+    assert g.get_stats()["products"] == [0, 12, 0, 0] and g.conversion_bytes() == 12 * nb * nb * 4
+    g.destroy()
+    g = G.GemmMP(256, 256, 256, 256)                                          # 256 is no multiple of 512: copies
+    for k in "AB":
+        g.set_precision_map(k, np.full((1, 1), G.MXFP4, dtype=np.uint16))
+    g.set_precision_map("C", np.full((1, 1), G.FP32, dtype=np.uint16))
+    assert g.get_stats()["products_mxfp4"] == 1 and g.conversion_bytes() == 2 * 256 * 256 * 4
     g.destroy()
 
 
@@ -201,7 +216,7 @@ def test_product_precision_and_stats_closed_forms():
             for pC in range(2):
                 assert G.product_precision(pA, pB, pC, G.POLICY_C_TILE) == pC
                 assert G.product_precision(pA, pB, pC, G.POLICY_OPERAND) == max(pC and 1, min(pA, pB))
-    assert G.product_precision(6, 0, 0) == -1 and G.product_precision(0, 0, 5) == -1
+    assert G.product_precision(7, 0, 0) == -1 and G.product_precision(0, 0, 5) == -1
     w = W.tiny()
     g = G.GemmMP(w.M, w.N, w.K, w.nb)
     for k, m in (("A", w.mapA), ("B", w.mapB), ("C", w.mapC)):

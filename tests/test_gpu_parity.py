@@ -8,7 +8,7 @@ import pytest
 
 import workloads as W
 from oracle import gemm_mp_oracle as orc
-from tests.harness import (BF16, FP8, FP16, FP32, FP64, MXFP8, OracleSide, compare_jobs, finish_low_c_tiles, gpu_problem,
+from tests.harness import (BF16, FP8, FP16, FP32, FP64, MXFP4, MXFP8, OracleSide, compare_jobs, finish_low_c_tiles, gpu_problem,
                            packed_codes_expected)
 
 pytestmark = pytest.mark.gpu
@@ -704,7 +704,7 @@ def test_random_small_integer_problems_over_all_formats_are_exact():
     from paper_2508_14848_amd.device import DeviceGemmMP
     rng = np.random.default_rng(20250815)
     for case in range(100):
-        nb = int(rng.choice([128, 256, 384]))
+        nb = int(rng.choice([128, 256, 384, 512]))
         MT, NT, KT = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.integers(1, 5))
         Mf, Nf, Kf = MT * nb, NT * nb, KT * nb
         A = np.zeros((Mf, Kf))
@@ -719,9 +719,9 @@ def test_random_small_integer_problems_over_all_formats_are_exact():
         K = Kf - (int(rng.integers(1, nb)) if ragged else 0)
         A, B = np.ascontiguousarray(A[:M, :K]), np.ascontiguousarray(B[:K, :N])
         C0 = rng.integers(-3, 4, (M, N)).astype(np.float64)
-        mA, mB, mC = rng.integers(0, 6, (MT, KT)), rng.integers(0, 6, (KT, NT)), rng.integers(0, 5, (MT, NT))
-        if case % 10 == 3:                               # MXFP8 everywhere: the block-scaled kernel where the tile size allows
-            mA[:], mB[:] = MXFP8, MXFP8
+        mA, mB, mC = rng.integers(0, 7, (MT, KT)), rng.integers(0, 7, (KT, NT)), rng.integers(0, 5, (MT, NT))
+        if case % 10 == 3:                               # one block-scaled format everywhere: its kernel where the tile size allows
+            mA[:], mB[:] = (MXFP8, MXFP8) if case % 20 == 3 else (MXFP4, MXFP4)
             mC[:] = rng.integers(1, 5, (MT, NT))
         policy, tA, tB = int(rng.integers(0, 2)), int(rng.integers(0, 2)), int(rng.integers(0, 2))
         alpha, beta = float(rng.choice([-2, -1, 1, 2])), float(rng.choice([-1, 0, 1]))
@@ -742,7 +742,7 @@ def test_random_small_integer_problems_over_all_formats_are_exact():
                 d.convert_tiles()
             d.run(alpha, beta)
         except G.GemmMPError as e:                     # a BF16 tile under an FP32 / FP64 product, an MXFP8 tile outside the block-scaled kernel
-            assert e.status == G.ESTATE and {BF16, MXFP8} & (set(mA.ravel()) | set(mB.ravel())), what
+            assert e.status == G.ESTATE and {BF16, MXFP8, MXFP4} & (set(mA.ravel()) | set(mB.ravel())), what
             d.convert_tiles()
             d.run(alpha, beta)
         got = d.unpack_tiles("C").cpu().numpy()
@@ -833,6 +833,81 @@ def test_mxfp8_tiles_pack_bit_for_bit_and_multiply_on_the_block_scaled_instructi
     w.mapA = np.full_like(w.mapA, MXFP8)
     w.mapB = np.full_like(w.mapB, MXFP8)
     w.mapC = np.full_like(w.mapC, FP32)
+    w.alpha, w.beta = 1.0, 0.0
+    A, B, _ = _dense(w)
+    side = OracleSide(w, A, B, None)
+    d, dev = gpu_problem(w, A, B, None)
+    assert np.array_equal(d.unpack_tiles("A").cpu().numpy(), side.Ay) and np.array_equal(d.unpack_tiles("B").cpu().numpy(), side.By)
+    d.run(1.0, 0.0)
+    C_gpu = d.unpack_tiles("C").cpu().numpy()
+    jobs = _all_jobs(w)
+    worst = compare_jobs(side, jobs, 0, 1.0, 0.0, C_gpu, side.gemm(jobs))
+    _say("  worst error / bound:", worst)
+    torch.cuda.synchronize()
+
+
+def test_mxfp4_tiles_pack_bit_for_bit_and_multiply_on_the_block_scaled_instruction():
+    """MXFP4 tiles: four-bit e2m1 codes (two a byte, the lower reduction index in the low bits) and
+    scale bytes equal the oracle's, both orientations; unpack returns the values; all-MXFP4
+    problems of small integers with block-wise different magnitudes are exact on the block-scaled
+    instruction (tile 512) and through FP32 copies (tile 256); general data within the bounds."""
+    import torch
+    from paper_2508_14848_amd import gemm_mp as G
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(62)
+    nb = 256
+    M, N, K = 2 * nb, nb - 50, 2 * nb - 31
+    A = rng.standard_normal((M, K)) * np.exp(rng.uniform(-20, 20, (M, K)))
+    B = rng.standard_normal((K, N)) * np.exp(rng.uniform(-20, 20, (K, N)))
+    d = DeviceGemmMP(M, N, K, nb)
+    d.set_precision_map("A", np.full((2, 2), MXFP4, dtype=np.uint16))
+    d.set_precision_map("B", np.full((2, 1), MXFP4, dtype=np.uint16))
+    d.pack_tiles("A", _even_ld(A))
+    d.pack_tiles("B", _even_ld(B))
+    Ap, Bp = orc.pad_to_tiles(A, nb), orc.pad_to_tiles(B, nb)
+    for which, Xp, tiles in (("A", Ap, [(0, 0), (1, 1)]), ("B", Bp, [(0, 0), (1, 0)])):
+        for (I, J) in tiles:
+            got, prec = d.tile_bytes(which, I, J)
+            tile = Xp[I * nb:(I + 1) * nb, J * nb:(J + 1) * nb]
+            rows = np.ascontiguousarray(tile.T if which == "B" else tile)
+            _, codes, scales = orc.mx4_blocks(rows)
+            codes = codes.ravel()
+            assert prec == MXFP4
+            assert np.array_equal(got[:nb * nb // 2], codes[0::2] | (codes[1::2] << 4)), (which, I, J)
+            assert np.array_equal(got[nb * nb // 2:], scales), (which, I, J)
+    Ya, _ = orc.store_tiles(Ap, nb, np.full((2, 2), MXFP4, dtype=np.uint16), mx_axis=0)
+    Yb, _ = orc.store_tiles(Bp, nb, np.full((2, 1), MXFP4, dtype=np.uint16), mx_axis=1)
+    assert np.array_equal(d.unpack_tiles("A").cpu().numpy(), Ya[:M, :K])
+    assert np.array_equal(d.unpack_tiles("B").cpu().numpy(), Yb[:K, :N])
+    for nb, MT, NT, KT in ((512, 2, 1, 2), (1024, 1, 1, 1), (256, 1, 2, 2)):
+        M, N, K = MT * nb, NT * nb, KT * nb
+        _say("MXFP4 integers", (M, N, K, nb))
+        A = rng.integers(-3, 4, (M, K)) * 2.0 ** rng.integers(0, 3, (M, K // 32)).repeat(32, axis=1)
+        B = rng.integers(-3, 4, (K, N)) * 2.0 ** rng.integers(0, 3, (K // 32, N)).repeat(32, axis=0)
+        C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
+        d = DeviceGemmMP(M, N, K, nb)
+        d.set_precision_map("A", np.full((MT, KT), MXFP4, dtype=np.uint16))
+        d.set_precision_map("B", np.full((KT, NT), MXFP4, dtype=np.uint16))
+        d.set_precision_map("C", np.full((MT, NT), FP32, dtype=np.uint16))
+        for which, X in (("A", A), ("B", B), ("C", C0)):
+            d.pack_tiles(which, torch.from_numpy(np.ascontiguousarray(X, dtype=np.float64)).cuda())
+        assert np.array_equal(d.unpack_tiles("A").cpu().numpy(), A) and np.array_equal(d.unpack_tiles("B").cpu().numpy(), B)
+        st = d.ctx.get_stats()
+        assert st["products_mxfp4"] == MT * NT * KT
+        if nb % 512 == 0:
+            assert st["work_items"] == MT * NT * (nb // 256) ** 2 and d.ctx.conversion_bytes() == 0
+        else:
+            with pytest.raises(G.GemmMPError) as e:
+                d.run(1.0, -1.0)
+            assert e.value.status == G.ESTATE
+            d.convert_tiles()
+        d.run(1.0, -1.0)
+        assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), A @ B - C0)
+    # general data against the oracle (tile 512: the block-scaled kernel)
+    w = W.tiny(M=1024, N=1024, K=1024, nb=512)
+    w.mapA = np.full((2, 2), MXFP4, dtype=np.uint16)
+    w.mapB = np.full((2, 2), MXFP4, dtype=np.uint16)
+    w.mapC = np.full((2, 2), FP32, dtype=np.uint16)
     w.alpha, w.beta = 1.0, 0.0
     A, B, _ = _dense(w)
     side = OracleSide(w, A, B, None)
