@@ -383,14 +383,11 @@ int32_t orc_scale_exponent(double maxabs, int32_t p)
  * FP64: copy.  FP32: C cast (round to nearest even, IEEE overflow / gradual
  * underflow).  FP16 / FP8: one direct rounding of x * 2^-e from FP64.
  * X and Y may be the same array. */
-static int g_mx_axis = 0;   /* blocks of MXFP8 tiles run along a row (0: A, C) or down a column (1: B) */
-void orc_set_mx_axis(int32_t axis) { g_mx_axis = axis; }
-
-void orc_store_tiles(const double *X, int64_t ld, int64_t rows, int64_t cols, int32_t nb,
-                     const uint16_t *map, const double *maxabs, double *Y, int64_t ldy,
-                     int32_t *exps)
+/* mx_axis: the blocks of block-scaled tiles run along a row (0: A) or down a column (1: B). */
+void orc_store_tiles_axis(const double *X, int64_t ld, int64_t rows, int64_t cols, int32_t nb,
+                          const uint16_t *map, const double *maxabs, double *Y, int64_t ldy,
+                          int32_t *exps, int32_t mx_axis)
 {
-    const int mx_axis = g_mx_axis;
     int64_t RT = rows / nb, CT = cols / nb;
 #pragma omp parallel for collapse(2) schedule(dynamic)
     for (int64_t I = 0; I < RT; ++I)
@@ -425,6 +422,13 @@ void orc_store_tiles(const double *X, int64_t ld, int64_t rows, int64_t cols, in
                     Y[(I * nb + r) * ldy + J * nb + c] = y;
                 }
         }
+}
+
+void orc_store_tiles(const double *X, int64_t ld, int64_t rows, int64_t cols, int32_t nb,
+                     const uint16_t *map, const double *maxabs, double *Y, int64_t ldy,
+                     int32_t *exps)
+{
+    orc_store_tiles_axis(X, ld, rows, cols, nb, map, maxabs, Y, ldy, exps, 0);
 }
 
 /* Precision of the product A(I,L)*B(L,J) that updates C(I,J).

@@ -45,7 +45,7 @@ def lib():
         _lib.orc_round_bf16_array.argtypes = [P, c_i64, P, P]
         _lib.orc_mx_blocks_array.argtypes = [P, c_i64, P, P, P]
         _lib.orc_mx4_blocks_array.argtypes = [P, c_i64, P, P, P]
-        _lib.orc_set_mx_axis.argtypes = [c_i32]
+        _lib.orc_store_tiles_axis.argtypes = [P, c_i64, c_i64, c_i64, c_i32, P, P, P, c_i64, P, c_i32]
         _lib.orc_bf16_value.restype = c_dbl
         _lib.orc_bf16_value.argtypes = [ctypes.c_uint16]
         _lib.orc_fp16_value.restype = c_dbl
@@ -192,9 +192,8 @@ def store_tiles(X, nb, pmap, maxabs=None, out=None, mx_axis=0):
     maxabs = np.ascontiguousarray(maxabs, dtype=np.float64)
     Y = np.empty_like(X) if out is None else _dense(out)
     exps = np.empty(pmap.shape, dtype=np.int32)
-    lib().orc_set_mx_axis(int(mx_axis))
-    lib().orc_store_tiles(_p(X), X.strides[0] // 8, rows, cols, nb, _p(pmap), _p(maxabs),
-                          _p(Y), Y.strides[0] // 8, _p(exps))
+    lib().orc_store_tiles_axis(_p(X), X.strides[0] // 8, rows, cols, nb, _p(pmap), _p(maxabs),
+                               _p(Y), Y.strides[0] // 8, _p(exps), int(mx_axis))
     return Y, exps
 
 
