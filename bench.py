@@ -32,8 +32,11 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cov16k",
                     choices=["tiny", "random8k", "cov16k", "rect32k", "cov64k",
-                             "paper100", "paper80", "paper50", "paper20", "paper0"],
-                    help="paperNN: the paper's own runs, NN %% of the tiles FP64 and the rest FP32 (Section 5.2)")
+                             "paper100", "paper80", "paper50", "paper20", "paper0",
+                             "format-fp64", "format-fp32", "format-fp16", "format-fp8", "format-bf16", "format-mxfp8",
+                             "format-mxfp4"],
+                    help="paperNN: the paper's own runs, NN %% of the tiles FP64 and the rest FP32 (Section 5.2); "
+                         "format-X: 16384^3, tile 1024, every tile of A and B stored as X (per-format rates; no CPU baseline)")
     ap.add_argument("--policy", type=int, default=None, choices=[0, 1],
                     help="0 = operand policy, 1 = C-tile policy (default: the workload's own)")
     ap.add_argument("--conversion", default="receiver", choices=["receiver", "sender"],
@@ -184,6 +187,7 @@ def main():
         key = w.name + ("" if args.policy == w.policy else "-policy%d" % args.policy) + ("" if args.conversion == "receiver" else "-sender")
         traffic = json.load(open(tpath)).get(key, {}).get("bytes_per_launch")
     used = [DTYPE_NAMES[q] for q in range(4) if st["products"][q]]
+    used += [n for n in ("bf16", "mxfp8", "mxfp4") if st["products_" + n]]
     out = {
         "metric": "effective TFLOP/s (2MNK/t) and % of precision-weighted MFMA peak, 1 GPU",
         "value": flops_total / (ms_per_step * 1e-3) / 1e12,
@@ -196,7 +200,8 @@ def main():
                    "alpha": w.alpha, "beta": w.beta, "policy": ["operand", "c_tile"][args.policy],
                    "conversion": args.conversion, "converted_tiles": st["converted_tiles"],
                    "converted_bytes": st["converted_bytes"],
-                   "products_by_precision": dict(zip(DTYPE_NAMES, st["products"])),
+                   "products_by_precision": dict(list(zip(DTYPE_NAMES, st["products"])) +
+                                                 [(n, st["products_" + n]) for n in ("bf16", "mxfp8", "mxfp4") if st["products_" + n]]),
                    "work_items": st["work_items"], "host_generation_s": round(t_gen, 1)},
         "stages_ms": {k: float(np.mean(v)) for k, v in stage_ms.items()},
         "run_only": {"ms": run_ms, "min_ms": float(np.min(stage_ms["run"])), "effective_tflops": achieved,
@@ -207,7 +212,7 @@ def main():
                              "achieved = 2MNK / mean event time of gemm_mp_run on its stream (product table and up to three "
                              "GEMM launches: FP64 C tiles, FP32 C tiles, FP32 C tiles of FP8 products only)"},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not w.name.startswith("format-"):
         out["cpu_baseline"] = cpu_baseline(w, A, B, C0, args.cpu_seconds)
     print(json.dumps(out), flush=True)
 
