@@ -324,12 +324,26 @@ hipError_t launch_pack(const double *X, int64_t ld, int64_t rows, int64_t cols, 
     return hipGetLastError();
 }
 
-// MXFP8 tiles (the block-scaled format of the OCP microscaling specification): one thread per
-// block of 32 consecutive reduction indices of one packed row (a row of an A tile, a column of a
-// B tile).  Scale 2^s, s = floor(log2 max|x|) - 8 within [-127, 127] (0 for a zero block or a
-// non-finite maximum); elements x * 2^-s rounded once to e4m3, saturating; the scale bytes
-// (s + 127) follow the tile's nb * nb element bytes, nb / 32 per packed row.  Entries outside the
-// rows x cols matrix count as zeros.
+// Block-scaled tiles (MXFP8, MXFP4: the formats of the OCP microscaling specification): per block
+// of 32 consecutive reduction indices of one packed row (a row of an A tile, a column of a B
+// tile) a scale 2^s, s = floor(log2 max|x|) - 8 (e4m3 elements) or - 2 (e2m1) within [-127, 127]
+// (0 for a zero block or a non-finite maximum); elements x * 2^-s rounded once, saturating; the
+// scale bytes (s + 127) follow the tile's element bytes, nb / 32 per packed row.  Entries outside
+// the rows x cols matrix count as zeros.
+// Scale exponent of a block from its largest magnitude (fp4: e2m1 elements, else e4m3).
+__device__ inline int mx_block_exponent(double m, bool fp4)
+{
+    const uint64_t bits = (uint64_t)__double_as_longlong(m);
+    const int field = (int)(bits >> 52);
+    const uint64_t man = bits & 0xfffffffffffffull;
+    if (field == 0x7ff || bits == 0) return 0;
+    const int lg = field ? field - 1023 : 63 - __builtin_clzll(man) - 1074;
+    const int s = lg - (fp4 ? 2 : 8);                            // exponent of the element format's largest binade
+    return s < -127 ? -127 : s > 127 ? 127 : s;
+}
+
+// B tiles (blocks run down the matrix columns): one thread per block, neighbouring threads on
+// neighbouring columns, so that every load of a wave is 512 contiguous bytes.
 __global__ __launch_bounds__(256) void pack_mx_kernel(const double *__restrict__ X, int64_t sr, int64_t sc, int64_t rows, int64_t cols,
                                                       int cols_t, int nb, bool is_b, PackedView v)
 {
@@ -339,8 +353,8 @@ __global__ __launch_bounds__(256) void pack_mx_kernel(const double *__restrict__
     const bool fp4 = p == GEMM_MP_MXFP4;
     const int I = tile / cols_t, J = tile % cols_t;
     const int per_row = nb / 32;
-    const int idx = blockIdx.x * 256 + threadIdx.x;              // (packed row, block): nb * nb / 32 of them, a multiple of 256
-    const int u = idx / per_row, kb = idx % per_row;
+    const int idx = blockIdx.x * 256 + threadIdx.x;              // (block, packed row): nb * nb / 32 of them, a multiple of 256
+    const int u = is_b ? idx % nb : idx / per_row, kb = is_b ? idx / nb : idx % per_row;
     double x[32];
     double m = 0.0;
 #pragma unroll
@@ -350,17 +364,7 @@ __global__ __launch_bounds__(256) void pack_mx_kernel(const double *__restrict__
         const double a = __builtin_fabs(x[k]);
         if (a > m) m = a;                                        // a NaN never enters m
     }
-    int s = 0;
-    {
-        const uint64_t bits = (uint64_t)__double_as_longlong(m);
-        const int field = (int)(bits >> 52);
-        const uint64_t man = bits & 0xfffffffffffffull;
-        if (field != 0x7ff && bits != 0) {
-            const int lg = field ? field - 1023 : 63 - __builtin_clzll(man) - 1074;
-            s = lg - (fp4 ? 2 : 8);                              // exponent of the element format's largest binade
-            s = s < -127 ? -127 : s > 127 ? 127 : s;
-        }
-    }
+    const int s = mx_block_exponent(m, fp4);
     char *base = v.storage + v.offset[tile];
     if (fp4) {                                                   // two elements a byte, the lower index in the low four bits
         uint32_t w[4] = {0, 0, 0, 0};
@@ -380,11 +384,60 @@ __global__ __launch_bounds__(256) void pack_mx_kernel(const double *__restrict__
     ((uint8_t *)base)[(int64_t)nb * nb + (int64_t)u * per_row + kb] = (uint8_t)(s + 127);
 }
 
+// A tiles (blocks run along the matrix rows): eight neighbouring lanes share a block, four
+// consecutive entries each, so that a wave reads 2 KB of a row at a time; the block maximum is
+// formed with three lane exchanges.
+__global__ __launch_bounds__(256) void pack_mx_rows_kernel(const double *__restrict__ X, int64_t sr, int64_t sc, int64_t rows, int64_t cols,
+                                                           int cols_t, int nb, PackedView v)
+{
+    const int tile = blockIdx.y;
+    const int p = v.prec[tile];
+    if (!is_block_scaled(p)) return;
+    const bool fp4 = p == GEMM_MP_MXFP4;
+    const int I = tile / cols_t, J = tile % cols_t;
+    const int per_row = nb / 32;
+    const int gidx = blockIdx.x * 256 + threadIdx.x;             // (block, quarter of eight): nb * nb / 4 of them
+    const int blk = gidx >> 3, sub = gidx & 7;
+    const int u = blk / per_row, kb = blk % per_row;
+    const int64_t r = (int64_t)I * nb + u, c0 = (int64_t)J * nb + 32 * kb + 4 * sub;
+    double x[4];
+    double m = 0.0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        x[k] = (r < rows && c0 + k < cols) ? X[r * sr + (c0 + k) * sc] : 0.0;
+        const double a = __builtin_fabs(x[k]);
+        if (a > m) m = a;
+    }
+#pragma unroll
+    for (int d = 1; d < 8; d <<= 1) {
+        const double o = __shfl_xor(m, d);
+        if (o > m) m = o;
+    }
+    const int s = mx_block_exponent(m, fp4);
+    char *base = v.storage + v.offset[tile];
+    if (fp4) {
+        const uint32_t w = to_fp4_bits(x[0], s) | (to_fp4_bits(x[1], s) << 4) | (to_fp4_bits(x[2], s) << 8) | (to_fp4_bits(x[3], s) << 12);
+        *(uint16_t *)(base + ((int64_t)u * nb + 32 * kb) / 2 + 2 * sub) = (uint16_t)w;
+        if (sub == 0) ((uint8_t *)base)[(int64_t)nb * nb / 2 + (int64_t)u * per_row + kb] = (uint8_t)(s + 127);
+        return;
+    }
+    const uint32_t w = to_fp8_bits(x[0], s) | (to_fp8_bits(x[1], s) << 8) | (to_fp8_bits(x[2], s) << 16) | (to_fp8_bits(x[3], s) << 24);
+    *(uint32_t *)(base + (int64_t)u * nb + 32 * kb + 4 * sub) = w;
+    if (sub == 0) ((uint8_t *)base)[(int64_t)nb * nb + (int64_t)u * per_row + kb] = (uint8_t)(s + 127);
+}
+
 hipError_t launch_pack_mx(const double *X, int64_t sr, int64_t sc, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb,
                           bool is_b, PackedView v, hipStream_t s)
 {
-    dim3 grid((unsigned)((int64_t)nb * nb / 32 / 256), (unsigned)(rows_t * cols_t));
-    pack_mx_kernel<<<grid, 256, 0, s>>>(X, sr, sc, rows, cols, cols_t, nb, is_b, v);
+    // the mapping that reads contiguously: by the direction in which the buffer is contiguous along the blocks
+    const bool along_contiguous = is_b ? sr == 1 : sc == 1;
+    if (along_contiguous && !is_b) {
+        dim3 grid((unsigned)((int64_t)nb * nb / 4 / 256), (unsigned)(rows_t * cols_t));
+        pack_mx_rows_kernel<<<grid, 256, 0, s>>>(X, sr, sc, rows, cols, cols_t, nb, v);
+    } else {
+        dim3 grid((unsigned)((int64_t)nb * nb / 32 / 256), (unsigned)(rows_t * cols_t));
+        pack_mx_kernel<<<grid, 256, 0, s>>>(X, sr, sc, rows, cols, cols_t, nb, is_b, v);
+    }
     return hipGetLastError();
 }
 
