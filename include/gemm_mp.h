@@ -38,14 +38,14 @@
  * power-of-two exponent e per tile chosen so that the largest magnitude falls
  * in [2^14,2^15) resp. [2^7,2^8); e = 0 for an all-zero tile.  BF16 tiles (8
  * exponent bits as FP32, 7 fraction bits, overflow to infinity) have FP32's
- * range and carry no scale (e = 0).  MXFP8 tiles (code 5; A and B only) are the block-scaled
+ * range and carry no scale (e = 0).  MXFP8 tiles (code 5) are the block-scaled
  * format of the OCP microscaling specification: e4m3 elements, tile_nb^2 bytes laid out like an
  * FP8 tile, followed by one scale byte (E8M0: 2^(code-127)) per 32 consecutive reduction
  * indices, row by row, tile_nb^2/32 bytes; scale = 2^(floor(log2 max|x|) - 8) of its block,
  * elements rounded once and saturating; no tile scale.  Where every product of a C tile is
  * MXFP8 x MXFP8 (C tile not FP64, tile_nb a multiple of 256) the tile runs on the block-scaled
  * matrix instruction; any other product with an MXFP8 operand reads widened copies of the MXFP8
- * tiles from the sender-side workspace: see gemm_mp_run.  MXFP4 tiles (code 6; A and B only)
+ * tiles from the sender-side workspace: see gemm_mp_run.  MXFP4 tiles (code 6)
  * are the same with e2m1 elements (magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6; scale
  * 2^(floor(log2 max|x|) - 2)): tile_nb^2/2 element bytes, two elements per byte with the lower
  * reduction index in the low four bits, then the tile_nb^2/32 scale bytes; block-scaled
@@ -56,7 +56,9 @@
  * get the precisions an FP32 tile's would and it is accumulated in FP32; when
  * the tile is finished its largest magnitude fixes a new exponent e by the rule
  * above and every entry is rounded once more, from FP32, to nearest even.  With
- * beta != 0 the old tile enters as stored number * 2^e.  The FP32 form lives in
+ * beta != 0 the old tile enters as stored number * 2^e.  BF16 C tiles are rounded
+ * without a scale; MXFP8 / MXFP4 C tiles are quantised block by block, the blocks
+ * of 32 running along the rows of the tile as in a tile of A.  The FP32 form lives in
  * a staging copy per such tile that follows the packed tiles in C's buffer
  * (gemm_mp_storage_bytes counts it), so the library still allocates no operand
  * memory; only gemm_mp_run touches the staging area.
@@ -149,7 +151,7 @@ int gemm_mp_set_transposed(gemm_mp_ctx *ctx, char which, int transposed);
 
 /* Give the precision map of matrix `which` ('A', 'B' or 'C'): rows x cols codes, row-major,
  * host memory, copied (Section 5.2).  rows/cols must equal the matrix's tile counts (EINVAL),
- * codes must be 0..6 (EINVAL); MXFP8 / MXFP4 C tiles are EUNSUPPORTED.  Any earlier binding and packed
+ * codes must be 0..6 (EINVAL).  Any earlier binding and packed
  * data of that matrix are forgotten.  Host only. */
 int gemm_mp_set_precision_map(gemm_mp_ctx *ctx, char which, const uint16_t *map_host,
                               int32_t rows, int32_t cols);

@@ -529,7 +529,7 @@ int32_t orc_gemm_jobs(int64_t M, int64_t N, int64_t K, int32_t nb,
             c1 > nb || c0 > c1)
             return -1;
         int pC = mapC[I * NT + J];
-        if (pC < P_FP64 || pC > P_BF16) return -1;      /* no MXFP8 C tiles */
+        if (pC < P_FP64 || pC > P_MXFP4) return -1;
         int T = pC == P_FP64 ? P_FP64 : P_FP32;       /* accumulate type: FP64 or FP32 */
         int64_t nr = r1 - r0, nc = c1 - c0;
         if (nr == 0 || nc == 0) continue;

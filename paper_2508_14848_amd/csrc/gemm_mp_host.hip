@@ -476,9 +476,6 @@ int gemm_mp_set_precision_map(gemm_mp_ctx *c, char which, const uint16_t *map, i
     if (rows != m.rows_t || cols != m.cols_t) return GEMM_MP_EINVAL;
     for (int t = 0; t < m.ntiles(); ++t)
         if (map[t] > GEMM_MP_MXFP4) return GEMM_MP_EINVAL;
-    if (w == 2)
-        for (int t = 0; t < m.ntiles(); ++t)
-            if (is_block_scaled(map[t])) return GEMM_MP_EUNSUPPORTED;
     return install_map(c, w, map);
 }
 
@@ -792,7 +789,7 @@ int gemm_mp_get_stats(gemm_mp_ctx *c, gemm_mp_stats *out)
 
 int gemm_mp_product_precision(int pA, int pB, int pC, int policy)
 {
-    if (pA < 0 || pA > 6 || pB < 0 || pB > 6 || pC < 0 || pC > 4) return -1;
+    if (pA < 0 || pA > 6 || pB < 0 || pB > 6 || pC < 0 || pC > 6) return -1;
     if (policy != GEMM_MP_POLICY_OPERAND && policy != GEMM_MP_POLICY_C_TILE) return -1;
     return product_precision(pA, pB, pC, policy);
 }

@@ -531,11 +531,11 @@ hipError_t launch_unpack(double *X, int64_t ld, int64_t rows, int64_t cols, int 
 //   maximum: largest magnitude per chunk, then per tile, and from it the tile's new exponent
 //            by the same rule as for packed operands;
 //   round:   stored number = staging * 2^-e rounded once to nearest even (FP8 saturates).
-__global__ __launch_bounds__(256) void low_expand_kernel(const LowTile *__restrict__ low, PackedView v)
+__global__ __launch_bounds__(256) void low_expand_kernel(const LowTile *__restrict__ low, PackedView v, int nb)
 {
     const LowTile lt = low[blockIdx.y];
     const int p = v.prec[lt.tile];
-    const int e = v.exp[lt.tile];
+    int e = v.exp[lt.tile];
     const char *src = v.storage + v.offset[lt.tile];
     float *dst = (float *)(v.storage + lt.stage);
     const int64_t i0 = (int64_t)blockIdx.x * kLowChunk + threadIdx.x * 4;
@@ -551,8 +551,21 @@ __global__ __launch_bounds__(256) void low_expand_kernel(const LowTile *__restri
             const uint2 h = *(const uint2 *)(src + i * 2);
             x = make_float4(__uint_as_float(h.x << 16), __uint_as_float(h.x & 0xffff0000u),
                             __uint_as_float(h.y << 16), __uint_as_float(h.y & 0xffff0000u));
+        } else if (p == GEMM_MP_MXFP4) {                       // the four entries share one block of 32
+            const uint32_t b = *(const uint16_t *)(src + i / 2);
+            float m[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t code = (b >> (4 * j)) & 15u;
+                const int ef = (code >> 1) & 3, mf = code & 1;
+                const float mag = ef ? ldexpf(1.0f + 0.5f * mf, ef - 1) : 0.5f * mf;
+                m[j] = (code & 8u) ? -mag : mag;
+            }
+            x = make_float4(m[0], m[1], m[2], m[3]);
+            e = (int)((const uint8_t *)src)[(int64_t)nb * nb / 2 + (i >> 5)] - 127;
         } else {
             const uint32_t b = *(const uint32_t *)(src + i);
+            if (p == GEMM_MP_MXFP8) e = (int)((const uint8_t *)src)[(int64_t)nb * nb + (i >> 5)] - 127;
             x = make_float4(__builtin_amdgcn_cvt_f32_fp8(b, 0), __builtin_amdgcn_cvt_f32_fp8(b, 1),
                             __builtin_amdgcn_cvt_f32_fp8(b, 2), __builtin_amdgcn_cvt_f32_fp8(b, 3));
         }
@@ -616,7 +629,8 @@ __global__ __launch_bounds__(256) void low_exponent_kernel(const LowTile *__rest
         const int field = (int)(bits >> 23);
         const uint32_t man = bits & 0x7fffffu;
         int e = 0;
-        if (field != 0xff && bits != 0 && prec[lt.tile] != GEMM_MP_BF16) {      // BF16 tiles carry no scale
+        if (field != 0xff && bits != 0 && prec[lt.tile] != GEMM_MP_BF16 && !is_block_scaled(prec[lt.tile])) {
+            // (BF16 tiles carry no scale, block-scaled tiles none for the whole tile)
             const int lg = field ? field - 127 : 31 - __builtin_clz(man) - 149;
             e = lg - (prec[lt.tile] == GEMM_MP_FP16 ? 14 : 7);
         }
@@ -624,7 +638,7 @@ __global__ __launch_bounds__(256) void low_exponent_kernel(const LowTile *__rest
     }
 }
 
-__global__ __launch_bounds__(256) void low_round_kernel(const LowTile *__restrict__ low, PackedView v)
+__global__ __launch_bounds__(256) void low_round_kernel(const LowTile *__restrict__ low, PackedView v, int nb)
 {
     const LowTile lt = low[blockIdx.y];
     const int p = v.prec[lt.tile];
@@ -637,6 +651,34 @@ __global__ __launch_bounds__(256) void low_round_kernel(const LowTile *__restric
     for (int it = 0; it < kLowChunk / 1024; ++it) {
         const int64_t i = i0 + it * 1024;
         const float4 x = *(const float4 *)(src + i);
+        if (is_block_scaled(p)) {                            // uniform over the workgroup
+            // eight neighbouring lanes hold one block of 32 along a row of the tile
+            const bool fp4 = p == GEMM_MP_MXFP4;
+            float m = __builtin_fabsf(x.x);
+            const float a[3] = {__builtin_fabsf(x.y), __builtin_fabsf(x.z), __builtin_fabsf(x.w)};
+            if (!(m == m)) m = 0.0f;                         // a NaN never enters m
+#pragma unroll
+            for (int j = 0; j < 3; ++j)
+                if (a[j] > m) m = a[j];
+#pragma unroll
+            for (int d = 1; d < 8; d <<= 1) {
+                const float o = __shfl_xor(m, d);
+                if (o > m) m = o;
+            }
+            const int s = mx_block_exponent((double)m, fp4);
+            if (fp4) {
+                const uint32_t w = to_fp4_bits((double)x.x, s) | (to_fp4_bits((double)x.y, s) << 4) |
+                                   (to_fp4_bits((double)x.z, s) << 8) | (to_fp4_bits((double)x.w, s) << 12);
+                *(uint16_t *)(dst + i / 2) = (uint16_t)w;
+                if ((threadIdx.x & 7) == 0) ((uint8_t *)dst)[(int64_t)nb * nb / 2 + (i >> 5)] = (uint8_t)(s + 127);
+            } else {
+                const uint32_t w = to_fp8_bits((double)x.x, s) | (to_fp8_bits((double)x.y, s) << 8) |
+                                   (to_fp8_bits((double)x.z, s) << 16) | (to_fp8_bits((double)x.w, s) << 24);
+                *(uint32_t *)(dst + i) = w;
+                if ((threadIdx.x & 7) == 0) ((uint8_t *)dst)[(int64_t)nb * nb + (i >> 5)] = (uint8_t)(s + 127);
+            }
+            continue;
+        }
         const uint64_t b[4] = {stored_bits((double)x.x, p, e), stored_bits((double)x.y, p, e),
                                stored_bits((double)x.z, p, e), stored_bits((double)x.w, p, e)};
         store4(dst + i * es, p, b);
@@ -647,7 +689,7 @@ hipError_t launch_low_expand(const LowTile *low_dev, int n_low, int nb, PackedVi
 {
     if (n_low == 0) return hipSuccess;
     dim3 grid((unsigned)((int64_t)nb * nb / kLowChunk), (unsigned)n_low);
-    low_expand_kernel<<<grid, 256, 0, s>>>(low_dev, c);
+    low_expand_kernel<<<grid, 256, 0, s>>>(low_dev, c, nb);
     return hipGetLastError();
 }
 
@@ -659,7 +701,7 @@ hipError_t launch_low_store(const LowTile *low_dev, int n_low, int nb, PackedVie
     dim3 grid((unsigned)parts, (unsigned)n_low);
     low_chunk_max_kernel<<<grid, 256, 0, s>>>(low_dev, c.storage, parts, part_max);
     low_exponent_kernel<<<n_low, 256, 0, s>>>(low_dev, c.prec, parts, part_max, exps);
-    low_round_kernel<<<grid, 256, 0, s>>>(low_dev, c);
+    low_round_kernel<<<grid, 256, 0, s>>>(low_dev, c, nb);
     return hipGetLastError();
 }
 

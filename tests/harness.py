@@ -115,7 +115,7 @@ def compare_jobs(side, jobs, policy, alpha, beta, C_gpu, C_orc):
             # format's normal range, a full smallest step below it, both doubled because the two
             # sides' exponents may differ by one when their maxima straddle a power of two
             tight += 2.0 * U[t["pC"]] * np.linalg.norm(o)
-            if t["pC"] != BF16:                     # BF16 has no tile scale; its subnormals lie below FP32's normal range
+            if t["pC"] in LOW_FORMAT:               # BF16 has no tile scale and FP32's range; block-scaled tiles scale per block
                 E, step = LOW_FORMAT[t["pC"]]
                 e_hi = np.floor(np.log2(np.abs(o).max())) - E + 1
                 tight += np.sqrt(float(o.size)) * step * 2.0 ** e_hi

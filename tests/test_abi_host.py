@@ -143,7 +143,7 @@ def test_bf16_codes_layout_products_and_conversion_plan():
     from oracle import gemm_mp_oracle as orc
     for pA in range(5):
         for pB in range(5):
-            for pC in range(5):
+            for pC in range(7):
                 for policy in (G.POLICY_OPERAND, G.POLICY_C_TILE):
                     assert G.product_precision(pA, pB, pC, policy) == orc.product_precision(pA, pB, pC, policy)
     nb = 128
@@ -174,7 +174,7 @@ def test_mxfp8_codes_layout_and_where_this_build_runs_them():
     from oracle import gemm_mp_oracle as orc
     for pA in range(7):
         for pB in range(7):
-            for pC in range(5):
+            for pC in range(7):
                 for policy in (G.POLICY_OPERAND, G.POLICY_C_TILE):
                     assert G.product_precision(pA, pB, pC, policy) == orc.product_precision(pA, pB, pC, policy)
     nb = 512
@@ -183,9 +183,10 @@ def test_mxfp8_codes_layout_and_where_this_build_runs_them():
     assert g.storage_bytes("A") == 6 * (nb * nb + nb * nb // 32)
     o, prec, _ = g.tile_info("A", 0, 1, want_exp=False)
     assert o == nb * nb + nb * nb // 32 and prec == G.MXFP8
-    with pytest.raises(G.GemmMPError) as e:
-        g.set_precision_map("C", np.full((2, 2), G.MXFP8, dtype=np.uint16))
-    assert e.value.status == G.EUNSUPPORTED
+    # a block-scaled C tile: its packed form, and an FP32 staging copy behind all packed tiles
+    g.set_precision_map("C", np.array([[G.MXFP8, G.FP32], [G.MXFP4, G.FP64]], dtype=np.uint16))
+    packed = (nb * nb + nb * nb // 32) + 4 * nb * nb + (nb * nb // 2 + nb * nb // 32) + 8 * nb * nb
+    assert g.storage_bytes("C") == packed + 2 * 4 * nb * nb
     g.set_precision_map("B", np.full((3, 2), G.MXFP8, dtype=np.uint16))
     g.set_precision_map("C", np.full((2, 2), G.FP32, dtype=np.uint16))
     st = g.get_stats()
@@ -216,7 +217,7 @@ def test_product_precision_and_stats_closed_forms():
             for pC in range(2):
                 assert G.product_precision(pA, pB, pC, G.POLICY_C_TILE) == pC
                 assert G.product_precision(pA, pB, pC, G.POLICY_OPERAND) == max(pC and 1, min(pA, pB))
-    assert G.product_precision(7, 0, 0) == -1 and G.product_precision(0, 0, 5) == -1
+    assert G.product_precision(7, 0, 0) == -1 and G.product_precision(0, 0, 7) == -1
     w = W.tiny()
     g = G.GemmMP(w.M, w.N, w.K, w.nb)
     for k, m in (("A", w.mapA), ("B", w.mapB), ("C", w.mapC)):

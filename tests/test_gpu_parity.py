@@ -551,6 +551,73 @@ def test_c_tiles_stored_in_fp16_and_fp8_match_the_oracle_on_general_data():
         assert low >= 4
 
 
+def test_c_tiles_stored_in_block_scaled_formats():
+    """C tiles in MXFP8 / MXFP4: accumulated in FP32 staging copies like the other narrow C tiles,
+    then stored block by block along the rows of the tile.  Small integers (|x| <= 3 fits both
+    element formats at every block maximum) must come back exactly, old C included; general data
+    must match the oracle's stored result per tile, and what the GPU stored must be a fixed point
+    of the oracle's block quantisation."""
+    import torch
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(97)
+    for nb, MT, NT, KT, cut in ((128, 2, 3, 2, (0, 0, 0)), (512, 2, 2, 2, (0, 0, 0)), (128, 3, 2, 2, (37, 101, 64))):
+        M, N, K = MT * nb, NT * nb, KT * nb
+        _say("block-scaled C tiles, integers:", (M, N, K, nb), "cut", cut)
+        A = np.zeros((M, K))
+        B = np.zeros((K, N))
+        A[np.arange(M), rng.integers(0, K, M)] = rng.integers(-1, 2, M)          # one entry per row: A @ B in {-1, 0, 1}
+        B[:] = rng.integers(-1, 2, (K, N))
+        C0 = rng.integers(-1, 2, (M, N)).astype(np.float64)
+        M, N, K = M - cut[0], N - cut[1], K - cut[2]
+        A, B, C0 = A[:M, :K], B[:K, :N], C0[:M, :N]
+        mA = rng.integers(0, 7, (MT, KT)).astype(np.uint16)
+        mB = rng.integers(0, 7, (KT, NT)).astype(np.uint16)
+        mC = rng.integers(0, 7, (MT, NT)).astype(np.uint16)
+        mC[0, 0], mC[MT - 1, NT - 1] = MXFP8, MXFP4
+        if nb == 512:
+            mA[0, :], mB[:, 0], mA[1, :], mB[:, 1] = MXFP8, MXFP8, MXFP4, MXFP4   # C(0,0), C(1,1) on the block-scaled kernel
+        want = (A.astype(np.int64) @ B.astype(np.int64)) + 2 * C0.astype(np.int64)
+        assert np.abs(want).max() <= 3
+        d = DeviceGemmMP(M, N, K, nb)
+        for k, m in (("A", mA), ("B", mB), ("C", mC)):
+            d.set_precision_map(k, m)
+        d.pack_tiles("A", _even_ld(A))
+        d.pack_tiles("B", _even_ld(B))
+        d.pack_tiles("C", _even_ld(C0))
+        assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), C0)
+        d.convert_tiles()
+        d.run(1.0, 2.0)
+        assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), want.astype(np.float64))
+        d.run(0.0, 1.0)
+        assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), want.astype(np.float64))
+        d.run(0.0, -1.0)
+        assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), -want.astype(np.float64))
+        torch.cuda.synchronize()
+
+    w = W.tiny()
+    w.mapC = rng.integers(0, 7, w.mapC.shape).astype(np.uint16)
+    w.mapC[0, :4] = (MXFP8, MXFP4, FP16, MXFP8)
+    w.alpha, w.beta = 0.75, -1.25
+    _say("block-scaled C tiles, general data")
+    A, B, C0 = _dense(w)
+    side = OracleSide(w, A, B, C0)
+    d, dev = gpu_problem(w, A, B, C0)
+    d.run(w.alpha, w.beta)
+    C_gpu = d.unpack_tiles("C").cpu().numpy()
+    torch.cuda.synchronize()
+    jobs = _all_jobs(w)
+    C_orc, _ = finish_low_c_tiles(side, side.gemm(jobs))
+    worst = compare_jobs(side, jobs, 0, w.alpha, w.beta, C_gpu, C_orc)
+    _say("  worst error / bound:", worst)
+    again, _ = finish_low_c_tiles(side, C_gpu)
+    for I in range(w.MT):
+        for J in range(w.NT):
+            if w.mapC[I, J] in (MXFP8, MXFP4):
+                blk = (slice(I * w.nb, (I + 1) * w.nb), slice(J * w.nb, (J + 1) * w.nb))
+                assert np.array_equal(again[blk], C_gpu[blk])
+                assert d.ctx.tile_info("C", I, J)[2] == 0
+
+
 def test_c_map_from_the_norm_rule_with_all_formats_and_sender_side_conversion():
     """C's own map made by the norm rule over all four formats from the old C (whose tiles decay
     away from the diagonal, so the rule picks every format), A and B likewise, operands converted

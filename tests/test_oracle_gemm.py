@@ -400,6 +400,40 @@ def test_c_tiles_stored_in_fp16_or_fp8_round_once_within_their_unit_roundoff():
             assert rel.max() > U[p] / 16                                       # and it did round
 
 
+def test_c_tiles_stored_in_block_scaled_formats_are_fp32_tiles_quantised_along_their_rows():
+    """A block-scaled C tile is an FP32 tile until it is stored: the job returns bit for bit what
+    the same job returns for an FP32 tile, and storing it quantises each block of 32 along a row
+    by that block's own maximum: element error at most half a step of the block's top binade
+    (2^-4 / 2^-2 of the block maximum's power of two for e4m3 / e2m1), except above the element
+    format's largest number (1.75 / 1.5 times that power of two), where it saturates."""
+    rng = np.random.default_rng(79)
+    nb, MT, NT, KT = 32, 2, 2, 2
+    A = rng.standard_normal((MT * nb, KT * nb))
+    B = rng.standard_normal((KT * nb, NT * nb))
+    mA = rng.integers(0, 4, (MT, KT)).astype(np.uint16)
+    mB = rng.integers(0, 4, (KT, NT)).astype(np.uint16)
+    mC = np.array([[MXFP8, MXFP4], [MXFP4, MXFP8]], dtype=np.uint16)
+    pre = _run(nb, A, mA, B, mB, None, mC, 1.5, 0.0)
+    assert np.array_equal(pre, _run(nb, A, mA, B, mB, None, np.full((MT, NT), FP32, dtype=np.uint16), 1.5, 0.0))
+    Y, e = _store(pre, nb, mC)
+    assert not e.any()
+    got = orc.stored_values(Y, nb, e)
+    seen_beyond = False
+    for I in range(MT):
+        for J in range(NT):
+            half_step, largest = (2.0 ** -4, 1.75) if mC[I, J] == MXFP8 else (2.0 ** -2, 1.5)
+            for r in range(nb):
+                row = pre[I * nb + r, J * nb:(J + 1) * nb]             # one block: nb = 32
+                top = 2.0 ** np.floor(np.log2(np.abs(row).max()))
+                out = got[I * nb + r, J * nb:(J + 1) * nb]
+                beyond = np.abs(row) > largest * top                   # above the format's largest number: saturates
+                assert np.array_equal(out[beyond], np.sign(row[beyond]) * largest * top)
+                assert np.abs(out - row)[~beyond].max() <= half_step * top
+                assert out[np.abs(row).argmax()] != 0.0
+                seen_beyond |= bool(beyond.any())
+    assert seen_beyond
+
+
 def test_product_precision_with_bf16_is_the_smallest_format_holding_both_operands():
     """BF16 and FP16 hold different numbers, so the formats form a lattice, written out here as
     sets of (fraction bits, least exponent, greatest exponent) of what each can hold once a tile
