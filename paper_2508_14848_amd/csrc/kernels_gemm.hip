@@ -1682,21 +1682,26 @@ struct BigScaleGeom {
     int soa, sob;        // byte offset of this lane's scale row, A block 0 / B block 0, from the tile's start
     int shift;           // 8 * (lane / 32)
 };
-// FMT 1 (MXFP8): four scale bytes per row and chunk, d[0..7].  FMT 2 (MXFP4): a chunk holds 256
-// reduction indices, eight scale bytes per row: those of its first half in d[0..7], of its second
-// in d[8..15].
+// One call fetches the scales of the chunk pair c, c + 1 (c even) with one load per row block.
+// (A wave's scale loads touch 32 different cache lines each, as costly for the vector memory path
+// as two of the chunk's DMA instructions: hence as few and as wide as possible.)
+// FMT 1 (MXFP8): four scale bytes per row and chunk: d[0..7] chunk c, d[8..15] chunk c + 1.
+// FMT 2 (MXFP4): a chunk holds 256 reduction indices, eight scale bytes per row: d[0..7] first half
+// of chunk c, d[8..15] its second half, d[16..31] the same of chunk c + 1.
 template <int FMT>
-__device__ __forceinline__ void big_load_scales(int (&d)[16], const BigScaleGeom &SG, uint64_t a, uint64_t b, int nb, int c)
+__device__ __forceinline__ void big_load_scales(int (&d)[32], const BigScaleGeom &SG, uint64_t a, uint64_t b, int nb, int c)
 {
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         if constexpr (FMT == 2) {
-            const u32x2 x = *(const u32x2 *)(uintptr_t)(a + (uint64_t)(SG.soa + t * nb + 8 * c));
-            const u32x2 y = *(const u32x2 *)(uintptr_t)(b + (uint64_t)(SG.sob + t * nb + 8 * c));
-            d[t] = (int)x.x; d[8 + t] = (int)x.y; d[4 + t] = (int)y.x; d[12 + t] = (int)y.y;
+            const u32x4 x = *(const u32x4 *)(uintptr_t)(a + (uint64_t)(SG.soa + t * nb + 8 * c));
+            const u32x4 y = *(const u32x4 *)(uintptr_t)(b + (uint64_t)(SG.sob + t * nb + 8 * c));
+            d[t] = (int)x.x; d[8 + t] = (int)x.y; d[16 + t] = (int)x.z; d[24 + t] = (int)x.w;
+            d[4 + t] = (int)y.x; d[12 + t] = (int)y.y; d[20 + t] = (int)y.z; d[28 + t] = (int)y.w;
         } else {
-            d[t] = (int)*(const uint32_t *)(uintptr_t)(a + (uint64_t)(SG.soa + t * nb + 4 * c));
-            d[4 + t] = (int)*(const uint32_t *)(uintptr_t)(b + (uint64_t)(SG.sob + t * nb + 4 * c));
+            const u32x2 x = *(const u32x2 *)(uintptr_t)(a + (uint64_t)(SG.soa + t * nb + 4 * c));
+            const u32x2 y = *(const u32x2 *)(uintptr_t)(b + (uint64_t)(SG.sob + t * nb + 4 * c));
+            d[t] = (int)x.x; d[8 + t] = (int)x.y; d[4 + t] = (int)y.x; d[12 + t] = (int)y.y;
         }
     }
 }
@@ -1710,21 +1715,22 @@ __device__ __forceinline__ i8v big_fp4_operand(const i8v &f, int j)
 // those of the next chunk's first half.  S2: the chunk two ahead, requested into STAGE.
 // FMT 2 (MXFP4): a half holds two reduction steps of 64 four-bit elements; the first step's MFMAs
 // carry the half's other instructions, the second step's follow.
-// FMT != 0: sc holds this chunk's block scales (see big_load_scales), sa / sb are not used; `raw` are
-// the scale words of the following chunk, loaded by the caller just before this call: they are
-// taken over (shifted into place, into `nx`) right behind the wait in the middle of the chunk,
-// the one point where nothing else is in flight, so that no other wait for them is needed.
-template <int STAGE, int FMT>
+// FMT != 0: sc holds the block scales of a chunk pair (see big_load_scales), this chunk's from
+// sc[SO] on; sa / sb are not used.  TAKE: `raw` are the scale words of the following pair, loaded
+// by the caller just before this call: they are taken over (shifted into place, into `nx`) right
+// behind the wait in the middle of the chunk, the one point where nothing else is in flight, so
+// that no other wait for them is needed.
+template <int STAGE, int FMT, bool TAKE, int SO>
 __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], const BigGeom &BG, const char *lds, const BigSource &S2,
-                                          int sa, int sb, const int (&sc)[16], const int (&raw)[16], int (&nx)[16], int shift)
+                                          int sa, int sb, const int (&sc)[32], const int (&raw)[32], int (&nx)[32], int shift)
 {
     constexpr bool MX = FMT == 1;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
-            if constexpr (FMT == 2) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[0][mt], 0), big_fp4_operand(f[0][4 + nt], 0), acc[mt][nt], 4, 4, 0, sc[mt], 0, sc[4 + nt]);
-            else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sc[mt], 0, sc[4 + nt]);
+            if constexpr (FMT == 2) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[0][mt], 0), big_fp4_operand(f[0][4 + nt], 0), acc[mt][nt], 4, 4, 0, sc[SO + mt], 0, sc[SO + 4 + nt]);
+            else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sc[SO + mt], 0, sc[SO + 4 + nt]);
             else acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
             SCHED_FENCE();
             const int k = mt * 4 + nt;                       // second half's fragments, 16 bytes per position: B first
@@ -1736,27 +1742,27 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
         for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[0][mt], 1), big_fp4_operand(f[0][4 + nt], 1), acc[mt][nt], 4, 4, 2, sc[mt], 2, sc[4 + nt]);
+                acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[0][mt], 1), big_fp4_operand(f[0][4 + nt], 1), acc[mt][nt], 4, 4, 2, sc[SO + mt], 2, sc[SO + 4 + nt]);
     }
 #if defined(__HIP_DEVICE_COMPILE__)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");         // the next chunk, requested a chunk ago, has landed
 #endif
     __syncthreads();                                         // ... in every wave; and all are done reading this stage
-    if constexpr (FMT != 0) {
+    if constexpr (TAKE) {
 #pragma unroll
-        for (int t = 0; t < (FMT == 2 ? 16 : 8); ++t) nx[t] = (int)((uint32_t)raw[t] >> shift);
+        for (int t = 0; t < (FMT == 2 ? 32 : 16); ++t) nx[t] = (int)((uint32_t)raw[t] >> shift);
 #if defined(__HIP_DEVICE_COMPILE__)
-        asm volatile("" : "+v"(nx[0]), "+v"(nx[1]), "+v"(nx[2]), "+v"(nx[3]), "+v"(nx[4]), "+v"(nx[5]), "+v"(nx[6]), "+v"(nx[7]));
-        if constexpr (FMT == 2)
-            asm volatile("" : "+v"(nx[8]), "+v"(nx[9]), "+v"(nx[10]), "+v"(nx[11]), "+v"(nx[12]), "+v"(nx[13]), "+v"(nx[14]), "+v"(nx[15]));
+#pragma unroll
+        for (int t = 0; t < (FMT == 2 ? 32 : 16); t += 8)
+            asm volatile("" : "+v"(nx[t]), "+v"(nx[t + 1]), "+v"(nx[t + 2]), "+v"(nx[t + 3]), "+v"(nx[t + 4]), "+v"(nx[t + 5]), "+v"(nx[t + 6]), "+v"(nx[t + 7]));
 #endif
     }
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
-            if constexpr (FMT == 2) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[1][mt], 0), big_fp4_operand(f[1][4 + nt], 0), acc[mt][nt], 4, 4, 0, sc[8 + mt], 0, sc[12 + nt]);
-            else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 2, sc[mt], 2, sc[4 + nt]);
+            if constexpr (FMT == 2) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[1][mt], 0), big_fp4_operand(f[1][4 + nt], 0), acc[mt][nt], 4, 4, 0, sc[SO + 8 + mt], 0, sc[SO + 12 + nt]);
+            else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 2, sc[SO + mt], 2, sc[SO + 4 + nt]);
             else acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
             SCHED_FENCE();
             const int k = mt * 4 + nt;
@@ -1769,7 +1775,7 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
         for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[1][mt], 1), big_fp4_operand(f[1][4 + nt], 1), acc[mt][nt], 4, 4, 2, sc[8 + mt], 2, sc[12 + nt]);
+                acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[1][mt], 1), big_fp4_operand(f[1][4 + nt], 1), acc[mt][nt], 4, 4, 2, sc[SO + 8 + mt], 2, sc[SO + 12 + nt]);
     }
 }
 
@@ -1857,11 +1863,13 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
         i8v f[2][8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) f[0][t] = big_read(BG, lds, 0, 0, t);
-        int sc[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, nsc[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        int sc[32], nsc[32];
+#pragma unroll
+        for (int t = 0; t < 32; ++t) sc[t] = nsc[t] = 0;
         if constexpr (MX) {
             big_load_scales<FMT>(sc, SG, S.a, S.b, nb, 0);
 #pragma unroll
-            for (int t = 0; t < 16; ++t) sc[t] = (int)((uint32_t)sc[t] >> SG.shift);
+            for (int t = 0; t < 32; ++t) sc[t] = (int)((uint32_t)sc[t] >> SG.shift);
         }
 
         for (int L = 0; L < kt; ++L) {
@@ -1886,22 +1894,25 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
             for (int c = 0; c < n; c += 2) {
                 BigSource S2 = (c + 2 < n) ? cur_src : next_src;
                 S2.c = (c + 2 < n) ? c + 2 : c + 2 - n;
-                // MX: the scales of the chunk after the one being computed are fetched under it
-                // (past the end of the reduction: those of the last chunk again, unused)
-                int nx[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-                if constexpr (MX) big_load_scales<FMT>(nsc, SG, cur_src.a, cur_src.b, nb, c + 1);
-                big_chunk<0, FMT>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
-                if constexpr (MX) {
+                // block scales of what follows are fetched under the chunk being computed (past the
+                // end of the reduction: those of the last chunks again, unused)
+                int nx[32];
 #pragma unroll
-                    for (int t = 0; t < 16; ++t) sc[t] = nx[t];
+                for (int t = 0; t < 32; ++t) nx[t] = 0;
+                if constexpr (MX) {
+                    // sc holds the scales of chunks c and c + 1; those of the next pair are requested
+                    // before the second chunk and taken over in its middle
                     const bool wrap = c + 2 >= n && nbytes != 0;
-                    big_load_scales<FMT>(nsc, SG, wrap ? next_src.a : cur_src.a, wrap ? next_src.b : cur_src.b, nb, c + 2 < n ? c + 2 : wrap ? 0 : n - 1);
-                }
-                S2.c += 1;
-                big_chunk<1, FMT>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
-                if constexpr (MX) {
+                    big_chunk<0, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
+                    big_load_scales<FMT>(nsc, SG, wrap ? next_src.a : cur_src.a, wrap ? next_src.b : cur_src.b, nb, c + 2 < n ? c + 2 : wrap ? 0 : n - 2);
+                    S2.c += 1;
+                    big_chunk<1, FMT, true, FMT == 2 ? 16 : 8>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
 #pragma unroll
-                    for (int t = 0; t < 16; ++t) sc[t] = nx[t];
+                    for (int t = 0; t < 32; ++t) sc[t] = nx[t];
+                } else {
+                    big_chunk<0, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
+                    S2.c += 1;
+                    big_chunk<1, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
                 }
             }
             lo = nlo;
