@@ -1614,6 +1614,7 @@ struct BigGeom {
     int rb[2][2][2];     // same for B (includes the operand offset)
     unsigned dst;        // LDS address of this wave's first DMA row of operand A, stage 0
     int rows8;           // byte distance of 8 tile rows
+    int rot, n;          // chunk c of a product (n of them) is chunk (c + rot) mod n of the tile rows; rot even
 };
 
 // Scale exponents of a product as the two E8M0 operands of the MFMA (bias 127, range +-127;
@@ -1653,7 +1654,9 @@ struct BigSource {
 __device__ __forceinline__ void big_request(const BigSource &S, const BigGeom &BG, int stage, int j)
 {
     const int op = j >> 3, jj = j & 7;
-    big_dma_one(op ? S.b : S.a, S.bytes, BG.voff[op][jj & 1], uni(S.c * kRowBytes + jj * BG.rows8),
+    int cc = S.c + BG.rot;
+    if (cc >= BG.n) cc -= BG.n;
+    big_dma_one(op ? S.b : S.a, S.bytes, BG.voff[op][jj & 1], uni(cc * kRowBytes + jj * BG.rows8),
                 BG.dst + (unsigned)(stage * kBigStage + op * kBigOperand + jj * 1024));
 }
 // Fragment t (0..3: A blocks of 32 rows, 4..7: B blocks) of half `hc` of the chunk in `stage`.
@@ -1681,6 +1684,7 @@ __device__ __forceinline__ void big_read_half(i8v &f, const BigGeom &BG, const c
 struct BigScaleGeom {
     int soa, sob;        // byte offset of this lane's scale row, A block 0 / B block 0, from the tile's start
     int shift;           // 8 * (lane / 32)
+    int rot, n;          // as in BigGeom
 };
 // One call fetches the scales of the chunk pair c, c + 1 (c even) with one load per row block.
 // (A wave's scale loads touch 32 different cache lines each, as costly for the vector memory path
@@ -1691,6 +1695,8 @@ struct BigScaleGeom {
 template <int FMT>
 __device__ __forceinline__ void big_load_scales(int (&d)[32], const BigScaleGeom &SG, uint64_t a, uint64_t b, int nb, int c)
 {
+    c += SG.rot;
+    if (c >= SG.n) c -= SG.n;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         if constexpr (FMT == 2) {
@@ -1813,6 +1819,11 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
         BG.voff[1][1] = BG.voff[1][0] ^ 64;
         BG.dst = (unsigned)uni(wave * (64 * kRowBytes));
         BG.rows8 = 8 * pitch;
+        BG.n = pitch / kRowBytes;
+        // Regions of one C tile run side by side on one XCD and would otherwise ask its L2 for the
+        // same 128-byte column of every panel row at the same time; each starts its pass over a
+        // product's chunks at its own (even) chunk instead.
+        BG.rot = (2 * (int)((((itw >> 32) & 0xffffu) + ((itw >> 48) & 0xffffu)) & 3u)) % BG.n;
         const int i = lane & 31, g = lane >> 5, x = (i >> 1) & 7;
 #pragma unroll
         for (int st = 0; st < 2; ++st)
@@ -1831,6 +1842,8 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
         SG.soa = nb * pitch + (arow0 + wm * 128 + (lane & 31)) * (nb / 32);
         SG.sob = nb * pitch + (brow0 + wn * 128 + (lane & 31)) * (nb / 32);
         SG.shift = 8 * (lane >> 5);
+        SG.rot = BG.rot;
+        SG.n = BG.n;
     }
 
     f16v acc[4][4];
