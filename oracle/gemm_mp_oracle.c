@@ -383,7 +383,8 @@ int32_t orc_scale_exponent(double maxabs, int32_t p)
  * FP64: copy.  FP32: C cast (round to nearest even, IEEE overflow / gradual
  * underflow).  FP16 / FP8: one direct rounding of x * 2^-e from FP64.
  * X and Y may be the same array. */
-/* mx_axis: the blocks of block-scaled tiles run along a row (0: A) or down a column (1: B). */
+/* mx_axis: the blocks of block-scaled tiles run along a row (0: A, and C, which has no reduction
+ * index: reading, Section 6 leaves such formats open) or down a column (1: B). */
 void orc_store_tiles_axis(const double *X, int64_t ld, int64_t rows, int64_t cols, int32_t nb,
                           const uint16_t *map, const double *maxabs, double *Y, int64_t ldy,
                           int32_t *exps, int32_t mx_axis)

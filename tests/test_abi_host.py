@@ -168,7 +168,7 @@ def test_bf16_codes_layout_products_and_conversion_plan():
 
 
 def test_mxfp8_codes_layout_and_where_this_build_runs_them():
-    """MXFP8 (code 5): nb^2 element bytes plus nb^2/32 scale bytes per tile, A and B only; the
+    """MXFP8 (code 5): nb^2 element bytes plus nb^2/32 scale bytes per tile (a C tile gets an FP32 staging copy besides); the
     product precision equals the oracle's; tiles made of MXFP8 x MXFP8 products only are cut into
     256 x 256 regions; statistics count such products apart."""
     from oracle import gemm_mp_oracle as orc
