@@ -817,6 +817,38 @@ def test_random_small_integer_problems_over_all_formats_are_exact():
     torch.cuda.synchronize()
 
 
+def test_256_regions_visit_every_chunk_once_at_tile_sizes_with_six_and_eight_chunks():
+    """The 256 x 256 kernels start each region's pass over a product's chunks at a chunk of its
+    own.  Integer problems (exact whatever the order of the additions) with block-wise different
+    magnitudes, at tile sizes where a product has six or eight chunks so that every starting chunk
+    and the wrap-around occur, over two products so that the scales of the next product are
+    fetched across the boundary: FP8, MXFP8 and MXFP4 tiles, C in FP32 with the old C at work."""
+    import torch
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(131)
+    for fmt, nb in ((FP8, 768), (FP8, 1024), (MXFP8, 768), (MXFP8, 1024), (MXFP4, 1536), (MXFP4, 2048)):
+        M, N, K = nb, nb, 2 * nb
+        _say("256 x 256 regions, integers:", {FP8: "FP8", MXFP8: "MXFP8", MXFP4: "MXFP4"}[fmt], (M, N, K, nb))
+        if fmt == FP8:                                   # one scale per tile: the same magnitude everywhere
+            A = rng.integers(-3, 4, (M, K)).astype(np.float64)
+            B = rng.integers(-3, 4, (K, N)).astype(np.float64)
+        else:
+            A = rng.integers(-3, 4, (M, K)) * 2.0 ** rng.integers(0, 3, (M, K // 32)).repeat(32, axis=1)
+            B = rng.integers(-3, 4, (K, N)) * 2.0 ** rng.integers(0, 3, (K // 32, N)).repeat(32, axis=0)
+        C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
+        d = DeviceGemmMP(M, N, K, nb)
+        d.set_precision_map("A", np.full((1, 2), fmt, dtype=np.uint16))
+        d.set_precision_map("B", np.full((2, 1), fmt, dtype=np.uint16))
+        d.set_precision_map("C", np.full((1, 1), FP32, dtype=np.uint16))
+        for which, X in (("A", A), ("B", B), ("C", C0)):
+            d.pack_tiles(which, torch.from_numpy(np.ascontiguousarray(X)).cuda())
+        assert np.array_equal(d.unpack_tiles("A").cpu().numpy(), A) and np.array_equal(d.unpack_tiles("B").cpu().numpy(), B)
+        assert d.ctx.get_stats()["work_items"] == (nb // 256) ** 2          # the 256 x 256 kernel
+        d.run(1.0, -1.0)
+        assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), A @ B - C0)
+        torch.cuda.synchronize()
+
+
 def test_mxfp8_tiles_pack_bit_for_bit_and_multiply_on_the_block_scaled_instruction():
     """MXFP8 tiles: element and scale bytes equal the oracle's block quantisation (blocks along the
     rows of A tiles and down the columns of B tiles, i.e. along the reduction index; a size off
