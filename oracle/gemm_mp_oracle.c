@@ -26,7 +26,12 @@
  * rational-arithmetic fused-multiply-add triple loop, integer-valued inputs
  * against exact integer products for every map, the standard gamma_k error
  * bound, tile visit-order invariance, closed forms of the precision rule and
- * of the product-precision counts.  No function here is "parity unpinned".
+ * of the product-precision counts; the receiver-side FP64 -> FP32 down-cast on
+ * FP32 midpoints against numpy's cast and an exact fmaf chain, the FP32 side
+ * accumulator and its fold into an FP64 tile re-enacted with exact fused
+ * multiply-adds, alpha and beta that FP32 cannot hold, BF16's rank and unit
+ * roundoff in the rule against the formula written out in the test.  No
+ * function here is "parity unpinned".
  *
  * Arithmetic rules used throughout: every fused multiply-add is an explicit
  * fma()/fmaf() call; the file must be compiled with -ffp-contract=off so that
@@ -40,7 +45,7 @@
 #include <omp.h>
 #endif
 
-/* Precision codes: 0/1 as in the paper's (commented) description of the map
+/* Precision codes: 0/1 as in the paper's description of the precision map
  * in Section 5.2; 2 and 3 extend it to FP16 and FP8 (OCP e4m3, "fn" variant:
  * no infinities, one NaN code per sign, max finite 448), 4 to BF16 (8 exponent
  * bits as FP32, 7 fraction bits).  The code is a name, not a rank: by unit
@@ -433,9 +438,9 @@ void orc_store_tiles(const double *X, int64_t ld, int64_t rows, int64_t cols, in
 }
 
 /* Precision of the product A(I,L)*B(L,J) that updates C(I,J).
- * POLICY_C_TILE is the paper's literal statement (Section 5.2, commented
- * text: the result precision follows the C tile, operands are converted when
- * their maps differ): q = pC.
+ * POLICY_C_TILE is the paper's literal statement (Section 5.2: the result
+ * precision follows the C tile, operands are converted when their maps
+ * differ): q = pC.
  * POLICY_OPERAND (default) is this build's reading once FP16 / FP8 exist:
  * compute at the precision of the better-stored operand, but never above
  * what the C tile keeps:  q = min(cap(pC), max(pA, pB)) in precision rank,
