@@ -53,7 +53,7 @@ def cpu_baseline(w, A, B, C0, seconds):
     """Time the oracle, as it stands, on a bounded sample of this workload's C tiles."""
     import numpy as np
     from oracle import gemm_mp_oracle as orc
-    from tests.harness import OracleSide
+    from oracle.checker import OracleSide
 
     side = OracleSide(w, A, B, C0)
     tiles = w.sample_tiles(64)

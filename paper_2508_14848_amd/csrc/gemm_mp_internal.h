@@ -135,5 +135,12 @@ hipError_t launch_low_expand(const LowTile *low_dev, int n_low, int nb, PackedVi
 hipError_t launch_low_store(const LowTile *low_dev, int n_low, int nb, PackedView c, int32_t *exps, float *part_max,
                             hipStream_t s);
 hipError_t gemm_kernel_setup();
+// One pair per kernel instance, each defined in its own translation unit (gemm_<name>.hip).
+#define GMP_DECLARE_INSTANCE(NAME) \
+    hipError_t setup_##NAME();     \
+    hipError_t launch_##NAME(const GemmArgs &a, const WorkItem *items, int n, hipStream_t s);
+GMP_DECLARE_INSTANCE(owner_d) GMP_DECLARE_INSTANCE(owner_d_mixed) GMP_DECLARE_INSTANCE(owner_d_bf)
+GMP_DECLARE_INSTANCE(owner_f) GMP_DECLARE_INSTANCE(owner_f_mixed) GMP_DECLARE_INSTANCE(owner_f_bf)
+GMP_DECLARE_INSTANCE(region_fp8) GMP_DECLARE_INSTANCE(region_mxfp8) GMP_DECLARE_INSTANCE(region_mxfp4)
 
 }  // namespace gmp

@@ -8,6 +8,7 @@ import pytest
 
 import workloads as W
 from oracle import gemm_mp_oracle as orc
+from oracle.checker import planted_mistake_is_caught
 from tests.harness import (BF16, FP8, FP16, FP32, FP64, MXFP4, MXFP8, OracleSide, compare_jobs, finish_low_c_tiles, gpu_problem,
                            packed_codes_expected)
 
@@ -61,6 +62,9 @@ def _run_and_compare(w, policy=0, jobs=None, check_storage_tiles=4, alpha=None, 
     C_orc = side.gemm(jobs, policy=policy, alpha=alpha, beta=beta)
     worst = compare_jobs(side, jobs, policy, alpha, beta, C_gpu, C_orc)
     _say("  worst error / bound:", worst)
+    # the comparison must be able to fail: a misplaced element of the result (host copy) is caught
+    caught = planted_mistake_is_caught(side, jobs, policy, alpha, beta, C_gpu, C_orc)
+    _say("  planted misplaced element caught:", caught)
     return d, side, C_gpu, C_orc
 
 
@@ -1217,14 +1221,17 @@ def test_paper_ratio_runs_match_the_oracle(pct):
 
 
 def test_config_cov64k_sampled_blocks():
-    """The largest configuration (65536^3, 2048-wide tiles): 16 rows of each of 66 C tiles."""
+    """The largest configuration (65536^3, 2048-wide tiles): 8 whole C tiles of the seeded sample
+    and 16 rows of each of the 66 sampled tiles, the rows placed so that every one of the 16 rows
+    of owner regions of a tile is met; per tile and per element."""
     w = W.CONFIGS["cov64k"]()
     tiles = sorted(set(w.sample_tiles(64)) | {(0, 0), (w.MT // 2, w.NT // 2 + 1)})
     rng = np.random.default_rng(11)
-    jobs = []
-    for (I, J) in tiles:
-        r0 = int(rng.integers(0, w.nb - 16))
+    jobs = [[I, J, 0, w.nb, 0, w.nb] for (I, J) in tiles[::len(tiles) // 8][:8]]
+    for k, (I, J) in enumerate(tiles):
+        r0 = (k % 16) * 128 + int(rng.integers(0, 128 - 16))
         jobs.append([I, J, r0, r0 + 16, 0, w.nb])
+    assert {j[2] // 128 for j in jobs[8:]} == set(range(16))
     jobs = np.array(jobs, dtype=np.int32)
     d, side, _, _ = _run_and_compare(w, jobs=jobs, check_storage_tiles=2)
     st = d.ctx.get_stats()
