@@ -6,10 +6,14 @@ already resident in HBM: tile scan + norm rule (where the workload's maps come f
 pack of A and B (and of C when beta != 0), schedule, and gemm_mp_run.  Unpacking is
 verification only and is not timed.
 
+The default workload is the largest single-GPU configuration, cov64k (65536^3, tile 2048).  With
+no --workload given the two other large configurations (cov16k, rect32k) are run after it, a few
+steps each, and reported under "also" in the same line.
+
 Prints ONE JSON line.  `value` is the effective rate 2*M*N*K / t_step in TFLOP/s; `roofline`
-prices the dominant kernel (the owner-workgroup GEMM kernel) against the precision-weighted
-MFMA peak of this workload's product mix; `cpu_baseline` is the CPU oracle timed on a bounded
-sample of the same workload on this machine's host cores.
+prices gemm_mp_run (the owner-workgroup GEMM kernels) against the precision-weighted MFMA peak of
+this workload's product mix; `cpu_baseline` is the CPU oracle timed on a bounded sample of the
+same workload on this machine's host cores.
 """
 import argparse
 import json
@@ -22,7 +26,13 @@ sys.path.insert(0, ROOT)
 
 # MI355X published dense peaks, TFLOP/s, by product precision code (FP64, FP32, FP16, FP8).
 PEAK_TFLOPS = [78.6, 157.3, 2516.6, 5033.2]
+PEAK_FP4_TFLOPS = 10066.4
 DTYPE_NAMES = ["f64", "f32", "f16", "f8e4m3"]
+HEADLINE = "cov64k"
+ALSO = ("cov16k", "rect32k")
+KERNEL_NAMES = ["gemm_mp_owner_kernel<double%s>", "gemm_mp_owner_kernel<float%s>", "gemm_mp_fp8_region_kernel<0>",
+                "gemm_mp_fp8_region_kernel<1>", "gemm_mp_fp8_region_kernel<2>"]
+INSTANCE = [", false, false", ", true, false", ", true, true"]
 
 
 def parse():
@@ -30,20 +40,22 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="cov16k",
+    ap.add_argument("--workload", default=None,
                     choices=["tiny", "random8k", "cov16k", "rect32k", "cov64k",
                              "paper100", "paper80", "paper50", "paper20", "paper0",
                              "format-fp64", "format-fp32", "format-fp16", "format-fp8", "format-bf16", "format-mxfp8",
                              "format-mxfp4"],
-                    help="paperNN: the paper's own runs, NN %% of the tiles FP64 and the rest FP32 (Section 5.2); "
-                         "format-X: 16384^3, tile 1024, every tile of A and B stored as X (per-format rates; no CPU baseline)")
+                    help="default: cov64k, followed by short runs of cov16k and rect32k.  paperNN: the paper's own runs, "
+                         "NN %% of the tiles FP64 and the rest FP32 (Section 5.2); format-X: 16384^3, tile 1024, every tile "
+                         "of A and B stored as X (per-format rates; no CPU baseline)")
     ap.add_argument("--policy", type=int, default=None, choices=[0, 1],
                     help="0 = operand policy, 1 = C-tile policy (default: the workload's own)")
     ap.add_argument("--conversion", default="receiver", choices=["receiver", "sender"],
                     help="receiver: every task converts its operands on the fly (the paper's strategy); sender: tiles are "
                          "converted once per needed precision into a workspace before the run (timed as its own stage)")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--cpu-seconds", type=float, default=24.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-also", action="store_true", help="only the headline workload")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy, three times (reference for the HBM byte counters)")
     return ap.parse_args()
@@ -94,33 +106,18 @@ def cpu_baseline(w, A, B, C0, seconds):
                       % (done_rows, nb, len(jobs), w.name, done_rows * flops_per_row)}
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build is a one-GPU path (no sharding, no collectives); run with --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
+def measure(name, steps, warmup, policy, conversion, cpu_seconds):
+    """Run one workload; returns the fields of its JSON record.  cpu_seconds = 0: no CPU baseline."""
     import numpy as np
     import torch
 
     import workloads as W
-    from paper_2508_14848_amd import gemm_mp as G
     from paper_2508_14848_amd.device import DeviceGemmMP
 
-    G.lib()
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    if args.calibrate_copy:
-        src = torch.ones(1 << 27, dtype=torch.float64, device=dev)          # 1 GiB
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"calibration": "plain copy", "bytes_read": src.numel() * 8, "bytes_written": src.numel() * 8}))
-        return
-    w = W.CONFIGS[args.workload]()
-    if args.policy is None:
-        args.policy = w.policy
+    w = W.CONFIGS[name]()
+    if policy is None:
+        policy = w.policy
     t0 = time.perf_counter()
     A = w.dense("A")
     B = A if w.a_equals_b else w.dense("B")
@@ -131,12 +128,13 @@ def main():
     dC = torch.from_numpy(C0).to(dev) if C0 is not None else None
     torch.cuda.synchronize()
 
-    d = DeviceGemmMP(w.M, w.N, w.K, w.nb, device=dev, policy=args.policy)
+    d = DeviceGemmMP(w.M, w.N, w.K, w.nb, device=dev, policy=policy)
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    stage_ms = {"scan_rule": [], "pack": [], "convert": [], "run": []}
+    stage_names = ("scan_rule", "pack", "convert", "schedule", "run")
+    stage_ms = {k: [] for k in stage_names}
 
     def step(record):
-        e = [ev() for _ in range(5)]
+        e = [ev() for _ in range(6)]
         e[0].record()
         if w.rule is not None:
             d.compute_precision_map("A", dA, w.rule["eps"], w.rule["allowed"])
@@ -151,25 +149,27 @@ def main():
         if dC is not None:
             d.pack_tiles("C", dC)
         e[2].record()
-        if args.conversion == "sender":
+        if conversion == "sender":
             d.convert_tiles()
         e[3].record()
-        d.run(w.alpha, w.beta)
+        d.prepare()                   # the schedule: host work plus small copies queued on the stream
         e[4].record()
+        d.run(w.alpha, w.beta)        # the product table kernel and the GEMM launches, nothing else
+        e[5].record()
         if record:
             torch.cuda.synchronize()
-            for k, (a, b) in zip(("scan_rule", "pack", "convert", "run"), ((0, 1), (1, 2), (2, 3), (3, 4))):
-                stage_ms[k].append(e[a].elapsed_time(e[b]))
+            for k, a in zip(stage_names, range(5)):
+                stage_ms[k].append(e[a].elapsed_time(e[a + 1]))
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step(False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step(True)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = wall / args.steps * 1e3
+    ms_per_step = wall / steps * 1e3
 
     st = d.ctx.get_stats()
     flops_total = 2.0 * w.M * w.N * w.K
@@ -177,28 +177,35 @@ def main():
     t_roof = sum(f / (p * 1e12) for f, p in zip(st["flops"], PEAK_TFLOPS))          # seconds
     t_roof += st["flops_bf16"] / (PEAK_TFLOPS[2] * 1e12)                             # BF16 peak = FP16 peak
     t_roof += st["flops_mxfp8"] / (PEAK_TFLOPS[3] * 1e12)                            # block-scaled FP8: the FP8 peak
-    t_roof += st["flops_mxfp4"] / (10066.4 * 1e12)                                   # block-scaled FP4: 10.1 PFLOP/s
+    t_roof += st["flops_mxfp4"] / (PEAK_FP4_TFLOPS * 1e12)                           # block-scaled FP4: 10.1 PFLOP/s
     run_ms = float(np.mean(stage_ms["run"]))
     achieved = flops_total / (run_ms * 1e-3) / 1e12
     peak_mix = flops_total / t_roof / 1e12
-    traffic = None
+    traffic, traffic_from = None, None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        key = w.name + ("" if args.policy == w.policy else "-policy%d" % args.policy) + ("" if args.conversion == "receiver" else "-sender")
-        traffic = json.load(open(tpath)).get(key, {}).get("bytes_per_launch")
+        key = w.name + ("" if policy == w.policy else "-policy%d" % policy) + ("" if conversion == "receiver" else "-sender")
+        entry = json.load(open(tpath)).get(key)
+        if entry:
+            traffic, traffic_from = entry.get("bytes_per_launch"), "profiles/traffic.json: " + entry.get("source", "")
     used = [DTYPE_NAMES[q] for q in range(4) if st["products"][q]]
     used += [n for n in ("bf16", "mxfp8", "mxfp4") if st["products_" + n]]
+    launched = []
+    for k, n in enumerate(st["launch_items"][:5]):
+        if n:
+            kn = KERNEL_NAMES[k]
+            launched.append({"kernel": kn % INSTANCE[st["owner_instance"][k]] if k < 2 else kn, "workgroups": n})
     out = {
         "metric": "effective TFLOP/s (2MNK/t) and % of precision-weighted MFMA peak, 1 GPU",
         "value": flops_total / (ms_per_step * 1e-3) / 1e12,
         "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "+".join(used), "data": "synthetic",
         "config": {"workload": w.name, "M": w.M, "N": w.N, "K": w.K, "tile_nb": w.nb,
-                   "alpha": w.alpha, "beta": w.beta, "policy": ["operand", "c_tile"][args.policy],
-                   "conversion": args.conversion, "converted_tiles": st["converted_tiles"],
+                   "alpha": w.alpha, "beta": w.beta, "policy": ["operand", "c_tile"][policy],
+                   "conversion": conversion, "converted_tiles": st["converted_tiles"],
                    "converted_bytes": st["converted_bytes"],
                    "products_by_precision": dict(list(zip(DTYPE_NAMES, st["products"])) +
                                                  [(n, st["products_" + n]) for n in ("bf16", "mxfp8", "mxfp4") if st["products_" + n]]),
@@ -206,14 +213,51 @@ def main():
         "stages_ms": {k: float(np.mean(v)) for k, v in stage_ms.items()},
         "run_only": {"ms": run_ms, "min_ms": float(np.min(stage_ms["run"])), "effective_tflops": achieved,
                      "roofline_ms": t_roof * 1e3, "frac_of_precision_weighted_peak": t_roof * 1e3 / run_ms},
-        "roofline": {"bound": "mfma", "kernel": "gemm_mp_run: gemm_mp_owner_kernel<double|float> + gemm_mp_fp8_region_kernel", "achieved": achieved, "peak": peak_mix,
-                     "unit": "TFLOP/s", "frac": achieved / peak_mix, "traffic": traffic,
+        "roofline": {"bound": "mfma", "kernel": "gemm_mp_run: product_table_kernel + " + " + ".join(k["kernel"] for k in launched),
+                     "launches": launched, "achieved": achieved, "peak": peak_mix,
+                     "unit": "TFLOP/s", "frac": achieved / peak_mix, "traffic": traffic, "traffic_source": traffic_from,
                      "note": "peak = 2MNK / sum_q(F_q/P_q), P = 78.6/157.3/2516.6/5033.2 TFLOP/s for f64/f32/f16/f8; "
-                             "achieved = 2MNK / mean event time of gemm_mp_run on its stream (product table and up to three "
-                             "GEMM launches: FP64 C tiles, FP32 C tiles, FP32 C tiles of FP8 products only)"},
+                             "achieved = 2MNK / mean HIP-event time of gemm_mp_run on its stream (the launches listed); "
+                             "traffic = HBM bytes per gemm_mp_run from rocprofv3 counter passes of this command, kept in "
+                             "profiles/ (null: no pass recorded for this workload)"},
     }
-    if not args.no_cpu_baseline and not w.name.startswith("format-"):
-        out["cpu_baseline"] = cpu_baseline(w, A, B, C0, args.cpu_seconds)
+    if cpu_seconds > 0 and not w.name.startswith("format-"):
+        out["cpu_baseline"] = cpu_baseline(w, A, B, C0, cpu_seconds)
+    del d, dA, dB, dC, A, B, C0
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build is a one-GPU path (no sharding, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2508_14848_amd import gemm_mp as G
+
+    G.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate_copy:
+        src = torch.ones(1 << 27, dtype=torch.float64, device="cuda:0")          # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "plain copy", "bytes_read": src.numel() * 8, "bytes_written": src.numel() * 8}))
+        return
+    name = args.workload or HEADLINE
+    out = measure(name, args.steps, args.warmup, args.policy, args.conversion, 0.0 if args.no_cpu_baseline else args.cpu_seconds)
+    if args.workload is None and not args.no_also:
+        # the other configurations of 16384^3 and more, a few steps each: run-only figures
+        out["also"] = {}
+        for other in ALSO:
+            r = measure(other, min(args.steps, 5), min(args.warmup, 2), None, args.conversion, 0.0)
+            out["also"][other] = {"ms_per_step": r["ms_per_step"], "value": r["value"], "run_only": r["run_only"],
+                                  "roofline_frac": r["roofline"]["frac"], "launches": r["roofline"]["launches"],
+                                  "products_by_precision": r["config"]["products_by_precision"], "steps": r["steps"]}
     print(json.dumps(out), flush=True)
 
 

@@ -19,8 +19,14 @@
  *   - Precision maps and everything returned through pointers marked "host"
  *     live in HOST memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Calls marked [async] only enqueue work on it; calls marked [sync] wait
- *     for it before they return.
+ *     Calls marked [async] only enqueue work on it (kernels and small
+ *     host-to-device copies from pinned memory that the library owns); calls
+ *     marked [sync] wait for it before they return.  The [async] calls on one
+ *     context must be issued on one stream, or on streams the caller has
+ *     ordered: each reads what the one before it queued.  The first [async]
+ *     call that meets a new shape allocates the library's tables (which waits
+ *     for the device); afterwards a context that sees maps of the same shapes
+ *     again allocates nothing and waits for nothing in those calls.
  *   - The library never allocates or frees operand memory.  The caller asks
  *     gemm_mp_storage_bytes() and binds a device buffer of at least that size
  *     per matrix; the buffer must stay valid until the context is destroyed or
@@ -121,6 +127,11 @@ typedef struct gemm_mp_stats {
     int64_t products_mxfp4;  /* the same for precision code 6 */
     double flops_mxfp4;
     int64_t tiles_mxfp4[3];
+    int64_t launch_items[8]; /* owner workgroups per kernel launch of gemm_mp_run: [0] 128 x 128 regions of
+                              * FP64 C tiles, [1] of C tiles accumulated in FP32, [2] / [3] / [4] 256 x 256
+                              * regions of tiles made of FP8 / MXFP8 / MXFP4 products only; the rest 0 */
+    int32_t owner_instance[2]; /* which instance of the 128 x 128 kernel serves [0] and [1]: 0 plain, 1 the one
+                              * whose DMA ring also takes FP16 products with an FP8 operand, 2 the BF16 one */
 } gemm_mp_stats;
 
 /* Create a context for C(MxN) = A(MxK) * B(KxN) with square tiles of tile_nb (Section 4:
@@ -195,6 +206,15 @@ int gemm_mp_bind_storage(gemm_mp_ctx *ctx, char which, void *dev_ptr, size_t byt
 int gemm_mp_pack_tiles(gemm_mp_ctx *ctx, char which, const double *dense_dev, int64_t ld,
                        gemm_mp_stream stream);
 
+/* Prepare [async] (optional): everything gemm_mp_run needs besides the packed data, for the
+ * current maps and policy: the schedule (which owner workgroup computes which region of which C
+ * tile, the precision of every tile product: the precision-bucketed task lists that stand in for
+ * the paper's runtime scheduling, Section 3) is built on the host and its tables are queued for
+ * copying on `stream`, and the library's device tables get their size.  gemm_mp_run does the same
+ * by itself when it finds it undone; calling this first, outside the timed or latency-critical
+ * part, leaves gemm_mp_run with nothing but kernel launches.  ESTATE until all three maps are set. */
+int gemm_mp_prepare(gemm_mp_ctx *ctx, gemm_mp_stream stream);
+
 /* Run [async]: C <- alpha*A*B + beta*C on the packed tiles (Algorithm 1; beta is applied once
  * per C tile, as in the definition in Section 4).  For each C tile the reduction tiles L are
  * taken in ascending order; a product whose precision equals the C tile's accumulate type
@@ -253,6 +273,11 @@ int gemm_mp_tile_info(gemm_mp_ctx *ctx, char which, int32_t I, int32_t J, size_t
 /* Product and storage statistics of the current maps and policy; ESTATE until all three maps
  * are set.  Host only. */
 int gemm_mp_get_stats(gemm_mp_ctx *ctx, gemm_mp_stats *out);
+
+/* How often this context has allocated device or pinned host memory, and how often it has made the
+ * host wait for the device, since it was created (either pointer may be NULL).  For callers and
+ * tests that must know that a steady-state loop of pack / prepare / run does neither.  Host only. */
+int gemm_mp_host_counters(gemm_mp_ctx *ctx, int64_t *allocations, int64_t *host_waits);
 
 /* Product precision the given policy assigns (pure function; -1 on a bad code). */
 int gemm_mp_product_precision(int pA, int pB, int pC, int policy);

@@ -13,6 +13,22 @@ using namespace gmp;
 
 namespace {
 
+// A small table that lives twice: in device memory, where the kernels read it, and in pinned host
+// memory, where the host composes it and from where it is copied with hipMemcpyAsync on the
+// caller's stream.  Both grow on demand and are never shrunk, so a context that sees the same
+// shapes again allocates nothing.  The pinned half has two slots used in turn, each with an
+// event that marks its last upload: the host rewrites a slot only after that upload has left,
+// which it finds to be so without waiting unless it is two uploads ahead of the device.
+template <typename T>
+struct Mirror {
+    T *dev = nullptr;
+    T *pin[2] = {nullptr, nullptr};
+    hipEvent_t sent[2] = {nullptr, nullptr};
+    bool pending[2] = {false, false};
+    int slot = 0;
+    size_t cap = 0;
+};
+
 struct Matrix {
     int64_t rows = 0, cols = 0;    // entries of the dense matrix
     int rows_t = 0, cols_t = 0;    // tiles: ceil(rows / nb), ceil(cols / nb)
@@ -27,16 +43,17 @@ struct Matrix {
     bool exps_valid = false;       // device exponents describe the packed (or to-be-packed) data
     bool exps_from_rule = false;   // ... and were taken from the scan of the norm rule
     bool tables_current = false;   // device copies of prec / offset match the host map
-    uint8_t *d_prec = nullptr;
-    uint64_t *d_offset = nullptr;
+    Mirror<uint8_t> prec;          // [tiles] precision codes
+    Mirror<uint64_t> off;          // [tiles] byte offsets
     int32_t *d_exp = nullptr;
     double *d_sumsq = nullptr, *d_maxabs = nullptr, *d_part_sum = nullptr, *d_part_max = nullptr;
     // C only: the tiles stored in FP16 / FP8, each with an FP32 staging copy behind the packed
     // tiles; the offset table the GEMM kernels see points those tiles at their staging copies
     std::vector<LowTile> low;
-    LowTile *d_low = nullptr;
-    uint64_t *d_offset_run = nullptr;
+    Mirror<LowTile> lowt;
+    Mirror<uint64_t> off_run;
     float *d_low_max = nullptr;
+    size_t low_max_cap = 0;
     hipStream_t last_stream = nullptr;
     int ntiles() const { return rows_t * cols_t; }
 };
@@ -53,9 +70,14 @@ struct gemm_mp_ctx {
     std::vector<WorkItem> items[5];   // regions of [0] FP64 C tiles, [1] C tiles accumulated in FP32 (stored
                                       // FP32 / FP16 / FP8), [2] those of them whose products are all
                                       // FP8 x FP8 (256 x 256 regions), [3] / [4] the same for MXFP8 x MXFP8 / MXFP4 x MXFP4
-    uint8_t *d_q = nullptr;
+    Mirror<uint8_t> qd;               // [MT*NT][KT] product precision of every task
+    Mirror<WorkItem> itemsd;          // the lists, [0] first
     ProductDesc *d_prod = nullptr;    // one record per task (+ 2 padding records), filled on the device
-    WorkItem *d_items = nullptr;      // the three lists, [0] first
+    size_t prod_cap = 0;
+    bool sched_uploaded = false;      // the device copies of q and the lists are those of the current schedule
+    hipStream_t sched_stream = nullptr;
+    int64_t n_allocs = 0;             // device / pinned allocations this context has made
+    int64_t n_syncs = 0;              // times it made the host wait for the device
     gemm_mp_stats stats;
     bool mixed32 = false;             // list [1] holds an FP16 / BF16 product with an operand stored in FP8
     bool mixed64 = false;             // the same for list [0]
@@ -89,21 +111,83 @@ int which_index(char w)
 
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) { (void)hipGetLastError(); return GEMM_MP_EHIP; } } while (0)
 
+// Device allocation of a table that is made once and kept (n elements + padding for the aligned
+// word reads of byte tables).
 template <typename T>
-int dev_alloc(T **p, size_t n)
+int dev_alloc(gemm_mp_ctx *c, T **p, size_t n)
 {
     if (*p) return GEMM_MP_OK;
     if (hipMalloc((void **)p, n * sizeof(T) + 16) != hipSuccess) { (void)hipGetLastError(); *p = nullptr; return GEMM_MP_ENOMEM; }
+    c->n_allocs += 1;
+    return GEMM_MP_OK;
+}
+
+// Room for n elements in both halves of a mirror.  Growing frees the old halves (hipFree waits
+// for the device, so nothing still reads them).
+template <typename T>
+void release(Mirror<T> &m)
+{
+    (void)hipFree(m.dev);
+    for (int k = 0; k < 2; ++k) {
+        (void)hipHostFree(m.pin[k]);
+        if (m.sent[k]) (void)hipEventDestroy(m.sent[k]);
+        m.pin[k] = nullptr; m.sent[k] = nullptr; m.pending[k] = false;
+    }
+    m.dev = nullptr; m.cap = 0;
+}
+template <typename T>
+int reserve(gemm_mp_ctx *c, Mirror<T> &m, size_t n)
+{
+    if (m.cap >= n && m.dev) return GEMM_MP_OK;
+    release(m);
+    bool ok = hipMalloc((void **)&m.dev, n * sizeof(T) + 16) == hipSuccess;
+    for (int k = 0; ok && k < 2; ++k)
+        ok = hipHostMalloc((void **)&m.pin[k], n * sizeof(T) + 16, hipHostMallocDefault) == hipSuccess &&
+             hipEventCreateWithFlags(&m.sent[k], hipEventDisableTiming) == hipSuccess;
+    if (!ok) { (void)hipGetLastError(); release(m); return GEMM_MP_ENOMEM; }
+    c->n_allocs += 3;
+    m.cap = n;
+    return GEMM_MP_OK;
+}
+// The pinned slot the host may compose the next version of the table in (null on a HIP error).
+template <typename T>
+T *begin_write(gemm_mp_ctx *c, Mirror<T> &m)
+{
+    m.slot ^= 1;
+    if (m.pending[m.slot]) {
+        if (hipEventQuery(m.sent[m.slot]) != hipSuccess) {
+            (void)hipGetLastError();
+            if (hipEventSynchronize(m.sent[m.slot]) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+            c->n_syncs += 1;
+        }
+        m.pending[m.slot] = false;
+    }
+    return m.pin[m.slot];
+}
+// Queue the copy of the first n elements of that slot to the device half on stream s.
+template <typename T>
+int upload(Mirror<T> &m, size_t n, hipStream_t s)
+{
+    if (n) HIP_TRY(hipMemcpyAsync(m.dev, m.pin[m.slot], n * sizeof(T), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipEventRecord(m.sent[m.slot], s));
+    m.pending[m.slot] = true;
+    return GEMM_MP_OK;
+}
+int host_wait(gemm_mp_ctx *c, hipStream_t s)
+{
+    HIP_TRY(hipStreamSynchronize(s));
+    c->n_syncs += 1;
     return GEMM_MP_OK;
 }
 
 void free_matrix_tables(Matrix &m)
 {
-    (void)hipFree(m.d_prec); (void)hipFree(m.d_offset); (void)hipFree(m.d_exp);
+    release(m.prec); release(m.off); release(m.lowt); release(m.off_run);
+    (void)hipFree(m.d_exp);
     (void)hipFree(m.d_sumsq); (void)hipFree(m.d_maxabs); (void)hipFree(m.d_part_sum); (void)hipFree(m.d_part_max);
-    (void)hipFree(m.d_low); (void)hipFree(m.d_offset_run); (void)hipFree(m.d_low_max);
-    m.d_low = nullptr; m.d_offset_run = nullptr; m.d_low_max = nullptr;
-    m.d_prec = nullptr; m.d_offset = nullptr; m.d_exp = nullptr;
+    (void)hipFree(m.d_low_max);
+    m.d_low_max = nullptr; m.low_max_cap = 0;
+    m.d_exp = nullptr;
     m.d_sumsq = m.d_maxabs = m.d_part_sum = m.d_part_max = nullptr;
 }
 
@@ -134,7 +218,6 @@ void layout(gemm_mp_ctx *c, Matrix &m, bool is_c)
 int install_map(gemm_mp_ctx *c, int w, const uint16_t *map)
 {
     Matrix &m = c->mat[w];
-    if (m.last_stream || m.d_prec) (void)hipStreamSynchronize(m.last_stream);   // tables may be in use
     m.map.assign(map, map + m.ntiles());
     m.has_map = true;
     layout(c, m, w == 2);
@@ -145,39 +228,51 @@ int install_map(gemm_mp_ctx *c, int w, const uint16_t *map)
     m.exps_from_rule = false;
     m.tables_current = false;
     c->sched_current = false;
+    c->sched_uploaded = false;
     return GEMM_MP_OK;
 }
 
-// Device copies of the per-tile tables (small; owned by the library).
-int ensure_tables(Matrix &m)
+// Device copies of the per-tile tables (small; owned by the library), brought up to date with
+// copies queued on stream s: later work on s sees them, and nothing here waits for the device
+// once the tables have their size.
+int ensure_tables(gemm_mp_ctx *c, Matrix &m, hipStream_t s)
 {
     const size_t n = (size_t)m.ntiles();
     int rc;
-    if ((rc = dev_alloc(&m.d_prec, n))) return rc;
-    if ((rc = dev_alloc(&m.d_offset, n))) return rc;
+    if ((rc = reserve(c, m.prec, n)) || (rc = reserve(c, m.off, n))) return rc;
     if (!m.d_exp) {
-        if ((rc = dev_alloc(&m.d_exp, n))) return rc;
-        HIP_TRY(hipMemset(m.d_exp, 0, n * sizeof(int32_t)));
+        if ((rc = dev_alloc(c, &m.d_exp, n))) return rc;
+        HIP_TRY(hipMemsetAsync(m.d_exp, 0, n * sizeof(int32_t), s));
     }
-    if (!m.tables_current) {
-        std::vector<uint8_t> p8(n);
-        for (size_t t = 0; t < n; ++t) p8[t] = (uint8_t)m.map[t];
-        HIP_TRY(hipMemcpy(m.d_prec, p8.data(), n, hipMemcpyHostToDevice));
-        HIP_TRY(hipMemcpy(m.d_offset, m.offset.data(), n * sizeof(uint64_t), hipMemcpyHostToDevice));
-        (void)hipFree(m.d_low); (void)hipFree(m.d_offset_run); (void)hipFree(m.d_low_max);
-        m.d_low = nullptr; m.d_offset_run = nullptr; m.d_low_max = nullptr;
-        if (!m.low.empty()) {
-            const size_t elems = (size_t)((m.bytes - m.low[0].stage) / m.low.size() / sizeof(float));   // nb * nb
-            std::vector<uint64_t> run(m.offset);
-            for (const LowTile &lt : m.low) run[lt.tile] = lt.stage;
-            if ((rc = dev_alloc(&m.d_low, m.low.size()))) return rc;
-            if ((rc = dev_alloc(&m.d_offset_run, n))) return rc;
-            if ((rc = dev_alloc(&m.d_low_max, m.low.size() * (elems / kLowChunk)))) return rc;
-            HIP_TRY(hipMemcpy(m.d_low, m.low.data(), m.low.size() * sizeof(LowTile), hipMemcpyHostToDevice));
-            HIP_TRY(hipMemcpy(m.d_offset_run, run.data(), n * sizeof(uint64_t), hipMemcpyHostToDevice));
+    if (m.tables_current) return GEMM_MP_OK;
+    if (!m.low.empty()) {
+        const size_t elems = (size_t)((m.bytes - m.low[0].stage) / m.low.size() / sizeof(float));   // nb * nb
+        const size_t need = m.low.size() * (elems / kLowChunk);
+        if ((rc = reserve(c, m.lowt, n)) || (rc = reserve(c, m.off_run, n))) return rc;
+        if (m.low_max_cap < need) {
+            (void)hipFree(m.d_low_max);
+            m.d_low_max = nullptr;
+            m.low_max_cap = 0;
+            if ((rc = dev_alloc(c, &m.d_low_max, need))) return rc;
+            m.low_max_cap = need;
         }
-        m.tables_current = true;
     }
+    uint8_t *p8 = begin_write(c, m.prec);
+    uint64_t *po = begin_write(c, m.off);
+    if (!p8 || !po) return GEMM_MP_EHIP;
+    for (size_t t = 0; t < n; ++t) p8[t] = (uint8_t)m.map[t];
+    std::memcpy(po, m.offset.data(), n * sizeof(uint64_t));
+    if ((rc = upload(m.prec, n, s)) || (rc = upload(m.off, n, s))) return rc;
+    if (!m.low.empty()) {
+        uint64_t *pr = begin_write(c, m.off_run);
+        LowTile *pl = begin_write(c, m.lowt);
+        if (!pr || !pl) return GEMM_MP_EHIP;
+        std::memcpy(pr, m.offset.data(), n * sizeof(uint64_t));
+        for (const LowTile &lt : m.low) pr[lt.tile] = lt.stage;
+        std::memcpy(pl, m.low.data(), m.low.size() * sizeof(LowTile));
+        if ((rc = upload(m.lowt, m.low.size(), s)) || (rc = upload(m.off_run, n, s))) return rc;
+    }
+    m.tables_current = true;
     return GEMM_MP_OK;
 }
 
@@ -185,18 +280,18 @@ int ensure_scan_buffers(gemm_mp_ctx *c, Matrix &m)
 {
     const size_t n = (size_t)m.ntiles(), parts = (size_t)(c->nb / kScanCols);
     int rc;
-    if ((rc = dev_alloc(&m.d_sumsq, n))) return rc;
-    if ((rc = dev_alloc(&m.d_maxabs, n))) return rc;
-    if ((rc = dev_alloc(&m.d_part_sum, n * parts))) return rc;
-    if ((rc = dev_alloc(&m.d_part_max, n * parts))) return rc;
+    if ((rc = dev_alloc(c, &m.d_sumsq, n))) return rc;
+    if ((rc = dev_alloc(c, &m.d_maxabs, n))) return rc;
+    if ((rc = dev_alloc(c, &m.d_part_sum, n * parts))) return rc;
+    if ((rc = dev_alloc(c, &m.d_part_max, n * parts))) return rc;
     return GEMM_MP_OK;
 }
 
 PackedView view_of(const Matrix &m)
 {
     PackedView v;
-    v.prec = m.d_prec;
-    v.offset = m.d_offset;
+    v.prec = m.prec.dev;
+    v.offset = m.off.dev;
     v.exp = m.d_exp;
     v.storage = (char *)m.storage;
     return v;
@@ -383,25 +478,45 @@ void build_schedule(gemm_mp_ctx *c)
         }
     }
     c->stats.work_items = (int64_t)(c->items[0].size() + c->items[1].size() + c->items[2].size() + c->items[3].size() + c->items[4].size());
+    for (int list = 0; list < 5; ++list) c->stats.launch_items[list] = (int64_t)c->items[list].size();
+    c->stats.owner_instance[0] = c->has_bf16 ? 2 : c->mixed64 ? 1 : 0;
+    c->stats.owner_instance[1] = c->has_bf16 ? 2 : c->mixed32 ? 1 : 0;
     c->sched_current = true;
 }
 
-int upload_schedule(gemm_mp_ctx *c)
+// The schedule of the current maps and policy on the device: built on the host if it is not
+// current, composed in pinned memory and copied with hipMemcpyAsync on stream s.  The device
+// tables are sized for the largest schedule these shapes can have, so a context allocates them
+// once.
+int prepare_schedule(gemm_mp_ctx *c, hipStream_t s)
 {
-    (void)hipFree(c->d_q); (void)hipFree(c->d_items); (void)hipFree(c->d_prod);
-    c->d_q = nullptr; c->d_items = nullptr; c->d_prod = nullptr;
+    if (!c->sched_current) build_schedule(c);
+    if (c->sched_uploaded) return GEMM_MP_OK;
+    const size_t tasks = c->q.size();
+    const size_t per_tile = (size_t)(c->nb / kMacro) * (size_t)(c->nb / kMacro);
+    const size_t max_items = (size_t)c->MT * c->NT * per_tile;
     int rc;
-    if ((rc = dev_alloc(&c->d_q, c->q.size()))) return rc;
-    if ((rc = dev_alloc(&c->d_prod, c->q.size() + 2))) return rc;
-    HIP_TRY(hipMemset(c->d_prod, 0, (c->q.size() + 2) * sizeof(ProductDesc)));
-    const size_t n0 = c->items[0].size(), n1 = c->items[1].size(), n2 = c->items[2].size(), n3 = c->items[3].size(), n4 = c->items[4].size();
-    if ((rc = dev_alloc(&c->d_items, n0 + n1 + n2 + n3 + n4))) return rc;
-    HIP_TRY(hipMemcpy(c->d_q, c->q.data(), c->q.size(), hipMemcpyHostToDevice));
-    if (n0) HIP_TRY(hipMemcpy(c->d_items, c->items[0].data(), n0 * sizeof(WorkItem), hipMemcpyHostToDevice));
-    if (n1) HIP_TRY(hipMemcpy(c->d_items + n0, c->items[1].data(), n1 * sizeof(WorkItem), hipMemcpyHostToDevice));
-    if (n2) HIP_TRY(hipMemcpy(c->d_items + n0 + n1, c->items[2].data(), n2 * sizeof(WorkItem), hipMemcpyHostToDevice));
-    if (n3) HIP_TRY(hipMemcpy(c->d_items + n0 + n1 + n2, c->items[3].data(), n3 * sizeof(WorkItem), hipMemcpyHostToDevice));
-    if (n4) HIP_TRY(hipMemcpy(c->d_items + n0 + n1 + n2 + n3, c->items[4].data(), n4 * sizeof(WorkItem), hipMemcpyHostToDevice));
+    if ((rc = reserve(c, c->qd, tasks)) || (rc = reserve(c, c->itemsd, max_items))) return rc;
+    if (c->prod_cap < tasks + 2) {
+        (void)hipFree(c->d_prod);
+        c->d_prod = nullptr;
+        c->prod_cap = 0;
+        if ((rc = dev_alloc(c, &c->d_prod, tasks + 2))) return rc;
+        c->prod_cap = tasks + 2;
+        HIP_TRY(hipMemsetAsync(c->d_prod, 0, (tasks + 2) * sizeof(ProductDesc), s));
+    }
+    uint8_t *pq = begin_write(c, c->qd);
+    WorkItem *pi = begin_write(c, c->itemsd);
+    if (!pq || !pi) return GEMM_MP_EHIP;
+    std::memcpy(pq, c->q.data(), tasks);
+    size_t n = 0;
+    for (int list = 0; list < 5; ++list) {
+        if (!c->items[list].empty()) std::memcpy(pi + n, c->items[list].data(), c->items[list].size() * sizeof(WorkItem));
+        n += c->items[list].size();
+    }
+    if ((rc = upload(c->qd, tasks, s)) || (rc = upload(c->itemsd, n, s))) return rc;
+    c->sched_uploaded = true;
+    c->sched_stream = s;
     return GEMM_MP_OK;
 }
 
@@ -426,6 +541,8 @@ int gemm_mp_create(gemm_mp_ctx **out, int64_t M, int64_t N, int64_t K, int32_t n
     const int64_t mt = (M + nb - 1) / nb, nt = (N + nb - 1) / nb, kt = (K + nb - 1) / nb;
     if (mt > 32767 || nt > 32767 || kt > 32767) return GEMM_MP_EINVAL;
     if (mt * nt > (int64_t)1 << 24 || mt * nt * kt > (int64_t)1 << 28) return GEMM_MP_EINVAL;
+    // pack and unpack put 64-row blocks of a matrix into the second grid dimension (at most 65535)
+    if (mt * nb / kPackBlock > 65535 || nt * nb / kPackBlock > 65535 || kt * nb / kPackBlock > 65535) return GEMM_MP_EINVAL;
     gemm_mp_ctx *c = new (std::nothrow) gemm_mp_ctx();
     if (!c) return GEMM_MP_ENOMEM;
     c->M = M; c->N = N; c->K = K; c->nb = nb;
@@ -442,8 +559,10 @@ int gemm_mp_destroy(gemm_mp_ctx *c)
 {
     if (!c) return GEMM_MP_EINVAL;
     for (auto &m : c->mat) free_matrix_tables(m);
-    (void)hipFree(c->d_q); (void)hipFree(c->d_items); (void)hipFree(c->d_prod);
+    release(c->qd); release(c->itemsd);
+    (void)hipFree(c->d_prod);
     (void)hipFree(c->d_conv[0]); (void)hipFree(c->d_conv[1]); (void)hipFree(c->d_jobs);
+
     (void)hipGetLastError();
     delete c;
     return GEMM_MP_OK;
@@ -452,7 +571,7 @@ int gemm_mp_destroy(gemm_mp_ctx *c)
 int gemm_mp_set_policy(gemm_mp_ctx *c, int policy)
 {
     if (!c || (policy != GEMM_MP_POLICY_OPERAND && policy != GEMM_MP_POLICY_C_TILE)) return GEMM_MP_EINVAL;
-    if (policy != c->policy) { c->policy = policy; c->sched_current = false; }
+    if (policy != c->policy) { c->policy = policy; c->sched_current = false; c->sched_uploaded = false; }
     return GEMM_MP_OK;
 }
 
@@ -489,7 +608,7 @@ int gemm_mp_tile_scan(gemm_mp_ctx *c, char which, const double *dense, int64_t l
     if ((rc = check_dense(dense, ld, m.transposed ? m.rows : m.cols))) return rc;
     hipStream_t s = (hipStream_t)stream;
     if ((rc = run_scan(c, m, dense, ld, s))) return rc;
-    HIP_TRY(hipStreamSynchronize(s));
+    if ((rc = host_wait(c, s))) return rc;
     const size_t n = (size_t)m.ntiles() * sizeof(double);
     if (sumsq_host) HIP_TRY(hipMemcpy(sumsq_host, m.d_sumsq, n, hipMemcpyDeviceToHost));
     if (maxabs_host) HIP_TRY(hipMemcpy(maxabs_host, m.d_maxabs, n, hipMemcpyDeviceToHost));
@@ -507,7 +626,7 @@ int gemm_mp_compute_precision_map(gemm_mp_ctx *c, char which, const double *dens
     if ((rc = check_dense(dense, ld, m.transposed ? m.rows : m.cols))) return rc;
     hipStream_t s = (hipStream_t)stream;
     if ((rc = run_scan(c, m, dense, ld, s))) return rc;
-    HIP_TRY(hipStreamSynchronize(s));
+    if ((rc = host_wait(c, s))) return rc;
     const int n = m.ntiles();
     std::vector<double> sumsq(n);
     HIP_TRY(hipMemcpy(sumsq.data(), m.d_sumsq, (size_t)n * sizeof(double), hipMemcpyDeviceToHost));
@@ -533,8 +652,8 @@ int gemm_mp_compute_precision_map(gemm_mp_ctx *c, char which, const double *dens
         map[t] = (uint16_t)chosen;
     }
     if ((rc = install_map(c, w, map.data()))) return rc;
-    if ((rc = ensure_tables(m))) return rc;
-    HIP_TRY(launch_exps(m.d_maxabs, m.d_prec, m.d_exp, n, s));
+    if ((rc = ensure_tables(c, m, s))) return rc;
+    HIP_TRY(launch_exps(m.d_maxabs, m.prec.dev, m.d_exp, n, s));
     m.exps_valid = true;
     m.exps_from_rule = true;
     m.last_stream = s;
@@ -573,14 +692,14 @@ int gemm_mp_pack_tiles(gemm_mp_ctx *c, char which, const double *dense, int64_t 
     int rc;
     if ((rc = check_dense(dense, ld, m.transposed ? m.rows : m.cols))) return rc;
     hipStream_t s = (hipStream_t)stream;
-    if ((rc = ensure_tables(m))) return rc;
+    if ((rc = ensure_tables(c, m, s))) return rc;
     if (!m.exps_from_rule) {
         bool low = false;
         for (uint16_t p : m.map) low |= p == GEMM_MP_FP16 || p == GEMM_MP_FP8_E4M3;
         if (low) {
             if ((rc = run_scan(c, m, dense, ld, s))) return rc;
         } else if ((rc = ensure_scan_buffers(c, m))) return rc;
-        HIP_TRY(launch_exps(m.d_maxabs, m.d_prec, m.d_exp, m.ntiles(), s));
+        HIP_TRY(launch_exps(m.d_maxabs, m.prec.dev, m.d_exp, m.ntiles(), s));
         m.exps_valid = true;
     }
     if (m.transposed)
@@ -606,8 +725,8 @@ int gemm_mp_unpack_tiles(gemm_mp_ctx *c, char which, double *dense, int64_t ld, 
     if (!m.has_map || !m.storage) return GEMM_MP_ESTATE;
     int rc;
     if ((rc = check_dense(dense, ld, m.transposed ? m.rows : m.cols))) return rc;
-    if ((rc = ensure_tables(m))) return rc;
     hipStream_t s = (hipStream_t)stream;
+    if ((rc = ensure_tables(c, m, s))) return rc;
     if (m.transposed)
         HIP_TRY(launch_unpack(dense, ld, m.cols, m.rows, m.cols_t, m.rows_t, c->nb, w != 1, true, view_of(m), s));
     else
@@ -616,41 +735,41 @@ int gemm_mp_unpack_tiles(gemm_mp_ctx *c, char which, double *dense, int64_t ld, 
     return GEMM_MP_OK;
 }
 
-int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream)
+int gemm_mp_prepare(gemm_mp_ctx *c, gemm_mp_stream stream)
 {
-    if (!c || std::isnan(alpha) || std::isnan(beta)) return GEMM_MP_EINVAL;
-    Matrix &A = c->mat[0], &B = c->mat[1], &C = c->mat[2];
-    if (!all_maps(c) || !A.packed || !B.packed || !C.storage) return GEMM_MP_ESTATE;
-    if (beta != 0.0 && !C.packed) return GEMM_MP_ESTATE;
-    if (!c->sched_current) {
-        if (c->d_q) (void)hipStreamSynchronize(C.last_stream);
-        build_schedule(c);
-        (void)hipFree(c->d_q); (void)hipFree(c->d_items); (void)hipFree(c->d_prod);     // of the old schedule
-        c->d_q = nullptr; c->d_items = nullptr; c->d_prod = nullptr;
-    }
-    if ((c->bf16_needs_copies || c->mx_needs_copies) && !c->conv_active) return GEMM_MP_ESTATE;
-    int rc;
+    if (!c) return GEMM_MP_EINVAL;
+    if (!all_maps(c)) return GEMM_MP_ESTATE;
     hipStream_t s = (hipStream_t)stream;
-    if ((rc = ensure_tables(C))) return rc;
-    if (!c->d_q && (rc = upload_schedule(c))) return rc;
+    int rc;
+    if ((rc = prepare_schedule(c, s))) return rc;
+    if ((rc = ensure_tables(c, c->mat[2], s))) return rc;
     if (!c->kernel_ready) {
         HIP_TRY(gemm_kernel_setup());
         c->kernel_ready = true;
     }
+    return GEMM_MP_OK;
+}
+
+namespace {
+
+// What both forms of the run share.  prod: where the product table of this run is written.
+int run_on(gemm_mp_ctx *c, double alpha, double beta, hipStream_t s, ProductDesc *prod)
+{
+    Matrix &A = c->mat[0], &B = c->mat[1], &C = c->mat[2];
     GemmArgs a;
     a.A = view_of(A); a.B = view_of(B); a.C = view_of(C);
     const int n_low = (int)C.low.size();
     if (n_low) {
         // FP16 / FP8 C tiles: the kernels work on the FP32 staging copies
-        if (beta != 0.0) HIP_TRY(launch_low_expand(C.d_low, n_low, c->nb, a.C, s));
-        a.C.offset = C.d_offset_run;
+        if (beta != 0.0) HIP_TRY(launch_low_expand(C.lowt.dev, n_low, c->nb, a.C, s));
+        a.C.offset = C.off_run.dev;
     }
-    a.q = c->d_q;
-    a.prod = c->d_prod;
+    a.q = c->qd.dev;
+    a.prod = prod;
     a.convA = c->conv_active ? c->d_conv[0] : nullptr;
     a.convB = c->conv_active ? c->d_conv[1] : nullptr;
-    a.items64 = c->d_items;
-    a.items32 = c->d_items + c->items[0].size();
+    a.items64 = c->itemsd.dev;
+    a.items32 = a.items64 + c->items[0].size();
     a.items8 = a.items32 + c->items[1].size();
     a.n_items64 = (int32_t)c->items[0].size();
     a.n_items32 = (int32_t)c->items[1].size();
@@ -666,10 +785,46 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
     a.kt_eff = alpha == 0.0 ? 0 : c->KT;
     a.alpha = alpha; a.beta = beta;
     HIP_TRY(launch_gemm(a, s));
-    if (n_low) HIP_TRY(launch_low_store(C.d_low, n_low, c->nb, view_of(C), C.d_exp, C.d_low_max, s));
+    if (n_low) HIP_TRY(launch_low_store(C.lowt.dev, n_low, c->nb, view_of(C), C.d_exp, C.d_low_max, s));
     C.packed = true;
     C.exps_valid = true;
     A.last_stream = B.last_stream = C.last_stream = s;
+    return GEMM_MP_OK;
+}
+
+int run_ready(gemm_mp_ctx *c, double alpha, double beta)
+{
+    if (!c || std::isnan(alpha) || std::isnan(beta)) return GEMM_MP_EINVAL;
+    Matrix &A = c->mat[0], &B = c->mat[1], &C = c->mat[2];
+    if (!all_maps(c) || !A.packed || !B.packed || !C.storage) return GEMM_MP_ESTATE;
+    if (beta != 0.0 && !C.packed) return GEMM_MP_ESTATE;
+    return GEMM_MP_OK;
+}
+
+}  // namespace
+
+int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream)
+{
+    int rc;
+    if ((rc = run_ready(c, alpha, beta))) return rc;
+    if (!c->sched_current) build_schedule(c);
+    if ((c->bf16_needs_copies || c->mx_needs_copies) && !c->conv_active) return GEMM_MP_ESTATE;
+    hipStream_t s = (hipStream_t)stream;
+    // what gemm_mp_prepare does, unless it has been done for these maps: only copies queued on s
+    if ((rc = prepare_schedule(c, s))) return rc;
+    if ((rc = ensure_tables(c, c->mat[2], s))) return rc;
+    if (!c->kernel_ready) {
+        HIP_TRY(gemm_kernel_setup());
+        c->kernel_ready = true;
+    }
+    return run_on(c, alpha, beta, s, c->d_prod);
+}
+
+int gemm_mp_host_counters(gemm_mp_ctx *c, int64_t *allocations, int64_t *host_waits)
+{
+    if (!c) return GEMM_MP_EINVAL;
+    if (allocations) *allocations = c->n_allocs;
+    if (host_waits) *host_waits = c->n_syncs;
     return GEMM_MP_OK;
 }
 
@@ -677,12 +832,7 @@ int gemm_mp_conversion_bytes(gemm_mp_ctx *c, size_t *bytes)
 {
     if (!c || !bytes) return GEMM_MP_EINVAL;
     if (!all_maps(c)) return GEMM_MP_ESTATE;
-    if (!c->sched_current) {
-        if (c->d_q) (void)hipStreamSynchronize(c->mat[2].last_stream);
-        build_schedule(c);
-        (void)hipFree(c->d_q); (void)hipFree(c->d_items); (void)hipFree(c->d_prod);
-        c->d_q = nullptr; c->d_items = nullptr; c->d_prod = nullptr;
-    }
+    if (!c->sched_current) build_schedule(c);
     *bytes = (size_t)c->conv_bytes;
     return GEMM_MP_OK;
 }
@@ -697,7 +847,7 @@ int gemm_mp_convert_tiles(gemm_mp_ctx *c, void *workspace, size_t bytes, gemm_mp
     if ((rc = gemm_mp_conversion_bytes(c, &need))) return rc;
     if (need > 0 && (!workspace || ((uintptr_t)workspace & 255) || bytes < need)) return GEMM_MP_EINVAL;
     hipStream_t s = (hipStream_t)stream;
-    if ((rc = ensure_tables(A)) || (rc = ensure_tables(B))) return rc;
+    if ((rc = ensure_tables(c, A, s)) || (rc = ensure_tables(c, B, s))) return rc;
     // jobs and address tables
     std::vector<ConvertJob> jobs;
     std::vector<uint64_t> addr[2];
@@ -725,15 +875,15 @@ int gemm_mp_convert_tiles(gemm_mp_ctx *c, void *workspace, size_t bytes, gemm_mp
         }
     }
     // the tables may be in use by an earlier run on another stream
-    if (c->d_conv[0]) (void)hipStreamSynchronize(c->mat[2].last_stream);
+    if (c->d_conv[0]) { (void)hipStreamSynchronize(c->mat[2].last_stream); c->n_syncs += 1; }
     (void)hipFree(c->d_conv[0]); (void)hipFree(c->d_conv[1]); (void)hipFree(c->d_jobs);
     c->d_conv[0] = c->d_conv[1] = nullptr; c->d_jobs = nullptr;
     for (int w = 0; w < 2; ++w) {
-        if ((rc = dev_alloc(&c->d_conv[w], addr[w].size()))) return rc;
+        if ((rc = dev_alloc(c, &c->d_conv[w], addr[w].size()))) return rc;
         HIP_TRY(hipMemcpy(c->d_conv[w], addr[w].data(), addr[w].size() * sizeof(uint64_t), hipMemcpyHostToDevice));
     }
     if (!jobs.empty()) {
-        if ((rc = dev_alloc(&c->d_jobs, jobs.size()))) return rc;
+        if ((rc = dev_alloc(c, &c->d_jobs, jobs.size()))) return rc;
         HIP_TRY(hipMemcpy(c->d_jobs, jobs.data(), jobs.size() * sizeof(ConvertJob), hipMemcpyHostToDevice));
         HIP_TRY(launch_convert(c->d_jobs, (int)jobs.size(), max_n16, A.d_exp, B.d_exp, s));
     }
@@ -761,7 +911,7 @@ int gemm_mp_tile_info(gemm_mp_ctx *c, char which, int32_t I, int32_t J, size_t *
     if (scale_exp) {
         if (m.map[t] == GEMM_MP_FP16 || m.map[t] == GEMM_MP_FP8_E4M3) {
             if (!m.exps_valid) return GEMM_MP_ESTATE;
-            HIP_TRY(hipStreamSynchronize(m.last_stream));
+            if (int rc = host_wait(c, m.last_stream)) return rc;
             HIP_TRY(hipMemcpy(&e, m.d_exp + t, sizeof(int), hipMemcpyDeviceToHost));
         }
     }
@@ -775,12 +925,7 @@ int gemm_mp_get_stats(gemm_mp_ctx *c, gemm_mp_stats *out)
 {
     if (!c || !out) return GEMM_MP_EINVAL;
     if (!all_maps(c)) return GEMM_MP_ESTATE;
-    if (!c->sched_current) {
-        if (c->d_q) (void)hipStreamSynchronize(c->mat[2].last_stream);
-        build_schedule(c);
-        (void)hipFree(c->d_q); (void)hipFree(c->d_items); (void)hipFree(c->d_prod);
-        c->d_q = nullptr; c->d_items = nullptr; c->d_prod = nullptr;
-    }
+    if (!c->sched_current) build_schedule(c);
     *out = c->stats;
     out->converted_tiles = c->conv_active ? c->conv_tiles : 0;
     out->converted_bytes = c->conv_active ? c->conv_bytes : 0;

@@ -50,10 +50,11 @@ __global__ void product_table_kernel(PackedView A, PackedView B, const uint8_t *
 // the very conversion the owner workgroups apply on the fly (convert<Q>), so a converted copy
 // holds bit for bit what the receiver-side path would have put into LDS.
 __global__ __launch_bounds__(256) void convert_tiles_kernel(const ConvertJob *__restrict__ jobs, const int32_t *__restrict__ expA,
-                                                            const int32_t *__restrict__ expB)
+                                                            const int32_t *__restrict__ expB, uint32_t per_job)
 {
-    const ConvertJob job = jobs[blockIdx.y];
-    const uint32_t seg = blockIdx.x * 256u + threadIdx.x;
+    // a one-dimensional grid: per_job workgroups for every job
+    const ConvertJob job = jobs[blockIdx.x / per_job];
+    const uint32_t seg = (blockIdx.x % per_job) * 256u + threadIdx.x;
     if (seg >= job.n16) return;
     const int p = job.p, q = job.q;
     if (p == GEMM_MP_MXFP4) {
@@ -143,7 +144,9 @@ hipError_t launch_convert(const ConvertJob *jobs_dev, int njobs, uint32_t max_n1
                           hipStream_t s)
 {
     if (njobs <= 0) return hipSuccess;
-    convert_tiles_kernel<<<dim3((max_n16 + 255u) / 256u, (unsigned)njobs), dim3(256), 0, s>>>(jobs_dev, expA, expB);
+    const uint32_t per_job = (max_n16 + 255u) / 256u;
+    if ((int64_t)per_job * njobs > 0x7fffffff) return hipErrorInvalidValue;
+    convert_tiles_kernel<<<dim3((unsigned)((int64_t)per_job * njobs)), dim3(256), 0, s>>>(jobs_dev, expA, expB, per_job);
     return hipGetLastError();
 }
 

@@ -347,13 +347,14 @@ __device__ inline int mx_block_exponent(double m, bool fp4)
 __global__ __launch_bounds__(256) void pack_mx_kernel(const double *__restrict__ X, int64_t sr, int64_t sc, int64_t rows, int64_t cols,
                                                       int cols_t, int nb, bool is_b, PackedView v)
 {
-    const int tile = blockIdx.y;
+    const unsigned per_tile = (unsigned)(nb * nb / 32 / 256);    // workgroups per tile; the grid is one-dimensional
+    const int tile = (int)(blockIdx.x / per_tile);
     const int p = v.prec[tile];
     if (!is_block_scaled(p)) return;
     const bool fp4 = p == GEMM_MP_MXFP4;
     const int I = tile / cols_t, J = tile % cols_t;
     const int per_row = nb / 32;
-    const int idx = blockIdx.x * 256 + threadIdx.x;              // (block, packed row): nb * nb / 32 of them, a multiple of 256
+    const int idx = (int)(blockIdx.x % per_tile) * 256 + threadIdx.x;   // (block, packed row): nb * nb / 32 of them, a multiple of 256
     const int u = is_b ? idx % nb : idx / per_row, kb = is_b ? idx / nb : idx % per_row;
     double x[32];
     double m = 0.0;
@@ -390,13 +391,14 @@ __global__ __launch_bounds__(256) void pack_mx_kernel(const double *__restrict__
 __global__ __launch_bounds__(256) void pack_mx_rows_kernel(const double *__restrict__ X, int64_t sr, int64_t sc, int64_t rows, int64_t cols,
                                                            int cols_t, int nb, PackedView v)
 {
-    const int tile = blockIdx.y;
+    const unsigned per_tile = (unsigned)(nb * nb / 4 / 256);     // workgroups per tile; the grid is one-dimensional
+    const int tile = (int)(blockIdx.x / per_tile);
     const int p = v.prec[tile];
     if (!is_block_scaled(p)) return;
     const bool fp4 = p == GEMM_MP_MXFP4;
     const int I = tile / cols_t, J = tile % cols_t;
     const int per_row = nb / 32;
-    const int gidx = blockIdx.x * 256 + threadIdx.x;             // (block, quarter of eight): nb * nb / 4 of them
+    const int gidx = (int)(blockIdx.x % per_tile) * 256 + threadIdx.x;   // (block, quarter of eight): nb * nb / 4 of them
     const int blk = gidx >> 3, sub = gidx & 7;
     const int u = blk / per_row, kb = blk % per_row;
     const int64_t r = (int64_t)I * nb + u, c0 = (int64_t)J * nb + 32 * kb + 4 * sub;
@@ -432,10 +434,14 @@ hipError_t launch_pack_mx(const double *X, int64_t sr, int64_t sc, int64_t rows,
     // the mapping that reads contiguously: by the direction in which the buffer is contiguous along the blocks
     const bool along_contiguous = is_b ? sr == 1 : sc == 1;
     if (along_contiguous && !is_b) {
-        dim3 grid((unsigned)((int64_t)nb * nb / 4 / 256), (unsigned)(rows_t * cols_t));
+        const int64_t blocks = (int64_t)nb * nb / 4 / 256 * rows_t * cols_t;
+        if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+        dim3 grid((unsigned)blocks);
         pack_mx_rows_kernel<<<grid, 256, 0, s>>>(X, sr, sc, rows, cols, cols_t, nb, v);
     } else {
-        dim3 grid((unsigned)((int64_t)nb * nb / 32 / 256), (unsigned)(rows_t * cols_t));
+        const int64_t blocks = (int64_t)nb * nb / 32 / 256 * rows_t * cols_t;
+        if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+        dim3 grid((unsigned)blocks);
         pack_mx_kernel<<<grid, 256, 0, s>>>(X, sr, sc, rows, cols, cols_t, nb, is_b, v);
     }
     return hipGetLastError();
@@ -533,12 +539,13 @@ hipError_t launch_unpack(double *X, int64_t ld, int64_t rows, int64_t cols, int 
 //   round:   stored number = staging * 2^-e rounded once to nearest even (FP8 saturates).
 __global__ __launch_bounds__(256) void low_expand_kernel(const LowTile *__restrict__ low, PackedView v, int nb)
 {
-    const LowTile lt = low[blockIdx.y];
+    const unsigned parts = (unsigned)(nb * nb / kLowChunk);     // workgroups per tile; the grid is one-dimensional
+    const LowTile lt = low[blockIdx.x / parts];
     const int p = v.prec[lt.tile];
     int e = v.exp[lt.tile];
     const char *src = v.storage + v.offset[lt.tile];
     float *dst = (float *)(v.storage + lt.stage);
-    const int64_t i0 = (int64_t)blockIdx.x * kLowChunk + threadIdx.x * 4;
+    const int64_t i0 = (int64_t)(blockIdx.x % parts) * kLowChunk + threadIdx.x * 4;
 #pragma unroll
     for (int it = 0; it < kLowChunk / 1024; ++it) {
         const int64_t i = i0 + it * 1024;
@@ -578,9 +585,9 @@ __global__ __launch_bounds__(256) void low_chunk_max_kernel(const LowTile *__res
                                                             int parts, float *__restrict__ part_max)
 {
     __shared__ float wm[4];
-    const LowTile lt = low[blockIdx.y];
+    const LowTile lt = low[blockIdx.x / (unsigned)parts];
     const float *src = (const float *)(storage + lt.stage);
-    const int64_t i0 = (int64_t)blockIdx.x * kLowChunk + threadIdx.x * 4;
+    const int64_t i0 = (int64_t)(blockIdx.x % (unsigned)parts) * kLowChunk + threadIdx.x * 4;
     float m = 0.0f;
 #pragma unroll
     for (int it = 0; it < kLowChunk / 1024; ++it) {
@@ -600,7 +607,7 @@ __global__ __launch_bounds__(256) void low_chunk_max_kernel(const LowTile *__res
     if (threadIdx.x == 0) {
         for (int k = 1; k < 4; ++k)
             if (wm[k] > m) m = wm[k];
-        part_max[(int64_t)blockIdx.y * parts + blockIdx.x] = m;
+        part_max[blockIdx.x] = m;                      // = tile * parts + chunk
     }
 }
 
@@ -640,13 +647,14 @@ __global__ __launch_bounds__(256) void low_exponent_kernel(const LowTile *__rest
 
 __global__ __launch_bounds__(256) void low_round_kernel(const LowTile *__restrict__ low, PackedView v, int nb)
 {
-    const LowTile lt = low[blockIdx.y];
+    const unsigned parts = (unsigned)(nb * nb / kLowChunk);     // workgroups per tile; the grid is one-dimensional
+    const LowTile lt = low[blockIdx.x / parts];
     const int p = v.prec[lt.tile];
     const int e = v.exp[lt.tile];
     char *dst = v.storage + v.offset[lt.tile];
     const float *src = (const float *)(v.storage + lt.stage);
     const int es = elem_bytes(p);
-    const int64_t i0 = (int64_t)blockIdx.x * kLowChunk + threadIdx.x * 4;
+    const int64_t i0 = (int64_t)(blockIdx.x % parts) * kLowChunk + threadIdx.x * 4;
 #pragma unroll
     for (int it = 0; it < kLowChunk / 1024; ++it) {
         const int64_t i = i0 + it * 1024;
@@ -688,7 +696,9 @@ __global__ __launch_bounds__(256) void low_round_kernel(const LowTile *__restric
 hipError_t launch_low_expand(const LowTile *low_dev, int n_low, int nb, PackedView c, hipStream_t s)
 {
     if (n_low == 0) return hipSuccess;
-    dim3 grid((unsigned)((int64_t)nb * nb / kLowChunk), (unsigned)n_low);
+    const int64_t blocks = (int64_t)nb * nb / kLowChunk * n_low;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    dim3 grid((unsigned)blocks);
     low_expand_kernel<<<grid, 256, 0, s>>>(low_dev, c, nb);
     return hipGetLastError();
 }
@@ -698,7 +708,8 @@ hipError_t launch_low_store(const LowTile *low_dev, int n_low, int nb, PackedVie
 {
     if (n_low == 0) return hipSuccess;
     const int parts = (int)((int64_t)nb * nb / kLowChunk);
-    dim3 grid((unsigned)parts, (unsigned)n_low);
+    if ((int64_t)parts * n_low > 0x7fffffff) return hipErrorInvalidValue;
+    dim3 grid((unsigned)((int64_t)parts * n_low));
     low_chunk_max_kernel<<<grid, 256, 0, s>>>(low_dev, c.storage, parts, part_max);
     low_exponent_kernel<<<n_low, 256, 0, s>>>(low_dev, c.prec, parts, part_max, exps);
     low_round_kernel<<<grid, 256, 0, s>>>(low_dev, c, nb);

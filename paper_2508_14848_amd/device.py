@@ -58,6 +58,9 @@ class DeviceGemmMP:
         assert dense.dtype == torch.float64 and dense.is_cuda and dense.stride(1) == 1
         self.ctx.pack_tiles(which, dense.data_ptr(), dense.stride(0), _stream())
 
+    def prepare(self):
+        self.ctx.prepare(_stream())
+
     def run(self, alpha, beta):
         self.ctx.run(float(alpha), float(beta), _stream())
 

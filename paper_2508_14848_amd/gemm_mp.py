@@ -24,6 +24,7 @@ EXPORTS = [
     "gemm_mp_bind_storage", "gemm_mp_pack_tiles", "gemm_mp_run", "gemm_mp_unpack_tiles",
     "gemm_mp_tile_info", "gemm_mp_get_stats", "gemm_mp_product_precision", "gemm_mp_strerror",
     "gemm_mp_conversion_bytes", "gemm_mp_convert_tiles", "gemm_mp_clear_conversion",
+    "gemm_mp_prepare", "gemm_mp_host_counters",
 ]
 
 
@@ -34,7 +35,8 @@ class Stats(ctypes.Structure):
                 ("converted_bytes", ctypes.c_uint64), ("products_bf16", ctypes.c_int64),
                 ("flops_bf16", ctypes.c_double), ("tiles_bf16", ctypes.c_int64 * 3),
                 ("products_mxfp8", ctypes.c_int64), ("flops_mxfp8", ctypes.c_double), ("tiles_mxfp8", ctypes.c_int64 * 3),
-                ("products_mxfp4", ctypes.c_int64), ("flops_mxfp4", ctypes.c_double), ("tiles_mxfp4", ctypes.c_int64 * 3)]
+                ("products_mxfp4", ctypes.c_int64), ("flops_mxfp4", ctypes.c_double), ("tiles_mxfp4", ctypes.c_int64 * 3),
+                ("launch_items", ctypes.c_int64 * 8), ("owner_instance", ctypes.c_int32 * 2)]
 
 
 class GemmMPError(RuntimeError):
@@ -66,6 +68,8 @@ def lib():
         L.gemm_mp_bind_storage.argtypes = [P, c, P, ctypes.c_size_t]
         L.gemm_mp_pack_tiles.argtypes = [P, c, P, i64, P]
         L.gemm_mp_run.argtypes = [P, dbl, dbl, P]
+        L.gemm_mp_prepare.argtypes = [P, P]
+        L.gemm_mp_host_counters.argtypes = [P, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.gemm_mp_unpack_tiles.argtypes = [P, c, P, i64, P]
         L.gemm_mp_conversion_bytes.argtypes = [P, ctypes.POINTER(ctypes.c_size_t)]
         L.gemm_mp_convert_tiles.argtypes = [P, P, ctypes.c_size_t, P]
@@ -165,8 +169,17 @@ class GemmMP:
     def pack_tiles(self, which, dense_ptr, ld, stream=None):
         _check(lib().gemm_mp_pack_tiles(self._h, _w(which), dense_ptr, ld, stream), "gemm_mp_pack_tiles")
 
+    def prepare(self, stream=None):
+        _check(lib().gemm_mp_prepare(self._h, stream), "gemm_mp_prepare")
+
     def run(self, alpha, beta, stream=None):
         _check(lib().gemm_mp_run(self._h, alpha, beta, stream), "gemm_mp_run")
+
+    def host_counters(self):
+        """(allocations, host waits) this context has made so far."""
+        a, w = ctypes.c_int64(), ctypes.c_int64()
+        _check(lib().gemm_mp_host_counters(self._h, ctypes.byref(a), ctypes.byref(w)), "gemm_mp_host_counters")
+        return a.value, w.value
 
     def conversion_bytes(self):
         n = ctypes.c_size_t()
@@ -197,4 +210,5 @@ class GemmMP:
                 "converted_bytes": s.converted_bytes, "products_bf16": s.products_bf16,
                 "flops_bf16": s.flops_bf16, "tiles_bf16": list(s.tiles_bf16), "products_mxfp8": s.products_mxfp8,
                 "flops_mxfp8": s.flops_mxfp8, "tiles_mxfp8": list(s.tiles_mxfp8), "products_mxfp4": s.products_mxfp4,
-                "flops_mxfp4": s.flops_mxfp4, "tiles_mxfp4": list(s.tiles_mxfp4)}
+                "flops_mxfp4": s.flops_mxfp4, "tiles_mxfp4": list(s.tiles_mxfp4),
+                "launch_items": list(s.launch_items), "owner_instance": list(s.owner_instance)}

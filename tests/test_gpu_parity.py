@@ -1237,3 +1237,42 @@ def test_config_cov64k_sampled_blocks():
     st = d.ctx.get_stats()
     _say("  products by precision:", st["products"])
     assert (w.M // 256) * (w.N // 256) <= st["work_items"] <= (w.M // 128) * (w.N // 128)
+
+
+def test_steady_state_calls_neither_allocate_nor_wait():
+    """After the first pass over a shape, a loop of set map / pack / prepare / run makes no device
+    or pinned allocation, and prepare and run make the host wait for nothing: the tables are
+    composed in pinned memory and copied on the caller's stream."""
+    import torch
+    w = W.random_maps(M=1024, N=1024, K=1024, nb=256, name="random1k")
+    A, B, C0 = _dense(w)
+    side = OracleSide(w, A, B, C0)
+    d, dev = gpu_problem(w, A, B, C0)
+    d.run(w.alpha, w.beta)
+    first = d.unpack_tiles("C").cpu().numpy()
+    torch.cuda.synchronize()
+    allocs0, waits0 = d.ctx.host_counters()
+    assert allocs0 > 0
+    rng = np.random.default_rng(3)
+    for it in range(3):
+        # new maps of the same shapes (a permutation of the rows of the old ones), new packed data
+        mA, mB = w.mapA[rng.permutation(w.MT)], w.mapB[rng.permutation(w.KT)]
+        d.ctx.set_precision_map("A", mA if it < 2 else w.mapA)
+        d.ctx.bind_storage("A", d.storage["A"].data_ptr(), d.storage["A"].numel())
+        d.ctx.set_precision_map("B", mB if it < 2 else w.mapB)
+        d.ctx.bind_storage("B", d.storage["B"].data_ptr(), d.storage["B"].numel())
+        d.ctx.set_precision_map("C", w.mapC)
+        d.ctx.bind_storage("C", d.storage["C"].data_ptr(), d.storage["C"].numel())
+        d.pack_tiles("A", dev["A"])
+        d.pack_tiles("B", dev["B"])
+        d.pack_tiles("C", dev["C"])
+        a1, w1 = d.ctx.host_counters()
+        if it == 1:
+            d.prepare()
+        d.run(w.alpha, w.beta)
+        a2, w2 = d.ctx.host_counters()
+        assert (a2, w2) == (a1, w1), "prepare / run allocated or waited: %s -> %s" % ((a1, w1), (a2, w2))
+    assert d.ctx.host_counters()[0] == allocs0            # the whole loop allocated nothing
+    last = d.unpack_tiles("C").cpu().numpy()
+    torch.cuda.synchronize()
+    assert np.array_equal(first, last)                    # the original maps again: the same C bit for bit
