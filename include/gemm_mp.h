@@ -94,7 +94,8 @@ enum {
     GEMM_MP_ESTATE = -2,       /* call order: a map, a buffer or packed data is missing */
     GEMM_MP_ENOMEM = -3,       /* a table could not be allocated */
     GEMM_MP_EUNSUPPORTED = -4, /* valid request this build does not implement */
-    GEMM_MP_EHIP = -5          /* the HIP runtime reported an error */
+    GEMM_MP_EHIP = -5,         /* the HIP runtime reported an error */
+    GEMM_MP_ETOOBIG = -6       /* gemm_mp_run_static: more tile products than its static scratch holds */
 };
 
 /* How the precision q of the product A(I,L)*B(L,J) that updates C(I,J) is chosen.
@@ -235,6 +236,25 @@ int gemm_mp_prepare(gemm_mp_ctx *ctx, gemm_mp_stream stream);
  * accumulation, which is what it is), and the call is ESTATE until gemm_mp_convert_tiles has
  * filled it. */
 int gemm_mp_run(gemm_mp_ctx *ctx, double alpha, double beta, gemm_mp_stream stream);
+
+/* Run without allocating [async].  For callers that cannot allocate device memory at the point
+ * of the call: code under HIP graph capture, tight serving loops, harnesses that forbid it.  The
+ * same computation as gemm_mp_run with the same kernels and bit for bit the same C; the one piece
+ * of scratch memory the run needs (the product table: one 32-byte record per tile product A(I,L)*
+ * B(L,J), filled by a small kernel at the start of the call) lives in a static device array of
+ * (GEMM_MP_STATIC_MAX_PRODUCTS + 2) * 32 bytes (2 MiB) that every GPU the library runs on holds
+ * until the process ends.  The call itself allocates nothing, frees nothing, copies nothing from
+ * the host and waits for nothing: it launches kernels on `stream`.
+ *   - ETOOBIG if the problem has more than GEMM_MP_STATIC_MAX_PRODUCTS tile products
+ *     (MT * NT * KT), whatever else its state.
+ *   - ESTATE unless gemm_mp_prepare has been called (on a stream ordered before `stream`) since the
+ *     last change of a map or of the policy, besides what gemm_mp_run asks for.
+ *   - Every call on one GPU uses that GPU's one array, from whatever context or thread: calls
+ *     whose execution may overlap on a GPU (different streams) race on it; put them on one stream
+ *     or order them.  gemm_mp_run has its own table and may overlap with it.  Nothing in the array
+ *     has to start at zero: each call writes every record it reads. */
+#define GEMM_MP_STATIC_MAX_PRODUCTS 65536
+int gemm_mp_run_static(gemm_mp_ctx *ctx, double alpha, double beta, gemm_mp_stream stream);
 
 /* Sender-side conversion (optional).  The paper converts at the receiver: a tile travels in its
  * stored precision and every task that needs another precision converts it again (Section 4,

@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <numeric>
 #include <vector>
@@ -530,6 +531,35 @@ int run_scan(gemm_mp_ctx *c, Matrix &m, const double *dense, int64_t ld, hipStre
     return GEMM_MP_OK;
 }
 
+// ---- scratch of gemm_mp_run_static -----------------------------------------------------------
+// The product table of a run (one 32-byte record per tile product, written by a small kernel
+// before the GEMM kernels read it) is the one piece of scratch memory gemm_mp_run takes from an
+// allocation of its own.  The entry point that must not allocate keeps it here instead: a
+// file-scope device array, one copy per GPU, held until the process ends.  In host code the
+// array's name is only a handle: the address a kernel can use comes from hipGetSymbolAddress,
+// asked once per device with that device current, and only that address is passed on.
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[((size_t)GEMM_MP_STATIC_MAX_PRODUCTS + 2) * sizeof(ProductDesc)];
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_lock;
+
+// out == nullptr: only make sure the current device's address is known.
+int static_scratch(ProductDesc **out)
+{
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return GEMM_MP_EHIP;
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return GEMM_MP_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    if (out) *out = (ProductDesc *)g_scratch_ptr[dev];
+    return GEMM_MP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -747,7 +777,7 @@ int gemm_mp_prepare(gemm_mp_ctx *c, gemm_mp_stream stream)
         HIP_TRY(gemm_kernel_setup());
         c->kernel_ready = true;
     }
-    return GEMM_MP_OK;
+    return static_scratch(nullptr);       // the current device's address of the static scratch, looked up once
 }
 
 namespace {
@@ -818,6 +848,20 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
         c->kernel_ready = true;
     }
     return run_on(c, alpha, beta, s, c->d_prod);
+}
+
+int gemm_mp_run_static(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream)
+{
+    if (!c) return GEMM_MP_EINVAL;
+    if ((int64_t)c->MT * c->NT * c->KT > (int64_t)GEMM_MP_STATIC_MAX_PRODUCTS) return GEMM_MP_ETOOBIG;
+    int rc;
+    if ((rc = run_ready(c, alpha, beta))) return rc;
+    // everything that would allocate, build or copy must have happened in gemm_mp_prepare
+    if (!c->sched_current || !c->sched_uploaded || !c->mat[2].tables_current || !c->kernel_ready) return GEMM_MP_ESTATE;
+    if ((c->bf16_needs_copies || c->mx_needs_copies) && !c->conv_active) return GEMM_MP_ESTATE;
+    ProductDesc *prod = nullptr;
+    if ((rc = static_scratch(&prod))) return rc;
+    return run_on(c, alpha, beta, (hipStream_t)stream, prod);
 }
 
 int gemm_mp_host_counters(gemm_mp_ctx *c, int64_t *allocations, int64_t *host_waits)
@@ -948,6 +992,7 @@ const char *gemm_mp_strerror(int status)
     case GEMM_MP_ENOMEM: return "out of memory for a table";
     case GEMM_MP_EUNSUPPORTED: return "not supported by this build";
     case GEMM_MP_EHIP: return "HIP runtime error";
+    case GEMM_MP_ETOOBIG: return "more tile products than the static scratch of gemm_mp_run_static holds";
     default: return "unknown status";
     }
 }

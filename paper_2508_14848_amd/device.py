@@ -64,6 +64,9 @@ class DeviceGemmMP:
     def run(self, alpha, beta):
         self.ctx.run(float(alpha), float(beta), _stream())
 
+    def run_static(self, alpha, beta):
+        self.ctx.run_static(float(alpha), float(beta), _stream())
+
     def convert_tiles(self):
         """Sender-side conversion: allocate the workspace and fill it; returns its size in bytes."""
         n = self.ctx.conversion_bytes()

@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libgemm_mp.so")
 
 FP64, FP32, FP16, FP8_E4M3, BF16, MXFP8, MXFP4 = 0, 1, 2, 3, 4, 5, 6
 POLICY_OPERAND, POLICY_C_TILE = 0, 1
-OK, EINVAL, ESTATE, ENOMEM, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ESTATE, ENOMEM, EUNSUPPORTED, EHIP, ETOOBIG = 0, -1, -2, -3, -4, -5, -6
+STATIC_MAX_PRODUCTS = 65536
 
 EXPORTS = [
     "gemm_mp_create", "gemm_mp_destroy", "gemm_mp_set_policy", "gemm_mp_set_transposed", "gemm_mp_set_precision_map",
@@ -24,7 +25,7 @@ EXPORTS = [
     "gemm_mp_bind_storage", "gemm_mp_pack_tiles", "gemm_mp_run", "gemm_mp_unpack_tiles",
     "gemm_mp_tile_info", "gemm_mp_get_stats", "gemm_mp_product_precision", "gemm_mp_strerror",
     "gemm_mp_conversion_bytes", "gemm_mp_convert_tiles", "gemm_mp_clear_conversion",
-    "gemm_mp_prepare", "gemm_mp_host_counters",
+    "gemm_mp_prepare", "gemm_mp_host_counters", "gemm_mp_run_static",
 ]
 
 
@@ -69,6 +70,7 @@ def lib():
         L.gemm_mp_pack_tiles.argtypes = [P, c, P, i64, P]
         L.gemm_mp_run.argtypes = [P, dbl, dbl, P]
         L.gemm_mp_prepare.argtypes = [P, P]
+        L.gemm_mp_run_static.argtypes = [P, dbl, dbl, P]
         L.gemm_mp_host_counters.argtypes = [P, ctypes.POINTER(i64), ctypes.POINTER(i64)]
         L.gemm_mp_unpack_tiles.argtypes = [P, c, P, i64, P]
         L.gemm_mp_conversion_bytes.argtypes = [P, ctypes.POINTER(ctypes.c_size_t)]
@@ -174,6 +176,9 @@ class GemmMP:
 
     def run(self, alpha, beta, stream=None):
         _check(lib().gemm_mp_run(self._h, alpha, beta, stream), "gemm_mp_run")
+
+    def run_static(self, alpha, beta, stream=None):
+        _check(lib().gemm_mp_run_static(self._h, alpha, beta, stream), "gemm_mp_run_static")
 
     def host_counters(self):
         """(allocations, host waits) this context has made so far."""
