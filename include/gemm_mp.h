@@ -224,6 +224,11 @@ int gemm_mp_prepare(gemm_mp_ctx *ctx, gemm_mp_stream stream);
  * products use FP32-accumulating matrix instructions on the scaled operands; 2^(eA+eB) is
  * applied to the finished tile product.  alpha, beta are rounded to the accumulate type.
  * beta == 0: C is not read.  alpha == 0: no product is formed.
+ * The run is one small table kernel and up to five GEMM launches (by kind of C tile); the
+ * launches touch disjoint C tiles and run side by side on streams of the library's own, forked
+ * off `stream` and joined to it again inside the call, so the caller sees one stream.  With the
+ * environment variable GEMM_MP_SERIAL_LAUNCHES=1 at gemm_mp_create they stay on `stream`, one
+ * after the other; C is the same either way.
  * ESTATE unless A and B are packed, C's map and buffer are set, and (beta != 0) C is packed.
  * BF16 tiles: the kernels take BF16 data only as an operand of a BF16 product (whose other
  * operand is BF16, or FP8 converted on the way like under an FP16 product); a BF16 tile under

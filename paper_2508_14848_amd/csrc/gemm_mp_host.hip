@@ -2,6 +2,7 @@
 // owner-workgroup schedule, and the C ABI declared in include/gemm_mp.h.
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -77,6 +78,9 @@ struct gemm_mp_ctx {
     size_t prod_cap = 0;
     bool sched_uploaded = false;      // the device copies of q and the lists are those of the current schedule
     hipStream_t sched_stream = nullptr;
+    LaunchLanes lanes{};              // side streams of a run (made with the schedule's tables)
+    bool has_lanes = false;
+    bool serial = false;              // keep the launches of a run on the caller's stream, one after the other
     int64_t n_allocs = 0;             // device / pinned allocations this context has made
     int64_t n_syncs = 0;              // times it made the host wait for the device
     gemm_mp_stats stats;
@@ -493,6 +497,15 @@ int prepare_schedule(gemm_mp_ctx *c, hipStream_t s)
 {
     if (!c->sched_current) build_schedule(c);
     if (c->sched_uploaded) return GEMM_MP_OK;
+    if (!c->has_lanes) {
+        for (int k = 0; k < 4; ++k) {
+            HIP_TRY(hipStreamCreateWithFlags(&c->lanes.side[k], hipStreamNonBlocking));
+            HIP_TRY(hipEventCreateWithFlags(&c->lanes.join[k], hipEventDisableTiming));
+        }
+        HIP_TRY(hipEventCreateWithFlags(&c->lanes.fork, hipEventDisableTiming));
+        c->has_lanes = true;
+        c->n_allocs += 1;
+    }
     const size_t tasks = c->q.size();
     const size_t per_tile = (size_t)(c->nb / kMacro) * (size_t)(c->nb / kMacro);
     const size_t max_items = (size_t)c->MT * c->NT * per_tile;
@@ -581,6 +594,8 @@ int gemm_mp_create(gemm_mp_ctx **out, int64_t M, int64_t N, int64_t K, int32_t n
     c->mat[1].rows_t = c->KT; c->mat[1].cols_t = c->NT; c->mat[1].rows = K; c->mat[1].cols = N;
     c->mat[2].rows_t = c->MT; c->mat[2].cols_t = c->NT; c->mat[2].rows = M; c->mat[2].cols = N;
     std::memset(&c->stats, 0, sizeof(c->stats));
+    const char *serial = std::getenv("GEMM_MP_SERIAL_LAUNCHES");
+    c->serial = serial && serial[0] == '1';
     *out = c;
     return GEMM_MP_OK;
 }
@@ -591,6 +606,10 @@ int gemm_mp_destroy(gemm_mp_ctx *c)
     for (auto &m : c->mat) free_matrix_tables(m);
     release(c->qd); release(c->itemsd);
     (void)hipFree(c->d_prod);
+    if (c->has_lanes) {
+        for (int k = 0; k < 4; ++k) { (void)hipStreamDestroy(c->lanes.side[k]); (void)hipEventDestroy(c->lanes.join[k]); }
+        (void)hipEventDestroy(c->lanes.fork);
+    }
     (void)hipFree(c->d_conv[0]); (void)hipFree(c->d_conv[1]); (void)hipFree(c->d_jobs);
 
     (void)hipGetLastError();
@@ -814,7 +833,7 @@ int run_on(gemm_mp_ctx *c, double alpha, double beta, hipStream_t s, ProductDesc
     a.nb = c->nb; a.MT = c->MT; a.NT = c->NT; a.KT = c->KT;
     a.kt_eff = alpha == 0.0 ? 0 : c->KT;
     a.alpha = alpha; a.beta = beta;
-    HIP_TRY(launch_gemm(a, s));
+    HIP_TRY(launch_gemm(a, s, c->has_lanes && !c->serial ? &c->lanes : nullptr));
     if (n_low) HIP_TRY(launch_low_store(C.lowt.dev, n_low, c->nb, view_of(C), C.d_exp, C.d_low_max, s));
     C.packed = true;
     C.exps_valid = true;

@@ -128,7 +128,13 @@ hipError_t launch_pack_mx(const double *X, int64_t sr, int64_t sc, int64_t rows,
                           bool is_b, PackedView v, hipStream_t s);
 hipError_t launch_unpack(double *X, int64_t ld, int64_t rows, int64_t cols, int rows_t, int cols_t, int nb, bool turn,
                          bool swap, PackedView v, hipStream_t s);
-hipError_t launch_gemm(const GemmArgs &a, hipStream_t s);
+// Side streams (default priority) and events for running the launches of one gemm_mp_run side by side.
+struct LaunchLanes {
+    hipStream_t side[4];
+    hipEvent_t fork;
+    hipEvent_t join[4];
+};
+hipError_t launch_gemm(const GemmArgs &a, hipStream_t s, const LaunchLanes *lanes);
 hipError_t launch_convert(const ConvertJob *jobs_dev, int njobs, uint32_t max_n16, const int32_t *expA, const int32_t *expB,
                           hipStream_t s);
 hipError_t launch_low_expand(const LowTile *low_dev, int n_low, int nb, PackedView c, hipStream_t s);

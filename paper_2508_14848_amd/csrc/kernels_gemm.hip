@@ -163,27 +163,48 @@ hipError_t gemm_kernel_setup()
 
 // The product table, then one launch per kind of C tile: the owner regions of FP64 C tiles, those
 // of FP32 C tiles, and the large regions of FP32 C tiles made of FP8 / MXFP8 / MXFP4 products only.
-hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
+// The kinds touch disjoint C tiles and only read A, B and the tables, so they may run side by side:
+// with `lanes` the first kind stays on the caller's stream and every further one goes to a side
+// stream of its own, forked off behind the product table and joined again before the call
+// returns to the caller's stream, so that workgroups of one kind fill the compute units the tail of
+// another leaves idle.  Which workgroup computes what does not change: C is bit for bit the same.
+hipError_t launch_gemm(const GemmArgs &a, hipStream_t s, const LaunchLanes *lanes)
 {
     const int64_t tasks = (int64_t)a.MT * a.NT * a.KT;
     product_table_kernel<<<dim3((unsigned)((tasks + 255) / 256)), dim3(256), 0, s>>>(a.A, a.B, a.q, a.MT, a.NT, a.KT, a.convA, a.convB, a.prod);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (a.n_items64 > 0) {
-        // BF16 tiles among the operands: the instances that know the BF16 matrix instruction; FP16 /
-        // BF16 products with an FP8 operand: the instances whose DMA ring takes them
-        e = a.bf16 ? launch_owner_d_bf(a, a.items64, a.n_items64, s)
-            : a.mixed64 ? launch_owner_d_mixed(a, a.items64, a.n_items64, s) : launch_owner_d(a, a.items64, a.n_items64, s);
-        if (e != hipSuccess) return e;
+    struct Kind {
+        hipError_t (*launch)(const GemmArgs &, const WorkItem *, int, hipStream_t);
+        const WorkItem *items;
+        int n;
+    };
+    // BF16 tiles among the operands: the instances that know the BF16 matrix instruction; FP16 /
+    // BF16 products with an FP8 operand: the instances whose DMA ring takes them
+    const Kind all[5] = {
+        {a.bf16 ? launch_owner_d_bf : a.mixed64 ? launch_owner_d_mixed : launch_owner_d, a.items64, a.n_items64},
+        {a.bf16 ? launch_owner_f_bf : a.mixed32 ? launch_owner_f_mixed : launch_owner_f, a.items32, a.n_items32},
+        {launch_region_fp8, a.items8, a.n_items8},
+        {launch_region_mxfp8, a.items_mx, a.n_items_mx},
+        {launch_region_mxfp4, a.items_mx4, a.n_items_mx4}};
+    Kind kinds[5];
+    int n = 0;
+    for (const Kind &k : all)
+        if (k.n > 0) kinds[n++] = k;
+    if (n <= 1 || !lanes) {
+        for (int i = 0; i < n; ++i)
+            if ((e = kinds[i].launch(a, kinds[i].items, kinds[i].n, s)) != hipSuccess) return e;
+        return hipSuccess;
     }
-    if (a.n_items32 > 0) {
-        e = a.bf16 ? launch_owner_f_bf(a, a.items32, a.n_items32, s)
-            : a.mixed32 ? launch_owner_f_mixed(a, a.items32, a.n_items32, s) : launch_owner_f(a, a.items32, a.n_items32, s);
-        if (e != hipSuccess) return e;
+    if ((e = hipEventRecord(lanes->fork, s)) != hipSuccess) return e;
+    if ((e = kinds[0].launch(a, kinds[0].items, kinds[0].n, s)) != hipSuccess) return e;
+    for (int i = 1; i < n; ++i) {
+        hipStream_t side = lanes->side[i - 1];
+        if ((e = hipStreamWaitEvent(side, lanes->fork, 0)) != hipSuccess) return e;
+        if ((e = kinds[i].launch(a, kinds[i].items, kinds[i].n, side)) != hipSuccess) return e;
+        if ((e = hipEventRecord(lanes->join[i - 1], side)) != hipSuccess) return e;
+        if ((e = hipStreamWaitEvent(s, lanes->join[i - 1], 0)) != hipSuccess) return e;
     }
-    if (a.n_items8 > 0 && (e = launch_region_fp8(a, a.items8, a.n_items8, s)) != hipSuccess) return e;
-    if (a.n_items_mx > 0 && (e = launch_region_mxfp8(a, a.items_mx, a.n_items_mx, s)) != hipSuccess) return e;
-    if (a.n_items_mx4 > 0 && (e = launch_region_mxfp4(a, a.items_mx4, a.n_items_mx4, s)) != hipSuccess) return e;
     return hipSuccess;
 }
 

@@ -1276,3 +1276,27 @@ def test_steady_state_calls_neither_allocate_nor_wait():
     last = d.unpack_tiles("C").cpu().numpy()
     torch.cuda.synchronize()
     assert np.array_equal(first, last)                    # the original maps again: the same C bit for bit
+
+
+def test_launches_side_by_side_give_the_same_c_as_one_after_the_other(monkeypatch):
+    """The kernels of a run (FP64 C tiles, FP32 C tiles, 256 x 256 regions) are forked onto side
+    streams behind the product table; with GEMM_MP_SERIAL_LAUNCHES=1 they stay on the caller's
+    stream.  Which workgroup computes what is the same, so C is bit for bit the same."""
+    import torch
+    w = W.decay_rect(M=2048, N=2048, K=1024, nb=256, eps=1e-4, name="rect2k")
+    w.mapC = np.where(np.add.outer(np.arange(w.MT), np.arange(w.NT)) % 3 == 0, FP64, FP32).astype(np.uint16)
+    A, B, C0 = _dense(w)
+    results = []
+    for serial in ("1", "0"):
+        monkeypatch.setenv("GEMM_MP_SERIAL_LAUNCHES", serial)
+        d, dev = gpu_problem(w, A, B, C0)
+        for _ in range(2):
+            d.run(w.alpha, w.beta)
+        results.append(d.unpack_tiles("C").cpu().numpy())
+        torch.cuda.synchronize()
+        st = d.ctx.get_stats()
+        assert sum(1 for n in st["launch_items"] if n) >= 3          # three kinds of launches at least
+    assert np.array_equal(results[0], results[1])
+    side = OracleSide(w, A, B, C0)
+    jobs = orc.whole_tile_jobs(w.nb, [(0, 0), (1, 1), (w.MT - 1, w.NT - 1), (2, w.NT - 1)])
+    compare_jobs(side, jobs, 0, w.alpha, w.beta, results[1], side.gemm(jobs))
