@@ -31,7 +31,8 @@ DTYPE_NAMES = ["f64", "f32", "f16", "f8e4m3"]
 HEADLINE = "cov64k"
 ALSO = ("cov16k", "rect32k")
 KERNEL_NAMES = ["gemm_mp_owner_kernel<double%s>", "gemm_mp_owner_kernel<float%s>", "gemm_mp_fp8_region_kernel<0>",
-                "gemm_mp_fp8_region_kernel<1>", "gemm_mp_fp8_region_kernel<2>"]
+                "gemm_mp_fp8_region_kernel<1>", "gemm_mp_fp8_region_kernel<2>", "gemm_mp_fp8_region_kernel<3>",
+                "gemm_mp_fp8_region_kernel<4>"]
 INSTANCE = [", false, false", ", true, false", ", true, true"]
 
 
@@ -191,7 +192,7 @@ def measure(name, steps, warmup, policy, conversion, cpu_seconds):
     used = [DTYPE_NAMES[q] for q in range(4) if st["products"][q]]
     used += [n for n in ("bf16", "mxfp8", "mxfp4") if st["products_" + n]]
     launched = []
-    for k, n in enumerate(st["launch_items"][:5]):
+    for k, n in enumerate(st["launch_items"][:7]):
         if n:
             kn = KERNEL_NAMES[k]
             launched.append({"kernel": kn % INSTANCE[st["owner_instance"][k]] if k < 2 else kn, "workgroups": n})

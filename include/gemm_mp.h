@@ -130,7 +130,8 @@ typedef struct gemm_mp_stats {
     int64_t tiles_mxfp4[3];
     int64_t launch_items[8]; /* owner workgroups per kernel launch of gemm_mp_run: [0] 128 x 128 regions of
                               * FP64 C tiles, [1] of C tiles accumulated in FP32, [2] / [3] / [4] 256 x 256
-                              * regions of tiles made of FP8 / MXFP8 / MXFP4 products only; the rest 0 */
+                              * regions of tiles made of FP8 / MXFP8 / MXFP4 products only, [5] / [6] of FP16 /
+                              * BF16 products only; [7] is 0 */
     int32_t owner_instance[2]; /* which instance of the 128 x 128 kernel serves [0] and [1]: 0 plain, 1 the one
                               * whose DMA ring also takes FP16 products with an FP8 operand, 2 the BF16 one */
 } gemm_mp_stats;

@@ -69,9 +69,10 @@ struct gemm_mp_ctx {
     Matrix mat[3];
     bool sched_current = false;
     std::vector<uint8_t> q;
-    std::vector<WorkItem> items[5];   // regions of [0] FP64 C tiles, [1] C tiles accumulated in FP32 (stored
+    std::vector<WorkItem> items[7];   // regions of [0] FP64 C tiles, [1] C tiles accumulated in FP32 (stored
                                       // FP32 / FP16 / FP8), [2] those of them whose products are all
-                                      // FP8 x FP8 (256 x 256 regions), [3] / [4] the same for MXFP8 x MXFP8 / MXFP4 x MXFP4
+                                      // FP8 x FP8 (256 x 256 regions), [3] / [4] the same for MXFP8 x MXFP8 / MXFP4 x MXFP4,
+                                      // [5] / [6] for FP16 x FP16 / BF16 x BF16
     Mirror<uint8_t> qd;               // [MT*NT][KT] product precision of every task
     Mirror<WorkItem> itemsd;          // the lists, [0] first
     ProductDesc *d_prod = nullptr;    // one record per task (+ 2 padding records), filled on the device
@@ -430,10 +431,24 @@ void build_schedule(gemm_mp_ctx *c)
                          B.map[L * NT + J] == GEMM_MP_FP8_E4M3;
                 all_fp8[(size_t)I * NT + J] = ok;
             }
+    // ... and likewise a tile whose every product multiplies two FP16 tiles, or two BF16 tiles (the
+    // 32x32x16 matrix instructions; the FP16 tiles' scales are followed by rescaling the sums)
+    std::vector<uint8_t> all_16((size_t)MT * NT, 0);         // 1: all FP16 x FP16, 2: all BF16 x BF16
+    if (c->nb % kMacroFp8 == 0)
+        for (int I = 0; I < MT; ++I)
+            for (int J = 0; J < NT; ++J) {
+                bool h = C.map[I * NT + J] != GEMM_MP_FP64 && KT > 0, b = h;
+                for (int L = 0; (h || b) && L < KT; ++L) {
+                    const int q = c->q[((size_t)I * NT + J) * KT + L], pa = A.map[I * KT + L], pb = B.map[L * NT + J];
+                    h = h && q == GEMM_MP_FP16 && pa == GEMM_MP_FP16 && pb == GEMM_MP_FP16;
+                    b = b && q == GEMM_MP_BF16 && pa == GEMM_MP_BF16 && pb == GEMM_MP_BF16;
+                }
+                all_16[(size_t)I * NT + J] = h ? 1 : b ? 2 : 0;
+            }
     c->mixed32 = c->mixed64 = false;
     for (int I = 0; I < MT; ++I)
         for (int J = 0; J < NT; ++J) {
-            if (all_fp8[(size_t)I * NT + J]) continue;
+            if (all_fp8[(size_t)I * NT + J] || all_16[(size_t)I * NT + J]) continue;
             bool mixed = false;
             for (int L = 0; L < KT; ++L) {
                 const int q = c->q[((size_t)I * NT + J) * KT + L];
@@ -444,12 +459,12 @@ void build_schedule(gemm_mp_ctx *c)
             else c->mixed32 |= mixed;
         }
     constexpr int kBins = 8;
-    for (int list = 0; list < 5; ++list) {
+    for (int list = 0; list < 7; ++list) {
         const int mr = c->nb / (list >= 2 ? kMacroFp8 : kMacro);
         const size_t per_tile = (size_t)mr * mr;
         std::vector<int> order;
         for (int t = 0; t < MT * NT; ++t) {
-            const int which = C.map[t] == GEMM_MP_FP64 ? 0 : all_fp8[t] ? 2 : all_mx[t] ? 2 + all_mx[t] : 1;
+            const int which = C.map[t] == GEMM_MP_FP64 ? 0 : all_fp8[t] ? 2 : all_mx[t] ? 2 + all_mx[t] : all_16[t] ? 4 + all_16[t] : 1;
             if (which == list) order.push_back(t);
         }
         std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cost[a] > cost[b]; });
@@ -482,8 +497,11 @@ void build_schedule(gemm_mp_ctx *c)
             }
         }
     }
-    c->stats.work_items = (int64_t)(c->items[0].size() + c->items[1].size() + c->items[2].size() + c->items[3].size() + c->items[4].size());
-    for (int list = 0; list < 5; ++list) c->stats.launch_items[list] = (int64_t)c->items[list].size();
+    c->stats.work_items = 0;
+    for (int list = 0; list < 7; ++list) {
+        c->stats.launch_items[list] = (int64_t)c->items[list].size();
+        c->stats.work_items += (int64_t)c->items[list].size();
+    }
     c->stats.owner_instance[0] = c->has_bf16 ? 2 : c->mixed64 ? 1 : 0;
     c->stats.owner_instance[1] = c->has_bf16 ? 2 : c->mixed32 ? 1 : 0;
     c->sched_current = true;
@@ -524,7 +542,7 @@ int prepare_schedule(gemm_mp_ctx *c, hipStream_t s)
     if (!pq || !pi) return GEMM_MP_EHIP;
     std::memcpy(pq, c->q.data(), tasks);
     size_t n = 0;
-    for (int list = 0; list < 5; ++list) {
+    for (int list = 0; list < 7; ++list) {
         if (!c->items[list].empty()) std::memcpy(pi + n, c->items[list].data(), c->items[list].size() * sizeof(WorkItem));
         n += c->items[list].size();
     }
@@ -827,6 +845,10 @@ int run_on(gemm_mp_ctx *c, double alpha, double beta, hipStream_t s, ProductDesc
     a.n_items_mx = (int32_t)c->items[3].size();
     a.items_mx4 = a.items_mx + c->items[3].size();
     a.n_items_mx4 = (int32_t)c->items[4].size();
+    a.items_h = a.items_mx4 + c->items[4].size();
+    a.n_items_h = (int32_t)c->items[5].size();
+    a.items_bf = a.items_h + c->items[5].size();
+    a.n_items_bf = (int32_t)c->items[6].size();
     a.mixed32 = c->mixed32 ? 1 : 0;
     a.mixed64 = c->mixed64 ? 1 : 0;
     a.bf16 = c->has_bf16 ? 1 : 0;

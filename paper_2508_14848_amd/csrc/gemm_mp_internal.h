@@ -104,7 +104,9 @@ struct GemmArgs {
     const WorkItem *items8;   // 256 x 256 regions of FP32 C tiles made of FP8 x FP8 products only
     const WorkItem *items_mx; // the same of tiles made of MXFP8 x MXFP8 products only
     const WorkItem *items_mx4;// ... of MXFP4 x MXFP4 products only
-    int32_t n_items64, n_items32, n_items8, n_items_mx, n_items_mx4;
+    const WorkItem *items_h;  // ... of FP16 x FP16 products only
+    const WorkItem *items_bf; // ... of BF16 x BF16 products only
+    int32_t n_items64, n_items32, n_items8, n_items_mx, n_items_mx4, n_items_h, n_items_bf;
     int32_t mixed32;         // some region of items32 has an FP16 / BF16 product with an operand stored in FP8
     int32_t mixed64;         // the same for items64
     int32_t bf16;            // some tile of A or B is stored in BF16
@@ -148,5 +150,6 @@ hipError_t gemm_kernel_setup();
 GMP_DECLARE_INSTANCE(owner_d) GMP_DECLARE_INSTANCE(owner_d_mixed) GMP_DECLARE_INSTANCE(owner_d_bf)
 GMP_DECLARE_INSTANCE(owner_f) GMP_DECLARE_INSTANCE(owner_f_mixed) GMP_DECLARE_INSTANCE(owner_f_bf)
 GMP_DECLARE_INSTANCE(region_fp8) GMP_DECLARE_INSTANCE(region_mxfp8) GMP_DECLARE_INSTANCE(region_mxfp4)
+GMP_DECLARE_INSTANCE(region_fp16) GMP_DECLARE_INSTANCE(region_bf16)
 
 }  // namespace gmp

@@ -136,6 +136,43 @@ __device__ __forceinline__ i8v big_fp4_operand(const i8v &f, int j)
     return j ? i8v{f[4], f[5], f[6], f[7], 0, 0, 0, 0} : i8v{f[0], f[1], f[2], f[3], 0, 0, 0, 0};
 }
 
+// FMT 3 (FP16) / 4 (BF16): reduction step w (0, 1) of a half on the 32x32x16 matrix instruction.  A
+// lane's operand is 16 bytes = 8 elements of its row, the indices 8 (lane / 32) ... of the
+// instruction's sixteen; which eight of the chunk row a lane holds is the same for A and B (the
+// w-th 16 bytes of its fragment), and over a half every 16-byte piece of the 64 bytes is met once.
+typedef _Float16 h8v __attribute__((ext_vector_type(8)));
+typedef __bf16 bf8v __attribute__((ext_vector_type(8)));
+template <int FMT>
+__device__ __forceinline__ f16v big_mfma16(const i8v &a, const i8v &b, const f16v &c, int w)
+{
+    const i32x4 x = w ? i32x4{a[4], a[5], a[6], a[7]} : i32x4{a[0], a[1], a[2], a[3]};
+    const i32x4 y = w ? i32x4{b[4], b[5], b[6], b[7]} : i32x4{b[0], b[1], b[2], b[3]};
+    if constexpr (FMT == 3) return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8v, x), __builtin_bit_cast(h8v, y), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf8v, x), __builtin_bit_cast(bf8v, y), c, 0, 0, 0);
+}
+
+// All 256 accumulator registers of a wave times a power of two.  The accumulators live in
+// accumulation registers, which the vector ALU cannot address: every value takes the road
+// read - multiply - write back through a vector register.  Left to itself the compiler sends all
+// values down this road at once and spills eighty accumulators to make room (on every product,
+// rescaled or not); the empty statements make each block of sixteen complete the round trip
+// before the next one sets out.
+__device__ __forceinline__ void big_rescale(f16v (&acc)[4][4], float ratio)
+{
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            f16v t = acc[mt][nt];
+            asm volatile("" : "+v"(t));
+#pragma unroll
+            for (int v = 0; v < 16; ++v) t[v] = t[v] * ratio;
+            asm volatile("" : "+v"(t));
+            acc[mt][nt] = t;
+            asm volatile("" : "+a"(acc[mt][nt]));
+        }
+}
+
 // One chunk held in `STAGE`.  On entry f[0] holds the fragments of its first half; on exit
 // those of the next chunk's first half.  S2: the chunk two ahead, requested into STAGE.
 // FMT 2 (MXFP4): a half holds two reduction steps of 64 four-bit elements; the first step's MFMAs
@@ -154,7 +191,10 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
-            if constexpr (FMT == 2) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[0][mt], 0), big_fp4_operand(f[0][4 + nt], 0), acc[mt][nt], 4, 4, 0, sc[SO + mt], 0, sc[SO + 4 + nt]);
+            if constexpr (FMT >= 3) {
+                acc[mt][nt] = big_mfma16<FMT>(f[0][mt], f[0][4 + nt], acc[mt][nt], 0);
+                acc[mt][nt] = big_mfma16<FMT>(f[0][mt], f[0][4 + nt], acc[mt][nt], 1);
+            } else if constexpr (FMT == 2) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[0][mt], 0), big_fp4_operand(f[0][4 + nt], 0), acc[mt][nt], 4, 4, 0, sc[SO + mt], 0, sc[SO + 4 + nt]);
             else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sc[SO + mt], 0, sc[SO + 4 + nt]);
             else acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
             SCHED_FENCE();
@@ -186,7 +226,10 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
-            if constexpr (FMT == 2) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[1][mt], 0), big_fp4_operand(f[1][4 + nt], 0), acc[mt][nt], 4, 4, 0, sc[SO + 8 + mt], 0, sc[SO + 12 + nt]);
+            if constexpr (FMT >= 3) {
+                acc[mt][nt] = big_mfma16<FMT>(f[1][mt], f[1][4 + nt], acc[mt][nt], 0);
+                acc[mt][nt] = big_mfma16<FMT>(f[1][mt], f[1][4 + nt], acc[mt][nt], 1);
+            } else if constexpr (FMT == 2) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[1][mt], 0), big_fp4_operand(f[1][4 + nt], 0), acc[mt][nt], 4, 4, 0, sc[SO + 8 + mt], 0, sc[SO + 12 + nt]);
             else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 2, sc[SO + mt], 2, sc[SO + 4 + nt]);
             else acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
             SCHED_FENCE();
@@ -223,8 +266,8 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     const int tileC = (int)(uint32_t)itw;
     const ArgsPtr K0 = args();
     const int nb = K0->nb, kt = K0->kt_eff;
-    constexpr bool MX = FMT != 0;
-    const int pitch = FMT == 2 ? nb / 2 : nb;                // bytes of a tile row
+    constexpr bool MX = FMT == 1 || FMT == 2;
+    const int pitch = FMT == 2 ? nb / 2 : FMT >= 3 ? 2 * nb : nb;   // bytes of a tile row
     const int arow0 = (int)((itw >> 32) & 0xffffu) * kBigMacro, brow0 = (int)((itw >> 48) & 0xffffu) * kBigMacro;
     const ProductDesc *prod = K0->prod + (int64_t)tileC * K0->KT;
 
@@ -266,121 +309,152 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     }
 
     f16v acc[4][4];
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[mt][nt][v] = 0.0f;
-
     const int n = pitch / kRowBytes;                         // chunks per product: even (the host sees to that)
     const int tile_bytes = nb * pitch;
-    if (kt > 0) {
-        const ConstQuad rec0 = (ConstQuad)(uintptr_t)prod;
-        u32x4 lo = rec0[0], hi = rec0[1];
-        BigSource S;
-        S.a = (uint64_t)lo.x | ((uint64_t)lo.y << 32);
-        S.b = (uint64_t)lo.z | ((uint64_t)lo.w << 32);
-        S.bytes = tile_bytes;
-        S.c = 0;
+
+    // FP16 tiles carry a power-of-two scale each, so the terms of product L count in units of
+    // 2^(eA + eB) of that product.  The one set of accumulators follows: at a product whose unit
+    // differs it is multiplied by the ratio of the units (exact: a power of two, kept far from
+    // the ends of FP32's range by the two bounds in the loop).  Where the units of the products
+    // summed so far and the next one lie more than 2^64 apart, the reduction is cut there: the
+    // sum so far leaves through the epilogue (alpha and beta applied, written to C), and the
+    // rest of the reduction starts again from zero accumulators as a segment of its own whose
+    // epilogue adds to what is there.  Every other format has one segment.
+    int e_cur = 0, e_hi = 0, e_lo = 0;
+    int L0 = 0;                                              // first product of the segment
+    bool again = false;                                      // the region has been written before
+    do {
 #pragma unroll
-        for (int j = 0; j < 16; ++j) big_request(S, BG, 0, j);
-        S.c = 1;
+        for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) big_request(S, BG, 1, j);
+            for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mt][nt][v] = 0.0f;
+        int L = L0;
+        if (kt > 0) {
+            if (L0 > 0) __syncthreads();                     // every wave has left the stages of the segment before
+            const ConstQuad rec0 = (ConstQuad)(uintptr_t)(prod + L0);
+            u32x4 lo = rec0[0], hi = rec0[1];
+            BigSource S;
+            S.a = (uint64_t)lo.x | ((uint64_t)lo.y << 32);
+            S.b = (uint64_t)lo.z | ((uint64_t)lo.w << 32);
+            S.bytes = tile_bytes;
+            S.c = 0;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) big_request(S, BG, 0, j);
+            S.c = 1;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) big_request(S, BG, 1, j);
 #if defined(__HIP_DEVICE_COMPILE__)
-        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");    // chunk 0 has landed
+            asm volatile("s_waitcnt vmcnt(16)" ::: "memory");    // chunk 0 has landed
 #endif
-        __syncthreads();
-        i8v f[2][8];
+            __syncthreads();
+            i8v f[2][8];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) f[0][t] = big_read(BG, lds, 0, 0, t);
-        int sc[32], nsc[32];
+            for (int t = 0; t < 8; ++t) f[0][t] = big_read(BG, lds, 0, 0, t);
+            int sc[32], nsc[32];
 #pragma unroll
-        for (int t = 0; t < 32; ++t) sc[t] = nsc[t] = 0;
-        if constexpr (MX) {
-            big_load_scales<FMT>(sc, SG, S.a, S.b, nb, 0);
+            for (int t = 0; t < 32; ++t) sc[t] = nsc[t] = 0;
+            if constexpr (MX) {
+                big_load_scales<FMT>(sc, SG, S.a, S.b, nb, 0);
 #pragma unroll
-            for (int t = 0; t < 32; ++t) sc[t] = (int)((uint32_t)sc[t] >> SG.shift);
+                for (int t = 0; t < 32; ++t) sc[t] = (int)((uint32_t)sc[t] >> SG.shift);
+            }
+
+            for (; L < kt; ++L) {
+                int sa, sb;
+                big_scales((int)hi.x, (int)hi.y, sa, sb);
+                if constexpr (FMT == 3) {
+                    const int e = (int)hi.x + (int)hi.y;
+                    if (L == L0) {
+                        e_cur = e_hi = e_lo = e;
+                    } else if (e != e_cur) {
+                        if (e_hi - e > 64 || e - e_lo > 64) break;       // cut the reduction here
+                        const float ratio = __uint_as_float((uint32_t)(e_cur - e + 127) << 23);      // 2^(e_cur - e), |e_cur - e| <= 64
+                        big_rescale(acc, ratio);
+                        e_hi = e > e_hi ? e : e_hi;
+                        e_lo = e < e_lo ? e : e_lo;
+                        e_cur = e;
+                    }
+                }
+                // the following product (descriptors of length zero past the end)
+                u32x4 nlo = lo, nhi = hi;
+                int nbytes = 0;
+                if (L + 1 < kt) {
+                    const ConstQuad rec = (ConstQuad)(uintptr_t)(prod + L + 1);
+                    nlo = rec[0];
+                    nhi = rec[1];
+                    nbytes = tile_bytes;
+                }
+                BigSource cur_src, next_src;
+                cur_src.a = (uint64_t)lo.x | ((uint64_t)lo.y << 32);
+                cur_src.b = (uint64_t)lo.z | ((uint64_t)lo.w << 32);
+                cur_src.bytes = tile_bytes;
+                next_src.a = (uint64_t)nlo.x | ((uint64_t)nlo.y << 32);
+                next_src.b = (uint64_t)nlo.z | ((uint64_t)nlo.w << 32);
+                next_src.bytes = nbytes;
+                for (int c = 0; c < n; c += 2) {
+                    BigSource S2 = (c + 2 < n) ? cur_src : next_src;
+                    S2.c = (c + 2 < n) ? c + 2 : c + 2 - n;
+                    // block scales of what follows are fetched under the chunk being computed (past the
+                    // end of the reduction: those of the last chunks again, unused)
+                    int nx[32];
+#pragma unroll
+                    for (int t = 0; t < 32; ++t) nx[t] = 0;
+                    if constexpr (MX) {
+                        // sc holds the scales of chunks c and c + 1; those of the next pair are requested
+                        // before the second chunk and taken over in its middle
+                        const bool wrap = c + 2 >= n && nbytes != 0;
+                        big_chunk<0, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
+                        big_load_scales<FMT>(nsc, SG, wrap ? next_src.a : cur_src.a, wrap ? next_src.b : cur_src.b, nb, c + 2 < n ? c + 2 : wrap ? 0 : n - 2);
+                        S2.c += 1;
+                        big_chunk<1, FMT, true, FMT == 2 ? 16 : 8>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
+#pragma unroll
+                        for (int t = 0; t < 32; ++t) sc[t] = nx[t];
+                    } else {
+                        big_chunk<0, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
+                        S2.c += 1;
+                        big_chunk<1, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
+                    }
+                }
+                lo = nlo;
+                hi = nhi;
+            }
+#if defined(__HIP_DEVICE_COMPILE__)
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // requests past the segment's end still write into the stages
+#endif
         }
 
-        for (int L = 0; L < kt; ++L) {
-            int sa, sb;
-            big_scales((int)hi.x, (int)hi.y, sa, sb);
-            // the following product (descriptors of length zero past the end)
-            u32x4 nlo = lo, nhi = hi;
-            int nbytes = 0;
-            if (L + 1 < kt) {
-                const ConstQuad rec = (ConstQuad)(uintptr_t)(prod + L + 1);
-                nlo = rec[0];
-                nhi = rec[1];
-                nbytes = tile_bytes;
-            }
-            BigSource cur_src, next_src;
-            cur_src.a = (uint64_t)lo.x | ((uint64_t)lo.y << 32);
-            cur_src.b = (uint64_t)lo.z | ((uint64_t)lo.w << 32);
-            cur_src.bytes = tile_bytes;
-            next_src.a = (uint64_t)nlo.x | ((uint64_t)nlo.y << 32);
-            next_src.b = (uint64_t)nlo.z | ((uint64_t)nlo.w << 32);
-            next_src.bytes = nbytes;
-            for (int c = 0; c < n; c += 2) {
-                BigSource S2 = (c + 2 < n) ? cur_src : next_src;
-                S2.c = (c + 2 < n) ? c + 2 : c + 2 - n;
-                // block scales of what follows are fetched under the chunk being computed (past the
-                // end of the reduction: those of the last chunks again, unused)
-                int nx[32];
+        // Epilogue: v = alpha*s (+ beta*c0), two rounded products and one rounded sum in FP32.  A
+        // 32 x 32 accumulator block holds, per register, one row piece of 32 consecutive columns
+        // in each half of the wave: 128-byte row segments straight from the registers.  FP16
+        // tiles: the accumulators hold the sum in units of 2^e_cur.  A later segment adds to what
+        // the earlier ones wrote (beta has been applied by the first).
+        const ArgsPtr K = args();
+        const float alpha = (float)K->alpha, beta = again ? 1.0f : (float)K->beta;
+        const bool use_c = again || K->beta != 0.0;
+        typedef __attribute__((address_space(1))) float *GlobalF;
+        GlobalF ctile = (GlobalF)(uintptr_t)(K->C.storage + table_u64(K->C.offset, tileC));
+        GlobalF cbase = ctile + (int64_t)(arow0 + wm * 128 + 4 * (lane >> 5)) * nb + brow0 + wn * 128 + (lane & 31);
 #pragma unroll
-                for (int t = 0; t < 32; ++t) nx[t] = 0;
-                if constexpr (MX) {
-                    // sc holds the scales of chunks c and c + 1; those of the next pair are requested
-                    // before the second chunk and taken over in its middle
-                    const bool wrap = c + 2 >= n && nbytes != 0;
-                    big_chunk<0, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
-                    big_load_scales<FMT>(nsc, SG, wrap ? next_src.a : cur_src.a, wrap ? next_src.b : cur_src.b, nb, c + 2 < n ? c + 2 : wrap ? 0 : n - 2);
-                    S2.c += 1;
-                    big_chunk<1, FMT, true, FMT == 2 ? 16 : 8>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
+        for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-                    for (int t = 0; t < 32; ++t) sc[t] = nx[t];
-                } else {
-                    big_chunk<0, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
-                    S2.c += 1;
-                    big_chunk<1, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
+            for (int nt = 0; nt < 4; ++nt) {
+                float c0[16];
+                if (use_c) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) c0[v] = cbase[(int64_t)(mt * 32 + 8 * (v >> 2) + (v & 3)) * nb + nt * 32];
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float val = alpha * (FMT == 3 ? ldexpf(acc[mt][nt][v], e_cur) : acc[mt][nt][v]);
+                    if (use_c) { const float bc = beta * c0[v]; val = val + bc; }
+                    cbase[(int64_t)(mt * 32 + 8 * (v >> 2) + (v & 3)) * nb + nt * 32] = val;
                 }
             }
-            lo = nlo;
-            hi = nhi;
-        }
-#if defined(__HIP_DEVICE_COMPILE__)
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the empty requests still write zeros into the stages
-#endif
-    }
-
-    // Epilogue: v = alpha*s (+ beta*c0), two rounded products and one rounded sum in FP32.  A
-    // 32 x 32 accumulator block holds, per register, one row piece of 32 consecutive columns
-    // in each half of the wave: 128-byte row segments straight from the registers.
-    const ArgsPtr K = args();
-    const float alpha = (float)K->alpha, beta = (float)K->beta;
-    const bool use_c = K->beta != 0.0;
-    typedef __attribute__((address_space(1))) float *GlobalF;
-    GlobalF ctile = (GlobalF)(uintptr_t)(K->C.storage + table_u64(K->C.offset, tileC));
-    const int i = lane & 31, g = lane >> 5;
-    GlobalF cbase = ctile + (int64_t)(arow0 + wm * 128 + 4 * g) * nb + brow0 + wn * 128 + i;
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-            float c0[16];
-            if (use_c) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) c0[v] = cbase[(int64_t)(mt * 32 + 8 * (v >> 2) + (v & 3)) * nb + nt * 32];
-            }
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float val = alpha * acc[mt][nt][v];
-                if (use_c) { const float bc = beta * c0[v]; val = val + bc; }
-                cbase[(int64_t)(mt * 32 + 8 * (v >> 2) + (v & 3)) * nb + nt * 32] = val;
-            }
-        }
+        again = true;
+        L0 = L;
+    } while (FMT == 3 && L0 < kt);
 }
 
 }  // namespace gmp

@@ -152,8 +152,9 @@ hipError_t launch_convert(const ConvertJob *jobs_dev, int njobs, uint32_t max_n1
 
 hipError_t gemm_kernel_setup()
 {
-    hipError_t (*const setups[9])() = {setup_owner_d, setup_owner_d_mixed, setup_owner_d_bf, setup_owner_f, setup_owner_f_mixed,
-                                       setup_owner_f_bf, setup_region_fp8, setup_region_mxfp8, setup_region_mxfp4};
+    hipError_t (*const setups[11])() = {setup_owner_d, setup_owner_d_mixed, setup_owner_d_bf, setup_owner_f, setup_owner_f_mixed,
+                                        setup_owner_f_bf, setup_region_fp8, setup_region_mxfp8, setup_region_mxfp4, setup_region_fp16,
+                                        setup_region_bf16};
     for (auto f : setups) {
         const hipError_t e = f();
         if (e != hipSuccess) return e;
@@ -162,7 +163,7 @@ hipError_t gemm_kernel_setup()
 }
 
 // The product table, then one launch per kind of C tile: the owner regions of FP64 C tiles, those
-// of FP32 C tiles, and the large regions of FP32 C tiles made of FP8 / MXFP8 / MXFP4 products only.
+// of FP32 C tiles, and the large regions of FP32 C tiles made of FP8 / MXFP8 / MXFP4 / FP16 / BF16 products only.
 // The kinds touch disjoint C tiles and only read A, B and the tables, so they may run side by side:
 // with `lanes` the first kind stays on the caller's stream and every further one goes to a side
 // stream of its own, forked off behind the product table and joined again before the call
@@ -181,13 +182,15 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s, const LaunchLanes *lane
     };
     // BF16 tiles among the operands: the instances that know the BF16 matrix instruction; FP16 /
     // BF16 products with an FP8 operand: the instances whose DMA ring takes them
-    const Kind all[5] = {
+    const Kind all[7] = {
         {a.bf16 ? launch_owner_d_bf : a.mixed64 ? launch_owner_d_mixed : launch_owner_d, a.items64, a.n_items64},
         {a.bf16 ? launch_owner_f_bf : a.mixed32 ? launch_owner_f_mixed : launch_owner_f, a.items32, a.n_items32},
         {launch_region_fp8, a.items8, a.n_items8},
         {launch_region_mxfp8, a.items_mx, a.n_items_mx},
-        {launch_region_mxfp4, a.items_mx4, a.n_items_mx4}};
-    Kind kinds[5];
+        {launch_region_mxfp4, a.items_mx4, a.n_items_mx4},
+        {launch_region_fp16, a.items_h, a.n_items_h},
+        {launch_region_bf16, a.items_bf, a.n_items_bf}};
+    Kind kinds[7];
     int n = 0;
     for (const Kind &k : all)
         if (k.n > 0) kinds[n++] = k;
@@ -199,10 +202,12 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s, const LaunchLanes *lane
     if ((e = hipEventRecord(lanes->fork, s)) != hipSuccess) return e;
     if ((e = kinds[0].launch(a, kinds[0].items, kinds[0].n, s)) != hipSuccess) return e;
     for (int i = 1; i < n; ++i) {
-        hipStream_t side = lanes->side[i - 1];
+        hipStream_t side = lanes->side[(i - 1) % 4];
         if ((e = hipStreamWaitEvent(side, lanes->fork, 0)) != hipSuccess) return e;
         if ((e = kinds[i].launch(a, kinds[i].items, kinds[i].n, side)) != hipSuccess) return e;
-        if ((e = hipEventRecord(lanes->join[i - 1], side)) != hipSuccess) return e;
+    }
+    for (int i = 1; i < n && i <= 4; ++i) {          // every side stream joins once, behind its last launch
+        if ((e = hipEventRecord(lanes->join[i - 1], lanes->side[i - 1])) != hipSuccess) return e;
         if ((e = hipStreamWaitEvent(s, lanes->join[i - 1], 0)) != hipSuccess) return e;
     }
     return hipSuccess;

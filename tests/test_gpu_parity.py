@@ -1300,3 +1300,78 @@ def test_launches_side_by_side_give_the_same_c_as_one_after_the_other(monkeypatc
     side = OracleSide(w, A, B, C0)
     jobs = orc.whole_tile_jobs(w.nb, [(0, 0), (1, 1), (w.MT - 1, w.NT - 1), (2, w.NT - 1)])
     compare_jobs(side, jobs, 0, w.alpha, w.beta, results[1], side.gemm(jobs))
+
+
+def test_fp32_tiles_made_of_fp16_or_bf16_products_only():
+    """C tiles accumulated in FP32 whose every product multiplies two FP16 tiles (or two BF16
+    tiles) run in 256 x 256 regions on the 32x32x16 matrix instructions; the FP16 tiles' scales
+    are followed by rescaling the one set of accumulators between products, and where the scales
+    of a C tile's products lie too far apart the sum so far leaves through the epilogue early.
+    Small integers (exact; tile sizes with 4, 8, 12 and 16 chunks, so the rotated chunk order
+    wraps; general alpha and beta; FP64 and mixed tiles beside them), small integers times powers
+    of two per tile (rescaling, still exact), then general data against the oracle, with tile
+    magnitudes that rescale and that force the early epilogue."""
+    import torch
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(35)
+    for fmt in (FP16, BF16):
+        for (nb, MT, NT, KT) in ((256, 2, 3, 5), (512, 2, 2, 3), (768, 1, 2, 2), (1024, 1, 2, 2)):
+            M, N, K = MT * nb, NT * nb, KT * nb
+            A = rng.integers(-3, 4, (M, K)).astype(np.float64)
+            B = rng.integers(-3, 4, (K, N)).astype(np.float64)
+            C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
+            shift = np.zeros(KT, dtype=np.int64)
+            if fmt == FP16:                          # tile scales that differ from product to product
+                shift = rng.integers(0, 4, KT)
+                for L in range(KT):
+                    A[:, L * nb:(L + 1) * nb] *= 2.0 ** float(shift[L])
+            mA = np.full((MT, KT), fmt, dtype=np.uint16)
+            mB = np.full((KT, NT), fmt, dtype=np.uint16)
+            mC = np.full((MT, NT), FP32, dtype=np.uint16)
+            if MT * NT > 2:
+                mC[0, 0] = FP64                      # an FP64 tile: the ordinary kernel
+            mB[KT - 1, NT - 1] = FP8                 # last tile column: one FP8 operand, so not that format only
+            _say("16-bit-only tiles", fmt, (nb, MT, NT, KT), "shifts", shift)
+            d = DeviceGemmMP(M, N, K, nb)
+            for which, m, X in (("A", mA, A), ("B", mB, B), ("C", mC, C0)):
+                d.set_precision_map(which, m)
+                d.pack_tiles(which, torch.from_numpy(X).cuda())
+            st = d.ctx.get_stats()
+            big = sum(1 for I in range(MT) for J in range(NT) if mC[I, J] == FP32 and J != NT - 1)
+            assert st["launch_items"][5 if fmt == FP16 else 6] == big * (nb // 256) ** 2
+            d.run(2.0, -3.0)
+            got = d.unpack_tiles("C").cpu().numpy()
+            want = 2 * (A.astype(np.int64) @ B.astype(np.int64)) - 3 * C0.astype(np.int64)
+            assert np.array_equal(got, want.astype(np.float64))
+            d.pack_tiles("C", torch.from_numpy(C0).cuda())
+            d.run(0.0, 1.0)                          # alpha == 0: no product is formed
+            assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), C0)
+    # general data against the oracle; the decaying tiles of this workload give every product its own scale
+    for fmt in (FP16, BF16):
+        w = W.tiny(M=512, N=768, K=1024, nb=256)
+        w.mapA = np.full((w.MT, w.KT), fmt, dtype=np.uint16)
+        w.mapB = np.full((w.KT, w.NT), fmt, dtype=np.uint16)
+        w.mapC = np.full((w.MT, w.NT), FP32, dtype=np.uint16)
+        w.mapC[1, 1] = FP16                          # a narrow C tile: accumulated in its FP32 staging copy
+        d, _, _, _ = _run_and_compare(w)
+        assert d.ctx.get_stats()["launch_items"][5 if fmt == FP16 else 6] == w.MT * w.NT
+        w.alpha, w.beta = -0.75, 1.25
+        _run_and_compare(w)
+
+    # tile magnitudes 2^0, 2^-50, 2^-90, 2^-40, 2^30 along the reduction: rescaling by up to 2^100 in
+    # two steps, and jumps beyond 2^64 that force the early epilogue (with and without an old C)
+    class _Jumps(type(W.tiny())):
+        def panel(self, which, r0, r1):
+            x = super().panel(which, r0, r1)
+            if which == "A":
+                for L, k in enumerate((0, -50, -90, -40, 30)):
+                    x[:, L * self.nb:(L + 1) * self.nb] *= 2.0 ** k
+            return x
+    w = _Jumps("jumps", 512, 512, 1280, 256, 1.5, 0.5, dist="uniform")
+    w.mapA = np.full((w.MT, w.KT), FP16, dtype=np.uint16)
+    w.mapB = np.full((w.KT, w.NT), FP16, dtype=np.uint16)
+    w.mapC = np.full((w.MT, w.NT), FP32, dtype=np.uint16)
+    assert w.KT == 5
+    _run_and_compare(w)
+    w.alpha, w.beta = 1.0, 0.0
+    _run_and_compare(w)
