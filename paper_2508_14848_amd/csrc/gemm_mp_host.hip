@@ -462,38 +462,45 @@ void build_schedule(gemm_mp_ctx *c)
     for (int list = 0; list < 7; ++list) {
         const int mr = c->nb / (list >= 2 ? kMacroFp8 : kMacro);
         const size_t per_tile = (size_t)mr * mr;
-        std::vector<int> order;
-        for (int t = 0; t < MT * NT; ++t) {
-            const int which = C.map[t] == GEMM_MP_FP64 ? 0 : all_fp8[t] ? 2 : all_mx[t] ? 2 + all_mx[t] : all_16[t] ? 4 + all_16[t] : 1;
-            if (which == list) order.push_back(t);
+        std::vector<WorkItem> bins[kBins];
+        {
+            // C tiles sorted by cost and dealt to the bins, heaviest first; a tile's regions stay
+            // together, row by row.  (For the 256 x 256 regions, whose kernels wait for operand
+            // bytes, an order in which the 32 regions an XCD holds at a time form a compact 4 x 8
+            // block of C was measured too: same run time, more bytes fetched into the L2s.  What
+            // those kernels wait for is the delivery from L2 to the compute units.)
+            std::vector<int> order;
+            for (int t = 0; t < MT * NT; ++t) {
+                const int which = C.map[t] == GEMM_MP_FP64 ? 0 : all_fp8[t] ? 2 : all_mx[t] ? 2 + all_mx[t] : all_16[t] ? 4 + all_16[t] : 1;
+                if (which == list) order.push_back(t);
+            }
+            std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cost[a] > cost[b]; });
+            double load[kBins] = {0};
+            for (int t : order) {
+                int best = 0;
+                for (int b = 1; b < kBins; ++b)
+                    if (load[b] < load[best]) best = b;
+                load[best] += cost[t];
+                for (size_t r = 0; r < per_tile; ++r) {
+                    WorkItem it;
+                    it.tile = (uint32_t)t;
+                    it.mi = (uint16_t)(r / mr);
+                    it.mj = (uint16_t)(r % mr);
+                    bins[best].push_back(it);
+                }
+            }
         }
-        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cost[a] > cost[b]; });
-        std::vector<int> bins[kBins];
-        double load[kBins] = {0};
-        for (int t : order) {
-            int best = 0;
-            for (int b = 1; b < kBins; ++b)
-                if (load[b] < load[best]) best = b;
-            bins[best].push_back(t);
-            load[best] += cost[t];
-        }
+        // launch order: the bins interleaved, workgroup p landing on XCD p mod 8
         std::vector<WorkItem> &items = c->items[list];
         items.clear();
-        items.reserve(order.size() * per_tile);
         size_t pos[kBins] = {0};
         bool any = true;
         while (any) {
             any = false;
             for (int b = 0; b < kBins; ++b) {
-                if (pos[b] >= bins[b].size() * per_tile) continue;
+                if (pos[b] >= bins[b].size()) continue;
                 any = true;
-                const size_t k = pos[b]++;
-                WorkItem it;
-                it.tile = (uint32_t)bins[b][k / per_tile];
-                const size_t r = k % per_tile;
-                it.mi = (uint16_t)(r / mr);
-                it.mj = (uint16_t)(r % mr);
-                items.push_back(it);
+                items.push_back(bins[b][pos[b]++]);
             }
         }
     }
