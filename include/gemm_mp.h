@@ -50,8 +50,8 @@
  * indices, row by row, tile_nb^2/32 bytes; scale = 2^(floor(log2 max|x|) - 8) of its block,
  * elements rounded once and saturating; no tile scale.  Where every product of a C tile is
  * MXFP8 x MXFP8 (C tile not FP64, tile_nb a multiple of 256) the tile runs on the block-scaled
- * matrix instruction; any other product with an MXFP8 operand reads widened copies of the MXFP8
- * tiles from the sender-side workspace: see gemm_mp_run.  MXFP4 tiles (code 6)
+ * matrix instruction; under any other product an MXFP8 tile is widened by the receiving
+ * workgroup (element times block scale): see gemm_mp_run.  MXFP4 tiles (code 6)
  * are the same with e2m1 elements (magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6; scale
  * 2^(floor(log2 max|x|) - 2)): tile_nb^2/2 element bytes, two elements per byte with the lower
  * reduction index in the low four bits, then the tile_nb^2/32 scale bytes; block-scaled
@@ -231,16 +231,12 @@ int gemm_mp_prepare(gemm_mp_ctx *ctx, gemm_mp_stream stream);
  * environment variable GEMM_MP_SERIAL_LAUNCHES=1 at gemm_mp_create they stay on `stream`, one
  * after the other; C is the same either way.
  * ESTATE unless A and B are packed, C's map and buffer are set, and (beta != 0) C is packed.
- * BF16 tiles: the kernels take BF16 data only as an operand of a BF16 product (whose other
- * operand is BF16, or FP8 converted on the way like under an FP16 product); a BF16 tile under
- * an FP32 / FP64 product is read as the widened copy in the sender-side workspace, and the call
- * is ESTATE until gemm_mp_convert_tiles has filled it.
- * MXFP8 / MXFP4 tiles: a C tile whose products are all MXFP8 x MXFP8 or all MXFP4 x MXFP4 (not an
- * FP64 tile, tile_nb a multiple of 256 resp. 512) needs nothing; any other product with such an
- * operand is computed from the exact FP32 / FP64 copies of those tiles in the sender-side
- * workspace (a product of two block-scaled tiles then as exact FP32 products with FP32
- * accumulation, which is what it is), and the call is ESTATE until gemm_mp_convert_tiles has
- * filled it. */
+ * BF16 / MXFP8 / MXFP4 tiles under an FP32 or FP64 product are widened on the receiving side like
+ * the paper's formats (a BF16 number is the upper half of an FP32 word; a block-scaled element
+ * times its block's scale is exact in FP32).  A C tile whose products are all MXFP8 x MXFP8 or all
+ * MXFP4 x MXFP4 (not an FP64 tile, tile_nb a multiple of 256 resp. 512) runs on the block-scaled
+ * matrix instruction; elsewhere a product of two block-scaled tiles is computed as exact FP32
+ * products with FP32 accumulation, which is what it is. */
 int gemm_mp_run(gemm_mp_ctx *ctx, double alpha, double beta, gemm_mp_stream stream);
 
 /* Run without allocating [async].  For callers that cannot allocate device memory at the point

@@ -88,8 +88,6 @@ struct gemm_mp_ctx {
     bool mixed32 = false;             // list [1] holds an FP16 / BF16 product with an operand stored in FP8
     bool mixed64 = false;             // the same for list [0]
     bool has_bf16 = false;            // A or B has a BF16 tile
-    bool mx_needs_copies = false;     // an MXFP8 tile takes part in a product outside the block-scaled kernel
-    bool bf16_needs_copies = false;   // ... that meets another precision in some product (see gemm_mp_run)
     bool kernel_ready = false;
     // sender-side conversion: per tile of A / B and product precision q, the offset of the copy
     // in precision q inside the workspace (kNoCopy: no task needs one)
@@ -357,23 +355,21 @@ void build_schedule(gemm_mp_ctx *c)
 
     // A C tile accumulated in FP32 whose every product multiplies two MXFP8 tiles goes to the
     // block-scaled instance of the 256 x 256 kernel.  Every other product with an MXFP8 operand
-    // is run by the 128 x 128 kernels on widened copies of the MXFP8 tiles (sender-side workspace):
+    // is run by the 128 x 128 kernels, which widen the block-scaled tiles on the receiving side
+    // (element times block scale, exact) or read the sender-side copies where there are any:
     // at FP32 where both operands are MXFP8 (exact products, FP32 accumulation: what an MXFP8
     // product is), at the product's own FP32 / FP64 otherwise.  c->q then holds the precision
     // the kernels work at, the statistics keep the product's nominal one.
     std::vector<uint8_t> all_mx((size_t)MT * NT, 0);         // 1: all MXFP8 x MXFP8, 2: all MXFP4 x MXFP4 (tile size a multiple of 512)
-    c->mx_needs_copies = false;
     for (int I = 0; I < MT; ++I)
         for (int J = 0; J < NT; ++J) {
             const bool fits = C.map[I * NT + J] != GEMM_MP_FP64 && KT > 0;
-            bool all8 = fits && c->nb % kMacroFp8 == 0, all4 = fits && c->nb % (2 * kMacroFp8) == 0, any = false;
+            bool all8 = fits && c->nb % kMacroFp8 == 0, all4 = fits && c->nb % (2 * kMacroFp8) == 0;
             for (int L = 0; L < KT; ++L) {
-                any |= is_block_scaled(A.map[I * KT + L]) || is_block_scaled(B.map[L * NT + J]);
                 all8 &= c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_MXFP8;
                 all4 &= c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_MXFP4;
             }
             all_mx[(size_t)I * NT + J] = all8 ? 1 : all4 ? 2 : 0;
-            c->mx_needs_copies |= any && !all8 && !all4;
             if (!all8 && !all4)
                 for (int L = 0; L < KT; ++L) {
                     uint8_t &q = c->q[((size_t)I * NT + J) * KT + L];
@@ -385,7 +381,6 @@ void build_schedule(gemm_mp_ctx *c)
     // would live in the workspace (256-byte aligned, A's copies first).
     c->conv_off[0].assign((size_t)MT * KT * kConvSlots, kNoCopy);
     c->conv_off[1].assign((size_t)KT * NT * kConvSlots, kNoCopy);
-    c->bf16_needs_copies = false;
     for (int I = 0; I < MT; ++I)
         for (int J = 0; J < NT; ++J)
             for (int L = 0; L < KT; ++L) {
@@ -394,8 +389,6 @@ void build_schedule(gemm_mp_ctx *c)
                 if (is_block_scaled(q)) continue;                             // block-scaled kernel: no copies
                 if (pa != q) c->conv_off[0][((size_t)I * KT + L) * kConvSlots + q] = 0;
                 if (pb != q) c->conv_off[1][((size_t)L * NT + J) * kConvSlots + q] = 0;
-                // the GEMM kernels take BF16 data only as operands of a BF16 product
-                c->bf16_needs_copies |= (pa == GEMM_MP_BF16 && q != GEMM_MP_BF16) || (pb == GEMM_MP_BF16 && q != GEMM_MP_BF16);
             }
     c->conv_bytes = 0;
     c->conv_tiles = 0;
@@ -886,7 +879,6 @@ int gemm_mp_run(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream stream
     int rc;
     if ((rc = run_ready(c, alpha, beta))) return rc;
     if (!c->sched_current) build_schedule(c);
-    if ((c->bf16_needs_copies || c->mx_needs_copies) && !c->conv_active) return GEMM_MP_ESTATE;
     hipStream_t s = (hipStream_t)stream;
     // what gemm_mp_prepare does, unless it has been done for these maps: only copies queued on s
     if ((rc = prepare_schedule(c, s))) return rc;
@@ -906,7 +898,6 @@ int gemm_mp_run_static(gemm_mp_ctx *c, double alpha, double beta, gemm_mp_stream
     if ((rc = run_ready(c, alpha, beta))) return rc;
     // everything that would allocate, build or copy must have happened in gemm_mp_prepare
     if (!c->sched_current || !c->sched_uploaded || !c->mat[2].tables_current || !c->kernel_ready) return GEMM_MP_ESTATE;
-    if ((c->bf16_needs_copies || c->mx_needs_copies) && !c->conv_active) return GEMM_MP_ESTATE;
     ProductDesc *prod = nullptr;
     if ((rc = static_scratch(&prod))) return rc;
     return run_on(c, alpha, beta, (hipStream_t)stream, prod);

@@ -92,7 +92,12 @@ struct Operand {
     int bytes;                     // formed from them at each load (scalar moves only)
     int p, e;                      // stored precision, scale exponent
     int voff;                      // this thread's first segment in chunk 0, aligned down to 16 B
-    int sub;                       // offset of that segment's source inside the 16 loaded bytes
+    int sub;                       // offset of that segment's source inside the 16 loaded bytes; from bit 8 up the
+                                   // variant of the format that p does not tell (kept in this per-lane register
+                                   // because scalar registers are the scarce ones): 1 = p is Q16 and the tile holds
+                                   // BF16 numbers (no scale), 2 / 3 = p is Q8 and the tile is MXFP8 / MXFP4 (one
+                                   // scale byte per block of 32 behind the elements).  Only the loop for such
+                                   // operands under FP64 / FP32 products (product_loop_widening) ever sees these bits.
 };
 
 // One tile product A(I,L)*B(L,J): q is its precision (-1: there is none).
@@ -212,8 +217,18 @@ __device__ __forceinline__ bool is_ring(const Product &pr, const Geometry &G)
         return G.ring && (pr.q == Q16 || pr.q == Q8) && pr.a.p == pr.q && pr.b.p == pr.q;
     }
 }
+// An FP64 / FP32 product one of whose operands is a BF16, MXFP8 or MXFP4 tile: such tiles are
+// widened on the receiving side by a loop of their own (product_loop_widening), which also stages
+// its own first chunk, so that the staging code of every other product stays what it is.
+__device__ __forceinline__ bool is_widening(const Product &pr)
+{
+    return pr.q >= 0 && pr.q <= Q32 && __builtin_amdgcn_readfirstlane((pr.a.sub | pr.b.sub) >> 8) != 0;
+}
 template <bool MIXED>
-__device__ __forceinline__ bool wants_first_chunk(const Product &pr, const Geometry &G) { return pr.q >= 0 && !is_ring<MIXED>(pr, G); }
+__device__ __forceinline__ bool wants_first_chunk(const Product &pr, const Geometry &G)
+{
+    return pr.q >= 0 && !is_ring<MIXED>(pr, G) && !is_widening(pr);
+}
 
 
 __device__ __forceinline__ int chunk_elems(int q) { return kRowBytes >> (3 - q); }   // 16, 32, 64, 128
@@ -484,18 +499,20 @@ __device__ __forceinline__ const char *uni(const char *p)
 
 // Descriptor of one operand tile from its table entries; `row0` is the first tile row this
 // workgroup reads.
-__device__ __forceinline__ Operand make_operand(const char *base, int p, int e, int q, int row0, const Geometry &G, int nb)
+__device__ __forceinline__ Operand make_operand(const char *base, int p, int e, int q, int row0, const Geometry &G, int nb, int fmt)
 {
     Operand o;
     o.base = base;
     o.p = p;
     o.e = e;
     const int shift = 3 - o.p;                                   // log2 of the element size
-    o.bytes = (nb * nb) << shift;
     const int n_q = 2 << q;                                      // elements per 16-byte converted segment
-    const int boff = ((row0 + G.seg_row) * nb + G.seg_part * n_q) << shift;
+    const int eidx = (row0 + G.seg_row) * nb + G.seg_part * n_q; // this thread's first element
+    const int elems = fmt == 3 ? (nb * nb) >> 1 : (nb * nb) << shift;   // bytes of the tile's elements (MXFP4: two to a byte)
+    o.bytes = fmt >= 2 ? elems + ((nb * nb) >> 5) : elems;       // block-scaled: one scale byte per 32 elements behind them
+    const int boff = fmt == 3 ? eidx >> 1 : eidx << shift;
     o.voff = boff & ~15;
-    o.sub = boff & 15;
+    o.sub = (boff & 15) | (fmt << 8);
     return o;
 }
 
@@ -507,10 +524,16 @@ __device__ __forceinline__ Product make_product(const u32x4 lo, const u32x4 hi, 
     Product pr;
     const uint64_t pta = (uint64_t)lo.x | ((uint64_t)lo.y << 32), ptb = (uint64_t)lo.z | ((uint64_t)lo.w << 32);
     const int ea = (int)hi.x, eb = (int)hi.y;
-    const int pa = (int)(hi.z & 0xffu), pb = (int)((hi.z >> 8) & 0xffu), q = (int)((hi.z >> 16) & 0xffu);
+    const int ca = (int)(hi.z & 0xffu), cb = (int)((hi.z >> 8) & 0xffu), q = (int)((hi.z >> 16) & 0xffu);
+    // bits 24 / 25: the A / B tile holds BF16 numbers (written as FP16 in the codes: the same element
+    // size); codes 5 / 6: an MXFP8 / MXFP4 tile under an FP32 / FP64 product, read like an FP8 tile
+    // whose scale comes per block
+    const int fa = ca >= GEMM_MP_MXFP8 ? ca - GEMM_MP_MXFP8 + 2 : (int)((hi.z >> 24) & 1u);
+    const int fb = cb >= GEMM_MP_MXFP8 ? cb - GEMM_MP_MXFP8 + 2 : (int)((hi.z >> 25) & 1u);
+    const int pa = ca >= GEMM_MP_MXFP8 ? (int)Q8 : ca, pb = cb >= GEMM_MP_MXFP8 ? (int)Q8 : cb;
     pr.q = q;
-    pr.a = make_operand((const char *)(uintptr_t)pta, pa, ea, q, R.arow0, G, R.nb);
-    pr.b = make_operand((const char *)(uintptr_t)ptb, pb, eb, q, R.brow0, G, R.nb);
+    pr.a = make_operand((const char *)(uintptr_t)pta, pa, ea, q, R.arow0, G, R.nb, fa);
+    pr.b = make_operand((const char *)(uintptr_t)ptb, pb, eb, q, R.brow0, G, R.nb, fb);
     return pr;
 }
 __device__ __forceinline__ Product open_product(int I, int J, int tileC, int L, const Geometry &G, const Region &R)
@@ -768,6 +791,123 @@ __device__ __forceinline__ void steady_chunks(Acc (&acc)[4][4], u32x4 (&fr)[2][8
         pipelined_chunk<Q, BASE, 0, 0, PA, PB>(acc, fr, r, cp, c, lds, 0, F, G, nb, sa, sb);
         stage = 1;
     }
+}
+
+// ---- FP64 / FP32 products with a BF16, MXFP8 or MXFP4 operand ---------------------------------
+// Receiver-side conversion of the formats beyond the paper's: a BF16 number is the upper half of
+// an FP32 word, a block-scaled element times the scale 2^(code - 127) of its block of 32 is exact
+// in FP32 (and FP64).  These products take a plain loop of their own: per chunk, fetch the eight
+// pieces (and, for a block-scaled tile, the scale byte of each segment's block: the blocks run
+// along the rows of the packed tile, one byte each, row by row behind the elements), convert, store
+// to LDS stage 0, and run the chunk's matrix instructions; nothing is overlapped.  The fast roads
+// for such tiles are their own kernels (BF16 x BF16, MXFP8 x MXFP8, MXFP4 x MXFP4 products) and
+// sender-side copies; this one keeps every tile convertible by its consumer.
+__device__ __forceinline__ float fp4_value(uint32_t code)      // an e2m1 code: sign, two exponent bits, one fraction bit
+{
+    const int ef = (int)(code >> 1) & 3, mf = (int)code & 1;
+    const float mag = ef ? ldexpf(1.0f + 0.5f * (float)mf, ef - 1) : 0.5f * (float)mf;
+    return (code & 8u) ? -mag : mag;
+}
+// Piece i = 2 * (row block) + (0: A, 1: B) of chunk c: the aligned 16 bytes around the source, the
+// second 16 for the one down-cast, the scale byte (into r.hi.x) for a block-scaled tile.
+__device__ __forceinline__ void load_piece_widening(Raw &r, const Product &pr, int nb, int c, int i)
+{
+    const int eoff = c * chunk_elems(pr.q) + (i >> 1) * 32 * nb;
+    const Operand &o = (i & 1) ? pr.b : pr.a;
+    const int fmt = __builtin_amdgcn_readfirstlane(o.sub >> 8);
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)o.base, 0, o.bytes, 0x00020000);
+    r.lo = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o.voff, fmt == 3 ? eoff >> 1 : eoff << (3 - o.p), 0);
+    if (pr.q == Q32 && o.p == Q64) {
+        r.hi = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o.voff + 16, eoff << (3 - o.p), 0);
+    } else if (fmt >= 2) {
+        // the element index comes back from the byte offset of the segment's source
+        const int boff = o.voff + (o.sub & 15);
+        const int svoff = fmt == 3 ? ((nb * nb) >> 1) + (boff >> 4) : nb * nb + (boff >> 5);
+        r.hi.x = (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rsrc, svoff, eoff >> 5, 0);
+    }
+}
+template <int Q>
+__device__ __forceinline__ u32x4 convert_widening(const Raw &r, const Operand &op)
+{
+    static_assert(Q == Q64 || Q == Q32, "FP64 / FP32 products only");
+    const int fmt = __builtin_amdgcn_readfirstlane(op.sub >> 8), sub = op.sub & 15;
+    if (fmt == 0) return convert<Q>(r, op.p, op.e, sub);
+    u32x4 o;
+    if (fmt == 1) {                                              // BF16: no scale
+        if constexpr (Q == Q32) {
+            const u32x2 w = pick_pair(r.lo, sub >> 3);
+            o = u32x4{w.x << 16, w.x & 0xffff0000u, w.y << 16, w.y & 0xffff0000u};
+        } else {
+            const uint32_t w = pick_word(r.lo, sub >> 2);
+            const u32x2 a = dbits((double)__uint_as_float(w << 16)), b = dbits((double)__uint_as_float(w & 0xffff0000u));
+            o = u32x4{a.x, a.y, b.x, b.y};
+        }
+        return o;
+    }
+    const int e = (int)(r.hi.x & 0xffu) - 127;                   // this segment's block scale
+    if (fmt == 2) return convert<Q>(r, Q8, e, sub);              // e4m3 elements: the FP8 road with the block's exponent
+    // MXFP4: four (FP32) or two (FP64) four-bit codes starting at byte `sub` of the loaded 16
+    const uint32_t w = pick_word(r.lo, sub >> 2) >> ((sub & 3) * 8);
+    if constexpr (Q == Q32) {
+        o = u32x4{__float_as_uint(ldexpf(fp4_value(w & 15u), e)), __float_as_uint(ldexpf(fp4_value((w >> 4) & 15u), e)),
+                  __float_as_uint(ldexpf(fp4_value((w >> 8) & 15u), e)), __float_as_uint(ldexpf(fp4_value((w >> 12) & 15u), e))};
+    } else {
+        const u32x2 a = dbits(ldexp((double)fp4_value(w & 15u), e)), b = dbits(ldexp((double)fp4_value((w >> 4) & 15u), e));
+        o = u32x4{a.x, a.y, b.x, b.y};
+    }
+    return o;
+}
+template <int Q, int BASE, typename Acc, int... U>
+__device__ __forceinline__ void chunk_mfmas(Acc (&acc)[4][4], const u32x4 (&fr)[2][8], std::integer_sequence<int, U...>)
+{
+    (mfma_half<Q, BASE, U>(acc, fr), ...);
+}
+// All chunks of such a product; returns the next product, whose first chunk (if it wants one) is
+// staged in LDS stage 0 on exit, as after a run of ring products.
+template <int Q, int BASE, bool MIXED, typename Acc>
+__device__ __forceinline__ Product product_loop_widening(Acc (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
+                                                         const Geometry &G0, const Region &R, bool &raw)
+{
+    const Geometry G = fresh(G0);
+    const HiFrag F = hi_frag<Q>(lds, G);
+    const int n = R.nb / (kRowBytes >> (3 - Q));
+    const Product next = open_product(W.I, W.J, W.tileC, Lnext, G, R);
+    Product cp = cur;
+    cp.q = Q;
+#pragma unroll 1
+    for (int c = 0; c < n; ++c) {
+        Raw r[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) load_piece_widening(r[i], cp, R.nb, c, i);
+        __syncthreads();                               // every wave has read the chunk before from the stage
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            char *dst = lds + G.wsw + (i >> 1) * (32 * kRowBytes) + (i & 1) * kOperandStage;
+            *(u32x4 *)dst = convert_widening<Q>(r[i], (i & 1) ? cp.b : cp.a);
+        }
+        __syncthreads();
+        u32x4 fr[2][8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            fr[0][t] = read_frag(F, 0, 0, t);
+            fr[1][t] = read_frag(F, 0, 1, t);
+        }
+        acc_fence<BASE>(acc);
+        chunk_mfmas<Q, BASE>(acc, fr, std::make_integer_sequence<int, 64>{});
+        acc_fence<BASE>(acc);
+    }
+    __syncthreads();
+    if (wants_first_chunk<MIXED>(next, G)) {
+        Raw xa[4], xb[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) load_pair(xa[j], xb[j], next, R.nb, 0, j);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) store_pair_any(xa[j], xb[j], next, G, lds, j);
+        __syncthreads();
+    }
+    stage = 0;
+    raw = false;
+    return next;
 }
 
 // All chunks of one FP64 / FP32 tile product; returns the next product.  On exit that one's
@@ -1503,8 +1643,10 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
             ++L;
             continue;
         }
+        const bool widening = is_widening(cur);
         if (q == QT) {
-            next = product_loop_pipelined<QT, (QT == Q32 ? 192 : -1), QT == Q32, MIXED>(s, cur, W, L + 1, lds, stage, G, R, hand, raw);
+            if (widening) next = product_loop_widening<QT, (QT == Q32 ? 192 : -1), MIXED>(s, cur, W, L + 1, lds, stage, G, R, raw);
+            else next = product_loop_pipelined<QT, (QT == Q32 ? 192 : -1), QT == Q32, MIXED>(s, cur, W, L + 1, lds, stage, G, R, hand, raw);
         } else {
             if constexpr (QT == Q64) {
                 // an FP32 product of an FP64 C tile: its FP32 accumulator lives only for that product
@@ -1513,7 +1655,8 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
-                next = product_loop_pipelined<Q32, -1, false, MIXED>(t, cur, W, L + 1, lds, stage, G, R, hand, raw);
+                if (widening) next = product_loop_widening<Q32, -1, MIXED>(t, cur, W, L + 1, lds, stage, G, R, raw);
+                else next = product_loop_pipelined<Q32, -1, false, MIXED>(t, cur, W, L + 1, lds, stage, G, R, hand, raw);
                 fold(s, t, 0);
             } else {
                 next = cur;                        // not reachable: the host never schedules FP64 products on FP32 tiles
