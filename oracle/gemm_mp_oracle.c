@@ -53,8 +53,10 @@
  * elements with one power-of-two scale per block of 32 consecutive reduction
  * indices (the block-scaled format of the OCP microscaling specification)
  * instead of one per tile; 6 is MXFP4, the same with e2m1 elements (magnitudes
- * 0, 0.5, 1, 1.5, 2, 3, 4, 6). */
-enum { P_FP64 = 0, P_FP32 = 1, P_FP16 = 2, P_FP8 = 3, P_BF16 = 4, P_MXFP8 = 5, P_MXFP4 = 6 };
+ * 0, 0.5, 1, 1.5, 2, 3, 4, 6); 7 is MXFP6, the same with e2m3 elements (two
+ * exponent and three fraction bits: multiples of 1/8 below 2, of 1/4 below 4,
+ * of 1/2 up to 7.5). */
+enum { P_FP64 = 0, P_FP32 = 1, P_FP16 = 2, P_FP8 = 3, P_BF16 = 4, P_MXFP8 = 5, P_MXFP4 = 6, P_MXFP6 = 7 };
 
 /* Which product-precision reading is applied (see orc_product_precision). */
 enum { POLICY_OPERAND = 0, POLICY_C_TILE = 1 };
@@ -234,7 +236,50 @@ int32_t orc_mx4_block(const double *x, int64_t stride, double *y, int64_t ystrid
     return s;
 }
 
+/* FP6 e2m3: 3 fraction bits, emin 0 (bias 1: the smallest normal is 1, the subnormals are the
+ * multiples of 1/8 below it), max finite 7.5, no infinity or NaN codes: overflow and infinities
+ * saturate to +-7.5; a NaN has no code and is stored as 0. */
+double orc_round_fp6(double x)
+{
+    if (isnan(x)) return 0.0;
+    if (isinf(x)) return copysign(7.5, x);
+    double r = round_to_format(x, 3, 0);
+    if (fabs(r) > 7.5) r = copysign(7.5, x);
+    return r;
+}
+/* sign, two exponent bits, three fraction bits */
+uint8_t orc_fp6_bits(double y)
+{
+    uint8_t s = signbit(y) ? 32u : 0u;
+    double a = fabs(y);
+    if (a < 1.0) return (uint8_t)(s | (uint8_t)(a * 8.0));          /* subnormals and zero: a = m / 8 */
+    int e = ilogb(a);
+    return (uint8_t)(s | ((uint8_t)(e + 1) << 3) | (uint8_t)((ldexp(a, -e) - 1.0) * 8.0));
+}
+/* MXFP6: as orc_mx_block with e2m3 elements; 2 = exponent of the largest e2m3 binade. */
+int32_t orc_mx6_block(const double *x, int64_t stride, double *y, int64_t ystride)
+{
+    double mx = 0.0;
+    for (int k = 0; k < 32; ++k) { double a = fabs(x[k * stride]); if (a > mx) mx = a; }
+    int s = 0;
+    if (mx != 0.0 && !isinf(mx)) {
+        s = ilogb(mx) - 2;
+        if (s < -127) s = -127;
+        if (s > 127) s = 127;
+    }
+    for (int k = 0; k < 32; ++k) y[k * ystride] = orc_round_fp6(ldexp(x[k * stride], -s));
+    return s;
+}
+
 /* Vector forms for the tests. */
+void orc_mx6_blocks_array(const double *x, int64_t nblocks, double *y, uint8_t *codes, uint8_t *scale_codes)
+{
+    for (int64_t b = 0; b < nblocks; ++b) {
+        int32_t s = orc_mx6_block(x + 32 * b, 1, y + 32 * b, 1);
+        scale_codes[b] = (uint8_t)(s + 127);
+        for (int k = 0; k < 32; ++k) codes[32 * b + k] = orc_fp6_bits(y[32 * b + k]);
+    }
+}
 void orc_mx4_blocks_array(const double *x, int64_t nblocks, double *y, uint8_t *codes, uint8_t *scale_codes)
 {
     for (int64_t b = 0; b < nblocks; ++b) {
@@ -330,6 +375,7 @@ static double unit_roundoff(int p)
     case P_BF16: return ldexp(1.0, -8);
     case P_MXFP8: return ldexp(1.0, -4);
     case P_MXFP4: return ldexp(1.0, -2);
+    case P_MXFP6: return ldexp(1.0, -4);
     default:     return ldexp(1.0, -4);      /* e4m3: 3 fraction bits */
     }
 }
@@ -401,14 +447,16 @@ void orc_store_tiles_axis(const double *X, int64_t ld, int64_t rows, int64_t col
             int p = map[I * CT + J];
             int32_t e = orc_scale_exponent(maxabs[I * CT + J], p);
             exps[I * CT + J] = e;
-            if (p == P_MXFP8 || p == P_MXFP4) {
+            if (p == P_MXFP8 || p == P_MXFP4 || p == P_MXFP6) {
                 /* the blocks run along the reduction index; Y receives the values the stored
                  * elements stand for, element * 2^s, which are exact in FP64 (and in FP32) */
                 double yb[32];
                 for (int32_t u = 0; u < nb; ++u)
                     for (int32_t k0 = 0; k0 < nb; k0 += 32) {
                         const double *x0 = mx_axis ? X + (I * nb + k0) * ld + J * nb + u : X + (I * nb + u) * ld + J * nb + k0;
-                        int32_t s = p == P_MXFP8 ? orc_mx_block(x0, mx_axis ? ld : 1, yb, 1) : orc_mx4_block(x0, mx_axis ? ld : 1, yb, 1);
+                        int32_t s = p == P_MXFP8 ? orc_mx_block(x0, mx_axis ? ld : 1, yb, 1)
+                                  : p == P_MXFP4 ? orc_mx4_block(x0, mx_axis ? ld : 1, yb, 1)
+                                                 : orc_mx6_block(x0, mx_axis ? ld : 1, yb, 1);
                         for (int k = 0; k < 32; ++k) {
                             double *y0 = mx_axis ? Y + (I * nb + k0 + k) * ldy + J * nb + u : Y + (I * nb + u) * ldy + J * nb + k0 + k;
                             *y0 = ldexp(yb[k], s);
@@ -453,8 +501,9 @@ static int holds_both(int pA, int pB)
 {
     if (pA == P_MXFP8 && pB == P_MXFP8) return P_MXFP8;
     if (pA == P_MXFP4 && pB == P_MXFP4) return P_MXFP4;
-    if (pA == P_MXFP8 || pA == P_MXFP4) pA = P_FP32;     /* block-scaled numbers are FP32 numbers, and of */
-    if (pB == P_MXFP8 || pB == P_MXFP4) pB = P_FP32;     /* no smaller format here                        */
+    if (pA == P_MXFP6 && pB == P_MXFP6) return P_MXFP6;
+    if (pA >= P_MXFP8) pA = P_FP32;                      /* block-scaled numbers are FP32 numbers, and of */
+    if (pB >= P_MXFP8) pB = P_FP32;                      /* no smaller format here                        */
     if (pA == P_FP64 || pB == P_FP64) return P_FP64;
     if (pA == P_FP32 || pB == P_FP32) return P_FP32;
     int h = (pA == P_FP16) || (pB == P_FP16), b = (pA == P_BF16) || (pB == P_BF16);
@@ -535,7 +584,7 @@ int32_t orc_gemm_jobs(int64_t M, int64_t N, int64_t K, int32_t nb,
             c1 > nb || c0 > c1)
             return -1;
         int pC = mapC[I * NT + J];
-        if (pC < P_FP64 || pC > P_MXFP4) return -1;
+        if (pC < P_FP64 || pC > P_MXFP6) return -1;
         int T = pC == P_FP64 ? P_FP64 : P_FP32;       /* accumulate type: FP64 or FP32 */
         int64_t nr = r1 - r0, nc = c1 - c0;
         if (nr == 0 || nc == 0) continue;
@@ -558,7 +607,7 @@ int32_t orc_gemm_jobs(int64_t M, int64_t N, int64_t K, int32_t nb,
             int ea = eA[I * KT + L], eb = eB[L * NT + J];
             /* an MXFP8 product multiplies the values its operands stand for (Ay, By hold them,
              * exponents 0) exactly and accumulates in FP32, like the other low products */
-            int esum = (q == P_FP16 || q == P_FP8 || q == P_BF16 || q == P_MXFP8 || q == P_MXFP4) ? ea + eb : 0;
+            int esum = (q == P_FP16 || q == P_FP8 || q == P_BF16 || q == P_MXFP8 || q == P_MXFP4 || q == P_MXFP6) ? ea + eb : 0;
 
             /* receiver-side conversion of the B tile columns this job needs */
 #pragma omp parallel for schedule(static)

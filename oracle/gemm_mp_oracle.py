@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gemm_mp_oracle.c")
 _LIB = os.path.join(_HERE, "libgemm_mp_oracle.so")
 
-FP64, FP32, FP16, FP8, BF16, MXFP8, MXFP4 = 0, 1, 2, 3, 4, 5, 6
+FP64, FP32, FP16, FP8, BF16, MXFP8, MXFP4, MXFP6 = 0, 1, 2, 3, 4, 5, 6, 7
 POLICY_OPERAND, POLICY_C_TILE = 0, 1
 ALL_PRECISIONS_MASK = 0xF          # the four formats of the configurations
 ALL_FORMATS_MASK = 0x1F            # ... and BF16
@@ -45,6 +45,7 @@ def lib():
         _lib.orc_round_bf16_array.argtypes = [P, c_i64, P, P]
         _lib.orc_mx_blocks_array.argtypes = [P, c_i64, P, P, P]
         _lib.orc_mx4_blocks_array.argtypes = [P, c_i64, P, P, P]
+        _lib.orc_mx6_blocks_array.argtypes = [P, c_i64, P, P, P]
         _lib.orc_store_tiles_axis.argtypes = [P, c_i64, c_i64, c_i64, c_i32, P, P, P, c_i64, P, c_i32]
         _lib.orc_bf16_value.restype = c_dbl
         _lib.orc_bf16_value.argtypes = [ctypes.c_uint16]
@@ -122,6 +123,18 @@ def mx4_blocks(x):
     codes = np.empty(x.shape, dtype=np.uint8)
     scales = np.empty(x.size // 32, dtype=np.uint8)
     lib().orc_mx4_blocks_array(_p(x), x.size // 32, _p(y), _p(codes), _p(scales))
+    return y, codes, scales
+
+
+def mx6_blocks(x):
+    """MXFP6 (e2m3) quantisation of consecutive blocks of 32 numbers.  Returns (element numbers as
+    FP64, 6-bit element codes one per byte, scale codes = s + 127)."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    assert x.size % 32 == 0
+    y = np.empty_like(x)
+    codes = np.empty(x.shape, dtype=np.uint8)
+    scales = np.empty(x.size // 32, dtype=np.uint8)
+    lib().orc_mx6_blocks_array(_p(x), x.size // 32, _p(y), _p(codes), _p(scales))
     return y, codes, scales
 
 

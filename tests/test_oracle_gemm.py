@@ -11,7 +11,7 @@ import pytest
 from oracle import gemm_mp_oracle as orc
 from tests.exact import fma32, fma64
 
-FP64, FP32, FP16, FP8, BF16, MXFP8, MXFP4 = 0, 1, 2, 3, 4, 5, 6
+FP64, FP32, FP16, FP8, BF16, MXFP8, MXFP4, MXFP6 = 0, 1, 2, 3, 4, 5, 6, 7
 U = {FP64: 2.0 ** -53, FP32: 2.0 ** -24, FP16: 2.0 ** -11, FP8: 2.0 ** -4, BF16: 2.0 ** -8}
 
 
@@ -404,15 +404,15 @@ def test_c_tiles_stored_in_block_scaled_formats_are_fp32_tiles_quantised_along_t
     """A block-scaled C tile is an FP32 tile until it is stored: the job returns bit for bit what
     the same job returns for an FP32 tile, and storing it quantises each block of 32 along a row
     by that block's own maximum: element error at most half a step of the block's top binade
-    (2^-4 / 2^-2 of the block maximum's power of two for e4m3 / e2m1), except above the element
-    format's largest number (1.75 / 1.5 times that power of two), where it saturates."""
+    (2^-4 / 2^-2 / 2^-4 of the block maximum's power of two for e4m3 / e2m1 / e2m3), except above the
+    element format's largest number (1.75 / 1.5 / 1.875 times that power of two), where it saturates."""
     rng = np.random.default_rng(79)
     nb, MT, NT, KT = 32, 2, 2, 2
     A = rng.standard_normal((MT * nb, KT * nb))
     B = rng.standard_normal((KT * nb, NT * nb))
     mA = rng.integers(0, 4, (MT, KT)).astype(np.uint16)
     mB = rng.integers(0, 4, (KT, NT)).astype(np.uint16)
-    mC = np.array([[MXFP8, MXFP4], [MXFP4, MXFP8]], dtype=np.uint16)
+    mC = np.array([[MXFP8, MXFP4], [MXFP6, MXFP8]], dtype=np.uint16)
     pre = _run(nb, A, mA, B, mB, None, mC, 1.5, 0.0)
     assert np.array_equal(pre, _run(nb, A, mA, B, mB, None, np.full((MT, NT), FP32, dtype=np.uint16), 1.5, 0.0))
     Y, e = _store(pre, nb, mC)
@@ -421,7 +421,7 @@ def test_c_tiles_stored_in_block_scaled_formats_are_fp32_tiles_quantised_along_t
     seen_beyond = False
     for I in range(MT):
         for J in range(NT):
-            half_step, largest = (2.0 ** -4, 1.75) if mC[I, J] == MXFP8 else (2.0 ** -2, 1.5)
+            half_step, largest = {MXFP8: (2.0 ** -4, 1.75), MXFP4: (2.0 ** -2, 1.5), MXFP6: (2.0 ** -4, 1.875)}[int(mC[I, J])]
             for r in range(nb):
                 row = pre[I * nb + r, J * nb:(J + 1) * nb]             # one block: nb = 32
                 top = 2.0 ** np.floor(np.log2(np.abs(row).max()))
@@ -512,18 +512,22 @@ def test_mxfp8_tiles_follow_the_reduction_index_and_give_exact_integer_products(
     assert rel[np.abs(X) > np.abs(X).max() * 2.0 ** -60].max() <= 1.0 and np.median(rel) < 2.0 ** -4
     for pA, pB, pC, want in ((MXFP8, MXFP8, FP32, MXFP8), (MXFP8, MXFP8, FP64, MXFP8), (MXFP8, FP8, FP32, FP32), (MXFP8, FP16, FP64, FP32),
                              (FP64, MXFP8, FP64, FP64), (FP64, MXFP8, FP32, FP32), (BF16, MXFP8, FP32, FP32),
-                             (MXFP4, MXFP4, FP32, MXFP4), (MXFP4, MXFP8, FP32, FP32), (MXFP4, FP64, FP64, FP64), (FP8, MXFP4, FP64, FP32)):
+                             (MXFP4, MXFP4, FP32, MXFP4), (MXFP4, MXFP8, FP32, FP32), (MXFP4, FP64, FP64, FP64), (FP8, MXFP4, FP64, FP32),
+                             (MXFP6, MXFP6, FP32, MXFP6), (MXFP6, MXFP6, FP64, MXFP6), (MXFP6, MXFP4, FP32, FP32), (MXFP8, MXFP6, FP64, FP32),
+                             (MXFP6, FP64, FP64, FP64), (MXFP6, FP64, FP32, FP32), (FP16, MXFP6, FP64, FP32)):
         assert orc.product_precision(pA, pB, pC, orc.POLICY_OPERAND) == want
-    for trial in range(4):
+    for trial in range(5):
         A = rng.integers(-3, 4, (M, K)).astype(np.float64)
         B = rng.integers(-3, 4, (K, N)).astype(np.float64)
         C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
-        mA = rng.choice([FP64, FP32, FP16, FP8, BF16, MXFP8, MXFP4], (MT, KT)).astype(np.uint16)
-        mB = rng.choice([FP64, FP32, FP16, FP8, BF16, MXFP8, MXFP4], (KT, NT)).astype(np.uint16)
+        mA = rng.choice([FP64, FP32, FP16, FP8, BF16, MXFP8, MXFP4, MXFP6], (MT, KT)).astype(np.uint16)
+        mB = rng.choice([FP64, FP32, FP16, FP8, BF16, MXFP8, MXFP4, MXFP6], (KT, NT)).astype(np.uint16)
         if trial == 0:
             mA[:], mB[:] = MXFP8, MXFP8
         if trial == 1:
             mA[:], mB[:] = MXFP4, MXFP4
+        if trial == 2:
+            mA[:], mB[:] = MXFP6, MXFP6
         mC = rng.integers(0, 2, (MT, NT)).astype(np.uint16)
         Ay, eA = orc.store_tiles(A, nb, mA, mx_axis=0)
         By, eB = orc.store_tiles(B, nb, mB, mx_axis=1)

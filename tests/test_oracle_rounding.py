@@ -212,3 +212,49 @@ def test_mxfp4_blocks_scale_window_and_nearest_e2m1_elements():
     ints = rng.integers(-3, 4, (40, 32)).astype(np.float64)
     y, codes, scales = orc.mx4_blocks(ints)
     assert np.array_equal(np.ldexp(y, (scales.astype(np.int64) - 127)[:, None]), ints)
+
+
+def test_mxfp6_blocks_scale_window_and_nearest_e2m3_elements():
+    """MXFP6: e2m3 elements (code = sign, two exponent bits with bias 1, three fraction bits: the
+    32 magnitudes are the multiples of 1/8 below 2, of 1/4 from 2 to 4 and of 1/2 from 4 to 7.5,
+    written out here from the bit fields), scale 2^(floor(log2 max) - 2); every element is the grid
+    value nearest to x * 2^-s with ties to the even code and saturation at 7.5; the 6-bit code is
+    the index into the ascending grid plus 32 for a negative number; blocks of integers up
+    to 7 in magnitude come back exactly."""
+    grid = []
+    for code in range(32):
+        e, m = code >> 3, code & 7
+        grid.append(Fraction(m, 8) if e == 0 else (1 + Fraction(m, 8)) * 2 ** (e - 1))
+    assert grid == sorted(grid) and grid[8] == 1 and grid[-1] == Fraction(15, 2) and grid[1] == Fraction(1, 8)
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((300, 32)) * np.exp(rng.uniform(-40, 40, (300, 1))) * np.exp(rng.uniform(-4, 0, (300, 32)))
+    # ties of the grid at scale 1 (largest entry 5 -> s = 0): subnormal step, the three normal steps, and beyond the top
+    x[0, :12] = [1 / 16, 3 / 16, 1.0625, 1.1875, 2.125, 2.375, 4.25, 4.75, 5.0, 7.75, -7.25, 7.6]
+    x[0, 12:] = 0.0
+    x[0, 8] = 5.0
+    x[1, :4] = [4.0, 7.75, -7.9, 7.5]                               # largest entry 7.9 -> s = 0: saturation at 7.5
+    x[1, 4:] = 0.0
+    y, codes, scales = orc.mx6_blocks(x)
+    for b in range(300):
+        s = int(scales[b]) - 127
+        m = np.abs(x[b]).max()
+        assert s == int(np.floor(np.log2(m))) - 2 and 4.0 <= m * 2.0 ** -s < 8.0
+        for k in range(32):
+            v = abs(Fraction(float(np.ldexp(x[b, k], -s))))
+            best = min(range(32), key=lambda c: (abs(grid[c] - v), c & 1))         # nearest, ties to the even code
+            if v > grid[31]:
+                best = 31
+            assert int(codes[b, k]) & 31 == best and Fraction(float(abs(y[b, k]))) == grid[best], (b, k, float(v))
+            if best:
+                assert (int(codes[b, k]) >> 5) == (1 if x[b, k] < 0 else 0)
+            assert int(codes[b, k]) < 64
+    assert list(y[0, :8]) == [0.0, 0.25, 1.0, 1.25, 2.0, 2.5, 4.0, 5.0]
+    assert list(y[1, :4]) == [4.0, 7.5, -7.5, 7.5]
+    ints = rng.integers(-7, 8, (40, 32)).astype(np.float64)
+    ints[0] = 0.0
+    y, codes, scales = orc.mx6_blocks(ints)
+    assert scales[0] == 127 and not y[0].any()
+    assert np.array_equal(np.ldexp(y, (scales.astype(np.int64) - 127)[:, None]), ints)
+    # NaN has no code: stored as zero, and it does not enter the block maximum; infinities saturate
+    y, codes, scales = orc.mx6_blocks(np.array([np.nan, 3.0, -np.inf] + [0.5] * 29))
+    assert y[0] == 0.0 and scales[0] == 127 and y[1] == 3.0 and y[2] == -7.5
