@@ -32,7 +32,7 @@ HEADLINE = "cov64k"
 ALSO = ("cov16k", "rect32k")
 KERNEL_NAMES = ["gemm_mp_owner_kernel<double%s>", "gemm_mp_owner_kernel<float%s>", "gemm_mp_fp8_region_kernel<0>",
                 "gemm_mp_fp8_region_kernel<1>", "gemm_mp_fp8_region_kernel<2>", "gemm_mp_fp8_region_kernel<3>",
-                "gemm_mp_fp8_region_kernel<4>"]
+                "gemm_mp_fp8_region_kernel<4>", "gemm_mp_fp8_region_kernel<5>"]
 INSTANCE = [", false, false", ", true, false", ", true, true"]
 
 
@@ -45,7 +45,7 @@ def parse():
                     choices=["tiny", "random8k", "cov16k", "rect32k", "cov64k",
                              "paper100", "paper80", "paper50", "paper20", "paper0",
                              "format-fp64", "format-fp32", "format-fp16", "format-fp8", "format-bf16", "format-mxfp8",
-                             "format-mxfp4"],
+                             "format-mxfp4", "format-mxfp6"],
                     help="default: cov64k, followed by short runs of cov16k and rect32k.  paperNN: the paper's own runs, "
                          "NN %% of the tiles FP64 and the rest FP32 (Section 5.2); format-X: 16384^3, tile 1024, every tile "
                          "of A and B stored as X (per-format rates; no CPU baseline)")
@@ -174,11 +174,11 @@ def measure(name, steps, warmup, policy, conversion, cpu_seconds):
 
     st = d.ctx.get_stats()
     flops_total = 2.0 * w.M * w.N * w.K
-    assert abs(sum(st["flops"]) + st["flops_bf16"] + st["flops_mxfp8"] + st["flops_mxfp4"] - flops_total) < 1e-6 * flops_total
+    assert abs(sum(st["flops"]) + st["flops_bf16"] + st["flops_mxfp8"] + st["flops_mxfp4"] + st["flops_mxfp6"] - flops_total) < 1e-6 * flops_total
     t_roof = sum(f / (p * 1e12) for f, p in zip(st["flops"], PEAK_TFLOPS))          # seconds
     t_roof += st["flops_bf16"] / (PEAK_TFLOPS[2] * 1e12)                             # BF16 peak = FP16 peak
     t_roof += st["flops_mxfp8"] / (PEAK_TFLOPS[3] * 1e12)                            # block-scaled FP8: the FP8 peak
-    t_roof += st["flops_mxfp4"] / (PEAK_FP4_TFLOPS * 1e12)                           # block-scaled FP4: 10.1 PFLOP/s
+    t_roof += (st["flops_mxfp4"] + st["flops_mxfp6"]) / (PEAK_FP4_TFLOPS * 1e12)     # block-scaled FP4 and FP6: 10.1 PFLOP/s
     run_ms = float(np.mean(stage_ms["run"]))
     achieved = flops_total / (run_ms * 1e-3) / 1e12
     peak_mix = flops_total / t_roof / 1e12
@@ -190,9 +190,9 @@ def measure(name, steps, warmup, policy, conversion, cpu_seconds):
         if entry:
             traffic, traffic_from = entry.get("bytes_per_launch"), "profiles/traffic.json: " + entry.get("source", "")
     used = [DTYPE_NAMES[q] for q in range(4) if st["products"][q]]
-    used += [n for n in ("bf16", "mxfp8", "mxfp4") if st["products_" + n]]
+    used += [n for n in ("bf16", "mxfp8", "mxfp4", "mxfp6") if st["products_" + n]]
     launched = []
-    for k, n in enumerate(st["launch_items"][:7]):
+    for k, n in enumerate(st["launch_items"][:8]):
         if n:
             kn = KERNEL_NAMES[k]
             launched.append({"kernel": kn % INSTANCE[st["owner_instance"][k]] if k < 2 else kn, "workgroups": n})
@@ -209,7 +209,7 @@ def measure(name, steps, warmup, policy, conversion, cpu_seconds):
                    "conversion": conversion, "converted_tiles": st["converted_tiles"],
                    "converted_bytes": st["converted_bytes"],
                    "products_by_precision": dict(list(zip(DTYPE_NAMES, st["products"])) +
-                                                 [(n, st["products_" + n]) for n in ("bf16", "mxfp8", "mxfp4") if st["products_" + n]]),
+                                                 [(n, st["products_" + n]) for n in ("bf16", "mxfp8", "mxfp4", "mxfp6") if st["products_" + n]]),
                    "work_items": st["work_items"], "host_generation_s": round(t_gen, 1)},
         "stages_ms": {k: float(np.mean(v)) for k, v in stage_ms.items()},
         "run_only": {"ms": run_ms, "min_ms": float(np.min(stage_ms["run"])), "effective_tflops": achieved,

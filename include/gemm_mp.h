@@ -56,6 +56,12 @@
  * 2^(floor(log2 max|x|) - 2)): tile_nb^2/2 element bytes, two elements per byte with the lower
  * reduction index in the low four bits, then the tile_nb^2/32 scale bytes; block-scaled
  * instruction where every product of a C tile is MXFP4 x MXFP4 and tile_nb is a multiple of 512.
+ * MXFP6 tiles (code 7) are the same with e2m3 elements (six bits: sign, two exponent bits with
+ * bias 1, three fraction bits; the magnitudes are the multiples of 1/8 below 2, of 1/4 below 4 and
+ * of 1/2 up to 7.5; scale 2^(floor(log2 max|x|) - 2)): 3*tile_nb^2/4 element bytes, a block of 32
+ * elements being 24 bytes with element k of the block in bits 6k .. 6k+5 (least significant bit
+ * first, as the matrix instruction reads them), then the tile_nb^2/32 scale bytes; block-scaled
+ * instruction where every product of a C tile is MXFP6 x MXFP6 and tile_nb is a multiple of 256.
  *
  * C tiles stored in FP16 / FP8 (formats beyond FP64 / FP32 are what the paper's
  * Section 6 leaves open): such a tile is a storage format only.  Its products
@@ -63,7 +69,7 @@
  * the tile is finished its largest magnitude fixes a new exponent e by the rule
  * above and every entry is rounded once more, from FP32, to nearest even.  With
  * beta != 0 the old tile enters as stored number * 2^e.  BF16 C tiles are rounded
- * without a scale; MXFP8 / MXFP4 C tiles are quantised block by block, the blocks
+ * without a scale; MXFP8 / MXFP4 / MXFP6 C tiles are quantised block by block, the blocks
  * of 32 running along the rows of the tile as in a tile of A.  The FP32 form lives in
  * a staging copy per such tile that follows the packed tiles in C's buffer
  * (gemm_mp_storage_bytes counts it), so the library still allocates no operand
@@ -86,7 +92,7 @@ typedef void *gemm_mp_stream;           /* a hipStream_t */
  * The code is a name, not a rank: by unit roundoff (2^-53, 2^-24, 2^-11, 2^-8, 2^-4) the formats
  * order FP64, FP32, FP16, BF16, FP8. */
 enum { GEMM_MP_FP64 = 0, GEMM_MP_FP32 = 1, GEMM_MP_FP16 = 2, GEMM_MP_FP8_E4M3 = 3, GEMM_MP_BF16 = 4,
-       GEMM_MP_MXFP8 = 5, GEMM_MP_MXFP4 = 6 };
+       GEMM_MP_MXFP8 = 5, GEMM_MP_MXFP4 = 6, GEMM_MP_MXFP6 = 7 };
 
 enum {
     GEMM_MP_OK = 0,
@@ -131,9 +137,12 @@ typedef struct gemm_mp_stats {
     int64_t launch_items[8]; /* owner workgroups per kernel launch of gemm_mp_run: [0] 128 x 128 regions of
                               * FP64 C tiles, [1] of C tiles accumulated in FP32, [2] / [3] / [4] 256 x 256
                               * regions of tiles made of FP8 / MXFP8 / MXFP4 products only, [5] / [6] of FP16 /
-                              * BF16 products only; [7] is 0 */
+                              * BF16 products only, [7] of MXFP6 products only */
     int32_t owner_instance[2]; /* which instance of the 128 x 128 kernel serves [0] and [1]: 0 plain, 1 the one
                               * whose DMA ring also takes FP16 products with an FP8 operand, 2 the BF16 one */
+    int64_t products_mxfp6;  /* as products_mxfp4, for precision code 7 */
+    double flops_mxfp6;
+    int64_t tiles_mxfp6[3];
 } gemm_mp_stats;
 
 /* Create a context for C(MxN) = A(MxK) * B(KxN) with square tiles of tile_nb (Section 4:

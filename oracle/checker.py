@@ -10,8 +10,8 @@ import numpy as np
 
 from . import gemm_mp_oracle as orc
 
-FP64, FP32, FP16, FP8, BF16, MXFP8, MXFP4 = 0, 1, 2, 3, 4, 5, 6
-U = {FP64: 2.0 ** -53, FP32: 2.0 ** -24, FP16: 2.0 ** -11, FP8: 2.0 ** -4, BF16: 2.0 ** -8, MXFP8: 2.0 ** -4, MXFP4: 2.0 ** -2}
+FP64, FP32, FP16, FP8, BF16, MXFP8, MXFP4, MXFP6 = 0, 1, 2, 3, 4, 5, 6, 7
+U = {FP64: 2.0 ** -53, FP32: 2.0 ** -24, FP16: 2.0 ** -11, FP8: 2.0 ** -4, BF16: 2.0 ** -8, MXFP8: 2.0 ** -4, MXFP4: 2.0 ** -2, MXFP6: 2.0 ** -4}
 
 
 class OracleSide:
@@ -200,7 +200,7 @@ def compare_jobs(side, jobs, policy, alpha, beta, C_gpu, C_orc, elementwise=True
         if not elementwise:
             continue
         eb, _ = element_bounds(side, job, policy, alpha, beta)
-        if t["pC"] in (MXFP8, MXFP4):
+        if t["pC"] in (MXFP8, MXFP4, MXFP6):
             # a block of 32 along the row is rounded relative to its own largest entry (and
             # saturates just below the next power of two): a quarter of that entry covers both
             ob = np.abs(o)

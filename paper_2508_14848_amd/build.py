@@ -10,7 +10,7 @@ SOURCES = ["gemm_mp_host.hip", "kernels_scan_pack.hip", "kernels_gemm.hip",
            "gemm_owner_d.hip", "gemm_owner_d_mixed.hip", "gemm_owner_d_bf.hip",
            "gemm_owner_f.hip", "gemm_owner_f_mixed.hip", "gemm_owner_f_bf.hip",
            "gemm_region_fp8.hip", "gemm_region_mxfp8.hip", "gemm_region_mxfp4.hip",
-           "gemm_region_fp16.hip", "gemm_region_bf16.hip"]
+           "gemm_region_fp16.hip", "gemm_region_bf16.hip", "gemm_region_mxfp6.hip"]
 # -ffp-contract=off: the only fused multiply-adds are the ones the code asks for.
 # packed-fp32 instructions are switched off for this target.
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-ffp-contract=off",

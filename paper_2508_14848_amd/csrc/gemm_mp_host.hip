@@ -69,10 +69,10 @@ struct gemm_mp_ctx {
     Matrix mat[3];
     bool sched_current = false;
     std::vector<uint8_t> q;
-    std::vector<WorkItem> items[7];   // regions of [0] FP64 C tiles, [1] C tiles accumulated in FP32 (stored
+    std::vector<WorkItem> items[8];   // regions of [0] FP64 C tiles, [1] C tiles accumulated in FP32 (stored
                                       // FP32 / FP16 / FP8), [2] those of them whose products are all
                                       // FP8 x FP8 (256 x 256 regions), [3] / [4] the same for MXFP8 x MXFP8 / MXFP4 x MXFP4,
-                                      // [5] / [6] for FP16 x FP16 / BF16 x BF16
+                                      // [5] / [6] for FP16 x FP16 / BF16 x BF16, [7] for MXFP6 x MXFP6
     Mirror<uint8_t> qd;               // [MT*NT][KT] product precision of every task
     Mirror<WorkItem> itemsd;          // the lists, [0] first
     ProductDesc *d_prod = nullptr;    // one record per task (+ 2 padding records), filled on the device
@@ -87,7 +87,7 @@ struct gemm_mp_ctx {
     gemm_mp_stats stats;
     bool mixed32 = false;             // list [1] holds an FP16 / BF16 product with an operand stored in FP8
     bool mixed64 = false;             // the same for list [0]
-    bool has_bf16 = false;            // A or B has a BF16 tile
+    bool has_bf16 = false;            // some product of the 128 x 128 kernels has a BF16 or block-scaled operand
     bool kernel_ready = false;
     // sender-side conversion: per tile of A / B and product precision q, the offset of the copy
     // in precision q inside the workspace (kNoCopy: no task needs one)
@@ -316,7 +316,7 @@ double unit_roundoff(int p)
 // Relative cost of one tile product by precision: inverse matrix-core peak (FP64 : FP32 :
 // FP16 : FP8 = 1/78.6 : 1/157.3 : 1/2516.6 : 1/5033.2 TFLOP/s) plus a floor for the operand
 // traffic that the low precisions cannot hide.
-const double kCost[7] = {64.0, 32.0, 3.0, 2.0, 3.0, 2.0, 1.5};
+const double kCost[8] = {64.0, 32.0, 3.0, 2.0, 3.0, 2.0, 1.5, 2.0};
 
 // The schedule.  Every C tile is cut into (nb/128)^2 owner regions; a region's cost is the
 // sum over its reduction tiles of the cost of that product's precision.  C tiles are sorted by
@@ -340,6 +340,7 @@ void build_schedule(gemm_mp_ctx *c)
                 if (q == GEMM_MP_BF16) c->stats.products_bf16 += 1;
                 else if (q == GEMM_MP_MXFP8) c->stats.products_mxfp8 += 1;
                 else if (q == GEMM_MP_MXFP4) c->stats.products_mxfp4 += 1;
+                else if (q == GEMM_MP_MXFP6) c->stats.products_mxfp6 += 1;
                 else c->stats.products[q] += 1;
                 cost[(size_t)I * NT + J] += kCost[q];
             }
@@ -349,9 +350,7 @@ void build_schedule(gemm_mp_ctx *c)
     c->stats.flops_bf16 = f * (double)c->stats.products_bf16;
     c->stats.flops_mxfp8 = f * (double)c->stats.products_mxfp8;
     c->stats.flops_mxfp4 = f * (double)c->stats.products_mxfp4;
-    c->has_bf16 = false;
-    for (int w = 0; w < 2; ++w)
-        for (uint16_t p : c->mat[w].map) c->has_bf16 |= p == GEMM_MP_BF16;
+    c->stats.flops_mxfp6 = f * (double)c->stats.products_mxfp6;
 
     // A C tile accumulated in FP32 whose every product multiplies two MXFP8 tiles goes to the
     // block-scaled instance of the 256 x 256 kernel.  Every other product with an MXFP8 operand
@@ -360,17 +359,18 @@ void build_schedule(gemm_mp_ctx *c)
     // at FP32 where both operands are MXFP8 (exact products, FP32 accumulation: what an MXFP8
     // product is), at the product's own FP32 / FP64 otherwise.  c->q then holds the precision
     // the kernels work at, the statistics keep the product's nominal one.
-    std::vector<uint8_t> all_mx((size_t)MT * NT, 0);         // 1: all MXFP8 x MXFP8, 2: all MXFP4 x MXFP4 (tile size a multiple of 512)
+    std::vector<uint8_t> all_mx((size_t)MT * NT, 0);         // 1: all MXFP8 x MXFP8, 2: all MXFP4 x MXFP4 (tile size a multiple of 512), 3: all MXFP6 x MXFP6
     for (int I = 0; I < MT; ++I)
         for (int J = 0; J < NT; ++J) {
             const bool fits = C.map[I * NT + J] != GEMM_MP_FP64 && KT > 0;
-            bool all8 = fits && c->nb % kMacroFp8 == 0, all4 = fits && c->nb % (2 * kMacroFp8) == 0;
+            bool all8 = fits && c->nb % kMacroFp8 == 0, all4 = fits && c->nb % (2 * kMacroFp8) == 0, all6 = all8;
             for (int L = 0; L < KT; ++L) {
                 all8 &= c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_MXFP8;
                 all4 &= c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_MXFP4;
+                all6 &= c->q[((size_t)I * NT + J) * KT + L] == GEMM_MP_MXFP6;
             }
-            all_mx[(size_t)I * NT + J] = all8 ? 1 : all4 ? 2 : 0;
-            if (!all8 && !all4)
+            all_mx[(size_t)I * NT + J] = all8 ? 1 : all4 ? 2 : all6 ? 3 : 0;
+            if (!all8 && !all4 && !all6)
                 for (int L = 0; L < KT; ++L) {
                     uint8_t &q = c->q[((size_t)I * NT + J) * KT + L];
                     if (is_block_scaled(q)) q = GEMM_MP_FP32;
@@ -407,6 +407,7 @@ void build_schedule(gemm_mp_ctx *c)
             if (p == GEMM_MP_BF16) c->stats.tiles_bf16[w] += 1;
             else if (p == GEMM_MP_MXFP8) c->stats.tiles_mxfp8[w] += 1;
             else if (p == GEMM_MP_MXFP4) c->stats.tiles_mxfp4[w] += 1;
+            else if (p == GEMM_MP_MXFP6) c->stats.tiles_mxfp6[w] += 1;
             else c->stats.tiles[w][p] += 1;
         }
         c->stats.packed_bytes[w] = c->mat[w].bytes;
@@ -438,13 +439,18 @@ void build_schedule(gemm_mp_ctx *c)
                 }
                 all_16[(size_t)I * NT + J] = h ? 1 : b ? 2 : 0;
             }
-    c->mixed32 = c->mixed64 = false;
+    // The formats beyond FP64 / FP32 / FP16 / FP8 (BF16 products in the ring, BF16 and block-scaled
+    // tiles widened under FP32 / FP64 products) are known to one instance of the 128 x 128 kernel
+    // only; it serves both launches as soon as one product of theirs has such an operand.
+    c->mixed32 = c->mixed64 = c->has_bf16 = false;
     for (int I = 0; I < MT; ++I)
         for (int J = 0; J < NT; ++J) {
-            if (all_fp8[(size_t)I * NT + J] || all_16[(size_t)I * NT + J]) continue;
+            if (all_fp8[(size_t)I * NT + J] || all_16[(size_t)I * NT + J] || all_mx[(size_t)I * NT + J]) continue;
             bool mixed = false;
             for (int L = 0; L < KT; ++L) {
                 const int q = c->q[((size_t)I * NT + J) * KT + L];
+                const int pa = A.map[I * KT + L], pb = B.map[L * NT + J];
+                c->has_bf16 |= pa == GEMM_MP_BF16 || pb == GEMM_MP_BF16 || is_block_scaled(pa) || is_block_scaled(pb);
                 mixed |= (q == GEMM_MP_FP16 || q == GEMM_MP_BF16) &&
                          (A.map[I * KT + L] == GEMM_MP_FP8_E4M3 || B.map[L * NT + J] == GEMM_MP_FP8_E4M3);
             }
@@ -452,7 +458,7 @@ void build_schedule(gemm_mp_ctx *c)
             else c->mixed32 |= mixed;
         }
     constexpr int kBins = 8;
-    for (int list = 0; list < 7; ++list) {
+    for (int list = 0; list < 8; ++list) {
         const int mr = c->nb / (list >= 2 ? kMacroFp8 : kMacro);
         const size_t per_tile = (size_t)mr * mr;
         std::vector<WorkItem> bins[kBins];
@@ -464,7 +470,7 @@ void build_schedule(gemm_mp_ctx *c)
             // those kernels wait for is the delivery from L2 to the compute units.)
             std::vector<int> order;
             for (int t = 0; t < MT * NT; ++t) {
-                const int which = C.map[t] == GEMM_MP_FP64 ? 0 : all_fp8[t] ? 2 : all_mx[t] ? 2 + all_mx[t] : all_16[t] ? 4 + all_16[t] : 1;
+                const int which = C.map[t] == GEMM_MP_FP64 ? 0 : all_fp8[t] ? 2 : all_mx[t] == 3 ? 7 : all_mx[t] ? 2 + all_mx[t] : all_16[t] ? 4 + all_16[t] : 1;
                 if (which == list) order.push_back(t);
             }
             std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cost[a] > cost[b]; });
@@ -498,7 +504,7 @@ void build_schedule(gemm_mp_ctx *c)
         }
     }
     c->stats.work_items = 0;
-    for (int list = 0; list < 7; ++list) {
+    for (int list = 0; list < 8; ++list) {
         c->stats.launch_items[list] = (int64_t)c->items[list].size();
         c->stats.work_items += (int64_t)c->items[list].size();
     }
@@ -542,7 +548,7 @@ int prepare_schedule(gemm_mp_ctx *c, hipStream_t s)
     if (!pq || !pi) return GEMM_MP_EHIP;
     std::memcpy(pq, c->q.data(), tasks);
     size_t n = 0;
-    for (int list = 0; list < 7; ++list) {
+    for (int list = 0; list < 8; ++list) {
         if (!c->items[list].empty()) std::memcpy(pi + n, c->items[list].data(), c->items[list].size() * sizeof(WorkItem));
         n += c->items[list].size();
     }
@@ -661,7 +667,7 @@ int gemm_mp_set_precision_map(gemm_mp_ctx *c, char which, const uint16_t *map, i
     Matrix &m = c->mat[w];
     if (rows != m.rows_t || cols != m.cols_t) return GEMM_MP_EINVAL;
     for (int t = 0; t < m.ntiles(); ++t)
-        if (map[t] > GEMM_MP_MXFP4) return GEMM_MP_EINVAL;
+        if (map[t] > GEMM_MP_MXFP6) return GEMM_MP_EINVAL;
     return install_map(c, w, map);
 }
 
@@ -849,6 +855,8 @@ int run_on(gemm_mp_ctx *c, double alpha, double beta, hipStream_t s, ProductDesc
     a.n_items_h = (int32_t)c->items[5].size();
     a.items_bf = a.items_h + c->items[5].size();
     a.n_items_bf = (int32_t)c->items[6].size();
+    a.items_mx6 = a.items_bf + c->items[6].size();
+    a.n_items_mx6 = (int32_t)c->items[7].size();
     a.mixed32 = c->mixed32 ? 1 : 0;
     a.mixed64 = c->mixed64 ? 1 : 0;
     a.bf16 = c->has_bf16 ? 1 : 0;

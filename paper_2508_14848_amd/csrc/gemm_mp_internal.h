@@ -23,9 +23,18 @@ __host__ __device__ inline uint64_t tile_bytes_of(int p, uint64_t elems)
 {
     if (p == GEMM_MP_MXFP8) return elems + elems / 32;
     if (p == GEMM_MP_MXFP4) return elems / 2 + elems / 32;
+    if (p == GEMM_MP_MXFP6) return elems / 4 * 3 + elems / 32;
     return elems * (uint64_t)elem_bytes(p);
 }
-__host__ __device__ inline bool is_block_scaled(int p) { return p == GEMM_MP_MXFP8 || p == GEMM_MP_MXFP4; }
+__host__ __device__ inline bool is_block_scaled(int p) { return p == GEMM_MP_MXFP8 || p == GEMM_MP_MXFP4 || p == GEMM_MP_MXFP6; }
+
+// Value of a six-bit e2m3 code: sign, two exponent bits (bias 1), three fraction bits; exact in FP32.
+__host__ __device__ inline float fp6_value(uint32_t code)
+{
+    const int ef = (int)(code >> 3) & 3, mf = (int)code & 7;
+    const float mag = ef ? (float)((8 + mf) << (ef - 1)) * 0.125f : 0.125f * (float)mf;
+    return (code & 32u) ? -mag : mag;
+}
 
 // Product precision (code) for stored precisions pA, pB, C tile precision pC.
 __host__ __device__ inline int product_precision(int pA, int pB, int pC, int policy)
@@ -35,8 +44,9 @@ __host__ __device__ inline int product_precision(int pA, int pB, int pC, int pol
     // the smallest format that holds both operands' numbers: FP64 > FP32 > {FP16, BF16} > FP8
     if (pA == GEMM_MP_MXFP8 && pB == GEMM_MP_MXFP8) return GEMM_MP_MXFP8;
     if (pA == GEMM_MP_MXFP4 && pB == GEMM_MP_MXFP4) return GEMM_MP_MXFP4;
-    if (pA == GEMM_MP_MXFP8 || pA == GEMM_MP_MXFP4) pA = GEMM_MP_FP32;      // block-scaled numbers are FP32 numbers
-    if (pB == GEMM_MP_MXFP8 || pB == GEMM_MP_MXFP4) pB = GEMM_MP_FP32;
+    if (pA == GEMM_MP_MXFP6 && pB == GEMM_MP_MXFP6) return GEMM_MP_MXFP6;
+    if (is_block_scaled(pA)) pA = GEMM_MP_FP32;                             // block-scaled numbers are FP32 numbers
+    if (is_block_scaled(pB)) pB = GEMM_MP_FP32;
     int q;
     const bool h = pA == GEMM_MP_FP16 || pB == GEMM_MP_FP16, b = pA == GEMM_MP_BF16 || pB == GEMM_MP_BF16;
     if (pA == GEMM_MP_FP64 || pB == GEMM_MP_FP64) q = GEMM_MP_FP64;
@@ -106,10 +116,11 @@ struct GemmArgs {
     const WorkItem *items_mx4;// ... of MXFP4 x MXFP4 products only
     const WorkItem *items_h;  // ... of FP16 x FP16 products only
     const WorkItem *items_bf; // ... of BF16 x BF16 products only
-    int32_t n_items64, n_items32, n_items8, n_items_mx, n_items_mx4, n_items_h, n_items_bf;
+    const WorkItem *items_mx6;// ... of MXFP6 x MXFP6 products only
+    int32_t n_items64, n_items32, n_items8, n_items_mx, n_items_mx4, n_items_h, n_items_bf, n_items_mx6;
     int32_t mixed32;         // some region of items32 has an FP16 / BF16 product with an operand stored in FP8
     int32_t mixed64;         // the same for items64
-    int32_t bf16;            // some tile of A or B is stored in BF16
+    int32_t bf16;            // some product of the 128 x 128 kernels has a BF16 or block-scaled operand
     int32_t nb, MT, NT, KT;
     int32_t kt_eff;          // KT, or 0 when alpha == 0
     double alpha, beta;
@@ -150,6 +161,6 @@ hipError_t gemm_kernel_setup();
 GMP_DECLARE_INSTANCE(owner_d) GMP_DECLARE_INSTANCE(owner_d_mixed) GMP_DECLARE_INSTANCE(owner_d_bf)
 GMP_DECLARE_INSTANCE(owner_f) GMP_DECLARE_INSTANCE(owner_f_mixed) GMP_DECLARE_INSTANCE(owner_f_bf)
 GMP_DECLARE_INSTANCE(region_fp8) GMP_DECLARE_INSTANCE(region_mxfp8) GMP_DECLARE_INSTANCE(region_mxfp4)
-GMP_DECLARE_INSTANCE(region_fp16) GMP_DECLARE_INSTANCE(region_bf16)
+GMP_DECLARE_INSTANCE(region_fp16) GMP_DECLARE_INSTANCE(region_bf16) GMP_DECLARE_INSTANCE(region_mxfp6)
 
 }  // namespace gmp

@@ -526,8 +526,8 @@ __device__ __forceinline__ Product make_product(const u32x4 lo, const u32x4 hi, 
     const int ea = (int)hi.x, eb = (int)hi.y;
     const int ca = (int)(hi.z & 0xffu), cb = (int)((hi.z >> 8) & 0xffu), q = (int)((hi.z >> 16) & 0xffu);
     // bits 24 / 25: the A / B tile holds BF16 numbers (written as FP16 in the codes: the same element
-    // size); codes 5 / 6: an MXFP8 / MXFP4 tile under an FP32 / FP64 product, read like an FP8 tile
-    // whose scale comes per block
+    // size); codes 5 / 6 / 7: an MXFP8 / MXFP4 / MXFP6 tile under an FP32 / FP64 product, read like an
+    // FP8 tile whose scale comes per block
     const int fa = ca >= GEMM_MP_MXFP8 ? ca - GEMM_MP_MXFP8 + 2 : (int)((hi.z >> 24) & 1u);
     const int fb = cb >= GEMM_MP_MXFP8 ? cb - GEMM_MP_MXFP8 + 2 : (int)((hi.z >> 25) & 1u);
     const int pa = ca >= GEMM_MP_MXFP8 ? (int)Q8 : ca, pb = cb >= GEMM_MP_MXFP8 ? (int)Q8 : cb;
@@ -793,7 +793,7 @@ __device__ __forceinline__ void steady_chunks(Acc (&acc)[4][4], u32x4 (&fr)[2][8
     }
 }
 
-// ---- FP64 / FP32 products with a BF16, MXFP8 or MXFP4 operand ---------------------------------
+// ---- FP64 / FP32 products with a BF16, MXFP8, MXFP4 or MXFP6 operand ---------------------------------
 // Receiver-side conversion of the formats beyond the paper's: a BF16 number is the upper half of
 // an FP32 word, a block-scaled element times the scale 2^(code - 127) of its block of 32 is exact
 // in FP32 (and FP64).  These products take a plain loop of their own: per chunk, fetch the eight
@@ -802,11 +802,14 @@ __device__ __forceinline__ void steady_chunks(Acc (&acc)[4][4], u32x4 (&fr)[2][8
 // to LDS stage 0, and run the chunk's matrix instructions; nothing is overlapped.  The fast roads
 // for such tiles are their own kernels (BF16 x BF16, MXFP8 x MXFP8, MXFP4 x MXFP4 products) and
 // sender-side copies; this one keeps every tile convertible by its consumer.
-__device__ __forceinline__ float fp4_value(uint32_t code)      // an e2m1 code: sign, two exponent bits, one fraction bit
+// Number of a narrow code (sign, two exponent bits with bias 1, mb fraction bits: e2m1 with mb = 1,
+// e2m3 with mb = 3) times 2^e; exact in FP32.
+__device__ __forceinline__ float narrow_value(uint32_t code, int mb, int e)
 {
-    const int ef = (int)(code >> 1) & 3, mf = (int)code & 1;
-    const float mag = ef ? ldexpf(1.0f + 0.5f * (float)mf, ef - 1) : 0.5f * (float)mf;
-    return (code & 8u) ? -mag : mag;
+    const int mf = (int)code & ((1 << mb) - 1), ef = (int)(code >> mb) & 3;
+    const int mant = ef ? ((1 << mb) + mf) << (ef - 1) : mf;   // in units of 2^-mb
+    const float mag = ldexpf((float)mant, e - mb);
+    return ((code >> (mb + 2)) & 1u) ? -mag : mag;
 }
 // Piece i = 2 * (row block) + (0: A, 1: B) of chunk c: the aligned 16 bytes around the source, the
 // second 16 for the one down-cast, the scale byte (into r.hi.x) for a block-scaled tile.
@@ -816,14 +819,29 @@ __device__ __forceinline__ void load_piece_widening(Raw &r, const Product &pr, i
     const Operand &o = (i & 1) ? pr.b : pr.a;
     const int fmt = __builtin_amdgcn_readfirstlane(o.sub >> 8);
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)o.base, 0, o.bytes, 0x00020000);
-    r.lo = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o.voff, fmt == 3 ? eoff >> 1 : eoff << (3 - o.p), 0);
+    if (fmt >= 3) {
+        // MXFP4 / MXFP6: W = 4 / 6 bits per element.  The operand's descriptor counts in bytes of
+        // an element size the kernel knows (MXFP4: two elements a byte; MXFP6 is announced like
+        // MXFP8, one byte per element), which gives back the thread's first element; its codes start
+        // at bit element * W of the tile.  The two aligned words from there on are read (at most 24
+        // bits from bit 28 of the first), and the bit offset in them goes along in r.hi.y.
+        const int W = fmt == 3 ? 4 : 6;
+        const int eidx = (o.voff + (o.sub & 15)) << (fmt == 3 ? 1 : 0);
+        const int bit = eidx * W;
+        const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (bit >> 5) << 2, (eoff * W) >> 3, 0);
+        r.lo.x = w.x;
+        r.lo.y = w.y;
+        r.hi.y = (uint32_t)(bit & 31);
+        r.hi.x = (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rsrc, ((nb * nb * W) >> 3) + (eidx >> 5), eoff >> 5, 0);
+        return;
+    }
+    r.lo = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o.voff, eoff << (3 - o.p), 0);
     if (pr.q == Q32 && o.p == Q64) {
         r.hi = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o.voff + 16, eoff << (3 - o.p), 0);
-    } else if (fmt >= 2) {
+    } else if (fmt == 2) {
         // the element index comes back from the byte offset of the segment's source
         const int boff = o.voff + (o.sub & 15);
-        const int svoff = fmt == 3 ? ((nb * nb) >> 1) + (boff >> 4) : nb * nb + (boff >> 5);
-        r.hi.x = (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rsrc, svoff, eoff >> 5, 0);
+        r.hi.x = (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rsrc, nb * nb + (boff >> 5), eoff >> 5, 0);
     }
 }
 template <int Q>
@@ -846,13 +864,16 @@ __device__ __forceinline__ u32x4 convert_widening(const Raw &r, const Operand &o
     }
     const int e = (int)(r.hi.x & 0xffu) - 127;                   // this segment's block scale
     if (fmt == 2) return convert<Q>(r, Q8, e, sub);              // e4m3 elements: the FP8 road with the block's exponent
-    // MXFP4: four (FP32) or two (FP64) four-bit codes starting at byte `sub` of the loaded 16
-    const uint32_t w = pick_word(r.lo, sub >> 2) >> ((sub & 3) * 8);
+    // MXFP4 / MXFP6: four (FP32) or two (FP64) codes of W bits from bit r.hi.y of the loaded eight bytes
+    const int W = fmt == 3 ? 4 : 6, mb = W - 3;
+    const uint64_t both = (uint64_t)r.lo.x | ((uint64_t)r.lo.y << 32);
+    const uint32_t w = (uint32_t)(both >> r.hi.y);
+    const uint32_t mask = (1u << W) - 1u;
     if constexpr (Q == Q32) {
-        o = u32x4{__float_as_uint(ldexpf(fp4_value(w & 15u), e)), __float_as_uint(ldexpf(fp4_value((w >> 4) & 15u), e)),
-                  __float_as_uint(ldexpf(fp4_value((w >> 8) & 15u), e)), __float_as_uint(ldexpf(fp4_value((w >> 12) & 15u), e))};
+        o = u32x4{__float_as_uint(narrow_value(w & mask, mb, e)), __float_as_uint(narrow_value((w >> W) & mask, mb, e)),
+                  __float_as_uint(narrow_value((w >> (2 * W)) & mask, mb, e)), __float_as_uint(narrow_value((w >> (3 * W)) & mask, mb, e))};
     } else {
-        const u32x2 a = dbits(ldexp((double)fp4_value(w & 15u), e)), b = dbits(ldexp((double)fp4_value((w >> 4) & 15u), e));
+        const u32x2 a = dbits(ldexp((double)narrow_value(w & mask, mb, 0), e)), b = dbits(ldexp((double)narrow_value((w >> W) & mask, mb, 0), e));
         o = u32x4{a.x, a.y, b.x, b.y};
     }
     return o;
@@ -1643,9 +1664,11 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
             ++L;
             continue;
         }
-        const bool widening = is_widening(cur);
+        // (only the instance for the formats beyond FP64 / FP32 / FP16 / FP8 carries the widening loop:
+        // the host launches it whenever some product outside the 256 x 256 regions has such an operand)
+        const bool widening = BF && is_widening(cur);
         if (q == QT) {
-            if (widening) next = product_loop_widening<QT, (QT == Q32 ? 192 : -1), MIXED>(s, cur, W, L + 1, lds, stage, G, R, raw);
+            if (BF && widening) next = product_loop_widening<QT, (QT == Q32 ? 192 : -1), MIXED>(s, cur, W, L + 1, lds, stage, G, R, raw);
             else next = product_loop_pipelined<QT, (QT == Q32 ? 192 : -1), QT == Q32, MIXED>(s, cur, W, L + 1, lds, stage, G, R, hand, raw);
         } else {
             if constexpr (QT == Q64) {
@@ -1655,7 +1678,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
-                if (widening) next = product_loop_widening<Q32, -1, MIXED>(t, cur, W, L + 1, lds, stage, G, R, raw);
+                if (BF && widening) next = product_loop_widening<Q32, -1, MIXED>(t, cur, W, L + 1, lds, stage, G, R, raw);
                 else next = product_loop_pipelined<Q32, -1, false, MIXED>(t, cur, W, L + 1, lds, stage, G, R, hand, raw);
                 fold(s, t, 0);
             } else {

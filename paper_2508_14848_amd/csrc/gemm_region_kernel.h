@@ -53,14 +53,24 @@ __device__ __forceinline__ void big_scales(int ea, int eb, int &sa, int &sb)
 // DMA instruction j = 0..15 of a wave for one chunk: j < 8 moves rows 8 j .. 8 j + 7 of the
 // wave's 64 rows of A, j >= 8 the same of B, 16 bytes per lane, into the stage at `dst`.
 // base / bytes: the operand tile (bytes = 0: nothing is fetched, zeros are written).
+// FMT 5 (MXFP6): 12 bytes per lane; the 12-byte form of the instruction still gives every lane a
+// 16-byte slot in LDS (lane l writes at 16 l, the last four bytes of the slot stay as they were),
+// so a stage has the layout of the other formats with three quarters of every slot in use.
+template <int FMT>
 __device__ __forceinline__ void big_dma_one(uint64_t base, int bytes, int voff, int soff, unsigned dst)
 {
     const i32x4 rsrc = {(int)(uint32_t)base, (int)((uint32_t)(base >> 32) & 0xffffu), bytes, 0x00020000};
 #if defined(__HIP_DEVICE_COMPILE__)
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :
-                 : "s"(dst), "v"(voff), "s"(rsrc), "s"(soff)
-                 : "memory", "m0");
+    if constexpr (FMT == 5)
+        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx3 %1, %2, %3 offen lds"
+                     :
+                     : "s"(dst), "v"(voff), "s"(rsrc), "s"(soff)
+                     : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :
+                     : "s"(dst), "v"(voff), "s"(rsrc), "s"(soff)
+                     : "memory", "m0");
 #else
     (void)rsrc; (void)voff; (void)soff; (void)dst;
 #endif
@@ -70,29 +80,47 @@ struct BigSource {
     int bytes;           // nb * nb, or 0 past the end of the reduction
     int c;               // chunk index in that product
 };
+template <int FMT>
 __device__ __forceinline__ void big_request(const BigSource &S, const BigGeom &BG, int stage, int j)
 {
     const int op = j >> 3, jj = j & 7;
     int cc = S.c + BG.rot;
     if (cc >= BG.n) cc -= BG.n;
-    big_dma_one(op ? S.b : S.a, S.bytes, BG.voff[op][jj & 1], uni(cc * kRowBytes + jj * BG.rows8),
+    constexpr int kChunkBytes = FMT == 5 ? 96 : kRowBytes;   // bytes of a tile row per chunk
+    big_dma_one<FMT>(op ? S.b : S.a, S.bytes, BG.voff[op][jj & 1], uni(cc * kChunkBytes + jj * BG.rows8),
                 BG.dst + (unsigned)(stage * kBigStage + op * kBigOperand + jj * 1024));
 }
-// Fragment t (0..3: A blocks of 32 rows, 4..7: B blocks) of half `hc` of the chunk in `stage`.
+// One 16-byte half (w) of fragment t (0..3: A blocks of 32 rows, 4..7: B blocks) of half `hc` of the
+// chunk in `stage`, into its place in the fragment.  FMT 5: the 12 bytes in use of
+// the slot; the two halves make the 24 bytes of the lane's block of 32 six-bit elements.
+struct __attribute__((aligned(16))) Words3 { uint32_t x, y, z; };
+template <int FMT>
+__device__ __forceinline__ void big_read_half(i8v &f, const BigGeom &BG, const char *lds, int stage, int hc, int t, int w)
+{
+    const char *p = lds + (t < 4 ? BG.ra[stage][hc][w] : BG.rb[stage][hc][w]) + (t & 3) * (32 * kRowBytes);
+    if constexpr (FMT == 5) {
+        const Words3 v = *(const Words3 *)p;
+        f[3 * w] = (int)v.x; f[3 * w + 1] = (int)v.y; f[3 * w + 2] = (int)v.z;
+    } else {
+        const u32x4 v = *(const u32x4 *)p;
+        f[4 * w] = (int)v.x; f[4 * w + 1] = (int)v.y; f[4 * w + 2] = (int)v.z; f[4 * w + 3] = (int)v.w;
+    }
+}
+
+// The whole fragment.
+template <int FMT>
 __device__ __forceinline__ i8v big_read(const BigGeom &BG, const char *lds, int stage, int hc, int t)
 {
+    if constexpr (FMT == 5) {
+        i8v f = {};
+        big_read_half<FMT>(f, BG, lds, stage, hc, t, 0);
+        big_read_half<FMT>(f, BG, lds, stage, hc, t, 1);
+        return f;
+    }
     const char *p0 = lds + (t < 4 ? BG.ra[stage][hc][0] : BG.rb[stage][hc][0]) + (t & 3) * (32 * kRowBytes);
     const char *p1 = lds + (t < 4 ? BG.ra[stage][hc][1] : BG.rb[stage][hc][1]) + (t & 3) * (32 * kRowBytes);
     const u32x4 lo = *(const u32x4 *)p0, hi = *(const u32x4 *)p1;
     return i8v{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
-}
-
-// One 16-byte half (w) of the same, into its place in the fragment.
-__device__ __forceinline__ void big_read_half(i8v &f, const BigGeom &BG, const char *lds, int stage, int hc, int t, int w)
-{
-    const char *p = lds + (t < 4 ? BG.ra[stage][hc][w] : BG.rb[stage][hc][w]) + (t & 3) * (32 * kRowBytes);
-    const u32x4 v = *(const u32x4 *)p;
-    f[4 * w] = (int)v.x; f[4 * w + 1] = (int)v.y; f[4 * w + 2] = (int)v.z; f[4 * w + 3] = (int)v.w;
 }
 
 // Block scales of an MXFP8 chunk: per A row block (0..3) and B row block (4..7) the four scale
@@ -186,20 +214,21 @@ template <int STAGE, int FMT, bool TAKE, int SO>
 __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], const BigGeom &BG, const char *lds, const BigSource &S2,
                                           int sa, int sb, const int (&sc)[32], const int (&raw)[32], int (&nx)[32], int shift)
 {
-    constexpr bool MX = FMT == 1;
+    constexpr bool MX = FMT == 1 || FMT == 5;
+    constexpr int EL = FMT == 5 ? 2 : 0;                     // element format of the instruction: e4m3, or e2m3
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
-            if constexpr (FMT >= 3) {
+            if constexpr (FMT == 3 || FMT == 4) {
                 acc[mt][nt] = big_mfma16<FMT>(f[0][mt], f[0][4 + nt], acc[mt][nt], 0);
                 acc[mt][nt] = big_mfma16<FMT>(f[0][mt], f[0][4 + nt], acc[mt][nt], 1);
             } else if constexpr (FMT == 2) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[0][mt], 0), big_fp4_operand(f[0][4 + nt], 0), acc[mt][nt], 4, 4, 0, sc[SO + mt], 0, sc[SO + 4 + nt]);
-            else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sc[SO + mt], 0, sc[SO + 4 + nt]);
+            else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], EL, EL, 0, sc[SO + mt], 0, sc[SO + 4 + nt]);
             else acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
             SCHED_FENCE();
             const int k = mt * 4 + nt;                       // second half's fragments, 16 bytes per position: B first
-            big_read_half(f[1][((k >> 1) + 4) & 7], BG, lds, STAGE, 1, ((k >> 1) + 4) & 7, k & 1);
+            big_read_half<FMT>(f[1][((k >> 1) + 4) & 7], BG, lds, STAGE, 1, ((k >> 1) + 4) & 7, k & 1);
             SCHED_FENCE();
         }
     if constexpr (FMT == 2) {
@@ -226,16 +255,16 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
-            if constexpr (FMT >= 3) {
+            if constexpr (FMT == 3 || FMT == 4) {
                 acc[mt][nt] = big_mfma16<FMT>(f[1][mt], f[1][4 + nt], acc[mt][nt], 0);
                 acc[mt][nt] = big_mfma16<FMT>(f[1][mt], f[1][4 + nt], acc[mt][nt], 1);
             } else if constexpr (FMT == 2) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[1][mt], 0), big_fp4_operand(f[1][4 + nt], 0), acc[mt][nt], 4, 4, 0, sc[SO + 8 + mt], 0, sc[SO + 12 + nt]);
-            else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 2, sc[SO + mt], 2, sc[SO + 4 + nt]);
+            else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], EL, EL, 2, sc[SO + mt], 2, sc[SO + 4 + nt]);
             else acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
             SCHED_FENCE();
             const int k = mt * 4 + nt;
-            big_read_half(f[0][((k >> 1) + 4) & 7], BG, lds, STAGE ^ 1, 0, ((k >> 1) + 4) & 7, k & 1);
-            big_request(S2, BG, STAGE, k);
+            big_read_half<FMT>(f[0][((k >> 1) + 4) & 7], BG, lds, STAGE ^ 1, 0, ((k >> 1) + 4) & 7, k & 1);
+            big_request<FMT>(S2, BG, STAGE, k);
             SCHED_FENCE();
         }
     if constexpr (FMT == 2) {
@@ -254,6 +283,10 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
 // FMT 2: MXFP4 tiles: half a byte per element, so a tile row is nb / 2 bytes and a chunk (128
 // bytes of each row) 256 reduction indices; a lane's 16 bytes per reduction step are one block of
 // 32 elements, scaled by that lane's own byte, and the fragment reads are those of FMT 1.
+// FMT 5: MXFP6 tiles: 24 bytes per block of 32 six-bit elements, a tile row is 3 nb / 4 bytes and a
+// chunk 96 bytes of each row = 128 reduction indices, in eight 12-byte pieces that land in the eight
+// 16-byte slots of the row's LDS line; a lane's operand of a 64-index step is the block 32 (lane / 32)
+// ... of the step, two neighbouring pieces, scaled by that lane's own byte (as for FMT 2).
 template <int FMT>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
@@ -266,8 +299,10 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     const int tileC = (int)(uint32_t)itw;
     const ArgsPtr K0 = args();
     const int nb = K0->nb, kt = K0->kt_eff;
-    constexpr bool MX = FMT == 1 || FMT == 2;
-    const int pitch = FMT == 2 ? nb / 2 : FMT >= 3 ? 2 * nb : nb;   // bytes of a tile row
+    constexpr bool MX = FMT == 1 || FMT == 2 || FMT == 5;
+    constexpr int kPiece = FMT == 5 ? 12 : 16;               // bytes a lane moves per DMA instruction
+    constexpr int kChunkBytes = 8 * kPiece;                  // bytes of a tile row per chunk
+    const int pitch = FMT == 5 ? (nb >> 2) * 3 : FMT == 2 ? nb / 2 : (FMT == 3 || FMT == 4) ? 2 * nb : nb;   // bytes of a tile row
     const int arow0 = (int)((itw >> 32) & 0xffffu) * kBigMacro, brow0 = (int)((itw >> 48) & 0xffffu) * kBigMacro;
     const ProductDesc *prod = K0->prod + (int64_t)tileC * K0->KT;
 
@@ -275,13 +310,13 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     {
         const int r = lane >> 3, slot = lane & 7;
         const int seg = slot ^ (r >> 1);                     // instruction 0; odd instructions: ^ 4
-        BG.voff[0][0] = (arow0 + wave * 64 + r) * pitch + seg * 16;
-        BG.voff[1][0] = (brow0 + wave * 64 + r) * pitch + seg * 16;
-        BG.voff[0][1] = BG.voff[0][0] ^ 64;
-        BG.voff[1][1] = BG.voff[1][0] ^ 64;
+        BG.voff[0][0] = (arow0 + wave * 64 + r) * pitch + seg * kPiece;
+        BG.voff[1][0] = (brow0 + wave * 64 + r) * pitch + seg * kPiece;
+        BG.voff[0][1] = (arow0 + wave * 64 + r) * pitch + (seg ^ 4) * kPiece;
+        BG.voff[1][1] = (brow0 + wave * 64 + r) * pitch + (seg ^ 4) * kPiece;
         BG.dst = (unsigned)uni(wave * (64 * kRowBytes));
         BG.rows8 = 8 * pitch;
-        BG.n = pitch / kRowBytes;
+        BG.n = pitch / kChunkBytes;
         // Regions of one C tile run side by side on one XCD and would otherwise ask its L2 for the
         // same 128-byte column of every panel row at the same time; each starts its pass over a
         // product's chunks at its own (even) chunk instead.
@@ -293,7 +328,7 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
             for (int hc = 0; hc < 2; ++hc)
 #pragma unroll
                 for (int w = 0; w < 2; ++w) {
-                    const int slot_r = (MX ? 4 * hc + g + 2 * w : 4 * hc + 2 * g + w) ^ x;
+                    const int slot_r = ((FMT == 1 || FMT == 2) ? 4 * hc + g + 2 * w : 4 * hc + 2 * g + w) ^ x;
                     BG.ra[st][hc][w] = st * kBigStage + (wm * 128 + i) * kRowBytes + slot_r * 16;
                     BG.rb[st][hc][w] = st * kBigStage + kBigOperand + (wn * 128 + i) * kRowBytes + slot_r * 16;
                 }
@@ -309,7 +344,7 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     }
 
     f16v acc[4][4];
-    const int n = pitch / kRowBytes;                         // chunks per product: even (the host sees to that)
+    const int n = pitch / kChunkBytes;                       // chunks per product: even (the host sees to that)
     const int tile_bytes = nb * pitch;
 
     // FP16 tiles carry a power-of-two scale each, so the terms of product L count in units of
@@ -341,17 +376,17 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
             S.bytes = tile_bytes;
             S.c = 0;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) big_request(S, BG, 0, j);
+            for (int j = 0; j < 16; ++j) big_request<FMT>(S, BG, 0, j);
             S.c = 1;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) big_request(S, BG, 1, j);
+            for (int j = 0; j < 16; ++j) big_request<FMT>(S, BG, 1, j);
 #if defined(__HIP_DEVICE_COMPILE__)
             asm volatile("s_waitcnt vmcnt(16)" ::: "memory");    // chunk 0 has landed
 #endif
             __syncthreads();
             i8v f[2][8];
 #pragma unroll
-            for (int t = 0; t < 8; ++t) f[0][t] = big_read(BG, lds, 0, 0, t);
+            for (int t = 0; t < 8; ++t) f[0][t] = big_read<FMT>(BG, lds, 0, 0, t);
             int sc[32], nsc[32];
 #pragma unroll
             for (int t = 0; t < 32; ++t) sc[t] = nsc[t] = 0;

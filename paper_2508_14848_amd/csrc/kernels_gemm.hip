@@ -80,6 +80,27 @@ __global__ __launch_bounds__(256) void convert_tiles_kernel(const ConvertJob *__
         *(u32x4 *)((char *)(uintptr_t)job.dst + (uint64_t)seg * 16) = o;
         return;
     }
+    if (p == GEMM_MP_MXFP6) {
+        // MXFP6 tile to FP32 / FP64: e2m3 element times the scale of its block of 32 (exact); four
+        // six-bit codes fill three bytes
+        const uint8_t *sb = (const uint8_t *)(uintptr_t)job.src;
+        const uint64_t elems = (uint64_t)job.n16 * (q == Q32 ? 4u : 2u);         // nb * nb
+        const uint64_t idx = (uint64_t)seg * (q == Q32 ? 4u : 2u);                // first element of this segment: even
+        const int sc = (int)sb[elems / 4 * 3 + (idx >> 5)] - 127;
+        const uint8_t *b3 = sb + (idx >> 2) * 3;
+        const uint32_t w = (b3[0] | ((uint32_t)b3[1] << 8) | ((uint32_t)b3[2] << 16)) >> (6 * (int)(idx & 3));
+        float v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v[k] = ldexpf(fp6_value((w >> (6 * k)) & 63u), sc);
+        u32x4 o;
+        if (q == Q32) o = u32x4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+        else {
+            const u32x2 a = dbits((double)v[0]), b = dbits((double)v[1]);
+            o = u32x4{a.x, a.y, b.x, b.y};
+        }
+        *(u32x4 *)((char *)(uintptr_t)job.dst + (uint64_t)seg * 16) = o;
+        return;
+    }
     if (p == GEMM_MP_MXFP8) {
         // MXFP8 tile to FP32 / FP64: element times the scale of its block of 32 (exact)
         const uint8_t *sb = (const uint8_t *)(uintptr_t)job.src;
@@ -152,9 +173,9 @@ hipError_t launch_convert(const ConvertJob *jobs_dev, int njobs, uint32_t max_n1
 
 hipError_t gemm_kernel_setup()
 {
-    hipError_t (*const setups[11])() = {setup_owner_d, setup_owner_d_mixed, setup_owner_d_bf, setup_owner_f, setup_owner_f_mixed,
+    hipError_t (*const setups[12])() = {setup_owner_d, setup_owner_d_mixed, setup_owner_d_bf, setup_owner_f, setup_owner_f_mixed,
                                         setup_owner_f_bf, setup_region_fp8, setup_region_mxfp8, setup_region_mxfp4, setup_region_fp16,
-                                        setup_region_bf16};
+                                        setup_region_bf16, setup_region_mxfp6};
     for (auto f : setups) {
         const hipError_t e = f();
         if (e != hipSuccess) return e;
@@ -163,7 +184,8 @@ hipError_t gemm_kernel_setup()
 }
 
 // The product table, then one launch per kind of C tile: the owner regions of FP64 C tiles, those
-// of FP32 C tiles, and the large regions of FP32 C tiles made of FP8 / MXFP8 / MXFP4 / FP16 / BF16 products only.
+// of FP32 C tiles, and the large regions of FP32 C tiles made of FP8 / MXFP8 / MXFP4 / FP16 / BF16 / MXFP6
+// products only.
 // The kinds touch disjoint C tiles and only read A, B and the tables, so they may run side by side:
 // with `lanes` the first kind stays on the caller's stream and every further one goes to a side
 // stream of its own, forked off behind the product table and joined again before the call
@@ -182,15 +204,16 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s, const LaunchLanes *lane
     };
     // BF16 tiles among the operands: the instances that know the BF16 matrix instruction; FP16 /
     // BF16 products with an FP8 operand: the instances whose DMA ring takes them
-    const Kind all[7] = {
+    const Kind all[8] = {
         {a.bf16 ? launch_owner_d_bf : a.mixed64 ? launch_owner_d_mixed : launch_owner_d, a.items64, a.n_items64},
         {a.bf16 ? launch_owner_f_bf : a.mixed32 ? launch_owner_f_mixed : launch_owner_f, a.items32, a.n_items32},
         {launch_region_fp8, a.items8, a.n_items8},
         {launch_region_mxfp8, a.items_mx, a.n_items_mx},
         {launch_region_mxfp4, a.items_mx4, a.n_items_mx4},
         {launch_region_fp16, a.items_h, a.n_items_h},
-        {launch_region_bf16, a.items_bf, a.n_items_bf}};
-    Kind kinds[7];
+        {launch_region_bf16, a.items_bf, a.n_items_bf},
+        {launch_region_mxfp6, a.items_mx6, a.n_items_mx6}};
+    Kind kinds[8];
     int n = 0;
     for (const Kind &k : all)
         if (k.n > 0) kinds[n++] = k;

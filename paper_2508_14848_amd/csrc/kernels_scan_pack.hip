@@ -219,6 +219,18 @@ __device__ inline uint32_t to_fp4_bits(double x, int e)
     return r ? (sign | r) : sign;
 }
 
+// FP6 e2m3 (3 fraction bits, smallest normal 1, largest 7.5; no infinity or NaN codes, as FP4).
+__device__ inline uint32_t to_fp6_bits(double x, int e)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(x);
+    const uint32_t sign = (uint32_t)(b >> 58) & 0x20u;
+    const uint64_t mag = b & 0x7fffffffffffffffull;
+    if (mag > 0x7ff0000000000000ull) return 0;                 // NaN has no code
+    if (mag == 0x7ff0000000000000ull) return sign | 31u;
+    uint32_t r = round_magnitude<3, 0, 1>(mag, e);
+    if (r > 31u) r = 31u;                                      // beyond 7.5 -> 7.5
+    return sign | r;
+}
 // The stored bit pattern of one element, right-aligned in 64 bits.
 __device__ inline uint64_t stored_bits(double x, int p, int e)
 {
@@ -324,21 +336,22 @@ hipError_t launch_pack(const double *X, int64_t ld, int64_t rows, int64_t cols, 
     return hipGetLastError();
 }
 
-// Block-scaled tiles (MXFP8, MXFP4: the formats of the OCP microscaling specification): per block
+// Block-scaled tiles (MXFP8, MXFP4, MXFP6: the formats of the OCP microscaling specification): per block
 // of 32 consecutive reduction indices of one packed row (a row of an A tile, a column of a B
-// tile) a scale 2^s, s = floor(log2 max|x|) - 8 (e4m3 elements) or - 2 (e2m1) within [-127, 127]
+// tile) a scale 2^s, s = floor(log2 max|x|) - 8 (e4m3 elements) or - 2 (e2m1, e2m3) within [-127, 127]
 // (0 for a zero block or a non-finite maximum); elements x * 2^-s rounded once, saturating; the
 // scale bytes (s + 127) follow the tile's element bytes, nb / 32 per packed row.  Entries outside
 // the rows x cols matrix count as zeros.
-// Scale exponent of a block from its largest magnitude (fp4: e2m1 elements, else e4m3).
-__device__ inline int mx_block_exponent(double m, bool fp4)
+// Scale exponent of a block from its largest magnitude (narrow: e2m1 or e2m3 elements, whose
+// largest binade is 4 .. 8; else e4m3).
+__device__ inline int mx_block_exponent(double m, bool narrow)
 {
     const uint64_t bits = (uint64_t)__double_as_longlong(m);
     const int field = (int)(bits >> 52);
     const uint64_t man = bits & 0xfffffffffffffull;
     if (field == 0x7ff || bits == 0) return 0;
     const int lg = field ? field - 1023 : 63 - __builtin_clzll(man) - 1074;
-    const int s = lg - (fp4 ? 2 : 8);                            // exponent of the element format's largest binade
+    const int s = lg - (narrow ? 2 : 8);                            // exponent of the element format's largest binade
     return s < -127 ? -127 : s > 127 ? 127 : s;
 }
 
@@ -351,7 +364,7 @@ __global__ __launch_bounds__(256) void pack_mx_kernel(const double *__restrict__
     const int tile = (int)(blockIdx.x / per_tile);
     const int p = v.prec[tile];
     if (!is_block_scaled(p)) return;
-    const bool fp4 = p == GEMM_MP_MXFP4;
+    const bool fp4 = p == GEMM_MP_MXFP4, fp6 = p == GEMM_MP_MXFP6;
     const int I = tile / cols_t, J = tile % cols_t;
     const int per_row = nb / 32;
     const int idx = (int)(blockIdx.x % per_tile) * 256 + threadIdx.x;   // (block, packed row): nb * nb / 32 of them, a multiple of 256
@@ -365,8 +378,22 @@ __global__ __launch_bounds__(256) void pack_mx_kernel(const double *__restrict__
         const double a = __builtin_fabs(x[k]);
         if (a > m) m = a;                                        // a NaN never enters m
     }
-    const int s = mx_block_exponent(m, fp4);
+    const int s = mx_block_exponent(m, fp4 || fp6);
     char *base = v.storage + v.offset[tile];
+    if (fp6) {                                                   // 32 six-bit codes in 24 bytes, code k at bits 6k .. 6k+5
+        uint64_t w[3] = {0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            const uint64_t code = to_fp6_bits(x[k], s);
+            w[(6 * k) / 64] |= code << ((6 * k) % 64);
+            if ((6 * k) % 64 > 58) w[(6 * k) / 64 + 1] |= code >> (64 - (6 * k) % 64);
+        }
+        uint2 *dst = (uint2 *)(base + ((int64_t)u * nb + 32 * kb) / 4 * 3);
+#pragma unroll
+        for (int j = 0; j < 3; ++j) dst[j] = make_uint2((uint32_t)w[j], (uint32_t)(w[j] >> 32));
+        ((uint8_t *)base)[(int64_t)nb * nb / 4 * 3 + (int64_t)u * per_row + kb] = (uint8_t)(s + 127);
+        return;
+    }
     if (fp4) {                                                   // two elements a byte, the lower index in the low four bits
         uint32_t w[4] = {0, 0, 0, 0};
 #pragma unroll
@@ -395,7 +422,7 @@ __global__ __launch_bounds__(256) void pack_mx_rows_kernel(const double *__restr
     const int tile = (int)(blockIdx.x / per_tile);
     const int p = v.prec[tile];
     if (!is_block_scaled(p)) return;
-    const bool fp4 = p == GEMM_MP_MXFP4;
+    const bool fp4 = p == GEMM_MP_MXFP4, fp6 = p == GEMM_MP_MXFP6;
     const int I = tile / cols_t, J = tile % cols_t;
     const int per_row = nb / 32;
     const int gidx = (int)(blockIdx.x % per_tile) * 256 + threadIdx.x;   // (block, quarter of eight): nb * nb / 4 of them
@@ -415,8 +442,15 @@ __global__ __launch_bounds__(256) void pack_mx_rows_kernel(const double *__restr
         const double o = __shfl_xor(m, d);
         if (o > m) m = o;
     }
-    const int s = mx_block_exponent(m, fp4);
+    const int s = mx_block_exponent(m, fp4 || fp6);
     char *base = v.storage + v.offset[tile];
+    if (fp6) {                                                   // four codes = three bytes
+        const uint32_t w = to_fp6_bits(x[0], s) | (to_fp6_bits(x[1], s) << 6) | (to_fp6_bits(x[2], s) << 12) | (to_fp6_bits(x[3], s) << 18);
+        uint8_t *d = (uint8_t *)base + ((int64_t)u * nb + 32 * kb) / 4 * 3 + 3 * sub;
+        d[0] = (uint8_t)w; d[1] = (uint8_t)(w >> 8); d[2] = (uint8_t)(w >> 16);
+        if (sub == 0) ((uint8_t *)base)[(int64_t)nb * nb / 4 * 3 + (int64_t)u * per_row + kb] = (uint8_t)(s + 127);
+        return;
+    }
     if (fp4) {
         const uint32_t w = to_fp4_bits(x[0], s) | (to_fp4_bits(x[1], s) << 4) | (to_fp4_bits(x[2], s) << 8) | (to_fp4_bits(x[3], s) << 12);
         *(uint16_t *)(base + ((int64_t)u * nb + 32 * kb) / 2 + 2 * sub) = (uint16_t)w;
@@ -464,6 +498,12 @@ __device__ inline double stored_value(const char *base, int64_t idx, int p, int 
         const int ef = (code >> 1) & 3, mf = code & 1;
         const double mag = ef ? ldexp(1.0 + 0.5 * mf, ef - 1) : 0.5 * mf;
         return ldexp((code & 8) ? -mag : mag, sc - 127);
+    }
+    case GEMM_MP_MXFP6: {
+        const int64_t at = (idx >> 2) * 3;                        // four codes = three bytes
+        const uint32_t w = ((const uint8_t *)base)[at] | ((uint32_t)((const uint8_t *)base)[at + 1] << 8) | ((uint32_t)((const uint8_t *)base)[at + 2] << 16);
+        const int sc = ((const uint8_t *)base)[(int64_t)nb * nb / 4 * 3 + (idx >> 5)];
+        return ldexp((double)fp6_value((w >> (6 * (int)(idx & 3))) & 63u), sc - 127);
     }
     case GEMM_MP_FP64: return ((const double *)base)[idx];
     case GEMM_MP_FP32: return (double)((const float *)base)[idx];
@@ -558,6 +598,11 @@ __global__ __launch_bounds__(256) void low_expand_kernel(const LowTile *__restri
             const uint2 h = *(const uint2 *)(src + i * 2);
             x = make_float4(__uint_as_float(h.x << 16), __uint_as_float(h.x & 0xffff0000u),
                             __uint_as_float(h.y << 16), __uint_as_float(h.y & 0xffff0000u));
+        } else if (p == GEMM_MP_MXFP6) {                       // four codes = three bytes, in one block of 32
+            const uint8_t *b3 = (const uint8_t *)src + i / 4 * 3;
+            const uint32_t b = b3[0] | ((uint32_t)b3[1] << 8) | ((uint32_t)b3[2] << 16);
+            x = make_float4(fp6_value(b & 63u), fp6_value((b >> 6) & 63u), fp6_value((b >> 12) & 63u), fp6_value((b >> 18) & 63u));
+            e = (int)((const uint8_t *)src)[(int64_t)nb * nb / 4 * 3 + (i >> 5)] - 127;
         } else if (p == GEMM_MP_MXFP4) {                       // the four entries share one block of 32
             const uint32_t b = *(const uint16_t *)(src + i / 2);
             float m[4];
@@ -661,7 +706,7 @@ __global__ __launch_bounds__(256) void low_round_kernel(const LowTile *__restric
         const float4 x = *(const float4 *)(src + i);
         if (is_block_scaled(p)) {                            // uniform over the workgroup
             // eight neighbouring lanes hold one block of 32 along a row of the tile
-            const bool fp4 = p == GEMM_MP_MXFP4;
+            const bool fp4 = p == GEMM_MP_MXFP4, fp6 = p == GEMM_MP_MXFP6;
             float m = __builtin_fabsf(x.x);
             const float a[3] = {__builtin_fabsf(x.y), __builtin_fabsf(x.z), __builtin_fabsf(x.w)};
             if (!(m == m)) m = 0.0f;                         // a NaN never enters m
@@ -673,8 +718,14 @@ __global__ __launch_bounds__(256) void low_round_kernel(const LowTile *__restric
                 const float o = __shfl_xor(m, d);
                 if (o > m) m = o;
             }
-            const int s = mx_block_exponent((double)m, fp4);
-            if (fp4) {
+            const int s = mx_block_exponent((double)m, fp4 || fp6);
+            if (fp6) {
+                const uint32_t w = to_fp6_bits((double)x.x, s) | (to_fp6_bits((double)x.y, s) << 6) |
+                                   (to_fp6_bits((double)x.z, s) << 12) | (to_fp6_bits((double)x.w, s) << 18);
+                uint8_t *d = (uint8_t *)dst + i / 4 * 3;
+                d[0] = (uint8_t)w; d[1] = (uint8_t)(w >> 8); d[2] = (uint8_t)(w >> 16);
+                if ((threadIdx.x & 7) == 0) ((uint8_t *)dst)[(int64_t)nb * nb / 4 * 3 + (i >> 5)] = (uint8_t)(s + 127);
+            } else if (fp4) {
                 const uint32_t w = to_fp4_bits((double)x.x, s) | (to_fp4_bits((double)x.y, s) << 4) |
                                    (to_fp4_bits((double)x.z, s) << 8) | (to_fp4_bits((double)x.w, s) << 12);
                 *(uint16_t *)(dst + i / 2) = (uint16_t)w;

@@ -91,7 +91,7 @@ class DeviceGemmMP:
         """Raw stored bytes of one tile as a uint8 host array (for bit-exact checks)."""
         off, prec, _ = self.ctx.tile_info(which, I, J, want_exp=False)
         e = self.ctx.nb * self.ctx.nb
-        n = {4: 2 * e, 5: e + e // 32, 6: e // 2 + e // 32}.get(prec, e * (8 >> min(prec, 3)))   # MX: block scales follow the elements
+        n = {4: 2 * e, 5: e + e // 32, 6: e // 2 + e // 32, 7: e // 4 * 3 + e // 32}.get(prec, e * (8 >> min(prec, 3)))   # MX: block scales follow the elements
         torch.cuda.synchronize()
         return self.storage[which][off:off + n].cpu().numpy(), prec
 

@@ -14,7 +14,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgemm_mp.so")
 
-FP64, FP32, FP16, FP8_E4M3, BF16, MXFP8, MXFP4 = 0, 1, 2, 3, 4, 5, 6
+FP64, FP32, FP16, FP8_E4M3, BF16, MXFP8, MXFP4, MXFP6 = 0, 1, 2, 3, 4, 5, 6, 7
 POLICY_OPERAND, POLICY_C_TILE = 0, 1
 OK, EINVAL, ESTATE, ENOMEM, EUNSUPPORTED, EHIP, ETOOBIG = 0, -1, -2, -3, -4, -5, -6
 STATIC_MAX_PRODUCTS = 65536
@@ -37,7 +37,8 @@ class Stats(ctypes.Structure):
                 ("flops_bf16", ctypes.c_double), ("tiles_bf16", ctypes.c_int64 * 3),
                 ("products_mxfp8", ctypes.c_int64), ("flops_mxfp8", ctypes.c_double), ("tiles_mxfp8", ctypes.c_int64 * 3),
                 ("products_mxfp4", ctypes.c_int64), ("flops_mxfp4", ctypes.c_double), ("tiles_mxfp4", ctypes.c_int64 * 3),
-                ("launch_items", ctypes.c_int64 * 8), ("owner_instance", ctypes.c_int32 * 2)]
+                ("launch_items", ctypes.c_int64 * 8), ("owner_instance", ctypes.c_int32 * 2),
+                ("products_mxfp6", ctypes.c_int64), ("flops_mxfp6", ctypes.c_double), ("tiles_mxfp6", ctypes.c_int64 * 3)]
 
 
 class GemmMPError(RuntimeError):
@@ -216,4 +217,5 @@ class GemmMP:
                 "flops_bf16": s.flops_bf16, "tiles_bf16": list(s.tiles_bf16), "products_mxfp8": s.products_mxfp8,
                 "flops_mxfp8": s.flops_mxfp8, "tiles_mxfp8": list(s.tiles_mxfp8), "products_mxfp4": s.products_mxfp4,
                 "flops_mxfp4": s.flops_mxfp4, "tiles_mxfp4": list(s.tiles_mxfp4),
+                "products_mxfp6": s.products_mxfp6, "flops_mxfp6": s.flops_mxfp6, "tiles_mxfp6": list(s.tiles_mxfp6),
                 "launch_items": list(s.launch_items), "owner_instance": list(s.owner_instance)}

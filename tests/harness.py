@@ -1,6 +1,6 @@
 """Shared set-up for the GPU parity tests: run one workload through the oracle and through the
 C ABI on the same seeded inputs.  The oracle's side and the tolerances live in oracle/checker.py."""
-from oracle.checker import (BF16, FP8, FP16, FP32, FP64, LOW_FORMAT, MXFP4, MXFP8, U, OracleSide, compare_jobs,  # noqa: F401
+from oracle.checker import (BF16, FP8, FP16, FP32, FP64, LOW_FORMAT, MXFP4, MXFP6, MXFP8, U, OracleSide, compare_jobs,  # noqa: F401
                             finish_low_c_tiles, job_tolerances, packed_codes_expected)
 
 

@@ -62,7 +62,7 @@ def test_map_validation_and_call_order():
         g.set_precision_map("A", np.zeros((3, 4), np.uint16))          # A is 4 x 3 tiles
     assert e.value.status == G.EINVAL
     with pytest.raises(G.GemmMPError) as e:
-        g.set_precision_map("A", np.full((4, 3), 7, np.uint16))        # code out of range
+        g.set_precision_map("A", np.full((4, 3), 8, np.uint16))        # code out of range
     assert e.value.status == G.EINVAL
     with pytest.raises(G.GemmMPError) as e:
         g.set_precision_map("X", np.zeros((4, 3), np.uint16))
@@ -200,6 +200,18 @@ def test_mxfp8_codes_layout_and_where_this_build_runs_them():
     st = g.get_stats()
     assert st["products_mxfp4"] == 12 and st["tiles_mxfp4"] == [6, 6, 0] and st["work_items"] == 4 * (nb // 256) ** 2
     assert g.conversion_bytes() == 0
+    # MXFP6 (code 7): three quarters of a byte per element; block-scaled kernel at multiples of 256
+    g.set_precision_map("A", np.full((2, 3), G.MXFP6, dtype=np.uint16))
+    g.set_precision_map("B", np.full((3, 2), G.MXFP6, dtype=np.uint16))
+    assert g.storage_bytes("A") == 6 * (nb * nb * 3 // 4 + nb * nb // 32)
+    o, prec, _ = g.tile_info("A", 1, 0, want_exp=False)
+    assert o == 3 * (nb * nb * 3 // 4 + nb * nb // 32) and prec == G.MXFP6
+    st = g.get_stats()
+    assert st["products_mxfp6"] == 12 and st["tiles_mxfp6"] == [6, 6, 0] and st["work_items"] == 4 * (nb // 256) ** 2
+    assert st["launch_items"] == [0, 0, 0, 0, 0, 0, 0, st["work_items"]] and st["flops_mxfp6"] == 12 * 2.0 * nb ** 3
+    assert g.conversion_bytes() == 0
+    g.set_precision_map("A", np.full((2, 3), G.MXFP4, dtype=np.uint16))
+    g.set_precision_map("B", np.full((3, 2), G.MXFP4, dtype=np.uint16))
     g.set_precision_map("B", np.full((3, 2), G.MXFP8, dtype=np.uint16))      # MXFP4 with MXFP8: FP32 on copies of both
     assert g.get_stats()["products"] == [0, 12, 0, 0] and g.conversion_bytes() == 12 * nb * nb * 4
     g.destroy()

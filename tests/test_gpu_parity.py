@@ -9,7 +9,7 @@ import pytest
 import workloads as W
 from oracle import gemm_mp_oracle as orc
 from oracle.checker import planted_mistake_is_caught
-from tests.harness import (BF16, FP8, FP16, FP32, FP64, MXFP4, MXFP8, OracleSide, compare_jobs, finish_low_c_tiles, gpu_problem,
+from tests.harness import (BF16, FP8, FP16, FP32, FP64, MXFP4, MXFP6, MXFP8, OracleSide, compare_jobs, finish_low_c_tiles, gpu_problem,
                            packed_codes_expected)
 
 pytestmark = pytest.mark.gpu
@@ -556,7 +556,7 @@ def test_c_tiles_stored_in_fp16_and_fp8_match_the_oracle_on_general_data():
 
 
 def test_c_tiles_stored_in_block_scaled_formats():
-    """C tiles in MXFP8 / MXFP4: accumulated in FP32 staging copies like the other narrow C tiles,
+    """C tiles in MXFP8 / MXFP4 / MXFP6: accumulated in FP32 staging copies like the other narrow C tiles,
     then stored block by block along the rows of the tile.  Small integers (|x| <= 3 fits both
     element formats at every block maximum) must come back exactly, old C included; general data
     must match the oracle's stored result per tile, and what the GPU stored must be a fixed point
@@ -574,10 +574,10 @@ def test_c_tiles_stored_in_block_scaled_formats():
         C0 = rng.integers(-1, 2, (M, N)).astype(np.float64)
         M, N, K = M - cut[0], N - cut[1], K - cut[2]
         A, B, C0 = A[:M, :K], B[:K, :N], C0[:M, :N]
-        mA = rng.integers(0, 7, (MT, KT)).astype(np.uint16)
-        mB = rng.integers(0, 7, (KT, NT)).astype(np.uint16)
-        mC = rng.integers(0, 7, (MT, NT)).astype(np.uint16)
-        mC[0, 0], mC[MT - 1, NT - 1] = MXFP8, MXFP4
+        mA = rng.integers(0, 8, (MT, KT)).astype(np.uint16)
+        mB = rng.integers(0, 8, (KT, NT)).astype(np.uint16)
+        mC = rng.integers(0, 8, (MT, NT)).astype(np.uint16)
+        mC[0, 0], mC[MT - 1, NT - 1], mC[0, 1] = MXFP8, MXFP4, MXFP6
         if nb == 512:
             mA[0, :], mB[:, 0], mA[1, :], mB[:, 1] = MXFP8, MXFP8, MXFP4, MXFP4   # C(0,0), C(1,1) on the block-scaled kernel
         want = (A.astype(np.int64) @ B.astype(np.int64)) + 2 * C0.astype(np.int64)
@@ -599,8 +599,8 @@ def test_c_tiles_stored_in_block_scaled_formats():
         torch.cuda.synchronize()
 
     w = W.tiny()
-    w.mapC = rng.integers(0, 7, w.mapC.shape).astype(np.uint16)
-    w.mapC[0, :4] = (MXFP8, MXFP4, FP16, MXFP8)
+    w.mapC = rng.integers(0, 8, w.mapC.shape).astype(np.uint16)
+    w.mapC[0, :4] = (MXFP8, MXFP4, MXFP6, MXFP8)
     w.alpha, w.beta = 0.75, -1.25
     _say("block-scaled C tiles, general data")
     A, B, C0 = _dense(w)
@@ -616,7 +616,7 @@ def test_c_tiles_stored_in_block_scaled_formats():
     again, _ = finish_low_c_tiles(side, C_gpu)
     for I in range(w.MT):
         for J in range(w.NT):
-            if w.mapC[I, J] in (MXFP8, MXFP4):
+            if w.mapC[I, J] in (MXFP8, MXFP4, MXFP6):
                 blk = (slice(I * w.nb, (I + 1) * w.nb), slice(J * w.nb, (J + 1) * w.nb))
                 assert np.array_equal(again[blk], C_gpu[blk])
                 assert d.ctx.tile_info("C", I, J)[2] == 0
@@ -778,9 +778,9 @@ def test_random_small_integer_problems_over_all_formats_are_exact():
         K = Kf - (int(rng.integers(1, nb)) if ragged else 0)
         A, B = np.ascontiguousarray(A[:M, :K]), np.ascontiguousarray(B[:K, :N])
         C0 = rng.integers(-3, 4, (M, N)).astype(np.float64)
-        mA, mB, mC = rng.integers(0, 7, (MT, KT)), rng.integers(0, 7, (KT, NT)), rng.integers(0, 5, (MT, NT))
+        mA, mB, mC = rng.integers(0, 8, (MT, KT)), rng.integers(0, 8, (KT, NT)), rng.integers(0, 5, (MT, NT))
         if case % 10 == 3:                               # one block-scaled format everywhere: its kernel where the tile size allows
-            mA[:], mB[:] = (MXFP8, MXFP8) if case % 20 == 3 else (MXFP4, MXFP4)
+            mA[:], mB[:] = ((MXFP8, MXFP8), (MXFP4, MXFP4), (MXFP6, MXFP6))[(case // 10) % 3]
             mC[:] = rng.integers(1, 5, (MT, NT))
         policy, tA, tB = int(rng.integers(0, 2)), int(rng.integers(0, 2)), int(rng.integers(0, 2))
         alpha, beta = float(rng.choice([-2, -1, 1, 2])), float(rng.choice([-1, 0, 1]))
@@ -813,9 +813,9 @@ def test_256_regions_visit_every_chunk_once_at_tile_sizes_with_six_and_eight_chu
     import torch
     from paper_2508_14848_amd.device import DeviceGemmMP
     rng = np.random.default_rng(131)
-    for fmt, nb in ((FP8, 768), (FP8, 1024), (MXFP8, 768), (MXFP8, 1024), (MXFP4, 1536), (MXFP4, 2048)):
+    for fmt, nb in ((FP8, 768), (FP8, 1024), (MXFP8, 768), (MXFP8, 1024), (MXFP4, 1536), (MXFP4, 2048), (MXFP6, 768), (MXFP6, 1024)):
         M, N, K = nb, nb, 2 * nb
-        _say("256 x 256 regions, integers:", {FP8: "FP8", MXFP8: "MXFP8", MXFP4: "MXFP4"}[fmt], (M, N, K, nb))
+        _say("256 x 256 regions, integers:", {FP8: "FP8", MXFP8: "MXFP8", MXFP4: "MXFP4", MXFP6: "MXFP6"}[fmt], (M, N, K, nb))
         if fmt == FP8:                                   # one scale per tile: the same magnitude everywhere
             A = rng.integers(-3, 4, (M, K)).astype(np.float64)
             B = rng.integers(-3, 4, (K, N)).astype(np.float64)
@@ -925,6 +925,127 @@ def test_mxfp8_tiles_pack_bit_for_bit_and_multiply_on_the_block_scaled_instructi
     side = OracleSide(w, A, B, None)
     d, dev = gpu_problem(w, A, B, None)
     assert np.array_equal(d.unpack_tiles("A").cpu().numpy(), side.Ay) and np.array_equal(d.unpack_tiles("B").cpu().numpy(), side.By)
+    d.run(1.0, 0.0)
+    C_gpu = d.unpack_tiles("C").cpu().numpy()
+    jobs = _all_jobs(w)
+    worst = compare_jobs(side, jobs, 0, 1.0, 0.0, C_gpu, side.gemm(jobs))
+    _say("  worst error / bound:", worst)
+    torch.cuda.synchronize()
+
+
+def _fp6_bytes(codes):
+    """Six-bit codes, four to three bytes, code k of a group in bits 6k .. 6k+5 of the group's 24."""
+    c = codes.reshape(-1, 4).astype(np.uint32)
+    w = c[:, 0] | (c[:, 1] << 6) | (c[:, 2] << 12) | (c[:, 3] << 18)
+    return np.stack([w & 255, (w >> 8) & 255, (w >> 16) & 255], axis=1).astype(np.uint8).ravel()
+
+
+def test_mxfp6_tiles_pack_bit_for_bit_and_multiply_on_the_block_scaled_instruction():
+    """MXFP6 tiles: six-bit e2m3 codes (a block of 32 in 24 bytes, code k at bits 6k .. 6k+5) and
+    scale bytes equal the oracle's, both orientations, a size off the tile grid included; unpack
+    returns the values; under FP64 C tiles the consumer widens them, with the same result as
+    sender-side copies and within the oracle's bounds; all-MXFP6 problems of small integers with
+    block-wise different magnitudes are exact on the block-scaled instruction, with FP32 and with
+    narrow C tiles; general data within the bounds."""
+    import torch
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(63)
+    nb = 256
+    M, N, K = 2 * nb, 2 * nb - 50, 3 * nb - 31
+    A = rng.standard_normal((M, K)) * np.exp(rng.uniform(-20, 20, (M, K)))
+    B = rng.standard_normal((K, N)) * np.exp(rng.uniform(-20, 20, (K, N)))
+    A[7, 32:64] = 0.0                                            # a zero block
+    d = DeviceGemmMP(M, N, K, nb)
+    d.set_precision_map("A", np.full((2, 3), MXFP6, dtype=np.uint16))
+    d.set_precision_map("B", np.full((3, 2), MXFP6, dtype=np.uint16))
+    d.pack_tiles("A", _even_ld(A))
+    d.pack_tiles("B", _even_ld(B))
+    Ap, Bp = orc.pad_to_tiles(A, nb), orc.pad_to_tiles(B, nb)
+    for which, Xp, tiles in (("A", Ap, [(0, 0), (1, 2)]), ("B", Bp, [(0, 0), (2, 1)])):
+        for (I, J) in tiles:
+            got, prec = d.tile_bytes(which, I, J)
+            tile = Xp[I * nb:(I + 1) * nb, J * nb:(J + 1) * nb]
+            rows = np.ascontiguousarray(tile.T if which == "B" else tile)
+            _, codes, scales = orc.mx6_blocks(rows)
+            assert prec == MXFP6 and got.size == nb * nb * 3 // 4 + nb * nb // 32
+            assert np.array_equal(got[:nb * nb * 3 // 4], _fp6_bytes(codes.ravel())), (which, I, J)
+            assert np.array_equal(got[nb * nb * 3 // 4:], scales), (which, I, J)
+    Ya, _ = orc.store_tiles(Ap, nb, np.full((2, 3), MXFP6, dtype=np.uint16), mx_axis=0)
+    Yb, _ = orc.store_tiles(Bp, nb, np.full((3, 2), MXFP6, dtype=np.uint16), mx_axis=1)
+    assert np.array_equal(d.unpack_tiles("A").cpu().numpy(), Ya[:M, :K])
+    assert np.array_equal(d.unpack_tiles("B").cpu().numpy(), Yb[:K, :N])
+    # FP64 C tiles: no block-scaled kernel; the consumer widens the tiles (FP32 products folded into
+    # FP64), and sender-side copies give the same bits
+    d.set_precision_map("C", np.full((2, 2), FP64, dtype=np.uint16))
+    d.run(1.0, 0.0)
+    C_receiver = d.unpack_tiles("C").cpu().numpy()
+    assert d.convert_tiles() == (6 + 6) * nb * nb * 4
+    d.run(1.0, 0.0)
+    assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), C_receiver)
+    Cg = np.zeros((2 * nb, 2 * nb))
+    Cg[:M, :N] = C_receiver
+    w = W.Workload("mx6-64", 2 * nb, 2 * nb, 3 * nb, nb, 1.0, 0.0)
+    w.mapA, w.mapB = np.full((2, 3), MXFP6, dtype=np.uint16), np.full((3, 2), MXFP6, dtype=np.uint16)
+    w.mapC = np.full((2, 2), FP64, dtype=np.uint16)
+    side = OracleSide(w, Ap, Bp, None)
+    jobs = _all_jobs(w)
+    compare_jobs(side, jobs, 0, 1.0, 0.0, Cg, side.gemm(jobs, alpha=1.0, beta=0.0))
+    # ... and beside FP64 / FP32 tiles (FP64 and FP32 products with one MXFP6 operand)
+    for other in (FP64, FP32):
+        w2 = W.Workload("mx6-mixed", 2 * nb, 2 * nb, 3 * nb, nb, 1.0, 0.0)
+        w2.mapA = np.full((2, 3), MXFP6, dtype=np.uint16)
+        w2.mapB = np.full((3, 2), other, dtype=np.uint16)
+        w2.mapA[1, 1], w2.mapB[0, 1] = other, MXFP6
+        w2.mapC = np.array([[FP64, FP32], [FP32, FP64]], dtype=np.uint16)
+        A2 = rng.standard_normal((2 * nb, 3 * nb))
+        B2 = rng.standard_normal((3 * nb, 2 * nb))
+        side2 = OracleSide(w2, A2, B2, None)
+        d2, _ = gpu_problem(w2, A2, B2, None)
+        d2.run(1.0, 0.0)
+        jobs2 = _all_jobs(w2)
+        compare_jobs(side2, jobs2, 0, 1.0, 0.0, d2.unpack_tiles("C").cpu().numpy(), side2.gemm(jobs2, alpha=1.0, beta=0.0))
+    # integers: exact; every block gets its own scale from a different largest entry
+    for nb, MT, NT, KT in ((256, 2, 1, 3), (512, 1, 2, 2)):
+        M, N, K = MT * nb, NT * nb, KT * nb
+        _say("MXFP6 integers", (M, N, K, nb))
+        A = rng.integers(-7, 8, (M, K)) * 2.0 ** rng.integers(0, 3, (M, K // 32)).repeat(32, axis=1)
+        B = rng.integers(-7, 8, (K, N)) * 2.0 ** rng.integers(0, 3, (K // 32, N)).repeat(32, axis=0)
+        C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
+        for pC in (FP32, FP16 if nb == 256 else MXFP6):
+            d = DeviceGemmMP(M, N, K, nb)
+            d.set_precision_map("A", np.full((MT, KT), MXFP6, dtype=np.uint16))
+            d.set_precision_map("B", np.full((KT, NT), MXFP6, dtype=np.uint16))
+            d.set_precision_map("C", np.full((MT, NT), pC, dtype=np.uint16))
+            for which, X in (("A", A), ("B", B), ("C", C0)):
+                d.pack_tiles(which, torch.from_numpy(np.ascontiguousarray(X, dtype=np.float64)).cuda())
+            assert np.array_equal(d.unpack_tiles("A").cpu().numpy(), A) and np.array_equal(d.unpack_tiles("B").cpu().numpy(), B)
+            st = d.ctx.get_stats()
+            assert st["products_mxfp6"] == MT * NT * KT and st["work_items"] == MT * NT * (nb // 256) ** 2
+            assert st["launch_items"][7] == st["work_items"] and d.ctx.conversion_bytes() == 0
+            if pC == FP32:
+                d.run(1.0, -1.0)
+                assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), A @ B - C0)
+            else:                                      # a narrow C tile cannot hold these sums exactly
+                d.run(1.0, 0.0)
+                want = A @ B
+                got = d.unpack_tiles("C").cpu().numpy()
+                if pC == FP16:
+                    assert np.abs(got - want).max() <= 2.0 ** -11 * np.abs(want).max()
+                else:                                  # each block of 32 along a row is rounded relative to its own largest entry
+                    top = np.abs(want).reshape(M, -1, 32).max(axis=2).repeat(32, axis=1)
+                    assert np.all(np.abs(got - want) <= 2.0 ** -3 * top)
+                    assert np.abs(got - want).max() > 0
+    # general data against the oracle (the block-scaled kernel)
+    w = W.tiny()
+    w.mapA = np.full_like(w.mapA, MXFP6)
+    w.mapB = np.full_like(w.mapB, MXFP6)
+    w.mapC = np.full_like(w.mapC, FP32)
+    w.alpha, w.beta = 1.0, 0.0
+    A, B, _ = _dense(w)
+    side = OracleSide(w, A, B, None)
+    d, dev = gpu_problem(w, A, B, None)
+    assert np.array_equal(d.unpack_tiles("A").cpu().numpy(), side.Ay) and np.array_equal(d.unpack_tiles("B").cpu().numpy(), side.By)
+    assert d.ctx.get_stats()["launch_items"][7] > 0
     d.run(1.0, 0.0)
     C_gpu = d.unpack_tiles("C").cpu().numpy()
     jobs = _all_jobs(w)

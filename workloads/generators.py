@@ -244,7 +244,7 @@ def one_format(p, n=16384, nb=1024, seed=MASTER_SEED):
     """Every tile of A and B in one storage format (precision code p), C tiles FP32 (FP64 for
     p = FP64), U[-1,1] entries: one product precision throughout, for per-format rates.  Not one
     of the paper's workloads (its maps are FP64 / FP32 mixtures, Section 5.2)."""
-    names = {0: "fp64", 1: "fp32", 2: "fp16", 3: "fp8", 4: "bf16", 5: "mxfp8", 6: "mxfp4"}
+    names = {0: "fp64", 1: "fp32", 2: "fp16", 3: "fp8", 4: "bf16", 5: "mxfp8", 6: "mxfp4", 7: "mxfp6"}
     w = _TileScaled("format-" + names[p], n, n, n, nb, 1.0, 0.0, seed=seed, dist="uniform")
     w.mapA = np.full((w.MT, w.KT), p, dtype=np.uint16)
     w.mapB = np.full((w.KT, w.NT), p, dtype=np.uint16)
@@ -265,5 +265,5 @@ CONFIGS = {
     "paper0": lambda: paper_ratio(0),
     "format-fp64": lambda: one_format(0), "format-fp32": lambda: one_format(1), "format-fp16": lambda: one_format(2),
     "format-fp8": lambda: one_format(3), "format-bf16": lambda: one_format(4), "format-mxfp8": lambda: one_format(5),
-    "format-mxfp4": lambda: one_format(6),
+    "format-mxfp4": lambda: one_format(6), "format-mxfp6": lambda: one_format(7),
 }
