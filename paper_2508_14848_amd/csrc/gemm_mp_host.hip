@@ -959,7 +959,7 @@ int gemm_mp_convert_tiles(gemm_mp_ctx *c, void *workspace, size_t bytes, gemm_mp
             j.which = (uint8_t)w;
             j.pad = 0;
             j.n16 = (uint32_t)(((uint64_t)c->nb * c->nb * elem_bytes(q)) / 16);
-            j.pad2 = 0;
+            j.nb = (uint32_t)c->nb;
             max_n16 = std::max(max_n16, j.n16);
             addr[w][k] = j.dst;
             jobs.push_back(j);

@@ -822,17 +822,25 @@ __device__ __forceinline__ void load_piece_widening(Raw &r, const Product &pr, i
     if (fmt >= 3) {
         // MXFP4 / MXFP6: W = 4 / 6 bits per element.  The operand's descriptor counts in bytes of
         // an element size the kernel knows (MXFP4: two elements a byte; MXFP6 is announced like
-        // MXFP8, one byte per element), which gives back the thread's first element; its codes start
-        // at bit element * W of the tile.  The two aligned words from there on are read (at most 24
-        // bits from bit 28 of the first), and the bit offset in them goes along in r.hi.y.
-        const int W = fmt == 3 ? 4 : 6;
-        const int eidx = (o.voff + (o.sub & 15)) << (fmt == 3 ? 1 : 0);
-        const int bit = eidx * W;
-        const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (bit >> 5) << 2, (eoff * W) >> 3, 0);
+        // MXFP8, one byte per element), which gives back the thread's first element.  The two
+        // aligned words around its codes are read (at most 24 bits from bit 28 of the first), and
+        // the bit offset in them goes along in r.hi.y.  MXFP4 codes lie row after row; where the
+        // three bytes of four MXFP6 codes lie is fp6_group_offset's business.
+        const int e0 = ((o.voff + (o.sub & 15)) << (fmt == 3 ? 1 : 0)) + eoff;
+        int byte, bit;
+        if (fmt == 3) {
+            byte = e0 >> 1;
+            bit = 8 * (byte & 3);
+        } else {
+            const int row = e0 / nb, k = e0 - row * nb;
+            byte = (int)fp6_group_offset(nb, row, k & ~3);
+            bit = 8 * (byte & 3) + 6 * (k & 3);
+        }
+        const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte & ~3, 0, 0);
         r.lo.x = w.x;
         r.lo.y = w.y;
-        r.hi.y = (uint32_t)(bit & 31);
-        r.hi.x = (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rsrc, ((nb * nb * W) >> 3) + (eidx >> 5), eoff >> 5, 0);
+        r.hi.y = (uint32_t)bit;
+        r.hi.x = (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(rsrc, ((nb * nb * (fmt == 3 ? 4 : 6)) >> 3) + (e0 >> 5), 0, 0);
         return;
     }
     r.lo = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o.voff, eoff << (3 - o.p), 0);

@@ -53,24 +53,14 @@ __device__ __forceinline__ void big_scales(int ea, int eb, int &sa, int &sb)
 // DMA instruction j = 0..15 of a wave for one chunk: j < 8 moves rows 8 j .. 8 j + 7 of the
 // wave's 64 rows of A, j >= 8 the same of B, 16 bytes per lane, into the stage at `dst`.
 // base / bytes: the operand tile (bytes = 0: nothing is fetched, zeros are written).
-// FMT 5 (MXFP6): 12 bytes per lane; the 12-byte form of the instruction still gives every lane a
-// 16-byte slot in LDS (lane l writes at 16 l, the last four bytes of the slot stay as they were),
-// so a stage has the layout of the other formats with three quarters of every slot in use.
-template <int FMT>
 __device__ __forceinline__ void big_dma_one(uint64_t base, int bytes, int voff, int soff, unsigned dst)
 {
     const i32x4 rsrc = {(int)(uint32_t)base, (int)((uint32_t)(base >> 32) & 0xffffu), bytes, 0x00020000};
 #if defined(__HIP_DEVICE_COMPILE__)
-    if constexpr (FMT == 5)
-        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx3 %1, %2, %3 offen lds"
-                     :
-                     : "s"(dst), "v"(voff), "s"(rsrc), "s"(soff)
-                     : "memory", "m0");
-    else
-        asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                     :
-                     : "s"(dst), "v"(voff), "s"(rsrc), "s"(soff)
-                     : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(dst), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory", "m0");
 #else
     (void)rsrc; (void)voff; (void)soff; (void)dst;
 #endif
@@ -83,25 +73,45 @@ struct BigSource {
 template <int FMT>
 __device__ __forceinline__ void big_request(const BigSource &S, const BigGeom &BG, int stage, int j)
 {
-    const int op = j >> 3, jj = j & 7;
     int cc = S.c + BG.rot;
     if (cc >= BG.n) cc -= BG.n;
-    constexpr int kChunkBytes = FMT == 5 ? 96 : kRowBytes;   // bytes of a tile row per chunk
-    big_dma_one<FMT>(op ? S.b : S.a, S.bytes, BG.voff[op][jj & 1], uni(cc * kChunkBytes + jj * BG.rows8),
-                BG.dst + (unsigned)(stage * kBigStage + op * kBigOperand + jj * 1024));
+    if constexpr (FMT == 5) {
+        // MXFP6: the 256 rows of an operand's chunk are 24 KB in one piece (a tile is stored panel by
+        // panel of 128 reduction indices, see fp6_group_offset) and go to LDS as they are: twelve
+        // instructions per wave and chunk, six for each operand, 1 KB each; rows8 is the size of a panel
+        if (j >= 12) return;
+        const int op = j >= 6, jj = op ? j - 6 : j;
+        big_dma_one(op ? S.b : S.a, S.bytes, BG.voff[op][0], uni(cc * BG.rows8 + jj * 1024),
+                    BG.dst + (unsigned)(stage * kBigStage + op * kBigOperand + jj * 1024));
+    } else {
+        const int op = j >> 3, jj = j & 7;
+        big_dma_one(op ? S.b : S.a, S.bytes, BG.voff[op][jj & 1], uni(cc * kRowBytes + jj * BG.rows8),
+                    BG.dst + (unsigned)(stage * kBigStage + op * kBigOperand + jj * 1024));
+    }
 }
 // One 16-byte half (w) of fragment t (0..3: A blocks of 32 rows, 4..7: B blocks) of half `hc` of the
-// chunk in `stage`, into its place in the fragment.  FMT 5: the 12 bytes in use of
-// the slot; the two halves make the 24 bytes of the lane's block of 32 six-bit elements.
-struct __attribute__((aligned(16))) Words3 { uint32_t x, y, z; };
+// chunk in `stage`, into its place in the fragment.
+// A fragment is the operand of one matrix instruction: eight registers, six for FMT 5 (kept in a
+// six-register type so that the two spare ones are not allocated sixteen times over): there a
+// lane's block of 32 six-bit elements is 24 consecutive bytes of its row, 8-byte aligned, read as
+// three pairs of registers, two with w = 0 and the third with w = 1.
+typedef int i6v __attribute__((ext_vector_type(6)));
+template <int FMT> struct BigFrag { typedef i8v type; };
+template <> struct BigFrag<5> { typedef i6v type; };
 template <int FMT>
-__device__ __forceinline__ void big_read_half(i8v &f, const BigGeom &BG, const char *lds, int stage, int hc, int t, int w)
+__device__ __forceinline__ void big_read_half(typename BigFrag<FMT>::type &f, const BigGeom &BG, const char *lds, int stage, int hc, int t, int w)
 {
-    const char *p = lds + (t < 4 ? BG.ra[stage][hc][w] : BG.rb[stage][hc][w]) + (t & 3) * (32 * kRowBytes);
     if constexpr (FMT == 5) {
-        const Words3 v = *(const Words3 *)p;
-        f[3 * w] = (int)v.x; f[3 * w + 1] = (int)v.y; f[3 * w + 2] = (int)v.z;
+        const char *p = lds + (t < 4 ? BG.ra[stage][hc][0] : BG.rb[stage][hc][0]) + (t & 3) * (32 * 96);
+        if (w == 0) {
+            const u32x2 a = *(const u32x2 *)p, b = *(const u32x2 *)(p + 8);
+            f[0] = (int)a.x; f[1] = (int)a.y; f[2] = (int)b.x; f[3] = (int)b.y;
+        } else {
+            const u32x2 c = *(const u32x2 *)(p + 16);
+            f[4] = (int)c.x; f[5] = (int)c.y;
+        }
     } else {
+        const char *p = lds + (t < 4 ? BG.ra[stage][hc][w] : BG.rb[stage][hc][w]) + (t & 3) * (32 * kRowBytes);
         const u32x4 v = *(const u32x4 *)p;
         f[4 * w] = (int)v.x; f[4 * w + 1] = (int)v.y; f[4 * w + 2] = (int)v.z; f[4 * w + 3] = (int)v.w;
     }
@@ -109,19 +119,24 @@ __device__ __forceinline__ void big_read_half(i8v &f, const BigGeom &BG, const c
 
 // The whole fragment.
 template <int FMT>
-__device__ __forceinline__ i8v big_read(const BigGeom &BG, const char *lds, int stage, int hc, int t)
+__device__ __forceinline__ typename BigFrag<FMT>::type big_read(const BigGeom &BG, const char *lds, int stage, int hc, int t)
 {
     if constexpr (FMT == 5) {
-        i8v f = {};
+        i6v f = {};
         big_read_half<FMT>(f, BG, lds, stage, hc, t, 0);
         big_read_half<FMT>(f, BG, lds, stage, hc, t, 1);
         return f;
-    }
+    } else {
     const char *p0 = lds + (t < 4 ? BG.ra[stage][hc][0] : BG.rb[stage][hc][0]) + (t & 3) * (32 * kRowBytes);
     const char *p1 = lds + (t < 4 ? BG.ra[stage][hc][1] : BG.rb[stage][hc][1]) + (t & 3) * (32 * kRowBytes);
     const u32x4 lo = *(const u32x4 *)p0, hi = *(const u32x4 *)p1;
     return i8v{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+    }
 }
+// The fragment as the eight-register value the instruction's builtin asks for (FMT 5: the two
+// registers beyond the six are not read by the instruction and are left undefined).
+__device__ __forceinline__ i8v big_operand(const i8v &f) { return f; }
+__device__ __forceinline__ i8v big_operand(const i6v &f) { return __builtin_shufflevector(f, f, 0, 1, 2, 3, 4, 5, -1, -1); }
 
 // Block scales of an MXFP8 chunk: per A row block (0..3) and B row block (4..7) the four scale
 // bytes of this lane's row (one per 32 reduction indices of the chunk), shifted so that byte 0
@@ -211,7 +226,7 @@ __device__ __forceinline__ void big_rescale(f16v (&acc)[4][4], float ratio)
 // behind the wait in the middle of the chunk, the one point where nothing else is in flight, so
 // that no other wait for them is needed.
 template <int STAGE, int FMT, bool TAKE, int SO>
-__device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], const BigGeom &BG, const char *lds, const BigSource &S2,
+__device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], typename BigFrag<FMT>::type (&f)[2][8], const BigGeom &BG, const char *lds, const BigSource &S2,
                                           int sa, int sb, const int (&sc)[32], const int (&raw)[32], int (&nx)[32], int shift)
 {
     constexpr bool MX = FMT == 1 || FMT == 5;
@@ -224,7 +239,7 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
                 acc[mt][nt] = big_mfma16<FMT>(f[0][mt], f[0][4 + nt], acc[mt][nt], 0);
                 acc[mt][nt] = big_mfma16<FMT>(f[0][mt], f[0][4 + nt], acc[mt][nt], 1);
             } else if constexpr (FMT == 2) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[0][mt], 0), big_fp4_operand(f[0][4 + nt], 0), acc[mt][nt], 4, 4, 0, sc[SO + mt], 0, sc[SO + 4 + nt]);
-            else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], EL, EL, 0, sc[SO + mt], 0, sc[SO + 4 + nt]);
+            else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_operand(f[0][mt]), big_operand(f[0][4 + nt]), acc[mt][nt], EL, EL, 0, sc[SO + mt], 0, sc[SO + 4 + nt]);
             else acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[0][mt], f[0][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
             SCHED_FENCE();
             const int k = mt * 4 + nt;                       // second half's fragments, 16 bytes per position: B first
@@ -259,7 +274,7 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
                 acc[mt][nt] = big_mfma16<FMT>(f[1][mt], f[1][4 + nt], acc[mt][nt], 0);
                 acc[mt][nt] = big_mfma16<FMT>(f[1][mt], f[1][4 + nt], acc[mt][nt], 1);
             } else if constexpr (FMT == 2) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_fp4_operand(f[1][mt], 0), big_fp4_operand(f[1][4 + nt], 0), acc[mt][nt], 4, 4, 0, sc[SO + 8 + mt], 0, sc[SO + 12 + nt]);
-            else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], EL, EL, 2, sc[SO + mt], 2, sc[SO + 4 + nt]);
+            else if constexpr (MX) acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(big_operand(f[1][mt]), big_operand(f[1][4 + nt]), acc[mt][nt], EL, EL, 2, sc[SO + mt], 2, sc[SO + 4 + nt]);
             else acc[mt][nt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f[1][mt], f[1][4 + nt], acc[mt][nt], 0, 0, 0, sa, 0, sb);
             SCHED_FENCE();
             const int k = mt * 4 + nt;
@@ -283,10 +298,12 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], i8v (&f)[2][8], con
 // FMT 2: MXFP4 tiles: half a byte per element, so a tile row is nb / 2 bytes and a chunk (128
 // bytes of each row) 256 reduction indices; a lane's 16 bytes per reduction step are one block of
 // 32 elements, scaled by that lane's own byte, and the fragment reads are those of FMT 1.
-// FMT 5: MXFP6 tiles: 24 bytes per block of 32 six-bit elements, a tile row is 3 nb / 4 bytes and a
-// chunk 96 bytes of each row = 128 reduction indices, in eight 12-byte pieces that land in the eight
-// 16-byte slots of the row's LDS line; a lane's operand of a 64-index step is the block 32 (lane / 32)
-// ... of the step, two neighbouring pieces, scaled by that lane's own byte (as for FMT 2).
+// FMT 5: MXFP6 tiles: 24 bytes per block of 32 six-bit elements; a chunk is a panel of 128 reduction
+// indices, 96 bytes of each row, stored row after row with the four blocks of a row rotated by
+// (row / 8) (see fp6_group_offset), and sits in LDS as it does in memory: rows of 96 bytes.  A
+// lane's operand of a 64-index step is the block 32 (lane / 32) ... of the step, scaled by that
+// lane's own byte (as for FMT 2); the rotation puts the blocks that 32 lanes read from 32
+// consecutive rows on all 64 banks.
 template <int FMT>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
@@ -300,8 +317,7 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     const ArgsPtr K0 = args();
     const int nb = K0->nb, kt = K0->kt_eff;
     constexpr bool MX = FMT == 1 || FMT == 2 || FMT == 5;
-    constexpr int kPiece = FMT == 5 ? 12 : 16;               // bytes a lane moves per DMA instruction
-    constexpr int kChunkBytes = 8 * kPiece;                  // bytes of a tile row per chunk
+    constexpr int kChunkBytes = FMT == 5 ? 96 : kRowBytes;   // bytes of a tile row per chunk
     const int pitch = FMT == 5 ? (nb >> 2) * 3 : FMT == 2 ? nb / 2 : (FMT == 3 || FMT == 4) ? 2 * nb : nb;   // bytes of a tile row
     const int arow0 = (int)((itw >> 32) & 0xffffu) * kBigMacro, brow0 = (int)((itw >> 48) & 0xffffu) * kBigMacro;
     const ProductDesc *prod = K0->prod + (int64_t)tileC * K0->KT;
@@ -310,12 +326,18 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     {
         const int r = lane >> 3, slot = lane & 7;
         const int seg = slot ^ (r >> 1);                     // instruction 0; odd instructions: ^ 4
-        BG.voff[0][0] = (arow0 + wave * 64 + r) * pitch + seg * kPiece;
-        BG.voff[1][0] = (brow0 + wave * 64 + r) * pitch + seg * kPiece;
-        BG.voff[0][1] = (arow0 + wave * 64 + r) * pitch + (seg ^ 4) * kPiece;
-        BG.voff[1][1] = (brow0 + wave * 64 + r) * pitch + (seg ^ 4) * kPiece;
+        BG.voff[0][0] = (arow0 + wave * 64 + r) * pitch + seg * 16;
+        BG.voff[1][0] = (brow0 + wave * 64 + r) * pitch + seg * 16;
+        BG.voff[0][1] = BG.voff[0][0] ^ 64;
+        BG.voff[1][1] = BG.voff[1][0] ^ 64;
         BG.dst = (unsigned)uni(wave * (64 * kRowBytes));
         BG.rows8 = 8 * pitch;
+        if constexpr (FMT == 5) {
+            BG.voff[0][0] = arow0 * 96 + wave * 6144 + lane * 16;
+            BG.voff[1][0] = brow0 * 96 + wave * 6144 + lane * 16;
+            BG.dst = (unsigned)uni(wave * 6144);
+            BG.rows8 = nb * 96;
+        }
         BG.n = pitch / kChunkBytes;
         // Regions of one C tile run side by side on one XCD and would otherwise ask its L2 for the
         // same 128-byte column of every panel row at the same time; each starts its pass over a
@@ -331,6 +353,11 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
                     const int slot_r = ((FMT == 1 || FMT == 2) ? 4 * hc + g + 2 * w : 4 * hc + 2 * g + w) ^ x;
                     BG.ra[st][hc][w] = st * kBigStage + (wm * 128 + i) * kRowBytes + slot_r * 16;
                     BG.rb[st][hc][w] = st * kBigStage + kBigOperand + (wn * 128 + i) * kRowBytes + slot_r * 16;
+                    if constexpr (FMT == 5) {
+                        const int pos = (2 * hc + g + (i >> 3)) & 3;
+                        BG.ra[st][hc][w] = st * kBigStage + (wm * 128 + i) * 96 + pos * 24;
+                        BG.rb[st][hc][w] = st * kBigStage + kBigOperand + (wn * 128 + i) * 96 + pos * 24;
+                    }
                 }
     }
 
@@ -381,10 +408,11 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 #pragma unroll
             for (int j = 0; j < 16; ++j) big_request<FMT>(S, BG, 1, j);
 #if defined(__HIP_DEVICE_COMPILE__)
-            asm volatile("s_waitcnt vmcnt(16)" ::: "memory");    // chunk 0 has landed
+            if constexpr (FMT == 5) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");    // chunk 0 has landed
 #endif
             __syncthreads();
-            i8v f[2][8];
+            typename BigFrag<FMT>::type f[2][8];
 #pragma unroll
             for (int t = 0; t < 8; ++t) f[0][t] = big_read<FMT>(BG, lds, 0, 0, t);
             int sc[32], nsc[32];

@@ -87,7 +87,8 @@ __global__ __launch_bounds__(256) void convert_tiles_kernel(const ConvertJob *__
         const uint64_t elems = (uint64_t)job.n16 * (q == Q32 ? 4u : 2u);         // nb * nb
         const uint64_t idx = (uint64_t)seg * (q == Q32 ? 4u : 2u);                // first element of this segment: even
         const int sc = (int)sb[elems / 4 * 3 + (idx >> 5)] - 127;
-        const uint8_t *b3 = sb + (idx >> 2) * 3;
+        const int nb = (int)job.nb;
+        const uint8_t *b3 = sb + fp6_group_offset(nb, (int)(idx / (uint64_t)nb), (int)(idx % (uint64_t)nb) & ~3);
         const uint32_t w = (b3[0] | ((uint32_t)b3[1] << 8) | ((uint32_t)b3[2] << 16)) >> (6 * (int)(idx & 3));
         float v[4];
 #pragma unroll

@@ -388,7 +388,7 @@ __global__ __launch_bounds__(256) void pack_mx_kernel(const double *__restrict__
             w[(6 * k) / 64] |= code << ((6 * k) % 64);
             if ((6 * k) % 64 > 58) w[(6 * k) / 64 + 1] |= code >> (64 - (6 * k) % 64);
         }
-        uint2 *dst = (uint2 *)(base + ((int64_t)u * nb + 32 * kb) / 4 * 3);
+        uint2 *dst = (uint2 *)(base + fp6_group_offset(nb, u, 32 * kb));
 #pragma unroll
         for (int j = 0; j < 3; ++j) dst[j] = make_uint2((uint32_t)w[j], (uint32_t)(w[j] >> 32));
         ((uint8_t *)base)[(int64_t)nb * nb / 4 * 3 + (int64_t)u * per_row + kb] = (uint8_t)(s + 127);
@@ -446,7 +446,7 @@ __global__ __launch_bounds__(256) void pack_mx_rows_kernel(const double *__restr
     char *base = v.storage + v.offset[tile];
     if (fp6) {                                                   // four codes = three bytes
         const uint32_t w = to_fp6_bits(x[0], s) | (to_fp6_bits(x[1], s) << 6) | (to_fp6_bits(x[2], s) << 12) | (to_fp6_bits(x[3], s) << 18);
-        uint8_t *d = (uint8_t *)base + ((int64_t)u * nb + 32 * kb) / 4 * 3 + 3 * sub;
+        uint8_t *d = (uint8_t *)base + fp6_group_offset(nb, u, 32 * kb + 4 * sub);
         d[0] = (uint8_t)w; d[1] = (uint8_t)(w >> 8); d[2] = (uint8_t)(w >> 16);
         if (sub == 0) ((uint8_t *)base)[(int64_t)nb * nb / 4 * 3 + (int64_t)u * per_row + kb] = (uint8_t)(s + 127);
         return;
@@ -500,7 +500,7 @@ __device__ inline double stored_value(const char *base, int64_t idx, int p, int 
         return ldexp((code & 8) ? -mag : mag, sc - 127);
     }
     case GEMM_MP_MXFP6: {
-        const int64_t at = (idx >> 2) * 3;                        // four codes = three bytes
+        const int64_t at = fp6_group_offset(nb, (int)(idx / nb), (int)(idx % nb) & ~3);   // four codes = three bytes
         const uint32_t w = ((const uint8_t *)base)[at] | ((uint32_t)((const uint8_t *)base)[at + 1] << 8) | ((uint32_t)((const uint8_t *)base)[at + 2] << 16);
         const int sc = ((const uint8_t *)base)[(int64_t)nb * nb / 4 * 3 + (idx >> 5)];
         return ldexp((double)fp6_value((w >> (6 * (int)(idx & 3))) & 63u), sc - 127);
@@ -599,7 +599,7 @@ __global__ __launch_bounds__(256) void low_expand_kernel(const LowTile *__restri
             x = make_float4(__uint_as_float(h.x << 16), __uint_as_float(h.x & 0xffff0000u),
                             __uint_as_float(h.y << 16), __uint_as_float(h.y & 0xffff0000u));
         } else if (p == GEMM_MP_MXFP6) {                       // four codes = three bytes, in one block of 32
-            const uint8_t *b3 = (const uint8_t *)src + i / 4 * 3;
+            const uint8_t *b3 = (const uint8_t *)src + fp6_group_offset(nb, (int)(i / nb), (int)(i % nb));
             const uint32_t b = b3[0] | ((uint32_t)b3[1] << 8) | ((uint32_t)b3[2] << 16);
             x = make_float4(fp6_value(b & 63u), fp6_value((b >> 6) & 63u), fp6_value((b >> 12) & 63u), fp6_value((b >> 18) & 63u));
             e = (int)((const uint8_t *)src)[(int64_t)nb * nb / 4 * 3 + (i >> 5)] - 127;
@@ -722,7 +722,7 @@ __global__ __launch_bounds__(256) void low_round_kernel(const LowTile *__restric
             if (fp6) {
                 const uint32_t w = to_fp6_bits((double)x.x, s) | (to_fp6_bits((double)x.y, s) << 6) |
                                    (to_fp6_bits((double)x.z, s) << 12) | (to_fp6_bits((double)x.w, s) << 18);
-                uint8_t *d = (uint8_t *)dst + i / 4 * 3;
+                uint8_t *d = (uint8_t *)dst + fp6_group_offset(nb, (int)(i / nb), (int)(i % nb));
                 d[0] = (uint8_t)w; d[1] = (uint8_t)(w >> 8); d[2] = (uint8_t)(w >> 16);
                 if ((threadIdx.x & 7) == 0) ((uint8_t *)dst)[(int64_t)nb * nb / 4 * 3 + (i >> 5)] = (uint8_t)(s + 127);
             } else if (fp4) {

@@ -933,11 +933,25 @@ def test_mxfp8_tiles_pack_bit_for_bit_and_multiply_on_the_block_scaled_instructi
     torch.cuda.synchronize()
 
 
-def _fp6_bytes(codes):
-    """Six-bit codes, four to three bytes, code k of a group in bits 6k .. 6k+5 of the group's 24."""
-    c = codes.reshape(-1, 4).astype(np.uint32)
-    w = c[:, 0] | (c[:, 1] << 6) | (c[:, 2] << 12) | (c[:, 3] << 18)
-    return np.stack([w & 255, (w >> 8) & 255, (w >> 16) & 255], axis=1).astype(np.uint8).ravel()
+def _fp6_bytes(codes, nb):
+    """The element bytes of an MXFP6 tile from its six-bit codes (nb packed rows of nb codes), as the
+    interface describes them: four codes to three bytes, code k of a group in bits 6k .. 6k+5 of the
+    group's 24; the tile stored panel by panel of 128 reduction indices (the last one 64 wide where
+    nb is an odd multiple of 64), row after row inside a panel, the blocks of 32 inside a row of a
+    panel rotated by (row // 8)."""
+    c = codes.reshape(nb, nb // 4, 4).astype(np.uint32)
+    w = c[:, :, 0] | (c[:, :, 1] << 6) | (c[:, :, 2] << 12) | (c[:, :, 3] << 18)
+    groups = np.stack([w & 255, (w >> 8) & 255, (w >> 16) & 255], axis=2).astype(np.uint8)      # [row][group of 4][3]
+    out = np.zeros(nb * nb * 3 // 4, dtype=np.uint8)
+    for p0 in range(0, nb, 128):
+        width = min(128, nb - p0)
+        nblk = width // 32
+        for r in range(nb):
+            for b in range(nblk):
+                at = (p0 // 128) * nb * 96 + r * (width * 3 // 4) + ((b + r // 8) % nblk) * 24
+                g0 = (p0 + 32 * b) // 4
+                out[at:at + 24] = groups[r, g0:g0 + 8].ravel()
+    return out
 
 
 def test_mxfp6_tiles_pack_bit_for_bit_and_multiply_on_the_block_scaled_instruction():
@@ -968,7 +982,7 @@ def test_mxfp6_tiles_pack_bit_for_bit_and_multiply_on_the_block_scaled_instructi
             rows = np.ascontiguousarray(tile.T if which == "B" else tile)
             _, codes, scales = orc.mx6_blocks(rows)
             assert prec == MXFP6 and got.size == nb * nb * 3 // 4 + nb * nb // 32
-            assert np.array_equal(got[:nb * nb * 3 // 4], _fp6_bytes(codes.ravel())), (which, I, J)
+            assert np.array_equal(got[:nb * nb * 3 // 4], _fp6_bytes(codes, nb)), (which, I, J)
             assert np.array_equal(got[nb * nb * 3 // 4:], scales), (which, I, J)
     Ya, _ = orc.store_tiles(Ap, nb, np.full((2, 3), MXFP6, dtype=np.uint16), mx_axis=0)
     Yb, _ = orc.store_tiles(Bp, nb, np.full((3, 2), MXFP6, dtype=np.uint16), mx_axis=1)
