@@ -236,6 +236,25 @@ __device__ __forceinline__ int chunk_elems(int q) { return kRowBytes >> (3 - q);
 // Nothing may be moved across this point by the instruction scheduler.
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// The per-lane values every loop works with, from the thread index.
+__device__ __forceinline__ Geometry make_geometry(int tid, bool ring)
+{
+    Geometry G;
+    G.ring = ring;
+    G.tid = tid;
+    G.lane = tid & 63;
+    G.li = G.lane & 15;
+    G.g = G.lane >> 4;
+    const int wave = tid >> 6;
+    G.wm = wave >> 1;
+    G.wn = wave & 1;
+    G.seg_row = tid >> 3;
+    G.seg_part = tid & 7;
+    G.wbase = G.seg_row * kRowStride + G.seg_part * 16;
+    G.wsw = G.seg_row * kRowBytes + ((G.seg_part ^ ((G.seg_row >> 1) & 7)) * 16);
+    return G;
+}
+
 // A copy of the lane geometry whose values the optimiser must treat as new.  Every product
 // loop starts from one: otherwise the per-lane addresses of all the specialised loops are
 // hoisted to the top of the kernel and held in registers for its whole life, which pushes the
@@ -1271,6 +1290,23 @@ __device__ __forceinline__ void lo_chunk(f4 (&acc)[4][4], u32x4 (&fr)[2][16], co
 template <typename AccS>
 __device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int esum);
 
+// A per-product FP32 accumulator set to zero, written register by register with an immediate.
+// (An assignment of a zero vector makes the compiler keep one zero vector for the whole kernel,
+// which in the FP64-tile kernel is spilled and fetched back from scratch memory at every product,
+// with a wait for all outstanding loads in front of the first matrix instruction.)
+__device__ __forceinline__ void zero_side(f4 (&t)[4][4])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float z0, z1, z2, z3;
+            asm volatile("v_accvgpr_write_b32 %0, 0\n\tv_accvgpr_write_b32 %1, 0\n\tv_accvgpr_write_b32 %2, 0\n\tv_accvgpr_write_b32 %3, 0"
+                         : "=a"(z0), "=a"(z1), "=a"(z2), "=a"(z3));
+            t[i][j] = f4{z0, z1, z2, z3};
+        }
+}
+
 // A run of consecutive ring products starting at product `cur` (reduction tile L).  On return
 // `cur` is the first product after the run (q = -1: none) and L its index; if that product wants
 // its first chunk staged, it is in stage 0 of the two-stage layout.
@@ -1599,19 +1635,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     constexpr int QT = std::is_same<T, double>::value ? Q64 : Q32;
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
-    Geometry G;
-    G.ring = true;
-    G.tid = threadIdx.x;
-    G.lane = G.tid & 63;
-    G.li = G.lane & 15;
-    G.g = G.lane >> 4;
-    const int wave = G.tid >> 6;
-    G.wm = wave >> 1;
-    G.wn = wave & 1;
-    G.seg_row = G.tid >> 3;
-    G.seg_part = G.tid & 7;
-    G.wbase = G.seg_row * kRowStride + G.seg_part * 16;
-    G.wsw = G.seg_row * kRowBytes + ((G.seg_part ^ ((G.seg_row >> 1) & 7)) * 16);
+    const Geometry G = make_geometry((int)threadIdx.x, true);
 
     // this workgroup's item and the kernel arguments it needs throughout: scalar loads
     const uint64_t itw = table_u64((const uint64_t *)items, blockIdx.x);
@@ -1660,10 +1684,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
         Product next;
         if (q == Q16 || q == Q8) {                 // FP16 / FP8 product outside the ring
             f4 t[4][4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
+            zero_side(t);
             const int esum = cur.a.e + cur.b.e;
             if (q == Q16) next = product_loop_simple<Q16, MIXED>(t, cur, W, L + 1, lds, stage, G, R);
             else next = product_loop_simple<Q8, MIXED>(t, cur, W, L + 1, lds, stage, G, R);
@@ -1682,10 +1703,7 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
             if constexpr (QT == Q64) {
                 // an FP32 product of an FP64 C tile: its FP32 accumulator lives only for that product
                 f4 t[4][4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
+                zero_side(t);
                 if (BF && widening) next = product_loop_widening<Q32, -1, MIXED>(t, cur, W, L + 1, lds, stage, G, R, raw);
                 else next = product_loop_pipelined<Q32, -1, false, MIXED>(t, cur, W, L + 1, lds, stage, G, R, hand, raw);
                 fold(s, t, 0);
