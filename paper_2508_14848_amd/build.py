@@ -1,6 +1,10 @@
 """Build libgemm_mp.so (HIP, gfx950 only) in-tree with hipcc."""
+import glob
 import os
+import shutil
 import subprocess
+
+from . import check_isa
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -22,9 +26,13 @@ def build_library(verbose=False, extra_flags=()):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
+    temps = os.path.join(CSRC, "_build")
+    os.makedirs(temps, exist_ok=True)
     for src in SOURCES:
-        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        # the 128 x 128 kernels keep their intermediate files: their assembly is checked below
+        owner = src.startswith("gemm_owner_")
+        obj = os.path.join(temps if owner else CSRC, src.replace(".hip", ".o"))
+        cmd = [hipcc, *FLAGS, *extra_flags, *(["-save-temps=obj"] if owner else []), "-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     for cmd, p in procs:
@@ -34,8 +42,14 @@ def build_library(verbose=False, extra_flags=()):
             raise RuntimeError("hipcc failed: %s\n%s" % (" ".join(cmd), out))
         if verbose and out.strip():
             print(out)
+    for asm in sorted(glob.glob(os.path.join(temps, "gemm_owner_*-hip-amdgcn-amd-amdhsa-gfx950.s"))):
+        n, bad = check_isa.violations(asm)
+        if n == 0 or bad:
+            raise RuntimeError("%s: %d basic blocks with inline-assembly matrix instructions, %d instructions that touch their "
+                               "accumulators in mid-run (first: %s)" % (os.path.basename(asm), n, len(bad), bad[:1]))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.run(cmd, check=True)
+    shutil.rmtree(temps, ignore_errors=True)            # tens of megabytes of intermediate files
     return LIB
 
 

@@ -1682,6 +1682,10 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
             continue;
         }
         Product next;
+        // (No schedule the host makes comes here any more: every FP16 / FP8 product is a ring product
+        // of the instance launched.  The loop stays as the road for a product no ring takes; taking
+        // it out also changed the register allocation of another instance into one that the
+        // build's check of the machine code rejects.)
         if (q == Q16 || q == Q8) {                 // FP16 / FP8 product outside the ring
             f4 t[4][4];
             zero_side(t);

@@ -307,3 +307,20 @@ def test_sender_side_conversion_plan_closed_forms():
         g.convert_tiles(0, 0, None)               # nothing is packed yet
     assert e.value.status == G.ESTATE
     g.clear_conversion()
+
+
+def test_isa_check_flags_a_copy_of_an_accumulator_inside_a_run_of_assembly_matrix_instructions(tmp_path):
+    """The build's machine-code check on three made-up basic blocks: a clean run, a run with a
+    register copy of one of its accumulators in the middle, and a copy behind the run."""
+    from paper_2508_14848_amd import check_isa
+    clean = "\n".join(["v_mfma_f32_16x16x4_f32 v[192:195], v1, v2, v[192:195]", "ds_read_b128 v[10:13], v5",
+                       "v_mfma_f32_16x16x4_f32 a[4:7], v1, v3, a[4:7]", "s_nop 11", "v_accvgpr_read_b32 v9, a4"])
+    dirty = "\n".join(["v_mfma_f32_16x16x4_f32 a[4:7], v1, v2, a[4:7]", "v_accvgpr_mov_b32 a9, a5",
+                       "v_mfma_f32_16x16x4_f32 a[4:7], v1, v3, a[4:7]"])
+    other = "\n".join(["v_mfma_f64_16x16x4_f64 a[0:7], v[0:1], v[2:3], a[0:7]", "v_accvgpr_mov_b32 a9, a5"])
+    p = tmp_path / "k.s"
+    p.write_text(".LBB0_1:\n" + clean + "\ns_cbranch_scc1 .LBB0_1\n.LBB0_2:\n" + other + "\n")
+    assert check_isa.violations(str(p)) == (1, [])
+    p.write_text(".LBB0_1:\n" + clean + "\ns_branch .LBB0_3\n.LBB0_2:\n" + dirty + "\ns_endpgm\n")
+    n, bad = check_isa.violations(str(p))
+    assert n == 2 and bad == ["v_accvgpr_mov_b32 a9, a5"]
