@@ -33,7 +33,7 @@ ALSO = ("cov16k", "rect32k")
 KERNEL_NAMES = ["gemm_mp_owner_kernel<double%s>", "gemm_mp_owner_kernel<float%s>", "gemm_mp_fp8_region_kernel<0>",
                 "gemm_mp_fp8_region_kernel<1>", "gemm_mp_fp8_region_kernel<2>", "gemm_mp_fp8_region_kernel<3>",
                 "gemm_mp_fp8_region_kernel<4>", "gemm_mp_fp8_region_kernel<5>"]
-INSTANCE = [", false, false", ", true, false", ", true, true"]
+INSTANCE = [", false, false", ", true, false", ", true, true", None]
 
 
 def parse():
@@ -195,7 +195,10 @@ def measure(name, steps, warmup, policy, conversion, cpu_seconds):
     for k, n in enumerate(st["launch_items"][:8]):
         if n:
             kn = KERNEL_NAMES[k]
-            launched.append({"kernel": kn % INSTANCE[st["owner_instance"][k]] if k < 2 else kn, "workgroups": n})
+            if k < 2:
+                inst = INSTANCE[st["owner_instance"][k]]
+                kn = kn % inst if inst else "gemm_mp_owner_low_kernel<false>"
+            launched.append({"kernel": kn, "workgroups": n})
     out = {
         "metric": "effective TFLOP/s (2MNK/t) and % of precision-weighted MFMA peak, 1 GPU",
         "value": flops_total / (ms_per_step * 1e-3) / 1e12,

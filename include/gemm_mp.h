@@ -143,7 +143,8 @@ typedef struct gemm_mp_stats {
                               * regions of tiles made of FP8 / MXFP8 / MXFP4 products only, [5] / [6] of FP16 /
                               * BF16 products only, [7] of MXFP6 products only */
     int32_t owner_instance[2]; /* which instance of the 128 x 128 kernel serves [0] and [1]: 0 plain, 1 the one
-                              * whose DMA ring also takes FP16 products with an FP8 operand, 2 the BF16 one */
+                              * whose DMA ring also takes FP16 products with an FP8 operand, 2 the one for BF16 and
+                              * block-scaled operands, 3 ([0] only) the one for FP64 C tiles without an FP64 product */
     int64_t products_mxfp6;  /* as products_mxfp4, for precision code 7 */
     double flops_mxfp6;
     int64_t tiles_mxfp6[3];

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgemm_mp.so")
 SOURCES = ["gemm_mp_host.hip", "kernels_scan_pack.hip", "kernels_gemm.hip",
            # the GEMM kernels: one template instance per file, compiled in parallel
-           "gemm_owner_d.hip", "gemm_owner_d_mixed.hip", "gemm_owner_d_bf.hip",
+           "gemm_owner_d.hip", "gemm_owner_d_mixed.hip", "gemm_owner_d_bf.hip", "gemm_owner_d_low.hip",
            "gemm_owner_f.hip", "gemm_owner_f_mixed.hip", "gemm_owner_f_bf.hip",
            "gemm_region_fp8.hip", "gemm_region_mxfp8.hip", "gemm_region_mxfp4.hip",
            "gemm_region_fp16.hip", "gemm_region_bf16.hip", "gemm_region_mxfp6.hip"]

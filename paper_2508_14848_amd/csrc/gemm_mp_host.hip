@@ -87,6 +87,7 @@ struct gemm_mp_ctx {
     gemm_mp_stats stats;
     bool mixed32 = false;             // list [1] holds an FP16 / BF16 product with an operand stored in FP8
     bool mixed64 = false;             // the same for list [0]
+    bool low64 = false;               // no region of list [0] has an FP64 product
     bool has_bf16 = false;            // some product of the 128 x 128 kernels has a BF16 or block-scaled operand
     bool kernel_ready = false;
     // sender-side conversion: per tile of A / B and product precision q, the offset of the copy
@@ -443,6 +444,7 @@ void build_schedule(gemm_mp_ctx *c)
     // tiles widened under FP32 / FP64 products) are known to one instance of the 128 x 128 kernel
     // only; it serves both launches as soon as one product of theirs has such an operand.
     c->mixed32 = c->mixed64 = c->has_bf16 = false;
+    c->low64 = true;                                     // no FP64 C tile has an FP64 product
     for (int I = 0; I < MT; ++I)
         for (int J = 0; J < NT; ++J) {
             if (all_fp8[(size_t)I * NT + J] || all_16[(size_t)I * NT + J] || all_mx[(size_t)I * NT + J]) continue;
@@ -456,6 +458,8 @@ void build_schedule(gemm_mp_ctx *c)
             }
             if (C.map[I * NT + J] == GEMM_MP_FP64) c->mixed64 |= mixed;
             else c->mixed32 |= mixed;
+            if (C.map[I * NT + J] == GEMM_MP_FP64)
+                for (int L = 0; L < KT; ++L) c->low64 &= c->q[((size_t)I * NT + J) * KT + L] != GEMM_MP_FP64;
         }
     constexpr int kBins = 8;
     for (int list = 0; list < 8; ++list) {
@@ -508,7 +512,7 @@ void build_schedule(gemm_mp_ctx *c)
         c->stats.launch_items[list] = (int64_t)c->items[list].size();
         c->stats.work_items += (int64_t)c->items[list].size();
     }
-    c->stats.owner_instance[0] = c->has_bf16 ? 2 : c->mixed64 ? 1 : 0;
+    c->stats.owner_instance[0] = c->has_bf16 ? 2 : c->mixed64 ? 1 : c->low64 ? 3 : 0;
     c->stats.owner_instance[1] = c->has_bf16 ? 2 : c->mixed32 ? 1 : 0;
     c->sched_current = true;
 }
@@ -860,6 +864,7 @@ int run_on(gemm_mp_ctx *c, double alpha, double beta, hipStream_t s, ProductDesc
     a.mixed32 = c->mixed32 ? 1 : 0;
     a.mixed64 = c->mixed64 ? 1 : 0;
     a.bf16 = c->has_bf16 ? 1 : 0;
+    a.low64 = c->low64 ? 1 : 0;
     a.nb = c->nb; a.MT = c->MT; a.NT = c->NT; a.KT = c->KT;
     a.kt_eff = alpha == 0.0 ? 0 : c->KT;
     a.alpha = alpha; a.beta = beta;

@@ -136,6 +136,7 @@ struct GemmArgs {
     int32_t n_items64, n_items32, n_items8, n_items_mx, n_items_mx4, n_items_h, n_items_bf, n_items_mx6;
     int32_t mixed32;         // some region of items32 has an FP16 / BF16 product with an operand stored in FP8
     int32_t mixed64;         // the same for items64
+    int32_t low64;           // no region of items64 has an FP64 product
     int32_t bf16;            // some product of the 128 x 128 kernels has a BF16 or block-scaled operand
     int32_t nb, MT, NT, KT;
     int32_t kt_eff;          // KT, or 0 when alpha == 0
@@ -174,7 +175,7 @@ hipError_t gemm_kernel_setup();
 #define GMP_DECLARE_INSTANCE(NAME) \
     hipError_t setup_##NAME();     \
     hipError_t launch_##NAME(const GemmArgs &a, const WorkItem *items, int n, hipStream_t s);
-GMP_DECLARE_INSTANCE(owner_d) GMP_DECLARE_INSTANCE(owner_d_mixed) GMP_DECLARE_INSTANCE(owner_d_bf)
+GMP_DECLARE_INSTANCE(owner_d) GMP_DECLARE_INSTANCE(owner_d_mixed) GMP_DECLARE_INSTANCE(owner_d_bf) GMP_DECLARE_INSTANCE(owner_d_low)
 GMP_DECLARE_INSTANCE(owner_f) GMP_DECLARE_INSTANCE(owner_f_mixed) GMP_DECLARE_INSTANCE(owner_f_bf)
 GMP_DECLARE_INSTANCE(region_fp8) GMP_DECLARE_INSTANCE(region_mxfp8) GMP_DECLARE_INSTANCE(region_mxfp4)
 GMP_DECLARE_INSTANCE(region_fp16) GMP_DECLARE_INSTANCE(region_bf16) GMP_DECLARE_INSTANCE(region_mxfp6)

@@ -337,6 +337,15 @@ __device__ __forceinline__ void load_piece_any(Raw &r, const Product &pr, int nb
     r.lo = __builtin_amdgcn_raw_buffer_load_b128(lo, o.voff, soff, 0);
     r.hi = __builtin_amdgcn_raw_buffer_load_b128(hi, o.voff + 16, soff, 0);
 }
+// The same where no piece is a down-cast (no FP64 tile under an FP32 product): the first half only.
+__device__ __forceinline__ void load_piece_lo(Raw &r, const Product &pr, int nb, int c, int i)
+{
+    const int eoff = c * chunk_elems(pr.q) + (i >> 1) * 32 * nb;
+    const Operand &o = (i & 1) ? pr.b : pr.a;
+    const __amdgpu_buffer_rsrc_t lo = __builtin_amdgcn_make_buffer_rsrc((void *)o.base, 0, o.bytes, 0x00020000);
+    r.lo = __builtin_amdgcn_raw_buffer_load_b128(lo, o.voff, eoff << (3 - o.p), 0);
+    r.hi = r.lo;
+}
 template <int Q>
 __device__ __forceinline__ void store_piece(const Raw &r, const Product &pr, const Geometry &G, char *stage, int i)
 {
@@ -705,6 +714,8 @@ struct ChunkCtx {
     char *wst;         // the latter's address
     HiScale sa, sb;    // MODE 0: the operands' scales
 };
+// MODE: 3 = as 2 where no operand is an FP64 tile under an FP32 product: only the first 16 bytes
+// of a piece are fetched, and only they stay in registers until the next product's loop.
 // MODE: 0 = a chunk followed by another of the same product; 1 = the last chunk, which also
 // stages chunk 0 of the next product (conversion chosen at run time); 2 = the last chunk, which
 // only loads it into `r` (the next product's own loop converts and stores it).
@@ -715,18 +726,19 @@ __device__ __forceinline__ void chunk_position(Acc (&acc)[4][4], u32x4 (&fr)[2][
     mfma_half<Q, BASE, u>(acc, fr);
     SCHED_FENCE();
     if constexpr (u < 16 && (u & 1) == 0) {
-        if constexpr (MODE != 0) load_piece_any(r[u >> 1], pr, nb, c, u >> 1);
+        if constexpr (MODE == 3) load_piece_lo(r[u >> 1], pr, nb, c, u >> 1);
+        else if constexpr (MODE != 0) load_piece_any(r[u >> 1], pr, nb, c, u >> 1);
         else if constexpr (PA >= 0) load_piece_exact<Q, PA, PB>(r[u >> 1], pr, nb, c, u >> 1);
         else load_piece(r[u >> 1], pr, nb, c, u >> 1);
     } else if constexpr (u < 16) {
         constexpr int t = ((u >> 1) + 4) & 7;                // B0..B3, A0..A3
         fr[1][t] = read_frag(F, X.so, 1, t);
-    } else if constexpr (MODE != 2 && u >= 34 && u <= 48 && (u & 1) == 0) {
+    } else if constexpr (MODE != 2 && MODE != 3 && u >= 34 && u <= 48 && (u & 1) == 0) {
         constexpr int i = (u - 34) >> 1;
         if constexpr (MODE == 0 && PA >= 0) store_piece_exact<Q, PA, PB>(r[i], X.sa, X.sb, G, X.wst, i);
         else if constexpr (MODE == 0) store_piece<Q>(r[i], pr, G, X.wst, i);
         else store_piece_any(r[i], pr, G, X.wst, i);   // q < 0 (nothing follows): stores nothing
-    } else if constexpr (MODE != 2 && u == 52) {
+    } else if constexpr (MODE != 2 && MODE != 3 && u == 52) {
         __syncthreads();
     } else if constexpr (MODE == 0 && u >= 53 && u <= 60) {
         constexpr int t = (u - 53 + 4) & 7;                  // B0..B3, A0..A3
@@ -961,7 +973,10 @@ __device__ __forceinline__ Product product_loop_widening(Acc (&acc)[4][4], const
 // All chunks of one FP64 / FP32 tile product; returns the next product.  On exit that one's
 // chunk 0 is in `hand` (raw = true: it is an FP64 / FP32 product too), or staged in LDS stage
 // `stage` (any other product that wants it).
-template <int Q, int BASE, bool LATE, bool MIXED, typename Acc>
+// LATE: 0 = the last chunk stages the next product's first chunk in LDS; 1 = it only loads it, and
+// the next product's own loop converts and stores it; 2 = as 1 in a kernel without FP64 products
+// (no FP64 tile feeds an FP32 product: half the registers on the way).
+template <int Q, int BASE, int LATE, bool MIXED, typename Acc>
 __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], const Product &cur, const Walk &W, int Lnext, char *lds, int &stage,
                                                           const Geometry &G0, const Region &R, Raw (&hand)[8], bool &raw)
 {
@@ -988,8 +1003,8 @@ __device__ __forceinline__ Product product_loop_pipelined(Acc (&acc)[4][4], cons
     Product ld = next;                                 // nothing to fetch: descriptors of length zero
     ld.a.bytes = want ? next.a.bytes : 0;
     ld.b.bytes = want ? next.b.bytes : 0;
-    if constexpr (LATE) {
-        pipelined_chunk<Q, BASE, 2>(acc, fr, hand, ld, 0, lds, stage, F, G, R.nb);
+    if constexpr (LATE != 0) {
+        pipelined_chunk<Q, BASE, (LATE == 2 ? 3 : 2)>(acc, fr, hand, ld, 0, lds, stage, F, G, R.nb);
         acc_fence<BASE>(acc);
         stage ^= 1;
         raw = want && next.q <= Q32;
@@ -1287,7 +1302,7 @@ __device__ __forceinline__ void lo_chunk(f4 (&acc)[4][4], u32x4 (&fr)[2][16], co
     }
 }
 
-template <typename AccS>
+template <typename AccS, bool BLOCKWISE = false>
 __device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int esum);
 
 // A per-product FP32 accumulator set to zero, written register by register with an immediate.
@@ -1608,7 +1623,10 @@ __device__ __forceinline__ Product product_loop_simple(f4 (&acc)[4][4], const Pr
 }
 
 // The finished tile product joins the running sum once: s += 2^esum * t.
-template <typename AccS>
+// BLOCKWISE (FP64 sums kept in accumulation registers, which the vector ALU cannot address): each
+// block of four sums completes the round trip read - add - write back before the next one sets
+// out; left to itself the compiler reads all 128 registers first and spills what else is live.
+template <typename AccS, bool BLOCKWISE>
 __device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int esum)
 {
     constexpr bool kDouble = std::is_same<AccS, d4>::value;
@@ -1616,6 +1634,16 @@ __device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int e
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
+            if constexpr (BLOCKWISE && kDouble) {
+                d4 x = s[i][j];
+                asm volatile("" : "+v"(x));
+#pragma unroll
+                for (int v = 0; v < 4; ++v) x[v] = x[v] + ldexp((double)t[i][j][v], esum);
+                asm volatile("" : "+v"(x));
+                s[i][j] = x;
+                asm volatile("" : "+a"(s[i][j]));
+                continue;
+            }
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 if constexpr (kDouble) s[i][j][v] = s[i][j][v] + ldexp((double)t[i][j][v], esum);
@@ -1627,10 +1655,16 @@ __device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int e
 // T = double: FP64 C tiles; the running sum s is FP64 and every product below FP64 is formed
 //             in the FP32 accumulator t first.
 // T = float : FP32 C tiles; FP32 products continue s, FP16 / FP8 products go through t.
-template <typename T, bool MIXED, bool BF>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
+// LOW (T = double only): the instance for FP64 C tiles none of whose products is FP64 (a
+//             covariance matrix whose tiles the norm rule stores in FP32 / FP16 throughout).  It
+//             carries no FP64 product loop, which leaves the registers for what the FP32-tile kernel
+//             does: the per-product accumulator in the pinned vector registers, and the next
+//             product's first chunk handed over in registers and converted by that product's own
+//             specialised loop.
+template <typename T, bool MIXED, bool BF, bool LOW>
+__device__ __forceinline__ void owner_body(const WorkItem *__restrict__ items)
 {
+    static_assert(!LOW || std::is_same<T, double>::value, "LOW is an instance for FP64 C tiles");
     using AccS = typename std::conditional<std::is_same<T, double>::value, d4, f4>::type;
     constexpr int QT = std::is_same<T, double>::value ? Q64 : Q32;
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -1700,16 +1734,27 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
         // (only the instance for the formats beyond FP64 / FP32 / FP16 / FP8 carries the widening loop:
         // the host launches it whenever some product outside the 256 x 256 regions has such an operand)
         const bool widening = BF && is_widening(cur);
-        if (q == QT) {
+        if (LOW && q == QT) {
+            next = cur;                            // not reachable: the host launches this instance only without FP64 products
+            next.q = -1;
+        } else if (q == QT) {
             if (BF && widening) next = product_loop_widening<QT, (QT == Q32 ? 192 : -1), MIXED>(s, cur, W, L + 1, lds, stage, G, R, raw);
-            else next = product_loop_pipelined<QT, (QT == Q32 ? 192 : -1), QT == Q32, MIXED>(s, cur, W, L + 1, lds, stage, G, R, hand, raw);
+            else next = product_loop_pipelined<QT, (QT == Q32 ? 192 : -1), (QT == Q32 ? 1 : 0), MIXED>(s, cur, W, L + 1, lds, stage, G, R, hand, raw);
         } else {
-            if constexpr (QT == Q64) {
+            if constexpr (QT == Q64 && LOW) {
+                f4 t[4][4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
+                next = product_loop_pipelined<Q32, 192, 2, MIXED>(t, cur, W, L + 1, lds, stage, G, R, hand, raw);
+                fold<AccS, true>(s, t, 0);
+            } else if constexpr (QT == Q64) {
                 // an FP32 product of an FP64 C tile: its FP32 accumulator lives only for that product
                 f4 t[4][4];
                 zero_side(t);
                 if (BF && widening) next = product_loop_widening<Q32, -1, MIXED>(t, cur, W, L + 1, lds, stage, G, R, raw);
-                else next = product_loop_pipelined<Q32, -1, false, MIXED>(t, cur, W, L + 1, lds, stage, G, R, hand, raw);
+                else next = product_loop_pipelined<Q32, -1, 0, MIXED>(t, cur, W, L + 1, lds, stage, G, R, hand, raw);
                 fold(s, t, 0);
             } else {
                 next = cur;                        // not reachable: the host never schedules FP64 products on FP32 tiles
@@ -1788,6 +1833,25 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 
 // One instance per translation unit: its set-up call (the dynamic LDS size must be raised once
 // per kernel) and its launcher.
+namespace gmp {
+template <typename T, bool MIXED, bool BF>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
+{
+    (void)P;                                       // read through the kernel argument segment (args())
+    owner_body<T, MIXED, BF, false>(items);
+}
+// FP64 C tiles without an FP64 product (see owner_body).  A template only so that the one
+// translation unit that names it compiles it; MIXED: as for the other instances.
+template <bool MIXED>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void gemm_mp_owner_low_kernel(GemmArgs P, const WorkItem *__restrict__ items)
+{
+    (void)P;
+    owner_body<double, MIXED, false, true>(items);
+}
+}  // namespace gmp
+
 #define GMP_OWNER_INSTANCE(NAME, T, MIXED, BF)                                                              \
     namespace gmp {                                                                                         \
     hipError_t setup_##NAME()                                                                               \
@@ -1798,6 +1862,19 @@ void gemm_mp_owner_kernel(GemmArgs P, const WorkItem *__restrict__ items)
     hipError_t launch_##NAME(const GemmArgs &a, const WorkItem *items, int n, hipStream_t s)                \
     {                                                                                                       \
         gemm_mp_owner_kernel<T, MIXED, BF><<<dim3((unsigned)n), dim3(kThreads), kLdsBytes, s>>>(a, items);  \
+        return hipGetLastError();                                                                           \
+    }                                                                                                       \
+    }
+#define GMP_OWNER_LOW_INSTANCE(NAME)                                                                        \
+    namespace gmp {                                                                                         \
+    hipError_t setup_##NAME()                                                                               \
+    {                                                                                                       \
+        return hipFuncSetAttribute((const void *)gemm_mp_owner_low_kernel<false>,                                 \
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);                  \
+    }                                                                                                       \
+    hipError_t launch_##NAME(const GemmArgs &a, const WorkItem *items, int n, hipStream_t s)                \
+    {                                                                                                       \
+        gemm_mp_owner_low_kernel<false><<<dim3((unsigned)n), dim3(kThreads), kLdsBytes, s>>>(a, items);     \
         return hipGetLastError();                                                                           \
     }                                                                                                       \
     }

@@ -174,7 +174,7 @@ hipError_t launch_convert(const ConvertJob *jobs_dev, int njobs, uint32_t max_n1
 
 hipError_t gemm_kernel_setup()
 {
-    hipError_t (*const setups[12])() = {setup_owner_d, setup_owner_d_mixed, setup_owner_d_bf, setup_owner_f, setup_owner_f_mixed,
+    hipError_t (*const setups[13])() = {setup_owner_d_low, setup_owner_d, setup_owner_d_mixed, setup_owner_d_bf, setup_owner_f, setup_owner_f_mixed,
                                         setup_owner_f_bf, setup_region_fp8, setup_region_mxfp8, setup_region_mxfp4, setup_region_fp16,
                                         setup_region_bf16, setup_region_mxfp6};
     for (auto f : setups) {
@@ -204,9 +204,10 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s, const LaunchLanes *lane
         int n;
     };
     // BF16 tiles among the operands: the instances that know the BF16 matrix instruction; FP16 /
-    // BF16 products with an FP8 operand: the instances whose DMA ring takes them
+    // BF16 products with an FP8 operand: the instances whose DMA ring takes them; FP64 C tiles
+    // without an FP64 product: the instance without the FP64 product loop
     const Kind all[8] = {
-        {a.bf16 ? launch_owner_d_bf : a.mixed64 ? launch_owner_d_mixed : launch_owner_d, a.items64, a.n_items64},
+        {a.bf16 ? launch_owner_d_bf : a.mixed64 ? launch_owner_d_mixed : a.low64 ? launch_owner_d_low : launch_owner_d, a.items64, a.n_items64},
         {a.bf16 ? launch_owner_f_bf : a.mixed32 ? launch_owner_f_mixed : launch_owner_f, a.items32, a.n_items32},
         {launch_region_fp8, a.items8, a.n_items8},
         {launch_region_mxfp8, a.items_mx, a.n_items_mx},

@@ -163,6 +163,48 @@ def test_pack_is_bit_exact_on_hard_values_and_unpack_round_trips():
             assert np.array_equal(back[ok], want[ok])
 
 
+def test_fp64_tiles_without_an_fp64_product_take_the_instance_without_the_fp64_loop():
+    """FP64 C tiles whose operands are all stored in FP32 / FP16 (what the norm rule makes of a
+    covariance matrix) run on an instance of their own: per-product accumulator in the pinned
+    registers, first chunk of the next product handed over in registers, block-wise fold.  Small
+    integers must come out exactly through every transition between FP32 products (with and
+    without an FP16 operand) and runs of FP16 ring products, old C included; one FP64 tile among
+    the operands sends the same problem back to the general instance, with the same result."""
+    import torch
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(171)
+    for (nb, MT, NT, KT) in ((128, 2, 2, 6), (256, 1, 2, 7), (512, 1, 1, 4)):
+        M, N, K = MT * nb, NT * nb, KT * nb
+        for trial in range(3):
+            A = rng.integers(-3, 4, (M, K)).astype(np.float64)
+            B = rng.integers(-3, 4, (K, N)).astype(np.float64)
+            C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
+            mA = rng.choice([FP32, FP16], (MT, KT), p=[0.6, 0.4]).astype(np.uint16)
+            mB = rng.choice([FP32, FP16], (KT, NT), p=[0.6, 0.4]).astype(np.uint16)
+            if trial == 1:
+                mA[:, KT // 2:] = FP16                     # a run of ring products at the end of some reductions
+                mB[KT // 2:, :] = FP16
+            mC = np.full((MT, NT), FP64, dtype=np.uint16)
+            if NT > 1:
+                mC[0, 1] = FP32
+            _say("FP64 tiles without FP64 products:", (nb, MT, NT, KT), "trial", trial)
+            want = (2 * (A.astype(np.int64) @ B.astype(np.int64)) - 3 * C0.astype(np.int64)).astype(np.float64)
+            results = []
+            for with_fp64_operand in (False, True):
+                mA2 = mA.copy()
+                if with_fp64_operand:
+                    mA2[0, 0] = FP64
+                d = DeviceGemmMP(M, N, K, nb)
+                for which, m, X in (("A", mA2, A), ("B", mB, B), ("C", mC, C0)):
+                    d.set_precision_map(which, m)
+                    d.pack_tiles(which, torch.from_numpy(X).cuda())
+                assert d.ctx.get_stats()["owner_instance"][0] == (0 if with_fp64_operand else 3)
+                d.run(2.0, -3.0)
+                results.append(d.unpack_tiles("C").cpu().numpy())
+                assert np.array_equal(results[-1], want), (nb, trial, with_fp64_operand)
+    torch.cuda.synchronize()
+
+
 def test_small_integer_inputs_are_exact_for_every_precision_combination():
     """Entries in {-3..3}: every format holds them exactly and every partial sum is a small
     integer, so the GPU result must equal the integer product bit for bit, whatever the maps.
