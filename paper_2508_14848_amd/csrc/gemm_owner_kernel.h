@@ -344,7 +344,7 @@ __device__ __forceinline__ void load_piece_lo(Raw &r, const Product &pr, int nb,
     const Operand &o = (i & 1) ? pr.b : pr.a;
     const __amdgpu_buffer_rsrc_t lo = __builtin_amdgcn_make_buffer_rsrc((void *)o.base, 0, o.bytes, 0x00020000);
     r.lo = __builtin_amdgcn_raw_buffer_load_b128(lo, o.voff, eoff << (3 - o.p), 0);
-    r.hi = r.lo;
+    r.hi = u32x4{0, 0, 0, 0};                          // never read: only a down-cast looks at it
 }
 template <int Q>
 __device__ __forceinline__ void store_piece(const Raw &r, const Product &pr, const Geometry &G, char *stage, int i)
