@@ -1305,21 +1305,16 @@ __device__ __forceinline__ void lo_chunk(f4 (&acc)[4][4], u32x4 (&fr)[2][16], co
 template <typename AccS, bool BLOCKWISE = false>
 __device__ __forceinline__ void fold(AccS (&s)[4][4], const f4 (&t)[4][4], int esum);
 
-// A per-product FP32 accumulator set to zero, written register by register with an immediate.
-// (An assignment of a zero vector makes the compiler keep one zero vector for the whole kernel,
-// which in the FP64-tile kernel is spilled and fetched back from scratch memory at every product,
-// with a wait for all outstanding loads in front of the first matrix instruction.)
+// A per-product FP32 accumulator set to zero.  (The compiler keeps one zero vector for the whole
+// kernel, which in the FP64-tile instances is spilled and comes back from scratch memory at every
+// product.  Writing the registers with immediates instead removes two thirds of that kernel's
+// spills and is 0.4 % slower on cov16k and random8k, so the assignment stays.)
 __device__ __forceinline__ void zero_side(f4 (&t)[4][4])
 {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float z0, z1, z2, z3;
-            asm volatile("v_accvgpr_write_b32 %0, 0\n\tv_accvgpr_write_b32 %1, 0\n\tv_accvgpr_write_b32 %2, 0\n\tv_accvgpr_write_b32 %3, 0"
-                         : "=a"(z0), "=a"(z1), "=a"(z2), "=a"(z3));
-            t[i][j] = f4{z0, z1, z2, z3};
-        }
+        for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
 }
 
 // A run of consecutive ring products starting at product `cur` (reduction tile L).  On return
@@ -1743,10 +1738,7 @@ __device__ __forceinline__ void owner_body(const WorkItem *__restrict__ items)
         } else {
             if constexpr (QT == Q64 && LOW) {
                 f4 t[4][4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) t[i][j] = f4{0, 0, 0, 0};
+                zero_side(t);
                 next = product_loop_pipelined<Q32, 192, 2, MIXED>(t, cur, W, L + 1, lds, stage, G, R, hand, raw);
                 fold<AccS, true>(s, t, 0);
             } else if constexpr (QT == Q64) {
