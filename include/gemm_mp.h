@@ -62,9 +62,8 @@
  * elements being 24 bytes with element k of the block in bits 6k .. 6k+5 (least significant bit
  * first, as the matrix instruction reads them), then the tile_nb^2/32 scale bytes, row by row.  The
  * element bytes are laid out for the kernel that multiplies them: panel by panel of 128 reduction
- * indices (the last panel is 64 wide where tile_nb is an odd multiple of 64); inside a panel row
- * after row (96 bytes each, 48 in a narrow last panel); inside a row of a panel, block b of the
- * panel's four (two) at block position (b + row/8) mod 4 (mod 2).  Block-scaled instruction
+ * indices; inside a panel row after row (96 bytes each); inside a row of a panel, block b of the
+ * panel's four at block position (b + row/8) mod 4.  Block-scaled instruction
  * where every product of a C tile is MXFP6 x MXFP6 and tile_nb is a multiple of 256.
  *
  * C tiles stored in FP16 / FP8 (formats beyond FP64 / FP32 are what the paper's

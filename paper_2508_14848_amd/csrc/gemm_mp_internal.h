@@ -37,8 +37,8 @@ __host__ __device__ inline float fp6_value(uint32_t code)
 }
 
 // Where the six-bit codes of an MXFP6 tile lie.  The elements of a tile are stored panel by panel:
-// a panel holds 128 consecutive reduction indices (four blocks of 32; the last panel of a tile size
-// that is an odd multiple of 64 holds 64) of every packed row, row after row, so that the part of a
+// a panel holds 128 consecutive reduction indices (four blocks of 32; tile sizes are multiples of
+// 128) of every packed row, row after row, 96 bytes each, so that the part of a
 // panel that 256 rows take up is one contiguous piece of memory which the 256 x 256 kernel copies to
 // LDS as it is.  Inside a row of a panel the blocks are rotated by (row / 8): block b sits at block
 // position (b + row / 8) mod 4, which spreads the block that 32 lanes read from 32 consecutive rows
@@ -46,10 +46,8 @@ __host__ __device__ inline float fp6_value(uint32_t code)
 // that hold the elements k .. k + 3 (k a multiple of 4) of packed row r.
 __host__ __device__ inline int64_t fp6_group_offset(int nb, int r, int k)
 {
-    const int p = k >> 7;
-    const int width = nb - (p << 7) < 128 ? nb - (p << 7) : 128;
-    const int pos = (((k >> 5) & 3) + (r >> 3)) & ((width >> 5) - 1);
-    return (int64_t)p * nb * 96 + (int64_t)r * (width / 4 * 3) + pos * 24 + ((k & 31) >> 2) * 3;
+    const int pos = (((k >> 5) & 3) + (r >> 3)) & 3;
+    return (int64_t)(k >> 7) * nb * 96 + (int64_t)r * 96 + pos * 24 + ((k & 31) >> 2) * 3;
 }
 
 // Product precision (code) for stored precisions pA, pB, C tile precision pC.

@@ -978,9 +978,8 @@ def test_mxfp8_tiles_pack_bit_for_bit_and_multiply_on_the_block_scaled_instructi
 def _fp6_bytes(codes, nb):
     """The element bytes of an MXFP6 tile from its six-bit codes (nb packed rows of nb codes), as the
     interface describes them: four codes to three bytes, code k of a group in bits 6k .. 6k+5 of the
-    group's 24; the tile stored panel by panel of 128 reduction indices (the last one 64 wide where
-    nb is an odd multiple of 64), row after row inside a panel, the blocks of 32 inside a row of a
-    panel rotated by (row // 8)."""
+    group's 24; the tile stored panel by panel of 128 reduction indices, row after row inside a
+    panel, the blocks of 32 inside a row of a panel rotated by (row // 8)."""
     c = codes.reshape(nb, nb // 4, 4).astype(np.uint32)
     w = c[:, :, 0] | (c[:, :, 1] << 6) | (c[:, :, 2] << 12) | (c[:, :, 3] << 18)
     groups = np.stack([w & 255, (w >> 8) & 255, (w >> 16) & 255], axis=2).astype(np.uint8)      # [row][group of 4][3]
