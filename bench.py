@@ -57,6 +57,12 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=24.0, help="target CPU time of the oracle sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-also", action="store_true", help="only the headline workload")
+    ap.add_argument("--operand-values", default="workload", choices=["workload", "zeros"],
+                    help="zeros: format-X workloads only, A and B all zero (same kernels, same accesses; shows how much of a "
+                         "format's rate the chip's power management takes on real data)")
+    ap.add_argument("--sample-clocks", type=float, default=0.0, metavar="SECONDS",
+                    help="after the timed steps, loop gemm_mp_run alone for SECONDS while a thread reads the shader clock "
+                         "from rocm-smi about once a second; reported under clock_probe")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy, three times (reference for the HBM byte counters)")
     return ap.parse_args()
@@ -107,7 +113,54 @@ def cpu_baseline(w, A, B, C0, seconds):
                       % (done_rows, nb, len(jobs), w.name, done_rows * flops_per_row)}
 
 
-def measure(name, steps, warmup, policy, conversion, cpu_seconds):
+def clock_probe(d, w, seconds):
+    """Loop gemm_mp_run alone for `seconds`; a thread samples the shader clock meanwhile (rocm-smi, a child process)."""
+    import re
+    import subprocess
+    import threading
+
+    import numpy as np
+    import torch
+
+    samples, stop = [], threading.Event()
+
+    def sampler():
+        while not stop.is_set():
+            try:
+                txt = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20).stdout
+                m = re.search(r"sclk[^\n]*\((\d+)Mhz\)", txt)
+                if m:
+                    samples.append(int(m.group(1)))
+            except Exception:
+                pass
+            stop.wait(0.5)
+
+    d.run(w.alpha, w.beta)
+    torch.cuda.synchronize()
+    th = threading.Thread(target=sampler)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    th.start()
+    time.sleep(1.0)                       # the first sample may still see the idle clock
+    t0, runs = time.perf_counter(), 0
+    e0.record()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(4):
+            d.run(w.alpha, w.beta)
+        runs += 4
+        torch.cuda.synchronize()
+    e1.record()
+    torch.cuda.synchronize()
+    stop.set()
+    th.join()
+    under_load = samples[1:] if len(samples) > 1 else samples
+    return {"seconds": seconds, "runs": runs, "run_ms": e0.elapsed_time(e1) / runs,
+            "sclk_mhz": {"median": float(np.median(under_load)) if under_load else None,
+                         "min": min(under_load) if under_load else None, "max": max(under_load) if under_load else None,
+                         "samples": len(under_load)},
+            "source": "rocm-smi --showclocks, about one reading a second while gemm_mp_run loops (beta as in the workload)"}
+
+
+def measure(name, steps, warmup, policy, conversion, cpu_seconds, operand_values="workload", clock_seconds=0.0):
     """Run one workload; returns the fields of its JSON record.  cpu_seconds = 0: no CPU baseline."""
     import numpy as np
     import torch
@@ -124,6 +177,10 @@ def measure(name, steps, warmup, policy, conversion, cpu_seconds):
     B = A if w.a_equals_b else w.dense("B")
     C0 = w.dense("C") if w.beta != 0.0 else None
     t_gen = time.perf_counter() - t0
+    if operand_values == "zeros":
+        assert name.startswith("format-"), "--operand-values zeros: format-X workloads only (their maps do not depend on the data)"
+        A = np.zeros_like(A)
+        B = A if w.a_equals_b else np.zeros_like(B)
     dA = torch.from_numpy(A).to(dev)
     dB = dA if w.a_equals_b else torch.from_numpy(B).to(dev)
     dC = torch.from_numpy(C0).to(dev) if C0 is not None else None
@@ -213,7 +270,8 @@ def measure(name, steps, warmup, policy, conversion, cpu_seconds):
                    "converted_bytes": st["converted_bytes"],
                    "products_by_precision": dict(list(zip(DTYPE_NAMES, st["products"])) +
                                                  [(n, st["products_" + n]) for n in ("bf16", "mxfp8", "mxfp4", "mxfp6") if st["products_" + n]]),
-                   "work_items": st["work_items"], "host_generation_s": round(t_gen, 1)},
+                   "work_items": st["work_items"], "host_generation_s": round(t_gen, 1),
+                   "operand_values": operand_values},
         "stages_ms": {k: float(np.mean(v)) for k, v in stage_ms.items()},
         "run_only": {"ms": run_ms, "min_ms": float(np.min(stage_ms["run"])), "effective_tflops": achieved,
                      "roofline_ms": t_roof * 1e3, "frac_of_precision_weighted_peak": t_roof * 1e3 / run_ms},
@@ -225,6 +283,8 @@ def measure(name, steps, warmup, policy, conversion, cpu_seconds):
                              "traffic = HBM bytes per gemm_mp_run from rocprofv3 counter passes of this command, kept in "
                              "profiles/ (null: no pass recorded for this workload)"},
     }
+    if clock_seconds > 0:
+        out["clock_probe"] = clock_probe(d, w, clock_seconds)
     if cpu_seconds > 0 and not w.name.startswith("format-"):
         out["cpu_baseline"] = cpu_baseline(w, A, B, C0, cpu_seconds)
     del d, dA, dB, dC, A, B, C0
@@ -253,7 +313,8 @@ def main():
         print(json.dumps({"calibration": "plain copy", "bytes_read": src.numel() * 8, "bytes_written": src.numel() * 8}))
         return
     name = args.workload or HEADLINE
-    out = measure(name, args.steps, args.warmup, args.policy, args.conversion, 0.0 if args.no_cpu_baseline else args.cpu_seconds)
+    out = measure(name, args.steps, args.warmup, args.policy, args.conversion, 0.0 if args.no_cpu_baseline else args.cpu_seconds,
+                  args.operand_values, args.sample_clocks)
     if args.workload is None and not args.no_also:
         # the other configurations of 16384^3 and more, a few steps each: run-only figures
         out["also"] = {}
