@@ -1757,7 +1757,14 @@ __device__ __forceinline__ void owner_body(const WorkItem *__restrict__ items)
         ++L;
     }
 
-    // Epilogue: v = alpha*s (+ beta*c0): two rounded products and one rounded sum in T.
+    // Epilogue: v = alpha*s (+ beta*c0): two rounded products and one rounded sum in T.  C is
+    // written with streaming stores: a region is written once and not read again, and should not
+    // displace the operand panels from L2.
+#ifdef GMP_OWNER_PLAIN_STORES
+#define GMP_STORE_C(v, p) (*(p) = (v))
+#else
+#define GMP_STORE_C(v, p) __builtin_nontemporal_store((v), (p))
+#endif
     const ArgsPtr K = args();
     const T alpha = (T)K->alpha, beta = (T)K->beta;
     const bool use_c = K->beta != 0.0;
@@ -1778,7 +1785,7 @@ __device__ __forceinline__ void owner_body(const WorkItem *__restrict__ items)
                     GlobalT p = ctile + (int64_t)row * R.nb + col;
                     T val = alpha * (T)s[mt][nt][v];
                     if (use_c) { const T bc = beta * *p; val = val + bc; }
-                    *p = val;
+                    GMP_STORE_C(val, p);
                 }
     } else {
         // FP32 tiles: the accumulator layout (a lane holds a 4-row column piece of each 16x16
@@ -1816,7 +1823,7 @@ __device__ __forceinline__ void owner_body(const WorkItem *__restrict__ items)
 #pragma unroll
                 for (int i = 0; i < kVec; ++i) { const T bc = beta * c0[i]; val[i] = val[i] + bc; }
             }
-            *gp = val;
+            GMP_STORE_C(val, gp);
         }
     }
 }

@@ -512,7 +512,9 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
                 for (int v = 0; v < 16; ++v) {
                     float val = alpha * (FMT == 3 ? ldexpf(acc[mt][nt][v], e_cur) : acc[mt][nt][v]);
                     if (use_c) { const float bc = beta * c0[v]; val = val + bc; }
-                    cbase[(int64_t)(mt * 32 + 8 * (v >> 2) + (v & 3)) * nb + nt * 32] = val;
+                    // a streaming store: the C block is written once and not read again, and it must
+                    // not push the operand panels, which fifteen other regions are reading, out of L2
+                    __builtin_nontemporal_store(val, &cbase[(int64_t)(mt * 32 + 8 * (v >> 2) + (v & 3)) * nb + nt * 32]);
                 }
             }
         again = true;
