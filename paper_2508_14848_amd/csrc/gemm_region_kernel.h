@@ -25,6 +25,11 @@ constexpr int kBigMacro = 256;
 constexpr int kBigOperand = kBigMacro * kRowBytes;     // 32 KB
 constexpr int kBigStage = 2 * kBigOperand;             // A then B
 constexpr int kBigLdsBytes = 2 * kBigStage;            // 128 KB
+// Block-scaled formats, tiles of up to 1024: the scale bytes of a product's 256 + 256 rows travel
+// through two buffers behind the stages (at most 8 KB per operand and product).
+constexpr int kBigScaleOperand = 8192;
+constexpr int kBigScaleBuf = 2 * kBigScaleOperand;     // A then B
+constexpr int kBigLdsScaled = kBigLdsBytes + 2 * kBigScaleBuf;   // 160 KB
 typedef float f16v __attribute__((ext_vector_type(16)));
 
 struct BigGeom {
@@ -147,6 +152,14 @@ struct BigScaleGeom {
     int soa, sob;        // byte offset of this lane's scale row, A block 0 / B block 0, from the tile's start
     int shift;           // 8 * (lane / 32)
     int rot, n;          // as in BigGeom
+    // scales through LDS (tiles of up to 1024: a row has at most 32 scale bytes):
+    int rb;              // scale bytes per tile row, nb / 32
+    int ua, ub;          // byte offset, from the tile's start, of the scale rows of the region's 256 rows of A / B
+    int la, lb;          // this lane's scale row in a scale buffer, A block 0 / B block 0
+    int lane16;          // 16 * lane
+};
+struct BigScaleTake {    // where the scale words of the following chunk pair are read from, if from LDS
+    int buf, c;
 };
 // One call fetches the scales of the chunk pair c, c + 1 (c even) with one load per row block.
 // (A wave's scale loads touch 32 different cache lines each, as costly for the vector memory path
@@ -169,6 +182,47 @@ __device__ __forceinline__ void big_load_scales(int (&d)[32], const BigScaleGeom
         } else {
             const u32x2 x = *(const u32x2 *)(uintptr_t)(a + (uint64_t)(SG.soa + t * nb + 4 * c));
             const u32x2 y = *(const u32x2 *)(uintptr_t)(b + (uint64_t)(SG.sob + t * nb + 4 * c));
+            d[t] = (int)x.x; d[8 + t] = (int)x.y; d[4 + t] = (int)y.x; d[12 + t] = (int)y.y;
+        }
+    }
+}
+// The scale bytes of a product through LDS.  The wave's scale loads from global memory touch 32
+// cache lines each (one row's 8 or 16 bytes out of every line), and a chunk pair needs eight of
+// them: measured 7-12 % of the run time of the three block-scaled kernels.  The scale rows of a
+// region's 256 rows are one contiguous block of 256 * nb / 32 bytes per operand and product, which
+// global -> LDS requests move in whole lines: four requests per wave and product (two per operand;
+// a request beyond the block has a descriptor of length zero), issued a product ahead.
+template <int FMT>
+__device__ __forceinline__ void big_request_scales(const BigSource &S, const BigScaleGeom &SG, int buf, int wave)
+{
+#pragma unroll
+    for (int op = 0; op < 2; ++op)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int piece = wave * 2 + h;                  // 1 KB pieces of the operand's block
+            const int block = 256 * SG.rb;
+            const int bytes = (S.bytes != 0 && piece * 1024 < block) ? block : 0;
+            big_dma_one((op ? S.b : S.a) + (uint64_t)(op ? SG.ub : SG.ua), bytes, SG.lane16, uni(piece * 1024),
+                        (unsigned)uni(kBigLdsBytes + buf * kBigScaleBuf + op * kBigScaleOperand + piece * 1024));
+        }
+}
+// The words big_load_scales delivers, read from scale buffer `buf` instead.
+template <int FMT>
+__device__ __forceinline__ void big_read_scales(int (&d)[32], const BigScaleGeom &SG, const char *lds, int buf, int c)
+{
+    c += SG.rot;
+    if (c >= SG.n) c -= SG.n;
+    const char *p = lds + kBigLdsBytes + buf * kBigScaleBuf;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        if constexpr (FMT == 2) {
+            const u32x4 x = *(const u32x4 *)(p + SG.la + t * 32 * SG.rb + 8 * c);
+            const u32x4 y = *(const u32x4 *)(p + SG.lb + t * 32 * SG.rb + 8 * c);
+            d[t] = (int)x.x; d[8 + t] = (int)x.y; d[16 + t] = (int)x.z; d[24 + t] = (int)x.w;
+            d[4 + t] = (int)y.x; d[12 + t] = (int)y.y; d[20 + t] = (int)y.z; d[28 + t] = (int)y.w;
+        } else {
+            const u32x2 x = *(const u32x2 *)(p + SG.la + t * 32 * SG.rb + 4 * c);
+            const u32x2 y = *(const u32x2 *)(p + SG.lb + t * 32 * SG.rb + 4 * c);
             d[t] = (int)x.x; d[8 + t] = (int)x.y; d[4 + t] = (int)y.x; d[12 + t] = (int)y.y;
         }
     }
@@ -225,9 +279,10 @@ __device__ __forceinline__ void big_rescale(f16v (&acc)[4][4], float ratio)
 // by the caller just before this call: they are taken over (shifted into place, into `nx`) right
 // behind the wait in the middle of the chunk, the one point where nothing else is in flight, so
 // that no other wait for them is needed.
-template <int STAGE, int FMT, bool TAKE, int SO>
+template <int STAGE, int FMT, bool TAKE, int SO, bool LS = false>
 __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], typename BigFrag<FMT>::type (&f)[2][8], const BigGeom &BG, const char *lds, const BigSource &S2,
-                                          int sa, int sb, const int (&sc)[32], const int (&raw)[32], int (&nx)[32], int shift)
+                                          int sa, int sb, const int (&sc)[32], int (&raw)[32], int (&nx)[32], const BigScaleGeom &SG,
+                                          const BigScaleTake tk = BigScaleTake{0, 0})
 {
     constexpr bool MX = FMT == 1 || FMT == 5;
     constexpr int EL = FMT == 5 ? 2 : 0;                     // element format of the instruction: e4m3, or e2m3
@@ -258,8 +313,10 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], typename BigFrag<FM
 #endif
     __syncthreads();                                         // ... in every wave; and all are done reading this stage
     if constexpr (TAKE) {
+        // from LDS: read here, behind the barrier that has just published them where they are a product's first
+        if constexpr (LS) big_read_scales<FMT>(raw, SG, lds, tk.buf, tk.c);
 #pragma unroll
-        for (int t = 0; t < (FMT == 2 ? 32 : 16); ++t) nx[t] = (int)((uint32_t)raw[t] >> shift);
+        for (int t = 0; t < (FMT == 2 ? 32 : 16); ++t) nx[t] = (int)((uint32_t)raw[t] >> SG.shift);
 #if defined(__HIP_DEVICE_COMPILE__)
 #pragma unroll
         for (int t = 0; t < (FMT == 2 ? 32 : 16); t += 8)
@@ -304,10 +361,12 @@ __device__ __forceinline__ void big_chunk(f16v (&acc)[4][4], typename BigFrag<FM
 // lane's operand of a 64-index step is the block 32 (lane / 32) ... of the step, scaled by that
 // lane's own byte (as for FMT 2); the rotation puts the blocks that 32 lanes read from 32
 // consecutive rows on all 64 banks.
-template <int FMT>
+// LS (block-scaled formats, tile sizes up to 1024): the scale bytes travel through LDS.
+template <int FMT, bool LS = false>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 {
+    static_assert(!LS || FMT == 1 || FMT == 2 || FMT == 5, "scale bytes exist in the block-scaled formats only");
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -368,7 +427,14 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
         SG.shift = 8 * (lane >> 5);
         SG.rot = BG.rot;
         SG.n = BG.n;
+        SG.rb = nb / 32;
+        SG.ua = nb * pitch + arow0 * SG.rb;
+        SG.ub = nb * pitch + brow0 * SG.rb;
+        SG.la = (wm * 128 + (lane & 31)) * SG.rb;
+        SG.lb = kBigScaleOperand + (wn * 128 + (lane & 31)) * SG.rb;
+        SG.lane16 = lane * 16;
     }
+    const int wave_u = uni(wave);
 
     f16v acc[4][4];
     const int n = pitch / kChunkBytes;                       // chunks per product: even (the host sees to that)
@@ -404,6 +470,7 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
             S.c = 0;
 #pragma unroll
             for (int j = 0; j < 16; ++j) big_request<FMT>(S, BG, 0, j);
+            if constexpr (LS) big_request_scales<FMT>(S, SG, 0, wave_u);      // the product's scale rows, buffer 0
             S.c = 1;
 #pragma unroll
             for (int j = 0; j < 16; ++j) big_request<FMT>(S, BG, 1, j);
@@ -424,6 +491,7 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
                 for (int t = 0; t < 32; ++t) sc[t] = (int)((uint32_t)sc[t] >> SG.shift);
             }
 
+            int sbuf = 0;                                    // scale buffer of the product being computed
             for (; L < kt; ++L) {
                 int sa, sb;
                 big_scales((int)hi.x, (int)hi.y, sa, sb);
@@ -456,6 +524,11 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
                 next_src.a = (uint64_t)nlo.x | ((uint64_t)nlo.y << 32);
                 next_src.b = (uint64_t)nlo.z | ((uint64_t)nlo.w << 32);
                 next_src.bytes = nbytes;
+                // The following product's scale rows go to the other scale buffer.  No wave reads that
+                // buffer any more: it held the scales of the product before this one, last read in the
+                // middle of that product's last chunk pair but one, at least two barriers ago (the last
+                // pair of a product takes over the first scales of the next, from this product's buffer).
+                if constexpr (LS) big_request_scales<FMT>(next_src, SG, sbuf ^ 1, wave_u);
                 for (int c = 0; c < n; c += 2) {
                     BigSource S2 = (c + 2 < n) ? cur_src : next_src;
                     S2.c = (c + 2 < n) ? c + 2 : c + 2 - n;
@@ -468,20 +541,24 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
                         // sc holds the scales of chunks c and c + 1; those of the next pair are requested
                         // before the second chunk and taken over in its middle
                         const bool wrap = c + 2 >= n && nbytes != 0;
-                        big_chunk<0, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
-                        big_load_scales<FMT>(nsc, SG, wrap ? next_src.a : cur_src.a, wrap ? next_src.b : cur_src.b, nb, c + 2 < n ? c + 2 : wrap ? 0 : n - 2);
+                        const int cnext = c + 2 < n ? c + 2 : wrap ? 0 : n - 2;
+                        big_chunk<0, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG);
+                        if constexpr (!LS)
+                            big_load_scales<FMT>(nsc, SG, wrap ? next_src.a : cur_src.a, wrap ? next_src.b : cur_src.b, nb, cnext);
                         S2.c += 1;
-                        big_chunk<1, FMT, true, FMT == 2 ? 16 : 8>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
+                        big_chunk<1, FMT, true, FMT == 2 ? 16 : 8, LS>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG,
+                                                                       BigScaleTake{wrap ? sbuf ^ 1 : sbuf, cnext});
 #pragma unroll
                         for (int t = 0; t < 32; ++t) sc[t] = nx[t];
                     } else {
-                        big_chunk<0, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
+                        big_chunk<0, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG);
                         S2.c += 1;
-                        big_chunk<1, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG.shift);
+                        big_chunk<1, FMT, false, 0>(acc, f, BG, lds, S2, sa, sb, sc, nsc, nx, SG);
                     }
                 }
                 lo = nlo;
                 hi = nhi;
+                sbuf ^= 1;
             }
 #if defined(__HIP_DEVICE_COMPILE__)
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // requests past the segment's end still write into the stages
@@ -526,14 +603,22 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
 
 #define GMP_REGION_INSTANCE(NAME, FMT)                                                                      \
     namespace gmp {                                                                                         \
+    constexpr bool kScaled_##NAME = (FMT) == 1 || (FMT) == 2 || (FMT) == 5;                                 \
     hipError_t setup_##NAME()                                                                               \
     {                                                                                                       \
-        return hipFuncSetAttribute((const void *)gemm_mp_fp8_region_kernel<FMT>,                            \
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);               \
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_mp_fp8_region_kernel<FMT, false>,             \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsBytes);       \
+        if (e != hipSuccess || !kScaled_##NAME) return e;                                                   \
+        return hipFuncSetAttribute((const void *)gemm_mp_fp8_region_kernel<FMT, kScaled_##NAME>,            \
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kBigLdsScaled);              \
     }                                                                                                       \
     hipError_t launch_##NAME(const GemmArgs &a, const WorkItem *items, int n, hipStream_t s)                \
     {                                                                                                       \
-        gemm_mp_fp8_region_kernel<FMT><<<dim3((unsigned)n), dim3(kThreads), kBigLdsBytes, s>>>(a, items);   \
+        /* block-scaled tiles of up to 1024: the instance that moves the scale bytes through LDS */         \
+        if (kScaled_##NAME && a.nb <= 1024)                                                                 \
+            gemm_mp_fp8_region_kernel<FMT, kScaled_##NAME><<<dim3((unsigned)n), dim3(kThreads), kBigLdsScaled, s>>>(a, items); \
+        else                                                                                                \
+            gemm_mp_fp8_region_kernel<FMT, false><<<dim3((unsigned)n), dim3(kThreads), kBigLdsBytes, s>>>(a, items); \
         return hipGetLastError();                                                                           \
     }                                                                                                       \
     }

@@ -855,8 +855,13 @@ def test_256_regions_visit_every_chunk_once_at_tile_sizes_with_six_and_eight_chu
     import torch
     from paper_2508_14848_amd.device import DeviceGemmMP
     rng = np.random.default_rng(131)
-    for fmt, nb in ((FP8, 768), (FP8, 1024), (MXFP8, 768), (MXFP8, 1024), (MXFP4, 1536), (MXFP4, 2048), (MXFP6, 768), (MXFP6, 1024)):
-        M, N, K = nb, nb, 2 * nb
+    # the block-scaled kernels have two instances: up to tile size 1024 the scale bytes travel through
+    # LDS, two buffers used in turn from product to product (three products: every buffer is reused;
+    # 256 / 512: a product is a single chunk pair), above it they are loaded from global memory
+    cases = ((FP8, 768, 2), (FP8, 1024, 2), (MXFP8, 768, 2), (MXFP8, 1024, 2), (MXFP4, 1536, 2), (MXFP4, 2048, 2), (MXFP6, 768, 2),
+             (MXFP6, 1024, 2), (MXFP8, 256, 3), (MXFP6, 256, 3), (MXFP4, 512, 3), (MXFP4, 1024, 3), (MXFP8, 1280, 2), (MXFP6, 1280, 2))
+    for fmt, nb, kt in cases:
+        M, N, K = nb, nb, kt * nb
         _say("256 x 256 regions, integers:", {FP8: "FP8", MXFP8: "MXFP8", MXFP4: "MXFP4", MXFP6: "MXFP6"}[fmt], (M, N, K, nb))
         if fmt == FP8:                                   # one scale per tile: the same magnitude everywhere
             A = rng.integers(-3, 4, (M, K)).astype(np.float64)
@@ -866,8 +871,8 @@ def test_256_regions_visit_every_chunk_once_at_tile_sizes_with_six_and_eight_chu
             B = rng.integers(-3, 4, (K, N)) * 2.0 ** rng.integers(0, 3, (K // 32, N)).repeat(32, axis=0)
         C0 = rng.integers(-5, 6, (M, N)).astype(np.float64)
         d = DeviceGemmMP(M, N, K, nb)
-        d.set_precision_map("A", np.full((1, 2), fmt, dtype=np.uint16))
-        d.set_precision_map("B", np.full((2, 1), fmt, dtype=np.uint16))
+        d.set_precision_map("A", np.full((1, kt), fmt, dtype=np.uint16))
+        d.set_precision_map("B", np.full((kt, 1), fmt, dtype=np.uint16))
         d.set_precision_map("C", np.full((1, 1), FP32, dtype=np.uint16))
         for which, X in (("A", A), ("B", B), ("C", C0)):
             d.pack_tiles(which, torch.from_numpy(np.ascontiguousarray(X)).cuda())
