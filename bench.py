@@ -160,6 +160,21 @@ def clock_probe(d, w, seconds):
             "source": "rocm-smi --showclocks, about one reading a second while gemm_mp_run loops (beta as in the workload)"}
 
 
+def hbm_rates(w, st, ms, packs_c):
+    """The HBM-bound passes in GB/s of their algorithmic bytes (peak 8000): the tile scan reads 8 bytes per
+    element of A and of B (its time includes the rule on the host and the waits for it); pack reads 8 bytes per
+    element and writes the packed tiles."""
+    elems = [w.M * w.K, w.K * w.N, w.M * w.N]
+    out = {}
+    if w.rule is not None and ms["scan_rule"] > 0:
+        out["scan_rule_GBps"] = 8.0 * (elems[0] + elems[1]) / (ms["scan_rule"] * 1e-3) / 1e9
+    which = (0, 1, 2) if packs_c else (0, 1)
+    if ms["pack"] > 0:
+        out["pack_GBps"] = sum(8.0 * elems[i] + st["packed_bytes"][i] for i in which) / (ms["pack"] * 1e-3) / 1e9
+    out["note"] = "algorithmic bytes over the stage's HIP-event time; where the maps were set by hand, pack first scans the matrices that have FP16 / FP8 tiles (8 more bytes per element, not counted)"
+    return out
+
+
 def measure(name, steps, warmup, policy, conversion, cpu_seconds, operand_values="workload", clock_seconds=0.0):
     """Run one workload; returns the fields of its JSON record.  cpu_seconds = 0: no CPU baseline."""
     import numpy as np
@@ -273,6 +288,7 @@ def measure(name, steps, warmup, policy, conversion, cpu_seconds, operand_values
                    "work_items": st["work_items"], "host_generation_s": round(t_gen, 1),
                    "operand_values": operand_values},
         "stages_ms": {k: float(np.mean(v)) for k, v in stage_ms.items()},
+        "stages_hbm": hbm_rates(w, st, {k: float(np.mean(v)) for k, v in stage_ms.items()}, dC is not None),
         "run_only": {"ms": run_ms, "min_ms": float(np.min(stage_ms["run"])), "effective_tflops": achieved,
                      "roofline_ms": t_roof * 1e3, "frac_of_precision_weighted_peak": t_roof * 1e3 / run_ms},
         "roofline": {"bound": "mfma", "kernel": "gemm_mp_run: product_table_kernel + " + " + ".join(k["kernel"] for k in launched),
