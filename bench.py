@@ -30,9 +30,11 @@ PEAK_FP4_TFLOPS = 10066.4
 DTYPE_NAMES = ["f64", "f32", "f16", "f8e4m3"]
 HEADLINE = "cov64k"
 ALSO = ("cov16k", "rect32k")
-KERNEL_NAMES = ["gemm_mp_owner_kernel<double%s>", "gemm_mp_owner_kernel<float%s>", "gemm_mp_fp8_region_kernel<0>",
-                "gemm_mp_fp8_region_kernel<1>", "gemm_mp_fp8_region_kernel<2>", "gemm_mp_fp8_region_kernel<3>",
-                "gemm_mp_fp8_region_kernel<4>", "gemm_mp_fp8_region_kernel<5>"]
+# the second argument of the 256 x 256 kernels: block-scaled tiles of up to 1024 take the instance that moves the scale
+# bytes through LDS
+KERNEL_NAMES = ["gemm_mp_owner_kernel<double%s>", "gemm_mp_owner_kernel<float%s>", "gemm_mp_fp8_region_kernel<0, false>",
+                "gemm_mp_fp8_region_kernel<1, %s>", "gemm_mp_fp8_region_kernel<2, %s>", "gemm_mp_fp8_region_kernel<3, false>",
+                "gemm_mp_fp8_region_kernel<4, false>", "gemm_mp_fp8_region_kernel<5, %s>"]
 INSTANCE = [", false, false", ", true, false", ", true, true", None]
 
 
@@ -270,6 +272,8 @@ def measure(name, steps, warmup, policy, conversion, cpu_seconds, operand_values
             if k < 2:
                 inst = INSTANCE[st["owner_instance"][k]]
                 kn = kn % inst if inst else "gemm_mp_owner_low_kernel<false>"
+            elif "%s" in kn:
+                kn = kn % ("true" if w.nb <= 1024 else "false")
             launched.append({"kernel": kn, "workgroups": n})
     out = {
         "metric": "effective TFLOP/s (2MNK/t) and % of precision-weighted MFMA peak, 1 GPU",
