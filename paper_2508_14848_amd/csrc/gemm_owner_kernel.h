@@ -1760,7 +1760,7 @@ __device__ __forceinline__ void owner_body(const WorkItem *__restrict__ items)
     // Epilogue: v = alpha*s (+ beta*c0): two rounded products and one rounded sum in T.  C is
     // written with streaming stores: a region is written once and not read again, and should not
     // displace the operand panels from L2.
-#ifdef GMP_OWNER_PLAIN_STORES
+#ifdef GMP_PLAIN_C_STORES
 #define GMP_STORE_C(v, p) (*(p) = (v))
 #else
 #define GMP_STORE_C(v, p) __builtin_nontemporal_store((v), (p))

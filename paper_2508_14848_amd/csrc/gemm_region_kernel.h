@@ -591,7 +591,11 @@ void gemm_mp_fp8_region_kernel(GemmArgs P, const WorkItem *__restrict__ items)
                     if (use_c) { const float bc = beta * c0[v]; val = val + bc; }
                     // a streaming store: the C block is written once and not read again, and it must
                     // not push the operand panels, which fifteen other regions are reading, out of L2
+#ifdef GMP_PLAIN_C_STORES                              /* a build switch for comparisons only */
+                    cbase[(int64_t)(mt * 32 + 8 * (v >> 2) + (v & 3)) * nb + nt * 32] = val;
+#else
                     __builtin_nontemporal_store(val, &cbase[(int64_t)(mt * 32 + 8 * (v >> 2) + (v & 3)) * nb + nt * 32]);
+#endif
                 }
             }
         again = true;
