@@ -468,10 +468,9 @@ void build_schedule(gemm_mp_ctx *c)
         std::vector<WorkItem> bins[kBins];
         {
             // C tiles sorted by cost and dealt to the bins, heaviest first; a tile's regions stay
-            // together, row by row.  (For the 256 x 256 regions, whose kernels wait for operand
-            // bytes, an order in which the 32 regions an XCD holds at a time form a compact 4 x 8
-            // block of C was measured too: same run time, more bytes fetched into the L2s.  What
-            // those kernels wait for is the delivery from L2 to the compute units.)
+            // together.  (For the 256 x 256 regions, whose kernels wait for operand bytes, an order
+            // in which the 32 regions an XCD holds at a time form a compact 4 x 8 block of C across
+            // two tiles was measured too: same run time, more bytes fetched into the L2s.)
             std::vector<int> order;
             for (int t = 0; t < MT * NT; ++t) {
                 const int which = C.map[t] == GEMM_MP_FP64 ? 0 : all_fp8[t] ? 2 : all_mx[t] == 3 ? 7 : all_mx[t] ? 2 + all_mx[t] : all_16[t] ? 4 + all_16[t] : 1;
@@ -484,11 +483,21 @@ void build_schedule(gemm_mp_ctx *c)
                 for (int b = 1; b < kBins; ++b)
                     if (load[b] < load[best]) best = b;
                 load[best] += cost[t];
+                // the 32 regions of a tile that an XCD works on at a time: a 4 x 8 block of the tile
+                // where its regions form more than 8 columns (they read 4 + 8 strips of the operand
+                // panels through that XCD's L2 instead of 2 + 16 or 1 + 32), else row by row
+                const bool blocked = list < 2 && mr > 8 && mr % 8 == 0;
                 for (size_t r = 0; r < per_tile; ++r) {
                     WorkItem it;
                     it.tile = (uint32_t)t;
-                    it.mi = (uint16_t)(r / mr);
-                    it.mj = (uint16_t)(r % mr);
+                    if (blocked) {
+                        const int blk = (int)(r / 32), in = (int)(r % 32), bpr = mr / 8;      // blocks per block row
+                        it.mi = (uint16_t)((blk / bpr) * 4 + in / 8);
+                        it.mj = (uint16_t)((blk % bpr) * 8 + in % 8);
+                    } else {
+                        it.mi = (uint16_t)(r / mr);
+                        it.mj = (uint16_t)(r % mr);
+                    }
                     bins[best].push_back(it);
                 }
             }

@@ -883,6 +883,32 @@ def test_256_regions_visit_every_chunk_once_at_tile_sizes_with_six_and_eight_chu
         torch.cuda.synchronize()
 
 
+def test_owner_regions_in_blocks_of_four_by_eight_cover_a_tile_once():
+    """Where a tile has more than eight columns of 128 x 128 regions the schedule hands them out in
+    blocks of 4 x 8 (what an XCD works on at a time) instead of row by row.  Integer problems (exact)
+    at tile sizes 2048 and 3072 (16 and 24 region columns), one FP64 and one FP32 C tile side by
+    side, C poisoned beforehand: a region left out or visited twice shows."""
+    import torch
+    from paper_2508_14848_amd.device import DeviceGemmMP
+    rng = np.random.default_rng(977)
+    for nb in (2048, 3072):
+        M, N, K = nb, 2 * nb, nb
+        _say("owner regions in 4 x 8 blocks:", (M, N, K, nb))
+        A = rng.integers(-3, 4, (M, K)).astype(np.float64)
+        B = rng.integers(-3, 4, (K, N)).astype(np.float64)
+        d = DeviceGemmMP(M, N, K, nb)
+        d.set_precision_map("A", np.full((1, 1), FP32, dtype=np.uint16))
+        d.set_precision_map("B", np.full((1, 2), FP32, dtype=np.uint16))
+        d.set_precision_map("C", np.array([[FP64, FP32]], dtype=np.uint16))
+        d.pack_tiles("A", torch.from_numpy(A).cuda())
+        d.pack_tiles("B", torch.from_numpy(B).cuda())
+        d.pack_tiles("C", torch.full((M, N), float("nan"), dtype=torch.float64, device="cuda"))
+        assert d.ctx.get_stats()["work_items"] == 2 * (nb // 128) ** 2
+        d.run(1.0, 0.0)
+        assert np.array_equal(d.unpack_tiles("C").cpu().numpy(), A @ B)
+        torch.cuda.synchronize()
+
+
 def test_mxfp8_tiles_pack_bit_for_bit_and_multiply_on_the_block_scaled_instruction():
     """MXFP8 tiles: element and scale bytes equal the oracle's block quantisation (blocks along the
     rows of A tiles and down the columns of B tiles, i.e. along the reduction index; a size off
